@@ -1,0 +1,406 @@
+/*
+ * CPU oracle for the verification hot path of Lookahead Reasoning
+ * (arXiv 2506.19830).  TEST INFRASTRUCTURE ONLY: this file is the slow, plain
+ * definition that the HIP library is checked against.  It shares no code,
+ * header, table or helper with the GPU path and must never be called from the
+ * product path.
+ *
+ * Everything is computed in fp64 from the exact bytes the GPU receives
+ * (fp32 / bf16 / fp8-e4m3fn storage is widened exactly).
+ *
+ *   lao_verify_attention  -- Section 3.1 / Algorithm 1 ("in parallel do",
+ *       prefixes x'_j): every drafted branch sees the common prefix x_{1:t}
+ *       followed only by its own continuation.  For each branch the key/value
+ *       sequence is written out explicitly as  prefix ++ branch tokens  and a
+ *       textbook max-subtracted softmax attention is evaluated per query row.
+ *       Nothing is shared between branches, nothing is tiled or split.
+ *   lao_attention_row_weights -- the softmax weights of one row (test hook
+ *       for the "rows sum to one" pin).
+ *   lao_spec_accept -- Section 2 ("Speculative Decoding"): the drafted tokens
+ *       are examined in order, each accepted with probability min(1, p/q);
+ *       at the first rejection the walk stops and one token is drawn from
+ *       norm(max(0, p - q)); when all K survive, a bonus token is drawn from
+ *       the (K+1)-th target row ("gamma+1 positions", Section 1).  Sampling is
+ *       a sequential inverse-CDF walk.
+ *
+ * Readings fixed here because the paper leaves them open (each is also listed
+ * in the repository's design notes):
+ *   - accept test is  u * q(x) < p(x)  with u in [0,1)  (so q(x)=0<p(x)
+ *     accepts, p(x)=q(x)=0 rejects);                         parity unpinned
+ *   - residual mass S == 0 after a rejection falls back to r = p_n;
+ *                                                             parity unpinned
+ *   - inverse CDF returns the first v whose running sum is > u*S (strict), so
+ *     zero-mass tokens are never returned (pinned: a sample must have mass).
+ * The first two items only matter on measure-zero / rounding-only inputs.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { LAO_F32 = 0, LAO_BF16 = 1, LAO_FP8_E4M3 = 2, LAO_F64 = 3 };
+
+/* ---- exact widening of the storage formats --------------------------------- */
+
+static double widen_bf16(uint16_t bits) {
+  /* bfloat16 is the upper half of an IEEE binary32 */
+  uint32_t w = (uint32_t)bits << 16;
+  float f;
+  memcpy(&f, &w, sizeof f);
+  return (double)f;
+}
+
+static double widen_fp8_e4m3fn(uint8_t bits) {
+  /* OCP 8-bit float, 1 sign / 4 exponent (bias 7) / 3 mantissa bits, no
+   * infinities, S.1111.111 is NaN, largest finite value 448. */
+  int sign = bits >> 7;
+  int e = (bits >> 3) & 0xF;
+  int m = bits & 0x7;
+  double mag;
+  if (e == 0xF && m == 0x7) return NAN;
+  if (e == 0)
+    mag = ldexp((double)m / 8.0, -6); /* subnormal */
+  else
+    mag = ldexp(1.0 + (double)m / 8.0, e - 7);
+  return sign ? -mag : mag;
+}
+
+static double load_elem(const void *base, int dtype, int64_t idx) {
+  switch (dtype) {
+  case LAO_F32:
+    return (double)((const float *)base)[idx];
+  case LAO_BF16:
+    return widen_bf16(((const uint16_t *)base)[idx]);
+  case LAO_FP8_E4M3:
+    return widen_fp8_e4m3fn(((const uint8_t *)base)[idx]);
+  case LAO_F64:
+    return ((const double *)base)[idx];
+  default:
+    return NAN;
+  }
+}
+
+/* Test hook: widen n elements of the given storage type. */
+int lao_widen(const void *src, int dtype, int64_t n, double *dst) {
+  if (!src || !dst || dtype < 0 || dtype > LAO_F64) return 1;
+  for (int64_t i = 0; i < n; ++i) dst[i] = load_elem(src, dtype, i);
+  return 0;
+}
+
+/* ---- attention ---------------------------------------------------------------
+ *
+ * Tensor layouts (all row-major, host memory):
+ *   q, k_branch, v_branch : [B, gamma, L, H, D]   (H = Hq for q, Hkv for k/v)
+ *   k_cache, v_cache      : [num_blocks, Hkv, block_size, D]
+ *   block_tables          : [B, max_blocks] int32, NULL => request b owns the
+ *                           physical blocks b*max_blocks .. (b+1)*max_blocks-1
+ *   prefix_lens           : [B] int32
+ *   k_scale, v_scale      : [Hkv] fp32 multipliers applied to fp8 storage
+ *                           (cache and, when stored as fp8, the branch K/V);
+ *                           NULL => 1
+ * A query row is named by  row_id = ((b*gamma + g)*L + i)*Hq + h.
+ */
+
+typedef struct {
+  int B, gamma, L, Hq, Hkv, D, block_size, max_blocks;
+  int q_dtype, kv_dtype, br_dtype;
+  double scale;
+  const void *q, *k_cache, *v_cache, *k_branch, *v_branch;
+  const int32_t *block_tables, *prefix_lens;
+  const float *k_scale, *v_scale;
+} attn_problem;
+
+/* Writes the key and value sequence seen by branch g of request b on kv head
+ * hk:  the P prefix tokens in logical order, then the branch's own L tokens.
+ * kcat, vcat: [(P+L), D]. */
+static void concat_branch_kv(const attn_problem *a, int b, int g, int hk, double *kcat, double *vcat) {
+  const int D = a->D;
+  const int P = a->prefix_lens[b];
+  const double ks = (a->k_scale && a->kv_dtype == LAO_FP8_E4M3) ? (double)a->k_scale[hk] : 1.0;
+  const double vs = (a->v_scale && a->kv_dtype == LAO_FP8_E4M3) ? (double)a->v_scale[hk] : 1.0;
+  for (int j = 0; j < P; ++j) {
+    int64_t logical_block = j / a->block_size;
+    int64_t phys = a->block_tables ? (int64_t)a->block_tables[(int64_t)b * a->max_blocks + logical_block]
+                                   : (int64_t)b * a->max_blocks + logical_block;
+    int64_t base = ((phys * a->Hkv + hk) * a->block_size + (j % a->block_size)) * D;
+    for (int d = 0; d < D; ++d) {
+      kcat[(int64_t)j * D + d] = load_elem(a->k_cache, a->kv_dtype, base + d) * ks;
+      vcat[(int64_t)j * D + d] = load_elem(a->v_cache, a->kv_dtype, base + d) * vs;
+    }
+  }
+  const double bks = (a->k_scale && a->br_dtype == LAO_FP8_E4M3) ? (double)a->k_scale[hk] : 1.0;
+  const double bvs = (a->v_scale && a->br_dtype == LAO_FP8_E4M3) ? (double)a->v_scale[hk] : 1.0;
+  for (int i = 0; i < a->L; ++i) {
+    int64_t base = ((((int64_t)b * a->gamma + g) * a->L + i) * a->Hkv + hk) * D;
+    for (int d = 0; d < D; ++d) {
+      kcat[(int64_t)(P + i) * D + d] = load_elem(a->k_branch, a->br_dtype, base + d) * bks;
+      vcat[(int64_t)(P + i) * D + d] = load_elem(a->v_branch, a->br_dtype, base + d) * bvs;
+    }
+  }
+}
+
+/* Softmax weights of query row (b,g,i,h) over its n = P+i+1 visible keys.
+ * w: [n]; returns log-sum-exp of the scaled scores through *lse. */
+static void row_softmax(const attn_problem *a, int b, int g, int i, int h, const double *kcat, int64_t n, double *w,
+                        double *lse) {
+  const int D = a->D;
+  int64_t qbase = ((((int64_t)b * a->gamma + g) * a->L + i) * a->Hq + h) * D;
+  double qrow[D];
+  for (int d = 0; d < D; ++d) qrow[d] = load_elem(a->q, a->q_dtype, qbase + d);
+  double m = -INFINITY;
+  for (int64_t j = 0; j < n; ++j) {
+    double s = 0.0;
+    for (int d = 0; d < D; ++d) s += qrow[d] * kcat[j * D + d];
+    s *= a->scale;
+    w[j] = s;
+    if (s > m) m = s;
+  }
+  double z = 0.0;
+  for (int64_t j = 0; j < n; ++j) {
+    w[j] = exp(w[j] - m);
+    z += w[j];
+  }
+  for (int64_t j = 0; j < n; ++j) w[j] /= z;
+  *lse = m + log(z);
+}
+
+static int check_problem(const attn_problem *a) {
+  if (a->B < 1 || a->gamma < 1 || a->L < 1 || a->Hq < 1 || a->Hkv < 1 || a->D < 1 || a->D > 1024) return 1;
+  if (a->Hq % a->Hkv) return 1;
+  if (a->block_size < 1 || a->max_blocks < 0) return 1;
+  if (!a->q || !a->k_branch || !a->v_branch || !a->prefix_lens) return 1;
+  for (int b = 0; b < a->B; ++b) {
+    if (a->prefix_lens[b] < 0) return 1;
+    if ((int64_t)a->prefix_lens[b] > (int64_t)a->max_blocks * a->block_size) return 1;
+    if (a->prefix_lens[b] > 0 && (!a->k_cache || !a->v_cache)) return 1;
+  }
+  return 0;
+}
+
+/* out: [n_rows, D] fp64, lse: [n_rows] fp64 or NULL.  row_ids == NULL means
+ * every row in order (n_rows must then equal B*gamma*L*Hq). */
+int lao_verify_attention(int B, int gamma, int L, int Hq, int Hkv, int D, int block_size, int max_blocks, int q_dtype,
+                         int kv_dtype, int br_dtype, double scale, const void *q, const void *k_cache,
+                         const void *v_cache, const int32_t *block_tables, const int32_t *prefix_lens,
+                         const void *k_branch, const void *v_branch, const float *k_scale, const float *v_scale,
+                         const int64_t *row_ids, int64_t n_rows, double *out, double *lse) {
+  attn_problem a = {B,  gamma,   L,       Hq,       Hkv,      D,           block_size, max_blocks, q_dtype, kv_dtype, br_dtype,
+                    scale, q, k_cache, v_cache, k_branch, v_branch, block_tables, prefix_lens, k_scale, v_scale};
+  if (check_problem(&a) || !out) return 1;
+  const int64_t total = (int64_t)B * gamma * L * Hq;
+  if (!row_ids && n_rows != total) return 1;
+  for (int64_t r = 0; row_ids && r < n_rows; ++r)
+    if (row_ids[r] < 0 || row_ids[r] >= total) return 1;
+  const int G = Hq / Hkv;
+  const int64_t groups = (int64_t)B * gamma * Hkv;
+  int failed = 0;
+
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t grp = 0; grp < groups; ++grp) {
+    const int hk = (int)(grp % Hkv);
+    const int g = (int)((grp / Hkv) % gamma);
+    const int b = (int)(grp / ((int64_t)Hkv * gamma));
+    /* does any requested row belong to this (request, branch, kv head)? */
+    int wanted = (row_ids == NULL);
+    for (int64_t r = 0; !wanted && r < n_rows; ++r) {
+      int64_t id = row_ids[r];
+      int h = (int)(id % Hq);
+      int64_t t = id / Hq / L; /* = b*gamma + g */
+      if (h / G == hk && t == (int64_t)b * gamma + g) wanted = 1;
+    }
+    if (!wanted) continue;
+    const int P = prefix_lens[b];
+    const int64_t n_max = (int64_t)P + L;
+    double *kcat = malloc(sizeof(double) * n_max * D);
+    double *vcat = malloc(sizeof(double) * n_max * D);
+    double *w = malloc(sizeof(double) * n_max);
+    if (!kcat || !vcat || !w) {
+      failed = 1;
+      free(kcat), free(vcat), free(w);
+      continue;
+    }
+    concat_branch_kv(&a, b, g, hk, kcat, vcat);
+    const int64_t n_iter = row_ids ? n_rows : (int64_t)L * G;
+    for (int64_t it = 0; it < n_iter; ++it) {
+      int i, h;
+      int64_t slot;
+      if (row_ids) {
+        int64_t id = row_ids[it];
+        h = (int)(id % Hq);
+        i = (int)((id / Hq) % L);
+        if (h / G != hk || id / Hq / L != (int64_t)b * gamma + g) continue;
+        slot = it;
+      } else {
+        i = (int)(it / G);
+        h = hk * G + (int)(it % G);
+        slot = ((((int64_t)b * gamma + g) * L + i) * Hq + h);
+      }
+      const int64_t n = (int64_t)P + i + 1; /* causal inside the branch */
+      double row_lse;
+      row_softmax(&a, b, g, i, h, kcat, n, w, &row_lse);
+      double *o = out + slot * D;
+      for (int d = 0; d < D; ++d) o[d] = 0.0;
+      for (int64_t j = 0; j < n; ++j)
+        for (int d = 0; d < D; ++d) o[d] += w[j] * vcat[j * D + d];
+      if (lse) lse[slot] = row_lse;
+    }
+    free(kcat), free(vcat), free(w);
+  }
+  return failed;
+}
+
+/* Softmax weights of one row over its P+i+1 visible keys (prefix first, then
+ * branch tokens 0..i).  w must hold prefix_lens[b]+i+1 doubles. */
+int lao_attention_row_weights(int B, int gamma, int L, int Hq, int Hkv, int D, int block_size, int max_blocks,
+                              int q_dtype, int kv_dtype, int br_dtype, double scale, const void *q,
+                              const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                              const int32_t *prefix_lens, const void *k_branch, const void *v_branch,
+                              const float *k_scale, const float *v_scale, int64_t row_id, double *w) {
+  attn_problem a = {B,  gamma,   L,       Hq,       Hkv,      D,           block_size, max_blocks, q_dtype, kv_dtype, br_dtype,
+                    scale, q, k_cache, v_cache, k_branch, v_branch, block_tables, prefix_lens, k_scale, v_scale};
+  if (check_problem(&a) || !w) return 1;
+  if (row_id < 0 || row_id >= (int64_t)B * gamma * L * Hq) return 1;
+  const int h = (int)(row_id % Hq);
+  const int i = (int)((row_id / Hq) % L);
+  const int g = (int)((row_id / Hq / L) % gamma);
+  const int b = (int)(row_id / Hq / L / gamma);
+  const int hk = h / (Hq / Hkv);
+  const int64_t n_max = (int64_t)prefix_lens[b] + L;
+  double *kcat = malloc(sizeof(double) * n_max * D);
+  double *vcat = malloc(sizeof(double) * n_max * D);
+  if (!kcat || !vcat) {
+    free(kcat), free(vcat);
+    return 1;
+  }
+  concat_branch_kv(&a, b, g, hk, kcat, vcat);
+  double lse;
+  row_softmax(&a, b, g, i, h, kcat, (int64_t)prefix_lens[b] + i + 1, w, &lse);
+  free(kcat), free(vcat);
+  return 0;
+}
+
+/* ---- speculative accept / resample -------------------------------------------
+ *
+ *   target_logits [NB, K+1, V], draft_logits [NB, K, V]  (storage dtype given)
+ *   draft_tokens  [NB, K] int32,  u_accept [NB, K] fp32,  u_sample [NB] fp32
+ * outputs
+ *   accepted_len [NB] (0..K), next_token [NB] (0..V-1)
+ *   ratio   [NB, K]  p(x)/q(x) at every examined position, NaN elsewhere
+ *   margin  [NB, K]  |u - min(1, p/q)| at every examined position, +inf elsewhere
+ *   cdf_lo, cdf_hi [NB]  normalised CDF edges of the returned token
+ *   (any of the four diagnostic outputs may be NULL)
+ */
+
+static void softmax_row(const void *logits, int dtype, int64_t base, int V, double temperature, double *p) {
+  double m = -INFINITY;
+  for (int v = 0; v < V; ++v) {
+    p[v] = load_elem(logits, dtype, base + v) / temperature;
+    if (p[v] > m) m = p[v];
+  }
+  double z = 0.0;
+  for (int v = 0; v < V; ++v) {
+    p[v] = exp(p[v] - m);
+    z += p[v];
+  }
+  for (int v = 0; v < V; ++v) p[v] /= z;
+}
+
+int lao_spec_accept(int NB, int K, int V, int logits_dtype, double temperature, const void *target_logits,
+                    const void *draft_logits, const int32_t *draft_tokens, const float *u_accept,
+                    const float *u_sample, int32_t *accepted_len, int32_t *next_token, double *ratio, double *margin,
+                    double *cdf_lo, double *cdf_hi) {
+  if (NB < 1 || K < 1 || V < 1 || !(temperature > 0.0)) return 1;
+  if (!target_logits || !draft_logits || !draft_tokens || !u_accept || !u_sample || !accepted_len || !next_token)
+    return 1;
+  for (int64_t t = 0; t < (int64_t)NB * K; ++t)
+    if (draft_tokens[t] < 0 || draft_tokens[t] >= V) return 1;
+  int failed = 0;
+
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int nb = 0; nb < NB; ++nb) {
+    double *p = malloc(sizeof(double) * V);
+    double *q = malloc(sizeof(double) * V);
+    double *r = malloc(sizeof(double) * V);
+    if (!p || !q || !r) {
+      failed = 1;
+      free(p), free(q), free(r);
+      continue;
+    }
+    for (int i = 0; i < K; ++i) {
+      if (ratio) ratio[(int64_t)nb * K + i] = NAN;
+      if (margin) margin[(int64_t)nb * K + i] = INFINITY;
+    }
+    /* examine the drafted tokens in order; stop at the first rejection */
+    int n = K;
+    for (int i = 0; i < K; ++i) {
+      softmax_row(target_logits, logits_dtype, ((int64_t)nb * (K + 1) + i) * V, V, temperature, p);
+      softmax_row(draft_logits, logits_dtype, ((int64_t)nb * K + i) * V, V, temperature, q);
+      const int x = draft_tokens[(int64_t)nb * K + i];
+      const double u = (double)u_accept[(int64_t)nb * K + i];
+      if (ratio) ratio[(int64_t)nb * K + i] = p[x] / q[x];
+      if (margin) {
+        double thr = (q[x] > 0.0) ? fmin(1.0, p[x] / q[x]) : (p[x] > 0.0 ? 1.0 : 0.0);
+        margin[(int64_t)nb * K + i] = fabs(u - thr);
+      }
+      const int accept = (u * q[x] < p[x]);
+      if (!accept) {
+        n = i;
+        break;
+      }
+    }
+    /* distribution of the one extra token */
+    double S = 0.0;
+    if (n < K) {
+      /* p and q still hold the rows of position n */
+      for (int v = 0; v < V; ++v) {
+        r[v] = p[v] - q[v];
+        if (r[v] < 0.0) r[v] = 0.0;
+        S += r[v];
+      }
+      if (!(S > 0.0)) {
+        S = 0.0;
+        for (int v = 0; v < V; ++v) {
+          r[v] = p[v];
+          S += r[v];
+        }
+      }
+    } else {
+      softmax_row(target_logits, logits_dtype, ((int64_t)nb * (K + 1) + K) * V, V, temperature, r);
+      for (int v = 0; v < V; ++v) S += r[v];
+    }
+    /* inverse-CDF walk */
+    const double thr = (double)u_sample[nb] * S;
+    double c = 0.0, lo = 0.0;
+    int tok = -1;
+    for (int v = 0; v < V; ++v) {
+      lo = c;
+      c += r[v];
+      if (c > thr) {
+        tok = v;
+        break;
+      }
+    }
+    if (tok < 0) { /* only reachable through rounding: last token with mass */
+      for (int v = V - 1; v >= 0; --v)
+        if (r[v] > 0.0) {
+          tok = v;
+          break;
+        }
+      lo = c - r[tok];
+    }
+    accepted_len[nb] = n;
+    next_token[nb] = tok;
+    if (cdf_lo) cdf_lo[nb] = lo / S;
+    if (cdf_hi) cdf_hi[nb] = (lo + r[tok]) / S;
+    free(p), free(q), free(r);
+  }
+  return failed;
+}
+
+/* Number of OpenMP threads a parallel region will use (for reporting). */
+#ifdef _OPENMP
+#include <omp.h>
+int lao_num_threads(void) { return omp_get_max_threads(); }
+#else
+int lao_num_threads(void) { return 1; }
+#endif

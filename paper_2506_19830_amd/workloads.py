@@ -1,0 +1,267 @@
+"""Seeded synthetic inputs shaped like the paper's workloads.
+
+This module only *produces inputs* (random tensors, storage-format encoding,
+block tables, drafted tokens).  It holds none of the arithmetic of the
+verification pass itself, so both the HIP path and the CPU checker can be fed
+from it without sharing any of the method's code.
+
+The paper evaluates 32B-class GQA reasoning models (Section 4, "Models" and
+"General Parameters": generations of up to 32K/37K tokens, a handful of
+drafted steps verified per pass, 8 speculative tokens for token-level SD).  Its
+weights and datasets are not available here, so every case below is random
+data of those shapes; the five numbered cases are the benchmark
+configurations this repository is measured on.
+
+bf16 tensors are returned as ``uint16`` bit patterns and fp8-e4m3fn tensors as
+``uint8`` bit patterns (numpy has neither type).
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field, replace
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+
+FP8_E4M3_MAX = 448.0
+
+
+# ----------------------------------------------------------------------------- storage encoders
+
+def encode_bf16(x: np.ndarray) -> np.ndarray:
+    """fp32 -> bfloat16 bit patterns, round to nearest even (finite inputs)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    bias = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
+    return ((u + bias) >> np.uint32(16)).astype(np.uint16)
+
+
+def _fp8_positive_values() -> np.ndarray:
+    vals = []
+    for code in range(127):  # 0x00 .. 0x7E, 0x7F is NaN
+        e, m = code >> 3, code & 7
+        vals.append((m / 8.0) * 2.0 ** -6 if e == 0 else (1.0 + m / 8.0) * 2.0 ** (e - 7))
+    return np.asarray(vals, dtype=np.float64)
+
+
+_FP8_VALUES = _fp8_positive_values()
+
+
+def encode_fp8_e4m3(x: np.ndarray) -> np.ndarray:
+    """fp32 -> OCP e4m3fn bit patterns: round to nearest even, saturate at +-448."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    a = np.minimum(np.abs(x).astype(np.float64), FP8_E4M3_MAX)
+    lo = np.searchsorted(_FP8_VALUES, a, side="right") - 1
+    hi = np.minimum(lo + 1, 126)
+    d_lo = a - _FP8_VALUES[lo]
+    d_hi = _FP8_VALUES[hi] - a
+    pick_hi = (d_hi < d_lo) | ((d_hi == d_lo) & (lo % 2 == 1))
+    code = np.where(pick_hi, hi, lo).astype(np.uint8)
+    return code | (np.signbit(x).astype(np.uint8) << np.uint8(7))
+
+
+def encode(x: np.ndarray, dtype: str) -> np.ndarray:
+    if dtype == "f32":
+        return np.ascontiguousarray(x, dtype=np.float32)
+    if dtype == "bf16":
+        return encode_bf16(x)
+    if dtype == "fp8_e4m3":
+        return encode_fp8_e4m3(x)
+    raise ValueError(dtype)
+
+
+# ----------------------------------------------------------------------------- case descriptions
+
+@dataclass(frozen=True)
+class AttnCase:
+    """One verify-attention workload: B requests, gamma branches of L tokens each."""
+    name: str
+    prefix_lens: Tuple[int, ...]
+    gamma: int
+    L: int
+    Hq: int
+    Hkv: int
+    D: int
+    q_dtype: str = "bf16"
+    kv_dtype: str = "bf16"
+    branch_kv_dtype: str = "bf16"
+    out_dtype: str = "bf16"
+    block_size: int = 16
+    paged: bool = False          # random block table over a shared pool
+    seed: int = 0
+    layer: int = 0               # stream offset so that layers of a sweep differ
+
+    @property
+    def B(self) -> int:
+        return len(self.prefix_lens)
+
+    @property
+    def scale(self) -> float:
+        return 1.0 / math.sqrt(self.D)
+
+    @property
+    def max_blocks(self) -> int:
+        return max(1, max(-(-p // self.block_size) for p in self.prefix_lens))
+
+    @property
+    def branch_tokens(self) -> int:
+        return self.B * self.gamma * self.L
+
+    def flops(self) -> float:
+        """4*D flops per (query row, visible key) pair."""
+        per_req = [self.gamma * self.L * self.Hq * 4.0 * self.D * (p + (self.L + 1) / 2.0) for p in self.prefix_lens]
+        return float(sum(per_req))
+
+    def algorithmic_bytes(self) -> float:
+        """Every K/V/Q element read once, every output element written once."""
+        sz = {"f32": 4, "bf16": 2, "fp8_e4m3": 1}
+        kv = sum(2 * self.Hkv * p * self.D * sz[self.kv_dtype] for p in self.prefix_lens)
+        rows = self.branch_tokens
+        br = 2 * rows * self.Hkv * self.D * sz[self.branch_kv_dtype]
+        qo = rows * self.Hq * self.D * (sz[self.q_dtype] + sz[self.out_dtype])
+        return float(kv + br + qo)
+
+
+@dataclass(frozen=True)
+class AcceptCase:
+    """One accept/resample workload: NB branches, K drafted tokens each, vocabulary V."""
+    name: str
+    NB: int
+    K: int
+    V: int
+    logits_dtype: str = "bf16"
+    target_std: float = 3.0
+    draft_noise_std: Optional[float] = 1.0   # draft = target + N(0, noise^2); None => independent N(0, target_std^2)
+    temperature: float = 1.0
+    seed: int = 0
+
+    def algorithmic_bytes(self) -> float:
+        sz = {"f32": 4, "bf16": 2}[self.logits_dtype]
+        return float(self.NB * (2 * self.K + 1) * self.V * sz)
+
+
+def config(n: int) -> Tuple[AttnCase, AcceptCase]:
+    """The five benchmark configurations (1-based)."""
+    if n == 1:
+        return (AttnCase("cfg1_tiny_f32", (256,), 2, 8, 4, 1, 64, "f32", "f32", "f32", "f32"),
+                AcceptCase("cfg1_accept", 2, 4, 512, "f32", target_std=2.0, draft_noise_std=None))
+    if n == 2:
+        return (AttnCase("cfg2_p4k_g4x32", (4096,), 4, 32, 64, 8, 128),
+                AcceptCase("cfg2_accept", 4, 4, 152064, "bf16"))
+    if n == 3:
+        return (AttnCase("cfg3_p16k_g8x64", (16384,), 8, 64, 40, 8, 128),
+                AcceptCase("cfg3_accept", 8, 8, 152064, "f32"))
+    if n == 4:
+        return (AttnCase("cfg4_paged_4req", (8192, 16384, 24576, 32768), 8, 48, 64, 8, 128, paged=True),
+                AcceptCase("cfg4_accept", 32, 8, 152064, "bf16"))
+    if n == 5:
+        return (AttnCase("cfg5_p32k_g8x64_fp8", (32768,), 8, 64, 40, 8, 128, "bf16", "fp8_e4m3", "fp8_e4m3", "bf16"),
+                AcceptCase("cfg5_accept", 8, 8, 152064, "bf16"))
+    raise ValueError("configs are numbered 1..5")
+
+
+NUM_LAYERS_CFG5 = 64
+
+
+# ----------------------------------------------------------------------------- numpy generators
+
+def _rng(seed: int, stream: int) -> np.random.Generator:
+    # Philox is counter based: (seed, stream) names an independent sequence.
+    return np.random.Generator(np.random.Philox(key=[seed & 0xFFFFFFFFFFFFFFFF, stream]))
+
+
+def make_attention_inputs(case: AttnCase) -> Dict[str, Optional[np.ndarray]]:
+    """Q/K/V ~ N(0,1) in the case's storage types, plus cache layout metadata.
+
+    cache layout  [num_blocks, Hkv, block_size, D]; branch tensors [B, gamma, L, H, D].
+    Contiguous cases own ``max_blocks`` consecutive blocks per request and pass
+    ``block_tables=None``; paged cases draw a random permutation of a pool that
+    holds exactly the blocks needed.  fp8 caches carry one scale per KV head
+    (amax/448); a branch K/V stored as fp8 reuses the cache's scales.
+    """
+    c = case
+    s0 = 16 * c.layer
+    B, bs = c.B, c.block_size
+    blocks_needed = [-(-p // bs) for p in c.prefix_lens]
+    if c.paged:
+        num_blocks = max(1, sum(blocks_needed))
+        perm = _rng(c.seed, s0 + 7).permutation(num_blocks).astype(np.int32)
+        tables = np.zeros((B, c.max_blocks), dtype=np.int32)
+        at = 0
+        for b, nb in enumerate(blocks_needed):
+            tables[b, :nb] = perm[at:at + nb]
+            at += nb
+    else:
+        num_blocks = B * c.max_blocks
+        tables = None
+
+    q = _rng(c.seed, s0 + 0).standard_normal((B, c.gamma, c.L, c.Hq, c.D), dtype=np.float32)
+    kb = _rng(c.seed, s0 + 1).standard_normal((B, c.gamma, c.L, c.Hkv, c.D), dtype=np.float32)
+    vb = _rng(c.seed, s0 + 2).standard_normal((B, c.gamma, c.L, c.Hkv, c.D), dtype=np.float32)
+    kc = _rng(c.seed, s0 + 3).standard_normal((num_blocks, c.Hkv, bs, c.D), dtype=np.float32)
+    vc = _rng(c.seed, s0 + 4).standard_normal((num_blocks, c.Hkv, bs, c.D), dtype=np.float32)
+
+    k_scale = v_scale = None
+    if c.kv_dtype == "fp8_e4m3":
+        k_scale = (np.abs(kc).max(axis=(0, 2, 3)) / FP8_E4M3_MAX).astype(np.float32)
+        v_scale = (np.abs(vc).max(axis=(0, 2, 3)) / FP8_E4M3_MAX).astype(np.float32)
+        kc = kc / k_scale[None, :, None, None]
+        vc = vc / v_scale[None, :, None, None]
+    if c.branch_kv_dtype == "fp8_e4m3":
+        if k_scale is None:
+            raise ValueError("fp8 branch K/V needs an fp8 cache (shared scales)")
+        kb = kb / k_scale[None, None, None, :, None]
+        vb = vb / v_scale[None, None, None, :, None]
+
+    return {
+        "q": encode(q, c.q_dtype),
+        "k_cache": encode(kc, c.kv_dtype),
+        "v_cache": encode(vc, c.kv_dtype),
+        "block_tables": tables,
+        "prefix_lens": np.asarray(c.prefix_lens, dtype=np.int32),
+        "k_branch": encode(kb, c.branch_kv_dtype),
+        "v_branch": encode(vb, c.branch_kv_dtype),
+        "k_scale": k_scale,
+        "v_scale": v_scale,
+    }
+
+
+def _decode_for_sampling(bits: np.ndarray, dtype: str) -> np.ndarray:
+    if dtype == "f32":
+        return bits.astype(np.float64)
+    if dtype == "bf16":
+        return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    raise ValueError(dtype)
+
+
+def make_accept_inputs(case: AcceptCase) -> Dict[str, np.ndarray]:
+    """Target/draft logits, drafted tokens and the uniforms of one accept call.
+
+    target ~ N(0, target_std^2); draft = target + N(0, noise^2) (or an
+    independent N(0, target_std^2) when ``draft_noise_std`` is None).  The K
+    drafted tokens are draws from the draft row's categorical distribution at
+    the case's temperature, taken with the Gumbel-argmax construction on the
+    *stored* (rounded) draft logits.  Uniforms are fp32 in [0, 1).
+    """
+    c = case
+    t = _rng(c.seed, 100).standard_normal((c.NB, c.K + 1, c.V), dtype=np.float32) * np.float32(c.target_std)
+    if c.draft_noise_std is None:
+        d = _rng(c.seed, 101).standard_normal((c.NB, c.K, c.V), dtype=np.float32) * np.float32(c.target_std)
+    else:
+        d = t[:, :c.K, :] + _rng(c.seed, 101).standard_normal((c.NB, c.K, c.V), dtype=np.float32) * np.float32(
+            c.draft_noise_std)
+    t_bits = encode(t, c.logits_dtype)
+    d_bits = encode(d, c.logits_dtype)
+    g = _rng(c.seed, 102)
+    tokens = np.empty((c.NB, c.K), dtype=np.int32)
+    for nb in range(c.NB):
+        row = _decode_for_sampling(d_bits[nb], c.logits_dtype) / c.temperature
+        gumbel = -np.log(-np.log(g.random(row.shape)))
+        tokens[nb] = np.argmax(row + gumbel, axis=-1)
+    u_acc = _rng(c.seed, 103).random((c.NB, c.K), dtype=np.float32)
+    u_smp = _rng(c.seed, 104).random((c.NB,), dtype=np.float32)
+    return {"target_logits": t_bits, "draft_logits": d_bits, "draft_tokens": tokens, "u_accept": u_acc,
+            "u_sample": u_smp}
+
+
+def with_layer(case: AttnCase, layer: int) -> AttnCase:
+    return replace(case, layer=layer)

@@ -1,0 +1,216 @@
+"""Pins of the CPU oracle's token-level accept / resample (no GPU).
+
+What fixes the expected values: the defining property of speculative sampling
+(the emitted token is distributed as the target p, Section 2), the expected
+number of emitted tokens (1-a^(K+1))/(1-a) (numerator of g, Section 2), the
+acceptance probability sum(min(p,q)), and hand-computed small distributions.
+"""
+import math
+
+import numpy as np
+import pytest
+
+
+def logits_of(p):
+    p = np.asarray(p, dtype=np.float64)
+    with np.errstate(divide="ignore"):
+        return np.where(p > 0, np.log(np.maximum(p, 1e-300)), -1.0e4).astype(np.float32)
+
+
+def run(oracle, t, d, tok, ua, us, **kw):
+    return oracle.spec_accept(np.asarray(t, np.float32), np.asarray(d, np.float32), tok, ua, us, logits_dtype="f32",
+                              **kw)
+
+
+def chi2(counts, probs):
+    n = counts.sum()
+    keep = probs > 0
+    assert counts[~keep].sum() == 0
+    e = n * probs[keep]
+    return float(((counts[keep] - e) ** 2 / e).sum())
+
+
+def test_emitted_token_is_distributed_as_target(oracle):
+    """V=8, K=1, 10^6 seeded trials with x ~ q: first emitted token ~ p_0, bonus ~ p_1, accept rate = sum min(p,q)."""
+    rng = np.random.default_rng(2025)
+    V, N = 8, 1_000_000
+    t_row = rng.normal(0, 2, size=(2, V)).astype(np.float32)
+    d_row = rng.normal(0, 2, size=(1, V)).astype(np.float32)
+    p0 = np.exp(t_row[0].astype(np.float64)); p0 /= p0.sum()
+    p1 = np.exp(t_row[1].astype(np.float64)); p1 /= p1.sum()
+    q0 = np.exp(d_row[0].astype(np.float64)); q0 /= q0.sum()
+    t = np.broadcast_to(t_row, (N, 2, V)).copy()
+    d = np.broadcast_to(d_row, (N, 1, V)).copy()
+    tok = rng.choice(V, size=(N, 1), p=q0).astype(np.int32)
+    ua = rng.random((N, 1), dtype=np.float32)
+    us = rng.random((N,), dtype=np.float32)
+    r = run(oracle, t, d, tok, ua, us)
+    n, nxt = r["accepted_len"], r["next_token"]
+    assert set(np.unique(n)) <= {0, 1}
+    first = np.where(n == 1, tok[:, 0], nxt)
+    # chi-square, 7 degrees of freedom: P(chi2 > 29.9) ~ 1e-4
+    assert chi2(np.bincount(first, minlength=V), p0) < 29.9
+    assert chi2(np.bincount(nxt[n == 1], minlength=V), p1) < 29.9
+    alpha = np.minimum(p0, q0).sum()
+    assert abs((n == 1).mean() - alpha) < 4.5 * math.sqrt(alpha * (1 - alpha) / N)
+    # a rejected draw never returns a token whose residual is zero
+    resid = np.maximum(p0 - q0, 0)
+    assert (resid[nxt[n == 0]] > 0).all()
+    assert chi2(np.bincount(nxt[n == 0], minlength=V), resid / resid.sum()) < 29.9
+
+
+def test_expected_emitted_length_follows_g_numerator(oracle):
+    """K identical (p,q) positions, tokens iid from q => E[n+1] = (1-a^(K+1))/(1-a)."""
+    rng = np.random.default_rng(7)
+    V, K, N = 6, 4, 300_000
+    p = np.array([0.35, 0.05, 0.2, 0.1, 0.25, 0.05])
+    q = np.array([0.15, 0.25, 0.2, 0.2, 0.1, 0.1])
+    t = np.broadcast_to(logits_of(p), (N, K + 1, V)).copy()
+    d = np.broadcast_to(logits_of(q), (N, K, V)).copy()
+    tok = rng.choice(V, size=(N, K), p=q).astype(np.int32)
+    r = run(oracle, t, d, tok, rng.random((N, K), dtype=np.float32), rng.random((N,), dtype=np.float32))
+    a = np.minimum(p, q).sum()
+    expect = (1 - a ** (K + 1)) / (1 - a)
+    emitted = r["accepted_len"].astype(np.float64) + 1
+    assert abs(emitted.mean() - expect) < 4.5 * emitted.std() / math.sqrt(N)
+    # geometric law of the accepted length
+    for k in range(K):
+        assert abs((r["accepted_len"] == k).mean() - a ** k * (1 - a)) < 5e-3
+    assert abs((r["accepted_len"] == K).mean() - a ** K) < 5e-3
+
+
+def test_hand_computed_residual_and_cdf(oracle):
+    # p=[.6,.1,.3], q=[.2,.6,.2], x=1: ratio 1/6; residual [.4,0,.1] -> token 0 for u<.8 else 2
+    p, q = [0.6, 0.1, 0.3], [0.2, 0.6, 0.2]
+    us = np.array([0.0, 0.5, 0.79, 0.81, 0.999], dtype=np.float32)
+    N = us.size
+    t = np.broadcast_to(logits_of(p), (N, 2, 3)).copy()
+    d = np.broadcast_to(logits_of(q), (N, 1, 3)).copy()
+    tok = np.full((N, 1), 1, dtype=np.int32)
+    r = run(oracle, t, d, tok, np.full((N, 1), 0.5, np.float32), us)
+    np.testing.assert_array_equal(r["accepted_len"], 0)
+    np.testing.assert_array_equal(r["next_token"], [0, 0, 0, 2, 2])
+    np.testing.assert_allclose(r["ratio"][:, 0], 1 / 6, rtol=1e-6)
+    np.testing.assert_allclose(r["margin"][:, 0], 0.5 - 1 / 6, rtol=1e-6)
+    np.testing.assert_allclose(r["cdf_lo"], [0, 0, 0, 0.8, 0.8], atol=1e-6)
+    np.testing.assert_allclose(r["cdf_hi"], [0.8, 0.8, 0.8, 1, 1], atol=1e-6)
+    # same rows, u below the ratio: accepted, bonus token from the next target row p1=[.1,.2,.7]
+    t[:, 1] = logits_of([0.1, 0.2, 0.7])
+    r = run(oracle, t, d, tok, np.full((N, 1), 0.1, np.float32), np.array([0.05, 0.15, 0.29, 0.31, 0.9], np.float32))
+    np.testing.assert_array_equal(r["accepted_len"], 1)
+    np.testing.assert_array_equal(r["next_token"], [0, 1, 1, 2, 2])
+    # x with p >= q is accepted for every u in [0,1)
+    tok0 = np.zeros((N, 1), dtype=np.int32)
+    r = run(oracle, t, d, tok0, np.full((N, 1), 0.999999, np.float32), us)
+    np.testing.assert_array_equal(r["accepted_len"], 1)
+
+
+def test_stops_at_first_rejection(oracle):
+    # position 0 accept (p==q), position 1 reject (p(x)=0), position 2 would accept
+    V, K = 4, 3
+    same = logits_of([0.25, 0.25, 0.25, 0.25])
+    t = np.stack([same, logits_of([0, 0.5, 0.5, 0]), same, same])[None]
+    d = np.stack([same, logits_of([1.0, 0, 0, 0]), same])[None]
+    tok = np.array([[2, 0, 1]], dtype=np.int32)
+    r = run(oracle, t, d, tok, np.array([[0.9, 0.0, 0.0]], np.float32), np.array([0.6], np.float32))
+    assert r["accepted_len"][0] == 1
+    assert r["next_token"][0] == 2                       # residual = p_1 = [0,.5,.5,0], u=.6 -> token 2
+    assert np.isnan(r["ratio"][0, 2]) and np.isinf(r["margin"][0, 2])   # position 2 never examined
+    # u_sample = 0 must still return a token that has mass (token 0 has none here)
+    r = run(oracle, t, d, tok, np.array([[0.9, 0.0, 0.0]], np.float32), np.array([0.0], np.float32))
+    assert r["accepted_len"][0] == 1 and r["next_token"][0] == 1
+
+
+def test_special_cases(oracle):
+    rng = np.random.default_rng(3)
+    V, K, N = 16, 5, 2000
+    lg = rng.normal(0, 2, size=(N, K + 1, V)).astype(np.float32)
+    tok = rng.integers(0, V, size=(N, K)).astype(np.int32)
+    ua = rng.random((N, K), dtype=np.float32)
+    us = rng.random((N,), dtype=np.float32)
+    # p == q  => everything accepted
+    r = run(oracle, lg, lg[:, :K].copy(), tok, ua, us)
+    np.testing.assert_array_equal(r["accepted_len"], K)
+    np.testing.assert_allclose(r["ratio"], 1.0, rtol=1e-12)
+    # disjoint supports => nothing accepted, resample from p_0 itself
+    t = lg.copy(); t[:, :, V // 2:] = -1.0e4
+    d = lg[:, :K].copy(); d[:, :, :V // 2] = -1.0e4
+    tok_hi = rng.integers(V // 2, V, size=(N, K)).astype(np.int32)
+    r = run(oracle, t, d, tok_hi, ua, us)
+    np.testing.assert_array_equal(r["accepted_len"], 0)
+    assert (r["next_token"] < V // 2).all()
+    p0 = np.exp(t[:, 0].astype(np.float64)); p0 /= p0.sum(-1, keepdims=True)
+    cdf = np.cumsum(p0, axis=-1)
+    expect = (cdf > us[:, None].astype(np.float64)).argmax(-1)
+    assert (r["next_token"] == expect).mean() > 0.999    # summation order may flip a draw sitting on an edge
+    # one-hot draft on x: accept probability p(x); on rejection x itself cannot come back
+    d1 = np.full((N, K, V), -1.0e4, dtype=np.float32)
+    np.put_along_axis(d1, tok[:, :, None].astype(np.int64), 0.0, axis=-1)
+    r = run(oracle, lg, d1, tok, ua, us)
+    p = np.exp(lg.astype(np.float64)); p /= p.sum(-1, keepdims=True)
+    px0 = np.take_along_axis(p[:, 0], tok[:, :1].astype(np.int64), axis=-1)[:, 0]
+    np.testing.assert_array_equal(r["accepted_len"] >= 1, ua[:, 0].astype(np.float64) < px0)
+    rej = r["accepted_len"] < K
+    rej_pos = r["accepted_len"][rej]
+    assert (r["next_token"][rej] != tok[rej, rej_pos]).all()
+    # u_accept == 0 accepts wherever p(x) > 0
+    r = run(oracle, lg, lg[:, :K][:, ::-1].copy(), tok, np.zeros_like(ua), us)
+    np.testing.assert_array_equal(r["accepted_len"], K)
+
+
+def test_temperature_is_logit_scaling(oracle):
+    rng = np.random.default_rng(4)
+    V, K, N = 32, 3, 500
+    t = rng.normal(0, 2, size=(N, K + 1, V)).astype(np.float32)
+    d = (t[:, :K] + rng.normal(0, 1, size=(N, K, V))).astype(np.float32)
+    tok = rng.integers(0, V, size=(N, K)).astype(np.int32)
+    ua = rng.random((N, K), dtype=np.float32)
+    us = rng.random((N,), dtype=np.float32)
+    a = run(oracle, t, d, tok, ua, us, temperature=0.5)
+    b = run(oracle, 2 * t, 2 * d, tok, ua, us, temperature=1.0)
+    for k in ("accepted_len", "next_token", "ratio"):
+        np.testing.assert_array_equal(a[k], b[k])
+    c = run(oracle, t, d, tok, ua, us, temperature=1.0)
+    assert not np.array_equal(a["ratio"], c["ratio"])
+
+
+def test_bf16_storage_equals_widened_f32(oracle):
+    from paper_2506_19830_amd import workloads as W
+    case = W.AcceptCase("a", 6, 3, 300, "bf16", seed=5)
+    inp = W.make_accept_inputs(case)
+    a = oracle.spec_accept(**inp, logits_dtype="bf16")
+    wide = dict(inp)
+    wide["target_logits"] = oracle.widen(inp["target_logits"], "bf16").astype(np.float32)
+    wide["draft_logits"] = oracle.widen(inp["draft_logits"], "bf16").astype(np.float32)
+    b = oracle.spec_accept(**wide, logits_dtype="f32")
+    for k in a:
+        np.testing.assert_array_equal(a[k], b[k])
+
+
+def test_ratio_matches_independent_softmax(oracle):
+    import torch
+    from paper_2506_19830_amd import workloads as W
+    case = W.AcceptCase("a", 5, 4, 1000, "f32", seed=6)
+    inp = W.make_accept_inputs(case)
+    r = oracle.spec_accept(**inp, logits_dtype="f32")
+    lp = torch.log_softmax(torch.from_numpy(inp["target_logits"]).double(), -1)[:, :4]
+    lq = torch.log_softmax(torch.from_numpy(inp["draft_logits"]).double(), -1)
+    idx = torch.from_numpy(inp["draft_tokens"]).long()[..., None]
+    ref = torch.exp(lp.gather(-1, idx) - lq.gather(-1, idx))[..., 0].numpy()
+    seen = ~np.isnan(r["ratio"])
+    assert seen[:, 0].all()
+    np.testing.assert_allclose(r["ratio"][seen], ref[seen], rtol=1e-10)
+    # accepted length is the first position whose uniform is not below min(1, ratio)
+    ok = inp["u_accept"].astype(np.float64) < np.minimum(1.0, ref)
+    expect = np.where(ok.all(1), 4, (~ok).argmax(1))
+    np.testing.assert_array_equal(r["accepted_len"], expect)
+
+
+def test_rejects_bad_arguments(oracle):
+    t = np.zeros((1, 2, 4), np.float32)
+    d = np.zeros((1, 1, 4), np.float32)
+    with pytest.raises(ValueError):
+        run(oracle, t, d, np.array([[4]], np.int32), np.zeros((1, 1), np.float32), np.zeros((1,), np.float32))
+    with pytest.raises(ValueError):
+        run(oracle, t, d, np.array([[0]], np.int32), np.zeros((1, 1), np.float32), np.zeros((1,), np.float32),
+            temperature=0.0)

@@ -1,0 +1,285 @@
+"""Pins of the CPU oracle's attention (no GPU).
+
+The oracle is checked against things other than itself: torch's CPU
+scaled_dot_product_attention in fp64 on the special cases that reduce to it,
+closed forms, and invariants that follow from Algorithm 1's prefix structure
+(a branch sees the shared prefix and only its own continuation).
+"""
+import math
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from paper_2506_19830_amd import workloads as W
+
+
+def run(oracle, case, inp, **kw):
+    return oracle.verify_attention(**inp, q_dtype=case.q_dtype, kv_dtype=case.kv_dtype,
+                                   branch_kv_dtype=case.branch_kv_dtype, block_size=case.block_size,
+                                   scale=kw.pop("scale", case.scale), **kw)
+
+
+def as_f64(bits, dtype):
+    """Independent widening through torch (not through the oracle)."""
+    if dtype == "f32":
+        return torch.from_numpy(bits).to(torch.float64)
+    if dtype == "bf16":
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(torch.float64)
+    if dtype == "fp8_e4m3":
+        return torch.from_numpy(bits).view(torch.float8_e4m3fn).to(torch.float64)
+    raise ValueError(dtype)
+
+
+def sdpa_reference(case, inp, scale=None):
+    """Per (request, branch): dense K/V gathered through the block table, then torch SDPA with a boolean mask."""
+    c = case
+    scale = c.scale if scale is None else scale
+    q = as_f64(inp["q"], c.q_dtype)
+    kc = as_f64(inp["k_cache"], c.kv_dtype)
+    vc = as_f64(inp["v_cache"], c.kv_dtype)
+    kb = as_f64(inp["k_branch"], c.branch_kv_dtype)
+    vb = as_f64(inp["v_branch"], c.branch_kv_dtype)
+    if inp["k_scale"] is not None:
+        ks = torch.from_numpy(inp["k_scale"]).to(torch.float64)
+        vs = torch.from_numpy(inp["v_scale"]).to(torch.float64)
+        kc = kc * ks[None, :, None, None]
+        vc = vc * vs[None, :, None, None]
+        if c.branch_kv_dtype == "fp8_e4m3":
+            kb = kb * ks[None, None, None, :, None]
+            vb = vb * vs[None, None, None, :, None]
+    G = c.Hq // c.Hkv
+    out = torch.empty((c.B, c.gamma, c.L, c.Hq, c.D), dtype=torch.float64)
+    for b in range(c.B):
+        P = c.prefix_lens[b]
+        nblk = -(-P // c.block_size)
+        if inp["block_tables"] is None:
+            ids = torch.arange(b * c.max_blocks, b * c.max_blocks + nblk)
+        else:
+            ids = torch.from_numpy(inp["block_tables"][b, :nblk].astype(np.int64))
+        kp = kc[ids].permute(1, 0, 2, 3).reshape(c.Hkv, nblk * c.block_size, c.D)[:, :P]
+        vp = vc[ids].permute(1, 0, 2, 3).reshape(c.Hkv, nblk * c.block_size, c.D)[:, :P]
+        for g in range(c.gamma):
+            k = torch.cat([kp, kb[b, g].permute(1, 0, 2)], dim=1).repeat_interleave(G, dim=0)
+            v = torch.cat([vp, vb[b, g].permute(1, 0, 2)], dim=1).repeat_interleave(G, dim=0)
+            qq = q[b, g].permute(1, 0, 2)  # [Hq, L, D]
+            mask = torch.ones((c.L, P + c.L), dtype=torch.bool)
+            mask[:, P:] = torch.tril(torch.ones((c.L, c.L), dtype=torch.bool))
+            o = F.scaled_dot_product_attention(qq[None], k[None], v[None], attn_mask=mask, scale=scale)[0]
+            out[b, g] = o.permute(1, 0, 2)
+    return out.numpy()
+
+
+SMALL = W.AttnCase("small", (37,), 1, 5, 2, 2, 16, "f32", "f32", "f32", "f32", block_size=4)
+
+
+def test_storage_widening_matches_torch(oracle):
+    allb = np.arange(256, dtype=np.uint8)
+    np.testing.assert_array_equal(oracle.widen(allb, "fp8_e4m3"), as_f64(allb, "fp8_e4m3").numpy())
+    bits = np.random.default_rng(1).integers(0, 0x7F80, size=4096).astype(np.uint16)
+    bits[::2] |= 0x8000
+    np.testing.assert_array_equal(oracle.widen(bits, "bf16"), as_f64(bits, "bf16").numpy())
+
+
+def test_single_branch_equals_sdpa_with_prefix_mask(oracle):
+    inp = W.make_attention_inputs(SMALL)
+    out, _ = run(oracle, SMALL, inp)
+    np.testing.assert_allclose(out, sdpa_reference(SMALL, inp), rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("dtypes", [("f32", "f32", "f32"), ("bf16", "bf16", "bf16"), ("bf16", "fp8_e4m3", "fp8_e4m3"),
+                                    ("bf16", "fp8_e4m3", "bf16")])
+@pytest.mark.parametrize("paged", [False, True])
+def test_gqa_branches_requests_paging_equal_sdpa(oracle, dtypes, paged):
+    case = W.AttnCase("mix", (19, 0, 33), 3, 4, 6, 2, 8, dtypes[0], dtypes[1], dtypes[2], "f32", block_size=4,
+                      paged=paged, seed=3)
+    inp = W.make_attention_inputs(case)
+    out, _ = run(oracle, case, inp)
+    np.testing.assert_allclose(out, sdpa_reference(case, inp), rtol=1e-11, atol=1e-12)
+
+
+def test_no_prefix_is_plain_causal_attention(oracle):
+    case = replace(SMALL, prefix_lens=(0,), L=9)
+    inp = W.make_attention_inputs(case)
+    out, _ = run(oracle, case, inp)
+    q = as_f64(inp["q"], "f32")[0, 0].permute(1, 0, 2)[None]
+    k = as_f64(inp["k_branch"], "f32")[0, 0].permute(1, 0, 2)[None]
+    v = as_f64(inp["v_branch"], "f32")[0, 0].permute(1, 0, 2)[None]
+    ref = F.scaled_dot_product_attention(q, k, v, is_causal=True, scale=case.scale)[0].permute(1, 0, 2)
+    np.testing.assert_allclose(out[0, 0], ref.numpy(), rtol=1e-12, atol=1e-13)
+
+
+def test_single_token_branch_is_decode_attention(oracle):
+    case = replace(SMALL, L=1, gamma=2)
+    inp = W.make_attention_inputs(case)
+    out, _ = run(oracle, case, inp)
+    np.testing.assert_allclose(out, sdpa_reference(case, inp), rtol=1e-12, atol=1e-13)
+
+
+def test_shared_prefix_equals_independent_branches(oracle):
+    """Batch of gamma branches == gamma separate single-branch problems on the same prefix (Algorithm 1)."""
+    case = W.AttnCase("iso", (29,), 4, 6, 4, 2, 8, "f32", "f32", "f32", "f32", block_size=4, paged=True, seed=5)
+    inp = W.make_attention_inputs(case)
+    out, lse = run(oracle, case, inp)
+    one = replace(case, gamma=1)
+    for g in range(case.gamma):
+        sub = dict(inp)
+        for name in ("q", "k_branch", "v_branch"):
+            sub[name] = np.ascontiguousarray(inp[name][:, g:g + 1])
+        o, l = run(oracle, one, sub)
+        np.testing.assert_array_equal(out[:, g:g + 1], o)
+        np.testing.assert_array_equal(lse[:, g:g + 1], l)
+
+
+def test_branch_isolation_and_causality(oracle):
+    case = W.AttnCase("iso", (21,), 3, 5, 4, 2, 8, "f32", "f32", "f32", "f32", block_size=4, seed=6)
+    inp = W.make_attention_inputs(case)
+    base, _ = run(oracle, case, inp)
+    # other branches' private K/V never reach branch 1
+    pert = {k: (None if v is None else v.copy()) for k, v in inp.items()}
+    pert["k_branch"][:, 0] += 3.0
+    pert["v_branch"][:, 2] -= 2.0
+    out, _ = run(oracle, case, pert)
+    np.testing.assert_array_equal(out[:, 1], base[:, 1])
+    assert not np.array_equal(out[:, 0], base[:, 0]) and not np.array_equal(out[:, 2], base[:, 2])
+    # tokens after i never reach row i
+    pert = {k: (None if v is None else v.copy()) for k, v in inp.items()}
+    pert["k_branch"][:, :, 3:] *= -1.0
+    pert["v_branch"][:, :, 3:] += 1.0
+    out, _ = run(oracle, case, pert)
+    np.testing.assert_array_equal(out[:, :, :3], base[:, :, :3])
+    assert not np.array_equal(out[:, :, 3], base[:, :, 3])
+    # the token's own key IS visible (j <= i, not j < i)
+    pert = {k: (None if v is None else v.copy()) for k, v in inp.items()}
+    pert["v_branch"][:, :, 0] += 1.0
+    out, _ = run(oracle, case, pert)
+    assert not np.array_equal(out[:, :, 0], base[:, :, 0])
+
+
+def test_closed_forms(oracle):
+    case = W.AttnCase("cf", (13,), 2, 4, 4, 2, 8, "f32", "f32", "f32", "f32", block_size=4, seed=7)
+    inp = W.make_attention_inputs(case)
+    # all keys equal -> arithmetic mean of the visible values
+    eq = dict(inp)
+    eq["k_cache"] = np.ones_like(inp["k_cache"])
+    eq["k_branch"] = np.ones_like(inp["k_branch"])
+    out, lse = run(oracle, case, eq)
+    vc = inp["v_cache"].astype(np.float64)
+    vb = inp["v_branch"].astype(np.float64)
+    G = case.Hq // case.Hkv
+    for g in range(case.gamma):
+        for i in range(case.L):
+            for h in range(case.Hq):
+                hk = h // G
+                vis = np.concatenate([vc[:, hk].reshape(-1, case.D)[:13], vb[0, g, :i + 1, hk]], axis=0)
+                np.testing.assert_allclose(out[0, g, i, h], vis.mean(axis=0), rtol=1e-13, atol=1e-14)
+                qsum = inp["q"][0, g, i, h].astype(np.float64).sum() * case.scale
+                assert lse[0, g, i, h] == pytest.approx(qsum + math.log(13 + i + 1), rel=1e-12, abs=1e-12)
+    # constant V -> that constant
+    cv = dict(inp)
+    cv["v_cache"] = np.full_like(inp["v_cache"], 0.75)
+    cv["v_branch"] = np.full_like(inp["v_branch"], 0.75)
+    out, _ = run(oracle, case, cv)
+    np.testing.assert_allclose(out, 0.75, rtol=1e-13)
+    # one key dominating by a score margin of ~1000 -> exactly its value row
+    dom = {k: (None if v is None else v.copy()) for k, v in inp.items()}
+    dom["q"][:] = 1.0
+    dom["k_cache"][:] = 0.0
+    dom["k_branch"][:] = 0.0
+    dom["k_cache"][1, :, 2, :] = 400.0   # logical key 6 of the contiguous cache
+    out, _ = run(oracle, case, dom)
+    for h in range(case.Hq):
+        np.testing.assert_allclose(out[0, :, :, h], np.broadcast_to(vc[1, h // G, 2], (2, 4, 8)), rtol=1e-12)
+
+
+def test_row_weights_sum_to_one_and_reproduce_output(oracle):
+    case = W.AttnCase("w", (26,), 2, 6, 4, 2, 8, "bf16", "fp8_e4m3", "fp8_e4m3", "f32", block_size=4, paged=True,
+                      seed=8)
+    inp = W.make_attention_inputs(case)
+    out, lse = run(oracle, case, inp)
+    ref = sdpa_reference(case, inp)
+    for row_id in (0, 17, case.gamma * case.L * case.Hq - 1):
+        w = oracle.attention_row_weights(**inp, q_dtype=case.q_dtype, kv_dtype=case.kv_dtype,
+                                         branch_kv_dtype=case.branch_kv_dtype, block_size=case.block_size,
+                                         scale=case.scale, row_id=row_id)
+        i = (row_id // case.Hq) % case.L
+        assert w.shape == (26 + i + 1,)
+        assert abs(w.sum() - 1.0) < 1e-12
+        assert (w > 0).all()
+        np.testing.assert_allclose(out.reshape(-1, case.D)[row_id], ref.reshape(-1, case.D)[row_id], rtol=1e-11)
+
+
+def test_lse_matches_logsumexp(oracle):
+    case = W.AttnCase("lse", (23,), 2, 3, 4, 2, 8, "f32", "f32", "f32", "f32", block_size=4, seed=9)
+    inp = W.make_attention_inputs(case)
+    _, lse = run(oracle, case, inp)
+    q = torch.from_numpy(inp["q"]).double()
+    kc = torch.from_numpy(inp["k_cache"]).double().permute(1, 0, 2, 3).reshape(case.Hkv, -1, case.D)[:, :23]
+    kb = torch.from_numpy(inp["k_branch"]).double()
+    G = case.Hq // case.Hkv
+    for g in range(case.gamma):
+        for i in range(case.L):
+            for h in range(case.Hq):
+                keys = torch.cat([kc[h // G], kb[0, g, :i + 1, h // G]], dim=0)
+                s = (keys @ q[0, g, i, h]) * case.scale
+                assert lse[0, g, i, h] == pytest.approx(torch.logsumexp(s, 0).item(), rel=1e-13, abs=1e-13)
+
+
+def test_block_permutation_invariance(oracle):
+    case = W.AttnCase("perm", (30, 11), 2, 3, 2, 1, 8, "f32", "f32", "f32", "f32", block_size=4, paged=True, seed=10)
+    inp = W.make_attention_inputs(case)
+    base, _ = run(oracle, case, inp)
+    nb = inp["k_cache"].shape[0]
+    perm = np.random.default_rng(0).permutation(nb)          # new physical slot of old block j is perm[j]
+    moved = dict(inp)
+    moved["k_cache"] = np.empty_like(inp["k_cache"])
+    moved["v_cache"] = np.empty_like(inp["v_cache"])
+    moved["k_cache"][perm] = inp["k_cache"]
+    moved["v_cache"][perm] = inp["v_cache"]
+    moved["block_tables"] = perm[inp["block_tables"]].astype(np.int32)
+    out, _ = run(oracle, case, moved)
+    np.testing.assert_array_equal(out, base)
+
+
+def test_fp8_scale_identities(oracle):
+    case = W.AttnCase("sc", (20,), 2, 3, 4, 2, 8, "bf16", "fp8_e4m3", "fp8_e4m3", "f32", block_size=4, seed=11)
+    inp = W.make_attention_inputs(case)
+    base, _ = run(oracle, case, inp)
+    twice = dict(inp)
+    twice["v_scale"] = inp["v_scale"] * np.float32(2.0)
+    out, _ = run(oracle, case, twice)
+    np.testing.assert_array_equal(out, 2.0 * base)
+    shifted = dict(inp)
+    shifted["k_scale"] = inp["k_scale"] * np.float32(4.0)
+    out, _ = run(oracle, case, shifted, scale=case.scale / 4.0)
+    np.testing.assert_allclose(out, base, rtol=1e-13, atol=1e-15)
+
+
+def test_row_subset_equals_full(oracle):
+    case = W.AttnCase("rows", (18, 7), 2, 4, 4, 2, 8, "bf16", "bf16", "bf16", "f32", block_size=4, paged=True, seed=12)
+    inp = W.make_attention_inputs(case)
+    out, lse = run(oracle, case, inp)
+    ids = np.array([0, 5, 63, 32, 47, 16, 31], dtype=np.int64)
+    o, l = run(oracle, case, inp, row_ids=ids)
+    np.testing.assert_array_equal(o, out.reshape(-1, case.D)[ids])
+    np.testing.assert_array_equal(l, lse.reshape(-1)[ids])
+
+
+def test_config1_shape_runs_and_matches_sdpa(oracle):
+    case, _ = W.config(1)
+    inp = W.make_attention_inputs(case)
+    out, _ = run(oracle, case, inp)
+    assert out.shape == (1, 2, 8, 4, 64)
+    np.testing.assert_allclose(out, sdpa_reference(case, inp), rtol=1e-11, atol=1e-13)
+
+
+def test_rejects_bad_arguments(oracle):
+    inp = W.make_attention_inputs(SMALL)
+    bad = dict(inp)
+    bad["prefix_lens"] = np.array([10_000], dtype=np.int32)
+    with pytest.raises(ValueError):
+        run(oracle, SMALL, bad)
+    with pytest.raises(ValueError):
+        run(oracle, SMALL, inp, row_ids=np.array([10 ** 9]))

@@ -1,0 +1,54 @@
+"""The pins must be able to fail: plant plausible mistakes in a copy of the oracle's C source (on the CPU), build
+each, and check that the pin suites reject every one of them."""
+import os
+import subprocess
+import sys
+from pathlib import Path
+
+import pytest
+
+ROOT = Path(__file__).resolve().parent.parent
+SRC = (ROOT / "oracle" / "la_oracle.c").read_text()
+
+MUTANTS = {
+    # attention
+    "causal_off_by_one": ("const int64_t n = (int64_t)P + i + 1;", "const int64_t n = (int64_t)P + i;"),
+    "sees_whole_branch": ("const int64_t n = (int64_t)P + i + 1;", "const int64_t n = (int64_t)P + L;"),
+    "scale_dropped": ("    s *= a->scale;\n", ""),
+    "gqa_head_map": ("h = hk * G + (int)(it % G);", "h = (int)(it % G) * Hkv + hk;"),
+    "wrong_branch_kv": ("int64_t base = ((((int64_t)b * a->gamma + g) * a->L + i) * a->Hkv + hk) * D;",
+                        "int64_t base = ((((int64_t)b * a->gamma + 0) * a->L + i) * a->Hkv + hk) * D;"),
+    "block_table_ignored": ("int64_t phys = a->block_tables ?", "int64_t phys = 0 ?"),
+    "block_offset": ("(j % a->block_size)) * D;", "((j + 1) % a->block_size)) * D;"),
+    "k_scale_on_v": ("load_elem(a->v_cache, a->kv_dtype, base + d) * vs;", "load_elem(a->v_cache, a->kv_dtype, base + d) * ks;"),
+    "no_max_subtraction_sign": ("w[j] = exp(w[j] - m);", "w[j] = exp(m - w[j]);"),
+    "fp8_bias": ("ldexp(1.0 + (double)m / 8.0, e - 7)", "ldexp(1.0 + (double)m / 8.0, e - 8)"),
+    "fp8_subnormal": ("ldexp((double)m / 8.0, -6)", "ldexp((double)m / 8.0, -7)"),
+    # accept / resample
+    "ratio_inverted": ("const int accept = (u * q[x] < p[x]);", "const int accept = (u * p[x] < q[x]);"),
+    "no_stop_at_rejection": ("        n = i;\n        break;", "        n = i;"),
+    "residual_sign": ("r[v] = p[v] - q[v];", "r[v] = q[v] - p[v];"),
+    "resample_from_p": ("        if (r[v] < 0.0) r[v] = 0.0;\n", "        r[v] = p[v];\n"),
+    "bonus_from_wrong_row": ("((int64_t)nb * (K + 1) + K) * V, V, temperature, r);",
+                             "((int64_t)nb * (K + 1) + K - 1) * V, V, temperature, r);"),
+    "cdf_not_strict_start": ("      if (c > thr) {", "      if (c >= thr) {"),
+    "temperature_ignored": ("p[v] = load_elem(logits, dtype, base + v) / temperature;",
+                            "p[v] = load_elem(logits, dtype, base + v);"),
+    "draft_row_index": ("softmax_row(draft_logits, logits_dtype, ((int64_t)nb * K + i) * V",
+                        "softmax_row(draft_logits, logits_dtype, ((int64_t)nb * K + 0) * V"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_pins_reject_mutant(name, tmp_path):
+    old, new = MUTANTS[name]
+    assert SRC.count(old) == 1, f"mutation site for {name} not found exactly once"
+    src = tmp_path / "mutant.c"
+    lib = tmp_path / "libmutant.so"
+    src.write_text(SRC.replace(old, new))
+    subprocess.run(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-w", "-o", str(lib), str(src), "-lm"], check=True)
+    env = dict(os.environ, LA_ORACLE_LIB=str(lib))
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
+                        "tests/test_oracle_attention.py", "tests/test_oracle_accept.py"],
+                       cwd=ROOT, env=env, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 1, f"mutant {name} was not caught:\n{r.stdout[-2000:]}"
