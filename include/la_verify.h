@@ -1,0 +1,174 @@
+/*
+ * la_verify.h -- C ABI of the MI355X (gfx950) verification hot path of
+ * Lookahead Reasoning (arXiv 2506.19830).
+ *
+ * One verification pass of the target model expands the drafted reasoning
+ * steps together (Section 3.1, Algorithm 1 "in parallel do": every candidate
+ * continuation shares the prefix x_{1:t} and differs only in what was appended
+ * after it), and token-level speculative decoding runs inside each step
+ * (Section 2 "Speculative Decoding", Section 3.3).  The two entry points are
+ * the two data-parallel pieces of that pass:
+ *
+ *   la_verify_attention  attention of gamma branches x L tokens against one
+ *                        shared prefix KV cache plus branch-private KV
+ *   la_spec_accept       accept length and one extra token per branch from
+ *                        target/draft logits, drafted tokens and uniforms
+ *
+ * Conventions for every call
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary
+ *     host memory.  All tensors are dense, row-major, 16-byte aligned.
+ *   - The caller owns every buffer.  The library allocates no device memory,
+ *     creates no stream and never synchronises; all work is enqueued on
+ *     `hip_stream` (a hipStream_t passed as void*, NULL = the null stream).
+ *   - Arguments are validated on the host before anything is launched; a
+ *     rejected call launches nothing and returns a status code.  No exception
+ *     or abort crosses this boundary.
+ *   - Results are deterministic: the same inputs give bit-identical outputs.
+ *   - Indices handed in by the caller (block ids, drafted token ids) are not
+ *     range-checked on the device; out-of-range values are undefined behaviour.
+ */
+#ifndef LA_VERIFY_H
+#define LA_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* only the la_* entry points below are exported from the shared library */
+#define LA_API __attribute__((visibility("default")))
+
+typedef enum {
+  LA_OK = 0,
+  LA_ERR_INVALID_ARG = 1,        /* NULL / negative / inconsistent argument            */
+  LA_ERR_UNSUPPORTED = 2,        /* valid, but no kernel for this shape / dtype mix    */
+  LA_ERR_WORKSPACE_TOO_SMALL = 3,
+  LA_ERR_LAUNCH = 4              /* the HIP runtime refused a launch                   */
+} la_status;
+
+typedef enum {
+  LA_F32 = 0,
+  LA_BF16 = 1,
+  LA_FP8_E4M3 = 2                /* OCP e4m3fn: no infinities, max 448                 */
+} la_dtype;
+
+/* ------------------------------------------------------------------------- *
+ *  la_verify_attention
+ *
+ *  For request b, branch g, token i, query head h (KV head h / (Hq/Hkv)):
+ *      keys/values = prefix tokens 0..P_b-1 of request b, then tokens 0..i of
+ *                    branch g itself (causal inside the branch; other branches
+ *                    are invisible -- Algorithm 1, prefixes x'_j)
+ *      out = softmax(softmax_scale * q . K^T) V         lse = log sum exp
+ *  The prefix cache is read once per KV head and shared by every branch and
+ *  every query head of the group.
+ *
+ *  Supported combinations (anything else: LA_ERR_UNSUPPORTED)
+ *      q f32,  cache f32,  branch f32,  out f32        head_dim 64 / 128 / 256
+ *      q bf16, cache bf16, branch bf16, out bf16|f32   head_dim 128
+ *      q bf16, cache fp8,  branch fp8|bf16, out bf16|f32  head_dim 128
+ *  fp8 storage is multiplied by k_scale[kv_head] / v_scale[kv_head]; a branch
+ *  K/V stored as fp8 uses the same scales as the cache.
+ * ------------------------------------------------------------------------- */
+typedef struct {
+  int32_t num_requests;            /* B >= 1                                           */
+  int32_t num_q_heads;             /* Hq, multiple of num_kv_heads                     */
+  int32_t num_kv_heads;            /* Hkv                                              */
+  int32_t head_dim;                /* D                                                */
+  int32_t gamma;                   /* branches per request                             */
+  int32_t branch_len;              /* L: tokens per branch (each a query and one private K,V) */
+  int32_t block_size;              /* tokens per cache block, multiple of 16           */
+  int32_t max_blocks_per_request;  /* row stride of block_tables                       */
+  int32_t q_dtype, kv_dtype, branch_kv_dtype, out_dtype;   /* la_dtype                 */
+  float softmax_scale;             /* e.g. 1/sqrt(D); > 0                              */
+  int32_t kv_split_tokens;         /* 0 = let the library choose how the prefix is cut
+                                      into independently reduced chunks; otherwise the
+                                      chunk length in tokens (multiple of 64)           */
+} la_attn_desc;
+
+/* Bytes of device workspace la_verify_attention needs for this descriptor and
+ * these prefix lengths (host array [B]).  0 is a valid answer. */
+LA_API la_status la_verify_attention_workspace(const la_attn_desc *desc, const int32_t *prefix_lens_host,
+                                        size_t *bytes_out);
+
+LA_API la_status la_verify_attention(
+    const la_attn_desc *desc,
+    const void *q,                   /* dev [B, gamma, L, Hq, D]            q_dtype              */
+    const void *k_cache,             /* dev [num_blocks, Hkv, block_size, D] kv_dtype (may be NULL if every prefix is empty) */
+    const void *v_cache,             /* dev, same shape as k_cache                               */
+    const int32_t *block_tables,     /* dev [B, max_blocks_per_request] physical block of each
+                                        logical block; NULL => request b owns blocks
+                                        b*max_blocks .. (b+1)*max_blocks-1 in order             */
+    const int32_t *prefix_lens,      /* dev [B] prefix length of each request, 0 allowed; the
+                                        last block may be partly filled                         */
+    const int32_t *prefix_lens_host, /* host [B], same values (used to size the launch)         */
+    const void *k_branch,            /* dev [B, gamma, L, Hkv, D]           branch_kv_dtype      */
+    const void *v_branch,            /* dev, same shape                                          */
+    const float *k_scale,            /* dev [Hkv] or NULL (=1); only read for fp8 storage        */
+    const float *v_scale,            /* dev [Hkv] or NULL (=1)                                   */
+    void *out,                       /* dev [B, gamma, L, Hq, D]            out_dtype            */
+    float *lse,                      /* dev [B, gamma, L, Hq] natural-log sum-exp, or NULL       */
+    void *workspace, size_t workspace_bytes, /* dev scratch, contents undefined before and after */
+    void *hip_stream);
+
+/* ------------------------------------------------------------------------- *
+ *  la_spec_accept
+ *
+ *  Token-level speculative sampling (Section 2): with p_i = softmax(target
+ *  row i / T) and q_i = softmax(draft row i / T), the drafted tokens x_0..
+ *  x_{K-1} of a branch are examined in order; x_i is accepted when
+ *  u_accept[i] * q_i(x_i) < p_i(x_i)  (probability min(1, p/q)); at the first
+ *  rejection n the walk stops and next_token is drawn from
+ *  norm(max(0, p_n - q_n)); when all K are accepted (n = K) next_token is
+ *  drawn from the extra target row p_K.  Drawing is inverse-CDF in token
+ *  order: the first v whose running sum exceeds u_sample * total.
+ *
+ *  The accept test runs in fp32; the resampling row is evaluated in fp64.
+ * ------------------------------------------------------------------------- */
+typedef struct {
+  int32_t num_branches;   /* NB >= 1                                   */
+  int32_t num_draft;      /* K  >= 1 drafted tokens per branch          */
+  int32_t vocab;          /* V  >= 1                                   */
+  int32_t logits_dtype;   /* LA_F32 or LA_BF16                          */
+  float temperature;      /* T > 0, divides every logit                 */
+} la_accept_desc;
+
+LA_API la_status la_spec_accept_workspace(const la_accept_desc *desc, size_t *bytes_out);
+
+LA_API la_status la_spec_accept(
+    const la_accept_desc *desc,
+    const void *target_logits,   /* dev [NB, K+1, V]                                      */
+    const void *draft_logits,    /* dev [NB, K,   V]                                      */
+    const int32_t *draft_tokens, /* dev [NB, K]  each in 0..V-1                           */
+    const float *u_accept,       /* dev [NB, K]  uniforms in [0,1)                        */
+    const float *u_sample,       /* dev [NB]     uniforms in [0,1)                        */
+    int32_t *accepted_len,       /* dev [NB] out: n in 0..K                               */
+    int32_t *next_token,         /* dev [NB] out: in 0..V-1                               */
+    float *accept_ratio,         /* dev [NB, K] out or NULL: p_i(x_i)/q_i(x_i) as computed,
+                                    every position (also those after the rejection)      */
+    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* ------------------------------------------------------------------------- *
+ *  Diagnostics
+ * ------------------------------------------------------------------------- */
+LA_API const char *la_status_string(la_status s);
+
+/* Per-kernel timing for benchmarks.  While enabled, every kernel the library
+ * launches is bracketed by HIP events on the caller's stream (process-wide
+ * state, not thread-safe; at most LA_PROFILE_MAX_RECORDS launches are kept,
+ * later ones are dropped).  la_profile_collect synchronises on the recorded
+ * events and accumulates them; la_profile_get then reports, per kernel slot,
+ * its name, number of timed launches and their total duration. */
+#define LA_PROFILE_MAX_RECORDS 8192
+LA_API la_status la_profile_enable(int on);
+LA_API la_status la_profile_collect(void);
+LA_API int32_t la_profile_num_kernels(void);
+LA_API la_status la_profile_get(int32_t slot, const char **name, int64_t *launches, double *total_ms);
+LA_API la_status la_profile_reset(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LA_VERIFY_H */

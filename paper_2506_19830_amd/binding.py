@@ -1,0 +1,198 @@
+"""ctypes binding of ``libla_verify.so`` (argument marshalling only).
+
+The functions mirror the C ABI in ``include/la_verify.h`` name for name.  torch
+is used for device memory and the current HIP stream, nothing else: every step
+of the verification path runs inside the library's kernels.  There is no
+fallback -- if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = Path(__file__).resolve().parent
+LIB_PATH = _HERE / "libla_verify.so"
+
+LA_F32, LA_BF16, LA_FP8_E4M3 = 0, 1, 2
+DTYPE_CODES = {"f32": LA_F32, "bf16": LA_BF16, "fp8_e4m3": LA_FP8_E4M3}
+_TORCH_DTYPES = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch.float8_e4m3fn}
+
+EXPORTED_SYMBOLS = (
+    "la_verify_attention_workspace", "la_verify_attention", "la_spec_accept_workspace", "la_spec_accept",
+    "la_status_string", "la_profile_enable", "la_profile_collect", "la_profile_num_kernels", "la_profile_get",
+    "la_profile_reset",
+)
+
+
+class la_attn_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "num_requests", "num_q_heads", "num_kv_heads", "head_dim", "gamma", "branch_len", "block_size",
+        "max_blocks_per_request", "q_dtype", "kv_dtype", "branch_kv_dtype", "out_dtype")] + [
+        ("softmax_scale", ctypes.c_float), ("kv_split_tokens", ctypes.c_int32)]
+
+
+class la_accept_desc(ctypes.Structure):
+    _fields_ = [("num_branches", ctypes.c_int32), ("num_draft", ctypes.c_int32), ("vocab", ctypes.c_int32),
+                ("logits_dtype", ctypes.c_int32), ("temperature", ctypes.c_float)]
+
+
+class LaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load the HIP library; raises if it was not built (there is no other implementation)."""
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it first (python -m paper_2506_19830_amd.build or "
+                "__graft_entry__.build()); the verification path has no fallback")
+        lib = ctypes.CDLL(str(LIB_PATH))
+        vp, i32p = ctypes.c_void_p, ctypes.c_void_p
+        lib.la_verify_attention_workspace.restype = ctypes.c_int
+        lib.la_verify_attention_workspace.argtypes = [ctypes.POINTER(la_attn_desc), ctypes.POINTER(ctypes.c_int32),
+                                                      ctypes.POINTER(ctypes.c_size_t)]
+        lib.la_verify_attention.restype = ctypes.c_int
+        lib.la_verify_attention.argtypes = [ctypes.POINTER(la_attn_desc), vp, vp, vp, i32p, i32p,
+                                            ctypes.POINTER(ctypes.c_int32), vp, vp, vp, vp, vp, vp, vp,
+                                            ctypes.c_size_t, vp]
+        lib.la_spec_accept_workspace.restype = ctypes.c_int
+        lib.la_spec_accept_workspace.argtypes = [ctypes.POINTER(la_accept_desc), ctypes.POINTER(ctypes.c_size_t)]
+        lib.la_spec_accept.restype = ctypes.c_int
+        lib.la_spec_accept.argtypes = [ctypes.POINTER(la_accept_desc), vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                       ctypes.c_size_t, vp]
+        lib.la_status_string.restype = ctypes.c_char_p
+        lib.la_status_string.argtypes = [ctypes.c_int]
+        lib.la_profile_enable.restype = ctypes.c_int
+        lib.la_profile_enable.argtypes = [ctypes.c_int]
+        lib.la_profile_collect.restype = ctypes.c_int
+        lib.la_profile_reset.restype = ctypes.c_int
+        lib.la_profile_num_kernels.restype = ctypes.c_int32
+        lib.la_profile_get.restype = ctypes.c_int
+        lib.la_profile_get.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_char_p),
+                                       ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_double)]
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().la_status_string(int(status)).decode()
+
+
+def _ptr(t: Optional[torch.Tensor]) -> ctypes.c_void_p:
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_attn_desc(*, num_requests, num_q_heads, num_kv_heads, head_dim, gamma, branch_len, block_size,
+                   max_blocks_per_request, q_dtype, kv_dtype, branch_kv_dtype, out_dtype, softmax_scale,
+                   kv_split_tokens=0) -> la_attn_desc:
+    return la_attn_desc(num_requests, num_q_heads, num_kv_heads, head_dim, gamma, branch_len, block_size,
+                        max_blocks_per_request, DTYPE_CODES[q_dtype], DTYPE_CODES[kv_dtype],
+                        DTYPE_CODES[branch_kv_dtype], DTYPE_CODES[out_dtype], softmax_scale, kv_split_tokens)
+
+
+def _host_lens(prefix_lens_host: Sequence[int]):
+    arr = (ctypes.c_int32 * len(prefix_lens_host))(*[int(x) for x in prefix_lens_host])
+    return arr
+
+
+def la_verify_attention_workspace(desc: la_attn_desc, prefix_lens_host: Sequence[int]) -> int:
+    out = ctypes.c_size_t(0)
+    st = load().la_verify_attention_workspace(ctypes.byref(desc), _host_lens(prefix_lens_host), ctypes.byref(out))
+    if st:
+        raise LaError(st, "la_verify_attention_workspace")
+    return int(out.value)
+
+
+def la_verify_attention(desc: la_attn_desc, q, k_cache, v_cache, block_tables, prefix_lens, prefix_lens_host,
+                        k_branch, v_branch, k_scale, v_scale, out, lse, workspace) -> None:
+    """Enqueue one verify-attention pass on torch's current stream.  All tensors are device tensors the caller
+    allocated (``workspace`` a uint8 tensor of at least ``la_verify_attention_workspace`` bytes, or None)."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = load().la_verify_attention(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+                                    _ptr(prefix_lens), _host_lens(prefix_lens_host), _ptr(k_branch), _ptr(v_branch),
+                                    _ptr(k_scale), _ptr(v_scale), _ptr(out), _ptr(lse), _ptr(workspace),
+                                    ctypes.c_size_t(ws_bytes), _stream())
+    if st:
+        raise LaError(st, "la_verify_attention")
+
+
+def make_accept_desc(*, num_branches, num_draft, vocab, logits_dtype, temperature=1.0) -> la_accept_desc:
+    return la_accept_desc(num_branches, num_draft, vocab, DTYPE_CODES[logits_dtype], temperature)
+
+
+def la_spec_accept_workspace(desc: la_accept_desc) -> int:
+    out = ctypes.c_size_t(0)
+    st = load().la_spec_accept_workspace(ctypes.byref(desc), ctypes.byref(out))
+    if st:
+        raise LaError(st, "la_spec_accept_workspace")
+    return int(out.value)
+
+
+def la_spec_accept(desc: la_accept_desc, target_logits, draft_logits, draft_tokens, u_accept, u_sample,
+                   accepted_len, next_token, accept_ratio, workspace) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = load().la_spec_accept(ctypes.byref(desc), _ptr(target_logits), _ptr(draft_logits), _ptr(draft_tokens),
+                               _ptr(u_accept), _ptr(u_sample), _ptr(accepted_len), _ptr(next_token),
+                               _ptr(accept_ratio), _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream())
+    if st:
+        raise LaError(st, "la_spec_accept")
+
+
+# ------------------------------------------------------------------------------------------- profiling
+
+def la_profile_enable(on: bool) -> None:
+    load().la_profile_enable(int(bool(on)))
+
+
+def la_profile_reset() -> None:
+    load().la_profile_reset()
+
+
+def la_profile_collect() -> dict:
+    """Synchronise on the recorded events; returns {kernel: (launches, total_ms)} since the last reset."""
+    lib = load()
+    st = lib.la_profile_collect()
+    if st:
+        raise LaError(st, "la_profile_collect")
+    res = {}
+    for slot in range(lib.la_profile_num_kernels()):
+        name = ctypes.c_char_p()
+        n = ctypes.c_int64()
+        ms = ctypes.c_double()
+        lib.la_profile_get(slot, ctypes.byref(name), ctypes.byref(n), ctypes.byref(ms))
+        res[name.value.decode()] = (int(n.value), float(ms.value))
+    return res
+
+
+# ------------------------------------------------------------------------------------------- tensor plumbing
+
+def to_device(bits, dtype: str, device="cuda") -> Optional[torch.Tensor]:
+    """numpy storage array (fp32 / uint16 bf16 bits / uint8 fp8 bits) -> device tensor of the matching torch dtype."""
+    if bits is None:
+        return None
+    import numpy as np
+    if dtype == "f32":
+        return torch.from_numpy(np.ascontiguousarray(bits, dtype=np.float32)).to(device)
+    if dtype == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device).view(torch.bfloat16)
+    if dtype == "fp8_e4m3":
+        return torch.from_numpy(np.ascontiguousarray(bits)).to(device).view(torch.float8_e4m3fn)
+    raise ValueError(dtype)
+
+
+def empty_out(shape, dtype: str, device="cuda") -> torch.Tensor:
+    return torch.empty(shape, dtype=_TORCH_DTYPES[dtype], device=device)

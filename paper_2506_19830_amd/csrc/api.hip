@@ -1,0 +1,311 @@
+// Host side of libla_verify: argument validation, launch planning, the extern "C" entry points
+// declared in la_verify.h and the optional per-kernel event timing.
+#include <math.h>
+#include <string.h>
+
+#include <vector>
+
+#include "la_internal.hpp"
+
+namespace la {
+namespace {
+
+constexpr int kNumCUs = 256;  // MI355X
+
+inline bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+enum AttnPath { PATH_NONE = 0, PATH_F32, PATH_MFMA };
+
+struct AttnPlan {
+  AttnPath path;
+  bool kv_fp8, br_fp8;
+  int tile_m, n_row_tiles, chunk_len, s_max, total_units;
+  size_t part_o_bytes, part_ml_bytes;
+};
+
+la_status validate_desc(const la_attn_desc *d) {
+  if (!d) return LA_ERR_INVALID_ARG;
+  if (d->num_requests < 1 || d->num_q_heads < 1 || d->num_kv_heads < 1 || d->head_dim < 1 || d->gamma < 1 ||
+      d->branch_len < 1)
+    return LA_ERR_INVALID_ARG;
+  if (d->num_q_heads % d->num_kv_heads) return LA_ERR_INVALID_ARG;
+  if (d->block_size < 16 || d->block_size % 16) return LA_ERR_INVALID_ARG;
+  if (d->max_blocks_per_request < 0) return LA_ERR_INVALID_ARG;
+  if (!(d->softmax_scale > 0.f) || !isfinite(d->softmax_scale)) return LA_ERR_INVALID_ARG;
+  if (d->kv_split_tokens < 0 || d->kv_split_tokens % 64) return LA_ERR_INVALID_ARG;
+  const int32_t dts[4] = {d->q_dtype, d->kv_dtype, d->branch_kv_dtype, d->out_dtype};
+  for (int i = 0; i < 4; ++i)
+    if (dts[i] < LA_F32 || dts[i] > LA_FP8_E4M3) return LA_ERR_INVALID_ARG;
+  // rows and prefix tokens are indexed with 32-bit integers on the device
+  const int64_t n_rows = (int64_t)d->gamma * d->branch_len * d->num_q_heads;
+  if (n_rows * d->num_requests > (int64_t)1 << 30) return LA_ERR_UNSUPPORTED;
+  if ((int64_t)d->max_blocks_per_request * d->block_size > (int64_t)1 << 30) return LA_ERR_UNSUPPORTED;
+  return LA_OK;
+}
+
+la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, AttnPlan *plan) {
+  la_status st = validate_desc(d);
+  if (st != LA_OK) return st;
+  if (!prefix_lens_host) return LA_ERR_INVALID_ARG;
+  int64_t max_p = 0, sum_p = 0;
+  for (int b = 0; b < d->num_requests; ++b) {
+    const int64_t P = prefix_lens_host[b];
+    if (P < 0 || P > (int64_t)d->max_blocks_per_request * d->block_size) return LA_ERR_INVALID_ARG;
+    max_p = P > max_p ? P : max_p;
+    sum_p += P;
+  }
+  memset(plan, 0, sizeof *plan);
+  const bool all_f32 =
+      d->q_dtype == LA_F32 && d->kv_dtype == LA_F32 && d->branch_kv_dtype == LA_F32 && d->out_dtype == LA_F32;
+  if (all_f32) {
+    if (d->head_dim != 64 && d->head_dim != 128 && d->head_dim != 256) return LA_ERR_UNSUPPORTED;
+    plan->path = PATH_F32;
+    return LA_OK;
+  }
+  const bool out_ok = d->out_dtype == LA_BF16 || d->out_dtype == LA_F32;
+  const bool bf16_all = d->q_dtype == LA_BF16 && d->kv_dtype == LA_BF16 && d->branch_kv_dtype == LA_BF16;
+  const bool fp8_kv = d->q_dtype == LA_BF16 && d->kv_dtype == LA_FP8_E4M3 &&
+                      (d->branch_kv_dtype == LA_FP8_E4M3 || d->branch_kv_dtype == LA_BF16);
+  if (!out_ok || !(bf16_all || fp8_kv) || d->head_dim != 128) return LA_ERR_UNSUPPORTED;
+  plan->path = PATH_MFMA;
+  plan->kv_fp8 = d->kv_dtype == LA_FP8_E4M3;
+  plan->br_fp8 = d->branch_kv_dtype == LA_FP8_E4M3;
+
+  const int G = d->num_q_heads / d->num_kv_heads;
+  const int R = d->gamma * d->branch_len * G;
+  plan->tile_m = attn_mfma_tile_m(R);
+  plan->n_row_tiles = (R + plan->tile_m - 1) / plan->tile_m;
+  int chunk = d->kv_split_tokens;
+  if (chunk == 0) {
+    // Aim for about four workgroups per CU so that the tail of the launch is short, but keep a
+    // chunk at least 1024 tokens long: every chunk costs one partial (row x (D+2) floats) in HBM.
+    const int64_t base_wgs = (int64_t)d->num_kv_heads * plan->n_row_tiles;
+    const int64_t want_units = (4 * kNumCUs + base_wgs - 1) / base_wgs;
+    int64_t len = sum_p > 0 ? (sum_p + want_units - 1) / want_units : 1024;
+    len = ((len + 63) / 64) * 64;
+    if (len < 1024) len = 1024;
+    chunk = (int)len;
+  }
+  plan->chunk_len = chunk;
+  int s_max = 1, total = 0;
+  for (int b = 0; b < d->num_requests; ++b) {
+    const int nc = attn_num_chunks(prefix_lens_host[b], chunk);
+    s_max = nc > s_max ? nc : s_max;
+    total += nc;
+  }
+  plan->s_max = s_max;
+  plan->total_units = total;
+  const size_t n_rows = (size_t)d->gamma * d->branch_len * d->num_q_heads;
+  plan->part_o_bytes = align_up((size_t)d->num_requests * s_max * n_rows * d->head_dim * sizeof(float));
+  plan->part_ml_bytes = align_up((size_t)d->num_requests * s_max * n_rows * 2 * sizeof(float));
+  return LA_OK;
+}
+
+// ---- profiling ---------------------------------------------------------------------------------
+const char *kSlotNames[SLOT_COUNT] = {"attn_mfma",     "attn_merge",   "attn_f32",   "accept_stats",
+                                      "accept_decide", "accept_resid", "accept_pick"};
+struct ProfileRecord {
+  int slot;
+  hipEvent_t start, stop;
+};
+bool g_profile_on = false;
+std::vector<ProfileRecord> g_records;       // pending (not yet collected)
+std::vector<hipEvent_t> g_free_events;
+int64_t g_launches[SLOT_COUNT];
+double g_total_ms[SLOT_COUNT];
+hipEvent_t g_open_start;                    // start event of the scope being recorded
+bool g_open = false;
+
+hipEvent_t take_event() {
+  if (!g_free_events.empty()) {
+    hipEvent_t e = g_free_events.back();
+    g_free_events.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+}  // namespace
+
+void profile_before(int slot, hipStream_t stream) {
+  (void)slot;
+  g_open = false;
+  if (!g_profile_on || g_records.size() >= LA_PROFILE_MAX_RECORDS) return;
+  hipEvent_t e = take_event();
+  if (!e) return;
+  if (hipEventRecord(e, stream) != hipSuccess) {
+    g_free_events.push_back(e);
+    return;
+  }
+  g_open_start = e;
+  g_open = true;
+}
+
+void profile_after(int slot, hipStream_t stream) {
+  if (!g_open) return;
+  g_open = false;
+  hipEvent_t e = take_event();
+  if (!e || hipEventRecord(e, stream) != hipSuccess) {
+    if (e) g_free_events.push_back(e);
+    g_free_events.push_back(g_open_start);
+    return;
+  }
+  g_records.push_back({slot, g_open_start, e});
+}
+
+}  // namespace la
+
+using namespace la;
+
+extern "C" {
+
+const char *la_status_string(la_status s) {
+  switch (s) {
+    case LA_OK: return "ok";
+    case LA_ERR_INVALID_ARG: return "invalid argument";
+    case LA_ERR_UNSUPPORTED: return "unsupported shape or dtype combination";
+    case LA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case LA_ERR_LAUNCH: return "kernel launch failed";
+  }
+  return "unknown status";
+}
+
+la_status la_verify_attention_workspace(const la_attn_desc *desc, const int32_t *prefix_lens_host,
+                                        size_t *bytes_out) {
+  if (!bytes_out) return LA_ERR_INVALID_ARG;
+  AttnPlan plan;
+  la_status st = make_plan(desc, prefix_lens_host, &plan);
+  if (st != LA_OK) return st;
+  *bytes_out = plan.path == PATH_MFMA ? plan.part_o_bytes + plan.part_ml_bytes : 0;
+  return LA_OK;
+}
+
+la_status la_verify_attention(const la_attn_desc *desc, const void *q, const void *k_cache, const void *v_cache,
+                              const int32_t *block_tables, const int32_t *prefix_lens,
+                              const int32_t *prefix_lens_host, const void *k_branch, const void *v_branch,
+                              const float *k_scale, const float *v_scale, void *out, float *lse, void *workspace,
+                              size_t workspace_bytes, void *hip_stream) {
+  AttnPlan plan;
+  la_status st = make_plan(desc, prefix_lens_host, &plan);
+  if (st != LA_OK) return st;
+  if (!q || !prefix_lens || !k_branch || !v_branch || !out) return LA_ERR_INVALID_ARG;
+  bool any_prefix = false;
+  for (int b = 0; b < desc->num_requests; ++b) any_prefix |= prefix_lens_host[b] > 0;
+  if (any_prefix && (!k_cache || !v_cache)) return LA_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(k_branch) || !aligned16(v_branch) ||
+      !aligned16(out) || !aligned16(workspace))
+    return LA_ERR_INVALID_ARG;
+  const size_t need = plan.path == PATH_MFMA ? plan.part_o_bytes + plan.part_ml_bytes : 0;
+  if (need > 0 && (!workspace || workspace_bytes < need)) return LA_ERR_WORKSPACE_TOO_SMALL;
+
+  AttnParams p;
+  memset(&p, 0, sizeof p);
+  p.q = q, p.k_cache = k_cache, p.v_cache = v_cache, p.k_branch = k_branch, p.v_branch = v_branch;
+  p.block_tables = block_tables, p.prefix_lens = prefix_lens;
+  p.k_scale = k_scale, p.v_scale = v_scale;
+  p.out = out, p.lse = lse;
+  p.B = desc->num_requests, p.Hq = desc->num_q_heads, p.Hkv = desc->num_kv_heads;
+  p.G = p.Hq / p.Hkv, p.D = desc->head_dim, p.gamma = desc->gamma, p.L = desc->branch_len;
+  p.block_size = desc->block_size, p.max_blocks = desc->max_blocks_per_request;
+  p.R = p.gamma * p.L * p.G;
+  p.n_rows = p.gamma * p.L * p.Hq;
+  p.out_f32 = desc->out_dtype == LA_F32;
+  p.scale_log2 = desc->softmax_scale * 1.44269504088896340736f;
+  hipStream_t stream = (hipStream_t)hip_stream;
+
+  if (plan.path == PATH_F32) return launch_attn_f32(p, stream) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+
+  p.n_row_tiles = plan.n_row_tiles, p.chunk_len = plan.chunk_len, p.s_max = plan.s_max;
+  p.total_units = plan.total_units;
+  p.part_o = (float *)workspace;
+  p.part_ml = (float *)((uint8_t *)workspace + plan.part_o_bytes);
+  if (launch_attn_mfma(p, plan.kv_fp8, plan.br_fp8, stream) != hipSuccess) return LA_ERR_LAUNCH;
+  if (launch_attn_merge(p, stream) != hipSuccess) return LA_ERR_LAUNCH;
+  return LA_OK;
+}
+
+static la_status validate_accept(const la_accept_desc *d) {
+  if (!d) return LA_ERR_INVALID_ARG;
+  if (d->num_branches < 1 || d->num_draft < 1 || d->vocab < 1) return LA_ERR_INVALID_ARG;
+  if (d->logits_dtype != LA_F32 && d->logits_dtype != LA_BF16)
+    return d->logits_dtype == LA_FP8_E4M3 ? LA_ERR_UNSUPPORTED : LA_ERR_INVALID_ARG;
+  if (!(d->temperature > 0.f) || !isfinite(d->temperature)) return LA_ERR_INVALID_ARG;
+  if ((int64_t)d->num_branches * (2 * (int64_t)d->num_draft + 1) > 65535) return LA_ERR_UNSUPPORTED;  // grid.y
+  return LA_OK;
+}
+
+la_status la_spec_accept_workspace(const la_accept_desc *desc, size_t *bytes_out) {
+  la_status st = validate_accept(desc);
+  if (st != LA_OK) return st;
+  if (!bytes_out) return LA_ERR_INVALID_ARG;
+  *bytes_out = accept_workspace_bytes(desc->num_branches, desc->num_draft, desc->vocab, nullptr, nullptr);
+  return LA_OK;
+}
+
+la_status la_spec_accept(const la_accept_desc *desc, const void *target_logits, const void *draft_logits,
+                         const int32_t *draft_tokens, const float *u_accept, const float *u_sample,
+                         int32_t *accepted_len, int32_t *next_token, float *accept_ratio, void *workspace,
+                         size_t workspace_bytes, void *hip_stream) {
+  la_status st = validate_accept(desc);
+  if (st != LA_OK) return st;
+  if (!target_logits || !draft_logits || !draft_tokens || !u_accept || !u_sample || !accepted_len || !next_token)
+    return LA_ERR_INVALID_ARG;
+  if (!aligned16(target_logits) || !aligned16(draft_logits) || !aligned16(workspace)) return LA_ERR_INVALID_ARG;
+  AcceptParams p;
+  memset(&p, 0, sizeof p);
+  const size_t need = accept_workspace_bytes(desc->num_branches, desc->num_draft, desc->vocab, &p.chunk, &p.n_chunks);
+  if (!workspace || workspace_bytes < need) return LA_ERR_WORKSPACE_TOO_SMALL;
+  p.target = target_logits, p.draft = draft_logits, p.tokens = draft_tokens;
+  p.u_accept = u_accept, p.u_sample = u_sample;
+  p.accepted_len = accepted_len, p.next_token = next_token, p.ratio = accept_ratio;
+  p.NB = desc->num_branches, p.K = desc->num_draft, p.V = desc->vocab;
+  p.bf16 = desc->logits_dtype == LA_BF16;
+  p.inv_temp_log2 = 1.44269504088896340736f / desc->temperature;
+  p.temperature = (double)desc->temperature;
+  p.inv_temp = 1.0 / p.temperature;
+  accept_carve_workspace(p, workspace);
+  return launch_accept(p, (hipStream_t)hip_stream) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
+la_status la_profile_enable(int on) {
+  g_profile_on = on != 0;
+  return LA_OK;
+}
+
+la_status la_profile_collect(void) {
+  la_status st = LA_OK;
+  for (const ProfileRecord &r : g_records) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.stop) == hipSuccess && hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
+      g_launches[r.slot] += 1;
+      g_total_ms[r.slot] += ms;
+    } else {
+      st = LA_ERR_LAUNCH;
+    }
+    g_free_events.push_back(r.start);
+    g_free_events.push_back(r.stop);
+  }
+  g_records.clear();
+  return st;
+}
+
+int32_t la_profile_num_kernels(void) { return SLOT_COUNT; }
+
+la_status la_profile_get(int32_t slot, const char **name, int64_t *launches, double *total_ms) {
+  if (slot < 0 || slot >= SLOT_COUNT) return LA_ERR_INVALID_ARG;
+  if (name) *name = kSlotNames[slot];
+  if (launches) *launches = g_launches[slot];
+  if (total_ms) *total_ms = g_total_ms[slot];
+  return LA_OK;
+}
+
+la_status la_profile_reset(void) {
+  la_status st = la_profile_collect();
+  for (int i = 0; i < SLOT_COUNT; ++i) g_launches[i] = 0, g_total_ms[i] = 0.0;
+  return st;
+}
+
+}  // extern "C"

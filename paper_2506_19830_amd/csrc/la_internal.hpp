@@ -1,0 +1,105 @@
+// Internal declarations shared by the host API and the kernel translation units
+// of libla_verify (gfx950 only).  Nothing here is part of the public C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "la_verify.h"
+
+namespace la {
+
+// ----------------------------------------------------------------------------
+// Verify attention.
+//
+// Rows that share one KV head: r = (g*L + i)*G + hh  for branch g, token i and
+// query head hh of the group (G = Hq/Hkv); R = gamma*L*G of them per request.
+// The prefix of request b is cut into n_chunks(b) = max(1, ceil(P_b/chunk_len))
+// chunks; one workgroup reduces (row tile, kv head, chunk) and the one that owns
+// the last chunk also reduces the branch-private keys.  Each writes an
+// unnormalised partial (O, m, l) that the merge kernel combines.
+// ----------------------------------------------------------------------------
+struct AttnParams {
+  const void *q, *k_cache, *v_cache, *k_branch, *v_branch;
+  const int32_t *block_tables, *prefix_lens;
+  const float *k_scale, *v_scale;
+  float *part_o;   // [B, s_max, n_rows, D]
+  float *part_ml;  // [B, s_max, n_rows, 2]  (running max in log2 units, sum)
+  void *out;       // [B, n_rows, D]
+  float *lse;      // [B, n_rows] or null
+  int B, Hq, Hkv, G, D, gamma, L;
+  int block_size, max_blocks;
+  int R;            // gamma*L*G
+  int n_rows;       // gamma*L*Hq
+  int n_row_tiles;  // ceil(R / tile_m)
+  int chunk_len;    // prefix tokens per chunk, multiple of 64
+  int s_max;        // partial slots per request = max_b n_chunks(b)
+  int total_units;  // sum_b n_chunks(b)
+  int out_f32;      // output dtype: 1 = fp32, 0 = bf16
+  float scale_log2; // softmax_scale * log2(e)
+};
+
+__host__ __device__ inline int attn_num_chunks(int prefix_len, int chunk_len) {
+  int n = (prefix_len + chunk_len - 1) / chunk_len;
+  return n < 1 ? 1 : n;
+}
+
+enum KernelSlot {
+  SLOT_ATTN_MFMA = 0,
+  SLOT_ATTN_MERGE,
+  SLOT_ATTN_F32,
+  SLOT_ACCEPT_STATS,
+  SLOT_ACCEPT_DECIDE,
+  SLOT_ACCEPT_RESID,
+  SLOT_ACCEPT_PICK,
+  SLOT_COUNT
+};
+
+// tile_m of the MFMA kernel variant chosen for this problem (rows per workgroup)
+int attn_mfma_tile_m(int R);
+hipError_t launch_attn_mfma(const AttnParams &p, bool kv_fp8, bool br_fp8, hipStream_t stream);
+hipError_t launch_attn_merge(const AttnParams &p, hipStream_t stream);
+hipError_t launch_attn_f32(const AttnParams &p, hipStream_t stream);
+
+// ----------------------------------------------------------------------------
+// Speculative accept / resample.
+// ----------------------------------------------------------------------------
+struct AcceptParams {
+  const void *target, *draft;  // [NB, K+1, V], [NB, K, V]
+  const int32_t *tokens;       // [NB, K]
+  const float *u_accept, *u_sample;
+  int32_t *accepted_len, *next_token;
+  float *ratio;                // [NB, K] or null
+  int NB, K, V, bf16;
+  int chunk;                   // vocabulary elements per workgroup slice
+  int n_chunks;                // ceil(V / chunk)
+  float inv_temp_log2;         // log2(e) / T
+  double inv_temp;             // 1 / T   (fp64 resampling path divides by T exactly as T)
+  double temperature;
+  // workspace
+  float *stats;                // [rows = NB*(2K+1), n_chunks, 2]  (max, sum 2^(z-max)) in log2 units
+  int32_t *n_acc;              // [NB]
+  double *zsum;                // [NB, 2, n_chunks]  fp64 sum exp(z - max) of the resampling rows
+  double *rsum;                // [NB, 2, n_chunks]  fp64 chunk sums of the residual and of p
+  float *rowmax;               // [NB, 2] exact row maxima (raw logits) of the resampling rows
+};
+
+size_t accept_workspace_bytes(int NB, int K, int V, int *chunk_out, int *n_chunks_out);
+void accept_carve_workspace(AcceptParams &p, void *ws);
+hipError_t launch_accept(const AcceptParams &p, hipStream_t stream);
+
+// ----------------------------------------------------------------------------
+// Optional per-kernel event timing (see la_profile_* in the public header).
+// ----------------------------------------------------------------------------
+void profile_before(int slot, hipStream_t stream);
+void profile_after(int slot, hipStream_t stream);
+
+struct ProfileScope {
+  int slot;
+  hipStream_t stream;
+  ProfileScope(int s, hipStream_t st) : slot(s), stream(st) { profile_before(slot, stream); }
+  ~ProfileScope() { profile_after(slot, stream); }
+};
+
+}  // namespace la

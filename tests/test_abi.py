@@ -1,0 +1,115 @@
+"""The C-ABI library without a GPU: it loads, exports every symbol the header declares, and rejects bad
+arguments on the host before anything is launched (these calls never reach a kernel)."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+
+from paper_2506_19830_amd import binding as B
+
+ROOT = Path(__file__).resolve().parent.parent
+
+
+def good_desc(**kw):
+    d = dict(num_requests=1, num_q_heads=40, num_kv_heads=8, head_dim=128, gamma=8, branch_len=64, block_size=16,
+             max_blocks_per_request=2048, q_dtype="bf16", kv_dtype="fp8_e4m3", branch_kv_dtype="fp8_e4m3",
+             out_dtype="bf16", softmax_scale=128 ** -0.5)
+    d.update(kw)
+    return B.make_attn_desc(**d)
+
+
+def test_library_exports_every_declared_symbol():
+    header = (ROOT / "include" / "la_verify.h").read_text()
+    declared = set(re.findall(r"LA_API[^;(]*?\b(la_\w+)\s*\(", header))
+    assert declared == set(B.EXPORTED_SYMBOLS)
+    lib = B.load()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_layouts_match_the_header():
+    assert ctypes.sizeof(B.la_attn_desc) == 14 * 4
+    assert ctypes.sizeof(B.la_accept_desc) == 5 * 4
+
+
+def test_status_strings():
+    assert B.status_string(0) == "ok"
+    assert "workspace" in B.status_string(3)
+    assert B.status_string(99) == "unknown status"
+
+
+def test_workspace_query_and_plan():
+    ws = B.la_verify_attention_workspace(good_desc(), [32768])
+    rows = 8 * 64 * 40
+    assert ws > 0 and ws % (rows * 130 * 4) < 512          # whole partial slots (O[128] + m + l per row)
+    assert B.la_verify_attention_workspace(good_desc(kv_split_tokens=32768), [32768]) < ws
+    f32 = good_desc(q_dtype="f32", kv_dtype="f32", branch_kv_dtype="f32", out_dtype="f32", head_dim=64)
+    assert B.la_verify_attention_workspace(f32, [32768]) == 0
+    acc = B.make_accept_desc(num_branches=8, num_draft=8, vocab=152064, logits_dtype="bf16")
+    assert B.la_spec_accept_workspace(acc) > 8 * 17 * 19 * 8
+
+
+@pytest.mark.parametrize("kw,lens,status", [
+    (dict(num_q_heads=41), [100], 1),
+    (dict(block_size=8), [100], 1),
+    (dict(softmax_scale=0.0), [100], 1),
+    (dict(kv_split_tokens=100), [100], 1),
+    (dict(gamma=0), [100], 1),
+    (dict(), [-1], 1),
+    (dict(max_blocks_per_request=4), [65], 1),
+    (dict(head_dim=64), [100], 2),
+    (dict(q_dtype="f32"), [100], 2),
+    (dict(kv_dtype="bf16", branch_kv_dtype="fp8_e4m3"), [100], 2),
+    (dict(out_dtype="fp8_e4m3"), [100], 2),
+])
+def test_attention_rejects_bad_descriptors(kw, lens, status):
+    with pytest.raises(B.LaError) as e:
+        B.la_verify_attention_workspace(good_desc(**kw), lens)
+    assert e.value.status == status
+
+
+def _call_attention(desc, lens, ptrs, ws_bytes):
+    lib = B.load()
+    arr = (ctypes.c_int32 * len(lens))(*lens)
+    vp = ctypes.c_void_p
+    return lib.la_verify_attention(ctypes.byref(desc), vp(ptrs.get("q", 256)), vp(ptrs.get("k", 256)),
+                                   vp(ptrs.get("v", 256)), vp(0), vp(ptrs.get("lens", 256)), arr,
+                                   vp(ptrs.get("kb", 256)), vp(ptrs.get("vb", 256)), vp(0), vp(0),
+                                   vp(ptrs.get("out", 256)), vp(0), vp(ptrs.get("ws", 256)),
+                                   ctypes.c_size_t(ws_bytes), vp(0))
+
+
+def test_attention_call_rejects_before_launch():
+    """Fake (never dereferenced) device addresses: each call must fail validation on the host."""
+    d = good_desc()
+    assert _call_attention(d, [32768], {"q": 0}, 1 << 40) == 1           # required pointer missing
+    assert _call_attention(d, [32768], {"k": 0}, 1 << 40) == 1           # prefix present but no cache
+    assert _call_attention(d, [32768], {"out": 264}, 1 << 40) == 1       # not 16-byte aligned
+    assert _call_attention(d, [32768], {}, 1024) == 3                    # workspace too small
+    assert _call_attention(d, [32768], {"ws": 0}, 0) == 3
+
+
+def test_accept_rejects_bad_arguments():
+    for kw, status in [(dict(num_branches=0), 1), (dict(num_draft=0), 1), (dict(vocab=0), 1),
+                       (dict(temperature=0.0), 1), (dict(logits_dtype="fp8_e4m3"), 2),
+                       (dict(num_branches=40000, num_draft=8), 2)]:
+        base = dict(num_branches=8, num_draft=8, vocab=152064, logits_dtype="bf16")
+        base.update(kw)
+        with pytest.raises(B.LaError) as e:
+            B.la_spec_accept_workspace(B.make_accept_desc(**base))
+        assert e.value.status == status
+    lib = B.load()
+    d = B.make_accept_desc(num_branches=8, num_draft=8, vocab=152064, logits_dtype="bf16")
+    vp = ctypes.c_void_p
+    args = [vp(256)] * 7 + [vp(0)]
+    assert lib.la_spec_accept(ctypes.byref(d), *args, vp(256), ctypes.c_size_t(16), vp(0)) == 3
+    args[0] = vp(0)
+    assert lib.la_spec_accept(ctypes.byref(d), *args, vp(256), ctypes.c_size_t(1 << 30), vp(0)) == 1
+
+
+def test_product_package_does_not_import_the_oracle():
+    for f in (ROOT / "paper_2506_19830_amd").rglob("*"):
+        if f.suffix in (".py", ".hip", ".hpp", ".h", ".cpp"):
+            text = f.read_text()
+            assert "import oracle" not in text and "from oracle" not in text and "la_oracle" not in text, f

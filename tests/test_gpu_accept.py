@@ -1,0 +1,76 @@
+"""GPU parity of la_spec_accept against the CPU oracle, through the C ABI.
+
+Bar: accepted lengths and token indices bit-exact for the fixed uniforms; branches whose decisive accept draw lies
+within 1e-6 of the min(1, p/q) threshold (in the oracle's fp64) are counted and set aside, as the benchmark states.
+"""
+import numpy as np
+import pytest
+
+from paper_2506_19830_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def check(oracle, case, max_near=None):
+    from gpu_util import compare_accept, run_accept
+    print(f"accept case {case.name} NB={case.NB} K={case.K} V={case.V} {case.logits_dtype} T={case.temperature}",
+          flush=True)
+    inp = W.make_accept_inputs(case)
+    got = run_accept(case, inp)
+    ref = oracle.spec_accept(**inp, logits_dtype=case.logits_dtype, temperature=case.temperature)
+    bad_n, bad_tok, near = compare_accept(got, ref)
+    print(f"  near-threshold branches set aside: {near} of {case.NB}", flush=True)
+    assert bad_n == 0, f"{bad_n} accepted lengths differ"
+    assert bad_tok == 0, f"{bad_tok} tokens differ"
+    if max_near is not None:
+        assert near <= max_near
+    examined = np.isfinite(ref["ratio"])
+    np.testing.assert_allclose(got["ratio"][examined], ref["ratio"][examined], rtol=2e-4)
+    assert (got["next_token"] >= 0).all() and (got["next_token"] < case.V).all()
+    return got, ref
+
+
+def test_config1_accept(oracle):
+    _, case = W.config(1)
+    check(oracle, case, max_near=0)
+
+
+@pytest.mark.parametrize("case", [
+    W.AcceptCase("many_small", 600, 4, 512, "f32", target_std=2.0, draft_noise_std=0.7, seed=1),
+    W.AcceptCase("odd_vocab_f32", 64, 3, 1001, "f32", seed=2),          # rows not 16-byte aligned: scalar loads
+    W.AcceptCase("odd_vocab_bf16", 64, 3, 8193, "bf16", seed=3),         # one full slice + 1 token
+    W.AcceptCase("tiny_vocab", 200, 2, 3, "f32", target_std=1.0, draft_noise_std=0.5, seed=4),
+    W.AcceptCase("two_slices_bf16", 50, 5, 16384, "bf16", seed=5),
+    W.AcceptCase("temperature", 100, 4, 4096, "f32", temperature=0.6, seed=6),
+    W.AcceptCase("k1", 128, 1, 2048, "bf16", seed=7),
+    W.AcceptCase("long_draft", 3, 70, 700, "f32", target_std=1.0, draft_noise_std=0.05, seed=8),   # K > 64
+], ids=lambda c: c.name)
+def test_accept_edge_shapes(oracle, case):
+    got, ref = check(oracle, case)
+    if case.name == "many_small":
+        # both outcomes are exercised
+        assert (ref["accepted_len"] == case.K).any() and (ref["accepted_len"] == 0).any()
+
+
+@pytest.mark.parametrize("n", [2, 3, 4, 5])
+def test_accept_benchmark_configs(oracle, n):
+    _, case = W.config(n)
+    check(oracle, case)
+
+
+def test_accept_is_deterministic():
+    from gpu_util import run_accept
+    case = W.AcceptCase("det", 16, 4, 50000, "bf16", seed=9)
+    inp = W.make_accept_inputs(case)
+    a, b = run_accept(case, inp), run_accept(case, inp)
+    for k in a:
+        np.testing.assert_array_equal(a[k], b[k])
+
+
+def test_identical_models_accept_everything():
+    from gpu_util import run_accept
+    case = W.AcceptCase("same", 8, 6, 30000, "bf16", draft_noise_std=0.0, seed=10)
+    inp = W.make_accept_inputs(case)
+    got = run_accept(case, inp)
+    np.testing.assert_array_equal(got["accepted_len"], case.K)
+    np.testing.assert_allclose(got["ratio"], 1.0, rtol=1e-6)
