@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the verification hot path on one MI355X.
+
+A *step* is one verification pass of a 64-layer, 40-query/8-KV-head, head_dim-128 target over one batch:
+for every layer, ``la_verify_attention`` of gamma=8 branches x L=64 tokens against a 32768-token shared prefix
+held as an fp8-e4m3 KV cache (bf16 queries), followed by one ``la_spec_accept`` over vocab 152064 for the
+8 branches x 8 drafted tokens.  All inputs are synthetic, seeded, and resident in HBM before the timed region.
+
+Prints ONE JSON line: whole-pass throughput in verified branch-tokens/s (the 512 query tokens of the batch per
+full 64-layer pass), the roofline of the dominant kernel (the MFMA prefix attention kernel, timed with HIP events
+on the launch stream by the library's profiling hook) and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+sys.path.insert(0, str(ROOT))
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
+PEAK_HBM_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--layers", type=int, default=None, help="layers in the sweep (default: the workload's 64)")
+    ap.add_argument("--config", type=int, default=5, help="benchmark configuration 2..5 (default 5, the headline)")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--kv-split-tokens", type=int, default=0)
+    return ap.parse_args()
+
+
+def read_traffic(name: str):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, if there is one."""
+    f = ROOT / "profiles" / name
+    if not f.exists():
+        return None
+    for line in f.read_text().splitlines():
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":", 1)[1])
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2506_19830_amd import binding as B
+    from paper_2506_19830_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    B.load()   # raises if the HIP library was not built: there is no fallback
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    attn_case, acc_case = W.config(args.config)
+    n_layers = args.layers if args.layers is not None else (W.NUM_LAYERS_CFG5 if args.config == 5 else 1)
+
+    # ---- inputs (resident in HBM before anything is timed) -------------------------------------------------
+    layers = [W.make_attention_inputs_device(W.with_layer(attn_case, l), dev) for l in range(n_layers)]
+    lens = [int(x) for x in attn_case.prefix_lens]
+    desc = B.make_attn_desc(num_requests=attn_case.B, num_q_heads=attn_case.Hq, num_kv_heads=attn_case.Hkv,
+                            head_dim=attn_case.D, gamma=attn_case.gamma, branch_len=attn_case.L,
+                            block_size=attn_case.block_size, max_blocks_per_request=attn_case.max_blocks,
+                            q_dtype=attn_case.q_dtype, kv_dtype=attn_case.kv_dtype,
+                            branch_kv_dtype=attn_case.branch_kv_dtype, out_dtype=attn_case.out_dtype,
+                            softmax_scale=attn_case.scale, kv_split_tokens=args.kv_split_tokens)
+    ws = torch.empty(max(16, B.la_verify_attention_workspace(desc, lens)), dtype=torch.uint8, device=dev)
+    outs = [B.empty_out((attn_case.B, attn_case.gamma, attn_case.L, attn_case.Hq, attn_case.D), attn_case.out_dtype,
+                        dev) for _ in range(n_layers)]
+
+    acc_np = W.make_accept_inputs(acc_case)
+    acc = {
+        "target_logits": B.to_device(acc_np["target_logits"], acc_case.logits_dtype, dev),
+        "draft_logits": B.to_device(acc_np["draft_logits"], acc_case.logits_dtype, dev),
+        "draft_tokens": torch.from_numpy(acc_np["draft_tokens"]).to(dev),
+        "u_accept": torch.from_numpy(acc_np["u_accept"]).to(dev),
+        "u_sample": torch.from_numpy(acc_np["u_sample"]).to(dev),
+    }
+    adesc = B.make_accept_desc(num_branches=acc_case.NB, num_draft=acc_case.K, vocab=acc_case.V,
+                               logits_dtype=acc_case.logits_dtype, temperature=acc_case.temperature)
+    aws = torch.empty(max(16, B.la_spec_accept_workspace(adesc)), dtype=torch.uint8, device=dev)
+    n_acc = torch.empty(acc_case.NB, dtype=torch.int32, device=dev)
+    nxt = torch.empty(acc_case.NB, dtype=torch.int32, device=dev)
+
+    def step():
+        for l in range(n_layers):
+            t = layers[l]
+            B.la_verify_attention(desc, t["q"], t["k_cache"], t["v_cache"], t["block_tables"], t["prefix_lens"], lens,
+                                  t["k_branch"], t["v_branch"], t["k_scale"], t["v_scale"], outs[l], None, ws)
+        B.la_spec_accept(adesc, acc["target_logits"], acc["draft_logits"], acc["draft_tokens"], acc["u_accept"],
+                         acc["u_sample"], n_acc, nxt, None, aws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly --steps steps, per-kernel HIP events recorded on the launch stream -------------
+    B.la_profile_reset()
+    B.la_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    B.la_profile_enable(False)
+    prof = B.la_profile_collect()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    branch_tokens = attn_case.branch_tokens
+    value = branch_tokens / (ms_per_step * 1e-3)
+
+    kern_launches, kern_ms = prof["attn_mfma"]
+    kern_avg_ms = kern_ms / max(1, kern_launches)
+    flops = attn_case.flops()
+    achieved_tflops = flops / (kern_avg_ms * 1e-3) / 1e12
+    alg_bytes = attn_case.algorithmic_bytes()
+    attn_ms = sum(prof[k][1] for k in ("attn_mfma", "attn_merge")) / args.steps
+    accept_ms = sum(prof[k][1] for k in ("accept_stats", "accept_decide", "accept_resid", "accept_pick")) / args.steps
+    stats_launches, stats_ms = prof["accept_stats"]
+    stats_gbs = acc_case.algorithmic_bytes() / (stats_ms / max(1, stats_launches) * 1e-3) / 1e9
+
+    result = {
+        "metric": "verified branch-tokens/sec + % HBM-BW peak, shared-prefix verify attention",
+        "value": value,
+        "unit": "branch-tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"config {args.config}: {attn_case.name}, {n_layers} layers, prefix {lens}, gamma "
+                        f"{attn_case.gamma} x L {attn_case.L}, {attn_case.Hq}q/{attn_case.Hkv}kv heads, D "
+                        f"{attn_case.D}, KV {attn_case.kv_dtype}, Q {attn_case.q_dtype}; accept NB {acc_case.NB} "
+                        f"K {acc_case.K} V {acc_case.V} {acc_case.logits_dtype}",
+            "layers": n_layers,
+            "branch_tokens_per_step": branch_tokens,
+            "kv_split_tokens": args.kv_split_tokens,
+        },
+        "roofline": {
+            "kernel": "attn_mfma_kernel",
+            "bound": "mfma",
+            "achieved": achieved_tflops,
+            "peak": PEAK_BF16_MFMA_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": achieved_tflops / PEAK_BF16_MFMA_TFLOPS,
+            "traffic": read_traffic(f"attn_mfma_config{args.config}_traffic.txt"),
+            "avg_launch_ms": kern_avg_ms,
+            "launches_timed": kern_launches,
+            "flops_per_launch": flops,
+            "algorithmic_bytes_per_launch": alg_bytes,
+            "hbm_gbs_at_algorithmic_bytes": alg_bytes / (kern_avg_ms * 1e-3) / 1e9,
+            "hbm_frac": alg_bytes / (kern_avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        },
+        "breakdown_ms_per_step": {"attention": attn_ms, "accept": accept_ms,
+                                  **{k: v[1] / args.steps for k, v in prof.items() if v[0]}},
+        "accept_stats_kernel": {"bound": "hbm", "achieved": stats_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                "frac": stats_gbs / PEAK_HBM_GBS,
+                                "algorithmic_bytes_per_launch": acc_case.algorithmic_bytes()},
+    }
+
+    # ---- CPU oracle on a bounded sample of the same workload (reported baseline, not a target) ----------------
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        host = W.device_inputs_to_numpy(attn_case, layers[0])
+        t0 = time.perf_counter()
+        ref, _ = oracle.verify_attention(**host, q_dtype=attn_case.q_dtype, kv_dtype=attn_case.kv_dtype,
+                                         branch_kv_dtype=attn_case.branch_kv_dtype, block_size=attn_case.block_size,
+                                         scale=attn_case.scale)
+        t_attn = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        aref = oracle.spec_accept(**acc_np, logits_dtype=acc_case.logits_dtype, temperature=acc_case.temperature)
+        t_acc = time.perf_counter() - t0
+        cpu_pass_s = t_attn * n_layers + t_acc
+        got = outs[0].double().cpu().numpy()
+        D = attn_case.D
+        err = np.abs(got.reshape(-1, D) - ref.reshape(-1, D)).max(1) / np.abs(ref.reshape(-1, D)).max(1)
+        near = np.array([(m[np.isfinite(m)] <= 1e-6).any() for m in aref["margin"]])
+        same = (n_acc.cpu().numpy() == aref["accepted_len"]) & (nxt.cpu().numpy() == aref["next_token"])
+        result["cpu_baseline"] = {
+            "value": branch_tokens / cpu_pass_s,
+            "unit": "branch-tokens/s",
+            "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"attention layer 0 of {n_layers} in full ({t_attn:.2f} s, scaled x{n_layers}) + the accept "
+                      f"call in full ({t_acc:.2f} s)",
+        }
+        result["parity"] = {"attention_layer0_max_row_rel_err": float(err.max()), "tolerance": 2e-2,
+                            "accept_mismatches": int((~same & ~near).sum()), "accept_near_threshold": int(near.sum())}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -265,3 +265,93 @@ def make_accept_inputs(case: AcceptCase) -> Dict[str, np.ndarray]:
 
 def with_layer(case: AttnCase, layer: int) -> AttnCase:
     return replace(case, layer=layer)
+
+
+# ----------------------------------------------------------------------------- on-device generators
+
+def make_attention_inputs_device(case: AttnCase, device="cuda"):
+    """Same recipe as :func:`make_attention_inputs`, drawn on the GPU with torch's seeded generator.
+
+    Used where the full-size tensors are too many to draw on the host in reasonable time (the 64-layer sweep:
+    4.3 GB of fp8 cache).  The values differ from the numpy stream for the same seed; a checker reads the tensors
+    back (``device_inputs_to_numpy``) so both sides still see identical bytes.
+    """
+    import torch
+
+    c = case
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch.float8_e4m3fn}
+    gen = torch.Generator(device=device)
+    gen.manual_seed((c.seed << 20) + 16 * c.layer + 1)
+    B, bs = c.B, c.block_size
+    blocks_needed = [-(-p // bs) for p in c.prefix_lens]
+    if c.paged:
+        num_blocks = max(1, sum(blocks_needed))
+        perm = torch.randperm(num_blocks, generator=gen, device=device).to(torch.int32)
+        tables = torch.zeros((B, c.max_blocks), dtype=torch.int32, device=device)
+        at = 0
+        for b, nb in enumerate(blocks_needed):
+            tables[b, :nb] = perm[at:at + nb]
+            at += nb
+    else:
+        num_blocks = B * c.max_blocks
+        tables = None
+
+    def normal(shape):
+        return torch.randn(shape, generator=gen, device=device, dtype=torch.float32)
+
+    q = normal((B, c.gamma, c.L, c.Hq, c.D))
+    kb = normal((B, c.gamma, c.L, c.Hkv, c.D))
+    vb = normal((B, c.gamma, c.L, c.Hkv, c.D))
+    kc = normal((num_blocks, c.Hkv, bs, c.D))
+    vc = normal((num_blocks, c.Hkv, bs, c.D))
+    k_scale = v_scale = None
+    if c.kv_dtype == "fp8_e4m3":
+        k_scale = (kc.abs().amax(dim=(0, 2, 3)) / FP8_E4M3_MAX).float()
+        v_scale = (vc.abs().amax(dim=(0, 2, 3)) / FP8_E4M3_MAX).float()
+        kc = kc / k_scale[None, :, None, None]
+        vc = vc / v_scale[None, :, None, None]
+    if c.branch_kv_dtype == "fp8_e4m3":
+        if k_scale is None:
+            raise ValueError("fp8 branch K/V needs an fp8 cache (shared scales)")
+        kb = (kb / k_scale[None, None, None, :, None]).clamp_(-FP8_E4M3_MAX, FP8_E4M3_MAX)
+        vb = (vb / v_scale[None, None, None, :, None]).clamp_(-FP8_E4M3_MAX, FP8_E4M3_MAX)
+    return {
+        "q": q.to(tdt[c.q_dtype]),
+        "k_cache": kc.to(tdt[c.kv_dtype]),
+        "v_cache": vc.to(tdt[c.kv_dtype]),
+        "block_tables": tables,
+        "prefix_lens": torch.tensor(c.prefix_lens, dtype=torch.int32, device=device),
+        "k_branch": kb.to(tdt[c.branch_kv_dtype]),
+        "v_branch": vb.to(tdt[c.branch_kv_dtype]),
+        "k_scale": k_scale,
+        "v_scale": v_scale,
+    }
+
+
+def device_inputs_to_numpy(case: AttnCase, dev: dict) -> Dict[str, Optional[np.ndarray]]:
+    """Read device tensors back as the storage arrays the host-side functions use (bit patterns for bf16/fp8)."""
+    import torch
+
+    def bits(t, dtype):
+        if t is None:
+            return None
+        t = t.detach().cpu().contiguous()
+        if dtype == "f32":
+            return t.numpy()
+        if dtype == "bf16":
+            return t.view(torch.int16).numpy().view(np.uint16)
+        if dtype == "fp8_e4m3":
+            return t.view(torch.uint8).numpy()
+        raise ValueError(dtype)
+
+    return {
+        "q": bits(dev["q"], case.q_dtype),
+        "k_cache": bits(dev["k_cache"], case.kv_dtype),
+        "v_cache": bits(dev["v_cache"], case.kv_dtype),
+        "block_tables": None if dev["block_tables"] is None else dev["block_tables"].cpu().numpy(),
+        "prefix_lens": dev["prefix_lens"].cpu().numpy(),
+        "k_branch": bits(dev["k_branch"], case.branch_kv_dtype),
+        "v_branch": bits(dev["v_branch"], case.branch_kv_dtype),
+        "k_scale": None if dev["k_scale"] is None else dev["k_scale"].cpu().numpy(),
+        "v_scale": None if dev["v_scale"] is None else dev["v_scale"].cpu().numpy(),
+    }
