@@ -79,7 +79,7 @@ typedef struct {
   int32_t head_dim;                /* D                                                */
   int32_t gamma;                   /* branches per request                             */
   int32_t branch_len;              /* L: tokens per branch (each a query and one private K,V) */
-  int32_t block_size;              /* tokens per cache block, multiple of 16           */
+  int32_t block_size;              /* tokens per cache block: power of two >= 16       */
   int32_t max_blocks_per_request;  /* row stride of block_tables                       */
   int32_t q_dtype, kv_dtype, branch_kv_dtype, out_dtype;   /* la_dtype                 */
   float softmax_scale;             /* e.g. 1/sqrt(D); > 0                              */

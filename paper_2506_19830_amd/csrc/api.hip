@@ -30,7 +30,7 @@ la_status validate_desc(const la_attn_desc *d) {
       d->branch_len < 1)
     return LA_ERR_INVALID_ARG;
   if (d->num_q_heads % d->num_kv_heads) return LA_ERR_INVALID_ARG;
-  if (d->block_size < 16 || d->block_size % 16) return LA_ERR_INVALID_ARG;
+  if (d->block_size < 16 || (d->block_size & (d->block_size - 1))) return LA_ERR_INVALID_ARG;  // power of two
   if (d->max_blocks_per_request < 0) return LA_ERR_INVALID_ARG;
   if (!(d->softmax_scale > 0.f) || !isfinite(d->softmax_scale)) return LA_ERR_INVALID_ARG;
   if (d->kv_split_tokens < 0 || d->kv_split_tokens % 64) return LA_ERR_INVALID_ARG;
@@ -86,6 +86,12 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, Attn
     len = ((len + 63) / 64) * 64;
     if (len < 1024) len = 1024;
     chunk = (int)len;
+  }
+  // the block ids of one chunk live in LDS
+  const int64_t max_chunk = (int64_t)(attn_mfma_max_chunk_blocks() - 1) * d->block_size;  // -1: unaligned chunk start
+  if (chunk > max_chunk) {
+    if (d->kv_split_tokens) return LA_ERR_UNSUPPORTED;
+    chunk = (int)(max_chunk / 64 * 64);
   }
   plan->chunk_len = chunk;
   int s_max = 1, total = 0;
@@ -210,6 +216,7 @@ la_status la_verify_attention(const la_attn_desc *desc, const void *q, const voi
   p.B = desc->num_requests, p.Hq = desc->num_q_heads, p.Hkv = desc->num_kv_heads;
   p.G = p.Hq / p.Hkv, p.D = desc->head_dim, p.gamma = desc->gamma, p.L = desc->branch_len;
   p.block_size = desc->block_size, p.max_blocks = desc->max_blocks_per_request;
+  p.block_shift = __builtin_ctz((unsigned)desc->block_size);
   p.R = p.gamma * p.L * p.G;
   p.n_rows = p.gamma * p.L * p.Hq;
   p.out_f32 = desc->out_dtype == LA_F32;

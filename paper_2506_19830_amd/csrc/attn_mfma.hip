@@ -37,7 +37,8 @@ constexpr int kVRow = kTileN * 2 + 16;       // bytes per d row of the V^T tile 
 constexpr int kKTileBytes = kTileN * kKRow;  // 17408
 constexpr int kVTileBytes = kD * kVRow;      // 18432
 constexpr int kStageBytes = kKTileBytes + kVTileBytes;
-constexpr int kLdsBytes = 2 * kStageBytes;   // double buffered: 71680
+constexpr int kMaxChunkBlocks = 4096;        // block ids of one chunk kept in LDS
+constexpr int kLdsTotal = 2 * kStageBytes + kMaxChunkBlocks * 4;   // two stages + block ids: 88064
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   f32x2 f = {a, b};
@@ -45,10 +46,10 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, h);
 }
 
-// two fp8-e4m3 of a 32-bit word (low or high half) -> two floats
+// two fp8-e4m3 of a 32-bit word (low or high half) -> a bf16 pair (exact), scale factor 1
 template <bool HI>
-__device__ __forceinline__ f32x2 fp8x2_to_f32(uint32_t w) {
-  return __builtin_amdgcn_cvt_pk_f32_fp8(w, HI);
+__device__ __forceinline__ uint32_t fp8x2_to_bf16x2(uint32_t w) {
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, HI));
 }
 
 // position of key quad kq (keys 4kq..4kq+3 of the tile) inside a V^T row: inside every group of 16 keys
@@ -57,9 +58,9 @@ __device__ __forceinline__ int vt_pos(int kq) { return 16 * (kq >> 2) + 8 * (kq 
 
 // Where the keys of one tile come from.
 struct TileSrc {
-  const uint8_t *k_base, *v_base;  // prefix: cache base; branch: row of token 0 of this request and kv head
-  const int32_t *table;            // prefix: block table row of the request or null (identity)
-  int ident_base;                  // prefix, identity mapping: first physical block of the request
+  const uint8_t *k_base, *v_base;  // prefix: cache base of this kv head; branch: row of token 0 of this request/head
+  const int32_t *blk;              // prefix: physical block ids of this chunk (LDS), indexed from first_lb
+  int first_lb;                    // prefix: logical block of blk[0]
   int first;                       // first key of the tile (prefix: token index; branch: token t = g*L+j)
   int limit;                       // keys >= limit are zero filled
   bool is_prefix;
@@ -71,61 +72,64 @@ struct TileRegs {
   uint32_t v[16];
 };
 
+// Address of key row `tok`.  Cache blocks are [block][Hkv][block_size][D]: inside a block consecutive tokens of
+// one head are contiguous.
 template <bool FP8>
 __device__ __forceinline__ const uint8_t *key_row(const AttnParams &p, const TileSrc &s, const uint8_t *base,
-                                                  int kvh, int tok) {
-  constexpr int esz = FP8 ? 1 : 2;
+                                                  int tok) {
+  constexpr int row_bytes = kD * (FP8 ? 1 : 2);
   if (s.is_prefix) {
-    const int lb = tok / p.block_size;
-    const int blk = s.table ? s.table[lb] : s.ident_base + lb;
-    return base + (((size_t)blk * p.Hkv + kvh) * p.block_size + (tok % p.block_size)) * (size_t)(kD * esz);
+    const int blk = s.blk[(tok >> p.block_shift) - s.first_lb];
+    return base + (((size_t)blk * p.Hkv) << p.block_shift) * row_bytes +
+           (size_t)(tok & (p.block_size - 1)) * row_bytes;
   }
-  return base + (size_t)tok * p.Hkv * (kD * esz);
+  return base + (size_t)tok * p.Hkv * row_bytes;
 }
 
-template <bool FP8>
-__device__ __forceinline__ void tile_load(const AttnParams &p, const TileSrc &s, int kvh, int tid, TileRegs &r) {
-  if constexpr (!FP8) {
+// Global -> registers.  FULL: every key of the tile is below s.limit.  Otherwise the address is clamped to the
+// last valid key and the value zeroed, so the loads stay unconditional and in bounds.
+template <bool FP8, bool FULL>
+__device__ __forceinline__ void tile_load(const AttnParams &p, const TileSrc &s, int tid, TileRegs &r) {
+  constexpr int row_bytes = kD * (FP8 ? 1 : 2);
+  constexpr int nk = FP8 ? 2 : 4;               // 16-byte K pieces per thread
+  constexpr int k_rows_per_pass = FP8 ? 32 : 16;  // keys covered by one pass of the 256 threads
+  constexpr int k_piece_mask = FP8 ? 7 : 15;
+  constexpr int k_piece_shift = FP8 ? 3 : 4;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {  // K: 16 B = 8 d of key (tid/16 + 16e)
-      const int tok = s.first + (tid >> 4) + 16 * e;
-      u32x4 val = {0, 0, 0, 0};
-      if (tok < s.limit) val = *(const u32x4 *)(key_row<FP8>(p, s, s.k_base, kvh, tok) + (tid & 15) * 16);
-      r.k[e] = val;
-    }
+  for (int e = 0; e < nk; ++e) {
+    const int tok = s.first + (tid >> k_piece_shift) + k_rows_per_pass * e;
+    const int tc = FULL ? tok : min(tok, s.limit - 1);
+    u32x4 val = *(const u32x4 *)(key_row<FP8>(p, s, s.k_base, tc) + (tid & k_piece_mask) * 16);
+    if (!FULL && tok >= s.limit) val = u32x4{0, 0, 0, 0};
+    r.k[e] = val;
+  }
+  constexpr int nv = FP8 ? 2 : 4;                // key quads per thread
+  constexpr int v_lane_mask = FP8 ? 31 : 63;     // 4-byte pieces per key row
+  constexpr int v_quad_shift = FP8 ? 5 : 6;
+  constexpr int v_quads_per_pass = FP8 ? 8 : 4;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {  // V: 4 B = d pair (tid%64) of the 4 keys of quad (tid/64 + 4e)
-      const int kq = (tid >> 6) + 4 * e;
+  for (int e = 0; e < nv; ++e) {
+    const int kq = (tid >> v_quad_shift) + v_quads_per_pass * e;
+    const int tok0 = s.first + 4 * kq;           // the four keys of a quad share a cache block (block_size % 16 == 0)
+    if (FULL || (s.is_prefix && tok0 + 3 < s.limit)) {
+      const uint8_t *row = key_row<FP8>(p, s, s.v_base, tok0) + (tid & v_lane_mask) * 4;
+      const size_t step = s.is_prefix ? (size_t)row_bytes : (size_t)p.Hkv * row_bytes;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) r.v[4 * e + c] = *(const uint32_t *)(row + c * step);
+    } else {
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const int tok = s.first + 4 * kq + c;
-        uint32_t val = 0;
-        if (tok < s.limit) val = *(const uint32_t *)(key_row<FP8>(p, s, s.v_base, kvh, tok) + (tid & 63) * 4);
-        r.v[4 * e + c] = val;
-      }
-    }
-  } else {
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {  // K: 16 B = 16 d of key (tid/8 + 32e)
-      const int tok = s.first + (tid >> 3) + 32 * e;
-      u32x4 val = {0, 0, 0, 0};
-      if (tok < s.limit) val = *(const u32x4 *)(key_row<FP8>(p, s, s.k_base, kvh, tok) + (tid & 7) * 16);
-      r.k[e] = val;
-    }
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {  // V: 4 B = d quad (tid%32) of the 4 keys of quad (tid/32 + 8e)
-      const int kq = (tid >> 5) + 8 * e;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const int tok = s.first + 4 * kq + c;
-        uint32_t val = 0;
-        if (tok < s.limit) val = *(const uint32_t *)(key_row<FP8>(p, s, s.v_base, kvh, tok) + (tid & 31) * 4);
-        r.v[4 * e + c] = val;
+        const int tok = tok0 + c;
+        const int tc = min(tok, s.limit - 1);
+        uint32_t val = *(const uint32_t *)(key_row<FP8>(p, s, s.v_base, tc) + (tid & v_lane_mask) * 4);
+        r.v[4 * e + c] = tok < s.limit ? val : 0u;
       }
     }
   }
 }
 
+// Registers -> LDS stage: K rows as they are, V transposed ([d][key], keys permuted by vt_pos); fp8 is widened to
+// bf16 on the way (exact: every e4m3 value is a bf16 value).
 template <bool FP8>
 __device__ __forceinline__ void tile_store(uint8_t *stage, int tid, const TileRegs &r) {
   uint8_t *kt = stage;
@@ -154,10 +158,9 @@ __device__ __forceinline__ void tile_store(uint8_t *stage, int tid, const TileRe
       uint32_t out[8];
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        const f32x2 lo = fp8x2_to_f32<false>(r.k[e][w]);
-        const f32x2 hi = fp8x2_to_f32<true>(r.k[e][w]);
-        out[2 * w] = pack_bf16(lo.x, lo.y);
-        out[2 * w + 1] = pack_bf16(hi.x, hi.y);
+        const uint32_t word = r.k[e][w];
+        out[2 * w] = fp8x2_to_bf16x2<false>(word);
+        out[2 * w + 1] = fp8x2_to_bf16x2<true>(word);
       }
       uint8_t *dst = kt + key * kKRow + (tid & 7) * 32;
       *(u32x4 *)(dst) = u32x4{out[0], out[1], out[2], out[3]};
@@ -167,24 +170,49 @@ __device__ __forceinline__ void tile_store(uint8_t *stage, int tid, const TileRe
     for (int e = 0; e < 2; ++e) {
       const int kq = (tid >> 5) + 8 * e;
       const int d0 = 4 * (tid & 31);
-      f32x2 lo[4], hi[4];  // of key c: (d0, d0+1) and (d0+2, d0+3)
+      uint32_t lo[4], hi[4];  // of key c: bf16 pairs (d0, d0+1) and (d0+2, d0+3)
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        lo[c] = fp8x2_to_f32<false>(r.v[4 * e + c]);
-        hi[c] = fp8x2_to_f32<true>(r.v[4 * e + c]);
+        lo[c] = fp8x2_to_bf16x2<false>(r.v[4 * e + c]);
+        hi[c] = fp8x2_to_bf16x2<true>(r.v[4 * e + c]);
       }
       uint8_t *dst = vt + d0 * kVRow + vt_pos(kq) * 2;
-      *(u32x2 *)(dst) = u32x2{pack_bf16(lo[0].x, lo[1].x), pack_bf16(lo[2].x, lo[3].x)};
-      *(u32x2 *)(dst + kVRow) = u32x2{pack_bf16(lo[0].y, lo[1].y), pack_bf16(lo[2].y, lo[3].y)};
-      *(u32x2 *)(dst + 2 * kVRow) = u32x2{pack_bf16(hi[0].x, hi[1].x), pack_bf16(hi[2].x, hi[3].x)};
-      *(u32x2 *)(dst + 3 * kVRow) = u32x2{pack_bf16(hi[0].y, hi[1].y), pack_bf16(hi[2].y, hi[3].y)};
+      // row d0: low halves of lo[0..3]; row d0+1: high halves; rows d0+2, d0+3 likewise from hi[]
+      *(u32x2 *)(dst) = u32x2{__builtin_amdgcn_perm(lo[1], lo[0], 0x05040100u),
+                              __builtin_amdgcn_perm(lo[3], lo[2], 0x05040100u)};
+      *(u32x2 *)(dst + kVRow) = u32x2{__builtin_amdgcn_perm(lo[1], lo[0], 0x07060302u),
+                                      __builtin_amdgcn_perm(lo[3], lo[2], 0x07060302u)};
+      *(u32x2 *)(dst + 2 * kVRow) = u32x2{__builtin_amdgcn_perm(hi[1], hi[0], 0x05040100u),
+                                          __builtin_amdgcn_perm(hi[3], hi[2], 0x05040100u)};
+      *(u32x2 *)(dst + 3 * kVRow) = u32x2{__builtin_amdgcn_perm(hi[1], hi[0], 0x07060302u),
+                                          __builtin_amdgcn_perm(hi[3], hi[2], 0x07060302u)};
     }
   }
 }
 
-template <bool KV_FP8, bool BR_FP8, int RB>
-__global__ __launch_bounds__(kThreads, RB == 1 ? 2 : 1) void attn_mfma_kernel(const AttnParams p) {
+// max / sum of a value with its partner in the other half of the wavefront (lane ^ 32)
+__device__ __forceinline__ float xhalf_max(float v) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, v);
+  const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  const uint32_t a = sw[0], b = sw[1];
+  return fmaxf(__builtin_bit_cast(float, a), __builtin_bit_cast(float, b));
+}
+__device__ __forceinline__ float xhalf_sum(float v) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, v);
+  const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  const uint32_t a = sw[0], b = sw[1];
+  return __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b);
+}
+
+// A running maximum is only raised when the tile maximum exceeds it by more than this many log2 units; until
+// then probabilities are allowed to reach 2^kRaise, which fp32 sums and bf16 operands hold without loss.  Raising
+// rarely keeps the accumulator rescale (128 multiplies per lane) off the common path.
+constexpr float kRaise = 6.0f;
+
+template <bool KV_FP8, bool BR_FP8>
+__global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(const AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  constexpr int RB = 2;           // 32-row blocks per wavefront
   constexpr int kTileM = 128 * RB;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -217,36 +245,50 @@ __global__ __launch_bounds__(kThreads, RB == 1 ? 2 : 1) void attn_mfma_kernel(co
   const int n_priv_tiles = (c == n_chunks - 1) ? (t_hi - tk0 + 1 + kTileN - 1) / kTileN : 0;
   const int n_tiles = n_prefix_tiles + n_priv_tiles;
 
-  constexpr int br_esz = BR_FP8 ? 1 : 2;
-  const size_t br_off = ((size_t)b * gl * p.Hkv + kvh) * (kD * br_esz);
+  // ---- physical block ids of this chunk -> LDS ---------------------------------------------
+  int32_t *blk_lds = (int32_t *)(lds + 2 * kStageBytes);
+  const int first_lb = k_begin >> p.block_shift;
+  if (n_prefix_tiles > 0) {
+    const int n_blk = ((k_end - 1) >> p.block_shift) - first_lb + 1;   // <= kMaxChunkBlocks (host guarantees)
+    const int32_t *table = p.block_tables ? p.block_tables + (size_t)b * p.max_blocks : nullptr;
+    for (int i = tid; i < n_blk; i += kThreads) blk_lds[i] = table ? table[first_lb + i] : b * p.max_blocks + first_lb + i;
+  }
+
+  constexpr int kv_row = kD * (KV_FP8 ? 1 : 2);
+  constexpr int br_row = kD * (BR_FP8 ? 1 : 2);
+  const uint8_t *kc_head = (const uint8_t *)p.k_cache + ((size_t)kvh << p.block_shift) * kv_row;
+  const uint8_t *vc_head = (const uint8_t *)p.v_cache + ((size_t)kvh << p.block_shift) * kv_row;
+  const size_t br_off = ((size_t)b * gl * p.Hkv + kvh) * br_row;
 
   auto tile_src = [&](int it) {
     TileSrc s;
+    s.blk = blk_lds;
+    s.first_lb = first_lb;
     if (it < n_prefix_tiles) {
       s.is_prefix = true;
       s.first = k_begin + it * kTileN;
       s.limit = k_end;
-      s.k_base = (const uint8_t *)p.k_cache;
-      s.v_base = (const uint8_t *)p.v_cache;
-      s.table = p.block_tables ? p.block_tables + (size_t)b * p.max_blocks : nullptr;
-      s.ident_base = b * p.max_blocks;
+      s.k_base = kc_head;
+      s.v_base = vc_head;
     } else {
       s.is_prefix = false;
       s.first = tk0 + (it - n_prefix_tiles) * kTileN;
       s.limit = t_hi + 1;
       s.k_base = (const uint8_t *)p.k_branch + br_off;
       s.v_base = (const uint8_t *)p.v_branch + br_off;
-      s.table = nullptr;
-      s.ident_base = 0;
     }
     return s;
   };
   auto load_tile = [&](int it, TileRegs &regs) {
     const TileSrc s = tile_src(it);
-    if (s.is_prefix)
-      tile_load<KV_FP8>(p, s, kvh, tid, regs);
-    else
-      tile_load<BR_FP8>(p, s, kvh, tid, regs);
+    if (s.is_prefix) {
+      if (s.first + kTileN <= s.limit)
+        tile_load<KV_FP8, true>(p, s, tid, regs);
+      else
+        tile_load<KV_FP8, false>(p, s, tid, regs);
+    } else {
+      tile_load<BR_FP8, false>(p, s, tid, regs);
+    }
   };
   auto store_tile = [&](int it, const TileRegs &regs) {
     uint8_t *stage = lds + (it & 1) * kStageBytes;
@@ -270,8 +312,8 @@ __global__ __launch_bounds__(kThreads, RB == 1 ? 2 : 1) void attn_mfma_kernel(co
         (const uint8_t *)p.q + (((size_t)b * gl + row_tok[rb]) * p.Hq + kvh * p.G + (rr % p.G)) * (size_t)(kD * 2);
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
-      u32x4 v = {0, 0, 0, 0};
-      if (r < p.R) v = *(const u32x4 *)(qrow + (16 * t + 8 * lh) * 2);
+      u32x4 v = *(const u32x4 *)(qrow + (16 * t + 8 * lh) * 2);
+      if (r >= p.R) v = u32x4{0, 0, 0, 0};
       qf[rb][t] = __builtin_bit_cast(bf16x8, v);
     }
   }
@@ -304,12 +346,12 @@ __global__ __launch_bounds__(kThreads, RB == 1 ? 2 : 1) void attn_mfma_kernel(co
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) m_run[rb] = -INFINITY, l_run[rb] = 0.f;
 
+  __syncthreads();  // block ids visible
+
   // ---- pipeline prologue -------------------------------------------------------------------
   TileRegs regs;
-  if (n_tiles > 0) {
-    load_tile(0, regs);
-    store_tile(0, regs);
-  }
+  load_tile(0, regs);
+  store_tile(0, regs);
   __syncthreads();
 
   for (int it = 0; it < n_tiles; ++it) {
@@ -374,18 +416,33 @@ __global__ __launch_bounds__(kThreads, RB == 1 ? 2 : 1) void attn_mfma_kernel(co
     const float voff = is_prefix ? 0.f : voff_branch;
     const float lmul = is_prefix ? 1.f : lmul_branch;
     uint32_t pb[2][RB][8];  // P^T as bf16 pairs: [kb][rb][j/2]
+    float mt[RB];
+    bool raise = false;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      float mt = -INFINITY;
+      float m0 = fmaxf(s[0][rb][0], s[1][rb][0]);
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int j = 1; j < 16; ++j) m0 = fmaxf(m0, fmaxf(s[0][rb][j], s[1][rb][j]));
+      mt[rb] = xhalf_max(m0) * cseg;
+      raise |= mt[rb] > m_run[rb] + kRaise;
+    }
+    if (__builtin_amdgcn_ballot_w64(raise) != 0) {   // wavefront-uniform: some row's maximum jumped
 #pragma unroll
-        for (int j = 0; j < 16; ++j) mt = fmaxf(mt, s[kb][rb][j]);
-      mt = fmaxf(mt, __shfl_xor(mt, 32));
-      const float m_new = fmaxf(m_run[rb], mt * cseg);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_use);
-      m_run[rb] = m_new;
+      for (int rb = 0; rb < RB; ++rb) {
+        const float m_new = fmaxf(m_run[rb], mt[rb]);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_use);   // 0 when m_run was -inf
+        m_run[rb] = m_new;
+        l_run[rb] *= alpha;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) o[db][rb][j] *= alpha;
+      }
+    }
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const float m_use = (m_run[rb] == -INFINITY) ? 0.f : m_run[rb];
       const float off = voff - m_use;
       float sum = 0.f;
 #pragma unroll
@@ -394,14 +451,13 @@ __global__ __launch_bounds__(kThreads, RB == 1 ? 2 : 1) void attn_mfma_kernel(co
         for (int j = 0; j < 16; j += 2) {
           const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][rb][j], cseg, off));
           const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][rb][j + 1], cseg, off));
-          sum += p0 + p1;
-          pb[kb][rb][j >> 1] = pack_bf16(p0, p1);
+          const uint32_t pk = pack_bf16(p0, p1);
+          pb[kb][rb][j >> 1] = pk;
+          // row sum of the rounded probabilities, the same numbers the PV product uses
+          sum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), __builtin_bit_cast(bf16x2, 0x3F803F80u),
+                                                sum, false);
         }
-      l_run[rb] = l_run[rb] * alpha + sum * lmul;
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) o[db][rb][j] *= alpha;
+      l_run[rb] += sum * lmul;
     }
 
     // ---- O^T += V^T P^T ------------------------------------------------------------------
@@ -433,7 +489,7 @@ __global__ __launch_bounds__(kThreads, RB == 1 ? 2 : 1) void attn_mfma_kernel(co
   const size_t slot = (size_t)b * p.s_max + c;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    const float l_tot = l_run[rb] + __shfl_xor(l_run[rb], 32);
+    const float l_tot = xhalf_sum(l_run[rb]);
     if (row[rb] < p.R) {
       const size_t out_row = slot * p.n_rows + (size_t)row_tok[rb] * p.Hq + kvh * p.G + (row[rb] % p.G);
       float *po = p.part_o + out_row * kD;
@@ -453,13 +509,17 @@ __global__ __launch_bounds__(kThreads, RB == 1 ? 2 : 1) void attn_mfma_kernel(co
   }
 }
 
-template <bool KV_FP8, bool BR_FP8, int RB>
+template <bool KV_FP8, bool BR_FP8>
 hipError_t launch_variant(const AttnParams &p, hipStream_t stream) {
   const int grid = p.Hkv * p.n_row_tiles * p.total_units;
-  auto kern = attn_mfma_kernel<KV_FP8, BR_FP8, RB>;
-  hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), kLdsBytes, stream, p);
+  auto kern = attn_mfma_kernel<KV_FP8, BR_FP8>;
+  static bool configured = false;   // per template instance
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), kLdsTotal, stream, p);
   return hipGetLastError();
 }
 
@@ -470,11 +530,13 @@ int attn_mfma_tile_m(int R) {
   return 256;
 }
 
+int attn_mfma_max_chunk_blocks() { return kMaxChunkBlocks; }
+
 hipError_t launch_attn_mfma(const AttnParams &p, bool kv_fp8, bool br_fp8, hipStream_t stream) {
   ProfileScope scope(SLOT_ATTN_MFMA, stream);
-  if (kv_fp8 && br_fp8) return launch_variant<true, true, 2>(p, stream);
-  if (kv_fp8 && !br_fp8) return launch_variant<true, false, 2>(p, stream);
-  if (!kv_fp8 && !br_fp8) return launch_variant<false, false, 2>(p, stream);
+  if (kv_fp8 && br_fp8) return launch_variant<true, true>(p, stream);
+  if (kv_fp8 && !br_fp8) return launch_variant<true, false>(p, stream);
+  if (!kv_fp8 && !br_fp8) return launch_variant<false, false>(p, stream);
   return hipErrorInvalidValue;
 }
 

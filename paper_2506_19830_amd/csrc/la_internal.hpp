@@ -29,7 +29,7 @@ struct AttnParams {
   void *out;       // [B, n_rows, D]
   float *lse;      // [B, n_rows] or null
   int B, Hq, Hkv, G, D, gamma, L;
-  int block_size, max_blocks;
+  int block_size, block_shift, max_blocks;  // block_size = 1 << block_shift
   int R;            // gamma*L*G
   int n_rows;       // gamma*L*Hq
   int n_row_tiles;  // ceil(R / tile_m)
@@ -58,6 +58,7 @@ enum KernelSlot {
 
 // tile_m of the MFMA kernel variant chosen for this problem (rows per workgroup)
 int attn_mfma_tile_m(int R);
+int attn_mfma_max_chunk_blocks();  // a chunk may span at most this many cache blocks
 hipError_t launch_attn_mfma(const AttnParams &p, bool kv_fp8, bool br_fp8, hipStream_t stream);
 hipError_t launch_attn_merge(const AttnParams &p, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnParams &p, hipStream_t stream);
