@@ -1,6 +1,7 @@
 // Host side of libla_verify: argument validation, launch planning, the extern "C" entry points
 // declared in la_verify.h and the optional per-kernel event timing.
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <vector>
@@ -20,7 +21,7 @@ enum AttnPath { PATH_NONE = 0, PATH_F32, PATH_MFMA };
 struct AttnPlan {
   AttnPath path;
   bool kv_fp8, br_fp8;
-  int tile_m, n_row_tiles, chunk_len, s_max, total_units;
+  int shape, tile_m, n_row_tiles, chunk_len, s_max, total_units;
   size_t part_o_bytes, part_ml_bytes;
 };
 
@@ -74,7 +75,12 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, Attn
 
   const int G = d->num_q_heads / d->num_kv_heads;
   const int R = d->gamma * d->branch_len * G;
-  plan->tile_m = attn_mfma_tile_m(R);
+  plan->shape = 0;
+  if (const char *e = getenv("LA_ATTN_SHAPE")) {  // tuning override: index into the kernel's shape table
+    const int v = atoi(e);
+    if (v >= 0 && v < attn_mfma_num_shapes()) plan->shape = v;
+  }
+  plan->tile_m = attn_mfma_tile_m(plan->shape);
   plan->n_row_tiles = (R + plan->tile_m - 1) / plan->tile_m;
   int chunk = d->kv_split_tokens;
   if (chunk == 0) {
@@ -229,7 +235,7 @@ la_status la_verify_attention(const la_attn_desc *desc, const void *q, const voi
   p.total_units = plan.total_units;
   p.part_o = (float *)workspace;
   p.part_ml = (float *)((uint8_t *)workspace + plan.part_o_bytes);
-  if (launch_attn_mfma(p, plan.kv_fp8, plan.br_fp8, stream) != hipSuccess) return LA_ERR_LAUNCH;
+  if (launch_attn_mfma(p, plan.shape, plan.kv_fp8, plan.br_fp8, stream) != hipSuccess) return LA_ERR_LAUNCH;
   if (launch_attn_merge(p, stream) != hipSuccess) return LA_ERR_LAUNCH;
   return LA_OK;
 }

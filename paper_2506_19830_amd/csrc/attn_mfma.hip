@@ -8,7 +8,7 @@
 // chunk of a request also reduces the branch-private keys under the mask
 // "same branch and key position <= query position".
 //
-// Per 64-key tile and wave (RB blocks of 32 rows each):
+// Per 64-key tile and wavefront (RB blocks of 32 rows each):
 //   S^T = K Q^T      v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = Q (registers)
 //   online softmax   each lane owns one query row (column of S^T): the row max is an
 //                    in-lane reduction plus one exchange with lane^32
@@ -31,14 +31,13 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int kD = 128;                      // head dim
 constexpr int kTileN = 64;                   // keys per tile
-constexpr int kThreads = 256;                // 4 waves
 constexpr int kKRow = kD * 2 + 16;           // bytes per key row of the K tile in LDS (padded)
 constexpr int kVRow = kTileN * 2 + 16;       // bytes per d row of the V^T tile in LDS (padded)
 constexpr int kKTileBytes = kTileN * kKRow;  // 17408
 constexpr int kVTileBytes = kD * kVRow;      // 18432
 constexpr int kStageBytes = kKTileBytes + kVTileBytes;
 constexpr int kMaxChunkBlocks = 4096;        // block ids of one chunk kept in LDS
-constexpr int kLdsTotal = 2 * kStageBytes + kMaxChunkBlocks * 4;   // two stages + block ids: 88064
+constexpr int kLdsTotal = 2 * kStageBytes + kMaxChunkBlocks * 4;  // two stages + block ids: 88064
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   f32x2 f = {a, b};
@@ -56,6 +55,20 @@ __device__ __forceinline__ uint32_t fp8x2_to_bf16x2(uint32_t w) {
 // key 8a+4h+c sits at 8h+4a+c, which is the order the S^T accumulator registers come in
 __device__ __forceinline__ int vt_pos(int kq) { return 16 * (kq >> 2) + 8 * (kq & 1) + 4 * ((kq >> 1) & 1); }
 
+// max / sum of a value with its partner in the other half of the wavefront (lane ^ 32)
+__device__ __forceinline__ float xhalf_max(float v) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, v);
+  const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  const uint32_t a = sw[0], b = sw[1];
+  return fmaxf(__builtin_bit_cast(float, a), __builtin_bit_cast(float, b));
+}
+__device__ __forceinline__ float xhalf_sum(float v) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, v);
+  const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  const uint32_t a = sw[0], b = sw[1];
+  return __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b);
+}
+
 // Where the keys of one tile come from.
 struct TileSrc {
   const uint8_t *k_base, *v_base;  // prefix: cache base of this kv head; branch: row of token 0 of this request/head
@@ -63,22 +76,24 @@ struct TileSrc {
   int first_lb;                    // prefix: logical block of blk[0]
   int first;                       // first key of the tile (prefix: token index; branch: token t = g*L+j)
   int limit;                       // keys >= limit are zero filled
-  bool is_prefix;
 };
 
-// Staging registers of one K tile and one V tile (per thread): 16 B pieces of K, 4 B pieces of V.
+// Staging registers of one K tile and one V tile per thread: 16-byte pieces of K rows, 4-byte pieces of V rows.
+template <bool FP8, int NT>
 struct TileRegs {
-  u32x4 k[4];
-  uint32_t v[16];
+  static constexpr int kNK = (FP8 ? 512 : 1024) / NT;  // K pieces per thread
+  static constexpr int kNV = (FP8 ? 512 : 1024) / NT;  // V key quads per thread
+  u32x4 k[kNK];
+  uint32_t v[4 * kNV];
 };
 
 // Address of key row `tok`.  Cache blocks are [block][Hkv][block_size][D]: inside a block consecutive tokens of
 // one head are contiguous.
-template <bool FP8>
+template <bool FP8, bool PREFIX>
 __device__ __forceinline__ const uint8_t *key_row(const AttnParams &p, const TileSrc &s, const uint8_t *base,
                                                   int tok) {
   constexpr int row_bytes = kD * (FP8 ? 1 : 2);
-  if (s.is_prefix) {
+  if constexpr (PREFIX) {
     const int blk = s.blk[(tok >> p.block_shift) - s.first_lb];
     return base + (((size_t)blk * p.Hkv) << p.block_shift) * row_bytes +
            (size_t)(tok & (p.block_size - 1)) * row_bytes;
@@ -86,42 +101,38 @@ __device__ __forceinline__ const uint8_t *key_row(const AttnParams &p, const Til
   return base + (size_t)tok * p.Hkv * row_bytes;
 }
 
-// Global -> registers.  FULL: every key of the tile is below s.limit.  Otherwise the address is clamped to the
-// last valid key and the value zeroed, so the loads stay unconditional and in bounds.
-template <bool FP8, bool FULL>
-__device__ __forceinline__ void tile_load(const AttnParams &p, const TileSrc &s, int tid, TileRegs &r) {
+// Global -> registers.  FULL: every key of the tile is below s.limit.  Otherwise addresses are clamped to the
+// last valid key and the values zeroed, so the loads stay unconditional and in bounds.
+template <bool FP8, bool PREFIX, bool FULL, int NT>
+__device__ __forceinline__ void tile_load(const AttnParams &p, const TileSrc &s, int tid, TileRegs<FP8, NT> &r) {
   constexpr int row_bytes = kD * (FP8 ? 1 : 2);
-  constexpr int nk = FP8 ? 2 : 4;               // 16-byte K pieces per thread
-  constexpr int k_rows_per_pass = FP8 ? 32 : 16;  // keys covered by one pass of the 256 threads
-  constexpr int k_piece_mask = FP8 ? 7 : 15;
-  constexpr int k_piece_shift = FP8 ? 3 : 4;
+  constexpr int k_piece_shift = FP8 ? 3 : 4;  // 16-byte pieces per key row: 8 (fp8) or 16 (bf16)
 #pragma unroll
-  for (int e = 0; e < nk; ++e) {
-    const int tok = s.first + (tid >> k_piece_shift) + k_rows_per_pass * e;
+  for (int e = 0; e < TileRegs<FP8, NT>::kNK; ++e) {
+    const int idx = tid + NT * e;
+    const int tok = s.first + (idx >> k_piece_shift);
     const int tc = FULL ? tok : min(tok, s.limit - 1);
-    u32x4 val = *(const u32x4 *)(key_row<FP8>(p, s, s.k_base, tc) + (tid & k_piece_mask) * 16);
+    u32x4 val = *(const u32x4 *)(key_row<FP8, PREFIX>(p, s, s.k_base, tc) + (idx & ((1 << k_piece_shift) - 1)) * 16);
     if (!FULL && tok >= s.limit) val = u32x4{0, 0, 0, 0};
     r.k[e] = val;
   }
-  constexpr int nv = FP8 ? 2 : 4;                // key quads per thread
-  constexpr int v_lane_mask = FP8 ? 31 : 63;     // 4-byte pieces per key row
-  constexpr int v_quad_shift = FP8 ? 5 : 6;
-  constexpr int v_quads_per_pass = FP8 ? 8 : 4;
+  constexpr int v_quad_shift = FP8 ? 5 : 6;  // 4-byte pieces per key row: 32 (fp8) or 64 (bf16)
 #pragma unroll
-  for (int e = 0; e < nv; ++e) {
-    const int kq = (tid >> v_quad_shift) + v_quads_per_pass * e;
-    const int tok0 = s.first + 4 * kq;           // the four keys of a quad share a cache block (block_size % 16 == 0)
-    if (FULL || (s.is_prefix && tok0 + 3 < s.limit)) {
-      const uint8_t *row = key_row<FP8>(p, s, s.v_base, tok0) + (tid & v_lane_mask) * 4;
-      const size_t step = s.is_prefix ? (size_t)row_bytes : (size_t)p.Hkv * row_bytes;
+  for (int e = 0; e < TileRegs<FP8, NT>::kNV; ++e) {
+    const int idx = tid + NT * e;
+    const int kq = idx >> v_quad_shift;
+    const int piece = idx & ((1 << v_quad_shift) - 1);
+    const int tok0 = s.first + 4 * kq;  // the four keys of a quad share a cache block (block_size % 16 == 0)
+    if constexpr (FULL && PREFIX) {
+      const uint8_t *row = key_row<FP8, PREFIX>(p, s, s.v_base, tok0) + piece * 4;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) r.v[4 * e + c] = *(const uint32_t *)(row + c * step);
+      for (int c = 0; c < 4; ++c) r.v[4 * e + c] = *(const uint32_t *)(row + c * row_bytes);
     } else {
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const int tok = tok0 + c;
         const int tc = min(tok, s.limit - 1);
-        uint32_t val = *(const uint32_t *)(key_row<FP8>(p, s, s.v_base, tc) + (tid & v_lane_mask) * 4);
+        const uint32_t val = *(const uint32_t *)(key_row<FP8, PREFIX>(p, s, s.v_base, tc) + piece * 4);
         r.v[4 * e + c] = tok < s.limit ? val : 0u;
       }
     }
@@ -130,20 +141,21 @@ __device__ __forceinline__ void tile_load(const AttnParams &p, const TileSrc &s,
 
 // Registers -> LDS stage: K rows as they are, V transposed ([d][key], keys permuted by vt_pos); fp8 is widened to
 // bf16 on the way (exact: every e4m3 value is a bf16 value).
-template <bool FP8>
-__device__ __forceinline__ void tile_store(uint8_t *stage, int tid, const TileRegs &r) {
+template <bool FP8, int NT>
+__device__ __forceinline__ void tile_store(uint8_t *stage, int tid, const TileRegs<FP8, NT> &r) {
   uint8_t *kt = stage;
   uint8_t *vt = stage + kKTileBytes;
   if constexpr (!FP8) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int key = (tid >> 4) + 16 * e;
-      *(u32x4 *)(kt + key * kKRow + (tid & 15) * 16) = r.k[e];
+    for (int e = 0; e < TileRegs<FP8, NT>::kNK; ++e) {
+      const int idx = tid + NT * e;
+      *(u32x4 *)(kt + (idx >> 4) * kKRow + (idx & 15) * 16) = r.k[e];
     }
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int kq = (tid >> 6) + 4 * e;
-      const int d0 = 2 * (tid & 63);
+    for (int e = 0; e < TileRegs<FP8, NT>::kNV; ++e) {
+      const int idx = tid + NT * e;
+      const int kq = idx >> 6;
+      const int d0 = 2 * (idx & 63);
       const uint32_t a = r.v[4 * e + 0], b = r.v[4 * e + 1], c = r.v[4 * e + 2], d = r.v[4 * e + 3];
       // low halves hold d0 of keys (a,b,c,d), high halves d0+1
       u32x2 lo = {__builtin_amdgcn_perm(b, a, 0x05040100u), __builtin_amdgcn_perm(d, c, 0x05040100u)};
@@ -153,8 +165,8 @@ __device__ __forceinline__ void tile_store(uint8_t *stage, int tid, const TileRe
     }
   } else {
 #pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      const int key = (tid >> 3) + 32 * e;
+    for (int e = 0; e < TileRegs<FP8, NT>::kNK; ++e) {
+      const int idx = tid + NT * e;
       uint32_t out[8];
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
@@ -162,14 +174,15 @@ __device__ __forceinline__ void tile_store(uint8_t *stage, int tid, const TileRe
         out[2 * w] = fp8x2_to_bf16x2<false>(word);
         out[2 * w + 1] = fp8x2_to_bf16x2<true>(word);
       }
-      uint8_t *dst = kt + key * kKRow + (tid & 7) * 32;
+      uint8_t *dst = kt + (idx >> 3) * kKRow + (idx & 7) * 32;
       *(u32x4 *)(dst) = u32x4{out[0], out[1], out[2], out[3]};
       *(u32x4 *)(dst + 16) = u32x4{out[4], out[5], out[6], out[7]};
     }
 #pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      const int kq = (tid >> 5) + 8 * e;
-      const int d0 = 4 * (tid & 31);
+    for (int e = 0; e < TileRegs<FP8, NT>::kNV; ++e) {
+      const int idx = tid + NT * e;
+      const int kq = idx >> 5;
+      const int d0 = 4 * (idx & 31);
       uint32_t lo[4], hi[4];  // of key c: bf16 pairs (d0, d0+1) and (d0+2, d0+3)
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
@@ -190,30 +203,150 @@ __device__ __forceinline__ void tile_store(uint8_t *stage, int tid, const TileRe
   }
 }
 
-// max / sum of a value with its partner in the other half of the wavefront (lane ^ 32)
-__device__ __forceinline__ float xhalf_max(float v) {
-  const uint32_t u = __builtin_bit_cast(uint32_t, v);
-  const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  const uint32_t a = sw[0], b = sw[1];
-  return fmaxf(__builtin_bit_cast(float, a), __builtin_bit_cast(float, b));
-}
-__device__ __forceinline__ float xhalf_sum(float v) {
-  const uint32_t u = __builtin_bit_cast(uint32_t, v);
-  const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  const uint32_t a = sw[0], b = sw[1];
-  return __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b);
-}
-
 // A running maximum is only raised when the tile maximum exceeds it by more than this many log2 units; until
 // then probabilities are allowed to reach 2^kRaise, which fp32 sums and bf16 operands hold without loss.  Raising
-// rarely keeps the accumulator rescale (128 multiplies per lane) off the common path.
+// rarely keeps the accumulator rescale (64 multiplies per lane and row block) off the common path.
 constexpr float kRaise = 6.0f;
 
-template <bool KV_FP8, bool BR_FP8>
-__global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(const AttnParams p) {
+// Per-wavefront state of RB blocks of 32 query rows.
+template <int RB>
+struct RowState {
+  bf16x8 qf[RB][8];  // Q^T operand: row ln of block rb, d = 16t + 8*lh .. +8
+  f32x16 o[4][RB];   // O^T accumulators: d block db, row block rb
+  float m_run[RB], l_run[RB];
+  int row_tok[RB], row_bstart[RB];
+};
+
+enum MaskMode { MASK_NONE = 0, MASK_TAIL = 1, MASK_BRANCH = 2 };
+
+// One 64-key tile from an LDS stage: scores, (masked) online softmax, PV accumulation.
+//   first / limit   MASK_TAIL: keys with first + key >= limit are masked
+//                   MASK_BRANCH: key token first + key is visible to a row iff row_bstart <= token <= row_tok
+//   cseg            score scale of this key segment (log2 units); voff/lmul move a differently scaled V segment into
+//                   the accumulator's units (p' = p * 2^voff, l += sum(p') * lmul)
+template <int RB, int MASK>
+__device__ __forceinline__ void compute_tile(const uint8_t *kt, RowState<RB> &st, int ln, int lh, int first,
+                                             int limit, float cseg, float voff, float lmul) {
+  const uint8_t *vt = kt + kKTileBytes;
+  // ---- S^T = K Q^T -------------------------------------------------------------------
+  f32x16 s[2][RB];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) s[kb][rb][j] = 0.f;
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    bf16x8 kf[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+      kf[kb] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(kt + (kb * 32 + ln) * kKRow + (16 * t + 8 * lh) * 2));
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+        s[kb][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb], st.qf[rb][t], s[kb][rb], 0, 0, 0);
+  }
+
+  // ---- mask: register j of block kb holds key  kb*32 + (j/4)*8 + lh*4 + j%4  of the tile ----
+  if constexpr (MASK == MASK_TAIL) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int key = first + kb * 32 + (j >> 2) * 8 + lh * 4 + (j & 3);
+        if (key >= limit) {
+#pragma unroll
+          for (int rb = 0; rb < RB; ++rb) s[kb][rb][j] = -INFINITY;
+        }
+      }
+  } else if constexpr (MASK == MASK_BRANCH) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int tk = first + kb * 32 + (j >> 2) * 8 + lh * 4 + (j & 3);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+          if (tk > st.row_tok[rb] || tk < st.row_bstart[rb]) s[kb][rb][j] = -INFINITY;
+      }
+  }
+
+  // ---- online softmax ------------------------------------------------------------------
+  float mt[RB];
+  bool raise = false;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    float m0 = fmaxf(s[0][rb][0], s[1][rb][0]);
+#pragma unroll
+    for (int j = 1; j < 16; ++j) m0 = fmaxf(m0, fmaxf(s[0][rb][j], s[1][rb][j]));
+    mt[rb] = xhalf_max(m0) * cseg;
+    raise |= mt[rb] > st.m_run[rb] + kRaise;
+  }
+  if (__builtin_amdgcn_ballot_w64(raise) != 0) {  // wavefront-uniform: some row's maximum jumped
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const float m_new = fmaxf(st.m_run[rb], mt[rb]);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(st.m_run[rb] - m_use);  // 0 when m_run was -inf
+      st.m_run[rb] = m_new;
+      st.l_run[rb] *= alpha;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) st.o[db][rb][j] *= alpha;
+    }
+  }
+  uint32_t pb[2][RB][8];  // P^T as bf16 pairs: [kb][rb][j/2]
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    const float m_use = (st.m_run[rb] == -INFINITY) ? 0.f : st.m_run[rb];
+    const float off = voff - m_use;
+    float sum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int j = 0; j < 16; j += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][rb][j], cseg, off));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][rb][j + 1], cseg, off));
+        const uint32_t pk = pack_bf16(p0, p1);
+        pb[kb][rb][j >> 1] = pk;
+        // row sum of the rounded probabilities, the same numbers the PV product uses
+        sum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), __builtin_bit_cast(bf16x2, 0x3F803F80u),
+                                              sum, false);
+      }
+    st.l_run[rb] += sum * lmul;
+  }
+
+  // ---- O^T += V^T P^T ------------------------------------------------------------------
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2) {
+      bf16x8 pf[RB];
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        u32x4 v = {pb[kb][rb][4 * t2], pb[kb][rb][4 * t2 + 1], pb[kb][rb][4 * t2 + 2], pb[kb][rb][4 * t2 + 3]};
+        pf[rb] = __builtin_bit_cast(bf16x8, v);
+      }
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        const bf16x8 vf = __builtin_bit_cast(
+            bf16x8, *(const u32x4 *)(vt + (db * 32 + ln) * kVRow + (kb * 32 + t2 * 16 + lh * 8) * 2));
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+          st.o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[rb], st.o[db][rb], 0, 0, 0);
+      }
+    }
+}
+
+// NW wavefronts of RB 32-row blocks each: a row tile of 32*NW*RB rows.
+template <bool KV_FP8, bool BR_FP8, int NW, int RB>
+__global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_kernel(const AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-  constexpr int RB = 2;           // 32-row blocks per wavefront
-  constexpr int kTileM = 128 * RB;
+  constexpr int NT = 64 * NW;
+  constexpr int kTileM = 32 * NW * RB;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
@@ -234,7 +367,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(const AttnParams
   const int n_chunks = attn_num_chunks(P, p.chunk_len);
   const int k_begin = c * p.chunk_len;
   const int k_end = min(P, k_begin + p.chunk_len);
-  const int n_prefix_tiles = k_end > k_begin ? (k_end - k_begin + kTileN - 1) / kTileN : 0;
+  const int n_full = k_end > k_begin ? (k_end - k_begin) / kTileN : 0;          // unmasked prefix tiles
+  const bool has_tail = k_end > k_begin && ((k_end - k_begin) % kTileN) != 0;  // one partly filled prefix tile
 
   const int r0 = row_tile * kTileM;
   const int r1 = min(p.R, r0 + kTileM);
@@ -242,80 +376,58 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(const AttnParams
   // branch-private keys needed by this row tile: tokens t = g*L + j in [tk0, t_hi]
   const int t_lo = r0 / p.G, t_hi = (r1 - 1) / p.G;
   const int tk0 = (t_lo / p.L) * p.L;
-  const int n_priv_tiles = (c == n_chunks - 1) ? (t_hi - tk0 + 1 + kTileN - 1) / kTileN : 0;
-  const int n_tiles = n_prefix_tiles + n_priv_tiles;
+  const int n_priv = (c == n_chunks - 1) ? (t_hi - tk0 + 1 + kTileN - 1) / kTileN : 0;
 
   // ---- physical block ids of this chunk -> LDS ---------------------------------------------
   int32_t *blk_lds = (int32_t *)(lds + 2 * kStageBytes);
   const int first_lb = k_begin >> p.block_shift;
-  if (n_prefix_tiles > 0) {
-    const int n_blk = ((k_end - 1) >> p.block_shift) - first_lb + 1;   // <= kMaxChunkBlocks (host guarantees)
+  if (k_end > k_begin) {
+    const int n_blk = ((k_end - 1) >> p.block_shift) - first_lb + 1;  // <= kMaxChunkBlocks (host guarantees)
     const int32_t *table = p.block_tables ? p.block_tables + (size_t)b * p.max_blocks : nullptr;
-    for (int i = tid; i < n_blk; i += kThreads) blk_lds[i] = table ? table[first_lb + i] : b * p.max_blocks + first_lb + i;
+    for (int i = tid; i < n_blk; i += NT)
+      blk_lds[i] = table ? table[first_lb + i] : b * p.max_blocks + first_lb + i;
   }
 
   constexpr int kv_row = kD * (KV_FP8 ? 1 : 2);
   constexpr int br_row = kD * (BR_FP8 ? 1 : 2);
-  const uint8_t *kc_head = (const uint8_t *)p.k_cache + ((size_t)kvh << p.block_shift) * kv_row;
-  const uint8_t *vc_head = (const uint8_t *)p.v_cache + ((size_t)kvh << p.block_shift) * kv_row;
+  TileSrc pre;  // prefix tiles
+  pre.k_base = (const uint8_t *)p.k_cache + ((size_t)kvh << p.block_shift) * kv_row;
+  pre.v_base = (const uint8_t *)p.v_cache + ((size_t)kvh << p.block_shift) * kv_row;
+  pre.blk = blk_lds;
+  pre.first_lb = first_lb;
+  pre.limit = k_end;
+  TileSrc brs;  // branch-private tiles
   const size_t br_off = ((size_t)b * gl * p.Hkv + kvh) * br_row;
-
-  auto tile_src = [&](int it) {
-    TileSrc s;
-    s.blk = blk_lds;
-    s.first_lb = first_lb;
-    if (it < n_prefix_tiles) {
-      s.is_prefix = true;
-      s.first = k_begin + it * kTileN;
-      s.limit = k_end;
-      s.k_base = kc_head;
-      s.v_base = vc_head;
-    } else {
-      s.is_prefix = false;
-      s.first = tk0 + (it - n_prefix_tiles) * kTileN;
-      s.limit = t_hi + 1;
-      s.k_base = (const uint8_t *)p.k_branch + br_off;
-      s.v_base = (const uint8_t *)p.v_branch + br_off;
-    }
-    return s;
-  };
-  auto load_tile = [&](int it, TileRegs &regs) {
-    const TileSrc s = tile_src(it);
-    if (s.is_prefix) {
-      if (s.first + kTileN <= s.limit)
-        tile_load<KV_FP8, true>(p, s, tid, regs);
-      else
-        tile_load<KV_FP8, false>(p, s, tid, regs);
-    } else {
-      tile_load<BR_FP8, false>(p, s, tid, regs);
-    }
-  };
-  auto store_tile = [&](int it, const TileRegs &regs) {
-    uint8_t *stage = lds + (it & 1) * kStageBytes;
-    if (it < n_prefix_tiles)
-      tile_store<KV_FP8>(stage, tid, regs);
-    else
-      tile_store<BR_FP8>(stage, tid, regs);
-  };
+  brs.k_base = (const uint8_t *)p.k_branch + br_off;
+  brs.v_base = (const uint8_t *)p.v_branch + br_off;
+  brs.blk = nullptr;
+  brs.first_lb = 0;
+  brs.limit = t_hi + 1;
 
   // ---- per-lane query rows ---------------------------------------------------------------
-  int row[RB], row_tok[RB], row_bstart[RB];
-  bf16x8 qf[RB][8];
+  RowState<RB> st;
+  int row[RB];
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     const int r = r0 + (wave * RB + rb) * 32 + ln;
     row[rb] = r;
     const int rr = min(r, p.R - 1);
-    row_tok[rb] = rr / p.G;
-    row_bstart[rb] = (row_tok[rb] / p.L) * p.L;
+    st.row_tok[rb] = rr / p.G;
+    st.row_bstart[rb] = (st.row_tok[rb] / p.L) * p.L;
     const uint8_t *qrow =
-        (const uint8_t *)p.q + (((size_t)b * gl + row_tok[rb]) * p.Hq + kvh * p.G + (rr % p.G)) * (size_t)(kD * 2);
+        (const uint8_t *)p.q + (((size_t)b * gl + st.row_tok[rb]) * p.Hq + kvh * p.G + (rr % p.G)) * (size_t)(kD * 2);
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       u32x4 v = *(const u32x4 *)(qrow + (16 * t + 8 * lh) * 2);
       if (r >= p.R) v = u32x4{0, 0, 0, 0};
-      qf[rb][t] = __builtin_bit_cast(bf16x8, v);
+      st.qf[rb][t] = __builtin_bit_cast(bf16x8, v);
     }
+    st.m_run[rb] = -INFINITY;
+    st.l_run[rb] = 0.f;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) st.o[db][rb][j] = 0.f;
   }
 
   // scale factors of the two key segments, in log2 units
@@ -335,153 +447,47 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(const AttnParams
   const float voff_branch = __builtin_log2f(vmul_branch);
   const float lmul_branch = 1.0f / vmul_branch;
 
-  f32x16 o[4][RB];
-#pragma unroll
-  for (int db = 0; db < 4; ++db)
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int j = 0; j < 16; ++j) o[db][rb][j] = 0.f;
-  float m_run[RB], l_run[RB];
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) m_run[rb] = -INFINITY, l_run[rb] = 0.f;
-
   __syncthreads();  // block ids visible
 
-  // ---- pipeline prologue -------------------------------------------------------------------
-  TileRegs regs;
-  load_tile(0, regs);
-  store_tile(0, regs);
-  __syncthreads();
-
-  for (int it = 0; it < n_tiles; ++it) {
-    const bool has_next = it + 1 < n_tiles;
-    if (has_next) load_tile(it + 1, regs);
-
-    const uint8_t *kt = lds + (it & 1) * kStageBytes;
-    const uint8_t *vt = kt + kKTileBytes;
-    const bool is_prefix = it < n_prefix_tiles;
-    const int first = is_prefix ? k_begin + it * kTileN : tk0 + (it - n_prefix_tiles) * kTileN;
-
-    // ---- S^T = K Q^T -------------------------------------------------------------------
-    f32x16 s[2][RB];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) s[kb][rb][j] = 0.f;
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      bf16x8 kf[2];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-        kf[kb] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(kt + (kb * 32 + ln) * kKRow + (16 * t + 8 * lh) * 2));
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-          s[kb][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb], qf[rb][t], s[kb][rb], 0, 0, 0);
-    }
-
-    // ---- mask --------------------------------------------------------------------------
-    // register j of block kb holds key  kb*32 + (j/4)*8 + lh*4 + j%4  of the tile
-    if (is_prefix) {
-      if (first + kTileN > k_end) {
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int j = 0; j < 16; ++j) {
-            const int key = first + kb * 32 + (j >> 2) * 8 + lh * 4 + (j & 3);
-            if (key >= k_end) {
-#pragma unroll
-              for (int rb = 0; rb < RB; ++rb) s[kb][rb][j] = -INFINITY;
-            }
-          }
+  // ---- phase 1: the unmasked prefix tiles, double buffered ------------------------------------
+  int stage = 0;
+  if (n_full > 0) {
+    TileRegs<KV_FP8, NT> regs;
+    pre.first = k_begin;
+    tile_load<KV_FP8, true, true, NT>(p, pre, tid, regs);
+    tile_store<KV_FP8, NT>(lds, tid, regs);
+    __syncthreads();
+    for (int it = 0; it < n_full; ++it) {
+      const bool has_next = it + 1 < n_full;
+      if (has_next) {
+        pre.first = k_begin + (it + 1) * kTileN;
+        tile_load<KV_FP8, true, true, NT>(p, pre, tid, regs);
       }
-    } else {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const int tk = first + kb * 32 + (j >> 2) * 8 + lh * 4 + (j & 3);
-#pragma unroll
-          for (int rb = 0; rb < RB; ++rb)
-            if (tk > row_tok[rb] || tk < row_bstart[rb]) s[kb][rb][j] = -INFINITY;
-        }
+      compute_tile<RB, MASK_NONE>(lds + stage * kStageBytes, st, ln, lh, 0, 0, c_prefix, 0.f, 1.f);
+      if (has_next) tile_store<KV_FP8, NT>(lds + (stage ^ 1) * kStageBytes, tid, regs);
+      __syncthreads();
+      stage ^= 1;
     }
-
-    // ---- online softmax ------------------------------------------------------------------
-    const float cseg = is_prefix ? c_prefix : c_branch;
-    const float voff = is_prefix ? 0.f : voff_branch;
-    const float lmul = is_prefix ? 1.f : lmul_branch;
-    uint32_t pb[2][RB][8];  // P^T as bf16 pairs: [kb][rb][j/2]
-    float mt[RB];
-    bool raise = false;
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      float m0 = fmaxf(s[0][rb][0], s[1][rb][0]);
-#pragma unroll
-      for (int j = 1; j < 16; ++j) m0 = fmaxf(m0, fmaxf(s[0][rb][j], s[1][rb][j]));
-      mt[rb] = xhalf_max(m0) * cseg;
-      raise |= mt[rb] > m_run[rb] + kRaise;
-    }
-    if (__builtin_amdgcn_ballot_w64(raise) != 0) {   // wavefront-uniform: some row's maximum jumped
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
-        const float m_new = fmaxf(m_run[rb], mt[rb]);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_use);   // 0 when m_run was -inf
-        m_run[rb] = m_new;
-        l_run[rb] *= alpha;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-          for (int j = 0; j < 16; ++j) o[db][rb][j] *= alpha;
-      }
-    }
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      const float m_use = (m_run[rb] == -INFINITY) ? 0.f : m_run[rb];
-      const float off = voff - m_use;
-      float sum = 0.f;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int j = 0; j < 16; j += 2) {
-          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][rb][j], cseg, off));
-          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][rb][j + 1], cseg, off));
-          const uint32_t pk = pack_bf16(p0, p1);
-          pb[kb][rb][j >> 1] = pk;
-          // row sum of the rounded probabilities, the same numbers the PV product uses
-          sum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), __builtin_bit_cast(bf16x2, 0x3F803F80u),
-                                                sum, false);
-        }
-      l_run[rb] += sum * lmul;
-    }
-
-    // ---- O^T += V^T P^T ------------------------------------------------------------------
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2) {
-        bf16x8 pf[RB];
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-          u32x4 v = {pb[kb][rb][4 * t2], pb[kb][rb][4 * t2 + 1], pb[kb][rb][4 * t2 + 2], pb[kb][rb][4 * t2 + 3]};
-          pf[rb] = __builtin_bit_cast(bf16x8, v);
-        }
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          const bf16x8 vf = __builtin_bit_cast(
-              bf16x8, *(const u32x4 *)(vt + (db * 32 + ln) * kVRow + (kb * 32 + t2 * 16 + lh * 8) * 2));
-#pragma unroll
-          for (int rb = 0; rb < RB; ++rb)
-            o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[rb], o[db][rb], 0, 0, 0);
-        }
-      }
-
-    if (has_next) store_tile(it + 1, regs);
+  }
+  // ---- phase 2: the partly filled prefix tile -------------------------------------------------
+  if (has_tail) {
+    TileRegs<KV_FP8, NT> regs;
+    pre.first = k_begin + n_full * kTileN;
+    tile_load<KV_FP8, true, false, NT>(p, pre, tid, regs);
+    tile_store<KV_FP8, NT>(lds + stage * kStageBytes, tid, regs);
+    __syncthreads();
+    compute_tile<RB, MASK_TAIL>(lds + stage * kStageBytes, st, ln, lh, pre.first, k_end, c_prefix, 0.f, 1.f);
+    __syncthreads();
+  }
+  // ---- phase 3: branch-private tiles (last chunk only) ------------------------------------------
+  for (int it = 0; it < n_priv; ++it) {
+    TileRegs<BR_FP8, NT> regs;
+    brs.first = tk0 + it * kTileN;
+    tile_load<BR_FP8, false, false, NT>(p, brs, tid, regs);
+    tile_store<BR_FP8, NT>(lds + stage * kStageBytes, tid, regs);
+    __syncthreads();
+    compute_tile<RB, MASK_BRANCH>(lds + stage * kStageBytes, st, ln, lh, brs.first, 0, c_branch, voff_branch,
+                                  lmul_branch);
     __syncthreads();
   }
 
@@ -489,54 +495,68 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(const AttnParams
   const size_t slot = (size_t)b * p.s_max + c;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    const float l_tot = xhalf_sum(l_run[rb]);
+    const float l_tot = xhalf_sum(st.l_run[rb]);
     if (row[rb] < p.R) {
-      const size_t out_row = slot * p.n_rows + (size_t)row_tok[rb] * p.Hq + kvh * p.G + (row[rb] % p.G);
+      const size_t out_row = slot * p.n_rows + (size_t)st.row_tok[rb] * p.Hq + kvh * p.G + (row[rb] % p.G);
       float *po = p.part_o + out_row * kD;
 #pragma unroll
       for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          f32x4 v = {o[db][rb][4 * q4] * v_out, o[db][rb][4 * q4 + 1] * v_out, o[db][rb][4 * q4 + 2] * v_out,
-                     o[db][rb][4 * q4 + 3] * v_out};
+          f32x4 v = {st.o[db][rb][4 * q4] * v_out, st.o[db][rb][4 * q4 + 1] * v_out,
+                     st.o[db][rb][4 * q4 + 2] * v_out, st.o[db][rb][4 * q4 + 3] * v_out};
           *(f32x4 *)(po + db * 32 + q4 * 8 + lh * 4) = v;
         }
       if (lh == 0) {
-        f32x2 ml = {m_run[rb], l_tot};
+        f32x2 ml = {st.m_run[rb], l_tot};
         *(f32x2 *)(p.part_ml + out_row * 2) = ml;
       }
     }
   }
 }
 
-template <bool KV_FP8, bool BR_FP8>
+template <bool KV_FP8, bool BR_FP8, int NW, int RB>
 hipError_t launch_variant(const AttnParams &p, hipStream_t stream) {
   const int grid = p.Hkv * p.n_row_tiles * p.total_units;
-  auto kern = attn_mfma_kernel<KV_FP8, BR_FP8>;
-  static bool configured = false;   // per template instance
+  auto kern = attn_mfma_kernel<KV_FP8, BR_FP8, NW, RB>;
+  static bool configured = false;  // per template instance
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), kLdsTotal, stream, p);
+  // two tile stages plus the block ids of one chunk (a chunk that does not start on a block boundary spans one more)
+  const int blk_entries = (p.chunk_len >> p.block_shift) + 2;
+  const int lds_bytes = 2 * kStageBytes + (blk_entries < kMaxChunkBlocks ? blk_entries : kMaxChunkBlocks) * 4;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NW), lds_bytes, stream, p);
   return hipGetLastError();
 }
 
-}  // namespace
-
-int attn_mfma_tile_m(int R) {
-  (void)R;
-  return 256;
+template <int NW, int RB>
+hipError_t launch_shape(const AttnParams &p, bool kv_fp8, bool br_fp8, hipStream_t stream) {
+  if (kv_fp8 && br_fp8) return launch_variant<true, true, NW, RB>(p, stream);
+  if (kv_fp8 && !br_fp8) return launch_variant<true, false, NW, RB>(p, stream);
+  if (!kv_fp8 && !br_fp8) return launch_variant<false, false, NW, RB>(p, stream);
+  return hipErrorInvalidValue;
 }
 
+// Kernel shapes: (wavefronts per workgroup, 32-row blocks per wavefront).
+constexpr int kShapes[][2] = {{8, 1}, {4, 2}, {4, 1}};
+constexpr int kNumShapes = 3;
+
+}  // namespace
+
+int attn_mfma_num_shapes() { return kNumShapes; }
+int attn_mfma_tile_m(int shape) { return 32 * kShapes[shape][0] * kShapes[shape][1]; }
 int attn_mfma_max_chunk_blocks() { return kMaxChunkBlocks; }
 
-hipError_t launch_attn_mfma(const AttnParams &p, bool kv_fp8, bool br_fp8, hipStream_t stream) {
+hipError_t launch_attn_mfma(const AttnParams &p, int shape, bool kv_fp8, bool br_fp8, hipStream_t stream) {
   ProfileScope scope(SLOT_ATTN_MFMA, stream);
-  if (kv_fp8 && br_fp8) return launch_variant<true, true>(p, stream);
-  if (kv_fp8 && !br_fp8) return launch_variant<true, false>(p, stream);
-  if (!kv_fp8 && !br_fp8) return launch_variant<false, false>(p, stream);
+  switch (shape) {
+    case 0: return launch_shape<8, 1>(p, kv_fp8, br_fp8, stream);
+    case 1: return launch_shape<4, 2>(p, kv_fp8, br_fp8, stream);
+    case 2: return launch_shape<4, 1>(p, kv_fp8, br_fp8, stream);
+  }
   return hipErrorInvalidValue;
 }
 
