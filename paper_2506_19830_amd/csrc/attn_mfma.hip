@@ -14,7 +14,10 @@
 //                    in-lane reduction plus one exchange with lane^32
 //   O^T += V^T P^T   A = V^T from LDS (stored transposed, keys permuted inside groups
 //                    of 16 so that the accumulator registers of S^T are already the
-//                    B operand), B = P^T (registers, bf16)
+//                    B operand; row 32*db + m of the LDS tile holds head-dim column
+//                    4*m + db, which makes the transposing LDS writes bank-conflict
+//                    free and the four db accumulators of a lane adjacent columns),
+//                    B = P^T (registers, bf16)
 // Everything is kept in log2 units: p = 2^(s*c - m).
 #include "la_internal.hpp"
 
@@ -54,6 +57,12 @@ __device__ __forceinline__ uint32_t fp8x2_to_bf16x2(uint32_t w) {
 // position of key quad kq (keys 4kq..4kq+3 of the tile) inside a V^T row: inside every group of 16 keys
 // key 8a+4h+c sits at 8h+4a+c, which is the order the S^T accumulator registers come in
 __device__ __forceinline__ int vt_pos(int kq) { return 16 * (kq >> 2) + 8 * (kq & 1) + 4 * ((kq >> 1) & 1); }
+
+// LDS row of head-dim column d in the V^T tile: block d%4, row d/4 inside the block
+__device__ __forceinline__ int vt_row(int d) { return (d & 3) * 32 + (d >> 2); }
+// bf16 V loads: lane -> column pair so that lanes 0..31 hold the even pairs and lanes 32..63 the odd ones; the
+// transposed LDS writes of a half wavefront then land in consecutive rows
+__device__ __forceinline__ int v_pair_of_lane(int lane) { return 2 * (lane & 31) + (lane >> 5); }
 
 // max / sum of a value with its partner in the other half of the wavefront (lane ^ 32)
 __device__ __forceinline__ float xhalf_max(float v) {
@@ -121,7 +130,7 @@ __device__ __forceinline__ void tile_load(const AttnParams &p, const TileSrc &s,
   for (int e = 0; e < TileRegs<FP8, NT>::kNV; ++e) {
     const int idx = tid + NT * e;
     const int kq = idx >> v_quad_shift;
-    const int piece = idx & ((1 << v_quad_shift) - 1);
+    const int piece = FP8 ? (idx & 31) : v_pair_of_lane(idx & 63);
     const int tok0 = s.first + 4 * kq;  // the four keys of a quad share a cache block (block_size % 16 == 0)
     if constexpr (FULL && PREFIX) {
       const uint8_t *row = key_row<FP8, PREFIX>(p, s, s.v_base, tok0) + piece * 4;
@@ -155,13 +164,13 @@ __device__ __forceinline__ void tile_store(uint8_t *stage, int tid, const TileRe
     for (int e = 0; e < TileRegs<FP8, NT>::kNV; ++e) {
       const int idx = tid + NT * e;
       const int kq = idx >> 6;
-      const int d0 = 2 * (idx & 63);
+      const int dp = v_pair_of_lane(idx & 63);  // this thread holds columns 2dp, 2dp+1 of the quad's 4 keys
       const uint32_t a = r.v[4 * e + 0], b = r.v[4 * e + 1], c = r.v[4 * e + 2], d = r.v[4 * e + 3];
-      // low halves hold d0 of keys (a,b,c,d), high halves d0+1
+      // low halves hold column 2dp of keys (a,b,c,d), high halves column 2dp+1
       u32x2 lo = {__builtin_amdgcn_perm(b, a, 0x05040100u), __builtin_amdgcn_perm(d, c, 0x05040100u)};
       u32x2 hi = {__builtin_amdgcn_perm(b, a, 0x07060302u), __builtin_amdgcn_perm(d, c, 0x07060302u)};
-      *(u32x2 *)(vt + d0 * kVRow + vt_pos(kq) * 2) = lo;
-      *(u32x2 *)(vt + (d0 + 1) * kVRow + vt_pos(kq) * 2) = hi;
+      *(u32x2 *)(vt + vt_row(2 * dp) * kVRow + vt_pos(kq) * 2) = lo;
+      *(u32x2 *)(vt + vt_row(2 * dp + 1) * kVRow + vt_pos(kq) * 2) = hi;
     }
   } else {
 #pragma unroll
@@ -189,16 +198,17 @@ __device__ __forceinline__ void tile_store(uint8_t *stage, int tid, const TileRe
         lo[c] = fp8x2_to_bf16x2<false>(r.v[4 * e + c]);
         hi[c] = fp8x2_to_bf16x2<true>(r.v[4 * e + c]);
       }
-      uint8_t *dst = vt + d0 * kVRow + vt_pos(kq) * 2;
-      // row d0: low halves of lo[0..3]; row d0+1: high halves; rows d0+2, d0+3 likewise from hi[]
+      // columns d0..d0+3 live in rows (d0/4) + 32*{0,1,2,3}: consecutive lanes write consecutive rows
+      uint8_t *dst = vt + (d0 >> 2) * kVRow + vt_pos(kq) * 2;
+      // column d0: low halves of lo[0..3]; column d0+1: high halves; columns d0+2, d0+3 likewise from hi[]
       *(u32x2 *)(dst) = u32x2{__builtin_amdgcn_perm(lo[1], lo[0], 0x05040100u),
                               __builtin_amdgcn_perm(lo[3], lo[2], 0x05040100u)};
-      *(u32x2 *)(dst + kVRow) = u32x2{__builtin_amdgcn_perm(lo[1], lo[0], 0x07060302u),
-                                      __builtin_amdgcn_perm(lo[3], lo[2], 0x07060302u)};
-      *(u32x2 *)(dst + 2 * kVRow) = u32x2{__builtin_amdgcn_perm(hi[1], hi[0], 0x05040100u),
-                                          __builtin_amdgcn_perm(hi[3], hi[2], 0x05040100u)};
-      *(u32x2 *)(dst + 3 * kVRow) = u32x2{__builtin_amdgcn_perm(hi[1], hi[0], 0x07060302u),
-                                          __builtin_amdgcn_perm(hi[3], hi[2], 0x07060302u)};
+      *(u32x2 *)(dst + 32 * kVRow) = u32x2{__builtin_amdgcn_perm(lo[1], lo[0], 0x07060302u),
+                                           __builtin_amdgcn_perm(lo[3], lo[2], 0x07060302u)};
+      *(u32x2 *)(dst + 64 * kVRow) = u32x2{__builtin_amdgcn_perm(hi[1], hi[0], 0x05040100u),
+                                           __builtin_amdgcn_perm(hi[3], hi[2], 0x05040100u)};
+      *(u32x2 *)(dst + 96 * kVRow) = u32x2{__builtin_amdgcn_perm(hi[1], hi[0], 0x07060302u),
+                                           __builtin_amdgcn_perm(hi[3], hi[2], 0x07060302u)};
     }
   }
 }
@@ -229,6 +239,7 @@ __device__ __forceinline__ void compute_tile(const uint8_t *kt, RowState<RB> &st
                                              int limit, float cseg, float voff, float lmul) {
   const uint8_t *vt = kt + kKTileBytes;
   // ---- S^T = K Q^T -------------------------------------------------------------------
+  // K fragments are fetched from LDS four head-dim steps ahead of the MFMAs that consume them.
   f32x16 s[2][RB];
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb)
@@ -236,18 +247,35 @@ __device__ __forceinline__ void compute_tile(const uint8_t *kt, RowState<RB> &st
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
       for (int j = 0; j < 16; ++j) s[kb][rb][j] = 0.f;
+  const uint8_t *krow = kt + ln * kKRow + lh * 16;
+  auto load_k = [&](int t, int kb) {
+    return __builtin_bit_cast(bf16x8, *(const u32x4 *)(krow + kb * 32 * kKRow + t * 32));
+  };
+  bf16x8 kf[4][2];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) kf[t][kb] = load_k(t, kb);
 #pragma unroll
   for (int t = 0; t < 8; ++t) {
-    bf16x8 kf[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-      kf[kb] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(kt + (kb * 32 + ln) * kKRow + (16 * t + 8 * lh) * 2));
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
-        s[kb][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb], st.qf[rb][t], s[kb][rb], 0, 0, 0);
+        s[kb][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t & 3][kb], st.qf[rb][t], s[kb][rb], 0, 0, 0);
+    if (t + 4 < 8) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) kf[t & 3][kb] = load_k(t + 4, kb);
+    }
   }
+  // pin the order: 8 LDS reads, then 2*RB MFMAs and 2 LDS reads alternating, then the remaining MFMAs
+  __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * RB, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+  }
+  __builtin_amdgcn_sched_group_barrier(0x008, 8 * RB, 0);
 
   // ---- mask: register j of block kb holds key  kb*32 + (j/4)*8 + lh*4 + j%4  of the tile ----
   if constexpr (MASK == MASK_TAIL) {
@@ -499,14 +527,13 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
     if (row[rb] < p.R) {
       const size_t out_row = slot * p.n_rows + (size_t)st.row_tok[rb] * p.Hq + kvh * p.G + (row[rb] % p.G);
       float *po = p.part_o + out_row * kD;
+      // accumulator register j of d block db is MFMA row m = 8*(j/4) + 4*lh + j%4, i.e. column 4m + db
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          f32x4 v = {st.o[db][rb][4 * q4] * v_out, st.o[db][rb][4 * q4 + 1] * v_out,
-                     st.o[db][rb][4 * q4 + 2] * v_out, st.o[db][rb][4 * q4 + 3] * v_out};
-          *(f32x4 *)(po + db * 32 + q4 * 8 + lh * 4) = v;
-        }
+      for (int j = 0; j < 16; ++j) {
+        const int m = 8 * (j >> 2) + 4 * lh + (j & 3);
+        f32x4 v = {st.o[0][rb][j] * v_out, st.o[1][rb][j] * v_out, st.o[2][rb][j] * v_out, st.o[3][rb][j] * v_out};
+        *(f32x4 *)(po + 4 * m) = v;
+      }
       if (lh == 0) {
         f32x2 ml = {st.m_run[rb], l_tot};
         *(f32x2 *)(p.part_ml + out_row * 2) = ml;
