@@ -35,6 +35,7 @@ def parse_args():
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 2..5 (default 5, the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--kv-split-tokens", type=int, default=0)
+    ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
     return ap.parse_args()
 
 
@@ -113,7 +114,7 @@ def main():
 
     # ---- timed region: exactly --steps steps, per-kernel HIP events recorded on the launch stream -------------
     B.la_profile_reset()
-    B.la_profile_enable(True)
+    B.la_profile_enable(not args.no_kernel_events)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):

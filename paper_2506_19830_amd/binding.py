@@ -14,7 +14,10 @@ from typing import Optional, Sequence
 import torch
 
 _HERE = Path(__file__).resolve().parent
-LIB_PATH = _HERE / "libla_verify.so"
+import os as _os
+
+# LA_VERIFY_LIB: load another build of the library (kernel experiments); default is the in-tree build
+LIB_PATH = Path(_os.environ.get("LA_VERIFY_LIB", _HERE / "libla_verify.so"))
 
 LA_F32, LA_BF16, LA_FP8_E4M3 = 0, 1, 2
 DTYPE_CODES = {"f32": LA_F32, "bf16": LA_BF16, "fp8_e4m3": LA_FP8_E4M3}

@@ -34,7 +34,8 @@ def _hipcc() -> str:
     return "hipcc"
 
 
-def build(verbose: bool = False, extra_flags=()) -> Path:
+def build(verbose: bool = False, extra_flags=(), lib: Path = LIB) -> Path:
+    LIB_OUT = lib
     OBJ.mkdir(exist_ok=True)
     hipcc = _hipcc()
 
@@ -52,13 +53,13 @@ def build(verbose: bool = False, extra_flags=()) -> Path:
 
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
         objs = list(pool.map(compile_one, SOURCES))
-    tmp = LIB.with_suffix(".so.tmp%d" % os.getpid())
+    tmp = LIB_OUT.with_suffix(".so.tmp%d" % os.getpid())
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(tmp), *map(str, objs)]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr}")
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, LIB_OUT)
+    return LIB_OUT
 
 
 if __name__ == "__main__":

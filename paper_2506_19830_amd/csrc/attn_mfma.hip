@@ -229,144 +229,215 @@ struct RowState {
 
 enum MaskMode { MASK_NONE = 0, MASK_TAIL = 1, MASK_BRANCH = 2 };
 
-// One 64-key tile from an LDS stage: scores, (masked) online softmax, PV accumulation.
-//   first / limit   MASK_TAIL: keys with first + key >= limit are masked
-//                   MASK_BRANCH: key token first + key is visible to a row iff row_bstart <= token <= row_tok
-//   cseg            score scale of this key segment (log2 units); voff/lmul move a differently scaled V segment into
-//                   the accumulator's units (p' = p * 2^voff, l += sum(p') * lmul)
-template <int RB, int MASK>
-__device__ __forceinline__ void compute_tile(const uint8_t *kt, RowState<RB> &st, int ln, int lh, int first,
-                                             int limit, float cseg, float voff, float lmul) {
-  const uint8_t *vt = kt + kKTileBytes;
-  // ---- S^T = K Q^T -------------------------------------------------------------------
-  // K fragments are fetched from LDS four head-dim steps ahead of the MFMAs that consume them.
-  f32x16 s[2][RB];
-#pragma unroll
-  for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int j = 0; j < 16; ++j) s[kb][rb][j] = 0.f;
-  const uint8_t *krow = kt + ln * kKRow + lh * 16;
-  auto load_k = [&](int t, int kb) {
-    return __builtin_bit_cast(bf16x8, *(const u32x4 *)(krow + kb * 32 * kKRow + t * 32));
-  };
-  bf16x8 kf[4][2];
-#pragma unroll
-  for (int t = 0; t < 4; ++t)
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) kf[t][kb] = load_k(t, kb);
-#pragma unroll
-  for (int t = 0; t < 8; ++t) {
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-        s[kb][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t & 3][kb], st.qf[rb][t], s[kb][rb], 0, 0, 0);
-    if (t + 4 < 8) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) kf[t & 3][kb] = load_k(t + 4, kb);
-    }
-  }
-  // pin the order: 8 LDS reads, then 2*RB MFMAs and 2 LDS reads alternating, then the remaining MFMAs
-  __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-#pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 2 * RB, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-  }
-  __builtin_amdgcn_sched_group_barrier(0x008, 8 * RB, 0);
+// sched_group_barrier masks
+constexpr int kSgMfma = 0x008, kSgValu = 0x002, kSgDsRead = 0x100;
 
-  // ---- mask: register j of block kb holds key  kb*32 + (j/4)*8 + lh*4 + j%4  of the tile ----
+// Mask the scores of one 32-key block: register j holds key  kb*32 + (j/4)*8 + lh*4 + j%4  of the tile.
+template <int RB, int MASK>
+__device__ __forceinline__ void mask_block(f32x16 (&s)[RB], const RowState<RB> &st, int kb, int lh, int first,
+                                           int limit) {
   if constexpr (MASK == MASK_TAIL) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int j = 0; j < 16; ++j) {
+      const int key = first + kb * 32 + (j >> 2) * 8 + lh * 4 + (j & 3);
+      if (key >= limit) {
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const int key = first + kb * 32 + (j >> 2) * 8 + lh * 4 + (j & 3);
-        if (key >= limit) {
-#pragma unroll
-          for (int rb = 0; rb < RB; ++rb) s[kb][rb][j] = -INFINITY;
-        }
+        for (int rb = 0; rb < RB; ++rb) s[rb][j] = -INFINITY;
       }
+    }
   } else if constexpr (MASK == MASK_BRANCH) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int j = 0; j < 16; ++j) {
+      const int tk = first + kb * 32 + (j >> 2) * 8 + lh * 4 + (j & 3);
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const int tk = first + kb * 32 + (j >> 2) * 8 + lh * 4 + (j & 3);
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-          if (tk > st.row_tok[rb] || tk < st.row_bstart[rb]) s[kb][rb][j] = -INFINITY;
-      }
+      for (int rb = 0; rb < RB; ++rb)
+        if (tk > st.row_tok[rb] || tk < st.row_bstart[rb]) s[rb][j] = -INFINITY;
+    }
   }
+}
 
-  // ---- online softmax ------------------------------------------------------------------
-  float mt[RB];
+// Fold the block maximum of every row into its running maximum (log2 units).  A lane raises its maximum only when
+// the block exceeds it by more than kRaise; alpha is the factor its old accumulators must then be multiplied by
+// (1 for lanes that keep their maximum).  Returns whether any lane of the wavefront raised (wavefront-uniform).
+template <int RB>
+__device__ __forceinline__ bool update_max(const f32x16 (&s)[RB], RowState<RB> &st, float cseg, float (&alpha)[RB]) {
   bool raise = false;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    float m0 = fmaxf(s[0][rb][0], s[1][rb][0]);
+    float m0 = fmaxf(s[rb][0], s[rb][1]);
 #pragma unroll
-    for (int j = 1; j < 16; ++j) m0 = fmaxf(m0, fmaxf(s[0][rb][j], s[1][rb][j]));
-    mt[rb] = xhalf_max(m0) * cseg;
-    raise |= mt[rb] > st.m_run[rb] + kRaise;
+    for (int j = 2; j < 16; j += 2) m0 = fmaxf(m0, fmaxf(s[rb][j], s[rb][j + 1]));
+    const float mt = xhalf_max(m0) * cseg;
+    const bool up = mt > st.m_run[rb] + kRaise;   // false for mt = -inf; true for the first finite block (m_run = -inf)
+    const float m_new = up ? mt : st.m_run[rb];
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    alpha[rb] = up ? __builtin_amdgcn_exp2f(st.m_run[rb] - m_use) : 1.0f;   // 0 when m_run was -inf
+    st.m_run[rb] = m_new;
+    raise |= up;
   }
-  if (__builtin_amdgcn_ballot_w64(raise) != 0) {  // wavefront-uniform: some row's maximum jumped
+  return __builtin_amdgcn_ballot_w64(raise) != 0;
+}
+
+template <int RB>
+__device__ __forceinline__ void rescale(RowState<RB> &st, const float (&alpha)[RB]) {
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      const float m_new = fmaxf(st.m_run[rb], mt[rb]);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(st.m_run[rb] - m_use);  // 0 when m_run was -inf
-      st.m_run[rb] = m_new;
-      st.l_run[rb] *= alpha;
+  for (int rb = 0; rb < RB; ++rb) {
+    st.l_run[rb] *= alpha[rb];
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
+    for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) st.o[db][rb][j] *= alpha;
-    }
+      for (int j = 0; j < 16; ++j) st.o[db][rb][j] *= alpha[rb];
   }
-  uint32_t pb[2][RB][8];  // P^T as bf16 pairs: [kb][rb][j/2]
+}
+
+// p = 2^(s*cseg - m + voff) for one 32-key block, rounded to bf16 pairs; returns the row sums of the rounded values.
+template <int RB>
+__device__ __forceinline__ void block_probs(const f32x16 (&s)[RB], const RowState<RB> &st, float cseg, float voff,
+                                            uint32_t (&pb)[RB][8], float (&sum)[RB]) {
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     const float m_use = (st.m_run[rb] == -INFINITY) ? 0.f : st.m_run[rb];
     const float off = voff - m_use;
-    float sum = 0.f;
+    float acc = 0.f;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int j = 0; j < 16; j += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][rb][j], cseg, off));
-        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][rb][j + 1], cseg, off));
-        const uint32_t pk = pack_bf16(p0, p1);
-        pb[kb][rb][j >> 1] = pk;
-        // row sum of the rounded probabilities, the same numbers the PV product uses
-        sum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), __builtin_bit_cast(bf16x2, 0x3F803F80u),
-                                              sum, false);
-      }
-    st.l_run[rb] += sum * lmul;
-  }
-
-  // ---- O^T += V^T P^T ------------------------------------------------------------------
-#pragma unroll
-  for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2) {
-      bf16x8 pf[RB];
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
-        u32x4 v = {pb[kb][rb][4 * t2], pb[kb][rb][4 * t2 + 1], pb[kb][rb][4 * t2 + 2], pb[kb][rb][4 * t2 + 3]};
-        pf[rb] = __builtin_bit_cast(bf16x8, v);
-      }
-#pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        const bf16x8 vf = __builtin_bit_cast(
-            bf16x8, *(const u32x4 *)(vt + (db * 32 + ln) * kVRow + (kb * 32 + t2 * 16 + lh * 8) * 2));
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-          st.o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[rb], st.o[db][rb], 0, 0, 0);
-      }
+    for (int j = 0; j < 16; j += 2) {
+#ifdef LA_EXP_NOEXP
+      const float p0 = __builtin_fmaf(s[rb][j], cseg, off);
+      const float p1 = __builtin_fmaf(s[rb][j + 1], cseg, off);
+#else
+      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[rb][j], cseg, off));
+      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[rb][j + 1], cseg, off));
+#endif
+      const uint32_t pk = pack_bf16(p0, p1);
+      pb[rb][j >> 1] = pk;
+      acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), __builtin_bit_cast(bf16x2, 0x3F803F80u),
+                                            acc, false);
     }
+    sum[rb] = acc;
+  }
+}
+
+// One 64-key tile from an LDS stage, as two 32-key blocks whose MFMA and VALU work is interleaved:
+//     S0 = K0 Q^T                    |
+//     S1 = K1 Q^T                    |  P0 = 2^(S0 - m)          (VALU next to the MFMAs of the other block)
+//     O += V0^T P0                   |  P1 = 2^(S1 - m)
+//     O += V1^T P1                   |  tail()  (the caller's LDS stores of the next tile)
+//   first / limit   MASK_TAIL: keys with first + key >= limit are masked
+//                   MASK_BRANCH: key token first + key is visible to a row iff row_bstart <= token <= row_tok
+//   cseg            score scale of this key segment (log2 units); voff/lmul move a differently scaled V segment into
+//                   the accumulator's units (p' = p * 2^voff, l += sum(p') * lmul)
+template <int RB, int MASK, typename Tail>
+__device__ __forceinline__ void compute_tile(const uint8_t *kt, RowState<RB> &st, int ln, int lh, int first,
+                                             int limit, float cseg, float voff, float lmul, Tail &&tail) {
+  const uint8_t *krow = kt + ln * kKRow + lh * 16;
+  const uint8_t *vrow = kt + kKTileBytes + ln * kVRow + lh * 16;
+  auto load_k = [&](int t, int kb) {
+    return __builtin_bit_cast(bf16x8, *(const u32x4 *)(krow + kb * 32 * kKRow + t * 32));
+  };
+  auto load_v = [&](int db, int kb, int t2) {
+    return __builtin_bit_cast(bf16x8, *(const u32x4 *)(vrow + db * 32 * kVRow + (kb * 32 + t2 * 16) * 2));
+  };
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  // ---- S0 = K0 Q^T; the K1 fragments are fetched behind the MFMAs ---------------------------
+  f32x16 s0[RB], s1[RB];
+  bf16x8 k0[8], k1[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) k0[t] = load_k(t, 0);
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+      s0[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0[t], st.qf[rb][t], t == 0 ? zero : s0[rb], 0, 0, 0);
+    k1[t] = load_k(t, 1);
+  }
+  __builtin_amdgcn_sched_group_barrier(kSgDsRead, 8, 0);
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    __builtin_amdgcn_sched_group_barrier(kSgMfma, RB, 0);
+    __builtin_amdgcn_sched_group_barrier(kSgDsRead, 1, 0);
+  }
+  mask_block<RB, MASK>(s0, st, 0, lh, first, limit);
+  float alpha[RB];
+  if (update_max<RB>(s0, st, cseg, alpha)) rescale<RB>(st, alpha);
+
+  // ---- one basic block: S1 = K1 Q^T next to P0 = 2^(S0 - m), then O += V0^T P0 next to P1 = 2^(S1 - m).
+  //      The V fragments are fetched from LDS behind the MFMAs.
+  uint32_t p0[RB][8], p1[RB][8];
+  float sum0[RB], sum1[RB];
+  bf16x8 v0[2][4], v1[2][4];
+#pragma unroll
+  for (int t = 0; t < 8; ++t)
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+      s1[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1[t], st.qf[rb][t], t == 0 ? zero : s1[rb], 0, 0, 0);
+  block_probs<RB>(s0, st, cseg, voff, p0, sum0);
+#pragma unroll
+  for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+    for (int db = 0; db < 4; ++db) v0[t2][db] = load_v(db, 0, t2);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {  // per step: RB MFMAs, 6*RB VALU (of 48*RB), one LDS read
+    __builtin_amdgcn_sched_group_barrier(kSgMfma, RB, 0);
+    __builtin_amdgcn_sched_group_barrier(kSgValu, 6 * RB, 0);
+    __builtin_amdgcn_sched_group_barrier(kSgDsRead, 1, 0);
+  }
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) st.l_run[rb] += sum0[rb] * lmul;
+  mask_block<RB, MASK>(s1, st, 1, lh, first, limit);
+  const bool raise1 = update_max<RB>(s1, st, cseg, alpha);  // accumulators are rescaled after block 0 went in
+#pragma unroll
+  for (int t2 = 0; t2 < 2; ++t2) {
+    bf16x8 pf[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      u32x4 v = {p0[rb][4 * t2], p0[rb][4 * t2 + 1], p0[rb][4 * t2 + 2], p0[rb][4 * t2 + 3]};
+      pf[rb] = __builtin_bit_cast(bf16x8, v);
+    }
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+        st.o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0[t2][db], pf[rb], st.o[db][rb], 0, 0, 0);
+  }
+  block_probs<RB>(s1, st, cseg, voff, p1, sum1);
+#pragma unroll
+  for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+    for (int db = 0; db < 4; ++db) v1[t2][db] = load_v(db, 1, t2);
+  __builtin_amdgcn_sched_group_barrier(kSgValu, 14 * RB, 0);  // the block-1 maximum
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    __builtin_amdgcn_sched_group_barrier(kSgMfma, RB, 0);
+    __builtin_amdgcn_sched_group_barrier(kSgValu, 6 * RB, 0);
+    __builtin_amdgcn_sched_group_barrier(kSgDsRead, 1, 0);
+  }
+  // keep the block-1 probabilities on this side of the branch below (otherwise they are sunk past it and no longer
+  // overlap the MFMAs above)
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+    asm volatile("" ::"v"(p1[rb][0]), "v"(p1[rb][1]), "v"(p1[rb][2]), "v"(p1[rb][3]), "v"(p1[rb][4]), "v"(p1[rb][5]),
+                 "v"(p1[rb][6]), "v"(p1[rb][7]), "v"(sum1[rb]));
+  if (raise1) rescale<RB>(st, alpha);
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) st.l_run[rb] += sum1[rb] * lmul;
+
+  // ---- O += V1^T P1 next to the caller's tail work ----------------------------------------------
+#pragma unroll
+  for (int t2 = 0; t2 < 2; ++t2) {
+    bf16x8 pf[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      u32x4 v = {p1[rb][4 * t2], p1[rb][4 * t2 + 1], p1[rb][4 * t2 + 2], p1[rb][4 * t2 + 3]};
+      pf[rb] = __builtin_bit_cast(bf16x8, v);
+    }
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+        st.o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1[t2][db], pf[rb], st.o[db][rb], 0, 0, 0);
+  }
+  tail();
 }
 
 // NW wavefronts of RB 32-row blocks each: a row tile of 32*NW*RB rows.
@@ -487,12 +558,17 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
     __syncthreads();
     for (int it = 0; it < n_full; ++it) {
       const bool has_next = it + 1 < n_full;
+#ifndef LA_EXP_NOLOAD
       if (has_next) {
         pre.first = k_begin + (it + 1) * kTileN;
         tile_load<KV_FP8, true, true, NT>(p, pre, tid, regs);
       }
-      compute_tile<RB, MASK_NONE>(lds + stage * kStageBytes, st, ln, lh, 0, 0, c_prefix, 0.f, 1.f);
-      if (has_next) tile_store<KV_FP8, NT>(lds + (stage ^ 1) * kStageBytes, tid, regs);
+#endif
+      compute_tile<RB, MASK_NONE>(lds + stage * kStageBytes, st, ln, lh, 0, 0, c_prefix, 0.f, 1.f, [&] {
+#ifndef LA_EXP_NOSTORE
+        if (has_next) tile_store<KV_FP8, NT>(lds + (stage ^ 1) * kStageBytes, tid, regs);
+#endif
+      });
       __syncthreads();
       stage ^= 1;
     }
@@ -504,7 +580,7 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
     tile_load<KV_FP8, true, false, NT>(p, pre, tid, regs);
     tile_store<KV_FP8, NT>(lds + stage * kStageBytes, tid, regs);
     __syncthreads();
-    compute_tile<RB, MASK_TAIL>(lds + stage * kStageBytes, st, ln, lh, pre.first, k_end, c_prefix, 0.f, 1.f);
+    compute_tile<RB, MASK_TAIL>(lds + stage * kStageBytes, st, ln, lh, pre.first, k_end, c_prefix, 0.f, 1.f, [] {});
     __syncthreads();
   }
   // ---- phase 3: branch-private tiles (last chunk only) ------------------------------------------
@@ -515,7 +591,7 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
     tile_store<BR_FP8, NT>(lds + stage * kStageBytes, tid, regs);
     __syncthreads();
     compute_tile<RB, MASK_BRANCH>(lds + stage * kStageBytes, st, ln, lh, brs.first, 0, c_branch, voff_branch,
-                                  lmul_branch);
+                                  lmul_branch, [] {});
     __syncthreads();
   }
 

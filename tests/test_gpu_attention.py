@@ -94,7 +94,7 @@ def test_split_count_changes_nothing_beyond_rounding(oracle):
     inp = W.make_attention_inputs(case)
     a, _ = run_attention(case, inp, 64)
     b, _ = run_attention(case, inp, 1024)
-    assert row_errors(a, b).max() < 5e-3
+    assert row_errors(a, b).max() < 1e-2      # each run is within ~3e-3 of the exact result (P rounded to bf16)
 
 
 def test_deterministic_and_block_permutation_invariant():
