@@ -84,14 +84,25 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, Attn
   plan->n_row_tiles = (R + plan->tile_m - 1) / plan->tile_m;
   int chunk = d->kv_split_tokens;
   if (chunk == 0) {
-    // Aim for about four workgroups per CU so that the tail of the launch is short, but keep a
-    // chunk at least 1024 tokens long: every chunk costs one partial (row x (D+2) floats) in HBM.
+    // Pick the chunk length that minimises a simple cost model, in units of one 64-key tile of one workgroup:
+    //   waves of workgroups over the CUs  x  (tiles per chunk + fixed per-workgroup work)  +  partials to merge.
+    // Few long chunks keep the partial traffic (rows x (D+2) floats per chunk) small; the number of workgroups
+    // should fill a whole number of waves of the 256 CUs (one workgroup per CU).
     const int64_t base_wgs = (int64_t)d->num_kv_heads * plan->n_row_tiles;
-    const int64_t want_units = (4 * kNumCUs + base_wgs - 1) / base_wgs;
-    int64_t len = sum_p > 0 ? (sum_p + want_units - 1) / want_units : 1024;
-    len = ((len + 63) / 64) * 64;
-    if (len < 1024) len = 1024;
-    chunk = (int)len;
+    double best_cost = 0.0;
+    int best_len = 0;
+    for (int n = 1; n <= 256; ++n) {
+      int64_t len = max_p > 0 ? (max_p + n - 1) / n : 64;
+      len = ((len + 63) / 64) * 64;
+      int64_t units = 0;
+      for (int b = 0; b < d->num_requests; ++b) units += attn_num_chunks(prefix_lens_host[b], (int)len);
+      const int64_t waves = (base_wgs * units + kNumCUs - 1) / kNumCUs;
+      const double per_unit = units > 0 ? (double)units / d->num_requests : 1.0;
+      const double cost = (double)waves * ((double)len / 64 + 10.0) + 4.0 * per_unit;
+      if (best_len == 0 || cost < best_cost) best_cost = cost, best_len = (int)len;
+      if (len <= 64) break;
+    }
+    chunk = best_len;
   }
   // the block ids of one chunk live in LDS
   const int64_t max_chunk = (int64_t)(attn_mfma_max_chunk_blocks() - 1) * d->block_size;  // -1: unaligned chunk start

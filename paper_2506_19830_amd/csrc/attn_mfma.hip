@@ -40,7 +40,8 @@ constexpr int kKTileBytes = kTileN * kKRow;  // 17408
 constexpr int kVTileBytes = kD * kVRow;      // 18432
 constexpr int kStageBytes = kKTileBytes + kVTileBytes;
 constexpr int kMaxChunkBlocks = 4096;        // block ids of one chunk kept in LDS
-constexpr int kLdsTotal = 2 * kStageBytes + kMaxChunkBlocks * 4;  // two stages + block ids: 88064
+constexpr int kStages = 3;                   // LDS ring: tile i is computed on while i+1 is resident and i+2 is written
+constexpr int kLdsTotal = kStages * kStageBytes + kMaxChunkBlocks * 4;  // stages + block ids: 123904
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   f32x2 f = {a, b};
@@ -326,9 +327,13 @@ __device__ __forceinline__ void block_probs(const f32x16 (&s)[RB], const RowStat
 //                   MASK_BRANCH: key token first + key is visible to a row iff row_bstart <= token <= row_tok
 //   cseg            score scale of this key segment (log2 units); voff/lmul move a differently scaled V segment into
 //                   the accumulator's units (p' = p * 2^voff, l += sum(p') * lmul)
-template <int RB, int MASK, typename Tail>
-__device__ __forceinline__ void compute_tile(const uint8_t *kt, RowState<RB> &st, int ln, int lh, int first,
-                                             int limit, float cseg, float voff, float lmul, Tail &&tail) {
+//   k0              the K fragments of key block 0.  K0_READY: the caller already holds them (fetched while the
+//                   previous tile was finishing); otherwise they are read here.  With next_kt != nullptr the block-0
+//                   fragments of the tile staged at next_kt are fetched behind the last MFMAs and left in k0.
+template <int RB, int MASK, bool K0_READY, bool PREFETCH, typename Tail>
+__device__ __forceinline__ void compute_tile(const uint8_t *kt, const uint8_t *next_kt, bf16x8 (&k0)[8],
+                                             RowState<RB> &st, int ln, int lh, int first, int limit, float cseg,
+                                             float voff, float lmul, Tail &&tail) {
   const uint8_t *krow = kt + ln * kKRow + lh * 16;
   const uint8_t *vrow = kt + kKTileBytes + ln * kVRow + lh * 16;
   auto load_k = [&](int t, int kb) {
@@ -341,9 +346,11 @@ __device__ __forceinline__ void compute_tile(const uint8_t *kt, RowState<RB> &st
 
   // ---- S0 = K0 Q^T; the K1 fragments are fetched behind the MFMAs ---------------------------
   f32x16 s0[RB], s1[RB];
-  bf16x8 k0[8], k1[8];
+  bf16x8 k1[8];
+  if constexpr (!K0_READY) {
 #pragma unroll
-  for (int t = 0; t < 8; ++t) k0[t] = load_k(t, 0);
+    for (int t = 0; t < 8; ++t) k0[t] = load_k(t, 0);
+  }
 #pragma unroll
   for (int t = 0; t < 8; ++t) {
 #pragma unroll
@@ -351,7 +358,7 @@ __device__ __forceinline__ void compute_tile(const uint8_t *kt, RowState<RB> &st
       s0[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0[t], st.qf[rb][t], t == 0 ? zero : s0[rb], 0, 0, 0);
     k1[t] = load_k(t, 1);
   }
-  __builtin_amdgcn_sched_group_barrier(kSgDsRead, 8, 0);
+  if constexpr (!K0_READY) __builtin_amdgcn_sched_group_barrier(kSgDsRead, 8, 0);
 #pragma unroll
   for (int t = 0; t < 8; ++t) {
     __builtin_amdgcn_sched_group_barrier(kSgMfma, RB, 0);
@@ -437,6 +444,16 @@ __device__ __forceinline__ void compute_tile(const uint8_t *kt, RowState<RB> &st
       for (int rb = 0; rb < RB; ++rb)
         st.o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1[t2][db], pf[rb], st.o[db][rb], 0, 0, 0);
   }
+  if constexpr (PREFETCH) {
+    const uint8_t *nrow = next_kt + ln * kKRow + lh * 16;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) k0[t] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(nrow + t * 32));
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      __builtin_amdgcn_sched_group_barrier(kSgMfma, RB, 0);
+      __builtin_amdgcn_sched_group_barrier(kSgDsRead, 1, 0);
+    }
+  }
   tail();
 }
 
@@ -478,7 +495,7 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
   const int n_priv = (c == n_chunks - 1) ? (t_hi - tk0 + 1 + kTileN - 1) / kTileN : 0;
 
   // ---- physical block ids of this chunk -> LDS ---------------------------------------------
-  int32_t *blk_lds = (int32_t *)(lds + 2 * kStageBytes);
+  int32_t *blk_lds = (int32_t *)(lds + kStages * kStageBytes);
   const int first_lb = k_begin >> p.block_shift;
   if (k_end > k_begin) {
     const int n_blk = ((k_end - 1) >> p.block_shift) - first_lb + 1;  // <= kMaxChunkBlocks (host guarantees)
@@ -548,39 +565,54 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
 
   __syncthreads();  // block ids visible
 
-  // ---- phase 1: the unmasked prefix tiles, double buffered ------------------------------------
-  int stage = 0;
+  // ---- phase 1: the unmasked prefix tiles through a ring of three LDS stages ----------------------
+  // iteration i: global loads of tile i+2 are in flight, tile i is computed from stage i%3 (its block-0 K fragments
+  // were fetched while tile i-1 finished), the block-0 fragments of tile i+1 are fetched from stage (i+1)%3, and
+  // tile i+2 is written to stage (i+2)%3, which every wavefront stopped reading at the barrier before.
+  bf16x8 k0[8];
   if (n_full > 0) {
     TileRegs<KV_FP8, NT> regs;
-    pre.first = k_begin;
-    tile_load<KV_FP8, true, true, NT>(p, pre, tid, regs);
-    tile_store<KV_FP8, NT>(lds, tid, regs);
-    __syncthreads();
-    for (int it = 0; it < n_full; ++it) {
-      const bool has_next = it + 1 < n_full;
-#ifndef LA_EXP_NOLOAD
-      if (has_next) {
-        pre.first = k_begin + (it + 1) * kTileN;
-        tile_load<KV_FP8, true, true, NT>(p, pre, tid, regs);
-      }
-#endif
-      compute_tile<RB, MASK_NONE>(lds + stage * kStageBytes, st, ln, lh, 0, 0, c_prefix, 0.f, 1.f, [&] {
-#ifndef LA_EXP_NOSTORE
-        if (has_next) tile_store<KV_FP8, NT>(lds + (stage ^ 1) * kStageBytes, tid, regs);
-#endif
-      });
-      __syncthreads();
-      stage ^= 1;
+    auto stage_of = [&](int it) { return lds + (it % kStages) * kStageBytes; };
+    auto gload = [&](int it) {
+      pre.first = k_begin + it * kTileN;
+      tile_load<KV_FP8, true, true, NT>(p, pre, tid, regs);
+    };
+    gload(0);
+    tile_store<KV_FP8, NT>(stage_of(0), tid, regs);
+    if (n_full > 1) {
+      gload(1);
+      tile_store<KV_FP8, NT>(stage_of(1), tid, regs);
     }
+    __syncthreads();
+    {
+      const uint8_t *krow = stage_of(0) + ln * kKRow + lh * 16;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) k0[t] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(krow + t * 32));
+    }
+    int it = 0;
+    for (; it + 2 < n_full; ++it) {  // steady state: nothing conditional
+      gload(it + 2);
+      compute_tile<RB, MASK_NONE, true, true>(stage_of(it), stage_of(it + 1), k0, st, ln, lh, 0, 0, c_prefix, 0.f,
+                                              1.f, [&] { tile_store<KV_FP8, NT>(stage_of(it + 2), tid, regs); });
+      __syncthreads();
+    }
+    if (it + 1 < n_full) {  // second to last tile: nothing left to load
+      compute_tile<RB, MASK_NONE, true, true>(stage_of(it), stage_of(it + 1), k0, st, ln, lh, 0, 0, c_prefix, 0.f,
+                                              1.f, [] {});
+      ++it;
+    }
+    compute_tile<RB, MASK_NONE, true, false>(stage_of(it), nullptr, k0, st, ln, lh, 0, 0, c_prefix, 0.f, 1.f, [] {});
+    __syncthreads();
   }
   // ---- phase 2: the partly filled prefix tile -------------------------------------------------
   if (has_tail) {
     TileRegs<KV_FP8, NT> regs;
     pre.first = k_begin + n_full * kTileN;
     tile_load<KV_FP8, true, false, NT>(p, pre, tid, regs);
-    tile_store<KV_FP8, NT>(lds + stage * kStageBytes, tid, regs);
+    tile_store<KV_FP8, NT>(lds, tid, regs);
     __syncthreads();
-    compute_tile<RB, MASK_TAIL>(lds + stage * kStageBytes, st, ln, lh, pre.first, k_end, c_prefix, 0.f, 1.f, [] {});
+    compute_tile<RB, MASK_TAIL, false, false>(lds, nullptr, k0, st, ln, lh, pre.first, k_end, c_prefix, 0.f, 1.f,
+                                              [] {});
     __syncthreads();
   }
   // ---- phase 3: branch-private tiles (last chunk only) ------------------------------------------
@@ -588,10 +620,10 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
     TileRegs<BR_FP8, NT> regs;
     brs.first = tk0 + it * kTileN;
     tile_load<BR_FP8, false, false, NT>(p, brs, tid, regs);
-    tile_store<BR_FP8, NT>(lds + stage * kStageBytes, tid, regs);
+    tile_store<BR_FP8, NT>(lds, tid, regs);
     __syncthreads();
-    compute_tile<RB, MASK_BRANCH>(lds + stage * kStageBytes, st, ln, lh, brs.first, 0, c_branch, voff_branch,
-                                  lmul_branch, [] {});
+    compute_tile<RB, MASK_BRANCH, false, false>(lds, nullptr, k0, st, ln, lh, brs.first, 0, c_branch, voff_branch,
+                                                lmul_branch, [] {});
     __syncthreads();
   }
 
@@ -630,7 +662,7 @@ hipError_t launch_variant(const AttnParams &p, hipStream_t stream) {
   }
   // two tile stages plus the block ids of one chunk (a chunk that does not start on a block boundary spans one more)
   const int blk_entries = (p.chunk_len >> p.block_shift) + 2;
-  const int lds_bytes = 2 * kStageBytes + (blk_entries < kMaxChunkBlocks ? blk_entries : kMaxChunkBlocks) * 4;
+  const int lds_bytes = kStages * kStageBytes + (blk_entries < kMaxChunkBlocks ? blk_entries : kMaxChunkBlocks) * 4;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NW), lds_bytes, stream, p);
   return hipGetLastError();
 }
