@@ -35,7 +35,9 @@ def parse_args():
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 2..5 (default 5, the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--kv-split-tokens", type=int, default=0)
-    ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (three times) before the timed region, so that a counter "
+                         "run can scale FETCH_SIZE / WRITE_SIZE by what they read for a kernel of known traffic")
     return ap.parse_args()
 
 
@@ -111,10 +113,17 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- timed region: exactly --steps steps, per-kernel HIP events recorded on the launch stream -------------
     B.la_profile_reset()
-    B.la_profile_enable(not args.no_kernel_events)
+    B.la_profile_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -185,19 +194,24 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         oracle.build()
-        host = W.device_inputs_to_numpy(attn_case, layers[0])
-        t0 = time.perf_counter()
-        ref, _ = oracle.verify_attention(**host, q_dtype=attn_case.q_dtype, kv_dtype=attn_case.kv_dtype,
-                                         branch_kv_dtype=attn_case.branch_kv_dtype, block_size=attn_case.block_size,
-                                         scale=attn_case.scale)
-        t_attn = time.perf_counter() - t0
+        sample_layers = sorted({0, n_layers - 1})        # first and last layer of the sweep, each in full
+        t_attn, worst = 0.0, 0.0
+        D = attn_case.D
+        for l in sample_layers:
+            host = W.device_inputs_to_numpy(attn_case, layers[l])
+            t0 = time.perf_counter()
+            ref, _ = oracle.verify_attention(**host, q_dtype=attn_case.q_dtype, kv_dtype=attn_case.kv_dtype,
+                                             branch_kv_dtype=attn_case.branch_kv_dtype,
+                                             block_size=attn_case.block_size, scale=attn_case.scale)
+            t_attn += time.perf_counter() - t0
+            got = outs[l].double().cpu().numpy()
+            err = np.abs(got.reshape(-1, D) - ref.reshape(-1, D)).max(1) / np.abs(ref.reshape(-1, D)).max(1)
+            worst = max(worst, float(err.max()))
+        t_layer = t_attn / len(sample_layers)
         t0 = time.perf_counter()
         aref = oracle.spec_accept(**acc_np, logits_dtype=acc_case.logits_dtype, temperature=acc_case.temperature)
         t_acc = time.perf_counter() - t0
-        cpu_pass_s = t_attn * n_layers + t_acc
-        got = outs[0].double().cpu().numpy()
-        D = attn_case.D
-        err = np.abs(got.reshape(-1, D) - ref.reshape(-1, D)).max(1) / np.abs(ref.reshape(-1, D)).max(1)
+        cpu_pass_s = t_layer * n_layers + t_acc
         near = np.array([(m[np.isfinite(m)] <= 1e-6).any() for m in aref["margin"]])
         same = (n_acc.cpu().numpy() == aref["accepted_len"]) & (nxt.cpu().numpy() == aref["next_token"])
         result["cpu_baseline"] = {
@@ -205,10 +219,10 @@ def main():
             "unit": "branch-tokens/s",
             "cores": oracle.num_threads(),
             "kind": "oracle",
-            "sample": f"attention layer 0 of {n_layers} in full ({t_attn:.2f} s, scaled x{n_layers}) + the accept "
-                      f"call in full ({t_acc:.2f} s)",
+            "sample": f"attention layers {sample_layers} of {n_layers} in full ({t_attn:.2f} s; per-layer mean scaled "
+                      f"x{n_layers}) + the accept call in full ({t_acc:.2f} s)",
         }
-        result["parity"] = {"attention_layer0_max_row_rel_err": float(err.max()), "tolerance": 2e-2,
+        result["parity"] = {"attention_sampled_layers_max_row_rel_err": worst, "tolerance": 2e-2,
                             "accept_mismatches": int((~same & ~near).sum()), "accept_near_threshold": int(near.sum())}
     print(json.dumps(result))
     return 0
