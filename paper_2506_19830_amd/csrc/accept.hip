@@ -6,17 +6,21 @@
 // a bonus token is drawn from p_K.
 //
 // Four launches:
-//   stats   one coalesced pass over every logit row (NB*(2K+1) rows x V): per
-//           (row, vocabulary slice) the exact maximum and sum 2^((x-max)*log2e/T), fp32.
-//           This is the HBM-bound part: each logit is read exactly once.
-//   decide  per branch: fold the slice statistics, gather p_i(x_i), q_i(x_i), test
-//           u*q < p in order, write n.  Also starts the fp64 resampling path:
-//   resid   (two phases in one kernel file) fp64 normaliser of the two rows at position n,
-//           then fp64 slice sums of max(0, p-q) (and of p, the fallback when the residual
-//           has no mass, and the distribution of the bonus token).
-//   pick    per branch: locate the slice in which the running sum first exceeds
-//           u_sample * total, then the token inside it (block scan in token order).
-// The resampling rows are re-read (2 rows of NB*(2K+1)); they are L2/Infinity-Cache hits.
+//   stats   one coalesced pass over every logit row (NB*(2K+1) rows x V): per (row, slice)
+//           the exact maximum and sum 2^((x-max)*log2e/T), fp32.  This is the HBM-bound
+//           part: each logit is read exactly once, 16-byte loads, eight in flight per lane.
+//   decide  grid (fine slices, NB): every workgroup folds the slice statistics of its
+//           branch, gathers p_i(x_i), q_i(x_i) and tests u*q < p in order (n); then the fp64
+//           resampling path starts: its share of sum exp(z - max) of the two rows at
+//           position n (target row n and draft row n, or target row K alone when n = K).
+//   resid   grid (fine slices, NB): fp64 normalisers from the shares above, then per lane
+//           the mass of its 8 consecutive tokens: max(0, p-q) (and p itself, which is the
+//           distribution of the bonus token and the fallback when the residual has no
+//           mass).  Per-lane and per-slice sums go to the workspace.
+//   pick    grid NB: the slice in which the running sum first exceeds u_sample * total,
+//           then the lane inside it (scan of the stored per-lane sums), then the token
+//           among that lane's 8 (re-evaluated by one lane).
+// The two resampling rows are re-read twice (2 of the 2K+1 rows of a branch; cache hits).
 // fp64 there makes the blocked running sum agree with a sequential one to ~1e-16, so the
 // drawn token does not depend on the summation order.
 #include <limits.h>
@@ -27,12 +31,11 @@ namespace la {
 namespace {
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 
 constexpr int kThreads = 256;
-constexpr int kPer = 32;                    // elements per thread per slice
-constexpr int kChunk = kThreads * kPer;     // 8192 vocabulary entries per slice
+constexpr int kFinePer = 8;                 // tokens per lane in the fp64 kernels
+constexpr int kFine = kThreads * kFinePer;  // 2048 tokens per fine slice
 
 // (bit-casting a vector element in place, __builtin_bit_cast(float, w[k]), reads element 0 with this compiler;
 // pass the element by value instead)
@@ -40,8 +43,9 @@ __device__ __forceinline__ float as_f32(uint32_t w) { return __builtin_bit_cast(
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xFFFF0000u); }
 
-__device__ __forceinline__ float load_logit(const void *base, size_t idx, bool bf16) {
-  if (bf16) return __builtin_bit_cast(float, (uint32_t)((const uint16_t *)base)[idx] << 16);
+template <bool BF16>
+__device__ __forceinline__ float load_logit(const void *base, size_t idx) {
+  if constexpr (BF16) return __builtin_bit_cast(float, (uint32_t)((const uint16_t *)base)[idx] << 16);
   return ((const float *)base)[idx];
 }
 
@@ -62,63 +66,76 @@ __device__ __forceinline__ double wave_sum(double v) {
 }
 
 // row rw of the stacked [target rows ; draft rows] list
+template <bool BF16>
 __device__ __forceinline__ const uint8_t *stacked_row(const AcceptParams &p, int rw) {
-  const size_t esz = p.bf16 ? 2 : 4;
+  constexpr size_t esz = BF16 ? 2 : 4;
   const int n_t = p.NB * (p.K + 1);
   if (rw < n_t) return (const uint8_t *)p.target + (size_t)rw * p.V * esz;
   return (const uint8_t *)p.draft + (size_t)(rw - n_t) * p.V * esz;
 }
 
 // ---------------------------------------------------------------------------------------------
-// stats: grid (n_chunks, rows)
+// stats: grid (n_chunks, rows); a slice is 256 lanes x 8 16-byte loads (16384 bf16 / 8192 fp32 logits)
 // ---------------------------------------------------------------------------------------------
+template <bool BF16>
+struct StatsShape {
+  static constexpr int kLoads = 8;
+  static constexpr int kPerVec = BF16 ? 8 : 4;
+  static constexpr int kPer = kLoads * kPerVec;  // logits per lane
+  static constexpr int kSlice = kThreads * kPer;
+};
+
 template <bool BF16, bool VEC>
 __global__ __launch_bounds__(kThreads) void accept_stats_kernel(const AcceptParams p) {
+  using Sh = StatsShape<BF16>;
   __shared__ float red[2][kThreads / 64];
   const int c = blockIdx.x, rw = blockIdx.y;
   const int tid = threadIdx.x;
-  const uint8_t *row = stacked_row(p, rw);
-  const int v0 = c * p.chunk;
-  const int v1 = min(p.V, v0 + p.chunk);
+  const uint8_t *row = stacked_row<BF16>(p, rw);
+  const int v0 = c * Sh::kSlice;
+  const int v1 = min(p.V, v0 + Sh::kSlice);
 
-  float x[kPer];
+  float x[Sh::kPer];
   if constexpr (VEC) {
-    constexpr int per_vec = BF16 ? 8 : 4;           // elements per 16-byte load
-    constexpr int n_vec = kPer / per_vec;           // loads per thread
+    u32x4 w[Sh::kLoads];
 #pragma unroll
-    for (int e = 0; e < n_vec; ++e) {
-      const int v = v0 + (e * kThreads + tid) * per_vec;   // consecutive lanes read consecutive 16 B
-      u32x4 w = {0, 0, 0, 0};
-      const bool in = v < v1;                       // V % per_vec == 0 on this path, so a vector is all-in or all-out
-      if (in) w = *(const u32x4 *)(row + (size_t)v * (BF16 ? 2 : 4));
+    for (int e = 0; e < Sh::kLoads; ++e) {
+      const int v = v0 + (e * kThreads + tid) * Sh::kPerVec;  // consecutive lanes read consecutive 16 B
+      // V % kPerVec == 0 on this path, so a vector is all-in or all-out; out-of-range lanes re-read the row start
+      w[e] = *(const u32x4 *)(row + (size_t)(v < v1 ? v : 0) * (BF16 ? 2 : 4));
+    }
+#pragma unroll
+    for (int e = 0; e < Sh::kLoads; ++e) {
+      const bool in = v0 + (e * kThreads + tid) * Sh::kPerVec < v1;
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
+        const uint32_t word = w[e][k];
         if constexpr (BF16) {
-          x[e * 8 + 2 * k] = in ? bf16_lo(w[k]) : -INFINITY;
-          x[e * 8 + 2 * k + 1] = in ? bf16_hi(w[k]) : -INFINITY;
+          x[e * 8 + 2 * k] = in ? bf16_lo(word) : -INFINITY;
+          x[e * 8 + 2 * k + 1] = in ? bf16_hi(word) : -INFINITY;
         } else {
-          x[e * 4 + k] = in ? as_f32(w[k]) : -INFINITY;
+          x[e * 4 + k] = in ? as_f32(word) : -INFINITY;
         }
       }
     }
   } else {
 #pragma unroll
-    for (int e = 0; e < kPer; ++e) {
+    for (int e = 0; e < Sh::kPer; ++e) {
       const int v = v0 + e * kThreads + tid;
-      x[e] = v < v1 ? load_logit(row, v, BF16) : -INFINITY;
+      x[e] = v < v1 ? load_logit<BF16>(row, v) : -INFINITY;
     }
   }
-  float m = -INFINITY;
+  float m = x[0];
 #pragma unroll
-  for (int e = 0; e < kPer; ++e) m = fmaxf(m, x[e]);
+  for (int e = 1; e < Sh::kPer; ++e) m = fmaxf(m, x[e]);
   m = wave_max(m);
   if ((tid & 63) == 0) red[0][tid >> 6] = m;
   __syncthreads();
-  m = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));   // slice maximum (finite: slice not empty)
+  m = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));  // slice maximum (finite: slice not empty)
   const float cm = -m * p.inv_temp_log2;
   float s = 0.f;
 #pragma unroll
-  for (int e = 0; e < kPer; ++e) s += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], p.inv_temp_log2, cm));
+  for (int e = 0; e < Sh::kPer; ++e) s += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], p.inv_temp_log2, cm));
   s = wave_sum(s);
   if ((tid & 63) == 0) red[1][tid >> 6] = s;
   __syncthreads();
@@ -128,145 +145,174 @@ __global__ __launch_bounds__(kThreads) void accept_stats_kernel(const AcceptPara
   }
 }
 
-// fold the slice statistics of one row: maximum and sum 2^((x-max)*c)
-__device__ __forceinline__ void fold_row(const AcceptParams &p, int rw, float &m_out, float &z_out) {
+// Fold the slice statistics of one row into its maximum and sum 2^((x-max)*c); called by a whole wavefront, lanes
+// over slices, the same result in every lane.
+__device__ __forceinline__ void wave_fold_row(const AcceptParams &p, int rw, int lane, float &m_out, float &z_out) {
   const float *st = p.stats + (size_t)rw * p.n_chunks * 2;
   float m = -INFINITY;
-  for (int c = 0; c < p.n_chunks; ++c) m = fmaxf(m, st[2 * c]);
+  for (int c = lane; c < p.n_chunks; c += 64) m = fmaxf(m, st[2 * c]);
+  m = wave_max(m);
   float z = 0.f;
-  for (int c = 0; c < p.n_chunks; ++c) z += st[2 * c + 1] * __builtin_amdgcn_exp2f((st[2 * c] - m) * p.inv_temp_log2);
+  for (int c = lane; c < p.n_chunks; c += 64)
+    z += st[2 * c + 1] * __builtin_amdgcn_exp2f((st[2 * c] - m) * p.inv_temp_log2);
   m_out = m;
-  z_out = z;
-}
-
-// ---------------------------------------------------------------------------------------------
-// decide: grid NB, one wavefront; lane i handles drafted position i (looping when K > 64)
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void accept_decide_kernel(const AcceptParams p) {
-  const int nb = blockIdx.x, lane = threadIdx.x;
-  const int n_t = p.NB * (p.K + 1);
-  int first_reject = p.K;
-  for (int i0 = 0; i0 < p.K; i0 += 64) {
-    const int i = i0 + lane;
-    bool reject = false;
-    if (i < p.K) {
-      const int rt = nb * (p.K + 1) + i, rd = n_t + nb * p.K + i;
-      float mp, zp, mq, zq;
-      fold_row(p, rt, mp, zp);
-      fold_row(p, rd, mq, zq);
-      const int x = p.tokens[(size_t)nb * p.K + i];
-      const float tx = load_logit(p.target, (size_t)rt * p.V + x, p.bf16);
-      const float dx = load_logit(p.draft, (size_t)(rd - n_t) * p.V + x, p.bf16);
-      const float px = __builtin_amdgcn_exp2f((tx - mp) * p.inv_temp_log2) / zp;
-      const float qx = __builtin_amdgcn_exp2f((dx - mq) * p.inv_temp_log2) / zq;
-      const float u = p.u_accept[(size_t)nb * p.K + i];
-      reject = !(u * qx < px);
-      if (p.ratio) p.ratio[(size_t)nb * p.K + i] = px / qx;
-    }
-    const unsigned long long mask = __ballot(reject);
-    if (mask && first_reject == p.K) first_reject = i0 + __builtin_ctzll(mask);
-  }
-  if (lane == 0) {
-    const int n = first_reject;
-    p.accepted_len[nb] = n;
-    p.n_acc[nb] = n;
-    // exact maxima of the resampling rows: target row n, draft row n (unused when n == K)
-    float m, z;
-    fold_row(p, nb * (p.K + 1) + n, m, z);
-    p.rowmax[2 * nb] = m;
-    if (n < p.K) {
-      fold_row(p, n_t + nb * p.K + n, m, z);
-      p.rowmax[2 * nb + 1] = m;
-    } else {
-      p.rowmax[2 * nb + 1] = 0.f;
-    }
-  }
+  z_out = wave_sum(z);
 }
 
 // fp64 probability mass (unnormalised) of one logit: exp(x/T - max/T)
-__device__ __forceinline__ double mass64(float x, double mx_over_t, double temperature) {
-  return exp((double)x / temperature - mx_over_t);
+__device__ __forceinline__ double mass64(float x, double mx_over_t, double inv_temp) {
+  return exp((double)x * inv_temp - mx_over_t);
 }
 
 // ---------------------------------------------------------------------------------------------
-// zsum: grid (n_chunks, NB, 2): fp64 sum exp(z - max) of one slice of a resampling row
+// decide: grid (n_fine, NB).  Accepted length of the branch (every workgroup derives it; slice 0 publishes it),
+// then this slice's share of the fp64 normalisers of the resampling rows.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void accept_zsum_kernel(const AcceptParams p) {
-  __shared__ double red[kThreads / 64];
-  const int c = blockIdx.x, nb = blockIdx.y, which = blockIdx.z;
-  const int tid = threadIdx.x;
-  const int n = p.n_acc[nb];
-  double total = 0.0;
-  if (!(which == 1 && n == p.K)) {
-    const size_t rowi = which == 0 ? (size_t)nb * (p.K + 1) + n : (size_t)nb * p.K + n;
-    const void *base = which == 0 ? p.target : p.draft;
-    const double mt = (double)p.rowmax[2 * nb + which] / p.temperature;
-    const int v0 = c * p.chunk, v1 = min(p.V, v0 + p.chunk);
-    double s = 0.0;
-    // thread t owns the kPer consecutive tokens v0 + t*kPer ..: the same partition as the pick kernel
-    for (int e = 0; e < kPer; ++e) {
-      const int v = v0 + tid * kPer + e;
-      if (v < v1) s += mass64(load_logit(base, rowi * p.V + v, p.bf16), mt, p.temperature);
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void accept_decide_kernel(const AcceptParams p) {
+  constexpr int kPass = 64;                       // drafted positions examined per pass
+  __shared__ float sm[2][kPass], sz[2][kPass];    // [target|draft][position in pass]: folded row statistics
+  __shared__ float s_top[2];                      // maxima of the resampling rows
+  __shared__ int s_first;
+  __shared__ double red[2][kThreads / 64];
+  const int c = blockIdx.x, nb = blockIdx.y, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int n_t = p.NB * (p.K + 1);
+  if (tid == 0) s_first = p.K;
+  __syncthreads();
+  int i0 = 0;
+  for (; i0 < p.K; i0 += kPass) {   // a later pass cannot lower the first rejection found in an earlier one
+    const int cnt = min(kPass, p.K - i0);
+    for (int slot = wave; slot < 2 * cnt; slot += kThreads / 64) {   // wavefront per row
+      const int which = slot >= cnt, j = slot - which * cnt;
+      const int rw = which ? n_t + nb * p.K + i0 + j : nb * (p.K + 1) + i0 + j;
+      float m, z;
+      wave_fold_row(p, rw, lane, m, z);
+      if (lane == 0) sm[which][j] = m, sz[which][j] = z;
     }
-    s = wave_sum(s);
-    if ((tid & 63) == 0) red[tid >> 6] = s;
     __syncthreads();
-    total = (red[0] + red[1]) + (red[2] + red[3]);
+    if (tid < cnt) {
+      const int i = i0 + tid;
+      const int x = p.tokens[(size_t)nb * p.K + i];
+      const float tx = load_logit<BF16>(p.target, ((size_t)nb * (p.K + 1) + i) * p.V + x);
+      const float dx = load_logit<BF16>(p.draft, ((size_t)nb * p.K + i) * p.V + x);
+      const float px = __builtin_amdgcn_exp2f((tx - sm[0][tid]) * p.inv_temp_log2) / sz[0][tid];
+      const float qx = __builtin_amdgcn_exp2f((dx - sm[1][tid]) * p.inv_temp_log2) / sz[1][tid];
+      const float u = p.u_accept[(size_t)nb * p.K + i];
+      if (!(u * qx < px)) atomicMin(&s_first, i);
+      if (c == 0 && p.ratio) p.ratio[(size_t)nb * p.K + i] = px / qx;
+    }
+    __syncthreads();
+    if (s_first < p.K) break;  // uniform: the first rejection lies in this pass
   }
-  if (tid == 0) p.zsum[((size_t)nb * 2 + which) * p.n_chunks + c] = total;
+  const int n = s_first;
+  // exact maxima of the resampling rows: target row n and draft row n (both folded in the pass that found n), or
+  // target row K alone when everything was accepted
+  if (n < p.K) {
+    if (tid == 0) s_top[0] = sm[0][n - i0], s_top[1] = sm[1][n - i0];
+  } else if (wave == 0) {
+    float m, z;
+    wave_fold_row(p, nb * (p.K + 1) + p.K, lane, m, z);
+    if (lane == 0) s_top[0] = m, s_top[1] = 0.f;
+  }
+  __syncthreads();
+  const float mt = s_top[0], mq = s_top[1];
+  if (c == 0 && tid == 0) {
+    p.accepted_len[nb] = n;
+    p.n_acc[nb] = n;
+    p.rowmax[2 * nb] = mt;
+    p.rowmax[2 * nb + 1] = mq;
+  }
+  const int v0 = c * kFine, v1 = min(p.V, v0 + kFine);
+  const size_t trow = ((size_t)nb * (p.K + 1) + n) * p.V;
+  const size_t drow = ((size_t)nb * p.K + (n < p.K ? n : 0)) * p.V;
+  const double mt_t = (double)mt * p.inv_temp, mq_t = (double)mq * p.inv_temp;
+  double st = 0.0, sq = 0.0;
+#pragma unroll
+  for (int e = 0; e < kFinePer; ++e) {
+    const int v = v0 + tid * kFinePer + e;
+    if (v < v1) {
+      st += mass64(load_logit<BF16>(p.target, trow + v), mt_t, p.inv_temp);
+      if (n < p.K) sq += mass64(load_logit<BF16>(p.draft, drow + v), mq_t, p.inv_temp);
+    }
+  }
+  st = wave_sum(st);
+  sq = wave_sum(sq);
+  if ((tid & 63) == 0) red[0][tid >> 6] = st, red[1][tid >> 6] = sq;
+  __syncthreads();
+  if (tid == 0) {
+    p.zsum[((size_t)nb * 2 + 0) * p.n_fine + c] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+    p.zsum[((size_t)nb * 2 + 1) * p.n_fine + c] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+  }
 }
 
-__device__ __forceinline__ double fold64(const double *v, int n) {
-  double s = 0.0;
-  for (int c = 0; c < n; ++c) s += v[c];
-  return s;
+constexpr int kMaxFine = 1024;   // fine slices per row the fp64 kernels can stage in LDS (vocab <= 2M)
+
+// Sum of n <= kMaxFine doubles in index order, the same value in every lane of the workgroup: all lanes stage the
+// terms in LDS, lane 0 adds them in order.
+__device__ __forceinline__ double fold64_block(const double *v, int n, double *buf, double *slot) {
+  for (int c = threadIdx.x; c < n; c += kThreads) buf[c] = v[c];
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double s = 0.0;
+    for (int c = 0; c < n; ++c) s += buf[c];
+    *slot = s;
+  }
+  __syncthreads();
+  return *slot;
 }
 
-// residual mass and target mass of token v of branch nb (position n), fp64
+// residual mass and target mass of the tokens of branch nb at position n, fp64
+template <bool BF16>
 struct ResidCtx {
   const void *target, *draft;
   size_t trow, drow;
-  double mt, mq, zt, zq, temperature;
-  bool has_draft, bf16;
+  double mt, mq, zt, zq, inv_temp;
+  bool has_draft;
   __device__ __forceinline__ void eval(int v, double &r, double &pm) const {
-    pm = mass64(load_logit(target, trow + v, bf16), mt, temperature) / zt;
+    pm = mass64(load_logit<BF16>(target, trow + v), mt, inv_temp) / zt;
     r = pm;
     if (has_draft) {
-      const double qm = mass64(load_logit(draft, drow + v, bf16), mq, temperature) / zq;
+      const double qm = mass64(load_logit<BF16>(draft, drow + v), mq, inv_temp) / zq;
       r = pm - qm;
       if (r < 0.0) r = 0.0;
     }
   }
 };
 
-__device__ __forceinline__ ResidCtx make_ctx(const AcceptParams &p, int nb) {
-  ResidCtx x;
+template <bool BF16>
+__device__ __forceinline__ ResidCtx<BF16> make_ctx(const AcceptParams &p, int nb, double *buf, double *slots) {
+  ResidCtx<BF16> x;
   const int n = p.n_acc[nb];
   x.target = p.target;
   x.draft = p.draft;
   x.trow = ((size_t)nb * (p.K + 1) + n) * p.V;
   x.has_draft = n < p.K;
   x.drow = x.has_draft ? ((size_t)nb * p.K + n) * p.V : 0;
-  x.temperature = p.temperature;
-  x.mt = (double)p.rowmax[2 * nb] / p.temperature;
-  x.mq = (double)p.rowmax[2 * nb + 1] / p.temperature;
-  x.zt = fold64(p.zsum + ((size_t)nb * 2 + 0) * p.n_chunks, p.n_chunks);
-  x.zq = x.has_draft ? fold64(p.zsum + ((size_t)nb * 2 + 1) * p.n_chunks, p.n_chunks) : 1.0;
-  x.bf16 = p.bf16 != 0;
+  x.inv_temp = p.inv_temp;
+  x.mt = (double)p.rowmax[2 * nb] * p.inv_temp;
+  x.mq = (double)p.rowmax[2 * nb + 1] * p.inv_temp;
+  x.zt = fold64_block(p.zsum + ((size_t)nb * 2 + 0) * p.n_fine, p.n_fine, buf, slots);
+  x.zq = fold64_block(p.zsum + ((size_t)nb * 2 + 1) * p.n_fine, p.n_fine, buf, slots + 1);
+  if (!x.has_draft) x.zq = 1.0;
   return x;
 }
 
 // ---------------------------------------------------------------------------------------------
-// resid: grid (n_chunks, NB): fp64 slice sums of the residual and of p
+// resid: grid (n_fine, NB): per-lane and per-slice fp64 sums of the residual and of p
 // ---------------------------------------------------------------------------------------------
+template <bool BF16>
 __global__ __launch_bounds__(kThreads) void accept_resid_kernel(const AcceptParams p) {
+  __shared__ double slots[2];
+  __shared__ double buf[kMaxFine];
   __shared__ double red[2][kThreads / 64];
   const int c = blockIdx.x, nb = blockIdx.y, tid = threadIdx.x;
-  const ResidCtx ctx = make_ctx(p, nb);
-  const int v0 = c * p.chunk, v1 = min(p.V, v0 + p.chunk);
+  const ResidCtx<BF16> ctx = make_ctx<BF16>(p, nb, buf, slots);
+  const int v0 = c * kFine, v1 = min(p.V, v0 + kFine);
   double sr = 0.0, sp = 0.0;
-  for (int e = 0; e < kPer; ++e) {
-    const int v = v0 + tid * kPer + e;
+#pragma unroll
+  for (int e = 0; e < kFinePer; ++e) {
+    const int v = v0 + tid * kFinePer + e;
     if (v < v1) {
       double r, pm;
       ctx.eval(v, r, pm);
@@ -274,103 +320,149 @@ __global__ __launch_bounds__(kThreads) void accept_resid_kernel(const AcceptPara
       sp += pm;
     }
   }
+  double *ls = p.lane_sums + (((size_t)nb * p.n_fine + c) * kThreads + tid) * 2;
+  ls[0] = sr;
+  ls[1] = sp;
   sr = wave_sum(sr);
   sp = wave_sum(sp);
   if ((tid & 63) == 0) red[0][tid >> 6] = sr, red[1][tid >> 6] = sp;
   __syncthreads();
   if (tid == 0) {
-    p.rsum[((size_t)nb * 2 + 0) * p.n_chunks + c] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
-    p.rsum[((size_t)nb * 2 + 1) * p.n_chunks + c] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    p.rsum[((size_t)nb * 2 + 0) * p.n_fine + c] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+    p.rsum[((size_t)nb * 2 + 1) * p.n_fine + c] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
   }
 }
 
 // ---------------------------------------------------------------------------------------------
 // pick: grid NB
 // ---------------------------------------------------------------------------------------------
+template <bool BF16>
 __global__ __launch_bounds__(kThreads) void accept_pick_kernel(const AcceptParams p) {
-  __shared__ double scan[kThreads];
-  __shared__ int best;
-  __shared__ int last_mass;
+  __shared__ double slots[2];
+  __shared__ double buf[kMaxFine];
+  __shared__ double s_before;
+  __shared__ double wave_tot[kThreads / 64];
+  __shared__ int s_slice, s_lane, s_last_lane, s_mode;
   const int nb = blockIdx.x, tid = threadIdx.x;
-  const ResidCtx ctx = make_ctx(p, nb);
-  const double *rs = p.rsum + ((size_t)nb * 2 + 0) * p.n_chunks;
-  double S = fold64(rs, p.n_chunks);
-  bool use_p = false;
-  if (!(S > 0.0)) {  // the residual has no mass (only through rounding): draw from p_n itself
-    rs = p.rsum + ((size_t)nb * 2 + 1) * p.n_chunks;
-    S = fold64(rs, p.n_chunks);
-    use_p = true;
+  const int lane = tid & 63, wave = tid >> 6;
+  const ResidCtx<BF16> ctx = make_ctx<BF16>(p, nb, buf, slots);
+  const double u = (double)p.u_sample[nb];
+  // total residual mass; without mass (rounding only) the draw is from p_n itself
+  int mode = 0;
+  double S = fold64_block(p.rsum + ((size_t)nb * 2 + 0) * p.n_fine, p.n_fine, buf, slots);
+  if (!(S > 0.0)) {   // uniform
+    mode = 1;
+    S = fold64_block(p.rsum + ((size_t)nb * 2 + 1) * p.n_fine, p.n_fine, buf, slots);
   }
-  const double thr = (double)p.u_sample[nb] * S;
-  // slice in which the running sum first exceeds thr
-  int cs = p.n_chunks - 1;
-  double before = 0.0;
-  {
-    double acc = 0.0;
-    for (int c = 0; c < p.n_chunks; ++c) {
-      if (acc + rs[c] > thr) {
+  const double thr = u * S;
+  if (tid == 0) {
+    // slice in which the running sum (buf still holds the slice sums) first exceeds thr; the last slice with mass
+    // if rounding hides the crossing
+    int cs = -1, last = 0;
+    double acc = 0.0, before = 0.0, before_last = 0.0;
+    for (int c = 0; c < p.n_fine; ++c) {
+      const double r = buf[c];
+      if (r > 0.0) last = c, before_last = acc;
+      if (acc + r > thr) {
         cs = c;
         before = acc;
         break;
       }
-      acc += rs[c];
-      if (c == p.n_chunks - 1) before = acc - rs[c];
+      acc += r;
     }
+    if (cs < 0) cs = last, before = before_last;
+    s_before = before, s_slice = cs, s_lane = INT_MAX, s_last_lane = -1;
   }
-  const int v0 = cs * p.chunk, v1 = min(p.V, v0 + p.chunk);
-  double mass[kPer];
-  double local = 0.0;
-  int my_last = -1;
-#pragma unroll
-  for (int e = 0; e < kPer; ++e) {
-    const int v = v0 + tid * kPer + e;
-    double r = 0.0, pm = 0.0;
-    if (v < v1) ctx.eval(v, r, pm);
-    mass[e] = use_p ? pm : r;
-    local += mass[e];
-    if (mass[e] > 0.0) my_last = v;
-  }
-  if (tid == 0) best = INT_MAX, last_mass = -1;
-  scan[tid] = local;
   __syncthreads();
-  // exclusive prefix of the per-thread sums, in token order (serial per thread: 256 adds, fixed order)
-  double run = before;
-  for (int t = 0; t < tid; ++t) run += scan[t];
-  int found = INT_MAX;
+  const int cs = s_slice;
+  // lane of that slice whose 8 tokens contain the crossing: inclusive scan of the stored per-lane sums
+  const double mine = p.lane_sums[(((size_t)nb * p.n_fine + cs) * kThreads + tid) * 2 + mode];
+  double incl = mine;
 #pragma unroll
-  for (int e = 0; e < kPer; ++e) {
-    run += mass[e];
-    if (found == INT_MAX && run > thr && mass[e] > 0.0) found = v0 + tid * kPer + e;
+  for (int off = 1; off < 64; off <<= 1) {
+    const double up = __shfl_up(incl, off);
+    if (lane >= off) incl += up;
   }
-  if (found != INT_MAX) atomicMin(&best, found);
-  if (my_last >= 0) atomicMax(&last_mass, my_last);
+  if (lane == 63) wave_tot[wave] = incl;
   __syncthreads();
-  if (tid == 0) p.next_token[nb] = best != INT_MAX ? best : last_mass;
-}
-
-template <bool BF16>
-void launch_stats(const AcceptParams &p, bool vec, hipStream_t stream) {
-  const dim3 grid(p.n_chunks, p.NB * (2 * p.K + 1));
-  if (vec)
-    hipLaunchKernelGGL((accept_stats_kernel<BF16, true>), grid, dim3(kThreads), 0, stream, p);
-  else
-    hipLaunchKernelGGL((accept_stats_kernel<BF16, false>), grid, dim3(kThreads), 0, stream, p);
+  double base = s_before;
+  for (int w = 0; w < wave; ++w) base += wave_tot[w];
+  const double hi = base + incl, lo = hi - mine;
+  if (mine > 0.0) {
+    atomicMax(&s_last_lane, tid);
+    if (hi > thr && !(lo > thr)) atomicMin(&s_lane, tid);
+  }
+  __syncthreads();
+  const int pick_lane = s_lane != INT_MAX ? s_lane : s_last_lane;
+  if (tid == pick_lane) {
+    const int v0 = cs * kFine + tid * kFinePer, v1 = min(p.V, cs * kFine + kFine);
+    double run = lo;
+    int tok = -1, last = -1;
+    for (int e = 0; e < kFinePer; ++e) {
+      const int v = v0 + e;
+      if (v >= v1) break;
+      double r, pm;
+      ctx.eval(v, r, pm);
+      const double mass = mode ? pm : r;
+      run += mass;
+      if (mass > 0.0) {
+        last = v;
+        if (tok < 0 && run > thr) tok = v;
+      }
+    }
+    p.next_token[nb] = tok >= 0 ? tok : last;
+  }
 }
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
+template <bool BF16>
+hipError_t launch_typed(const AcceptParams &p, hipStream_t stream) {
+  const bool vec = ((size_t)p.V * (BF16 ? 2 : 4)) % 16 == 0;
+  {
+    ProfileScope scope(SLOT_ACCEPT_STATS, stream);
+    const dim3 grid(p.n_chunks, p.NB * (2 * p.K + 1));
+    if (vec)
+      hipLaunchKernelGGL((accept_stats_kernel<BF16, true>), grid, dim3(kThreads), 0, stream, p);
+    else
+      hipLaunchKernelGGL((accept_stats_kernel<BF16, false>), grid, dim3(kThreads), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  {
+    ProfileScope scope(SLOT_ACCEPT_DECIDE, stream);
+    hipLaunchKernelGGL(accept_decide_kernel<BF16>, dim3(p.n_fine, p.NB), dim3(kThreads), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  {
+    ProfileScope scope(SLOT_ACCEPT_RESID, stream);
+    hipLaunchKernelGGL(accept_resid_kernel<BF16>, dim3(p.n_fine, p.NB), dim3(kThreads), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  {
+    ProfileScope scope(SLOT_ACCEPT_PICK, stream);
+    hipLaunchKernelGGL(accept_pick_kernel<BF16>, dim3(p.NB), dim3(kThreads), 0, stream, p);
+    return hipGetLastError();
+  }
+}
+
 }  // namespace
 
-size_t accept_workspace_bytes(int NB, int K, int V, int *chunk_out, int *n_chunks_out) {
-  const int n_chunks = (V + kChunk - 1) / kChunk;
-  if (chunk_out) *chunk_out = kChunk;
+size_t accept_workspace_bytes(int NB, int K, int V, bool bf16, int *n_chunks_out, int *n_fine_out) {
+  const int slice = bf16 ? StatsShape<true>::kSlice : StatsShape<false>::kSlice;
+  const int n_chunks = (V + slice - 1) / slice;
+  const int n_fine = (V + kFine - 1) / kFine;
   if (n_chunks_out) *n_chunks_out = n_chunks;
+  if (n_fine_out) *n_fine_out = n_fine;
   size_t b = 0;
   b += align_up((size_t)NB * (2 * K + 1) * n_chunks * 2 * sizeof(float));  // stats
   b += align_up((size_t)NB * sizeof(int32_t));                             // n_acc
-  b += align_up((size_t)NB * 2 * n_chunks * sizeof(double));               // zsum
-  b += align_up((size_t)NB * 2 * n_chunks * sizeof(double));               // rsum
+  b += align_up((size_t)NB * 2 * n_fine * sizeof(double));                 // zsum
+  b += align_up((size_t)NB * 2 * n_fine * sizeof(double));                 // rsum
   b += align_up((size_t)NB * 2 * sizeof(float));                           // rowmax
+  b += align_up((size_t)NB * n_fine * kThreads * 2 * sizeof(double));      // lane_sums
   return b;
 }
 
@@ -381,44 +473,16 @@ void accept_carve_workspace(AcceptParams &p, void *ws) {
   p.n_acc = (int32_t *)at;
   at += align_up((size_t)p.NB * sizeof(int32_t));
   p.zsum = (double *)at;
-  at += align_up((size_t)p.NB * 2 * p.n_chunks * sizeof(double));
+  at += align_up((size_t)p.NB * 2 * p.n_fine * sizeof(double));
   p.rsum = (double *)at;
-  at += align_up((size_t)p.NB * 2 * p.n_chunks * sizeof(double));
+  at += align_up((size_t)p.NB * 2 * p.n_fine * sizeof(double));
   p.rowmax = (float *)at;
+  at += align_up((size_t)p.NB * 2 * sizeof(float));
+  p.lane_sums = (double *)at;
 }
 
 hipError_t launch_accept(const AcceptParams &p, hipStream_t stream) {
-  const size_t esz = p.bf16 ? 2 : 4;
-  const bool vec = ((size_t)p.V * esz) % 16 == 0;
-  {
-    ProfileScope scope(SLOT_ACCEPT_STATS, stream);
-    if (p.bf16)
-      launch_stats<true>(p, vec, stream);
-    else
-      launch_stats<false>(p, vec, stream);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
-  {
-    ProfileScope scope(SLOT_ACCEPT_DECIDE, stream);
-    hipLaunchKernelGGL(accept_decide_kernel, dim3(p.NB), dim3(64), 0, stream, p);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
-  {
-    ProfileScope scope(SLOT_ACCEPT_RESID, stream);
-    hipLaunchKernelGGL(accept_zsum_kernel, dim3(p.n_chunks, p.NB, 2), dim3(kThreads), 0, stream, p);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(accept_resid_kernel, dim3(p.n_chunks, p.NB), dim3(kThreads), 0, stream, p);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
-  {
-    ProfileScope scope(SLOT_ACCEPT_PICK, stream);
-    hipLaunchKernelGGL(accept_pick_kernel, dim3(p.NB), dim3(kThreads), 0, stream, p);
-    return hipGetLastError();
-  }
+  return p.bf16 ? launch_typed<true>(p, stream) : launch_typed<false>(p, stream);
 }
 
 }  // namespace la

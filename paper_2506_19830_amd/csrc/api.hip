@@ -258,6 +258,7 @@ static la_status validate_accept(const la_accept_desc *d) {
     return d->logits_dtype == LA_FP8_E4M3 ? LA_ERR_UNSUPPORTED : LA_ERR_INVALID_ARG;
   if (!(d->temperature > 0.f) || !isfinite(d->temperature)) return LA_ERR_INVALID_ARG;
   if ((int64_t)d->num_branches * (2 * (int64_t)d->num_draft + 1) > 65535) return LA_ERR_UNSUPPORTED;  // grid.y
+  if (d->vocab > (1 << 21)) return LA_ERR_UNSUPPORTED;  // fine slices of one row are staged in LDS
   return LA_OK;
 }
 
@@ -265,7 +266,8 @@ la_status la_spec_accept_workspace(const la_accept_desc *desc, size_t *bytes_out
   la_status st = validate_accept(desc);
   if (st != LA_OK) return st;
   if (!bytes_out) return LA_ERR_INVALID_ARG;
-  *bytes_out = accept_workspace_bytes(desc->num_branches, desc->num_draft, desc->vocab, nullptr, nullptr);
+  *bytes_out = accept_workspace_bytes(desc->num_branches, desc->num_draft, desc->vocab,
+                                      desc->logits_dtype == LA_BF16, nullptr, nullptr);
   return LA_OK;
 }
 
@@ -280,7 +282,8 @@ la_status la_spec_accept(const la_accept_desc *desc, const void *target_logits, 
   if (!aligned16(target_logits) || !aligned16(draft_logits) || !aligned16(workspace)) return LA_ERR_INVALID_ARG;
   AcceptParams p;
   memset(&p, 0, sizeof p);
-  const size_t need = accept_workspace_bytes(desc->num_branches, desc->num_draft, desc->vocab, &p.chunk, &p.n_chunks);
+  const size_t need = accept_workspace_bytes(desc->num_branches, desc->num_draft, desc->vocab,
+                                             desc->logits_dtype == LA_BF16, &p.n_chunks, &p.n_fine);
   if (!workspace || workspace_bytes < need) return LA_ERR_WORKSPACE_TOO_SMALL;
   p.target = target_logits, p.draft = draft_logits, p.tokens = draft_tokens;
   p.u_accept = u_accept, p.u_sample = u_sample;
@@ -288,8 +291,7 @@ la_status la_spec_accept(const la_accept_desc *desc, const void *target_logits, 
   p.NB = desc->num_branches, p.K = desc->num_draft, p.V = desc->vocab;
   p.bf16 = desc->logits_dtype == LA_BF16;
   p.inv_temp_log2 = 1.44269504088896340736f / desc->temperature;
-  p.temperature = (double)desc->temperature;
-  p.inv_temp = 1.0 / p.temperature;
+  p.inv_temp = 1.0 / (double)desc->temperature;
   accept_carve_workspace(p, workspace);
   return launch_accept(p, (hipStream_t)hip_stream) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }

@@ -74,20 +74,20 @@ struct AcceptParams {
   int32_t *accepted_len, *next_token;
   float *ratio;                // [NB, K] or null
   int NB, K, V, bf16;
-  int chunk;                   // vocabulary elements per workgroup slice
-  int n_chunks;                // ceil(V / chunk)
+  int n_chunks;                // slices of the fp32 statistics pass per row
+  int n_fine;                  // 2048-token slices of the fp64 resampling path per row
   float inv_temp_log2;         // log2(e) / T
-  double inv_temp;             // 1 / T   (fp64 resampling path divides by T exactly as T)
-  double temperature;
+  double inv_temp;             // 1 / T
   // workspace
-  float *stats;                // [rows = NB*(2K+1), n_chunks, 2]  (max, sum 2^(z-max)) in log2 units
+  float *stats;                // [rows = NB*(2K+1), n_chunks, 2]  (exact max, sum 2^((x-max)*log2e/T))
   int32_t *n_acc;              // [NB]
-  double *zsum;                // [NB, 2, n_chunks]  fp64 sum exp(z - max) of the resampling rows
-  double *rsum;                // [NB, 2, n_chunks]  fp64 chunk sums of the residual and of p
+  double *zsum;                // [NB, 2, n_fine]  fp64 sum exp(z - max) of the resampling rows
+  double *rsum;                // [NB, 2, n_fine]  fp64 slice sums of the residual and of p
   float *rowmax;               // [NB, 2] exact row maxima (raw logits) of the resampling rows
+  double *lane_sums;           // [NB, n_fine, 256, 2] per-lane sums of the residual and of p
 };
 
-size_t accept_workspace_bytes(int NB, int K, int V, int *chunk_out, int *n_chunks_out);
+size_t accept_workspace_bytes(int NB, int K, int V, bool bf16, int *n_chunks_out, int *n_fine_out);
 void accept_carve_workspace(AcceptParams &p, void *ws);
 hipError_t launch_accept(const AcceptParams &p, hipStream_t stream);
 
