@@ -342,7 +342,7 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(const AcceptParam
   __shared__ double buf[kMaxFine];
   __shared__ double s_before;
   __shared__ double wave_tot[kThreads / 64];
-  __shared__ int s_slice, s_lane, s_last_lane, s_mode;
+  __shared__ int s_slice, s_lane, s_last_lane;
   const int nb = blockIdx.x, tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const ResidCtx<BF16> ctx = make_ctx<BF16>(p, nb, buf, slots);

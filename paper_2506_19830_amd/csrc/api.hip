@@ -49,12 +49,11 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, Attn
   la_status st = validate_desc(d);
   if (st != LA_OK) return st;
   if (!prefix_lens_host) return LA_ERR_INVALID_ARG;
-  int64_t max_p = 0, sum_p = 0;
+  int64_t max_p = 0;
   for (int b = 0; b < d->num_requests; ++b) {
     const int64_t P = prefix_lens_host[b];
     if (P < 0 || P > (int64_t)d->max_blocks_per_request * d->block_size) return LA_ERR_INVALID_ARG;
     max_p = P > max_p ? P : max_p;
-    sum_p += P;
   }
   memset(plan, 0, sizeof *plan);
   const bool all_f32 =

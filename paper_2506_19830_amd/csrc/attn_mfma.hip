@@ -291,7 +291,7 @@ __device__ __forceinline__ void rescale(RowState<RB> &st, const float (&alpha)[R
   }
 }
 
-// p = 2^(s*cseg - m + voff) for one 32-key block, rounded to bf16 pairs; returns the row sums of the rounded values.
+// p = 2^(s*cseg - m + voff) for one 32-key block, rounded to bf16 pairs; also the fp32 row sums.
 template <int RB>
 __device__ __forceinline__ void block_probs(const f32x16 (&s)[RB], const RowState<RB> &st, float cseg, float voff,
                                             uint32_t (&pb)[RB][8], float (&sum)[RB]) {
@@ -309,10 +309,10 @@ __device__ __forceinline__ void block_probs(const f32x16 (&s)[RB], const RowStat
       const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[rb][j], cseg, off));
       const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[rb][j + 1], cseg, off));
 #endif
-      const uint32_t pk = pack_bf16(p0, p1);
-      pb[rb][j >> 1] = pk;
-      acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), __builtin_bit_cast(bf16x2, 0x3F803F80u),
-                                            acc, false);
+      pb[rb][j >> 1] = pack_bf16(p0, p1);
+      // (a v_dot2c_f32_bf16 on the packed pair would sum the rounded values in one instruction, but on gfx950 it
+      // stalls against the MFMAs in flight: measured slower than the two adds)
+      acc += p0 + p1;
     }
     sum[rb] = acc;
   }
