@@ -35,6 +35,8 @@ def parse_args():
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 2..5 (default 5, the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--kv-split-tokens", type=int, default=0)
+    ap.add_argument("--branch-len", type=int, default=None,
+                    help="override L, the tokens per branch (branch-length sweep at the configuration's shape)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (three times) before the timed region, so that a counter "
                          "run can scale FETCH_SIZE / WRITE_SIZE by what they read for a kernel of known traffic")
@@ -73,6 +75,9 @@ def main():
     torch.cuda.set_device(0)
 
     attn_case, acc_case = W.config(args.config)
+    if args.branch_len is not None:
+        from dataclasses import replace
+        attn_case = replace(attn_case, L=args.branch_len, name=f"{attn_case.name}_L{args.branch_len}")
     n_layers = args.layers if args.layers is not None else (W.NUM_LAYERS_CFG5 if args.config == 5 else 1)
 
     # ---- inputs (resident in HBM before anything is timed) -------------------------------------------------

@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "la_internal.hpp"
+#include <cstdio>
 
 namespace la {
 namespace {
@@ -74,35 +75,47 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, Attn
 
   const int G = d->num_q_heads / d->num_kv_heads;
   const int R = d->gamma * d->branch_len * G;
-  plan->shape = 0;
+  const size_t n_rows = (size_t)d->gamma * d->branch_len * d->num_q_heads;
+
+  // Choose the kernel shape and the chunk length that minimise a simple cost model (microseconds, constants
+  // fitted to measurements on MI355X):
+  //   rounds of workgroups over the CU slots  x  (tiles per chunk x time per 64-key tile + fixed start-up)
+  //   + the merge of the partials (rows x (D+2) floats per chunk, written once and read once).
+  // Few long chunks keep the partial traffic small, many short ones fill the chip when there are few rows.
+  // Candidates: the 256-row shape (one workgroup per CU) and the 128-row two-stage shape (two per CU).
+  const int candidates[2] = {0, 3};
+  int forced = -1;
   if (const char *e = getenv("LA_ATTN_SHAPE")) {  // tuning override: index into the kernel's shape table
     const int v = atoi(e);
-    if (v >= 0 && v < attn_mfma_num_shapes()) plan->shape = v;
+    if (v >= 0 && v < attn_mfma_num_shapes()) forced = v;
   }
-  plan->tile_m = attn_mfma_tile_m(plan->shape);
-  plan->n_row_tiles = (R + plan->tile_m - 1) / plan->tile_m;
-  int chunk = d->kv_split_tokens;
-  if (chunk == 0) {
-    // Pick the chunk length that minimises a simple cost model, in units of one 64-key tile of one workgroup:
-    //   waves of workgroups over the CUs  x  (tiles per chunk + fixed per-workgroup work)  +  partials to merge.
-    // Few long chunks keep the partial traffic (rows x (D+2) floats per chunk) small; the number of workgroups
-    // should fill a whole number of waves of the 256 CUs (one workgroup per CU).
-    const int64_t base_wgs = (int64_t)d->num_kv_heads * plan->n_row_tiles;
-    double best_cost = 0.0;
-    int best_len = 0;
-    for (int n = 1; n <= 256; ++n) {
+  double best_cost = 0.0;
+  int best_len = 0, best_shape = -1;
+  for (int ci = 0; ci < (forced >= 0 ? 1 : 2); ++ci) {
+    const int shape = forced >= 0 ? forced : candidates[ci];
+    const int tile_m = attn_mfma_tile_m(shape);
+    const int per_cu = attn_mfma_wgs_per_cu(shape);
+    const int64_t base_wgs = (int64_t)d->num_kv_heads * ((R + tile_m - 1) / tile_m);
+    const double t_tile = 1.45 * per_cu * tile_m / 256.0 + (per_cu > 1 ? 0.1 : 0.0);  // per workgroup, CU shared
+    const double t_fixed = per_cu > 1 ? 5.0 : 7.0;
+    for (int n = 1; n <= 512; ++n) {
       int64_t len = max_p > 0 ? (max_p + n - 1) / n : 64;
       len = ((len + 63) / 64) * 64;
+      if (d->kv_split_tokens) len = d->kv_split_tokens;
       int64_t units = 0;
       for (int b = 0; b < d->num_requests; ++b) units += attn_num_chunks(prefix_lens_host[b], (int)len);
-      const int64_t waves = (base_wgs * units + kNumCUs - 1) / kNumCUs;
-      const double per_unit = units > 0 ? (double)units / d->num_requests : 1.0;
-      const double cost = (double)waves * ((double)len / 64 + 10.0) + 4.0 * per_unit;
-      if (best_len == 0 || cost < best_cost) best_cost = cost, best_len = (int)len;
-      if (len <= 64) break;
+      const int64_t slots = (int64_t)kNumCUs * per_cu;
+      const int64_t rounds = (base_wgs * units + slots - 1) / slots;
+      const double merge_us = 3.0 + (double)units * n_rows * (d->head_dim + 2) * 8.0 / 3.0e6;
+      const double cost = (double)rounds * ((double)len / 64 * t_tile + t_fixed) + merge_us;
+      if (best_shape < 0 || cost < best_cost) best_cost = cost, best_len = (int)len, best_shape = shape;
+      if (len <= 64 || d->kv_split_tokens) break;
     }
-    chunk = best_len;
   }
+  plan->shape = best_shape;
+  plan->tile_m = attn_mfma_tile_m(plan->shape);
+  plan->n_row_tiles = (R + plan->tile_m - 1) / plan->tile_m;
+  int chunk = best_len;
   // the block ids of one chunk live in LDS
   const int64_t max_chunk = (int64_t)(attn_mfma_max_chunk_blocks() - 1) * d->block_size;  // -1: unaligned chunk start
   if (chunk > max_chunk) {
@@ -118,9 +131,11 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, Attn
   }
   plan->s_max = s_max;
   plan->total_units = total;
-  const size_t n_rows = (size_t)d->gamma * d->branch_len * d->num_q_heads;
   plan->part_o_bytes = align_up((size_t)d->num_requests * s_max * n_rows * d->head_dim * sizeof(float));
   plan->part_ml_bytes = align_up((size_t)d->num_requests * s_max * n_rows * 2 * sizeof(float));
+  if (getenv("LA_DEBUG_PLAN"))
+    fprintf(stderr, "la plan: shape %d (tile_m %d) row_tiles %d chunk_len %d units %d s_max %d\n", plan->shape,
+            plan->tile_m, plan->n_row_tiles, plan->chunk_len, plan->total_units, plan->s_max);
   return LA_OK;
 }
 

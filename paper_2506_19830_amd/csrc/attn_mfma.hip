@@ -21,6 +21,8 @@
 // Everything is kept in log2 units: p = 2^(s*c - m).
 #include "la_internal.hpp"
 
+#include <type_traits>
+
 namespace la {
 namespace {
 
@@ -40,8 +42,8 @@ constexpr int kKTileBytes = kTileN * kKRow;  // 17408
 constexpr int kVTileBytes = kD * kVRow;      // 18432
 constexpr int kStageBytes = kKTileBytes + kVTileBytes;
 constexpr int kMaxChunkBlocks = 4096;        // block ids of one chunk kept in LDS
-constexpr int kStages = 3;                   // LDS ring: tile i is computed on while i+1 is resident and i+2 is written
-constexpr int kLdsTotal = kStages * kStageBytes + kMaxChunkBlocks * 4;  // stages + block ids: 123904
+constexpr int kMaxStages = 3;
+constexpr int kLdsTotal = kMaxStages * kStageBytes + kMaxChunkBlocks * 4;  // stages + block ids: 123904
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   f32x2 f = {a, b};
@@ -149,6 +151,62 @@ __device__ __forceinline__ void tile_load(const AttnParams &p, const TileSrc &s,
   }
 }
 
+// Full prefix tiles, the steady state: everything about an address that does not change from tile to tile is
+// computed once per thread.  A tile starts at a multiple of 64 tokens and blocks hold a power of two >= 16 tokens, so
+// for token first + tl (tl < 64 fixed per thread)
+//   block index   = (first >> shift) + (tl >> shift)          (no carry between the two terms)
+//   offset inside = (first & (bs-1)) + (tl & (bs-1))
+// which leaves one LDS read of the block id and one 64-bit multiply-add per load.
+template <bool FP8, int NT>
+struct PrefixLoader {
+  static constexpr int kNK = TileRegs<FP8, NT>::kNK, kNV = TileRegs<FP8, NT>::kNV;
+  static constexpr int row_bytes = kD * (FP8 ? 1 : 2);
+  const int32_t *blk;                        // LDS: block ids of the chunk
+  int slot_k[kNK], slot_v[kNV];              // tl >> shift: block slot relative to the tile's first block
+  const uint8_t *base_k[kNK], *base_v[kNV];  // cache base of the kv head + the thread's fixed byte offset
+  size_t blk_stride;
+  int shift, bs_mask, first_lb;
+
+  __device__ __forceinline__ void init(const AttnParams &p, const TileSrc &s, int tid) {
+    shift = p.block_shift;
+    bs_mask = p.block_size - 1;
+    first_lb = s.first_lb;
+    blk = s.blk;
+    blk_stride = ((size_t)p.Hkv << p.block_shift) * row_bytes;
+    constexpr int k_piece_shift = FP8 ? 3 : 4;
+#pragma unroll
+    for (int e = 0; e < kNK; ++e) {
+      const int idx = tid + NT * e;
+      const int tl = idx >> k_piece_shift;
+      slot_k[e] = tl >> shift;
+      base_k[e] = s.k_base + (size_t)(tl & bs_mask) * row_bytes + (idx & ((1 << k_piece_shift) - 1)) * 16;
+    }
+    constexpr int v_quad_shift = FP8 ? 5 : 6;
+#pragma unroll
+    for (int e = 0; e < kNV; ++e) {
+      const int idx = tid + NT * e;
+      const int tl = 4 * (idx >> v_quad_shift);
+      const int piece = FP8 ? (idx & 31) : v_pair_of_lane(idx & 63);
+      slot_v[e] = tl >> shift;
+      base_v[e] = s.v_base + (size_t)(tl & bs_mask) * row_bytes + piece * 4;
+    }
+  }
+  // `first`: first token of the tile (a multiple of 64, every key of the tile valid)
+  __device__ __forceinline__ void load(int first, TileRegs<FP8, NT> &r) const {
+    const int rel = (first >> shift) - first_lb;
+    const size_t inside = (size_t)(first & bs_mask) * row_bytes;
+#pragma unroll
+    for (int e = 0; e < kNK; ++e)
+      r.k[e] = *(const u32x4 *)(base_k[e] + (size_t)(uint32_t)blk[rel + slot_k[e]] * blk_stride + inside);
+#pragma unroll
+    for (int e = 0; e < kNV; ++e) {
+      const uint8_t *row = base_v[e] + (size_t)(uint32_t)blk[rel + slot_v[e]] * blk_stride + inside;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) r.v[4 * e + c] = *(const uint32_t *)(row + c * row_bytes);
+    }
+  }
+};
+
 // Registers -> LDS stage: K rows as they are, V transposed ([d][key], keys permuted by vt_pos); fp8 is widened to
 // bf16 on the way (exact: every e4m3 value is a bf16 value).
 template <bool FP8, int NT>
@@ -222,8 +280,12 @@ constexpr float kRaise = 6.0f;
 // Per-wavefront state of RB blocks of 32 query rows.
 template <int RB>
 struct RowState {
-  bf16x8 qf[RB][8];  // Q^T operand: row ln of block rb, d = 16t + 8*lh .. +8
+  bf16x8 qf[RB][8];  // Q^T operand, already multiplied by the prefix score scale (log2 units): row ln of block rb,
+                     // d = 16t + 8*lh .. +8
   f32x16 o[4][RB];   // O^T accumulators: d block db, row block rb
+  f32x16 negb[RB];   // every element = -base: the accumulator a full prefix tile's S^T starts from, so that the
+                     // MFMAs deliver s - base directly
+  float base[RB];    // == m_run once a maximum exists, 0 before
   float m_run[RB], l_run[RB];
   int row_tok[RB], row_bstart[RB];
 };
@@ -231,7 +293,7 @@ struct RowState {
 enum MaskMode { MASK_NONE = 0, MASK_TAIL = 1, MASK_BRANCH = 2 };
 
 // sched_group_barrier masks
-constexpr int kSgMfma = 0x008, kSgValu = 0x002, kSgDsRead = 0x100;
+constexpr int kSgMfma = 0x008, kSgValu = 0x002, kSgSalu = 0x004, kSgVmemRead = 0x020, kSgDsRead = 0x100;
 
 // Mask the scores of one 32-key block: register j holds key  kb*32 + (j/4)*8 + lh*4 + j%4  of the tile.
 template <int RB, int MASK>
@@ -257,20 +319,34 @@ __device__ __forceinline__ void mask_block(f32x16 (&s)[RB], const RowState<RB> &
   }
 }
 
-// Fold the block maximum of every row into its running maximum (log2 units).  A lane raises its maximum only when
-// the block exceeds it by more than kRaise; alpha is the factor its old accumulators must then be multiplied by
-// (1 for lanes that keep their maximum).  Returns whether any lane of the wavefront raised (wavefront-uniform).
+// Absolute maximum (log2 units) of one 32-key block per row.  The scores arrive as x with absolute value
+// x*crel + binit (binit: what the accumulators were started from, per lane).
 template <int RB>
-__device__ __forceinline__ bool update_max(const f32x16 (&s)[RB], RowState<RB> &st, float cseg, float (&alpha)[RB]) {
+__device__ __forceinline__ void block_max(const f32x16 (&s)[RB], float crel, const float (&binit)[RB],
+                                          float (&mt)[RB]) {
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    float ma = fmaxf(fmaxf(s[rb][0], s[rb][1]), s[rb][2]);
+    float mb = fmaxf(fmaxf(s[rb][8], s[rb][9]), s[rb][10]);
+    ma = fmaxf(fmaxf(ma, s[rb][3]), s[rb][4]);
+    mb = fmaxf(fmaxf(mb, s[rb][11]), s[rb][12]);
+    ma = fmaxf(fmaxf(ma, s[rb][5]), s[rb][6]);
+    mb = fmaxf(fmaxf(mb, s[rb][13]), s[rb][14]);
+    const float m0 = fmaxf(fmaxf(ma, s[rb][7]), fmaxf(mb, s[rb][15]));
+    mt[rb] = __builtin_fmaf(xhalf_max(m0), crel, binit[rb]);
+  }
+}
+
+// Fold the block maxima into the running maxima.  A lane raises its maximum only when the block exceeds it by more
+// than kRaise; alpha is the factor its old accumulators must then be multiplied by (1 for lanes that keep their
+// maximum).  Returns whether any lane of the wavefront raised (wavefront-uniform).
+template <int RB>
+__device__ __forceinline__ bool raise_max(const float (&mt)[RB], RowState<RB> &st, float (&alpha)[RB]) {
   bool raise = false;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    float m0 = fmaxf(s[rb][0], s[rb][1]);
-#pragma unroll
-    for (int j = 2; j < 16; j += 2) m0 = fmaxf(m0, fmaxf(s[rb][j], s[rb][j + 1]));
-    const float mt = xhalf_max(m0) * cseg;
-    const bool up = mt > st.m_run[rb] + kRaise;   // false for mt = -inf; true for the first finite block (m_run = -inf)
-    const float m_new = up ? mt : st.m_run[rb];
+    const bool up = mt[rb] > st.m_run[rb] + kRaise;   // false for mt = -inf; true for the first finite block
+    const float m_new = up ? mt[rb] : st.m_run[rb];
     const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
     alpha[rb] = up ? __builtin_amdgcn_exp2f(st.m_run[rb] - m_use) : 1.0f;   // 0 when m_run was -inf
     st.m_run[rb] = m_new;
@@ -291,24 +367,18 @@ __device__ __forceinline__ void rescale(RowState<RB> &st, const float (&alpha)[R
   }
 }
 
-// p = 2^(s*cseg - m + voff) for one 32-key block, rounded to bf16 pairs; also the fp32 row sums.
-template <int RB>
-__device__ __forceinline__ void block_probs(const f32x16 (&s)[RB], const RowState<RB> &st, float cseg, float voff,
+// p = 2^(x*crel + off) for one 32-key block, rounded to bf16 pairs; also the fp32 row sums.  off = binit + voff - m
+// per lane.  FAST: crel == 1 and off == 0 for every lane (accumulators started from -m), so p = 2^x.
+template <int RB, bool FAST>
+__device__ __forceinline__ void block_probs(const f32x16 (&s)[RB], float crel, const float (&off)[RB],
                                             uint32_t (&pb)[RB][8], float (&sum)[RB]) {
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    const float m_use = (st.m_run[rb] == -INFINITY) ? 0.f : st.m_run[rb];
-    const float off = voff - m_use;
     float acc = 0.f;
 #pragma unroll
     for (int j = 0; j < 16; j += 2) {
-#ifdef LA_EXP_NOEXP
-      const float p0 = __builtin_fmaf(s[rb][j], cseg, off);
-      const float p1 = __builtin_fmaf(s[rb][j + 1], cseg, off);
-#else
-      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[rb][j], cseg, off));
-      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[rb][j + 1], cseg, off));
-#endif
+      const float p0 = __builtin_amdgcn_exp2f(FAST ? s[rb][j] : __builtin_fmaf(s[rb][j], crel, off[rb]));
+      const float p1 = __builtin_amdgcn_exp2f(FAST ? s[rb][j + 1] : __builtin_fmaf(s[rb][j + 1], crel, off[rb]));
       pb[rb][j >> 1] = pack_bf16(p0, p1);
       // (a v_dot2c_f32_bf16 on the packed pair would sum the rounded values in one instruction, but on gfx950 it
       // stalls against the MFMAs in flight: measured slower than the two adds)
@@ -325,14 +395,15 @@ __device__ __forceinline__ void block_probs(const f32x16 (&s)[RB], const RowStat
 //     O += V1^T P1                   |  tail()  (the caller's LDS stores of the next tile)
 //   first / limit   MASK_TAIL: keys with first + key >= limit are masked
 //                   MASK_BRANCH: key token first + key is visible to a row iff row_bstart <= token <= row_tok
-//   cseg            score scale of this key segment (log2 units); voff/lmul move a differently scaled V segment into
-//                   the accumulator's units (p' = p * 2^voff, l += sum(p') * lmul)
+//   crel            score scale of this key segment relative to the prefix scale that Q already carries (1 for prefix
+//                   tiles); voff/lmul move a differently scaled V segment into the accumulator's units
+//                   (p' = p * 2^voff, l += sum(p') * lmul)
 //   k0              the K fragments of key block 0.  K0_READY: the caller already holds them (fetched while the
 //                   previous tile was finishing); otherwise they are read here.  With next_kt != nullptr the block-0
 //                   fragments of the tile staged at next_kt are fetched behind the last MFMAs and left in k0.
-template <int RB, int MASK, bool K0_READY, bool PREFETCH, typename Tail>
+template <int RB, int MASK, bool K0_READY, bool PREFETCH, int GL = 0, typename Tail>
 __device__ __forceinline__ void compute_tile(const uint8_t *kt, const uint8_t *next_kt, bf16x8 (&k0)[8],
-                                             RowState<RB> &st, int ln, int lh, int first, int limit, float cseg,
+                                             RowState<RB> &st, int ln, int lh, int first, int limit, float crel,
                                              float voff, float lmul, Tail &&tail) {
   const uint8_t *krow = kt + ln * kKRow + lh * 16;
   const uint8_t *vrow = kt + kKTileBytes + ln * kVRow + lh * 16;
@@ -343,6 +414,22 @@ __device__ __forceinline__ void compute_tile(const uint8_t *kt, const uint8_t *n
     return __builtin_bit_cast(bf16x8, *(const u32x4 *)(vrow + db * 32 * kVRow + (kb * 32 + t2 * 16) * 2));
   };
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  // Full prefix tiles start S^T from -base (base == running maximum once one exists), so the MFMAs deliver s - m
+  // and the probabilities need no multiply-add in front of the exponential, unless a maximum is raised in this
+  // tile.  Other tiles (masked, or with their own score scale) start from zero and take the general form.
+  constexpr bool kFastable = MASK == MASK_NONE;
+  float binit[RB];
+  f32x16 c_init[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    binit[rb] = kFastable ? st.base[rb] : 0.f;
+    c_init[rb] = kFastable ? st.negb[rb] : zero;
+  }
+  auto exp_offset = [&](float (&off)[RB]) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+      off[rb] = binit[rb] + voff - ((st.m_run[rb] == -INFINITY) ? 0.f : st.m_run[rb]);
+  };
 
   // ---- S0 = K0 Q^T; the K1 fragments are fetched behind the MFMAs ---------------------------
   f32x16 s0[RB], s1[RB];
@@ -355,44 +442,67 @@ __device__ __forceinline__ void compute_tile(const uint8_t *kt, const uint8_t *n
   for (int t = 0; t < 8; ++t) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
-      s0[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0[t], st.qf[rb][t], t == 0 ? zero : s0[rb], 0, 0, 0);
+      s0[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0[t], st.qf[rb][t], t == 0 ? c_init[rb] : s0[rb], 0, 0, 0);
     k1[t] = load_k(t, 1);
   }
+  // Order inside this stretch: the LDS addresses of the stage and, when the caller has just issued the global loads
+  // of a later tile (GL > 0 load groups), the LDS reads of their block ids first; then one K1 fragment read behind
+  // every MFMA, the 64-bit address arithmetic of the global loads once the block ids have arrived, and the loads.
+  __builtin_amdgcn_sched_group_barrier(kSgSalu, 8, 0);
+  __builtin_amdgcn_sched_group_barrier(kSgValu, 2 + 2 * GL, 0);
+  __builtin_amdgcn_sched_group_barrier(kSgDsRead, GL, 0);
   if constexpr (!K0_READY) __builtin_amdgcn_sched_group_barrier(kSgDsRead, 8, 0);
 #pragma unroll
   for (int t = 0; t < 8; ++t) {
     __builtin_amdgcn_sched_group_barrier(kSgMfma, RB, 0);
     __builtin_amdgcn_sched_group_barrier(kSgDsRead, 1, 0);
+    if (t == 1 && GL > 0) __builtin_amdgcn_sched_group_barrier(kSgValu, 5 * GL, 0);
+    if (t == 2 && GL > 0) __builtin_amdgcn_sched_group_barrier(kSgVmemRead, 5 * GL, 0);
   }
-  mask_block<RB, MASK>(s0, st, 0, lh, first, limit);
-  float alpha[RB];
-  if (update_max<RB>(s0, st, cseg, alpha)) rescale<RB>(st, alpha);
-
-  // ---- one basic block: S1 = K1 Q^T next to P0 = 2^(S0 - m), then O += V0^T P0 next to P1 = 2^(S1 - m).
-  //      The V fragments are fetched from LDS behind the MFMAs.
+  // ---- S1 = K1 Q^T next to P0, then O += V0^T P0 next to P1.  Full prefix tiles compute P = 2^x straight from the
+  //      accumulators, without waiting for the block maximum; the maximum is formed beside it and, in the rare case
+  //      that a row's maximum has to be raised, P of that block is computed again in the general form.  The V
+  //      fragments are fetched from LDS behind the MFMAs.
   uint32_t p0[RB][8], p1[RB][8];
-  float sum0[RB], sum1[RB];
+  float sum0[RB], sum1[RB], mt[RB], alpha[RB], off[RB];
   bf16x8 v0[2][4], v1[2][4];
 #pragma unroll
   for (int t = 0; t < 8; ++t)
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
-      s1[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1[t], st.qf[rb][t], t == 0 ? zero : s1[rb], 0, 0, 0);
-  block_probs<RB>(s0, st, cseg, voff, p0, sum0);
+      s1[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1[t], st.qf[rb][t], t == 0 ? c_init[rb] : s1[rb], 0, 0, 0);
+  mask_block<RB, MASK>(s0, st, 0, lh, first, limit);
+  if constexpr (kFastable) block_probs<RB, true>(s0, crel, off, p0, sum0);
+  block_max<RB>(s0, crel, binit, mt);
+  // V fragments are fetched half a block ahead of the MFMAs that use them (16 registers in flight, not 32)
 #pragma unroll
-  for (int t2 = 0; t2 < 2; ++t2)
+  for (int db = 0; db < 4; ++db) v0[0][db] = load_v(db, 0, 0);
 #pragma unroll
-    for (int db = 0; db < 4; ++db) v0[t2][db] = load_v(db, 0, t2);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {  // per step: RB MFMAs, 6*RB VALU (of 48*RB), one LDS read
+  for (int i = 0; i < 8; ++i) {  // per step: RB MFMAs, a share of the VALU work, one LDS read
     __builtin_amdgcn_sched_group_barrier(kSgMfma, RB, 0);
     __builtin_amdgcn_sched_group_barrier(kSgValu, 6 * RB, 0);
     __builtin_amdgcn_sched_group_barrier(kSgDsRead, 1, 0);
   }
+  // keep the speculative probabilities on this side of the branch below (otherwise they are sunk into the arm that
+  // uses them and no longer overlap the MFMAs above)
+  if constexpr (kFastable) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+      asm volatile("" ::"v"(p0[rb][0]), "v"(p0[rb][1]), "v"(p0[rb][2]), "v"(p0[rb][3]), "v"(p0[rb][4]),
+                   "v"(p0[rb][5]), "v"(p0[rb][6]), "v"(p0[rb][7]), "v"(sum0[rb]));
+  }
+  const bool raise0 = raise_max<RB>(mt, st, alpha);
+  if (!kFastable || raise0) {
+    if (raise0) rescale<RB>(st, alpha);
+    exp_offset(off);
+    block_probs<RB, false>(s0, crel, off, p0, sum0);
+  }
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) st.l_run[rb] += sum0[rb] * lmul;
-  mask_block<RB, MASK>(s1, st, 1, lh, first, limit);
-  const bool raise1 = update_max<RB>(s1, st, cseg, alpha);  // accumulators are rescaled after block 0 went in
+
+#pragma unroll
+  for (int db = 0; db < 4; ++db) v0[1][db] = load_v(db, 0, 1);
+  __builtin_amdgcn_sched_group_barrier(kSgDsRead, 4, 0);
 #pragma unroll
   for (int t2 = 0; t2 < 2; ++t2) {
     bf16x8 pf[RB];
@@ -407,29 +517,45 @@ __device__ __forceinline__ void compute_tile(const uint8_t *kt, const uint8_t *n
       for (int rb = 0; rb < RB; ++rb)
         st.o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0[t2][db], pf[rb], st.o[db][rb], 0, 0, 0);
   }
-  block_probs<RB>(s1, st, cseg, voff, p1, sum1);
+  mask_block<RB, MASK>(s1, st, 1, lh, first, limit);
+  if constexpr (kFastable) block_probs<RB, true>(s1, crel, off, p1, sum1);
+  block_max<RB>(s1, crel, binit, mt);
 #pragma unroll
-  for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-    for (int db = 0; db < 4; ++db) v1[t2][db] = load_v(db, 1, t2);
-  __builtin_amdgcn_sched_group_barrier(kSgValu, 14 * RB, 0);  // the block-1 maximum
+  for (int db = 0; db < 4; ++db) v1[0][db] = load_v(db, 1, 0);
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     __builtin_amdgcn_sched_group_barrier(kSgMfma, RB, 0);
     __builtin_amdgcn_sched_group_barrier(kSgValu, 6 * RB, 0);
     __builtin_amdgcn_sched_group_barrier(kSgDsRead, 1, 0);
   }
-  // keep the block-1 probabilities on this side of the branch below (otherwise they are sunk past it and no longer
-  // overlap the MFMAs above)
+  if constexpr (kFastable) {
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
-    asm volatile("" ::"v"(p1[rb][0]), "v"(p1[rb][1]), "v"(p1[rb][2]), "v"(p1[rb][3]), "v"(p1[rb][4]), "v"(p1[rb][5]),
-                 "v"(p1[rb][6]), "v"(p1[rb][7]), "v"(sum1[rb]));
-  if (raise1) rescale<RB>(st, alpha);
+    for (int rb = 0; rb < RB; ++rb)
+      asm volatile("" ::"v"(p1[rb][0]), "v"(p1[rb][1]), "v"(p1[rb][2]), "v"(p1[rb][3]), "v"(p1[rb][4]),
+                   "v"(p1[rb][5]), "v"(p1[rb][6]), "v"(p1[rb][7]), "v"(sum1[rb]));
+  }
+  const bool raise1 = raise_max<RB>(mt, st, alpha);  // the accumulators now hold block 0 in the old units
+  if (!kFastable || raise0 || raise1) {  // after a raise in block 0, S1 is no longer relative to the maximum
+    if (raise1) rescale<RB>(st, alpha);
+    exp_offset(off);
+    block_probs<RB, false>(s1, crel, off, p1, sum1);
+  }
+  if (raise0 || raise1) {  // keep base == running maximum for the next tile
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const float bnew = (st.m_run[rb] == -INFINITY) ? 0.f : st.m_run[rb];
+      st.base[rb] = bnew;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) st.negb[rb][j] = -bnew;
+    }
+  }
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) st.l_run[rb] += sum1[rb] * lmul;
 
   // ---- O += V1^T P1 next to the caller's tail work ----------------------------------------------
+#pragma unroll
+  for (int db = 0; db < 4; ++db) v1[1][db] = load_v(db, 1, 1);
+  __builtin_amdgcn_sched_group_barrier(kSgDsRead, 4, 0);
 #pragma unroll
   for (int t2 = 0; t2 < 2; ++t2) {
     bf16x8 pf[RB];
@@ -457,14 +583,19 @@ __device__ __forceinline__ void compute_tile(const uint8_t *kt, const uint8_t *n
   tail();
 }
 
-// NW wavefronts of RB 32-row blocks each: a row tile of 32*NW*RB rows.
-template <bool KV_FP8, bool BR_FP8, int NW, int RB>
+// NW wavefronts of RB 32-row blocks each: a row tile of 32*NW*RB rows.  STAGES LDS stages per workgroup:
+//   3: tile i is computed on while tile i+1 is resident (its first K fragments are fetched early) and tile i+2 is
+//      written; one workgroup per CU.  The shape for large row counts, where the matrix cores are the limit.
+//   2: tile i is computed on while tile i+1 is written and tiles i+2, i+3 are in flight from HBM; two workgroups
+//      share a CU, which hides the start-up and per-tile latencies when the row count is small and the KV
+//      stream is the limit.
+template <bool KV_FP8, bool BR_FP8, int NW, int RB, int STAGES>
 __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_kernel(const AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   constexpr int NT = 64 * NW;
   constexpr int kTileM = 32 * NW * RB;
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ln = lane & 31, lh = lane >> 5;
 
   // ---- which (kv head, row tile, request, chunk) -------------------------------------------
@@ -495,7 +626,7 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
   const int n_priv = (c == n_chunks - 1) ? (t_hi - tk0 + 1 + kTileN - 1) / kTileN : 0;
 
   // ---- physical block ids of this chunk -> LDS ---------------------------------------------
-  int32_t *blk_lds = (int32_t *)(lds + kStages * kStageBytes);
+  int32_t *blk_lds = (int32_t *)(lds + STAGES * kStageBytes);
   const int first_lb = k_begin >> p.block_shift;
   if (k_end > k_begin) {
     const int n_blk = ((k_end - 1) >> p.block_shift) - first_lb + 1;  // <= kMaxChunkBlocks (host guarantees)
@@ -520,6 +651,28 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
   brs.first_lb = 0;
   brs.limit = t_hi + 1;
 
+  // two-stage shape: a wavefront whose rows all lie past R stages tiles but computes nothing
+  const bool active = STAGES == 3 || r0 + wave * RB * 32 < p.R;
+
+  // Score scales of the two key segments, in log2 units.  Q is multiplied by the prefix scale when it is loaded
+  // (and rounded to bf16 again), so prefix scores leave the MFMAs ready for the exponential; a branch segment with
+  // another scale is corrected by crel_branch.
+  float c_prefix = p.scale_log2, crel_branch = 1.0f;
+  float vmul_branch = 1.0f;  // branch V is multiplied by this to live in the prefix segment's V units
+  float v_out = 1.0f;
+  if (KV_FP8) {
+    const float ks = p.k_scale ? p.k_scale[kvh] : 1.0f;
+    const float vs = p.v_scale ? p.v_scale[kvh] : 1.0f;
+    c_prefix *= ks;
+    v_out = vs;
+    if (!BR_FP8) {
+      crel_branch = 1.0f / ks;
+      vmul_branch = 1.0f / vs;
+    }
+  }
+  const float voff_branch = __builtin_log2f(vmul_branch);
+  const float lmul_branch = 1.0f / vmul_branch;
+
   // ---- per-lane query rows ---------------------------------------------------------------
   RowState<RB> st;
   int row[RB];
@@ -536,73 +689,121 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
     for (int t = 0; t < 8; ++t) {
       u32x4 v = *(const u32x4 *)(qrow + (16 * t + 8 * lh) * 2);
       if (r >= p.R) v = u32x4{0, 0, 0, 0};
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {  // bf16 pair -> fp32, times the prefix scale, back to bf16 (round to nearest even)
+        const uint32_t word = v[w];
+        const uint32_t wl = word << 16, wh = word & 0xffff0000u;
+        v[w] = pack_bf16(__builtin_bit_cast(float, wl) * c_prefix, __builtin_bit_cast(float, wh) * c_prefix);
+      }
       st.qf[rb][t] = __builtin_bit_cast(bf16x8, v);
     }
     st.m_run[rb] = -INFINITY;
     st.l_run[rb] = 0.f;
+    st.base[rb] = 0.f;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) st.negb[rb][j] = 0.f;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
       for (int j = 0; j < 16; ++j) st.o[db][rb][j] = 0.f;
   }
 
-  // scale factors of the two key segments, in log2 units
-  float c_prefix = p.scale_log2, c_branch = p.scale_log2;
-  float vmul_branch = 1.0f;  // branch V is multiplied by this to live in the prefix segment's V units
-  float v_out = 1.0f;
-  if (KV_FP8) {
-    const float ks = p.k_scale ? p.k_scale[kvh] : 1.0f;
-    const float vs = p.v_scale ? p.v_scale[kvh] : 1.0f;
-    c_prefix *= ks;
-    v_out = vs;
-    if (BR_FP8)
-      c_branch *= ks;
-    else
-      vmul_branch = 1.0f / vs;
-  }
-  const float voff_branch = __builtin_log2f(vmul_branch);
-  const float lmul_branch = 1.0f / vmul_branch;
-
   __syncthreads();  // block ids visible
 
-  // ---- phase 1: the unmasked prefix tiles through a ring of three LDS stages ----------------------
-  // iteration i: global loads of tile i+2 are in flight, tile i is computed from stage i%3 (its block-0 K fragments
-  // were fetched while tile i-1 finished), the block-0 fragments of tile i+1 are fetched from stage (i+1)%3, and
-  // tile i+2 is written to stage (i+2)%3, which every wavefront stopped reading at the barrier before.
+  // ---- phase 1: the unmasked prefix tiles -----------------------------------------------------
   bf16x8 k0[8];
-  if (n_full > 0) {
-    TileRegs<KV_FP8, NT> regs;
-    auto stage_of = [&](int it) { return lds + (it % kStages) * kStageBytes; };
-    auto gload = [&](int it) {
-      pre.first = k_begin + it * kTileN;
-      tile_load<KV_FP8, true, true, NT>(p, pre, tid, regs);
-    };
-    gload(0);
-    tile_store<KV_FP8, NT>(stage_of(0), tid, regs);
-    if (n_full > 1) {
-      gload(1);
-      tile_store<KV_FP8, NT>(stage_of(1), tid, regs);
-    }
-    __syncthreads();
-    {
-      const uint8_t *krow = stage_of(0) + ln * kKRow + lh * 16;
+  if constexpr (STAGES == 3) {
+    // ring of three stages.  iteration i: global loads of tile i+2 are in flight, tile i is computed from stage
+    // i%3 (its block-0 K fragments were fetched while tile i-1 finished), the block-0 fragments of tile i+1 are
+    // fetched from stage (i+1)%3, and tile i+2 is written to stage (i+2)%3, which every wavefront stopped
+    // reading at the barrier before.
+    if (n_full > 0) {
+      TileRegs<KV_FP8, NT> regs;
+      PrefixLoader<KV_FP8, NT> loader;
+      loader.init(p, pre, tid);
+      auto gload = [&](int it) { loader.load(k_begin + it * kTileN, regs); };
+      // byte offsets of the stages holding tile it, it+1 and it+2; rotated once per tile
+      int o_cur = 0, o_next = kStageBytes, o_store = 2 * kStageBytes;
+      gload(0);
+      tile_store<KV_FP8, NT>(lds + o_cur, tid, regs);
+      if (n_full > 1) {
+        gload(1);
+        tile_store<KV_FP8, NT>(lds + o_next, tid, regs);
+      }
+      __syncthreads();
+      {
+        const uint8_t *krow = lds + ln * kKRow + lh * 16;
 #pragma unroll
-      for (int t = 0; t < 8; ++t) k0[t] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(krow + t * 32));
-    }
-    int it = 0;
-    for (; it + 2 < n_full; ++it) {  // steady state: nothing conditional
-      gload(it + 2);
-      compute_tile<RB, MASK_NONE, true, true>(stage_of(it), stage_of(it + 1), k0, st, ln, lh, 0, 0, c_prefix, 0.f,
-                                              1.f, [&] { tile_store<KV_FP8, NT>(stage_of(it + 2), tid, regs); });
+        for (int t = 0; t < 8; ++t) k0[t] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(krow + t * 32));
+      }
+      int it = 0;
+      for (; it + 2 < n_full; ++it) {  // steady state: nothing conditional
+        gload(it + 2);
+        compute_tile<RB, MASK_NONE, true, true, TileRegs<KV_FP8, NT>::kNK + TileRegs<KV_FP8, NT>::kNV>(
+            lds + o_cur, lds + o_next, k0, st, ln, lh, 0, 0, 1.f, 0.f, 1.f,
+            [&] { tile_store<KV_FP8, NT>(lds + o_store, tid, regs); });
+        __syncthreads();
+        const int o = o_cur;
+        o_cur = o_next;
+        o_next = o_store;
+        o_store = o;
+      }
+      if (it + 1 < n_full) {  // second to last tile: nothing left to load
+        compute_tile<RB, MASK_NONE, true, true>(lds + o_cur, lds + o_next, k0, st, ln, lh, 0, 0, 1.f, 0.f, 1.f, [] {});
+        o_cur = o_next;
+      }
+      compute_tile<RB, MASK_NONE, true, false>(lds + o_cur, nullptr, k0, st, ln, lh, 0, 0, 1.f, 0.f, 1.f, [] {});
       __syncthreads();
     }
-    if (it + 1 < n_full) {  // second to last tile: nothing left to load
-      compute_tile<RB, MASK_NONE, true, true>(stage_of(it), stage_of(it + 1), k0, st, ln, lh, 0, 0, c_prefix, 0.f,
-                                              1.f, [] {});
-      ++it;
+  } else {
+    // two stages, one register set.  Iteration i computes on stage i%2 and then writes tile i+1 (loaded during
+    // iteration i-1) to the other stage and issues the loads of tile i+2.  Those loads have one tile time to
+    // arrive, less than an HBM round trip under load, so every 128-byte line of a tile is touched four tiles
+    // ahead with a one-word load whose value is only folded into a sink: the staging loads then hit L2.
+    uint32_t sink = 0;
+    if (n_full > 0) {
+      TileRegs<KV_FP8, NT> regs;
+      PrefixLoader<KV_FP8, NT> loader;
+      loader.init(p, pre, tid);
+      auto gload = [&](int it) { loader.load(k_begin + it * kTileN, regs); };
+      constexpr int kLinesPerRow = kv_row / 128;       // 1 (fp8) or 2 (bf16)
+      constexpr int kLines = kTileN * kLinesPerRow;    // lines of the K tile; the V tile has as many
+      static_assert(2 * kLines <= NT, "one touch per thread");
+      auto touch = [&](int it) -> uint32_t {
+        if (it >= n_full || tid >= 2 * kLines) return 0u;
+        pre.first = k_begin + it * kTileN;
+        const int line = tid % kLines;
+        const uint8_t *base = tid < kLines ? pre.k_base : pre.v_base;
+        return *(const uint32_t *)(key_row<KV_FP8, true>(p, pre, base, pre.first + line / kLinesPerRow) +
+                                   (line % kLinesPerRow) * 128);
+      };
+      const uint32_t t1 = touch(1), t2 = touch(2), t3 = touch(3);
+      gload(0);
+      tile_store<KV_FP8, NT>(lds, tid, regs);
+      if (n_full > 1) gload(1);
+      uint32_t pf = t1 ^ t2 ^ t3;
+      __syncthreads();
+      for (int it = 0; it < n_full; ++it) {
+        const uint8_t *cur = lds + (it & 1) * kStageBytes;
+        uint8_t *other = lds + ((it + 1) & 1) * kStageBytes;
+        auto tail = [&] {
+          if (it + 1 < n_full) {
+            tile_store<KV_FP8, NT>(other, tid, regs);
+            if (it + 2 < n_full) gload(it + 2);
+          }
+          sink ^= pf;
+          pf = touch(it + 4);
+        };
+        if (active)
+          compute_tile<RB, MASK_NONE, false, false>(cur, nullptr, k0, st, ln, lh, 0, 0, 1.f, 0.f, 1.f, tail);
+        else
+          tail();
+        __syncthreads();
+      }
+      sink ^= pf;
     }
-    compute_tile<RB, MASK_NONE, true, false>(stage_of(it), nullptr, k0, st, ln, lh, 0, 0, c_prefix, 0.f, 1.f, [] {});
-    __syncthreads();
+    // never true (R >= 1): keeps the touched words alive without a store on any real path
+    if (p.R < 0) p.part_ml[0] = __builtin_bit_cast(float, sink);
   }
   // ---- phase 2: the partly filled prefix tile -------------------------------------------------
   if (has_tail) {
@@ -611,8 +812,9 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
     tile_load<KV_FP8, true, false, NT>(p, pre, tid, regs);
     tile_store<KV_FP8, NT>(lds, tid, regs);
     __syncthreads();
-    compute_tile<RB, MASK_TAIL, false, false>(lds, nullptr, k0, st, ln, lh, pre.first, k_end, c_prefix, 0.f, 1.f,
-                                              [] {});
+    if (active)
+      compute_tile<RB, MASK_TAIL, false, false>(lds, nullptr, k0, st, ln, lh, pre.first, k_end, 1.f, 0.f, 1.f,
+                                                [] {});
     __syncthreads();
   }
   // ---- phase 3: branch-private tiles (last chunk only) ------------------------------------------
@@ -622,8 +824,9 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
     tile_load<BR_FP8, false, false, NT>(p, brs, tid, regs);
     tile_store<BR_FP8, NT>(lds, tid, regs);
     __syncthreads();
-    compute_tile<RB, MASK_BRANCH, false, false>(lds, nullptr, k0, st, ln, lh, brs.first, 0, c_branch, voff_branch,
-                                                lmul_branch, [] {});
+    if (active)
+      compute_tile<RB, MASK_BRANCH, false, false>(lds, nullptr, k0, st, ln, lh, brs.first, 0, crel_branch, voff_branch,
+                                                  lmul_branch, [] {});
     __syncthreads();
   }
 
@@ -650,47 +853,49 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
   }
 }
 
-template <bool KV_FP8, bool BR_FP8, int NW, int RB>
+template <bool KV_FP8, bool BR_FP8, int NW, int RB, int STAGES>
 hipError_t launch_variant(const AttnParams &p, hipStream_t stream) {
   const int grid = p.Hkv * p.n_row_tiles * p.total_units;
-  auto kern = attn_mfma_kernel<KV_FP8, BR_FP8, NW, RB>;
+  auto kern = attn_mfma_kernel<KV_FP8, BR_FP8, NW, RB, STAGES>;
   static bool configured = false;  // per template instance
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  // two tile stages plus the block ids of one chunk (a chunk that does not start on a block boundary spans one more)
+  // the tile stages plus the block ids of one chunk (a chunk that does not start on a block boundary spans one more)
   const int blk_entries = (p.chunk_len >> p.block_shift) + 2;
-  const int lds_bytes = kStages * kStageBytes + (blk_entries < kMaxChunkBlocks ? blk_entries : kMaxChunkBlocks) * 4;
+  const int lds_bytes = STAGES * kStageBytes + (blk_entries < kMaxChunkBlocks ? blk_entries : kMaxChunkBlocks) * 4;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NW), lds_bytes, stream, p);
   return hipGetLastError();
 }
 
-template <int NW, int RB>
+template <int NW, int RB, int STAGES>
 hipError_t launch_shape(const AttnParams &p, bool kv_fp8, bool br_fp8, hipStream_t stream) {
-  if (kv_fp8 && br_fp8) return launch_variant<true, true, NW, RB>(p, stream);
-  if (kv_fp8 && !br_fp8) return launch_variant<true, false, NW, RB>(p, stream);
-  if (!kv_fp8 && !br_fp8) return launch_variant<false, false, NW, RB>(p, stream);
+  if (kv_fp8 && br_fp8) return launch_variant<true, true, NW, RB, STAGES>(p, stream);
+  if (kv_fp8 && !br_fp8) return launch_variant<true, false, NW, RB, STAGES>(p, stream);
+  if (!kv_fp8 && !br_fp8) return launch_variant<false, false, NW, RB, STAGES>(p, stream);
   return hipErrorInvalidValue;
 }
 
-// Kernel shapes: (wavefronts per workgroup, 32-row blocks per wavefront).
-constexpr int kShapes[][2] = {{8, 1}, {4, 2}, {4, 1}};
-constexpr int kNumShapes = 3;
+// Kernel shapes: (wavefronts per workgroup, 32-row blocks per wavefront, LDS stages).
+constexpr int kShapes[][3] = {{8, 1, 3}, {4, 2, 3}, {4, 1, 3}, {4, 1, 2}};
+constexpr int kNumShapes = 4;
 
 }  // namespace
 
 int attn_mfma_num_shapes() { return kNumShapes; }
 int attn_mfma_tile_m(int shape) { return 32 * kShapes[shape][0] * kShapes[shape][1]; }
+int attn_mfma_wgs_per_cu(int shape) { return kShapes[shape][2] == 2 ? 2 : 1; }
 int attn_mfma_max_chunk_blocks() { return kMaxChunkBlocks; }
 
 hipError_t launch_attn_mfma(const AttnParams &p, int shape, bool kv_fp8, bool br_fp8, hipStream_t stream) {
   ProfileScope scope(SLOT_ATTN_MFMA, stream);
   switch (shape) {
-    case 0: return launch_shape<8, 1>(p, kv_fp8, br_fp8, stream);
-    case 1: return launch_shape<4, 2>(p, kv_fp8, br_fp8, stream);
-    case 2: return launch_shape<4, 1>(p, kv_fp8, br_fp8, stream);
+    case 0: return launch_shape<8, 1, 3>(p, kv_fp8, br_fp8, stream);
+    case 1: return launch_shape<4, 2, 3>(p, kv_fp8, br_fp8, stream);
+    case 2: return launch_shape<4, 1, 3>(p, kv_fp8, br_fp8, stream);
+    case 3: return launch_shape<4, 1, 2>(p, kv_fp8, br_fp8, stream);
   }
   return hipErrorInvalidValue;
 }

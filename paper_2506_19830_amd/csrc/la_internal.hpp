@@ -59,6 +59,7 @@ enum KernelSlot {
 // The MFMA kernel is built in a few (wavefronts, row blocks per wavefront) shapes.
 int attn_mfma_num_shapes();
 int attn_mfma_tile_m(int shape);   // rows per workgroup of a shape
+int attn_mfma_wgs_per_cu(int shape);  // workgroups of a shape that fit on one CU (LDS)
 int attn_mfma_max_chunk_blocks();  // a chunk may span at most this many cache blocks
 hipError_t launch_attn_mfma(const AttnParams &p, int shape, bool kv_fp8, bool br_fp8, hipStream_t stream);
 hipError_t launch_attn_merge(const AttnParams &p, hipStream_t stream);
