@@ -96,7 +96,7 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, Attn
     const int tile_m = attn_mfma_tile_m(shape);
     const int per_cu = attn_mfma_wgs_per_cu(shape);
     const int64_t base_wgs = (int64_t)d->num_kv_heads * ((R + tile_m - 1) / tile_m);
-    const double t_tile = 1.45 * per_cu * tile_m / 256.0 + (per_cu > 1 ? 0.1 : 0.0);  // per workgroup, CU shared
+    const double t_tile = per_cu > 1 ? 2.25 : 1.87;  // per workgroup and 64-key tile, the CU shared by per_cu
     const double t_fixed = per_cu > 1 ? 5.0 : 7.0;
     for (int n = 1; n <= 512; ++n) {
       int64_t len = max_p > 0 ? (max_p + n - 1) / n : 64;

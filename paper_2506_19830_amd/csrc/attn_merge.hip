@@ -51,9 +51,23 @@ __global__ __launch_bounds__(64 * kWaves) void attn_merge_kernel(const AttnParam
     acc1 *= rescale;
     denom = denom * rescale + wl;
     m_all = m_new;
-    for (int s = 0; s < cnt; ++s) {
+    const float *po = p.part_o + ((slot0 + s0) * p.n_rows + r) * kD + 2 * lane;
+    const size_t stride = (size_t)p.n_rows * kD;  // between the partials of consecutive chunks
+    int s = 0;
+    for (; s + 8 <= cnt; s += 8) {  // eight independent loads in flight: with many chunks this loop is latency bound
+      f32x2 o[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) o[j] = *(const f32x2 *)(po + (size_t)(s + j) * stride);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float ws = __shfl(w, s + j);
+        acc0 = __builtin_fmaf(ws, o[j].x, acc0);
+        acc1 = __builtin_fmaf(ws, o[j].y, acc1);
+      }
+    }
+    for (; s < cnt; ++s) {
       const float ws = __shfl(w, s);
-      const f32x2 o = *(const f32x2 *)(p.part_o + ((slot0 + s0 + s) * p.n_rows + r) * kD + 2 * lane);
+      const f32x2 o = *(const f32x2 *)(po + (size_t)s * stride);
       acc0 = __builtin_fmaf(ws, o.x, acc0);
       acc1 = __builtin_fmaf(ws, o.y, acc1);
     }
