@@ -83,7 +83,7 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, Attn
   //   + the merge of the partials (rows x (D+2) floats per chunk, written once and read once).
   // Few long chunks keep the partial traffic small, many short ones fill the chip when there are few rows.
   // Candidates: the 256-row shape (one workgroup per CU) and the 128-row two-stage shape (two per CU).
-  const int candidates[2] = {0, 3};
+  const int candidates[2] = {0, 1};
   int forced = -1;
   if (const char *e = getenv("LA_ATTN_SHAPE")) {  // tuning override: index into the kernel's shape table
     const int v = atoi(e);
@@ -97,7 +97,7 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, Attn
     const int per_cu = attn_mfma_wgs_per_cu(shape);
     const int64_t base_wgs = (int64_t)d->num_kv_heads * ((R + tile_m - 1) / tile_m);
     const double t_tile = per_cu > 1 ? 2.25 : 1.87;  // per workgroup and 64-key tile, the CU shared by per_cu
-    const double t_fixed = per_cu > 1 ? 5.0 : 7.0;
+    const double t_fixed = per_cu > 1 ? 8.0 : 9.0;
     for (int n = 1; n <= 512; ++n) {
       int64_t len = max_p > 0 ? (max_p + n - 1) / n : 64;
       len = ((len + 63) / 64) * 64;
@@ -106,7 +106,7 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, Attn
       for (int b = 0; b < d->num_requests; ++b) units += attn_num_chunks(prefix_lens_host[b], (int)len);
       const int64_t slots = (int64_t)kNumCUs * per_cu;
       const int64_t rounds = (base_wgs * units + slots - 1) / slots;
-      const double merge_us = 3.0 + (double)units * n_rows * (d->head_dim + 2) * 8.0 / 3.0e6;
+      const double merge_us = 3.0 + (double)units * n_rows * (d->head_dim + 2) * 4.0 / 3.0e6;  // read at ~3 TB/s
       const double cost = (double)rounds * ((double)len / 64 * t_tile + t_fixed) + merge_us;
       if (best_shape < 0 || cost < best_cost) best_cost = cost, best_len = (int)len, best_shape = shape;
       if (len <= 64 || d->kv_split_tokens) break;

@@ -80,7 +80,7 @@ def test_mfma_small_cases(oracle, case, split):
     check_full(oracle, case, TOL_LOWP, kv_split_tokens=split)
 
 
-@pytest.mark.parametrize("shape", [0, 1, 2, 3])
+@pytest.mark.parametrize("shape", [0, 1])
 @pytest.mark.parametrize("case", [MFMA_CASES[0], MFMA_CASES[2], MFMA_CASES[3], MFMA_CASES[5]], ids=lambda c: c.name)
 def test_every_kernel_shape(oracle, case, shape, monkeypatch):
     """The planner picks one of the kernel's (wavefronts, row blocks, LDS stages) shapes by a cost model; here
