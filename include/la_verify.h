@@ -160,9 +160,16 @@ LA_API const char *la_status_string(la_status s);
  * state, not thread-safe; at most LA_PROFILE_MAX_RECORDS launches are kept,
  * later ones are dropped).  la_profile_collect synchronises on the recorded
  * events and accumulates them; la_profile_get then reports, per kernel slot,
- * its name, number of timed launches and their total duration. */
+ * its name, number of timed launches and their total duration.
+ * la_profile_select narrows what is bracketed: bit k of slot_mask selects
+ * kernel slot k (default: all), and of a selected slot's launches only every
+ * stride-th one is timed (default 1); the event pairs cost a few microseconds
+ * each on the stream, so a benchmark that wants its wall time undisturbed
+ * times only the kernel it reports and a sample of its launches.  Returns
+ * LA_ERR_INVALID_ARG for stride < 1. */
 #define LA_PROFILE_MAX_RECORDS 8192
 LA_API la_status la_profile_enable(int on);
+LA_API la_status la_profile_select(uint32_t slot_mask, int32_t stride);
 LA_API la_status la_profile_collect(void);
 LA_API int32_t la_profile_num_kernels(void);
 LA_API la_status la_profile_get(int32_t slot, const char **name, int64_t *launches, double *total_ms);

@@ -25,7 +25,7 @@ _TORCH_DTYPES = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch
 
 EXPORTED_SYMBOLS = (
     "la_verify_attention_workspace", "la_verify_attention", "la_spec_accept_workspace", "la_spec_accept",
-    "la_status_string", "la_profile_enable", "la_profile_collect", "la_profile_num_kernels", "la_profile_get",
+    "la_status_string", "la_profile_enable", "la_profile_select", "la_profile_collect", "la_profile_num_kernels", "la_profile_get",
     "la_profile_reset",
 )
 
@@ -77,6 +77,8 @@ def load() -> ctypes.CDLL:
         lib.la_status_string.argtypes = [ctypes.c_int]
         lib.la_profile_enable.restype = ctypes.c_int
         lib.la_profile_enable.argtypes = [ctypes.c_int]
+        lib.la_profile_select.restype = ctypes.c_int
+        lib.la_profile_select.argtypes = [ctypes.c_uint32, ctypes.c_int32]
         lib.la_profile_collect.restype = ctypes.c_int
         lib.la_profile_reset.restype = ctypes.c_int
         lib.la_profile_num_kernels.restype = ctypes.c_int32
@@ -159,6 +161,24 @@ def la_spec_accept(desc: la_accept_desc, target_logits, draft_logits, draft_toke
 
 def la_profile_enable(on: bool) -> None:
     load().la_profile_enable(int(bool(on)))
+
+
+def la_profile_select(kernels=None, stride: int = 1) -> None:
+    """Time only the named kernels (None = all), and of their launches every ``stride``-th one."""
+    lib = load()
+    mask = 0xFFFFFFFF
+    if kernels is not None:
+        names = {}
+        for slot in range(lib.la_profile_num_kernels()):
+            name = ctypes.c_char_p()
+            lib.la_profile_get(slot, ctypes.byref(name), ctypes.byref(ctypes.c_int64()), ctypes.byref(ctypes.c_double()))
+            names[name.value.decode()] = slot
+        mask = 0
+        for k in kernels:
+            mask |= 1 << names[k]
+    st = lib.la_profile_select(mask, int(stride))
+    if st:
+        raise LaError(st, "la_profile_select")
 
 
 def la_profile_reset() -> None:

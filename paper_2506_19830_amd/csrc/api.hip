@@ -147,6 +147,9 @@ struct ProfileRecord {
   hipEvent_t start, stop;
 };
 bool g_profile_on = false;
+uint32_t g_profile_mask = 0xffffffffu;      // slots that are timed
+int g_profile_stride = 1;                   // of their launches, every stride-th one
+int64_t g_seen[SLOT_COUNT];                 // launches of a slot seen while enabled
 std::vector<ProfileRecord> g_records;       // pending (not yet collected)
 std::vector<hipEvent_t> g_free_events;
 int64_t g_launches[SLOT_COUNT];
@@ -168,9 +171,9 @@ hipEvent_t take_event() {
 }  // namespace
 
 void profile_before(int slot, hipStream_t stream) {
-  (void)slot;
   g_open = false;
-  if (!g_profile_on || g_records.size() >= LA_PROFILE_MAX_RECORDS) return;
+  if (!g_profile_on || !((g_profile_mask >> slot) & 1u)) return;
+  if ((g_seen[slot]++ % g_profile_stride) != 0 || g_records.size() >= LA_PROFILE_MAX_RECORDS) return;
   hipEvent_t e = take_event();
   if (!e) return;
   if (hipEventRecord(e, stream) != hipSuccess) {
@@ -310,6 +313,13 @@ la_status la_spec_accept(const la_accept_desc *desc, const void *target_logits, 
   return launch_accept(p, (hipStream_t)hip_stream) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }
 
+la_status la_profile_select(uint32_t slot_mask, int32_t stride) {
+  if (stride < 1) return LA_ERR_INVALID_ARG;
+  g_profile_mask = slot_mask;
+  g_profile_stride = stride;
+  return LA_OK;
+}
+
 la_status la_profile_enable(int on) {
   g_profile_on = on != 0;
   return LA_OK;
@@ -344,7 +354,7 @@ la_status la_profile_get(int32_t slot, const char **name, int64_t *launches, dou
 
 la_status la_profile_reset(void) {
   la_status st = la_profile_collect();
-  for (int i = 0; i < SLOT_COUNT; ++i) g_launches[i] = 0, g_total_ms[i] = 0.0;
+  for (int i = 0; i < SLOT_COUNT; ++i) g_launches[i] = 0, g_total_ms[i] = 0.0, g_seen[i] = 0;
   return st;
 }
 
