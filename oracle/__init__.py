@@ -174,12 +174,12 @@ def attention_row_weights(q, k_cache, v_cache, block_tables, prefix_lens, k_bran
 def spec_accept(target_logits, draft_logits, draft_tokens, u_accept, u_sample, *, logits_dtype, temperature=1.0):
     """Sequential token-level accept / resample.  Returns a dict with
     ``accepted_len`` [NB], ``next_token`` [NB], ``ratio`` [NB,K], ``margin`` [NB,K],
-    ``cdf_lo`` [NB], ``cdf_hi`` [NB]."""
+    ``cdf_lo`` [NB], ``cdf_hi`` [NB].  ``draft_logits=None``: point-mass draft at the drafted tokens."""
     t = _storage(target_logits, logits_dtype, "target_logits")
-    d = _storage(draft_logits, logits_dtype, "draft_logits")
+    d = None if draft_logits is None else _storage(draft_logits, logits_dtype, "draft_logits")
     NB, K1, V = t.shape
     K = K1 - 1
-    if d.shape != (NB, K, V):
+    if d is not None and d.shape != (NB, K, V):
         raise ValueError("draft_logits must be [NB, K, V] with target_logits [NB, K+1, V]")
     tok = np.ascontiguousarray(draft_tokens, dtype=np.int32)
     ua = np.ascontiguousarray(u_accept, dtype=np.float32)

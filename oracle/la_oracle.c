@@ -32,6 +32,10 @@
  *   - inverse CDF returns the first v whose running sum is > u*S (strict), so
  *     zero-mass tokens are never returned (pinned: a sample must have mass).
  * The first two items only matter on measure-zero / rounding-only inputs.
+ *   - draft_logits == NULL: the drafter proposes tokens without a distribution
+ *     (Section 4, Setup: prompt-lookup / n-gram drafts), i.e. q_i is the point
+ *     mass at the drafted token x_i.  The same rule then reads: accept with
+ *     probability p_i(x_i); on rejection draw from p_n with x_n removed.
  */
 #include <math.h>
 #include <stdint.h>
@@ -310,8 +314,7 @@ int lao_spec_accept(int NB, int K, int V, int logits_dtype, double temperature, 
                     const float *u_sample, int32_t *accepted_len, int32_t *next_token, double *ratio, double *margin,
                     double *cdf_lo, double *cdf_hi) {
   if (NB < 1 || K < 1 || V < 1 || !(temperature > 0.0)) return 1;
-  if (!target_logits || !draft_logits || !draft_tokens || !u_accept || !u_sample || !accepted_len || !next_token)
-    return 1;
+  if (!target_logits || !draft_tokens || !u_accept || !u_sample || !accepted_len || !next_token) return 1;
   for (int64_t t = 0; t < (int64_t)NB * K; ++t)
     if (draft_tokens[t] < 0 || draft_tokens[t] >= V) return 1;
   int failed = 0;
@@ -334,8 +337,13 @@ int lao_spec_accept(int NB, int K, int V, int logits_dtype, double temperature, 
     int n = K;
     for (int i = 0; i < K; ++i) {
       softmax_row(target_logits, logits_dtype, ((int64_t)nb * (K + 1) + i) * V, V, temperature, p);
-      softmax_row(draft_logits, logits_dtype, ((int64_t)nb * K + i) * V, V, temperature, q);
       const int x = draft_tokens[(int64_t)nb * K + i];
+      if (draft_logits) {
+        softmax_row(draft_logits, logits_dtype, ((int64_t)nb * K + i) * V, V, temperature, q);
+      } else { /* point-mass draft */
+        for (int v = 0; v < V; ++v) q[v] = 0.0;
+        q[x] = 1.0;
+      }
       const double u = (double)u_accept[(int64_t)nb * K + i];
       if (ratio) ratio[(int64_t)nb * K + i] = p[x] / q[x];
       if (margin) {

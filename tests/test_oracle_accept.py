@@ -214,3 +214,73 @@ def test_rejects_bad_arguments(oracle):
     with pytest.raises(ValueError):
         run(oracle, t, d, np.array([[0]], np.int32), np.zeros((1, 1), np.float32), np.zeros((1,), np.float32),
             temperature=0.0)
+
+
+# ------------------------------------------------------------------------------------------ point-mass draft
+# Section 4 (Setup): the paper's token-level drafts come from prompt lookup (n-gram), which proposes tokens without a
+# distribution: q_i is the point mass at x_i.  The rule of Section 2 then accepts with probability p_i(x_i) and
+# resamples from p_n with x_n removed.
+
+def run_onehot(oracle, t, tok, ua, us, **kw):
+    return oracle.spec_accept(np.asarray(t, np.float32), None, tok, ua, us, logits_dtype="f32", **kw)
+
+
+def test_point_mass_draft_emits_the_target_distribution(oracle):
+    """V=8, K=1, a fixed drafted token: P(accept) = p(x); the emitted token is still distributed as p_0 (accepted
+    x with probability p(x), otherwise y != x with probability (1-p(x)) * p(y)/(1-p(x)))."""
+    rng = np.random.default_rng(77)
+    V, N, x = 8, 600_000, 3
+    t_row = rng.normal(0, 1.5, size=(2, V)).astype(np.float32)
+    p0 = np.exp(t_row[0].astype(np.float64)); p0 /= p0.sum()
+    p1 = np.exp(t_row[1].astype(np.float64)); p1 /= p1.sum()
+    t = np.broadcast_to(t_row, (N, 2, V)).copy()
+    tok = np.full((N, 1), x, dtype=np.int32)
+    ua = rng.random((N, 1), dtype=np.float32)
+    us = rng.random((N,), dtype=np.float32)
+    r = run_onehot(oracle, t, tok, ua, us)
+    n, nxt = r["accepted_len"], r["next_token"]
+    assert abs((n == 1).mean() - p0[x]) < 4.5 * math.sqrt(p0[x] * (1 - p0[x]) / N)
+    np.testing.assert_array_equal(n == 1, ua[:, 0].astype(np.float64) < p0[x])      # the test is u < p(x)
+    assert (nxt[n == 0] != x).all()                                                  # x is removed from the residual
+    first = np.where(n == 1, x, nxt)
+    assert chi2(np.bincount(first, minlength=V), p0) < 29.9
+    assert chi2(np.bincount(nxt[n == 1], minlength=V), p1) < 29.9
+    rest = p0.copy(); rest[x] = 0
+    assert chi2(np.bincount(nxt[n == 0], minlength=V), rest / rest.sum()) < 29.9
+    np.testing.assert_allclose(r["ratio"][:, 0], p0[x], rtol=1e-12)
+
+
+def test_point_mass_draft_equals_a_dense_draft_that_is_a_point_mass(oracle):
+    """The same problem written with dense draft logits that put all mass on the drafted token (every other logit
+    1e9 lower, so the fp64 softmax is exactly 0/1) must give identical results through the dense code path."""
+    rng = np.random.default_rng(5)
+    NB, K, V = 256, 5, 37
+    t = rng.normal(0, 2.5, size=(NB, K + 1, V)).astype(np.float32)
+    tok = rng.integers(0, V, size=(NB, K)).astype(np.int32)
+    # make acceptance likely enough that all lengths 0..K occur
+    for b in range(NB):
+        for i in range(K):
+            t[b, i, tok[b, i]] += 7.0
+    ua = rng.random((NB, K), dtype=np.float32)
+    us = rng.random((NB,), dtype=np.float32)
+    d = np.full((NB, K, V), -1.0e9, dtype=np.float32)
+    np.put_along_axis(d, tok[:, :, None], 0.0, axis=2)
+    a = run_onehot(oracle, t, tok, ua, us)
+    b_ = run(oracle, t, d, tok, ua, us)
+    assert set(np.unique(a["accepted_len"])) == set(range(K + 1))
+    for k in ("accepted_len", "next_token"):
+        np.testing.assert_array_equal(a[k], b_[k])
+    for k in ("ratio", "cdf_lo", "cdf_hi"):
+        np.testing.assert_array_equal(np.nan_to_num(a[k], nan=-1.0), np.nan_to_num(b_[k], nan=-1.0))
+
+
+def test_point_mass_draft_certain_token_is_always_accepted(oracle):
+    V, K = 6, 3
+    t = np.full((1, K + 1, V), -1.0e4, dtype=np.float32)
+    tok = np.array([[2, 4, 1]], dtype=np.int32)
+    for i in range(K):
+        t[0, i, tok[0, i]] = 0.0
+    t[0, K] = np.log(np.array([0.1, 0.2, 0.3, 0.15, 0.15, 0.1], dtype=np.float32))
+    r = run_onehot(oracle, t, tok, np.array([[0.999, 0.5, 0.0]], np.float32), np.array([0.35], np.float32))
+    assert r["accepted_len"][0] == K
+    assert r["next_token"][0] == 2          # cumulative 0.1, 0.3, 0.6: first sum > 0.35 is token 2

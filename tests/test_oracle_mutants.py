@@ -34,6 +34,8 @@ MUTANTS = {
     "cdf_not_strict_start": ("      if (c > thr) {", "      if (c >= thr) {"),
     "temperature_ignored": ("p[v] = load_elem(logits, dtype, base + v) / temperature;",
                             "p[v] = load_elem(logits, dtype, base + v);"),
+    "point_mass_keeps_x": ("        q[x] = 1.0;\n", "        q[x] = 0.0;\n"),
+    "point_mass_on_wrong_token": ("        q[x] = 1.0;\n", "        q[(x + 1) % V] = 1.0;\n"),
     "draft_row_index": ("softmax_row(draft_logits, logits_dtype, ((int64_t)nb * K + i) * V",
                         "softmax_row(draft_logits, logits_dtype, ((int64_t)nb * K + 0) * V"),
 }
