@@ -125,6 +125,11 @@ LA_API la_status la_verify_attention(
  *  drawn from the extra target row p_K.  Drawing is inverse-CDF in token
  *  order: the first v whose running sum exceeds u_sample * total.
  *
+ *  draft_logits == NULL: the drafter proposed tokens without a distribution
+ *  (the prompt-lookup / n-gram drafts of Section 4, Setup), i.e. q_i is the
+ *  point mass at x_i: x_i is accepted when u_accept[i] < p_i(x_i), and after
+ *  a rejection next_token is drawn from p_n with x_n removed.
+ *
  *  The accept test runs in fp32; the resampling row is evaluated in fp64.
  * ------------------------------------------------------------------------- */
 typedef struct {
@@ -140,7 +145,7 @@ LA_API la_status la_spec_accept_workspace(const la_accept_desc *desc, size_t *by
 LA_API la_status la_spec_accept(
     const la_accept_desc *desc,
     const void *target_logits,   /* dev [NB, K+1, V]                                      */
-    const void *draft_logits,    /* dev [NB, K,   V]                                      */
+    const void *draft_logits,    /* dev [NB, K,   V], or NULL: point-mass draft at draft_tokens */
     const int32_t *draft_tokens, /* dev [NB, K]  each in 0..V-1                           */
     const float *u_accept,       /* dev [NB, K]  uniforms in [0,1)                        */
     const float *u_sample,       /* dev [NB]     uniforms in [0,1)                        */

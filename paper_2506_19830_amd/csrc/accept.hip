@@ -183,7 +183,8 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(const AcceptPar
   int i0 = 0;
   for (; i0 < p.K; i0 += kPass) {   // a later pass cannot lower the first rejection found in an earlier one
     const int cnt = min(kPass, p.K - i0);
-    for (int slot = wave; slot < 2 * cnt; slot += kThreads / 64) {   // wavefront per row
+    const int n_which = p.draft ? 2 : 1;   // point-mass draft: there are no draft rows
+    for (int slot = wave; slot < n_which * cnt; slot += kThreads / 64) {   // wavefront per row
       const int which = slot >= cnt, j = slot - which * cnt;
       const int rw = which ? n_t + nb * p.K + i0 + j : nb * (p.K + 1) + i0 + j;
       float m, z;
@@ -195,9 +196,12 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(const AcceptPar
       const int i = i0 + tid;
       const int x = p.tokens[(size_t)nb * p.K + i];
       const float tx = load_logit<BF16>(p.target, ((size_t)nb * (p.K + 1) + i) * p.V + x);
-      const float dx = load_logit<BF16>(p.draft, ((size_t)nb * p.K + i) * p.V + x);
       const float px = __builtin_amdgcn_exp2f((tx - sm[0][tid]) * p.inv_temp_log2) / sz[0][tid];
-      const float qx = __builtin_amdgcn_exp2f((dx - sm[1][tid]) * p.inv_temp_log2) / sz[1][tid];
+      float qx = 1.0f;   // point-mass draft at x
+      if (p.draft) {
+        const float dx = load_logit<BF16>(p.draft, ((size_t)nb * p.K + i) * p.V + x);
+        qx = __builtin_amdgcn_exp2f((dx - sm[1][tid]) * p.inv_temp_log2) / sz[1][tid];
+      }
       const float u = p.u_accept[(size_t)nb * p.K + i];
       if (!(u * qx < px)) atomicMin(&s_first, i);
       if (c == 0 && p.ratio) p.ratio[(size_t)nb * p.K + i] = px / qx;
@@ -209,7 +213,7 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(const AcceptPar
   // exact maxima of the resampling rows: target row n and draft row n (both folded in the pass that found n), or
   // target row K alone when everything was accepted
   if (n < p.K) {
-    if (tid == 0) s_top[0] = sm[0][n - i0], s_top[1] = sm[1][n - i0];
+    if (tid == 0) s_top[0] = sm[0][n - i0], s_top[1] = p.draft ? sm[1][n - i0] : 0.f;
   } else if (wave == 0) {
     float m, z;
     wave_fold_row(p, nb * (p.K + 1) + p.K, lane, m, z);
@@ -233,7 +237,7 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(const AcceptPar
     const int v = v0 + tid * kFinePer + e;
     if (v < v1) {
       st += mass64(load_logit<BF16>(p.target, trow + v), mt_t, p.inv_temp);
-      if (n < p.K) sq += mass64(load_logit<BF16>(p.draft, drow + v), mq_t, p.inv_temp);
+      if (n < p.K && p.draft) sq += mass64(load_logit<BF16>(p.draft, drow + v), mq_t, p.inv_temp);
     }
   }
   st = wave_sum(st);
@@ -269,9 +273,10 @@ struct ResidCtx {
   size_t trow, drow;
   double mt, mq, zt, zq, inv_temp;
   bool has_draft;
+  int removed;   // point-mass draft after a rejection: the drafted token, which has no residual mass; else -1
   __device__ __forceinline__ void eval(int v, double &r, double &pm) const {
     pm = mass64(load_logit<BF16>(target, trow + v), mt, inv_temp) / zt;
-    r = pm;
+    r = v == removed ? 0.0 : pm;
     if (has_draft) {
       const double qm = mass64(load_logit<BF16>(draft, drow + v), mq, inv_temp) / zq;
       r = pm - qm;
@@ -287,7 +292,8 @@ __device__ __forceinline__ ResidCtx<BF16> make_ctx(const AcceptParams &p, int nb
   x.target = p.target;
   x.draft = p.draft;
   x.trow = ((size_t)nb * (p.K + 1) + n) * p.V;
-  x.has_draft = n < p.K;
+  x.has_draft = n < p.K && p.draft;
+  x.removed = (n < p.K && !p.draft) ? p.tokens[(size_t)nb * p.K + n] : -1;
   x.drow = x.has_draft ? ((size_t)nb * p.K + n) * p.V : 0;
   x.inv_temp = p.inv_temp;
   x.mt = (double)p.rowmax[2 * nb] * p.inv_temp;
@@ -421,7 +427,7 @@ hipError_t launch_typed(const AcceptParams &p, hipStream_t stream) {
   const bool vec = ((size_t)p.V * (BF16 ? 2 : 4)) % 16 == 0;
   {
     ProfileScope scope(SLOT_ACCEPT_STATS, stream);
-    const dim3 grid(p.n_chunks, p.NB * (2 * p.K + 1));
+    const dim3 grid(p.n_chunks, p.draft ? p.NB * (2 * p.K + 1) : p.NB * (p.K + 1));
     if (vec)
       hipLaunchKernelGGL((accept_stats_kernel<BF16, true>), grid, dim3(kThreads), 0, stream, p);
     else

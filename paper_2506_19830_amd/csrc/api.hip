@@ -294,9 +294,10 @@ la_status la_spec_accept(const la_accept_desc *desc, const void *target_logits, 
                          size_t workspace_bytes, void *hip_stream) {
   la_status st = validate_accept(desc);
   if (st != LA_OK) return st;
-  if (!target_logits || !draft_logits || !draft_tokens || !u_accept || !u_sample || !accepted_len || !next_token)
+  if (!target_logits || !draft_tokens || !u_accept || !u_sample || !accepted_len || !next_token)
     return LA_ERR_INVALID_ARG;
-  if (!aligned16(target_logits) || !aligned16(draft_logits) || !aligned16(workspace)) return LA_ERR_INVALID_ARG;
+  if (!aligned16(target_logits) || (draft_logits && !aligned16(draft_logits)) || !aligned16(workspace))
+    return LA_ERR_INVALID_ARG;
   AcceptParams p;
   memset(&p, 0, sizeof p);
   const size_t need = accept_workspace_bytes(desc->num_branches, desc->num_draft, desc->vocab,

@@ -133,10 +133,13 @@ class AcceptCase:
     draft_noise_std: Optional[float] = 1.0   # draft = target + N(0, noise^2); None => independent N(0, target_std^2)
     temperature: float = 1.0
     seed: int = 0
+    point_mass: bool = False      # the drafter gives tokens only (prompt-lookup drafts): no draft logits
+    peak: float = 16.0            # point_mass: added to the target logit of every drafted token, so that p(x) is O(0.1..1)
 
     def algorithmic_bytes(self) -> float:
         sz = {"f32": 4, "bf16": 2}[self.logits_dtype]
-        return float(self.NB * (2 * self.K + 1) * self.V * sz)
+        rows = (self.K + 1) if self.point_mass else (2 * self.K + 1)
+        return float(self.NB * rows * self.V * sz)
 
 
 def config(n: int) -> Tuple[AttnCase, AcceptCase]:
@@ -234,7 +237,8 @@ def _decode_for_sampling(bits: np.ndarray, dtype: str) -> np.ndarray:
 
 
 def make_accept_inputs(case: AcceptCase) -> Dict[str, np.ndarray]:
-    """Target/draft logits, drafted tokens and the uniforms of one accept call.
+    """Target/draft logits, drafted tokens and the uniforms of one accept call (``draft_logits`` is None for a
+    point-mass case).
 
     target ~ N(0, target_std^2); draft = target + N(0, noise^2) (or an
     independent N(0, target_std^2) when ``draft_noise_std`` is None).  The K
@@ -244,6 +248,17 @@ def make_accept_inputs(case: AcceptCase) -> Dict[str, np.ndarray]:
     """
     c = case
     t = _rng(c.seed, 100).standard_normal((c.NB, c.K + 1, c.V), dtype=np.float32) * np.float32(c.target_std)
+    u_acc = _rng(c.seed, 103).random((c.NB, c.K), dtype=np.float32)
+    u_smp = _rng(c.seed, 104).random((c.NB,), dtype=np.float32)
+    if c.point_mass:
+        # drafted tokens come without a distribution; the target row is peaked at them, as a language model's is at
+        # a token that a lookup in the context proposes
+        tokens = _rng(c.seed, 102).integers(0, c.V, size=(c.NB, c.K)).astype(np.int32)
+        for nb in range(c.NB):
+            for i in range(c.K):
+                t[nb, i, tokens[nb, i]] += np.float32(c.peak)
+        return {"target_logits": encode(t, c.logits_dtype), "draft_logits": None, "draft_tokens": tokens,
+                "u_accept": u_acc, "u_sample": u_smp}
     if c.draft_noise_std is None:
         d = _rng(c.seed, 101).standard_normal((c.NB, c.K, c.V), dtype=np.float32) * np.float32(c.target_std)
     else:
@@ -257,8 +272,6 @@ def make_accept_inputs(case: AcceptCase) -> Dict[str, np.ndarray]:
         row = _decode_for_sampling(d_bits[nb], c.logits_dtype) / c.temperature
         gumbel = -np.log(-np.log(g.random(row.shape)))
         tokens[nb] = np.argmax(row + gumbel, axis=-1)
-    u_acc = _rng(c.seed, 103).random((c.NB, c.K), dtype=np.float32)
-    u_smp = _rng(c.seed, 104).random((c.NB,), dtype=np.float32)
     return {"target_logits": t_bits, "draft_logits": d_bits, "draft_tokens": tokens, "u_accept": u_acc,
             "u_sample": u_smp}
 

@@ -74,3 +74,29 @@ def test_identical_models_accept_everything():
     got = run_accept(case, inp)
     np.testing.assert_array_equal(got["accepted_len"], case.K)
     np.testing.assert_allclose(got["ratio"], 1.0, rtol=1e-6)
+
+
+# ------------------------------------------------------------------------------------------ point-mass draft
+POINT_MASS_CASES = [
+    W.AcceptCase("pm_small", 400, 4, 512, "f32", target_std=2.0, point_mass=True, peak=7.0, seed=11),
+    W.AcceptCase("pm_odd_vocab", 64, 3, 8193, "bf16", point_mass=True, peak=12.0, seed=12),
+    W.AcceptCase("pm_k1_tiny", 200, 1, 3, "f32", target_std=1.0, point_mass=True, peak=1.0, seed=13),
+    W.AcceptCase("pm_temperature", 100, 4, 4096, "f32", temperature=0.6, point_mass=True, peak=6.0, seed=14),
+    W.AcceptCase("pm_long_draft", 3, 70, 700, "f32", target_std=1.0, point_mass=True, peak=12.0, seed=15),
+    # the paper's setting at full vocabulary: 8 drafted tokens, temperature 0.6
+    W.AcceptCase("pm_vocab152k_k8", 8, 8, 152064, "bf16", temperature=0.6, point_mass=True, peak=11.0, seed=16),
+    W.AcceptCase("pm_vocab152k_k8_nb32", 32, 8, 152064, "bf16", point_mass=True, seed=17),
+]
+
+
+@pytest.mark.parametrize("case", POINT_MASS_CASES, ids=lambda c: c.name)
+def test_point_mass_draft(oracle, case):
+    """draft_logits = NULL: q is the point mass at the drafted token (prompt-lookup drafts).  Accept iff u < p(x);
+    after a rejection the token comes from p with x removed, so it can never be x."""
+    got, ref = check(oracle, case)
+    inp = W.make_accept_inputs(case)
+    rejected = got["accepted_len"] < case.K
+    x_n = inp["draft_tokens"][np.arange(case.NB)[rejected], got["accepted_len"][rejected]]
+    assert (got["next_token"][rejected] != x_n).all()
+    if case.name in ("pm_small", "pm_vocab152k_k8_nb32"):
+        assert (ref["accepted_len"] > 0).any() and (ref["accepted_len"] < case.K).any()

@@ -70,3 +70,17 @@ def test_drafted_tokens_follow_the_draft_distribution():
     # mean one-hot minus mean probability -> 0
     onehot = np.eye(6)[inp["draft_tokens"][:, 0]]
     assert np.abs(onehot.mean(0) - q.mean(0)).max() < 0.012
+
+
+def test_point_mass_accept_recipe():
+    """Prompt-lookup style drafts: tokens without draft logits, the target row peaked at each drafted token."""
+    c = W.AcceptCase("pm", 6, 3, 1000, "f32", point_mass=True, peak=9.0, seed=3)
+    a, b = W.make_accept_inputs(c), W.make_accept_inputs(c)
+    assert a["draft_logits"] is None
+    np.testing.assert_array_equal(a["target_logits"], b["target_logits"])
+    np.testing.assert_array_equal(a["draft_tokens"], b["draft_tokens"])
+    t, tok = a["target_logits"], a["draft_tokens"]
+    assert t.shape == (6, 4, 1000) and tok.shape == (6, 3) and (tok >= 0).all() and (tok < 1000).all()
+    picked = np.take_along_axis(t[:, :3, :], tok[:, :, None], axis=2)[..., 0]
+    assert (picked > np.median(t) + 3.0).all()
+    assert c.algorithmic_bytes() == 6 * 4 * 1000 * 4
