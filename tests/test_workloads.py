@@ -82,5 +82,5 @@ def test_point_mass_accept_recipe():
     t, tok = a["target_logits"], a["draft_tokens"]
     assert t.shape == (6, 4, 1000) and tok.shape == (6, 3) and (tok >= 0).all() and (tok < 1000).all()
     picked = np.take_along_axis(t[:, :3, :], tok[:, :, None], axis=2)[..., 0]
-    assert (picked > np.median(t) + 3.0).all()
+    assert picked.mean() > 6.0 and abs(float(np.median(t))) < 0.5      # N(0, 3^2) + 9 at the drafted tokens
     assert c.algorithmic_bytes() == 6 * 4 * 1000 * 4
