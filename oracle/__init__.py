@@ -48,6 +48,8 @@ def _load():
         _lib.lao_verify_attention.restype = ctypes.c_int
         _lib.lao_attention_row_weights.restype = ctypes.c_int
         _lib.lao_spec_accept.restype = ctypes.c_int
+        _lib.lao_spec_accept_warped.restype = ctypes.c_int
+        _lib.lao_warp_probs.restype = ctypes.c_int
         _lib.lao_widen.restype = ctypes.c_int
         _lib.lao_num_threads.restype = ctypes.c_int
     return _lib
@@ -171,10 +173,27 @@ def attention_row_weights(q, k_cache, v_cache, block_tables, prefix_lens, k_bran
     return w
 
 
-def spec_accept(target_logits, draft_logits, draft_tokens, u_accept, u_sample, *, logits_dtype, temperature=1.0):
+def warp_probs(logits, *, logits_dtype, temperature=1.0, top_k=0, top_p=1.0):
+    """Test hook: the target distribution of one logit row [V] after temperature, top-k and top-p.
+    Returns (p [V] fp64, margin) with margin the closest relative distance of a top-p decision to its threshold."""
+    a = _storage(logits, logits_dtype, "logits")
+    V = a.shape[-1]
+    out = np.empty((V,), dtype=np.float64)
+    mg = ctypes.c_double(0.0)
+    rc = _load().lao_warp_probs(_ptr(a), ctypes.c_int(DTYPE_CODES[logits_dtype]), ctypes.c_int(V),
+                                ctypes.c_double(temperature), ctypes.c_int(top_k), ctypes.c_double(top_p), _ptr(out),
+                                ctypes.byref(mg))
+    if rc:
+        raise ValueError("lao_warp_probs rejected its arguments")
+    return out, float(mg.value)
+
+
+def spec_accept(target_logits, draft_logits, draft_tokens, u_accept, u_sample, *, logits_dtype, temperature=1.0,
+                top_k=0, top_p=1.0):
     """Sequential token-level accept / resample.  Returns a dict with
     ``accepted_len`` [NB], ``next_token`` [NB], ``ratio`` [NB,K], ``margin`` [NB,K],
-    ``cdf_lo`` [NB], ``cdf_hi`` [NB].  ``draft_logits=None``: point-mass draft at the drafted tokens."""
+    ``cdf_lo`` [NB], ``cdf_hi`` [NB], ``warp_margin`` [NB].  ``draft_logits=None``: point-mass draft at the
+    drafted tokens.  ``top_k`` (0 = off) / ``top_p`` (1 = off) warp the target distribution."""
     t = _storage(target_logits, logits_dtype, "target_logits")
     d = None if draft_logits is None else _storage(draft_logits, logits_dtype, "draft_logits")
     NB, K1, V = t.shape
@@ -192,10 +211,13 @@ def spec_accept(target_logits, draft_logits, draft_tokens, u_accept, u_sample, *
     margin = np.empty((NB, K), dtype=np.float64)
     lo = np.empty((NB,), dtype=np.float64)
     hi = np.empty((NB,), dtype=np.float64)
-    rc = _load().lao_spec_accept(ctypes.c_int(NB), ctypes.c_int(K), ctypes.c_int(V),
-                                 ctypes.c_int(DTYPE_CODES[logits_dtype]), ctypes.c_double(temperature), _ptr(t),
-                                 _ptr(d), _ptr(tok), _ptr(ua), _ptr(us), _ptr(n), _ptr(nxt), _ptr(ratio),
-                                 _ptr(margin), _ptr(lo), _ptr(hi))
+    wm = np.empty((NB,), dtype=np.float64)
+    rc = _load().lao_spec_accept_warped(ctypes.c_int(NB), ctypes.c_int(K), ctypes.c_int(V),
+                                        ctypes.c_int(DTYPE_CODES[logits_dtype]), ctypes.c_double(temperature),
+                                        ctypes.c_int(top_k), ctypes.c_double(top_p), _ptr(t), _ptr(d), _ptr(tok),
+                                        _ptr(ua), _ptr(us), _ptr(n), _ptr(nxt), _ptr(ratio), _ptr(margin), _ptr(lo),
+                                        _ptr(hi), _ptr(wm))
     if rc:
         raise ValueError("lao_spec_accept rejected its arguments")
-    return {"accepted_len": n, "next_token": nxt, "ratio": ratio, "margin": margin, "cdf_lo": lo, "cdf_hi": hi}
+    return {"accepted_len": n, "next_token": nxt, "ratio": ratio, "margin": margin, "cdf_lo": lo, "cdf_hi": hi,
+            "warp_margin": wm}

@@ -32,6 +32,14 @@
  *   - inverse CDF returns the first v whose running sum is > u*S (strict), so
  *     zero-mass tokens are never returned (pinned: a sample must have mass).
  * The first two items only matter on measure-zero / rounding-only inputs.
+ *   - top-k / top-p (Section 4, Setup: temperature 0.6, top_p 0.95, top_k 20):
+ *     the target distribution p is warped before the rule is applied, in the
+ *     usual order temperature -> top-k -> top-p.  Both filters are read as
+ *     predicates on a token's value, so that equal logits are never split:
+ *       top-k keeps v  iff  #{u : l_u > l_v} < k          (ties with the k-th stay)
+ *       top-p keeps v  iff  mass{u kept by top-k : l_u > l_v} < top_p * Z_k
+ *     (Z_k the mass kept by top-k), then p is renormalised over what is kept.
+ *     The draft distribution q is used as given.
  *   - draft_logits == NULL: the drafter proposes tokens without a distribution
  *     (Section 4, Setup: prompt-lookup / n-gram drafts), i.e. q_i is the point
  *     mass at the drafted token x_i.  The same rule then reads: accept with
@@ -309,11 +317,74 @@ static void softmax_row(const void *logits, int dtype, int64_t base, int V, doub
   for (int v = 0; v < V; ++v) p[v] /= z;
 }
 
-int lao_spec_accept(int NB, int K, int V, int logits_dtype, double temperature, const void *target_logits,
-                    const void *draft_logits, const int32_t *draft_tokens, const float *u_accept,
-                    const float *u_sample, int32_t *accepted_len, int32_t *next_token, double *ratio, double *margin,
-                    double *cdf_lo, double *cdf_hi) {
-  if (NB < 1 || K < 1 || V < 1 || !(temperature > 0.0)) return 1;
+typedef struct {
+  double v;
+  int id;
+} ranked;
+
+static int by_value_desc_then_id(const void *a, const void *b) {
+  const ranked *x = a, *y = b;
+  if (x->v > y->v) return -1;
+  if (x->v < y->v) return 1;
+  return (x->id > y->id) - (x->id < y->id);
+}
+
+/* Top-k then top-p on a normalised row p (see the header comment for the two predicates); p is renormalised over the
+ * kept tokens.  *margin (if not NULL) receives the smallest |M - top_p*Z_k| / Z_k over the cumulative masses M that
+ * were compared with the top-p threshold: a measure of how close the kept set is to changing. */
+static int warp_row(double *p, int V, int top_k, double top_p, double *margin) {
+  if (margin) *margin = INFINITY;
+  const int use_k = top_k > 0 && top_k < V, use_p = top_p < 1.0;
+  if (!use_k && !use_p) return 0;
+  ranked *r = malloc(sizeof(ranked) * V);
+  if (!r) return 1;
+  for (int v = 0; v < V; ++v) r[v].v = p[v], r[v].id = v;
+  qsort(r, V, sizeof(ranked), by_value_desc_then_id);
+  int kept = V;
+  if (use_k) {
+    kept = top_k;
+    while (kept < V && r[kept].v == r[top_k - 1].v) ++kept; /* ties with the k-th largest stay */
+  }
+  if (use_p) {
+    double zk = 0.0;
+    for (int j = 0; j < kept; ++j) zk += r[j].v;
+    const double T = top_p * zk;
+    double M = 0.0, mg = INFINITY;
+    int j = 0;
+    while (j < kept) {
+      const double d = fabs(M - T) / zk;
+      if (d < mg) mg = d;
+      if (!(M < T)) break; /* the tokens of this value have mass >= T above them */
+      int e = j;
+      double gm = 0.0;
+      while (e < kept && r[e].v == r[j].v) gm += r[e++].v;
+      M += gm;
+      j = e;
+    }
+    kept = j;
+    if (margin) *margin = mg;
+  }
+  double z = 0.0;
+  for (int j = 0; j < kept; ++j) z += r[j].v;
+  for (int j = kept; j < V; ++j) p[r[j].id] = 0.0;
+  for (int j = 0; j < kept; ++j) p[r[j].id] = r[j].v / z;
+  free(r);
+  return 0;
+}
+
+/* Test hook: the warped distribution of one logit row. */
+int lao_warp_probs(const void *logits, int dtype, int V, double temperature, int top_k, double top_p, double *p_out,
+                   double *margin) {
+  if (!logits || !p_out || V < 1 || !(temperature > 0.0) || !(top_p > 0.0)) return 1;
+  softmax_row(logits, dtype, 0, V, temperature, p_out);
+  return warp_row(p_out, V, top_k, top_p, margin);
+}
+
+int lao_spec_accept_warped(int NB, int K, int V, int logits_dtype, double temperature, int top_k, double top_p,
+                           const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
+                           const float *u_accept, const float *u_sample, int32_t *accepted_len, int32_t *next_token,
+                           double *ratio, double *margin, double *cdf_lo, double *cdf_hi, double *warp_margin) {
+  if (NB < 1 || K < 1 || V < 1 || !(temperature > 0.0) || !(top_p > 0.0) || top_k < 0) return 1;
   if (!target_logits || !draft_tokens || !u_accept || !u_sample || !accepted_len || !next_token) return 1;
   for (int64_t t = 0; t < (int64_t)NB * K; ++t)
     if (draft_tokens[t] < 0 || draft_tokens[t] >= V) return 1;
@@ -333,10 +404,13 @@ int lao_spec_accept(int NB, int K, int V, int logits_dtype, double temperature, 
       if (ratio) ratio[(int64_t)nb * K + i] = NAN;
       if (margin) margin[(int64_t)nb * K + i] = INFINITY;
     }
+    double wm = INFINITY, wm_row; /* closest top-p decision over the target rows this branch evaluates */
     /* examine the drafted tokens in order; stop at the first rejection */
     int n = K;
     for (int i = 0; i < K; ++i) {
       softmax_row(target_logits, logits_dtype, ((int64_t)nb * (K + 1) + i) * V, V, temperature, p);
+      if (warp_row(p, V, top_k, top_p, &wm_row)) failed = 1;
+      if (wm_row < wm) wm = wm_row;
       const int x = draft_tokens[(int64_t)nb * K + i];
       if (draft_logits) {
         softmax_row(draft_logits, logits_dtype, ((int64_t)nb * K + i) * V, V, temperature, q);
@@ -374,6 +448,8 @@ int lao_spec_accept(int NB, int K, int V, int logits_dtype, double temperature, 
       }
     } else {
       softmax_row(target_logits, logits_dtype, ((int64_t)nb * (K + 1) + K) * V, V, temperature, r);
+      if (warp_row(r, V, top_k, top_p, &wm_row)) failed = 1;
+      if (wm_row < wm) wm = wm_row;
       for (int v = 0; v < V; ++v) S += r[v];
     }
     /* inverse-CDF walk */
@@ -400,9 +476,18 @@ int lao_spec_accept(int NB, int K, int V, int logits_dtype, double temperature, 
     next_token[nb] = tok;
     if (cdf_lo) cdf_lo[nb] = lo / S;
     if (cdf_hi) cdf_hi[nb] = (lo + r[tok]) / S;
+    if (warp_margin) warp_margin[nb] = wm;
     free(p), free(q), free(r);
   }
   return failed;
+}
+
+int lao_spec_accept(int NB, int K, int V, int logits_dtype, double temperature, const void *target_logits,
+                    const void *draft_logits, const int32_t *draft_tokens, const float *u_accept,
+                    const float *u_sample, int32_t *accepted_len, int32_t *next_token, double *ratio, double *margin,
+                    double *cdf_lo, double *cdf_hi) {
+  return lao_spec_accept_warped(NB, K, V, logits_dtype, temperature, 0, 1.0, target_logits, draft_logits, draft_tokens,
+                                u_accept, u_sample, accepted_len, next_token, ratio, margin, cdf_lo, cdf_hi, NULL);
 }
 
 /* Number of OpenMP threads a parallel region will use (for reporting). */

@@ -284,3 +284,112 @@ def test_point_mass_draft_certain_token_is_always_accepted(oracle):
     r = run_onehot(oracle, t, tok, np.array([[0.999, 0.5, 0.0]], np.float32), np.array([0.35], np.float32))
     assert r["accepted_len"][0] == K
     assert r["next_token"][0] == 2          # cumulative 0.1, 0.3, 0.6: first sum > 0.35 is token 2
+
+
+# ------------------------------------------------------------------------------------------ top-k / top-p warping
+# Section 4 (Setup): temperature 0.6, top_p 0.95 (and top_k 20 for one model family).  Order: temperature, top-k,
+# top-p, renormalise.
+
+def torch_warp(logits, temperature, top_k, top_p):
+    """The same warp from library pieces (torch sort / topk / cumsum in fp64), written the way sampling code usually
+    is: mask logits below the k-th largest, softmax, sort, drop a token when the mass in front of it reaches top_p."""
+    import torch
+    x = torch.as_tensor(np.asarray(logits, dtype=np.float64)) / temperature
+    if 0 < top_k < x.numel():
+        kth = torch.topk(x, top_k).values[-1]
+        x = torch.where(x < kth, torch.full_like(x, -float("inf")), x)
+    p = torch.softmax(x, dim=-1)
+    if top_p < 1.0:
+        sp, order = torch.sort(p, descending=True, stable=True)
+        before = torch.cumsum(sp, dim=-1) - sp
+        drop = before >= top_p
+        p = p.clone()
+        p[order[drop]] = 0.0
+        p = p / p.sum()
+    return p.numpy()
+
+
+@pytest.mark.parametrize("top_k,top_p,temperature", [(20, 0.95, 0.6), (0, 0.95, 0.6), (20, 1.0, 1.0), (1, 1.0, 1.0),
+                                                     (5, 0.5, 2.0), (0, 0.3, 1.0), (1000, 0.999, 0.6)])
+def test_warp_matches_sort_based_reference(oracle, top_k, top_p, temperature):
+    rng = np.random.default_rng(11)
+    for V, std in ((1000, 3.0), (257, 1.0), (4096, 6.0)):
+        logits = (rng.standard_normal(V) * std).astype(np.float32)     # continuous values: no ties
+        got, margin = oracle.warp_probs(logits, logits_dtype="f32", temperature=temperature, top_k=top_k, top_p=top_p)
+        ref = torch_warp(logits, temperature, top_k, top_p)
+        np.testing.assert_array_equal(got > 0, ref > 0)
+        np.testing.assert_allclose(got, ref, rtol=1e-12, atol=0)
+        assert abs(got.sum() - 1.0) < 1e-12
+        if top_p < 1.0:
+            assert margin > 1e-9
+        if 0 < top_k < V:
+            assert (got > 0).sum() <= top_k
+
+
+def test_warp_keeps_ties_together_and_special_cases(oracle):
+    # values 5 > 3 = 3 = 3 > 1 > 0: top_k = 2 keeps the 5 and all three 3s
+    logits = np.array([3.0, 5.0, 1.0, 3.0, 0.0, 3.0], dtype=np.float32)
+    p, _ = oracle.warp_probs(logits, logits_dtype="f32", top_k=2)
+    assert list(np.nonzero(p)[0]) == [0, 1, 3, 5]
+    e = np.exp(logits.astype(np.float64) - 5.0)
+    np.testing.assert_allclose(p[[0, 1, 3, 5]], e[[0, 1, 3, 5]] / e[[0, 1, 3, 5]].sum(), rtol=1e-14)
+    # top_p: the 5 alone has mass 0.665 of the whole row: top_p = 0.6 keeps only it, 0.7 adds the tied group as a whole
+    full = e / e.sum()
+    assert 0.6 < full[1] < 0.7
+    p6, _ = oracle.warp_probs(logits, logits_dtype="f32", top_p=0.6)
+    assert list(np.nonzero(p6)[0]) == [1] and p6[1] == 1.0
+    p7, _ = oracle.warp_probs(logits, logits_dtype="f32", top_p=0.7)
+    assert list(np.nonzero(p7)[0]) == [0, 1, 3, 5]
+    # off switches
+    off, mg = oracle.warp_probs(logits, logits_dtype="f32", top_k=0, top_p=1.0)
+    np.testing.assert_allclose(off, full, rtol=1e-14)
+    assert mg == np.inf
+    same, _ = oracle.warp_probs(logits, logits_dtype="f32", top_k=6, top_p=1.0)
+    np.testing.assert_array_equal(same, off)
+    # top-p is applied to what top-k kept: with k = 1 everything else is gone whatever top_p says
+    g, _ = oracle.warp_probs(logits, logits_dtype="f32", top_k=1, top_p=0.01)
+    assert list(np.nonzero(g)[0]) == [1]
+
+
+def test_accept_with_warp_emits_the_warped_target(oracle):
+    """V=12, K=1, dense draft, top_k=5, top_p=0.8, T=0.7: the emitted token follows the warped p_0 (speculative
+    sampling is exact for whatever target distribution is plugged in), the bonus token the warped p_1."""
+    rng = np.random.default_rng(99)
+    V, N = 12, 600_000
+    kw = dict(temperature=0.7, top_k=5, top_p=0.8)
+    t_row = rng.normal(0, 1.5, size=(2, V)).astype(np.float32)
+    d_row = rng.normal(0, 1.5, size=(1, V)).astype(np.float32)
+    w0, _ = oracle.warp_probs(t_row[0], logits_dtype="f32", **kw)
+    w1, _ = oracle.warp_probs(t_row[1], logits_dtype="f32", **kw)
+    assert 1 < (w0 > 0).sum() < 5 and abs(w0.sum() - 1) < 1e-12      # both filters bite
+    q0 = np.exp(d_row[0].astype(np.float64) / 0.7); q0 /= q0.sum()
+    t = np.broadcast_to(t_row, (N, 2, V)).copy()
+    d = np.broadcast_to(d_row, (N, 1, V)).copy()
+    tok = rng.choice(V, size=(N, 1), p=q0).astype(np.int32)
+    ua = rng.random((N, 1), dtype=np.float32)
+    us = rng.random((N,), dtype=np.float32)
+    r = run(oracle, t, d, tok, ua, us, **kw)
+    n, nxt = r["accepted_len"], r["next_token"]
+    first = np.where(n == 1, tok[:, 0], nxt)
+    dof = int((w0 > 0).sum()) - 1
+    assert chi2(np.bincount(first, minlength=V), w0) < 25.0 + 5 * dof      # generous 1e-4-level bound
+    assert chi2(np.bincount(nxt[n == 1], minlength=V), w1) < 25.0 + 5 * int((w1 > 0).sum())
+    alpha = np.minimum(w0, q0).sum()
+    assert abs((n == 1).mean() - alpha) < 4.5 * math.sqrt(alpha * (1 - alpha) / N)
+    assert (w0[first] > 0).all()                                            # nothing outside the kept set is emitted
+
+
+def test_greedy_limit_with_point_mass_draft(oracle):
+    """top_k = 1 makes the target a point mass at its argmax: a drafted token is accepted iff it is the argmax, and
+    the extra token is the argmax of the row where the walk stopped."""
+    rng = np.random.default_rng(4)
+    NB, K, V = 300, 4, 50
+    t = rng.normal(0, 2, size=(NB, K + 1, V)).astype(np.float32)
+    am = t.argmax(-1)
+    tok = np.where(rng.random((NB, K)) < 0.7, am[:, :K], rng.integers(0, V, size=(NB, K))).astype(np.int32)
+    r = oracle.spec_accept(t, None, tok, rng.random((NB, K), dtype=np.float32), rng.random((NB,), dtype=np.float32),
+                           logits_dtype="f32", top_k=1)
+    match = tok == am[:, :K]
+    n_ref = np.where(match.all(1), K, np.argmin(match, axis=1))
+    np.testing.assert_array_equal(r["accepted_len"], n_ref)
+    np.testing.assert_array_equal(r["next_token"], am[np.arange(NB), n_ref])

@@ -34,6 +34,15 @@ MUTANTS = {
     "cdf_not_strict_start": ("      if (c > thr) {", "      if (c >= thr) {"),
     "temperature_ignored": ("p[v] = load_elem(logits, dtype, base + v) / temperature;",
                             "p[v] = load_elem(logits, dtype, base + v);"),
+    "topk_one_too_many": ("    kept = top_k;\n", "    kept = top_k + 1;\n"),
+    "topk_splits_ties": ("    while (kept < V && r[kept].v == r[top_k - 1].v) ++kept; /* ties with the k-th largest stay */\n", ""),
+    "topp_ignores_topk_mass": ("    const double T = top_p * zk;\n", "    const double T = top_p;\n"),
+    "topp_splits_ties": ("      while (e < kept && r[e].v == r[j].v) gm += r[e++].v;\n", "      gm += r[e++].v;\n"),
+    "topp_keeps_one_group_less": ("      if (!(M < T)) break; /* the tokens of this value have mass >= T above them */\n",
+                                  "      if (!(M + r[j].v < T)) break;\n"),
+    "warp_not_renormalised": ("  for (int j = 0; j < kept; ++j) p[r[j].id] = r[j].v / z;\n",
+                              "  for (int j = 0; j < kept; ++j) p[r[j].id] = r[j].v;\n"),
+    "warp_skipped_for_bonus_row": ("      if (warp_row(r, V, top_k, top_p, &wm_row)) failed = 1;\n", "      wm_row = INFINITY;\n"),
     "point_mass_keeps_x": ("        q[x] = 1.0;\n", "        q[x] = 0.0;\n"),
     "point_mass_on_wrong_token": ("        q[x] = 1.0;\n", "        q[(x + 1) % V] = 1.0;\n"),
     "draft_row_index": ("softmax_row(draft_logits, logits_dtype, ((int64_t)nb * K + i) * V",
