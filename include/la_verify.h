@@ -130,7 +130,12 @@ LA_API la_status la_verify_attention(
  *  point mass at x_i: x_i is accepted when u_accept[i] < p_i(x_i), and after
  *  a rejection next_token is drawn from p_n with x_n removed.
  *
- *  The accept test runs in fp32; the resampling row is evaluated in fp64.
+ *  top_k / top_p warp the target distributions p_i only (Section 4, Setup:
+ *  temperature 0.6, top_p 0.95, top_k 20), in the order temperature, top-k,
+ *  top-p; the draft distribution is used as given.
+ *
+ *  The accept test runs in fp32; the resampling row and the top-p masses are
+ *  evaluated in fp64.
  * ------------------------------------------------------------------------- */
 typedef struct {
   int32_t num_branches;   /* NB >= 1                                   */
@@ -138,6 +143,11 @@ typedef struct {
   int32_t vocab;          /* V  >= 1                                   */
   int32_t logits_dtype;   /* LA_F32 or LA_BF16                          */
   float temperature;      /* T > 0, divides every logit                 */
+  int32_t top_k;          /* 0 = off; else the target keeps a token iff fewer than top_k tokens
+                             of its row have a larger logit (ties with the k-th stay)            */
+  float top_p;            /* in (0, 1]; 1 = off; else, of what top_k kept, a token stays iff the
+                             mass of the kept tokens with a larger logit is below top_p times
+                             the kept mass; the target is then renormalised over what stays     */
 } la_accept_desc;
 
 LA_API la_status la_spec_accept_workspace(const la_accept_desc *desc, size_t *bytes_out);

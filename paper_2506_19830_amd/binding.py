@@ -39,7 +39,8 @@ class la_attn_desc(ctypes.Structure):
 
 class la_accept_desc(ctypes.Structure):
     _fields_ = [("num_branches", ctypes.c_int32), ("num_draft", ctypes.c_int32), ("vocab", ctypes.c_int32),
-                ("logits_dtype", ctypes.c_int32), ("temperature", ctypes.c_float)]
+                ("logits_dtype", ctypes.c_int32), ("temperature", ctypes.c_float), ("top_k", ctypes.c_int32),
+                ("top_p", ctypes.c_float)]
 
 
 class LaError(RuntimeError):
@@ -135,8 +136,9 @@ def la_verify_attention(desc: la_attn_desc, q, k_cache, v_cache, block_tables, p
         raise LaError(st, "la_verify_attention")
 
 
-def make_accept_desc(*, num_branches, num_draft, vocab, logits_dtype, temperature=1.0) -> la_accept_desc:
-    return la_accept_desc(num_branches, num_draft, vocab, DTYPE_CODES[logits_dtype], temperature)
+def make_accept_desc(*, num_branches, num_draft, vocab, logits_dtype, temperature=1.0, top_k=0,
+                     top_p=1.0) -> la_accept_desc:
+    return la_accept_desc(num_branches, num_draft, vocab, DTYPE_CODES[logits_dtype], temperature, top_k, top_p)
 
 
 def la_spec_accept_workspace(desc: la_accept_desc) -> int:

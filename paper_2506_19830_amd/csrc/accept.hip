@@ -5,7 +5,7 @@
 // stops the walk and one token is drawn from norm(max(0, p_n - q_n)); with all K accepted
 // a bonus token is drawn from p_K.
 //
-// Four launches:
+// Launches:
 //   stats   one coalesced pass over every logit row (NB*(2K+1) rows x V): per (row, slice)
 //           the exact maximum and sum 2^((x-max)*log2e/T), fp32.  This is the HBM-bound
 //           part: each logit is read exactly once, 16-byte loads, eight in flight per lane.
@@ -20,6 +20,13 @@
 //   pick    grid NB: the slice in which the running sum first exceeds u_sample * total,
 //           then the lane inside it (scan of the stored per-lane sums), then the token
 //           among that lane's 8 (re-evaluated by one lane).
+//   warp    (only with top-k / top-p) one workgroup per target row: the smallest logit the row keeps and the
+//           mass of the kept tokens, by two radix selections over an order-preserving key of the logit: the
+//           k-th largest by count, then among those the value at which the descending cumulative mass reaches
+//           top_p of the kept mass.  Both filters are predicates on a token's value (keep v iff fewer than k
+//           tokens are larger; keep v iff the mass of the larger kept tokens is below top_p * Z_k), so equal
+//           logits are never split and nothing has to be sorted.  decide / resid / pick then use
+//           p(v) = [key(v) >= key_min] * exp((x_v - max)/T) / Z_kept for the target rows.
 // The two resampling rows are re-read twice (2 of the 2K+1 rows of a branch; cache hits).
 // fp64 there makes the blocked running sum agree with a sequential one to ~1e-16, so the
 // drawn token does not depend on the summation order.
@@ -159,9 +166,222 @@ __device__ __forceinline__ void wave_fold_row(const AcceptParams &p, int rw, int
   z_out = wave_sum(z);
 }
 
+// Order-preserving key of an fp32 value: larger value <=> larger key (as unsigned).
+__device__ __forceinline__ uint32_t order_key(float x) {
+  const uint32_t b = __builtin_bit_cast(uint32_t, x);
+  return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+
 // fp64 probability mass (unnormalised) of one logit: exp(x/T - max/T)
 __device__ __forceinline__ double mass64(float x, double mx_over_t, double inv_temp) {
   return exp((double)x * inv_temp - mx_over_t);
+}
+
+// ---------------------------------------------------------------------------------------------
+// warp: grid NB*(K+1), one workgroup of 1024 lanes per target row (Section 4, Setup: temperature, top_k, top_p)
+// ---------------------------------------------------------------------------------------------
+constexpr int kWarpThreads = 1024;
+constexpr int kRep = 16;   // histogram copies per workgroup
+
+// Calls f(x) for every logit of a row, the workgroup's lanes striding over it, with several loads in flight per
+// lane (16-byte loads when the row allows: four per lane and batch).
+template <bool BF16, typename F>
+__device__ __forceinline__ void row_foreach(const void *row, int V, F &&f) {
+  constexpr int kPerVec = BF16 ? 8 : 4;
+  const int tid = threadIdx.x;
+  if (V % kPerVec == 0) {   // then every row starts on a 16-byte boundary
+    const int n_vec = V / kPerVec;
+    for (int i0 = tid; i0 < n_vec; i0 += 4 * kWarpThreads) {
+      u32x4 w[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int i = i0 + j * kWarpThreads;
+        w[j] = *(const u32x4 *)((const uint8_t *)row + (size_t)(i < n_vec ? i : i0) * 16);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (i0 + j * kWarpThreads >= n_vec) break;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const uint32_t word = w[j][k];
+          if constexpr (BF16) {
+            f(bf16_lo(word));
+            f(bf16_hi(word));
+          } else {
+            f(as_f32(word));
+          }
+        }
+      }
+    }
+  } else {
+    for (int v0 = tid; v0 < V; v0 += 8 * kWarpThreads) {
+      float x[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int v = v0 + j * kWarpThreads;
+        x[j] = load_logit<BF16>(row, v < V ? v : v0);
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (v0 + j * kWarpThreads < V) f(x[j]);
+    }
+  }
+}
+
+// Radix selection over the keys of a set of values, 8 bits per round from the top.  BY_MASS = false: the k-th
+// largest key (count{key > result} < k <= count{key >= result}).  BY_MASS = true: the key at which the descending
+// cumulative mass first reaches target (mass{key > result} < target <= mass{key >= result}); if the whole mass
+// stays below target, floor_key.  BF16 values have 16 significant key bits: two rounds instead of four.
+// `each(f)` calls f(x) for every value of the set, the workgroup's lanes sharing the work; values with a key below
+// floor_key take no part (the caller guarantees that the answer lies at or above it).
+template <bool BF16, bool BY_MASS, typename Each>
+__device__ __forceinline__ uint32_t radix_select(Each &&each, double mx_over_t, double inv_temp, uint32_t floor_key,
+                                                 int k, double target, uint32_t *cnt, double *mass,
+                                                 uint32_t *s_pick, double *s_above) {
+  constexpr int kRounds = BF16 ? 2 : 4;
+  const int tid = threadIdx.x;
+  uint32_t prefix = 0;          // the bits chosen so far (high bits of the key)
+  double above = 0.0;           // BY_MASS: mass of the keys above the chosen prefix range
+  int k_rem = k;
+#pragma unroll 1
+  for (int round = 0; round < kRounds; ++round) {
+    const int shift = 24 - 8 * round;
+    // kRep copies of the histogram, chosen by lane: the logits of a row crowd into a few of the 256 buckets of the
+    // leading byte, and LDS serialises atomics of one instruction that hit the same address
+    for (int i = tid; i < 256 * kRep; i += kWarpThreads) {
+      if constexpr (BY_MASS)
+        mass[i] = 0.0;
+      else
+        cnt[i] = 0;
+    }
+    __syncthreads();
+    const int rep = (tid & (kRep - 1)) * 256;
+    each([&](float x) {
+      const uint32_t key = order_key(x);
+      const bool in_range = round == 0 || (key >> (shift + 8)) == (prefix >> (shift + 8));
+      if (!in_range || key < floor_key) return;
+      if constexpr (BY_MASS)
+        atomicAdd(&mass[rep + ((key >> shift) & 255)], mass64(x, mx_over_t, inv_temp));
+      else
+        atomicAdd(&cnt[rep + ((key >> shift) & 255)], 1u);
+    });
+    __syncthreads();
+    if (tid < 256) {   // fold the copies, in order
+      if constexpr (BY_MASS) {
+        double t = 0.0;
+        for (int r = 0; r < kRep; ++r) t += mass[r * 256 + tid];
+        mass[tid] = t;
+      } else {
+        uint32_t t = 0;
+        for (int r = 0; r < kRep; ++r) t += cnt[r * 256 + tid];
+        cnt[tid] = t;
+      }
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int pick = -1;
+      if constexpr (BY_MASS) {
+        double m = above;
+        int lowest = -1;
+        for (int b = 255; b >= 0; --b) {
+          if (!(mass[b] > 0.0)) continue;
+          if (m + mass[b] >= target) {
+            pick = b;
+            break;
+          }
+          lowest = b;
+          m += mass[b];
+        }
+        // below the first round the parent bucket did cross; if the regrouped sums miss that by a rounding, the
+        // crossing is in the lowest bucket with mass
+        if (pick < 0 && round > 0) pick = lowest, m -= mass[lowest];
+        *s_above = m;
+      } else {
+        int c = 0;
+        for (int b = 255; b >= 0; --b) {
+          if (c + (int)cnt[b] >= k_rem) {
+            pick = b;
+            k_rem -= c;
+            break;
+          }
+          c += (int)cnt[b];
+        }
+        *s_above = (double)k_rem;
+      }
+      *s_pick = (uint32_t)pick;
+    }
+    __syncthreads();
+    const uint32_t pick = *s_pick;
+    if (pick == 0xFFFFFFFFu) return floor_key;   // BY_MASS only: the target lies beyond the whole mass
+    prefix |= pick << shift;
+    if constexpr (BY_MASS)
+      above = *s_above;
+    else
+      k_rem = (int)*s_above;
+    __syncthreads();
+  }
+  // a bf16 logit widened to fp32 has 16 zero low bits, which the key turns into 0xFFFF for negative values
+  return BF16 ? (prefix | ((prefix >> 31) ? 0u : 0xFFFFu)) : prefix;
+}
+
+// Sum over the row of exp((x - max)/T) for keys >= floor_key, fp64, in a fixed order (per lane in token order, then
+// a shuffle tree, then the wavefronts in order): the same value in every lane.
+template <bool BF16>
+__device__ __forceinline__ double kept_mass(const void *row, int V, double mx_over_t, double inv_temp,
+                                            uint32_t floor_key, double *red, double *slot) {
+  const int tid = threadIdx.x;
+  double acc = 0.0;
+  row_foreach<BF16>(row, V, [&](float x) {
+    if (order_key(x) >= floor_key) acc += mass64(x, mx_over_t, inv_temp);
+  });
+  acc = wave_sum(acc);
+  if ((tid & 63) == 0) red[tid >> 6] = acc;
+  __syncthreads();
+  if (tid == 0) {
+    double t = 0.0;
+    for (int w = 0; w < kWarpThreads / 64; ++w) t += red[w];
+    *slot = t;
+  }
+  __syncthreads();
+  const double out = *slot;
+  __syncthreads();
+  return out;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kWarpThreads) void accept_warp_kernel(const AcceptParams p) {
+  __shared__ double mass[256 * kRep];                 // the count histogram shares this storage
+  uint32_t *cnt = (uint32_t *)mass;
+  __shared__ uint32_t s_pick;
+  __shared__ double s_above, s_slot;
+  __shared__ double red[kWarpThreads / 64];
+  __shared__ float s_m;
+  const int rw = blockIdx.x;   // target row nb*(K+1) + i
+  const int tid = threadIdx.x;
+  const uint8_t *row = (const uint8_t *)p.target + (size_t)rw * p.V * (BF16 ? 2 : 4);
+  if (tid < 64) {
+    float m, z;
+    wave_fold_row(p, rw, tid, m, z);
+    if (tid == 0) s_m = m;
+  }
+  __syncthreads();
+  const float m = s_m;
+  const double mx_over_t = (double)m * p.inv_temp;
+  auto each_of_row = [&](auto &&f) { row_foreach<BF16>(row, p.V, f); };
+  uint32_t key_min = 0;
+  if (p.top_k > 0 && p.top_k < p.V)
+    key_min = radix_select<BF16, false>(each_of_row, 0.0, 0.0, 0u, p.top_k, 0.0, cnt, mass, &s_pick, &s_above);
+  if (p.top_p < 1.0f) {
+    const double zk = kept_mass<BF16>(row, p.V, mx_over_t, p.inv_temp, key_min, red, &s_slot);
+    key_min = radix_select<BF16, true>(each_of_row, mx_over_t, p.inv_temp, key_min, 0, (double)p.top_p * zk, cnt, mass,
+                                       &s_pick, &s_above);
+  }
+  const double zw = kept_mass<BF16>(row, p.V, mx_over_t, p.inv_temp, key_min, red, &s_slot);
+  if (tid == 0) {
+    p.warp_key[rw] = key_min;
+    p.warp_z[rw] = zw;
+    p.warp_max[rw] = m;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -196,7 +416,13 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(const AcceptPar
       const int i = i0 + tid;
       const int x = p.tokens[(size_t)nb * p.K + i];
       const float tx = load_logit<BF16>(p.target, ((size_t)nb * (p.K + 1) + i) * p.V + x);
-      const float px = __builtin_amdgcn_exp2f((tx - sm[0][tid]) * p.inv_temp_log2) / sz[0][tid];
+      float px = __builtin_amdgcn_exp2f((tx - sm[0][tid]) * p.inv_temp_log2) / sz[0][tid];
+      if (p.warp_key) {  // warped target: x has mass only if its row keeps it, normalised by the kept mass
+        const int wr = nb * (p.K + 1) + i;
+        px = order_key(tx) >= p.warp_key[wr]
+                 ? __builtin_amdgcn_exp2f((tx - sm[0][tid]) * p.inv_temp_log2) / (float)p.warp_z[wr]
+                 : 0.f;
+      }
       float qx = 1.0f;   // point-mass draft at x
       if (p.draft) {
         const float dx = load_logit<BF16>(p.draft, ((size_t)nb * p.K + i) * p.V + x);
@@ -274,8 +500,10 @@ struct ResidCtx {
   double mt, mq, zt, zq, inv_temp;
   bool has_draft;
   int removed;   // point-mass draft after a rejection: the drafted token, which has no residual mass; else -1
+  uint32_t key_min;   // warped target: smallest key the row keeps (0: everything)
   __device__ __forceinline__ void eval(int v, double &r, double &pm) const {
-    pm = mass64(load_logit<BF16>(target, trow + v), mt, inv_temp) / zt;
+    const float tx = load_logit<BF16>(target, trow + v);
+    pm = order_key(tx) >= key_min ? mass64(tx, mt, inv_temp) / zt : 0.0;
     r = v == removed ? 0.0 : pm;
     if (has_draft) {
       const double qm = mass64(load_logit<BF16>(draft, drow + v), mq, inv_temp) / zq;
@@ -301,6 +529,11 @@ __device__ __forceinline__ ResidCtx<BF16> make_ctx(const AcceptParams &p, int nb
   x.zt = fold64_block(p.zsum + ((size_t)nb * 2 + 0) * p.n_fine, p.n_fine, buf, slots);
   x.zq = fold64_block(p.zsum + ((size_t)nb * 2 + 1) * p.n_fine, p.n_fine, buf, slots + 1);
   if (!x.has_draft) x.zq = 1.0;
+  x.key_min = 0;
+  if (p.warp_key) {   // the kept mass replaces the row's full normaliser
+    x.key_min = p.warp_key[nb * (p.K + 1) + n];
+    x.zt = p.warp_z[nb * (p.K + 1) + n];
+  }
   return x;
 }
 
@@ -435,6 +668,12 @@ hipError_t launch_typed(const AcceptParams &p, hipStream_t stream) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
+  if (p.warp_key) {
+    ProfileScope scope(SLOT_ACCEPT_WARP, stream);
+    hipLaunchKernelGGL(accept_warp_kernel<BF16>, dim3(p.NB * (p.K + 1)), dim3(kWarpThreads), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   {
     ProfileScope scope(SLOT_ACCEPT_DECIDE, stream);
     hipLaunchKernelGGL(accept_decide_kernel<BF16>, dim3(p.n_fine, p.NB), dim3(kThreads), 0, stream, p);
@@ -469,6 +708,9 @@ size_t accept_workspace_bytes(int NB, int K, int V, bool bf16, int *n_chunks_out
   b += align_up((size_t)NB * 2 * n_fine * sizeof(double));                 // rsum
   b += align_up((size_t)NB * 2 * sizeof(float));                           // rowmax
   b += align_up((size_t)NB * n_fine * kThreads * 2 * sizeof(double));      // lane_sums
+  b += align_up((size_t)NB * (K + 1) * sizeof(uint32_t));                  // warp_key
+  b += align_up((size_t)NB * (K + 1) * sizeof(double));                    // warp_z
+  b += align_up((size_t)NB * (K + 1) * sizeof(float));                     // warp_max
   return b;
 }
 
@@ -485,6 +727,13 @@ void accept_carve_workspace(AcceptParams &p, void *ws) {
   p.rowmax = (float *)at;
   at += align_up((size_t)p.NB * 2 * sizeof(float));
   p.lane_sums = (double *)at;
+  at += align_up((size_t)p.NB * p.n_fine * kThreads * 2 * sizeof(double));
+  const bool warp = (p.top_k > 0 && p.top_k < p.V) || p.top_p < 1.0f;
+  p.warp_key = warp ? (uint32_t *)at : nullptr;
+  at += align_up((size_t)p.NB * (p.K + 1) * sizeof(uint32_t));
+  p.warp_z = warp ? (double *)at : nullptr;
+  at += align_up((size_t)p.NB * (p.K + 1) * sizeof(double));
+  p.warp_max = warp ? (float *)at : nullptr;
 }
 
 hipError_t launch_accept(const AcceptParams &p, hipStream_t stream) {

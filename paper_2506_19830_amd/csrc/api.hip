@@ -140,7 +140,7 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, Attn
 }
 
 // ---- profiling ---------------------------------------------------------------------------------
-const char *kSlotNames[SLOT_COUNT] = {"attn_mfma",     "attn_merge",   "attn_f32",   "accept_stats",
+const char *kSlotNames[SLOT_COUNT] = {"attn_mfma",     "attn_merge",   "attn_f32",   "accept_stats", "accept_warp",
                                       "accept_decide", "accept_resid", "accept_pick"};
 struct ProfileRecord {
   int slot;
@@ -271,6 +271,7 @@ la_status la_verify_attention(const la_attn_desc *desc, const void *q, const voi
 static la_status validate_accept(const la_accept_desc *d) {
   if (!d) return LA_ERR_INVALID_ARG;
   if (d->num_branches < 1 || d->num_draft < 1 || d->vocab < 1) return LA_ERR_INVALID_ARG;
+  if (d->top_k < 0 || !(d->top_p > 0.0f) || d->top_p > 1.0f) return LA_ERR_INVALID_ARG;
   if (d->logits_dtype != LA_F32 && d->logits_dtype != LA_BF16)
     return d->logits_dtype == LA_FP8_E4M3 ? LA_ERR_UNSUPPORTED : LA_ERR_INVALID_ARG;
   if (!(d->temperature > 0.f) || !isfinite(d->temperature)) return LA_ERR_INVALID_ARG;
@@ -310,6 +311,7 @@ la_status la_spec_accept(const la_accept_desc *desc, const void *target_logits, 
   p.bf16 = desc->logits_dtype == LA_BF16;
   p.inv_temp_log2 = 1.44269504088896340736f / desc->temperature;
   p.inv_temp = 1.0 / (double)desc->temperature;
+  p.top_k = desc->top_k, p.top_p = desc->top_p;
   accept_carve_workspace(p, workspace);
   return launch_accept(p, (hipStream_t)hip_stream) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }

@@ -50,6 +50,7 @@ enum KernelSlot {
   SLOT_ATTN_MERGE,
   SLOT_ATTN_F32,
   SLOT_ACCEPT_STATS,
+  SLOT_ACCEPT_WARP,
   SLOT_ACCEPT_DECIDE,
   SLOT_ACCEPT_RESID,
   SLOT_ACCEPT_PICK,
@@ -86,6 +87,12 @@ struct AcceptParams {
   double *rsum;                // [NB, 2, n_fine]  fp64 slice sums of the residual and of p
   float *rowmax;               // [NB, 2] exact row maxima (raw logits) of the resampling rows
   double *lane_sums;           // [NB, n_fine, 256, 2] per-lane sums of the residual and of p
+  // top-k / top-p warping of the target rows (off: top_k == 0 and top_p >= 1)
+  int top_k;
+  float top_p;
+  uint32_t *warp_key;          // [NB*(K+1)] order-preserving key of the smallest logit a row keeps
+  double *warp_z;              // [NB*(K+1)] sum exp((x - max)/T) over the kept tokens
+  float *warp_max;             // [NB*(K+1)] row maximum (raw logits)
 };
 
 size_t accept_workspace_bytes(int NB, int K, int V, bool bf16, int *n_chunks_out, int *n_fine_out);

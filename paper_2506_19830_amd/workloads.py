@@ -133,6 +133,8 @@ class AcceptCase:
     draft_noise_std: Optional[float] = 1.0   # draft = target + N(0, noise^2); None => independent N(0, target_std^2)
     temperature: float = 1.0
     seed: int = 0
+    top_k: int = 0                # 0 = off
+    top_p: float = 1.0            # 1 = off; an fp32 field of the descriptor: checkers must use float(np.float32(top_p))
     point_mass: bool = False      # the drafter gives tokens only (prompt-lookup drafts): no draft logits
     peak: float = 16.0            # point_mass: added to the target logit of every drafted token, so that p(x) is O(0.1..1)
 

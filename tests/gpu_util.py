@@ -69,7 +69,7 @@ def upload_accept(case: W.AcceptCase, inp: dict) -> dict:
 def run_accept(case: W.AcceptCase, inp: dict, dev=None):
     dev = dev or upload_accept(case, inp)
     desc = B.make_accept_desc(num_branches=case.NB, num_draft=case.K, vocab=case.V, logits_dtype=case.logits_dtype,
-                              temperature=case.temperature)
+                              temperature=case.temperature, top_k=case.top_k, top_p=case.top_p)
     ws = torch.empty(max(B.la_spec_accept_workspace(desc), 16), dtype=torch.uint8, device="cuda")
     n = torch.full((case.NB,), -7, dtype=torch.int32, device="cuda")
     tok = torch.full((case.NB,), -7, dtype=torch.int32, device="cuda")
@@ -89,6 +89,9 @@ def compare_accept(got: dict, ref: dict, threshold_eps: float = 1e-6, edge_eps: 
     for nb in range(NB):
         examined = np.isfinite(ref["margin"][nb])
         near_thr[nb] = bool((ref["margin"][nb][examined] <= threshold_eps).any())
+    # a top-p decision closer than 1e-9 (relative mass) to its threshold may fall either way between two fp64
+    # summation orders; such branches are set aside too
+    near_thr |= ref["warp_margin"] < 1e-9
     clean = ~near_thr
     bad_n = clean & (got["accepted_len"] != ref["accepted_len"])
     same_n = clean & ~bad_n

@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(B.la_attn_desc) == 14 * 4
-    assert ctypes.sizeof(B.la_accept_desc) == 5 * 4
+    assert ctypes.sizeof(B.la_accept_desc) == 7 * 4
 
 
 def test_status_strings():
@@ -93,7 +93,8 @@ def test_attention_call_rejects_before_launch():
 def test_accept_rejects_bad_arguments():
     for kw, status in [(dict(num_branches=0), 1), (dict(num_draft=0), 1), (dict(vocab=0), 1),
                        (dict(temperature=0.0), 1), (dict(logits_dtype="fp8_e4m3"), 2),
-                       (dict(num_branches=40000, num_draft=8), 2)]:
+                       (dict(num_branches=40000, num_draft=8), 2), (dict(top_k=-1), 1), (dict(top_p=0.0), 1),
+                       (dict(top_p=1.5), 1)]:
         base = dict(num_branches=8, num_draft=8, vocab=152064, logits_dtype="bf16")
         base.update(kw)
         with pytest.raises(B.LaError) as e:

@@ -17,7 +17,8 @@ def check(oracle, case, max_near=None):
           flush=True)
     inp = W.make_accept_inputs(case)
     got = run_accept(case, inp)
-    ref = oracle.spec_accept(**inp, logits_dtype=case.logits_dtype, temperature=case.temperature)
+    ref = oracle.spec_accept(**inp, logits_dtype=case.logits_dtype, temperature=case.temperature, top_k=case.top_k,
+                             top_p=float(np.float32(case.top_p)))
     bad_n, bad_tok, near = compare_accept(got, ref)
     print(f"  near-threshold branches set aside: {near} of {case.NB}", flush=True)
     assert bad_n == 0, f"{bad_n} accepted lengths differ"
@@ -100,3 +101,36 @@ def test_point_mass_draft(oracle, case):
     assert (got["next_token"][rejected] != x_n).all()
     if case.name in ("pm_small", "pm_vocab152k_k8_nb32"):
         assert (ref["accepted_len"] > 0).any() and (ref["accepted_len"] < case.K).any()
+
+
+# ------------------------------------------------------------------------------------------ top-k / top-p warping
+WARP_CASES = [
+    W.AcceptCase("warp_small_dense", 300, 4, 512, "f32", target_std=2.0, draft_noise_std=0.7, temperature=0.6, top_k=20,
+                 top_p=0.95, seed=21),
+    W.AcceptCase("warp_topp_only", 100, 3, 4096, "f32", temperature=0.6, top_p=0.95, seed=22),
+    W.AcceptCase("warp_topk_only_bf16", 64, 3, 8193, "bf16", top_k=20, seed=23),          # bf16: many tied logits
+    W.AcceptCase("warp_greedy", 200, 4, 1000, "f32", top_k=1, point_mass=True, peak=3.0, seed=24),
+    W.AcceptCase("warp_tiny_vocab", 200, 2, 3, "f32", target_std=1.0, draft_noise_std=0.5, top_k=2, top_p=0.7, seed=25),
+    W.AcceptCase("warp_k_above_vocab", 50, 2, 100, "f32", top_k=500, top_p=0.9, seed=26),
+    # the two settings of the paper's runs at full vocabulary, prompt-lookup drafts: (T 0.6, top_p 0.95, top_k 20)
+    # and (T 0.6, top_p 0.95)
+    W.AcceptCase("warp_qwen3_setting", 8, 8, 152064, "bf16", temperature=0.6, top_k=20, top_p=0.95, point_mass=True,
+                 peak=11.0, seed=27),
+    W.AcceptCase("warp_r1_setting", 8, 8, 152064, "bf16", temperature=0.6, top_p=0.95, point_mass=True, peak=11.0,
+                 seed=28),
+    W.AcceptCase("warp_dense_152k_f32", 4, 4, 152064, "f32", temperature=0.6, top_k=20, top_p=0.95, seed=29),
+]
+
+
+@pytest.mark.parametrize("case", WARP_CASES, ids=lambda c: c.name)
+def test_warped_target(oracle, case):
+    """Temperature, top-k and top-p applied to the target rows before the accept rule (Section 4, Setup)."""
+    got, ref = check(oracle, case)
+    inp = W.make_accept_inputs(case)
+    # the extra token always lies in the kept set of the row it was drawn from
+    for nb in range(min(case.NB, 16)):
+        n = int(ref["accepted_len"][nb])
+        row = inp["target_logits"][nb, n]
+        p, _ = oracle.warp_probs(row, logits_dtype=case.logits_dtype, temperature=case.temperature, top_k=case.top_k,
+                                 top_p=float(np.float32(case.top_p)))
+        assert p[got["next_token"][nb]] > 0
