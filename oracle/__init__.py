@@ -46,6 +46,7 @@ def _load():
         override = os.environ.get("LA_ORACLE_LIB")   # used by the mutation test to load a deliberately broken build
         _lib = ctypes.CDLL(override if override else str(build()))
         _lib.lao_verify_attention.restype = ctypes.c_int
+        _lib.lao_verify_attention_nested.restype = ctypes.c_int
         _lib.lao_attention_row_weights.restype = ctypes.c_int
         _lib.lao_spec_accept.restype = ctypes.c_int
         _lib.lao_spec_accept_warped.restype = ctypes.c_int
@@ -128,8 +129,11 @@ def _attn_args(q, k_cache, v_cache, block_tables, prefix_lens, k_branch, v_branc
 
 
 def verify_attention(q, k_cache, v_cache, block_tables, prefix_lens, k_branch, v_branch, k_scale=None, v_scale=None,
-                     *, q_dtype, kv_dtype, branch_kv_dtype, block_size, scale, row_ids=None):
-    """Attention of every branch token over ``prefix ++ own branch`` (causal inside the branch).
+                     *, q_dtype, kv_dtype, branch_kv_dtype, block_size, scale, row_ids=None, k_chain=None,
+                     v_chain=None, chain_vis=None):
+    """Attention of every branch token over ``prefix ++ own branch`` (causal inside the branch).  Nested form:
+    with ``k_chain``/``v_chain`` ``[B, C, Hkv, D]`` (branch storage dtype) and ``chain_vis`` ``[B, gamma]``, branch g
+    sees ``prefix ++ chain[:chain_vis[b, g]] ++ own branch``.
 
     Returns ``(out, lse)`` in fp64.  Without ``row_ids`` the shapes are
     ``[B, gamma, L, Hq, D]`` and ``[B, gamma, L, Hq]``; with ``row_ids`` (flat
@@ -149,7 +153,17 @@ def verify_attention(q, k_cache, v_cache, block_tables, prefix_lens, k_branch, v
         n = ids.size
         out = np.empty((n, D), dtype=np.float64)
         lse = np.empty((n,), dtype=np.float64)
-    rc = _load().lao_verify_attention(*head, _ptr(ids), ctypes.c_int64(n), _ptr(out), _ptr(lse))
+    if k_chain is None:
+        C, kc, vc, vis = 0, None, None, None
+    else:
+        kc = _storage(k_chain, branch_kv_dtype, "k_chain")
+        vc = _storage(v_chain, branch_kv_dtype, "v_chain")
+        C = kc.shape[1]
+        vis = np.ascontiguousarray(chain_vis, dtype=np.int32)
+        if vis.shape != (B, gamma) or kc.shape != vc.shape or kc.shape[0] != B or kc.shape[3] != D:
+            raise ValueError("k_chain/v_chain must be [B, C, Hkv, D] and chain_vis [B, gamma]")
+    rc = _load().lao_verify_attention_nested(*head, ctypes.c_int(C), _ptr(kc), _ptr(vc), _ptr(vis), _ptr(ids),
+                                             ctypes.c_int64(n), _ptr(out), _ptr(lse))
     del keep
     if rc:
         raise ValueError("lao_verify_attention rejected its arguments")

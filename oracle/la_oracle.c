@@ -14,6 +14,9 @@
  *       sequence is written out explicitly as  prefix ++ branch tokens  and a
  *       textbook max-subtracted softmax attention is evaluated per query row.
  *       Nothing is shared between branches, nothing is tiled or split.
+ *       Nested form (Algorithm 1: x'_j = x (+) s^_0 .. s^_{j-1}): the drafted
+ *       steps form one chain of C tokens; branch g additionally sees the
+ *       first chain_vis[g] chain tokens, between the prefix and its own tokens.
  *   lao_attention_row_weights -- the softmax weights of one row (test hook
  *       for the "rows sum to one" pin).
  *   lao_spec_accept -- Section 2 ("Speculative Decoding"): the drafted tokens
@@ -120,11 +123,20 @@ typedef struct {
   const void *q, *k_cache, *v_cache, *k_branch, *v_branch;
   const int32_t *block_tables, *prefix_lens;
   const float *k_scale, *v_scale;
+  /* nested branches: a chain of C drafted tokens per request, [B, C, Hkv, D] in the branch dtype; branch g of
+   * request b sees chain tokens 0 .. chain_vis[b*gamma+g]-1.  C == 0: flat form. */
+  int C;
+  const void *k_chain, *v_chain;
+  const int32_t *chain_vis;
 } attn_problem;
 
+static int visible_chain(const attn_problem *a, int b, int g) {
+  return a->C > 0 ? a->chain_vis[(int64_t)b * a->gamma + g] : 0;
+}
+
 /* Writes the key and value sequence seen by branch g of request b on kv head
- * hk:  the P prefix tokens in logical order, then the branch's own L tokens.
- * kcat, vcat: [(P+L), D]. */
+ * hk:  the P prefix tokens in logical order, then the visible part of the
+ * drafted chain, then the branch's own L tokens.  kcat, vcat: [(P+vis+L), D]. */
 static void concat_branch_kv(const attn_problem *a, int b, int g, int hk, double *kcat, double *vcat) {
   const int D = a->D;
   const int P = a->prefix_lens[b];
@@ -142,11 +154,19 @@ static void concat_branch_kv(const attn_problem *a, int b, int g, int hk, double
   }
   const double bks = (a->k_scale && a->br_dtype == LAO_FP8_E4M3) ? (double)a->k_scale[hk] : 1.0;
   const double bvs = (a->v_scale && a->br_dtype == LAO_FP8_E4M3) ? (double)a->v_scale[hk] : 1.0;
+  const int vis = visible_chain(a, b, g);
+  for (int c = 0; c < vis; ++c) {
+    int64_t base = (((int64_t)b * a->C + c) * a->Hkv + hk) * D;
+    for (int d = 0; d < D; ++d) {
+      kcat[(int64_t)(P + c) * D + d] = load_elem(a->k_chain, a->br_dtype, base + d) * bks;
+      vcat[(int64_t)(P + c) * D + d] = load_elem(a->v_chain, a->br_dtype, base + d) * bvs;
+    }
+  }
   for (int i = 0; i < a->L; ++i) {
     int64_t base = ((((int64_t)b * a->gamma + g) * a->L + i) * a->Hkv + hk) * D;
     for (int d = 0; d < D; ++d) {
-      kcat[(int64_t)(P + i) * D + d] = load_elem(a->k_branch, a->br_dtype, base + d) * bks;
-      vcat[(int64_t)(P + i) * D + d] = load_elem(a->v_branch, a->br_dtype, base + d) * bvs;
+      kcat[(int64_t)(P + vis + i) * D + d] = load_elem(a->k_branch, a->br_dtype, base + d) * bks;
+      vcat[(int64_t)(P + vis + i) * D + d] = load_elem(a->v_branch, a->br_dtype, base + d) * bvs;
     }
   }
 }
@@ -186,18 +206,27 @@ static int check_problem(const attn_problem *a) {
     if ((int64_t)a->prefix_lens[b] > (int64_t)a->max_blocks * a->block_size) return 1;
     if (a->prefix_lens[b] > 0 && (!a->k_cache || !a->v_cache)) return 1;
   }
+  if (a->C < 0) return 1;
+  if (a->C > 0) {
+    if (!a->k_chain || !a->v_chain || !a->chain_vis) return 1;
+    for (int64_t t = 0; t < (int64_t)a->B * a->gamma; ++t)
+      if (a->chain_vis[t] < 0 || a->chain_vis[t] > a->C) return 1;
+  }
   return 0;
 }
 
 /* out: [n_rows, D] fp64, lse: [n_rows] fp64 or NULL.  row_ids == NULL means
  * every row in order (n_rows must then equal B*gamma*L*Hq). */
-int lao_verify_attention(int B, int gamma, int L, int Hq, int Hkv, int D, int block_size, int max_blocks, int q_dtype,
-                         int kv_dtype, int br_dtype, double scale, const void *q, const void *k_cache,
-                         const void *v_cache, const int32_t *block_tables, const int32_t *prefix_lens,
-                         const void *k_branch, const void *v_branch, const float *k_scale, const float *v_scale,
-                         const int64_t *row_ids, int64_t n_rows, double *out, double *lse) {
+int lao_verify_attention_nested(int B, int gamma, int L, int Hq, int Hkv, int D, int block_size, int max_blocks,
+                                int q_dtype, int kv_dtype, int br_dtype, double scale, const void *q,
+                                const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                                const int32_t *prefix_lens, const void *k_branch, const void *v_branch,
+                                const float *k_scale, const float *v_scale, int chain_len, const void *k_chain,
+                                const void *v_chain, const int32_t *chain_vis, const int64_t *row_ids, int64_t n_rows,
+                                double *out, double *lse) {
   attn_problem a = {B,  gamma,   L,       Hq,       Hkv,      D,           block_size, max_blocks, q_dtype, kv_dtype, br_dtype,
-                    scale, q, k_cache, v_cache, k_branch, v_branch, block_tables, prefix_lens, k_scale, v_scale};
+                    scale, q, k_cache, v_cache, k_branch, v_branch, block_tables, prefix_lens, k_scale, v_scale,
+                    chain_len, k_chain, v_chain, chain_vis};
   if (check_problem(&a) || !out) return 1;
   const int64_t total = (int64_t)B * gamma * L * Hq;
   if (!row_ids && n_rows != total) return 1;
@@ -222,7 +251,8 @@ int lao_verify_attention(int B, int gamma, int L, int Hq, int Hkv, int D, int bl
     }
     if (!wanted) continue;
     const int P = prefix_lens[b];
-    const int64_t n_max = (int64_t)P + L;
+    const int vis = visible_chain(&a, b, g);
+    const int64_t n_max = (int64_t)P + vis + L;
     double *kcat = malloc(sizeof(double) * n_max * D);
     double *vcat = malloc(sizeof(double) * n_max * D);
     double *w = malloc(sizeof(double) * n_max);
@@ -247,7 +277,7 @@ int lao_verify_attention(int B, int gamma, int L, int Hq, int Hkv, int D, int bl
         h = hk * G + (int)(it % G);
         slot = ((((int64_t)b * gamma + g) * L + i) * Hq + h);
       }
-      const int64_t n = (int64_t)P + i + 1; /* causal inside the branch */
+      const int64_t n = (int64_t)P + vis + i + 1; /* causal inside the branch */
       double row_lse;
       row_softmax(&a, b, g, i, h, kcat, n, w, &row_lse);
       double *o = out + slot * D;
@@ -261,6 +291,16 @@ int lao_verify_attention(int B, int gamma, int L, int Hq, int Hkv, int D, int bl
   return failed;
 }
 
+int lao_verify_attention(int B, int gamma, int L, int Hq, int Hkv, int D, int block_size, int max_blocks, int q_dtype,
+                         int kv_dtype, int br_dtype, double scale, const void *q, const void *k_cache,
+                         const void *v_cache, const int32_t *block_tables, const int32_t *prefix_lens,
+                         const void *k_branch, const void *v_branch, const float *k_scale, const float *v_scale,
+                         const int64_t *row_ids, int64_t n_rows, double *out, double *lse) {
+  return lao_verify_attention_nested(B, gamma, L, Hq, Hkv, D, block_size, max_blocks, q_dtype, kv_dtype, br_dtype,
+                                     scale, q, k_cache, v_cache, block_tables, prefix_lens, k_branch, v_branch,
+                                     k_scale, v_scale, 0, NULL, NULL, NULL, row_ids, n_rows, out, lse);
+}
+
 /* Softmax weights of one row over its P+i+1 visible keys (prefix first, then
  * branch tokens 0..i).  w must hold prefix_lens[b]+i+1 doubles. */
 int lao_attention_row_weights(int B, int gamma, int L, int Hq, int Hkv, int D, int block_size, int max_blocks,
@@ -269,7 +309,8 @@ int lao_attention_row_weights(int B, int gamma, int L, int Hq, int Hkv, int D, i
                               const int32_t *prefix_lens, const void *k_branch, const void *v_branch,
                               const float *k_scale, const float *v_scale, int64_t row_id, double *w) {
   attn_problem a = {B,  gamma,   L,       Hq,       Hkv,      D,           block_size, max_blocks, q_dtype, kv_dtype, br_dtype,
-                    scale, q, k_cache, v_cache, k_branch, v_branch, block_tables, prefix_lens, k_scale, v_scale};
+                    scale, q, k_cache, v_cache, k_branch, v_branch, block_tables, prefix_lens, k_scale, v_scale,
+                    0, NULL, NULL, NULL};
   if (check_problem(&a) || !w) return 1;
   if (row_id < 0 || row_id >= (int64_t)B * gamma * L * Hq) return 1;
   const int h = (int)(row_id % Hq);

@@ -278,6 +278,25 @@ def make_accept_inputs(case: AcceptCase) -> Dict[str, np.ndarray]:
             "u_sample": u_smp}
 
 
+def make_chain_inputs(case: AttnCase, chain_len: int, inp: Dict[str, Optional[np.ndarray]],
+                      chain_vis: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+    """The drafted chain of the nested form: ``chain_len`` tokens of K/V ~ N(0,1) per request, ``[B, C, Hkv, D]`` in
+    the branch storage type (fp8: the cache's scales, taken from ``inp``), and ``chain_vis [B, gamma]``, how many of
+    them each branch sees.  Default: branch g sees the first ``g`` of ``gamma`` equal steps (the first branch none),
+    the shape of a chain of drafted steps in which branch j is conditioned on steps 0..j-1."""
+    c = case
+    s0 = 16 * c.layer
+    kch = _rng(c.seed, s0 + 8).standard_normal((c.B, chain_len, c.Hkv, c.D), dtype=np.float32)
+    vch = _rng(c.seed, s0 + 9).standard_normal((c.B, chain_len, c.Hkv, c.D), dtype=np.float32)
+    if c.branch_kv_dtype == "fp8_e4m3":
+        kch = kch / inp["k_scale"][None, None, :, None]
+        vch = vch / inp["v_scale"][None, None, :, None]
+    if chain_vis is None:
+        chain_vis = np.tile((np.arange(c.gamma) * chain_len) // c.gamma, (c.B, 1))
+    return {"k_chain": encode(kch, c.branch_kv_dtype), "v_chain": encode(vch, c.branch_kv_dtype),
+            "chain_vis": np.asarray(chain_vis, dtype=np.int32)}
+
+
 def with_layer(case: AttnCase, layer: int) -> AttnCase:
     return replace(case, layer=layer)
 

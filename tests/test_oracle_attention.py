@@ -283,3 +283,79 @@ def test_rejects_bad_arguments(oracle):
         run(oracle, SMALL, bad)
     with pytest.raises(ValueError):
         run(oracle, SMALL, inp, row_ids=np.array([10 ** 9]))
+
+
+# ------------------------------------------------------------------------------------------ nested branch prefixes
+# Algorithm 1: candidate j is conditioned on x'_j = x (+) s^_0 .. s^_{j-1}, i.e. besides the common prefix it sees the
+# first j drafted steps.  The drafted steps form one chain of C tokens per request; chain_vis[b, g] of them are
+# visible to branch g.
+
+def flat_problem_with_extended_prefix(case, inp, chain, b, g):
+    """The same rows as a *flat* one-request, one-branch problem whose prefix is  prefix_b ++ chain[:vis]  written
+    into a fresh contiguous cache (independent of the nested code path; only the pinned flat path is used)."""
+    c = case
+    P, vis, bs = int(inp["prefix_lens"][b]), int(chain["chain_vis"][b, g]), c.block_size
+    n = P + vis
+    nblk = max(1, -(-n // bs))
+    kc = np.zeros((nblk, c.Hkv, bs, c.D), dtype=inp["k_cache"].dtype)
+    vc = np.zeros_like(kc)
+    for j in range(n):
+        if j < P:
+            lb = j // bs
+            blk = inp["block_tables"][b, lb] if inp["block_tables"] is not None else b * c.max_blocks + lb
+            krow, vrow = inp["k_cache"][blk, :, j % bs], inp["v_cache"][blk, :, j % bs]
+        else:
+            krow, vrow = chain["k_chain"][b, j - P], chain["v_chain"][b, j - P]
+        kc[j // bs, :, j % bs] = krow
+        vc[j // bs, :, j % bs] = vrow
+    sub = replace(c, prefix_lens=(n,), gamma=1, paged=False)
+    sub_inp = {"q": inp["q"][b:b + 1, g:g + 1], "k_cache": kc, "v_cache": vc, "block_tables": None,
+               "prefix_lens": np.array([n], dtype=np.int32), "k_branch": inp["k_branch"][b:b + 1, g:g + 1],
+               "v_branch": inp["v_branch"][b:b + 1, g:g + 1], "k_scale": inp["k_scale"], "v_scale": inp["v_scale"]}
+    return sub, sub_inp
+
+
+@pytest.mark.parametrize("dtypes", [("f32", "f32", "f32"), ("bf16", "fp8_e4m3", "fp8_e4m3"), ("bf16", "bf16", "bf16")])
+def test_nested_equals_flat_with_the_chain_appended_to_the_prefix(oracle, dtypes):
+    """Same storage type for cache and chain, so the chain tokens can be written into a cache: every branch of the
+    nested problem equals a flat problem whose prefix is extended by the chain tokens it sees (bit for bit: the same
+    keys in the same order)."""
+    qd, kvd, brd = dtypes
+    case = W.AttnCase("nested", (37, 0, 20), 4, 5, 4, 2, 32, qd, kvd, brd, "f32", paged=True, seed=31)
+    inp = W.make_attention_inputs(case)
+    vis = np.array([[0, 3, 7, 11], [2, 2, 0, 11], [11, 5, 1, 0]], dtype=np.int32)     # also non-monotone
+    chain = W.make_chain_inputs(case, 11, inp, vis)
+    out, lse = run(oracle, case, inp, **chain)
+    for b in range(case.B):
+        for g in range(case.gamma):
+            sub, sub_inp = flat_problem_with_extended_prefix(case, inp, chain, b, g)
+            ref, ref_lse = run(oracle, sub, sub_inp)
+            np.testing.assert_array_equal(out[b, g], ref[0, 0])
+            np.testing.assert_array_equal(lse[b, g], ref_lse[0, 0])
+
+
+def test_nested_with_nothing_visible_is_the_flat_form(oracle):
+    case = W.AttnCase("nested0", (19, 6), 3, 4, 4, 2, 32, "f32", "f32", "f32", "f32", seed=32)
+    inp = W.make_attention_inputs(case)
+    chain = W.make_chain_inputs(case, 9, inp, np.zeros((2, 3), dtype=np.int32))
+    a, la = run(oracle, case, inp, **chain)
+    b, lb = run(oracle, case, inp)
+    np.testing.assert_array_equal(a, b)
+    np.testing.assert_array_equal(la, lb)
+
+
+def test_nested_chain_visibility(oracle):
+    """A branch is blind to chain tokens past its visible count, and to every other request's chain."""
+    case = W.AttnCase("nested_vis", (8, 8), 3, 2, 2, 1, 16, "f32", "f32", "f32", "f32", seed=33)
+    inp = W.make_attention_inputs(case)
+    chain = W.make_chain_inputs(case, 6, inp)                      # vis = [0, 2, 4] per request
+    base, _ = run(oracle, case, inp, **chain)
+    pert = {k: v.copy() for k, v in chain.items()}
+    pert["k_chain"][0, 2:] += 1.0                                   # request 0, tokens 2.. : seen by branch 2 only
+    pert["v_chain"][0, 2:] -= 1.0
+    out, _ = run(oracle, case, inp, **pert)
+    np.testing.assert_array_equal(out[0, :2], base[0, :2])
+    assert not np.array_equal(out[0, 2], base[0, 2])
+    np.testing.assert_array_equal(out[1], base[1])
+    with pytest.raises(ValueError):
+        run(oracle, case, inp, **{**chain, "chain_vis": np.full((2, 3), 7, dtype=np.int32)})   # more than C

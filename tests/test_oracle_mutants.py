@@ -12,8 +12,15 @@ SRC = (ROOT / "oracle" / "la_oracle.c").read_text()
 
 MUTANTS = {
     # attention
-    "causal_off_by_one": ("const int64_t n = (int64_t)P + i + 1;", "const int64_t n = (int64_t)P + i;"),
-    "sees_whole_branch": ("const int64_t n = (int64_t)P + i + 1;", "const int64_t n = (int64_t)P + L;"),
+    "causal_off_by_one": ("const int64_t n = (int64_t)P + vis + i + 1;", "const int64_t n = (int64_t)P + vis + i;"),
+    "sees_whole_branch": ("const int64_t n = (int64_t)P + vis + i + 1;", "const int64_t n = (int64_t)P + vis + L;"),
+    "chain_not_counted": ("const int64_t n = (int64_t)P + vis + i + 1;", "const int64_t n = (int64_t)P + i + 1;"),
+    "chain_of_wrong_request": ("int64_t base = (((int64_t)b * a->C + c) * a->Hkv + hk) * D;",
+                               "int64_t base = (((int64_t)0 * a->C + c) * a->Hkv + hk) * D;"),
+    "chain_vis_of_wrong_branch": ("return a->C > 0 ? a->chain_vis[(int64_t)b * a->gamma + g] : 0;",
+                                  "return a->C > 0 ? a->chain_vis[(int64_t)b * a->gamma + 0] : 0;"),
+    "own_tokens_overwrite_chain": ("kcat[(int64_t)(P + vis + i) * D + d] = load_elem(a->k_branch",
+                                   "kcat[(int64_t)(P + i) * D + d] = load_elem(a->k_branch"),
     "scale_dropped": ("    s *= a->scale;\n", ""),
     "gqa_head_map": ("h = hk * G + (int)(it % G);", "h = (int)(it % G) * Hkv + hk;"),
     "wrong_branch_kv": ("int64_t base = ((((int64_t)b * a->gamma + g) * a->L + i) * a->Hkv + hk) * D;",
