@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--kv-split-tokens", type=int, default=0)
     ap.add_argument("--branch-len", type=int, default=None,
                     help="override L, the tokens per branch (branch-length sweep at the configuration's shape)")
+    ap.add_argument("--chain-len", type=int, default=0,
+                    help="nested branches: a drafted chain of this many tokens per request, of which branch g sees "
+                         "the first g/gamma (la_verify_attention_nested); 0 = the flat form, the headline workload")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (three times) before the timed region, so that a counter "
                          "run can scale FETCH_SIZE / WRITE_SIZE by what they read for a kernel of known traffic")
@@ -93,6 +96,18 @@ def main():
     outs = [B.empty_out((attn_case.B, attn_case.gamma, attn_case.L, attn_case.Hq, attn_case.D), attn_case.out_dtype,
                         dev) for _ in range(n_layers)]
 
+    C = args.chain_len
+    chains, vis_host, vis_dev = None, None, None
+    if C > 0:
+        tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch.float8_e4m3fn}[attn_case.branch_kv_dtype]
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(4242)
+        shape = (attn_case.B, C, attn_case.Hkv, attn_case.D)
+        chains = [tuple(torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(tdt) for _ in "kv")
+                  for _ in range(n_layers)]
+        vis_host = [[(g * C) // attn_case.gamma for g in range(attn_case.gamma)] for _ in range(attn_case.B)]
+        vis_dev = torch.tensor(vis_host, dtype=torch.int32, device=dev)
+
     acc_np = W.make_accept_inputs(acc_case)
     acc = {
         "target_logits": B.to_device(acc_np["target_logits"], acc_case.logits_dtype, dev),
@@ -110,6 +125,12 @@ def main():
     def step():
         for l in range(n_layers):
             t = layers[l]
+            if C > 0:
+                B.la_verify_attention_nested(desc, t["q"], t["k_cache"], t["v_cache"], t["block_tables"],
+                                             t["prefix_lens"], lens, t["k_branch"], t["v_branch"], chains[l][0],
+                                             chains[l][1], vis_dev, vis_host, t["k_scale"], t["v_scale"], outs[l],
+                                             None, ws)
+                continue
             B.la_verify_attention(desc, t["q"], t["k_cache"], t["v_cache"], t["block_tables"], t["prefix_lens"], lens,
                                   t["k_branch"], t["v_branch"], t["k_scale"], t["v_scale"], outs[l], None, ws)
         B.la_spec_accept(adesc, acc["target_logits"], acc["draft_logits"], acc["draft_tokens"], acc["u_accept"],
@@ -156,6 +177,8 @@ def main():
     kern_launches, kern_ms = prof["attn_mfma"]
     kern_avg_ms = kern_ms / max(1, kern_launches)
     flops = attn_case.flops()
+    if C > 0:   # 4*D flops per (query row, visible chain key) pair on top of the flat form's
+        flops += sum(4.0 * attn_case.D * attn_case.L * attn_case.Hq * v for row in vis_host for v in row)
     achieved_tflops = flops / (kern_avg_ms * 1e-3) / 1e12
     alg_bytes = attn_case.algorithmic_bytes()
     attn_ms = sum(prof_all[k][1] for k in ("attn_mfma", "attn_merge"))
@@ -184,6 +207,7 @@ def main():
             "layers": n_layers,
             "branch_tokens_per_step": branch_tokens,
             "kv_split_tokens": args.kv_split_tokens,
+            "chain_len": C,
         },
         "roofline": {
             "kernel": "attn_mfma_kernel",
@@ -217,6 +241,10 @@ def main():
         D = attn_case.D
         for l in sample_layers:
             host = W.device_inputs_to_numpy(attn_case, layers[l])
+            if C > 0:
+                host.update(k_chain=W.device_bits(chains[l][0], attn_case.branch_kv_dtype),
+                            v_chain=W.device_bits(chains[l][1], attn_case.branch_kv_dtype),
+                            chain_vis=np.array(vis_host, dtype=np.int32))
             t0 = time.perf_counter()
             ref, _ = oracle.verify_attention(**host, q_dtype=attn_case.q_dtype, kv_dtype=attn_case.kv_dtype,
                                              branch_kv_dtype=attn_case.branch_kv_dtype,

@@ -113,6 +113,26 @@ LA_API la_status la_verify_attention(
     void *workspace, size_t workspace_bytes, /* dev scratch, contents undefined before and after */
     void *hip_stream);
 
+/* Nested branches (Algorithm 1: candidate j is conditioned on
+ * x'_j = x (+) s^_0 .. s^_{j-1}, the common prefix followed by the first j
+ * drafted steps).  The drafted steps of a request form one chain of chain_len
+ * tokens; branch g sees the first chain_vis[b][g] of them, after the prefix
+ * and before its own tokens (all chain tokens precede the branch's own, so
+ * there is no mask inside the visible part).  chain_len == 0 is
+ * la_verify_attention.  Same workspace as la_verify_attention. */
+LA_API la_status la_verify_attention_nested(
+    const la_attn_desc *desc, const void *q, const void *k_cache, const void *v_cache,
+    const int32_t *block_tables, const int32_t *prefix_lens, const int32_t *prefix_lens_host,
+    const void *k_branch, const void *v_branch,
+    const void *k_chain,             /* dev [B, chain_len, Hkv, D]  branch_kv_dtype (fp8: the cache's
+                                        scales); NULL when chain_len == 0                          */
+    const void *v_chain,             /* dev, same shape                                          */
+    int32_t chain_len,               /* C >= 0                                                   */
+    const int32_t *chain_vis,        /* dev [B, gamma], each in 0..C                             */
+    const int32_t *chain_vis_host,   /* host [B, gamma], same values (validated)                 */
+    const float *k_scale, const float *v_scale, void *out, float *lse,
+    void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* ------------------------------------------------------------------------- *
  *  la_spec_accept
  *

@@ -24,7 +24,8 @@ DTYPE_CODES = {"f32": LA_F32, "bf16": LA_BF16, "fp8_e4m3": LA_FP8_E4M3}
 _TORCH_DTYPES = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch.float8_e4m3fn}
 
 EXPORTED_SYMBOLS = (
-    "la_verify_attention_workspace", "la_verify_attention", "la_spec_accept_workspace", "la_spec_accept",
+    "la_verify_attention_workspace", "la_verify_attention", "la_verify_attention_nested", "la_spec_accept_workspace",
+    "la_spec_accept",
     "la_status_string", "la_profile_enable", "la_profile_select", "la_profile_collect", "la_profile_num_kernels", "la_profile_get",
     "la_profile_reset",
 )
@@ -69,6 +70,11 @@ def load() -> ctypes.CDLL:
         lib.la_verify_attention.argtypes = [ctypes.POINTER(la_attn_desc), vp, vp, vp, i32p, i32p,
                                             ctypes.POINTER(ctypes.c_int32), vp, vp, vp, vp, vp, vp, vp,
                                             ctypes.c_size_t, vp]
+        lib.la_verify_attention_nested.restype = ctypes.c_int
+        lib.la_verify_attention_nested.argtypes = [ctypes.POINTER(la_attn_desc), vp, vp, vp, i32p, i32p,
+                                                   ctypes.POINTER(ctypes.c_int32), vp, vp, vp, vp, ctypes.c_int32, i32p,
+                                                   ctypes.POINTER(ctypes.c_int32), vp, vp, vp, vp, vp, ctypes.c_size_t,
+                                                   vp]
         lib.la_spec_accept_workspace.restype = ctypes.c_int
         lib.la_spec_accept_workspace.argtypes = [ctypes.POINTER(la_accept_desc), ctypes.POINTER(ctypes.c_size_t)]
         lib.la_spec_accept.restype = ctypes.c_int
@@ -134,6 +140,24 @@ def la_verify_attention(desc: la_attn_desc, q, k_cache, v_cache, block_tables, p
                                     ctypes.c_size_t(ws_bytes), _stream())
     if st:
         raise LaError(st, "la_verify_attention")
+
+
+def la_verify_attention_nested(desc: la_attn_desc, q, k_cache, v_cache, block_tables, prefix_lens, prefix_lens_host,
+                               k_branch, v_branch, k_chain, v_chain, chain_vis, chain_vis_host, k_scale, v_scale, out,
+                               lse, workspace) -> None:
+    """As la_verify_attention, with the drafted chain ``k_chain``/``v_chain`` [B, C, Hkv, D] and ``chain_vis``
+    [B, gamma] (device int32) / ``chain_vis_host`` (nested sequence of ints, same values)."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    C = 0 if k_chain is None else int(k_chain.shape[1])
+    flat = [int(x) for row in chain_vis_host for x in row] if C else []
+    vis_host = (ctypes.c_int32 * max(1, len(flat)))(*flat)
+    st = load().la_verify_attention_nested(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                           _ptr(block_tables), _ptr(prefix_lens), _host_lens(prefix_lens_host),
+                                           _ptr(k_branch), _ptr(v_branch), _ptr(k_chain), _ptr(v_chain),
+                                           ctypes.c_int32(C), _ptr(chain_vis), vis_host, _ptr(k_scale), _ptr(v_scale),
+                                           _ptr(out), _ptr(lse), _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream())
+    if st:
+        raise LaError(st, "la_verify_attention_nested")
 
 
 def make_accept_desc(*, num_branches, num_draft, vocab, logits_dtype, temperature=1.0, top_k=0,

@@ -223,11 +223,13 @@ la_status la_verify_attention_workspace(const la_attn_desc *desc, const int32_t 
   return LA_OK;
 }
 
-la_status la_verify_attention(const la_attn_desc *desc, const void *q, const void *k_cache, const void *v_cache,
-                              const int32_t *block_tables, const int32_t *prefix_lens,
-                              const int32_t *prefix_lens_host, const void *k_branch, const void *v_branch,
-                              const float *k_scale, const float *v_scale, void *out, float *lse, void *workspace,
-                              size_t workspace_bytes, void *hip_stream) {
+la_status la_verify_attention_nested(const la_attn_desc *desc, const void *q, const void *k_cache,
+                                     const void *v_cache, const int32_t *block_tables, const int32_t *prefix_lens,
+                                     const int32_t *prefix_lens_host, const void *k_branch, const void *v_branch,
+                                     const void *k_chain, const void *v_chain, int32_t chain_len,
+                                     const int32_t *chain_vis, const int32_t *chain_vis_host, const float *k_scale,
+                                     const float *v_scale, void *out, float *lse, void *workspace,
+                                     size_t workspace_bytes, void *hip_stream) {
   AttnPlan plan;
   la_status st = make_plan(desc, prefix_lens_host, &plan);
   if (st != LA_OK) return st;
@@ -238,12 +240,20 @@ la_status la_verify_attention(const la_attn_desc *desc, const void *q, const voi
   if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(k_branch) || !aligned16(v_branch) ||
       !aligned16(out) || !aligned16(workspace))
     return LA_ERR_INVALID_ARG;
+  if (chain_len < 0) return LA_ERR_INVALID_ARG;
+  if (chain_len > 0) {
+    if (!k_chain || !v_chain || !chain_vis || !chain_vis_host || !aligned16(k_chain) || !aligned16(v_chain))
+      return LA_ERR_INVALID_ARG;
+    for (int64_t t = 0; t < (int64_t)desc->num_requests * desc->gamma; ++t)
+      if (chain_vis_host[t] < 0 || chain_vis_host[t] > chain_len) return LA_ERR_INVALID_ARG;
+  }
   const size_t need = plan.path == PATH_MFMA ? plan.part_o_bytes + plan.part_ml_bytes : 0;
   if (need > 0 && (!workspace || workspace_bytes < need)) return LA_ERR_WORKSPACE_TOO_SMALL;
 
   AttnParams p;
   memset(&p, 0, sizeof p);
   p.q = q, p.k_cache = k_cache, p.v_cache = v_cache, p.k_branch = k_branch, p.v_branch = v_branch;
+  p.k_chain = k_chain, p.v_chain = v_chain, p.chain_vis = chain_vis, p.C = chain_len;
   p.block_tables = block_tables, p.prefix_lens = prefix_lens;
   p.k_scale = k_scale, p.v_scale = v_scale;
   p.out = out, p.lse = lse;
@@ -266,6 +276,16 @@ la_status la_verify_attention(const la_attn_desc *desc, const void *q, const voi
   if (launch_attn_mfma(p, plan.shape, plan.kv_fp8, plan.br_fp8, stream) != hipSuccess) return LA_ERR_LAUNCH;
   if (launch_attn_merge(p, stream) != hipSuccess) return LA_ERR_LAUNCH;
   return LA_OK;
+}
+
+la_status la_verify_attention(const la_attn_desc *desc, const void *q, const void *k_cache, const void *v_cache,
+                              const int32_t *block_tables, const int32_t *prefix_lens,
+                              const int32_t *prefix_lens_host, const void *k_branch, const void *v_branch,
+                              const float *k_scale, const float *v_scale, void *out, float *lse, void *workspace,
+                              size_t workspace_bytes, void *hip_stream) {
+  return la_verify_attention_nested(desc, q, k_cache, v_cache, block_tables, prefix_lens, prefix_lens_host, k_branch,
+                                    v_branch, nullptr, nullptr, 0, nullptr, nullptr, k_scale, v_scale, out, lse,
+                                    workspace, workspace_bytes, hip_stream);
 }
 
 static la_status validate_accept(const la_accept_desc *d) {

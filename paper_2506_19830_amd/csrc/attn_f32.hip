@@ -1,9 +1,10 @@
 // Verify attention for fp32 tensors (gfx950), the small-case / reference-precision path.
 //
 // One wavefront owns one query row (request b, branch g, token i, head h) and walks
-// its visible keys -- the request's prefix through the block table, then tokens 0..i
-// of its own branch (Algorithm 1: a branch sees the shared prefix and only its own
-// continuation) -- 64 at a time:
+// its visible keys -- the request's prefix through the block table, then the part of
+// the request's drafted chain its branch sees, then tokens 0..i of its own branch
+// (Algorithm 1: a branch sees the shared prefix, the drafted steps before it and only
+// its own continuation) -- 64 at a time:
 //   lane k   : score of key k0+k (full dot product over D, fp32 FMA chain)
 //   wavefront: running max / sum by shuffle reductions (online softmax)
 //   lane d   : output columns d, d+64, ... accumulate p_k * V[k][d], p_k broadcast by shuffle
@@ -29,7 +30,8 @@ __global__ __launch_bounds__(64 * kWaves) void attn_f32_kernel(const AttnParams 
   const int i = t % p.L, bstart = t - i;
   const int kvh = h / p.G;
   const int P = p.prefix_lens[b];
-  const int n_keys = P + i + 1;
+  const int vis = p.C > 0 ? p.chain_vis[b * p.gamma + t / p.L] : 0;
+  const int n_keys = P + vis + i + 1;
 
   const float *q = (const float *)p.q + grow * D;
   for (int d = lane; d < D; d += 64) q_lds[wave][d] = q[d];
@@ -38,17 +40,19 @@ __global__ __launch_bounds__(64 * kWaves) void attn_f32_kernel(const AttnParams 
   const float *kc = (const float *)p.k_cache, *vc = (const float *)p.v_cache;
   const float *kb = (const float *)p.k_branch + ((size_t)b * p.gamma * p.L * p.Hkv + kvh) * D;
   const float *vb = (const float *)p.v_branch + ((size_t)b * p.gamma * p.L * p.Hkv + kvh) * D;
+  const float *kn = (const float *)p.k_chain + ((size_t)b * p.C * p.Hkv + kvh) * D;
+  const float *vn = (const float *)p.v_chain + ((size_t)b * p.C * p.Hkv + kvh) * D;
   const int32_t *table = p.block_tables ? p.block_tables + (size_t)b * p.max_blocks : nullptr;
 
-  auto row_offset = [&](int key, bool &is_prefix) -> size_t {
+  // row of key `key` in the K tensors (k = true) or the V tensors
+  auto kv_row = [&](int key, bool k) -> const float * {
     if (key < P) {
-      is_prefix = true;
       const int lb = key / p.block_size;
       const int blk = table ? table[lb] : b * p.max_blocks + lb;
-      return (((size_t)blk * p.Hkv + kvh) * p.block_size + key % p.block_size) * D;
+      return (k ? kc : vc) + (((size_t)blk * p.Hkv + kvh) * p.block_size + key % p.block_size) * D;
     }
-    is_prefix = false;
-    return (size_t)(bstart + key - P) * p.Hkv * D;
+    if (key < P + vis) return (k ? kn : vn) + (size_t)(key - P) * p.Hkv * D;
+    return (k ? kb : vb) + (size_t)(bstart + key - P - vis) * p.Hkv * D;
   };
 
   constexpr int E = D / 64;
@@ -61,9 +65,7 @@ __global__ __launch_bounds__(64 * kWaves) void attn_f32_kernel(const AttnParams 
     const int key = k0 + lane;
     float s = -INFINITY;
     if (key < n_keys) {
-      bool pre;
-      const size_t off = row_offset(key, pre);
-      const float *krow = (pre ? kc : kb) + off;
+      const float *krow = kv_row(key, true);
       float dot = 0.f;
 #pragma unroll 8
       for (int d = 0; d < D; ++d) dot = __builtin_fmaf(q_lds[wave][d], krow[d], dot);
@@ -85,9 +87,7 @@ __global__ __launch_bounds__(64 * kWaves) void attn_f32_kernel(const AttnParams 
     const int cnt = min(64, n_keys - k0);
     for (int j = 0; j < cnt; ++j) {
       const float pj = __shfl(pr, j);
-      bool pre;
-      const size_t off = row_offset(k0 + j, pre);
-      const float *vrow = (pre ? vc : vb) + off;
+      const float *vrow = kv_row(k0 + j, false);
 #pragma unroll
       for (int e = 0; e < E; ++e) acc[e] = __builtin_fmaf(pj, vrow[lane + 64 * e], acc[e]);
     }

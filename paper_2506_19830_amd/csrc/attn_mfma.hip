@@ -6,7 +6,9 @@
 // (row tile, kv head, prefix chunk), streams the chunk's K/V tiles through LDS
 // once and reuses every tile for all its rows.  The workgroup that owns the last
 // chunk of a request also reduces the branch-private keys under the mask
-// "same branch and key position <= query position".
+// "same branch and key position <= query position" and, for nested branches
+// (x'_j = x (+) s^_0 .. s^_{j-1}), the part of the request's drafted chain that each
+// branch sees.
 //
 // Per 64-key tile and wavefront (RB blocks of 32 rows each):
 //   S^T = K Q^T      v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = Q (registers)
@@ -539,7 +541,9 @@ __device__ __forceinline__ void compute_tile(const uint8_t *kt, const uint8_t *n
 //   2: tile i is computed on while tile i+1 is written and tiles i+2, i+3 are in flight from HBM; two workgroups
 //      share a CU, which hides the start-up and per-tile latencies when the row count is small and the KV
 //      stream is the limit.
-template <bool KV_FP8, bool BR_FP8, int NW, int RB, int STAGES>
+//   NESTED: the call carries a drafted chain.  A build switch rather than a run-time test so that the flat kernels
+//   keep the register allocation they were tuned with.
+template <bool KV_FP8, bool BR_FP8, int NW, int RB, int STAGES, bool NESTED>
 __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_kernel(const AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   constexpr int NT = 64 * NW;
@@ -767,17 +771,50 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
                                                 [] {});
     __syncthreads();
   }
-  // ---- phase 3: branch-private tiles (last chunk only) ------------------------------------------
-  for (int it = 0; it < n_priv; ++it) {
+  // ---- phase 3: the drafted chain of a nested problem, then the branch-private tiles (last chunk only) ----------
+  // Branch g sees chain tokens 0 .. vis[g]-1: that is the branch mask with the window [0, vis-1], so the rows'
+  // windows are swapped for it while the chain tiles run and both segments share one loop.
+  int n_chain = 0;
+  TileSrc chn = brs;
+  if (NESTED && c == n_chunks - 1) {
+    int vmax = 0;  // wavefront-uniform: the longest visible part among the branches of this row tile
+    for (int g = t_lo / p.L; g <= t_hi / p.L; ++g) vmax = max(vmax, p.chain_vis[b * p.gamma + g]);
+    vmax = min(vmax, p.C);
+    n_chain = (vmax + kTileN - 1) / kTileN;
+    const size_t ch_off = ((size_t)b * p.C * p.Hkv + kvh) * br_row;
+    chn.k_base = (const uint8_t *)p.k_chain + ch_off;
+    chn.v_base = (const uint8_t *)p.v_chain + ch_off;
+    chn.limit = vmax;
+    if (n_chain > 0) {
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        st.row_tok[rb] = p.chain_vis[b * p.gamma + st.row_tok[rb] / p.L] - 1;
+        st.row_bstart[rb] = 0;
+      }
+    }
+  }
+  for (int it = 0; it < n_chain + n_priv; ++it) {
+    if (NESTED && it == n_chain && n_chain > 0) {  // back to the rows' own windows
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        st.row_tok[rb] = min(row[rb], p.R - 1) / p.G;
+        st.row_bstart[rb] = (st.row_tok[rb] / p.L) * p.L;
+      }
+    }
     TileRegs<BR_FP8, NT> regs;
-    brs.first = tk0 + it * kTileN;
-    tile_load<BR_FP8, false, false, NT>(p, brs, tid, regs);
+    TileSrc src = it < n_chain ? chn : brs;
+    src.first = it < n_chain ? it * kTileN : tk0 + (it - n_chain) * kTileN;
+    tile_load<BR_FP8, false, false, NT>(p, src, tid, regs);
     tile_store<BR_FP8, NT>(lds, tid, regs);
     __syncthreads();
     if (active)
-      compute_tile<RB, MASK_BRANCH, false, false>(lds, nullptr, k0, st, ln, lh, brs.first, 0, crel_branch, voff_branch,
+      compute_tile<RB, MASK_BRANCH, false, false>(lds, nullptr, k0, st, ln, lh, src.first, 0, crel_branch, voff_branch,
                                                   lmul_branch, [] {});
     __syncthreads();
+  }
+  if (NESTED && n_chain > 0 && n_priv == 0) {  // not reached (the last chunk always has private tiles); keeps row_tok honest
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) st.row_tok[rb] = min(row[rb], p.R - 1) / p.G;
   }
 
   // ---- write the partial -----------------------------------------------------------------
@@ -803,10 +840,10 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
   }
 }
 
-template <bool KV_FP8, bool BR_FP8, int NW, int RB, int STAGES>
+template <bool KV_FP8, bool BR_FP8, int NW, int RB, int STAGES, bool NESTED>
 hipError_t launch_variant(const AttnParams &p, hipStream_t stream) {
   const int grid = p.Hkv * p.n_row_tiles * p.total_units;
-  auto kern = attn_mfma_kernel<KV_FP8, BR_FP8, NW, RB, STAGES>;
+  auto kern = attn_mfma_kernel<KV_FP8, BR_FP8, NW, RB, STAGES, NESTED>;
   static bool configured = false;  // per template instance
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
@@ -822,9 +859,15 @@ hipError_t launch_variant(const AttnParams &p, hipStream_t stream) {
 
 template <int NW, int RB, int STAGES>
 hipError_t launch_shape(const AttnParams &p, bool kv_fp8, bool br_fp8, hipStream_t stream) {
-  if (kv_fp8 && br_fp8) return launch_variant<true, true, NW, RB, STAGES>(p, stream);
-  if (kv_fp8 && !br_fp8) return launch_variant<true, false, NW, RB, STAGES>(p, stream);
-  if (!kv_fp8 && !br_fp8) return launch_variant<false, false, NW, RB, STAGES>(p, stream);
+  if (p.C > 0) {
+    if (kv_fp8 && br_fp8) return launch_variant<true, true, NW, RB, STAGES, true>(p, stream);
+    if (kv_fp8 && !br_fp8) return launch_variant<true, false, NW, RB, STAGES, true>(p, stream);
+    if (!kv_fp8 && !br_fp8) return launch_variant<false, false, NW, RB, STAGES, true>(p, stream);
+    return hipErrorInvalidValue;
+  }
+  if (kv_fp8 && br_fp8) return launch_variant<true, true, NW, RB, STAGES, false>(p, stream);
+  if (kv_fp8 && !br_fp8) return launch_variant<true, false, NW, RB, STAGES, false>(p, stream);
+  if (!kv_fp8 && !br_fp8) return launch_variant<false, false, NW, RB, STAGES, false>(p, stream);
   return hipErrorInvalidValue;
 }
 

@@ -22,6 +22,11 @@ namespace la {
 // ----------------------------------------------------------------------------
 struct AttnParams {
   const void *q, *k_cache, *v_cache, *k_branch, *v_branch;
+  // nested branches: a chain of C drafted tokens per request [B, C, Hkv, D] (branch storage type); branch g of
+  // request b sees chain tokens 0 .. chain_vis[b*gamma + g] - 1, between the prefix and its own tokens.  C == 0: none
+  const void *k_chain, *v_chain;
+  const int32_t *chain_vis;
+  int C;
   const int32_t *block_tables, *prefix_lens;
   const float *k_scale, *v_scale;
   float *part_o;   // [B, s_max, n_rows, D]

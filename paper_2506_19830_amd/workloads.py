@@ -362,22 +362,25 @@ def make_attention_inputs_device(case: AttnCase, device="cuda"):
     }
 
 
-def device_inputs_to_numpy(case: AttnCase, dev: dict) -> Dict[str, Optional[np.ndarray]]:
-    """Read device tensors back as the storage arrays the host-side functions use (bit patterns for bf16/fp8)."""
+def device_bits(t, dtype: str) -> Optional[np.ndarray]:
+    """A device tensor as the storage array the host-side functions use (bit patterns for bf16/fp8)."""
     import torch
 
-    def bits(t, dtype):
-        if t is None:
-            return None
-        t = t.detach().cpu().contiguous()
-        if dtype == "f32":
-            return t.numpy()
-        if dtype == "bf16":
-            return t.view(torch.int16).numpy().view(np.uint16)
-        if dtype == "fp8_e4m3":
-            return t.view(torch.uint8).numpy()
-        raise ValueError(dtype)
+    if t is None:
+        return None
+    t = t.detach().cpu().contiguous()
+    if dtype == "f32":
+        return t.numpy()
+    if dtype == "bf16":
+        return t.view(torch.int16).numpy().view(np.uint16)
+    if dtype == "fp8_e4m3":
+        return t.view(torch.uint8).numpy()
+    raise ValueError(dtype)
 
+
+def device_inputs_to_numpy(case: AttnCase, dev: dict) -> Dict[str, Optional[np.ndarray]]:
+    """Read the device tensors of one attention problem back as host storage arrays."""
+    bits = device_bits
     return {
         "q": bits(dev["q"], case.q_dtype),
         "k_cache": bits(dev["k_cache"], case.kv_dtype),

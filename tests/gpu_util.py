@@ -49,6 +49,26 @@ def run_attention(case: W.AttnCase, inp: dict, kv_split_tokens: int = 0, want_ls
     return out.double().cpu().numpy(), (None if lse is None else lse.double().cpu().numpy())
 
 
+def run_attention_nested(case: W.AttnCase, inp: dict, chain: dict, kv_split_tokens: int = 0):
+    """la_verify_attention_nested on ``inp`` plus the drafted chain ``chain`` (k_chain, v_chain, chain_vis)."""
+    dev = upload_attention(case, inp)
+    desc = attn_desc(case, kv_split_tokens)
+    lens = [int(x) for x in inp["prefix_lens"]]
+    ws = torch.empty(max(B.la_verify_attention_workspace(desc, lens), 16), dtype=torch.uint8, device="cuda")
+    out = B.empty_out((case.B, case.gamma, case.L, case.Hq, case.D), case.out_dtype)
+    out.fill_(float("nan"))
+    lse = torch.full((case.B, case.gamma, case.L, case.Hq), float("nan"), dtype=torch.float32, device="cuda")
+    has = chain["k_chain"].shape[1] > 0
+    kch = B.to_device(chain["k_chain"], case.branch_kv_dtype) if has else None
+    vch = B.to_device(chain["v_chain"], case.branch_kv_dtype) if has else None
+    vis = torch.from_numpy(chain["chain_vis"]).cuda() if has else None
+    B.la_verify_attention_nested(desc, dev["q"], dev["k_cache"], dev["v_cache"], dev["block_tables"],
+                                 dev["prefix_lens"], lens, dev["k_branch"], dev["v_branch"], kch, vch, vis,
+                                 chain["chain_vis"].tolist(), dev["k_scale"], dev["v_scale"], out, lse, ws)
+    torch.cuda.synchronize()
+    return out.double().cpu().numpy(), lse.double().cpu().numpy()
+
+
 def row_errors(got: np.ndarray, ref: np.ndarray):
     """Per output row: max |got-ref| over D divided by max |ref| over D.  Returns the vector of row errors."""
     D = ref.shape[-1]

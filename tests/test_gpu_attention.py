@@ -91,6 +91,88 @@ def test_every_kernel_shape(oracle, case, shape, monkeypatch):
         check_full(oracle, case, TOL_LOWP, kv_split_tokens=split)
 
 
+# ----------------------------------------------------------------------------------------- nested branches
+
+def check_nested(oracle, case, chain_len, tol, chain_vis=None, kv_split_tokens=0):
+    from gpu_util import row_errors, run_attention_nested
+    inp = W.make_attention_inputs(case)
+    chain = W.make_chain_inputs(case, chain_len, inp, chain_vis)
+    print(f"nested case {case.name} prefix={case.prefix_lens} gamma={case.gamma} L={case.L} C={chain_len} "
+          f"vis={chain['chain_vis'].tolist()} kv={case.kv_dtype} br={case.branch_kv_dtype} split={kv_split_tokens}",
+          flush=True)
+    got, lse = run_attention_nested(case, inp, chain, kv_split_tokens)
+    ref, ref_lse = oracle.verify_attention(**inp, **chain, q_dtype=case.q_dtype, kv_dtype=case.kv_dtype,
+                                           branch_kv_dtype=case.branch_kv_dtype, block_size=case.block_size,
+                                           scale=case.scale)
+    assert np.isfinite(got).all()
+    err = row_errors(got, ref)
+    assert err.max() <= tol, f"max row error {err.max():.3e} at row {err.argmax()}"
+    assert np.abs(lse - ref_lse).max() <= (1e-5 if tol == TOL_F32 else 1e-2)
+    return got
+
+
+NESTED_CASES = [
+    # (case, chain length, visibility or None = branch g sees g/gamma of the chain)
+    (W.AttnCase("nested_f32", (77, 0, 130), 3, 5, 6, 2, 128, "f32", "f32", "f32", "f32", seed=11), 10, None),
+    (W.AttnCase("nested_f32_paged_long_chain", (300, 45), 4, 9, 8, 2, 64, "f32", "f32", "f32", "f32", paged=True,
+                seed=12), 150, None),
+    # Algorithm 1's shape: gamma steps of L tokens, step j conditioned on steps 0..j-1, so C = (gamma-1)*L
+    (W.AttnCase("nested_bf16_steps", (1000,), 4, 20, 16, 2, 128, seed=13), 60, None),
+    # chain longer than a key tile, visibility neither monotone nor the same in the two requests, one branch
+    # sees nothing and one everything; row tiles straddle branches (L*G = 210)
+    (W.AttnCase("nested_bf16_ragged_vis", (130, 515), 4, 70, 6, 2, 128, paged=True, seed=14), 150,
+     [[150, 0, 67, 64], [1, 149, 0, 3]]),
+    (W.AttnCase("nested_fp8", (900,), 3, 33, 10, 2, 128, "bf16", "fp8_e4m3", "fp8_e4m3", "bf16", seed=15), 70, None),
+    (W.AttnCase("nested_fp8_bf16_branch", (515, 64), 2, 40, 8, 1, 128, "bf16", "fp8_e4m3", "bf16", "f32", paged=True,
+                seed=16), 90, [[90, 13], [0, 64]]),
+    # no prefix at all: the chain and the branch are all there is; the first branch sees only itself
+    (W.AttnCase("nested_bf16_no_prefix", (0,), 3, 8, 8, 2, 128, seed=17), 16, None),
+    (W.AttnCase("nested_bf16_single_token_branches", (321,), 8, 1, 40, 8, 128, seed=18), 7, None),
+]
+
+
+@pytest.mark.parametrize("case,chain_len,vis", NESTED_CASES, ids=lambda x: getattr(x, "name", None))
+def test_nested_small_cases(oracle, case, chain_len, vis):
+    tol = TOL_F32 if case.kv_dtype == "f32" else TOL_LOWP
+    for split in ((0,) if case.kv_dtype == "f32" else (0, 64, 256)):
+        check_nested(oracle, case, chain_len, tol, None if vis is None else np.array(vis), split)
+
+
+@pytest.mark.parametrize("shape", [0, 1])
+def test_nested_every_kernel_shape(oracle, shape, monkeypatch):
+    monkeypatch.setenv("LA_ATTN_SHAPE", str(shape))
+    for case, chain_len, vis in (NESTED_CASES[2], NESTED_CASES[3], NESTED_CASES[4]):
+        for split in (0, 192):
+            check_nested(oracle, case, chain_len, TOL_LOWP, None if vis is None else np.array(vis), split)
+
+
+@pytest.mark.parametrize("case", [NESTED_CASES[0][0], NESTED_CASES[3][0]], ids=lambda c: c.name)
+def test_nested_with_nothing_visible_is_the_flat_call_bit_for_bit(case):
+    """A chain no branch sees (all of chain_vis zero), and an empty chain, must reproduce la_verify_attention
+    exactly: no tile of the chain is touched."""
+    from gpu_util import run_attention, run_attention_nested
+    inp = W.make_attention_inputs(case)
+    flat, flat_lse = run_attention(case, inp)
+    chain = W.make_chain_inputs(case, 40, inp, np.zeros((case.B, case.gamma), dtype=np.int32))
+    got, lse = run_attention_nested(case, inp, chain)
+    assert np.array_equal(got, flat) and np.array_equal(lse, flat_lse)
+    empty = W.make_chain_inputs(case, 0, inp)
+    got, lse = run_attention_nested(case, inp, empty)
+    assert np.array_equal(got, flat) and np.array_equal(lse, flat_lse)
+
+
+def test_nested_rejects_bad_visibility():
+    from gpu_util import run_attention_nested
+    from paper_2506_19830_amd import binding as B
+    case = NESTED_CASES[0][0]
+    inp = W.make_attention_inputs(case)
+    for bad in (11, -1):
+        vis = np.zeros((case.B, case.gamma), dtype=np.int32)
+        vis[1, 2] = bad
+        with pytest.raises(B.LaError):
+            run_attention_nested(case, inp, W.make_chain_inputs(case, 10, inp, vis))
+
+
 def test_mfma_fp32_output_is_tight(oracle):
     """With fp32 output the low-precision steps left are P rounded to bf16 and Q rounded to bf16 again after the
     score scale is folded in: errors stay at a few 1e-3, well inside the 2e-2 bar."""
