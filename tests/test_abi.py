@@ -90,6 +90,34 @@ def test_attention_call_rejects_before_launch():
     assert _call_attention(d, [32768], {"ws": 0}, 0) == 3
 
 
+def test_nested_attention_call_rejects_before_launch():
+    """Chain arguments are validated on the host: length, pointers, alignment, visibility within 0..C."""
+    lib = B.load()
+    d = good_desc()
+    vp = ctypes.c_void_p
+    lens = (ctypes.c_int32 * 1)(32768)
+    n_vis = d.num_requests * d.gamma
+
+    def call(chain_len, k_chain=256, v_chain=256, vis_dev=256, vis=None, vis_host_null=False, ws_bytes=1024):
+        vis_arr = (ctypes.c_int32 * n_vis)(*(vis if vis is not None else [0] * n_vis))
+        host = ctypes.POINTER(ctypes.c_int32)() if vis_host_null else vis_arr
+        return lib.la_verify_attention_nested(ctypes.byref(d), vp(256), vp(256), vp(256), vp(0), vp(256), lens,
+                                              vp(256), vp(256), vp(k_chain), vp(v_chain), ctypes.c_int32(chain_len),
+                                              vp(vis_dev), host, vp(0), vp(0), vp(256), vp(0), vp(256),
+                                              ctypes.c_size_t(ws_bytes), vp(0))
+
+    assert call(-1) == 1
+    assert call(4, k_chain=0) == 1
+    assert call(4, v_chain=264) == 1                       # not 16-byte aligned
+    assert call(4, vis_dev=0) == 1
+    assert call(4, vis_host_null=True) == 1
+    assert call(4, vis=[0] * (n_vis - 1) + [5]) == 1       # sees more than the chain holds
+    assert call(4, vis=[-1] + [0] * (n_vis - 1)) == 1
+    # valid chain arguments get as far as the workspace check (nothing is launched: the workspace is too small)
+    assert call(4, vis=[4] * n_vis) == 3
+    assert call(0, k_chain=0, v_chain=0, vis_dev=0, vis_host_null=True) == 3
+
+
 def test_accept_rejects_bad_arguments():
     for kw, status in [(dict(num_branches=0), 1), (dict(num_draft=0), 1), (dict(vocab=0), 1),
                        (dict(temperature=0.0), 1), (dict(logits_dtype="fp8_e4m3"), 2),
