@@ -52,6 +52,8 @@ def _load():
         _lib.lao_spec_accept_warped.restype = ctypes.c_int
         _lib.lao_warp_probs.restype = ctypes.c_int
         _lib.lao_widen.restype = ctypes.c_int
+        _lib.lao_kv_commit.restype = ctypes.c_int
+        _lib.lao_quantize_fp8_e4m3.restype = ctypes.c_int
         _lib.lao_num_threads.restype = ctypes.c_int
     return _lib
 
@@ -185,6 +187,63 @@ def attention_row_weights(q, k_cache, v_cache, block_tables, prefix_lens, k_bran
     if rc:
         raise ValueError("lao_attention_row_weights rejected its arguments")
     return w
+
+
+def kv_commit(k_cache, v_cache, block_tables, prefix_lens, k_branch, v_branch, k_chain, v_chain, src_branch, n_chain,
+              n_own, k_scale=None, v_scale=None, *, kv_dtype, branch_kv_dtype, block_size):
+    """Append, per request, the first ``n_chain[b]`` tokens of the drafted chain and then the first ``n_own[b]``
+    tokens of branch ``src_branch[b]`` behind the prefix (Algorithm 1, once j* is known).
+
+    Returns ``(k_cache, v_cache, new_prefix_lens)``: updated *copies* of the caches (storage bit patterns) and the
+    grown prefix lengths.  ``k_chain`` may be ``None`` (no chain: ``n_chain`` must be all zero)."""
+    kc = _storage(k_cache, kv_dtype, "k_cache").copy()
+    vc = _storage(v_cache, kv_dtype, "v_cache").copy()
+    kb = _storage(k_branch, branch_kv_dtype, "k_branch")
+    vb = _storage(v_branch, branch_kv_dtype, "v_branch")
+    B, gamma, L, Hkv, D = kb.shape
+    lens = np.ascontiguousarray(prefix_lens, dtype=np.int32)
+    if block_tables is not None:
+        block_tables = np.ascontiguousarray(block_tables, dtype=np.int32)
+        max_blocks = block_tables.shape[1]
+        if int(block_tables.max()) >= kc.shape[0]:
+            raise ValueError("block id out of range")
+    else:
+        max_blocks = kc.shape[0] // B
+    if kc.shape[1:] != (Hkv, block_size, D) or vc.shape != kc.shape:
+        raise ValueError("cache must be [num_blocks, Hkv, block_size, D]")
+    if k_chain is None:
+        C, kch, vch = 0, None, None
+    else:
+        kch = _storage(k_chain, branch_kv_dtype, "k_chain")
+        vch = _storage(v_chain, branch_kv_dtype, "v_chain")
+        C = kch.shape[1]
+        if kch.shape != (B, C, Hkv, D) or vch.shape != kch.shape:
+            raise ValueError("k_chain/v_chain must be [B, C, Hkv, D]")
+    sb = np.ascontiguousarray(src_branch, dtype=np.int32)
+    nc = np.ascontiguousarray(n_chain, dtype=np.int32)
+    no = np.ascontiguousarray(n_own, dtype=np.int32)
+    ks = None if k_scale is None else np.ascontiguousarray(k_scale, dtype=np.float32)
+    vs = None if v_scale is None else np.ascontiguousarray(v_scale, dtype=np.float32)
+    new_lens = np.empty((B,), dtype=np.int32)
+    rc = _load().lao_kv_commit(ctypes.c_int(B), ctypes.c_int(gamma), ctypes.c_int(L), ctypes.c_int(Hkv),
+                               ctypes.c_int(D), ctypes.c_int(block_size), ctypes.c_int(max_blocks),
+                               ctypes.c_int(DTYPE_CODES[kv_dtype]), ctypes.c_int(DTYPE_CODES[branch_kv_dtype]),
+                               _ptr(kc), _ptr(vc), _ptr(block_tables), _ptr(lens), _ptr(kb), _ptr(vb),
+                               ctypes.c_int(C), _ptr(kch), _ptr(vch), _ptr(sb), _ptr(nc), _ptr(no), _ptr(ks),
+                               _ptr(vs), _ptr(new_lens))
+    if rc:
+        raise ValueError(f"lao_kv_commit rejected its arguments (status {rc})")
+    return kc, vc, new_lens
+
+
+def quantize_fp8_e4m3(x, scale: float) -> np.ndarray:
+    """Test hook: e4m3fn codes of ``x / scale`` (fp32 quotient, nearest, ties to even, saturating)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint8)
+    rc = _load().lao_quantize_fp8_e4m3(_ptr(x), ctypes.c_int64(x.size), ctypes.c_float(scale), _ptr(out))
+    if rc:
+        raise ValueError("lao_quantize_fp8_e4m3 rejected its arguments")
+    return out
 
 
 def warp_probs(logits, *, logits_dtype, temperature=1.0, top_k=0, top_p=1.0):

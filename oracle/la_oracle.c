@@ -25,6 +25,15 @@
  *       norm(max(0, p - q)); when all K survive, a bonus token is drawn from
  *       the (K+1)-th target row ("gamma+1 positions", Section 1).  Sampling is
  *       a sequential inverse-CDF walk.
+ *   lao_kv_commit -- Algorithm 1, the step after j* is known (the output
+ *       s^_0 .. s^_{j*-1} (+) s_{j*} is appended to x): for each request the
+ *       first n_chain drafted-chain tokens and then the first n_own tokens of
+ *       one chosen branch are written behind the prefix in the paged cache,
+ *       one token at a time, and the prefix length grows by n_chain + n_own.
+ *       Same storage type: the bytes are copied.  bf16 source into an fp8
+ *       cache: code = nearest e4m3fn value (ties to even, saturating at 448)
+ *       of  x / scale[head]  with the quotient taken in fp32, the precision
+ *       the cache's writer computes in (the paper fixes none).
  *
  * Readings fixed here because the paper leaves them open (each is also listed
  * in the repository's design notes):
@@ -532,6 +541,103 @@ int lao_spec_accept(int NB, int K, int V, int logits_dtype, double temperature, 
 }
 
 /* Number of OpenMP threads a parallel region will use (for reporting). */
+/* ---- KV commit ------------------------------------------------------------------ */
+
+/* Nearest e4m3fn code of y (finite): candidates are the 127 non-negative finite values, the nearest wins, a tie goes
+ * to the code with an even mantissa, magnitudes beyond the largest finite value 448 saturate to it. */
+static uint8_t nearest_fp8_e4m3fn(float y) {
+  double a = fabs((double)y);
+  int best = 0;
+  double best_d = INFINITY;
+  for (int code = 0; code < 127; ++code) {
+    double d = fabs(widen_fp8_e4m3fn((uint8_t)code) - a);
+    if (d < best_d || (d == best_d && (code & 1) == 0)) {
+      best = code;
+      best_d = d;
+    }
+  }
+  if (a > 448.0) best = 126;
+  return (uint8_t)(best | (signbit(y) ? 0x80 : 0));
+}
+
+static size_t storage_size(int dtype) {
+  return dtype == LAO_F32 ? 4 : dtype == LAO_BF16 ? 2 : dtype == LAO_FP8_E4M3 ? 1 : 8;
+}
+
+/* One token row of one kv head: D elements from src (storage src_dtype) to dst (storage dst_dtype). */
+static int commit_row(const void *src, int src_dtype, int64_t src_idx, void *dst, int dst_dtype, int64_t dst_idx,
+                      int D, const float *scale, int hk) {
+  if (src_dtype == dst_dtype) {
+    size_t sz = storage_size(src_dtype);
+    memcpy((char *)dst + (size_t)dst_idx * sz, (const char *)src + (size_t)src_idx * sz, (size_t)D * sz);
+    return 0;
+  }
+  if (src_dtype == LAO_BF16 && dst_dtype == LAO_FP8_E4M3) {
+    const float s = scale ? scale[hk] : 1.0f;
+    for (int d = 0; d < D; ++d) {
+      const float x = (float)widen_bf16(((const uint16_t *)src)[src_idx + d]);
+      const float y = x / s; /* fp32 quotient, correctly rounded */
+      ((uint8_t *)dst)[dst_idx + d] = nearest_fp8_e4m3fn(y);
+    }
+    return 0;
+  }
+  return 1;
+}
+
+/* k_cache / v_cache are updated in place.  src_branch [B] in 0..gamma-1, n_chain [B] in 0..C, n_own [B] in 0..L.
+ * new_prefix_lens [B] receives prefix_lens + n_chain + n_own.  The block table must already map every position
+ * that is written. */
+int lao_kv_commit(int B, int gamma, int L, int Hkv, int D, int block_size, int max_blocks, int kv_dtype, int br_dtype,
+                  void *k_cache, void *v_cache, const int32_t *block_tables, const int32_t *prefix_lens,
+                  const void *k_branch, const void *v_branch, int C, const void *k_chain, const void *v_chain,
+                  const int32_t *src_branch, const int32_t *n_chain, const int32_t *n_own, const float *k_scale,
+                  const float *v_scale, int32_t *new_prefix_lens) {
+  if (B < 1 || gamma < 1 || L < 1 || Hkv < 1 || D < 1 || block_size < 1 || C < 0) return 1;
+  if (!k_cache || !v_cache || !prefix_lens || !k_branch || !v_branch || !src_branch || !n_chain || !n_own ||
+      !new_prefix_lens)
+    return 1;
+  if (C > 0 && (!k_chain || !v_chain)) return 1;
+  for (int b = 0; b < B; ++b) {
+    if (src_branch[b] < 0 || src_branch[b] >= gamma || n_chain[b] < 0 || n_chain[b] > C || n_own[b] < 0 ||
+        n_own[b] > L)
+      return 1;
+    if ((int64_t)prefix_lens[b] + n_chain[b] + n_own[b] > (int64_t)max_blocks * block_size) return 1;
+  }
+  for (int b = 0; b < B; ++b) {
+    int pos = prefix_lens[b]; /* next free position of the request */
+    for (int t = 0; t < n_chain[b] + n_own[b]; ++t, ++pos) {
+      const int from_chain = t < n_chain[b];
+      const int64_t logical_block = pos / block_size;
+      const int64_t phys = block_tables ? (int64_t)block_tables[(int64_t)b * max_blocks + logical_block]
+                                        : (int64_t)b * max_blocks + logical_block;
+      for (int hk = 0; hk < Hkv; ++hk) {
+        const int64_t dst = ((phys * Hkv + hk) * block_size + (pos % block_size)) * D;
+        int64_t src;
+        const void *ks, *vs;
+        if (from_chain) {
+          src = (((int64_t)b * C + t) * Hkv + hk) * D;
+          ks = k_chain, vs = v_chain;
+        } else {
+          const int i = t - n_chain[b];
+          src = ((((int64_t)b * gamma + src_branch[b]) * L + i) * Hkv + hk) * D;
+          ks = k_branch, vs = v_branch;
+        }
+        if (commit_row(ks, br_dtype, src, k_cache, kv_dtype, dst, D, k_scale, hk)) return 2;
+        if (commit_row(vs, br_dtype, src, v_cache, kv_dtype, dst, D, v_scale, hk)) return 2;
+      }
+    }
+    new_prefix_lens[b] = pos;
+  }
+  return 0;
+}
+
+/* Test hook: the quantiser alone, n fp32 values divided by `scale`. */
+int lao_quantize_fp8_e4m3(const float *x, int64_t n, float scale, uint8_t *codes) {
+  if (!x || !codes || !(scale > 0.0f)) return 1;
+  for (int64_t i = 0; i < n; ++i) codes[i] = nearest_fp8_e4m3fn(x[i] / scale);
+  return 0;
+}
+
 #ifdef _OPENMP
 #include <omp.h>
 int lao_num_threads(void) { return omp_get_max_threads(); }

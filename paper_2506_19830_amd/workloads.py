@@ -89,6 +89,7 @@ class AttnCase:
     paged: bool = False          # random block table over a shared pool
     seed: int = 0
     layer: int = 0               # stream offset so that layers of a sweep differ
+    spare_tokens: int = 0        # cache room (mapped by the block table) behind every prefix, for the KV commit
 
     @property
     def B(self) -> int:
@@ -100,7 +101,7 @@ class AttnCase:
 
     @property
     def max_blocks(self) -> int:
-        return max(1, max(-(-p // self.block_size) for p in self.prefix_lens))
+        return max(1, max(-(-(p + self.spare_tokens) // self.block_size) for p in self.prefix_lens))
 
     @property
     def branch_tokens(self) -> int:
@@ -186,7 +187,7 @@ def make_attention_inputs(case: AttnCase) -> Dict[str, Optional[np.ndarray]]:
     c = case
     s0 = 16 * c.layer
     B, bs = c.B, c.block_size
-    blocks_needed = [-(-p // bs) for p in c.prefix_lens]
+    blocks_needed = [-(-(p + c.spare_tokens) // bs) for p in c.prefix_lens]
     if c.paged:
         num_blocks = max(1, sum(blocks_needed))
         perm = _rng(c.seed, s0 + 7).permutation(num_blocks).astype(np.int32)
@@ -297,6 +298,19 @@ def make_chain_inputs(case: AttnCase, chain_len: int, inp: Dict[str, Optional[np
             "chain_vis": np.asarray(chain_vis, dtype=np.int32)}
 
 
+def make_commit_inputs(case: AttnCase, chain_len: int, decisions=None) -> Dict[str, np.ndarray]:
+    """What a verification pass decided per request, for the KV commit: which branch survives (``src_branch``), how
+    many tokens of the drafted chain (``n_chain``, 0..chain_len) and then of that branch (``n_own``, 0..L) are
+    appended to the prefix.  Random unless ``decisions = (src_branch, n_chain, n_own)`` is given."""
+    c = case
+    if decisions is None:
+        r = _rng(c.seed, 16 * c.layer + 10)
+        decisions = (r.integers(0, c.gamma, size=c.B), r.integers(0, chain_len + 1, size=c.B),
+                     r.integers(0, c.L + 1, size=c.B))
+    src, nch, nown = (np.asarray(x, dtype=np.int32) for x in decisions)
+    return {"src_branch": src, "n_chain": nch, "n_own": nown}
+
+
 def with_layer(case: AttnCase, layer: int) -> AttnCase:
     return replace(case, layer=layer)
 
@@ -317,7 +331,7 @@ def make_attention_inputs_device(case: AttnCase, device="cuda"):
     gen = torch.Generator(device=device)
     gen.manual_seed((c.seed << 20) + 16 * c.layer + 1)
     B, bs = c.B, c.block_size
-    blocks_needed = [-(-p // bs) for p in c.prefix_lens]
+    blocks_needed = [-(-(p + c.spare_tokens) // bs) for p in c.prefix_lens]
     if c.paged:
         num_blocks = max(1, sum(blocks_needed))
         perm = torch.randperm(num_blocks, generator=gen, device=device).to(torch.int32)

@@ -1,0 +1,185 @@
+"""Pins of the oracle's KV commit (Algorithm 1, the step after j* is known: the accepted drafted steps and the
+target's step are appended to x) against things other than itself:
+
+* where the bytes land: attending over the committed cache must reproduce, bit for bit, the rows of the nested
+  verification problem that saw the same tokens *before* they were committed (same keys in the same order);
+* what the bytes are when the cache is fp8 and the source bf16: torch's own float8_e4m3fn conversion of the clamped
+  fp32 quotient, and the storage encoder of the input generators (written independently, searchsorted based);
+* what must not change: every byte of the cache outside the appended positions.
+"""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2506_19830_amd import workloads as W
+
+
+def attn_kwargs(case):
+    return dict(q_dtype=case.q_dtype, kv_dtype=case.kv_dtype, branch_kv_dtype=case.branch_kv_dtype,
+                block_size=case.block_size, scale=case.scale)
+
+
+def commit(oracle, case, inp, chain, dec):
+    return oracle.kv_commit(inp["k_cache"], inp["v_cache"], inp["block_tables"], inp["prefix_lens"], inp["k_branch"],
+                            inp["v_branch"], None if chain is None else chain["k_chain"],
+                            None if chain is None else chain["v_chain"], dec["src_branch"], dec["n_chain"],
+                            dec["n_own"], inp["k_scale"], inp["v_scale"], kv_dtype=case.kv_dtype,
+                            branch_kv_dtype=case.branch_kv_dtype, block_size=case.block_size)
+
+
+CASES = [
+    # ragged prefixes (not multiples of the block size), paged, appends that cross block boundaries
+    (W.AttnCase("commit_f32_paged", (37, 0, 130), 3, 9, 4, 2, 64, "f32", "f32", "f32", "f32", paged=True, seed=21,
+                spare_tokens=40), 25),
+    (W.AttnCase("commit_bf16", (100, 15), 4, 20, 4, 2, 128, seed=22, spare_tokens=64), 30),
+    (W.AttnCase("commit_fp8_fp8", (77,), 2, 5, 4, 2, 128, "bf16", "fp8_e4m3", "fp8_e4m3", "bf16", paged=True, seed=23,
+                spare_tokens=24), 12),
+]
+
+
+@pytest.mark.parametrize("case,C", CASES, ids=lambda x: getattr(x, "name", None))
+def test_attention_over_the_committed_cache_equals_the_nested_row_that_saw_the_same_tokens(oracle, case, C):
+    """Row (g*, i = n_own) of the nested problem with chain_vis[g*] = n_chain sees
+    prefix ++ chain[:n_chain] ++ own[0..n_own].  After the commit the first two pieces and own[:n_own] are the
+    prefix, so a one-token branch made of own[n_own] (same query) sees the same sequence: fp64 results must be
+    identical, not just close."""
+    inp = W.make_attention_inputs(case)
+    chain = W.make_chain_inputs(case, C, inp)
+    rng = np.random.default_rng(case.seed)
+    for trial in range(3):
+        src = rng.integers(0, case.gamma, size=case.B)
+        nch = rng.integers(0, C + 1, size=case.B)
+        nown = rng.integers(0, case.L, size=case.B)          # < L: token n_own exists and plays the new branch
+        dec = W.make_commit_inputs(case, C, (src, nch, nown))
+        vis = np.zeros((case.B, case.gamma), dtype=np.int32)
+        vis[np.arange(case.B), src] = nch
+        ref, ref_lse = oracle.verify_attention(**inp, k_chain=chain["k_chain"], v_chain=chain["v_chain"],
+                                               chain_vis=vis, **attn_kwargs(case))
+        kc, vc, new_lens = commit(oracle, case, inp, chain, dec)
+        assert np.array_equal(new_lens, inp["prefix_lens"] + nch + nown)
+        b_idx = np.arange(case.B)
+        after = dict(inp, k_cache=kc, v_cache=vc, prefix_lens=new_lens,
+                     q=inp["q"][b_idx, src, nown][:, None, None],
+                     k_branch=inp["k_branch"][b_idx, src, nown][:, None, None],
+                     v_branch=inp["v_branch"][b_idx, src, nown][:, None, None])
+        got, got_lse = oracle.verify_attention(**after, **attn_kwargs(case))
+        for b in range(case.B):
+            assert np.array_equal(got[b, 0, 0], ref[b, src[b], nown[b]]), (trial, b)
+            assert np.array_equal(got_lse[b, 0, 0], ref_lse[b, src[b], nown[b]])
+
+
+@pytest.mark.parametrize("case,C", CASES, ids=lambda x: getattr(x, "name", None))
+def test_only_the_appended_positions_change(oracle, case, C):
+    inp = W.make_attention_inputs(case)
+    chain = W.make_chain_inputs(case, C, inp)
+    dec = W.make_commit_inputs(case, C)
+    kc, vc, new_lens = commit(oracle, case, inp, chain, dec)
+    changed = np.zeros(inp["k_cache"].shape[:1] + inp["k_cache"].shape[2:3], dtype=bool)    # [block, slot]
+    bs = case.block_size
+    for b in range(case.B):
+        for pos in range(int(inp["prefix_lens"][b]), int(new_lens[b])):
+            blk = inp["block_tables"][b, pos // bs] if inp["block_tables"] is not None else b * case.max_blocks + pos // bs
+            changed[blk, pos % bs] = True
+    assert changed.sum() == int((dec["n_chain"] + dec["n_own"]).sum())
+    for new, old in ((kc, inp["k_cache"]), (vc, inp["v_cache"])):
+        same = (new == old).all(axis=(1, 3))                                                  # over heads and D
+        assert same[~changed].all()
+        assert not same[changed].any()          # random data: an appended token never equals what was there
+    # the inputs themselves are not written (the wrapper works on copies)
+    again = W.make_attention_inputs(case)
+    assert np.array_equal(again["k_cache"], inp["k_cache"])
+
+
+def test_nothing_to_commit_changes_nothing(oracle):
+    case, C = CASES[1]
+    inp = W.make_attention_inputs(case)
+    zeros = np.zeros(case.B, dtype=np.int32)
+    kc, vc, new_lens = commit(oracle, case, inp, None, W.make_commit_inputs(case, 0, (zeros, zeros, zeros)))
+    assert np.array_equal(kc, inp["k_cache"]) and np.array_equal(vc, inp["v_cache"])
+    assert np.array_equal(new_lens, inp["prefix_lens"])
+
+
+def test_commit_rejects_what_does_not_fit(oracle):
+    case, C = CASES[1]
+    inp = W.make_attention_inputs(case)
+    chain = W.make_chain_inputs(case, C, inp)
+    ok = (np.zeros(case.B, dtype=np.int32), np.full(case.B, C), np.full(case.B, case.L))
+    commit(oracle, case, inp, chain, W.make_commit_inputs(case, C, ok))
+    for bad in ((np.full(case.B, case.gamma), ok[1], ok[2]), (ok[0], np.full(case.B, C + 1), ok[2]),
+                (ok[0], ok[1], np.full(case.B, case.L + 1)), (np.full(case.B, -1), ok[1], ok[2])):
+        with pytest.raises(ValueError):
+            commit(oracle, case, inp, chain, W.make_commit_inputs(case, C, bad))
+    tight = replace(case, spare_tokens=10)                 # room for 10 more tokens, 50 asked for
+    inp = W.make_attention_inputs(tight)
+    with pytest.raises(ValueError):
+        commit(oracle, tight, inp, W.make_chain_inputs(tight, C, inp), W.make_commit_inputs(tight, C, ok))
+
+
+# ------------------------------------------------------------------------------------------ quantiser
+
+def torch_fp8_codes(y: np.ndarray) -> np.ndarray:
+    t = torch.from_numpy(y.astype(np.float32)).clamp(-448.0, 448.0).to(torch.float8_e4m3fn)
+    return t.view(torch.uint8).numpy()
+
+
+def test_quantiser_against_torch_and_the_generators_encoder(oracle):
+    rng = np.random.default_rng(5)
+    x = np.concatenate([
+        rng.standard_normal(20000).astype(np.float32) * 100,
+        rng.standard_normal(20000).astype(np.float32),
+        rng.standard_normal(20000).astype(np.float32) * 2.0 ** -7,            # subnormal range of e4m3
+        np.array([0.0, -0.0, 448.0, -448.0, 449.0, 464.0, 465.0, 1e6, -1e6, 2.0 ** -9, 2.0 ** -10, 3 * 2.0 ** -11],
+                 dtype=np.float32),
+    ])
+    got = oracle.quantize_fp8_e4m3(x, 1.0)
+    assert np.array_equal(got, torch_fp8_codes(x))
+    assert np.array_equal(got, W.encode_fp8_e4m3(x))
+
+
+def test_quantiser_ties_go_to_the_even_code_and_every_code_is_a_fixed_point(oracle):
+    codes = np.arange(127, dtype=np.uint8)
+    vals = oracle.widen(codes, "fp8_e4m3").astype(np.float32)
+    assert np.array_equal(oracle.quantize_fp8_e4m3(vals, 1.0), codes)
+    assert np.array_equal(oracle.quantize_fp8_e4m3(-vals, 1.0), codes | 0x80)
+    mid = ((vals[:-1].astype(np.float64) + vals[1:].astype(np.float64)) / 2).astype(np.float32)   # exact in fp32
+    want = np.where(codes[:-1] % 2 == 0, codes[:-1], codes[1:])
+    assert np.array_equal(oracle.quantize_fp8_e4m3(mid, 1.0), want)
+    just_above = np.nextafter(mid, np.float32(np.inf))
+    assert np.array_equal(oracle.quantize_fp8_e4m3(just_above, 1.0), codes[1:])
+
+
+def test_quantiser_divides_by_the_scale_in_fp32(oracle):
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal(50000).astype(np.float32) * 3
+    for scale in (np.float32(0.0123), np.float32(1 / 3), np.float32(7.0)):
+        y = x / scale                                             # numpy: IEEE fp32 division
+        assert np.array_equal(oracle.quantize_fp8_e4m3(x, float(scale)), torch_fp8_codes(y))
+
+
+def test_commit_into_an_fp8_cache_from_bf16_branches(oracle):
+    """The bytes written are the quantiser applied to (bf16 value / head scale), K with the K scales and V with the
+    V scales; the dequantised committed token is within half an e4m3 step of the source."""
+    case = W.AttnCase("commit_fp8_from_bf16", (50, 9), 3, 6, 4, 2, 128, "bf16", "fp8_e4m3", "bf16", "bf16", seed=24,
+                      spare_tokens=32)
+    C = 10
+    inp = W.make_attention_inputs(case)
+    chain = W.make_chain_inputs(case, C, inp)
+    dec = W.make_commit_inputs(case, C, ([2, 0], [10, 3], [6, 4]))
+    kc, vc, new_lens = commit(oracle, case, inp, chain, dec)
+    bs = case.block_size
+    for new, br, ch, scale in ((kc, inp["k_branch"], chain["k_chain"], inp["k_scale"]),
+                               (vc, inp["v_branch"], chain["v_chain"], inp["v_scale"])):
+        for b in range(case.B):
+            nch, nown, g = int(dec["n_chain"][b]), int(dec["n_own"][b]), int(dec["src_branch"][b])
+            src_bits = np.concatenate([ch[b, :nch], br[b, g, :nown]])                       # [n, Hkv, D] bf16 bits
+            src = (src_bits.astype(np.uint32) << 16).view(np.float32)
+            want = torch_fp8_codes(src / scale[None, :, None])
+            for t in range(nch + nown):
+                pos = int(inp["prefix_lens"][b]) + t
+                blk = b * case.max_blocks + pos // bs
+                assert np.array_equal(new[blk, :, pos % bs], want[t]), (b, t)
+            deq = oracle.widen(want, "fp8_e4m3") * scale[None, :, None]
+            step = np.maximum(np.abs(src) * 2.0 ** -4, scale[None, :, None] * 2.0 ** -10)   # half a step, or subnormal
+            assert (np.abs(deq - src) <= step).all()

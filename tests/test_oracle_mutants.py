@@ -56,6 +56,38 @@ MUTANTS = {
                         "softmax_row(draft_logits, logits_dtype, ((int64_t)nb * K + 0) * V"),
 }
 
+# KV commit: checked by its own pin file only
+COMMIT_MUTANTS = {
+    "commit_position_off_by_one": ("    int pos = prefix_lens[b]; /* next free position of the request */",
+                                   "    int pos = prefix_lens[b] + 1;"),
+    "commit_own_before_chain": ("      const int from_chain = t < n_chain[b];",
+                                "      const int from_chain = t >= n_own[b];"),
+    "commit_own_index_not_rebased": ("          const int i = t - n_chain[b];", "          const int i = t;"),
+    "commit_wrong_branch": ("src = ((((int64_t)b * gamma + src_branch[b]) * L + i) * Hkv + hk) * D;",
+                            "src = ((((int64_t)b * gamma + 0) * L + i) * Hkv + hk) * D;"),
+    "commit_chain_of_wrong_request": ("          src = (((int64_t)b * C + t) * Hkv + hk) * D;",
+                                      "          src = (((int64_t)0 * C + t) * Hkv + hk) * D;"),
+    "commit_block_table_ignored": ("      const int64_t phys = block_tables ? (int64_t)block_tables[(int64_t)b * max_blocks + logical_block]",
+                                   "      const int64_t phys = 0 ? (int64_t)block_tables[(int64_t)b * max_blocks + logical_block]"),
+    "commit_slot_in_block": ("const int64_t dst = ((phys * Hkv + hk) * block_size + (pos % block_size)) * D;",
+                             "const int64_t dst = ((phys * Hkv + hk) * block_size + (t % block_size)) * D;"),
+    "commit_v_from_k": ("if (commit_row(vs, br_dtype, src, v_cache, kv_dtype, dst, D, v_scale, hk)) return 2;",
+                        "if (commit_row(ks, br_dtype, src, v_cache, kv_dtype, dst, D, v_scale, hk)) return 2;"),
+    "commit_k_scale_on_v": ("if (commit_row(vs, br_dtype, src, v_cache, kv_dtype, dst, D, v_scale, hk)) return 2;",
+                            "if (commit_row(vs, br_dtype, src, v_cache, kv_dtype, dst, D, k_scale, hk)) return 2;"),
+    "commit_new_len_without_chain": ("    new_prefix_lens[b] = pos;", "    new_prefix_lens[b] = prefix_lens[b] + n_own[b];"),
+    "quantiser_multiplies": ("      const float y = x / s; /* fp32 quotient, correctly rounded */",
+                             "      const float y = x * s;"),
+    "quantiser_scale_of_head_0": ("    const float s = scale ? scale[hk] : 1.0f;", "    const float s = scale ? scale[0] : 1.0f;"),
+    "quantiser_ties_up": ("    if (d < best_d || (d == best_d && (code & 1) == 0)) {", "    if (d <= best_d) {"),
+    "quantiser_ties_down": ("    if (d < best_d || (d == best_d && (code & 1) == 0)) {", "    if (d < best_d) {"),
+    "quantiser_no_saturation": ("  if (a > 448.0) best = 126;\n", "  if (a > 448.0) best = 127;\n"),
+    "quantiser_drops_sign": ("  return (uint8_t)(best | (signbit(y) ? 0x80 : 0));", "  return (uint8_t)best;"),
+}
+SUITES = {name: ["tests/test_oracle_attention.py", "tests/test_oracle_accept.py"] for name in MUTANTS}
+SUITES.update({name: ["tests/test_oracle_commit.py"] for name in COMMIT_MUTANTS})
+MUTANTS.update(COMMIT_MUTANTS)
+
 
 @pytest.mark.parametrize("name", sorted(MUTANTS))
 def test_pins_reject_mutant(name, tmp_path):
@@ -67,6 +99,6 @@ def test_pins_reject_mutant(name, tmp_path):
     subprocess.run(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-w", "-o", str(lib), str(src), "-lm"], check=True)
     env = dict(os.environ, LA_ORACLE_LIB=str(lib))
     r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
-                        "tests/test_oracle_attention.py", "tests/test_oracle_accept.py"],
+                        *SUITES[name]],
                        cwd=ROOT, env=env, capture_output=True, text=True, timeout=300)
     assert r.returncode == 1, f"mutant {name} was not caught:\n{r.stdout[-2000:]}"
