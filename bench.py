@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--chain-len", type=int, default=0,
                     help="nested branches: a drafted chain of this many tokens per request, of which branch g sees "
                          "the first g/gamma (la_verify_attention_nested); 0 = the flat form, the headline workload")
+    ap.add_argument("--kv-commit", action="store_true",
+                    help="measure la_kv_commit instead (the step after the pass: all layers' surviving K/V appended "
+                         "to the paged cache in one launch) and print its JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (three times) before the timed region, so that a counter "
                          "run can scale FETCH_SIZE / WRITE_SIZE by what they read for a kernel of known traffic")
@@ -57,12 +60,157 @@ def read_traffic(name: str):
     return None
 
 
+def bench_commit(args):
+    """la_kv_commit at the headline configuration's shape: every layer of the model in one launch, the whole chain
+    and a whole branch surviving (the most a pass can append)."""
+    from dataclasses import replace
+
+    import numpy as np
+    import torch
+
+    from paper_2506_19830_amd import binding as B
+    from paper_2506_19830_amd import workloads as W
+
+    B.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    base, _ = W.config(args.config)
+    C = args.chain_len if args.chain_len > 0 else (base.gamma - 1) * base.L
+    n_layers = args.layers if args.layers is not None else W.NUM_LAYERS_CFG5
+    sz = {"f32": 4, "bf16": 2, "fp8_e4m3": 1}
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch.float8_e4m3fn}
+    results = {}
+    for label, br_dtype in (("same_dtype", base.branch_kv_dtype), ("quantising", "bf16")):
+        if label == "quantising" and base.kv_dtype != "fp8_e4m3":
+            continue
+        case = replace(base, branch_kv_dtype=br_dtype, spare_tokens=C + base.L)
+        nb = case.B * case.max_blocks
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(777)
+
+        def rnd(shape, dtype):
+            if dtype == "fp8_e4m3":   # random codes, NaN patterns excluded
+                return torch.randint(0, 0x7f, shape, generator=gen, device=dev, dtype=torch.uint8).view(tdt[dtype])
+            return torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(tdt[dtype])
+
+        # several independent sets of tensors, used in rotation, so that a call finds neither its sources nor its
+        # destination lines in the 256 MB last-level cache from the call before
+        n_sets = 4
+        sets = []
+        for _ in range(n_sets):
+            sets.append(dict(
+                kc=rnd((n_layers, nb, case.Hkv, case.block_size, case.D), case.kv_dtype),
+                vc=rnd((n_layers, nb, case.Hkv, case.block_size, case.D), case.kv_dtype),
+                kb=rnd((n_layers, case.B, case.gamma, case.L, case.Hkv, case.D), br_dtype),
+                vb=rnd((n_layers, case.B, case.gamma, case.L, case.Hkv, case.D), br_dtype),
+                kch=rnd((n_layers, case.B, C, case.Hkv, case.D), br_dtype),
+                vch=rnd((n_layers, case.B, C, case.Hkv, case.D), br_dtype)))
+        kc, vc, kb, vb, kch, vch = (sets[0][k] for k in ("kc", "vc", "kb", "vb", "kch", "vch"))
+        ks = vs = None
+        if case.kv_dtype == "fp8_e4m3":
+            ks = (torch.rand((n_layers, case.Hkv), generator=gen, device=dev) * 0.02 + 0.005).float()
+            vs = (torch.rand((n_layers, case.Hkv), generator=gen, device=dev) * 0.02 + 0.005).float()
+        lens = [int(x) for x in case.prefix_lens]
+        d_lens = torch.tensor(lens, dtype=torch.int32, device=dev)
+        src = torch.full((case.B,), case.gamma - 1, dtype=torch.int32, device=dev)
+        nch = torch.full((case.B,), C, dtype=torch.int32, device=dev)
+        nown = torch.full((case.B,), case.L, dtype=torch.int32, device=dev)
+        new_lens = torch.zeros((case.B,), dtype=torch.int32, device=dev)
+        desc = B.make_attn_desc(num_requests=case.B, num_q_heads=case.Hq, num_kv_heads=case.Hkv, head_dim=case.D,
+                                gamma=case.gamma, branch_len=case.L, block_size=case.block_size,
+                                max_blocks_per_request=case.max_blocks, q_dtype=case.q_dtype, kv_dtype=case.kv_dtype,
+                                branch_kv_dtype=br_dtype, out_dtype=case.out_dtype, softmax_scale=case.scale)
+        strides = B.la_layer_strides(num_layers=n_layers, cache_stride=kc[0].numel(), branch_stride=kb[0].numel(),
+                                     chain_stride=kch[0].numel(), scale_stride=case.Hkv)
+        before = {l: (W.device_bits(kc[l], case.kv_dtype).copy(), W.device_bits(vc[l], case.kv_dtype).copy())
+                  for l in sorted({0, n_layers - 1})}
+
+        calls = [0]
+
+        def step():
+            t = sets[calls[0] % n_sets]
+            calls[0] += 1
+            B.la_kv_commit(desc, t["kc"], t["vc"], None, d_lens, lens, t["kb"], t["vb"], t["kch"], t["vch"], src, nch,
+                           nown, ks, vs, new_lens, strides)
+
+        for _ in range(max(args.warmup, n_sets)):
+            step()
+        torch.cuda.synchronize()
+        B.la_profile_reset()
+        B.la_profile_select(["kv_commit"], 1)
+        B.la_profile_enable(True)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        B.la_profile_enable(False)
+        launches, ms = B.la_profile_collect()["kv_commit"]
+        B.la_profile_reset()
+        tokens = case.B * (C + case.L)
+        alg_bytes = 2.0 * tokens * case.Hkv * case.D * (sz[br_dtype] + sz[case.kv_dtype]) * n_layers
+        avg_ms = ms / max(1, launches)
+        res = {"avg_launch_ms": avg_ms, "wall_ms_per_call": (t1 - t0) * 1e3 / args.steps,
+               "algorithmic_bytes_per_launch": alg_bytes, "gbs": alg_bytes / (avg_ms * 1e-3) / 1e9,
+               "tokens": tokens, "layers": n_layers, "src": br_dtype, "dst": case.kv_dtype}
+        if not args.no_cpu_baseline:
+            import oracle
+            oracle.build()
+            t_cpu, ok = 0.0, True
+            for l, (k0, v0) in before.items():
+                t0 = time.perf_counter()
+                rk, rv, rl = oracle.kv_commit(
+                    k0, v0, None, np.array(lens, dtype=np.int32), W.device_bits(kb[l], br_dtype),
+                    W.device_bits(vb[l], br_dtype), W.device_bits(kch[l], br_dtype), W.device_bits(vch[l], br_dtype),
+                    src.cpu().numpy(), nch.cpu().numpy(), nown.cpu().numpy(),
+                    None if ks is None else ks[l].cpu().numpy(), None if vs is None else vs[l].cpu().numpy(),
+                    kv_dtype=case.kv_dtype, branch_kv_dtype=br_dtype, block_size=case.block_size)
+                t_cpu += time.perf_counter() - t0
+                ok &= bool(np.array_equal(W.device_bits(kc[l], case.kv_dtype), rk))
+                ok &= bool(np.array_equal(W.device_bits(vc[l], case.kv_dtype), rv))
+                ok &= bool(np.array_equal(new_lens.cpu().numpy(), rl))
+            res["parity_bytes_equal_on_sampled_layers"] = ok
+            res["cpu_oracle_s_per_layer"] = t_cpu / len(before)
+        results[label] = res
+        del kc, vc, kb, vb, kch, vch, sets
+        torch.cuda.empty_cache()
+
+    main_res = results["same_dtype"]
+    out = {
+        "metric": "KV commit: appended K/V bytes moved per second, all layers in one launch",
+        "value": main_res["gbs"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_res["wall_ms_per_call"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u8" if main_res["src"] == "fp8_e4m3" else main_res["src"],
+        "data": "synthetic",
+        "config": {"workload": f"config {args.config} shape, {n_layers} layers, {main_res['tokens']} tokens appended "
+                               f"(chain {C} + branch {base.L}), {base.Hkv} kv heads, D {base.D}, "
+                               f"{main_res['src']} -> {main_res['dst']}"},
+        "roofline": {"kernel": "kv_commit_kernel", "bound": "hbm", "achieved": main_res["gbs"], "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": main_res["gbs"] / PEAK_HBM_GBS, "traffic": None,
+                     "avg_launch_ms": main_res["avg_launch_ms"],
+                     "algorithmic_bytes_per_launch": main_res["algorithmic_bytes_per_launch"]},
+        "variants": results,
+    }
+    if "cpu_oracle_s_per_layer" in main_res:
+        out["cpu_baseline"] = {"value": main_res["algorithmic_bytes_per_launch"] / n_layers /
+                               main_res["cpu_oracle_s_per_layer"] / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": "first and last layer in full, per-layer mean"}
+    print(json.dumps(out))
+    return 0
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
               file=sys.stderr)
         return 2
+    if args.kv_commit:
+        import torch
+        if not torch.cuda.is_available():
+            print("bench.py: no GPU visible", file=sys.stderr)
+            return 2
+        return bench_commit(args)
 
     import numpy as np
     import torch

@@ -134,6 +134,72 @@ LA_API la_status la_verify_attention_nested(
     void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* ------------------------------------------------------------------------- *
+ *  la_kv_commit
+ *
+ *  Algorithm 1, once j* is known: the output  s^_0 .. s^_{j*-1} (+) s_{j*}
+ *  becomes part of x.  For the cache that means: per request, the first
+ *  n_chain[b] tokens of the drafted chain and then the first n_own[b] tokens
+ *  of branch src_branch[b] are appended behind the prefix, token t of that
+ *  sequence at position prefix_lens[b] + t through the block table, and
+ *  new_prefix_lens[b] = prefix_lens[b] + n_chain[b] + n_own[b].  Everything
+ *  else of the pass's private K/V is simply not copied.
+ *
+ *  The three decisions are device arrays (they come out of the accept step),
+ *  so nothing here waits for the host; the kernel clamps them to their ranges
+ *  (branch 0..gamma-1, n_chain 0..chain_len, n_own 0..branch_len) and never
+ *  writes past max_blocks_per_request * block_size.  Because the host cannot
+ *  see them, the block table must already map room for the most that can be
+ *  appended: prefix_lens_host[b] + chain_len + branch_len positions, else
+ *  LA_ERR_INVALID_ARG.
+ *
+ *  Storage: kv_dtype == branch_kv_dtype copies bytes (an fp8 branch already
+ *  carries the cache's scales).  A bf16 source with an fp8 cache is quantised:
+ *  code = e4m3fn(x / scale[head]), the quotient in fp32, round to nearest even,
+ *  saturating at +-448.  Other pairs: LA_ERR_UNSUPPORTED.  head_dim % 16 == 0.
+ *
+ *  All layers of a model take the same decisions; `layers` (may be NULL = one
+ *  layer) lets one call commit them all: layer l's tensors start l * stride
+ *  ELEMENTS after layer 0's (cache_stride for k_cache and v_cache,
+ *  branch_stride for k_branch and v_branch, chain_stride for the chain,
+ *  scale_stride for k_scale and v_scale, 0 = shared scales); each layer's
+ *  tensors must start 16-byte aligned.  block_tables, prefix_lens and the
+ *  decisions are shared by all layers.
+ *
+ *  new_prefix_lens must not alias prefix_lens.  No workspace, no
+ *  synchronisation, deterministic.  desc: the fields of the verification call
+ *  (q_dtype, out_dtype, softmax_scale and kv_split_tokens are not used but
+ *  must be valid).
+ * ------------------------------------------------------------------------- */
+typedef struct {
+  int32_t num_layers;     /* 1..65535 */
+  int64_t cache_stride;   /* elements */
+  int64_t branch_stride;
+  int64_t chain_stride;
+  int64_t scale_stride;
+} la_layer_strides;
+
+LA_API la_status la_kv_commit(
+    const la_attn_desc *desc,
+    void *k_cache,                   /* dev, written: [num_blocks, Hkv, block_size, D] per layer   */
+    void *v_cache,
+    const int32_t *block_tables,     /* dev [B, max_blocks_per_request] or NULL (identity)          */
+    const int32_t *prefix_lens,      /* dev [B]                                                     */
+    const int32_t *prefix_lens_host, /* host [B], same values (room check)                         */
+    const void *k_branch,            /* dev [B, gamma, L, Hkv, D] per layer                        */
+    const void *v_branch,
+    const void *k_chain,             /* dev [B, chain_len, Hkv, D] per layer; NULL if chain_len 0  */
+    const void *v_chain,
+    int32_t chain_len,
+    const int32_t *src_branch,       /* dev [B]                                                     */
+    const int32_t *n_chain,          /* dev [B]                                                     */
+    const int32_t *n_own,            /* dev [B]                                                     */
+    const float *k_scale,            /* dev [Hkv] per layer, or NULL = 1 (used when quantising)    */
+    const float *v_scale,
+    int32_t *new_prefix_lens,        /* dev [B], written                                           */
+    const la_layer_strides *layers,  /* host, or NULL                                              */
+    void *hip_stream);
+
+/* ------------------------------------------------------------------------- *
  *  la_spec_accept
  *
  *  Token-level speculative sampling (Section 2): with p_i = softmax(target

@@ -24,7 +24,8 @@ DTYPE_CODES = {"f32": LA_F32, "bf16": LA_BF16, "fp8_e4m3": LA_FP8_E4M3}
 _TORCH_DTYPES = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch.float8_e4m3fn}
 
 EXPORTED_SYMBOLS = (
-    "la_verify_attention_workspace", "la_verify_attention", "la_verify_attention_nested", "la_spec_accept_workspace",
+    "la_verify_attention_workspace", "la_verify_attention", "la_verify_attention_nested", "la_kv_commit",
+    "la_spec_accept_workspace",
     "la_spec_accept",
     "la_status_string", "la_profile_enable", "la_profile_select", "la_profile_collect", "la_profile_num_kernels", "la_profile_get",
     "la_profile_reset",
@@ -42,6 +43,11 @@ class la_accept_desc(ctypes.Structure):
     _fields_ = [("num_branches", ctypes.c_int32), ("num_draft", ctypes.c_int32), ("vocab", ctypes.c_int32),
                 ("logits_dtype", ctypes.c_int32), ("temperature", ctypes.c_float), ("top_k", ctypes.c_int32),
                 ("top_p", ctypes.c_float)]
+
+
+class la_layer_strides(ctypes.Structure):
+    _fields_ = [("num_layers", ctypes.c_int32), ("cache_stride", ctypes.c_int64), ("branch_stride", ctypes.c_int64),
+                ("chain_stride", ctypes.c_int64), ("scale_stride", ctypes.c_int64)]
 
 
 class LaError(RuntimeError):
@@ -75,6 +81,10 @@ def load() -> ctypes.CDLL:
                                                    ctypes.POINTER(ctypes.c_int32), vp, vp, vp, vp, ctypes.c_int32, i32p,
                                                    ctypes.POINTER(ctypes.c_int32), vp, vp, vp, vp, vp, ctypes.c_size_t,
                                                    vp]
+        lib.la_kv_commit.restype = ctypes.c_int
+        lib.la_kv_commit.argtypes = [ctypes.POINTER(la_attn_desc), vp, vp, i32p, i32p, ctypes.POINTER(ctypes.c_int32),
+                                     vp, vp, vp, vp, ctypes.c_int32, i32p, i32p, i32p, vp, vp, i32p,
+                                     ctypes.POINTER(la_layer_strides), vp]
         lib.la_spec_accept_workspace.restype = ctypes.c_int
         lib.la_spec_accept_workspace.argtypes = [ctypes.POINTER(la_accept_desc), ctypes.POINTER(ctypes.c_size_t)]
         lib.la_spec_accept.restype = ctypes.c_int
@@ -158,6 +168,24 @@ def la_verify_attention_nested(desc: la_attn_desc, q, k_cache, v_cache, block_ta
                                            _ptr(out), _ptr(lse), _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream())
     if st:
         raise LaError(st, "la_verify_attention_nested")
+
+
+def la_kv_commit(desc: la_attn_desc, k_cache, v_cache, block_tables, prefix_lens, prefix_lens_host, k_branch, v_branch,
+                 k_chain, v_chain, src_branch, n_chain, n_own, k_scale, v_scale, new_prefix_lens,
+                 layers: Optional[la_layer_strides] = None) -> None:
+    """Append the surviving tokens' K/V to the paged cache (in place) and write the grown prefix lengths.
+    ``k_chain`` may be None (no chain).  With ``layers`` the tensors hold that many layers back to back."""
+    if k_chain is None:
+        C = 0
+    else:
+        C = int(k_chain.shape[-3])   # [.., C, Hkv, D]
+    st = load().la_kv_commit(ctypes.byref(desc), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables), _ptr(prefix_lens),
+                             _host_lens(prefix_lens_host), _ptr(k_branch), _ptr(v_branch), _ptr(k_chain),
+                             _ptr(v_chain), ctypes.c_int32(C), _ptr(src_branch), _ptr(n_chain), _ptr(n_own),
+                             _ptr(k_scale), _ptr(v_scale), _ptr(new_prefix_lens),
+                             ctypes.byref(layers) if layers is not None else None, _stream())
+    if st:
+        raise LaError(st, "la_kv_commit")
 
 
 def make_accept_desc(*, num_branches, num_draft, vocab, logits_dtype, temperature=1.0, top_k=0,

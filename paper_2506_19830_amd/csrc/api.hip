@@ -141,7 +141,7 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, Attn
 
 // ---- profiling ---------------------------------------------------------------------------------
 const char *kSlotNames[SLOT_COUNT] = {"attn_mfma",     "attn_merge",   "attn_f32",   "accept_stats", "accept_warp",
-                                      "accept_decide", "accept_resid", "accept_pick"};
+                                      "accept_decide", "accept_resid", "accept_pick", "kv_commit"};
 struct ProfileRecord {
   int slot;
   hipEvent_t start, stop;
@@ -286,6 +286,65 @@ la_status la_verify_attention(const la_attn_desc *desc, const void *q, const voi
   return la_verify_attention_nested(desc, q, k_cache, v_cache, block_tables, prefix_lens, prefix_lens_host, k_branch,
                                     v_branch, nullptr, nullptr, 0, nullptr, nullptr, k_scale, v_scale, out, lse,
                                     workspace, workspace_bytes, hip_stream);
+}
+
+la_status la_kv_commit(const la_attn_desc *desc, void *k_cache, void *v_cache, const int32_t *block_tables,
+                       const int32_t *prefix_lens, const int32_t *prefix_lens_host, const void *k_branch,
+                       const void *v_branch, const void *k_chain, const void *v_chain, int32_t chain_len,
+                       const int32_t *src_branch, const int32_t *n_chain, const int32_t *n_own, const float *k_scale,
+                       const float *v_scale, int32_t *new_prefix_lens, const la_layer_strides *layers,
+                       void *hip_stream) {
+  la_status st = validate_desc(desc);
+  if (st != LA_OK) return st;
+  if (!k_cache || !v_cache || !prefix_lens || !prefix_lens_host || !k_branch || !v_branch || !src_branch ||
+      !n_chain || !n_own || !new_prefix_lens)
+    return LA_ERR_INVALID_ARG;
+  if (new_prefix_lens == prefix_lens) return LA_ERR_INVALID_ARG;  // read by every workgroup while one writes
+  if (chain_len < 0 || (chain_len > 0 && (!k_chain || !v_chain))) return LA_ERR_INVALID_ARG;
+  if (!aligned16(k_cache) || !aligned16(v_cache) || !aligned16(k_branch) || !aligned16(v_branch) ||
+      !aligned16(k_chain) || !aligned16(v_chain))
+    return LA_ERR_INVALID_ARG;
+  const int kv = desc->kv_dtype, br = desc->branch_kv_dtype;
+  const bool quantise = kv == LA_FP8_E4M3 && br == LA_BF16;
+  if (kv != br && !quantise) return LA_ERR_UNSUPPORTED;
+  if (desc->head_dim % 16) return LA_ERR_UNSUPPORTED;
+  const int64_t capacity = (int64_t)desc->max_blocks_per_request * desc->block_size;
+  // what is appended is decided on the device; the block table must have room for the most it can be
+  for (int b = 0; b < desc->num_requests; ++b)
+    if (prefix_lens_host[b] < 0 || (int64_t)prefix_lens_host[b] + chain_len + desc->branch_len > capacity)
+      return LA_ERR_INVALID_ARG;
+  const int n_layers = layers ? layers->num_layers : 1;
+  if (n_layers < 1 || n_layers > 65535 || desc->num_requests > 65535) return LA_ERR_INVALID_ARG;
+  const int elem_bytes[3] = {4, 2, 1};  // LA_F32, LA_BF16, LA_FP8_E4M3
+  if (layers) {
+    if (layers->cache_stride < 0 || layers->branch_stride < 0 || layers->chain_stride < 0 ||
+        layers->scale_stride < 0)
+      return LA_ERR_INVALID_ARG;
+    // every layer's tensors must start on a 16-byte boundary
+    if ((layers->cache_stride * elem_bytes[kv]) % 16 || (layers->branch_stride * elem_bytes[br]) % 16 ||
+        (layers->chain_stride * elem_bytes[br]) % 16)
+      return LA_ERR_INVALID_ARG;
+  }
+
+  CommitParams p;
+  memset(&p, 0, sizeof p);
+  p.k_cache = k_cache, p.v_cache = v_cache;
+  p.k_branch = k_branch, p.v_branch = v_branch, p.k_chain = k_chain, p.v_chain = v_chain;
+  p.block_tables = block_tables, p.prefix_lens = prefix_lens;
+  p.src_branch = src_branch, p.n_chain = n_chain, p.n_own = n_own;
+  p.k_scale = k_scale, p.v_scale = v_scale;
+  p.new_prefix_lens = new_prefix_lens;
+  p.B = desc->num_requests, p.Hkv = desc->num_kv_heads, p.D = desc->head_dim, p.gamma = desc->gamma;
+  p.L = desc->branch_len, p.C = chain_len;
+  p.block_size = desc->block_size, p.block_shift = __builtin_ctz((unsigned)desc->block_size);
+  p.max_blocks = desc->max_blocks_per_request;
+  p.capacity = (int)capacity;
+  p.num_layers = n_layers;
+  if (layers) {
+    p.cache_stride = layers->cache_stride, p.branch_stride = layers->branch_stride;
+    p.chain_stride = layers->chain_stride, p.scale_stride = layers->scale_stride;
+  }
+  return launch_kv_commit(p, elem_bytes[br], quantise, (hipStream_t)hip_stream) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }
 
 static la_status validate_accept(const la_accept_desc *d) {

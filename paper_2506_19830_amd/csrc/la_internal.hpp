@@ -59,6 +59,7 @@ enum KernelSlot {
   SLOT_ACCEPT_DECIDE,
   SLOT_ACCEPT_RESID,
   SLOT_ACCEPT_PICK,
+  SLOT_KV_COMMIT,
   SLOT_COUNT
 };
 
@@ -103,6 +104,22 @@ struct AcceptParams {
 size_t accept_workspace_bytes(int NB, int K, int V, bool bf16, int *n_chunks_out, int *n_fine_out);
 void accept_carve_workspace(AcceptParams &p, void *ws);
 hipError_t launch_accept(const AcceptParams &p, hipStream_t stream);
+
+// ----------------------------------------------------------------------------
+// KV commit.
+// ----------------------------------------------------------------------------
+struct CommitParams {
+  void *k_cache, *v_cache;  // [layers][num_blocks, Hkv, block_size, D], written
+  const void *k_branch, *v_branch, *k_chain, *v_chain;
+  const int32_t *block_tables, *prefix_lens, *src_branch, *n_chain, *n_own;
+  const float *k_scale, *v_scale;
+  int32_t *new_prefix_lens;
+  int B, Hkv, D, gamma, L, C, block_size, block_shift, max_blocks, num_layers;
+  int capacity;                                                     // max_blocks * block_size
+  int64_t cache_stride, branch_stride, chain_stride, scale_stride;  // elements between consecutive layers
+};
+// src_bytes: storage size of a source element; quantise: bf16 source into an fp8 cache
+hipError_t launch_kv_commit(const CommitParams &p, int src_bytes, bool quantise, hipStream_t stream);
 
 // ----------------------------------------------------------------------------
 // Optional per-kernel event timing (see la_profile_* in the public header).

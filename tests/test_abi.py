@@ -31,6 +31,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(B.la_attn_desc) == 14 * 4
     assert ctypes.sizeof(B.la_accept_desc) == 7 * 4
+    assert ctypes.sizeof(B.la_layer_strides) == 8 + 4 * 8        # int32 padded to the int64 that follows
 
 
 def test_status_strings():
@@ -116,6 +117,34 @@ def test_nested_attention_call_rejects_before_launch():
     # valid chain arguments get as far as the workspace check (nothing is launched: the workspace is too small)
     assert call(4, vis=[4] * n_vis) == 3
     assert call(0, k_chain=0, v_chain=0, vis_dev=0, vis_host_null=True) == 3
+
+
+def test_kv_commit_rejects_before_launch():
+    lib = B.load()
+    vp = ctypes.c_void_p
+    lens = (ctypes.c_int32 * 1)(32768)
+
+    def call(desc, chain_len=8, strides=None, **ptrs):
+        g = lambda k, dflt=256: vp(ptrs.get(k, dflt))
+        return lib.la_kv_commit(ctypes.byref(desc), g("kc"), g("vc"), vp(0), g("lens"), lens, g("kb"), g("vb"),
+                                g("kch"), g("vch"), ctypes.c_int32(chain_len), g("src"), g("nch"), g("nown"), vp(0),
+                                vp(0), g("new", 512), ctypes.byref(strides) if strides is not None else None, vp(0))
+
+    roomy = good_desc(max_blocks_per_request=2048 + 8)           # 32768 + 128 positions
+    assert call(good_desc()) == 1                                # table maps exactly the prefix: no room
+    assert call(roomy, kc=0) == 1
+    assert call(roomy, kch=0) == 1                               # chain_len 8 without a chain
+    assert call(roomy, chain_len=-1) == 1
+    assert call(roomy, kb=264) == 1                              # not 16-byte aligned
+    assert call(roomy, new=256, lens=256) == 1                   # new lengths alias the old ones
+    assert call(good_desc(max_blocks_per_request=2048 + 8, kv_dtype="bf16", branch_kv_dtype="bf16",
+                          head_dim=100)) == 2
+    assert call(good_desc(max_blocks_per_request=2048 + 8, q_dtype="f32", kv_dtype="f32",
+                          branch_kv_dtype="bf16", out_dtype="f32")) == 2   # no such conversion
+    bad = B.la_layer_strides(num_layers=0)
+    assert call(roomy, strides=bad) == 1
+    odd = B.la_layer_strides(num_layers=2, cache_stride=1 << 20, branch_stride=7, chain_stride=1 << 10)
+    assert call(roomy, strides=odd) == 1                         # layer 1 of the branch tensors would be unaligned
 
 
 def test_accept_rejects_bad_arguments():
