@@ -102,3 +102,40 @@ def test_pins_reject_mutant(name, tmp_path):
                         *SUITES[name]],
                        cwd=ROOT, env=env, capture_output=True, text=True, timeout=300)
     assert r.returncode == 1, f"mutant {name} was not caught:\n{r.stdout[-2000:]}"
+
+
+# ---- the planner oracle is Python: same idea, on its source text ------------------------------------------------
+PLANNER_SRC = (ROOT / "oracle" / "planner.py").read_text()
+PLANNER_MUTANTS = {
+    "first_rejection_returns_last": ("        if not ok:\n            return j\n", "        if not ok:\n            last = j\n"),
+    "all_accepted_off_by_one": ("    return len(verdicts)\n", "    return len(verdicts) - 1\n"),
+    "output_keeps_own_of_next_branch": ("out.append((j, j, int(vis[j]), int(own[j])))",
+                                        "out.append((j, j, int(vis[j]), int(own[min(j + 1, len(own) - 1)])))"),
+    "output_chain_of_previous_branch": ("out.append((j, j, int(vis[j]), int(own[j])))",
+                                        "out.append((j, j, int(vis[max(j - 1, 0)]), int(own[j])))"),
+    "sync_counts_k_drafts": ("    emitted = _expect(alpha, lambda x: min(x, k - 1) + 1)\n    return emitted / ((k - 1) * c + 1.0)",
+                             "    emitted = _expect(alpha, lambda x: min(x, k - 1) + 1)\n    return emitted / (k * c + 1.0)"),
+    "sync_emits_up_to_k_drafts": ("lambda x: min(x, k - 1) + 1)", "lambda x: min(x, k) + 1)"),
+    "async_floor_instead_of_ceil": ("lambda x: -(-(x + 1) // k) + c * (x % k))", "lambda x: (x + 1) // k + c * (x % k))"),
+    "async_mod_of_x_plus_1": ("lambda x: -(-(x + 1) // k) + c * (x % k))", "lambda x: -(-(x + 1) // k) + c * ((x + 1) % k))"),
+    "async_case_switch_strict": ("    if k >= depth_limit(c):", "    if k > depth_limit(c):"),
+    "depth_limit_floor": ("    return int(math.ceil(1.0 / c))", "    return int(math.floor(1.0 / c))"),
+    "geometric_law_shifted": ("    total, n, w = 0.0, 0, 1.0 - alpha", "    total, n, w = 0.0, 1, 1.0 - alpha"),
+    "async_budget_uses_k1": ("    return min(depth_limit(c1), k1) if asynchronous else k1", "    return k1"),
+    "budget_is_a_sum": ("            if parallel_dim_f(c1, k1, asynchronous) * k2 > budget:",
+                        "            if parallel_dim_f(c1, k1, asynchronous) + k2 > budget:"),
+    "plan_minimises": ("            if best is None or h > best[2]:", "            if best is None or h < best[2]:"),
+    "token_level_uses_step_parameters": ("    g = {k2: speedup_sync(alpha2, c2, k2)", "    g = {k2: speedup_sync(alpha1, c1, k2)"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(PLANNER_MUTANTS))
+def test_planner_pins_reject_mutant(name, tmp_path):
+    old, new = PLANNER_MUTANTS[name]
+    assert PLANNER_SRC.count(old) == 1, f"mutation site for {name} not found exactly once"
+    src = tmp_path / "planner_mutant.py"
+    src.write_text(PLANNER_SRC.replace(old, new))
+    env = dict(os.environ, LA_ORACLE_PLANNER_SRC=str(src))
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
+                        "tests/test_oracle_planner.py"], cwd=ROOT, env=env, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 1, f"mutant {name} was not caught:\n{r.stdout[-2000:]}"
