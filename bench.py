@@ -43,6 +43,9 @@ def parse_args():
     ap.add_argument("--kv-commit", action="store_true",
                     help="measure la_kv_commit instead (the step after the pass: all layers' surviving K/V appended "
                          "to the paged cache in one launch) and print its JSON line")
+    ap.add_argument("--planner", action="store_true",
+                    help="time the host-only budget planner (la_plan_budget) and the step selection instead; no GPU "
+                         "work; prints its own JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (three times) before the timed region, so that a counter "
                          "run can scale FETCH_SIZE / WRITE_SIZE by what they read for a kernel of known traffic")
@@ -199,8 +202,52 @@ def bench_commit(args):
     return 0
 
 
+def bench_planner(args):
+    """Host-only: plans per second of la_plan_budget over a sweep of parameters in the paper's ranges (Section 3.3:
+    acceptance 0.52..0.8, c1 < 1/3, c2 < 1/5) at budgets 16..64, and la_step_select over a batch of requests."""
+    import numpy as np
+
+    from paper_2506_19830_amd import binding as B
+    params = [(a1, c1, a2, c2, M, asyn) for a1 in (0.53, 0.62, 0.71, 0.79) for c1 in (0.05, 0.15, 0.3)
+              for a2 in (0.55, 0.7) for c2 in (0.05, 0.15) for M in (16, 32, 64) for asyn in (False, True)]
+    reps = max(1, args.steps)
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        plans = [B.la_plan_budget(*p) for p in params]
+    t_lib = (time.perf_counter() - t0) / (reps * len(params))
+    rng = np.random.default_rng(0)
+    verdicts = rng.random((4096, 8)) < 0.7
+    vis = np.sort(rng.integers(0, 512, size=(4096, 9)), axis=1)
+    own = rng.integers(1, 65, size=(4096, 9))
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        B.la_step_select(verdicts, vis, own)
+    t_sel = (time.perf_counter() - t0) / reps
+    out = {"metric": "budget plans per second (host only)", "value": 1.0 / t_lib, "unit": "plans/s", "n_gpus": 0,
+           "steps": reps, "warmup": 0, "ms_per_step": t_lib * 1e3, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+           "config": {"workload": f"{len(params)} parameter sets, budgets 16/32/64, sync and async"},
+           "step_select": {"requests": 4096, "branches": 9, "us_per_call": t_sel * 1e6},
+           "hybrid_plans": sum(1 for k1, k2, _ in plans if k1 >= 2 and k2 >= 2), "plans": len(plans)}
+    if not args.no_cpu_baseline:
+        from oracle import planner as P
+        sample = params[:: max(1, len(params) // 24)]
+        t0 = time.perf_counter()
+        ref = [P.plan(*p)[:3] for p in sample]
+        t_or = (time.perf_counter() - t0) / len(sample)
+        got = [B.la_plan_budget(*p) for p in sample]
+        out["cpu_baseline"] = {"value": 1.0 / t_or, "unit": "plans/s", "cores": 1, "kind": "oracle",
+                               "sample": f"{len(sample)} of the parameter sets"}
+        out["parity"] = {"same_plan": sum(1 for g, r in zip(got, ref) if g[:2] == r[:2]), "of": len(sample),
+                         "max_rel_speedup_diff": max(abs(g[2] - r[2]) / r[2] for g, r in zip(got, ref))}
+    print(json.dumps(out))
+    return 0
+
+
 def main():
     args = parse_args()
+    if args.planner:
+        return bench_planner(args)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
               file=sys.stderr)

@@ -252,6 +252,54 @@ LA_API la_status la_spec_accept(
     void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* ------------------------------------------------------------------------- *
+ *  Step-level controller and budget planner (host only: every pointer below
+ *  is a host pointer, nothing touches the GPU).
+ *
+ *  la_step_select -- Algorithm 1, verification and output construction.
+ *  A pass has num_branches branches per request: branch j < num_branches-1
+ *  checks draft step j (verdicts[b][j] != 0: the verifier accepted it), the
+ *  last branch is the target's step behind all drafts.  j* = the first
+ *  rejected draft, or num_branches-1 when none was rejected.  The output
+ *  "accepted drafts, then the target's step j*" is what branch j* saw of the
+ *  drafted chain plus what it produced, so the arguments of la_kv_commit are
+ *  src_branch = j*, n_chain = chain_vis[b][j*], n_own = own_len[b][j*]
+ *  (own_len: tokens of the target's step held by each branch).  Any of
+ *  src_branch / n_chain / n_own may be NULL; chain_vis / own_len may be NULL
+ *  when the output they feed is.
+ *
+ *  la_speedup_* -- closed forms, alpha in (0,1) the acceptance rate, c in
+ *  (0,1) the draft's cost relative to the target, k >= 1 the depth:
+ *    step level, sync  (Section 3.2):  (1-a^k) / ((1-a)(1-c+ck))
+ *    step level, async (Section 3.2, Appendix B):
+ *        k >= ceil(1/c):  1 / (c + (1-c)(1-a))
+ *        else          :  (1-a^k) / ((1-a) + c [a - a^(k+1) - k(1-a)a^k])
+ *    token level (Section 3.3, g): the sync form with (alpha2, c2, k2).
+ *
+ *  la_plan_budget -- Section 3.3:  max f(k1) g(k2)  over integers k1, k2 >= 1
+ *  with ParallelDim_f * k2 <= budget, ParallelDim_f = k1 (sync) or
+ *  min(ceil(1/c1), k1) (async).  Exhaustive over the feasible pairs; among
+ *  equal maxima the smallest k1, then the smallest k2.  k1 = 1 is pure
+ *  token-level speculation, k2 = 1 pure lookahead reasoning.
+ * ------------------------------------------------------------------------- */
+typedef struct {
+  double alpha1, c1;     /* step level  */
+  double alpha2, c2;     /* token level */
+  int32_t budget;        /* M >= 1      */
+  int32_t asynchronous;  /* 0 = sync f, else async f */
+} la_plan_desc;
+
+LA_API la_status la_step_select(int32_t num_requests, int32_t num_branches,
+                                const uint8_t *verdicts,   /* [B, num_branches-1] */
+                                const int32_t *chain_vis,  /* [B, num_branches]   */
+                                const int32_t *own_len,    /* [B, num_branches]   */
+                                int32_t *j_star,           /* [B] out             */
+                                int32_t *src_branch, int32_t *n_chain, int32_t *n_own /* [B] out, optional */);
+LA_API la_status la_speedup_step_sync(double alpha1, double c1, int32_t k1, double *speedup);
+LA_API la_status la_speedup_step_async(double alpha1, double c1, int32_t k1, double *speedup);
+LA_API la_status la_speedup_token(double alpha2, double c2, int32_t k2, double *speedup);
+LA_API la_status la_plan_budget(const la_plan_desc *desc, int32_t *k1, int32_t *k2, double *speedup);
+
+/* ------------------------------------------------------------------------- *
  *  Diagnostics
  * ------------------------------------------------------------------------- */
 LA_API const char *la_status_string(la_status s);

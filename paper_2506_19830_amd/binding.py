@@ -25,6 +25,7 @@ _TORCH_DTYPES = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch
 
 EXPORTED_SYMBOLS = (
     "la_verify_attention_workspace", "la_verify_attention", "la_verify_attention_nested", "la_kv_commit",
+    "la_step_select", "la_speedup_step_sync", "la_speedup_step_async", "la_speedup_token", "la_plan_budget",
     "la_spec_accept_workspace",
     "la_spec_accept",
     "la_status_string", "la_profile_enable", "la_profile_select", "la_profile_collect", "la_profile_num_kernels", "la_profile_get",
@@ -48,6 +49,11 @@ class la_accept_desc(ctypes.Structure):
 class la_layer_strides(ctypes.Structure):
     _fields_ = [("num_layers", ctypes.c_int32), ("cache_stride", ctypes.c_int64), ("branch_stride", ctypes.c_int64),
                 ("chain_stride", ctypes.c_int64), ("scale_stride", ctypes.c_int64)]
+
+
+class la_plan_desc(ctypes.Structure):
+    _fields_ = [("alpha1", ctypes.c_double), ("c1", ctypes.c_double), ("alpha2", ctypes.c_double),
+                ("c2", ctypes.c_double), ("budget", ctypes.c_int32), ("asynchronous", ctypes.c_int32)]
 
 
 class LaError(RuntimeError):
@@ -85,6 +91,14 @@ def load() -> ctypes.CDLL:
         lib.la_kv_commit.argtypes = [ctypes.POINTER(la_attn_desc), vp, vp, i32p, i32p, ctypes.POINTER(ctypes.c_int32),
                                      vp, vp, vp, vp, ctypes.c_int32, i32p, i32p, i32p, vp, vp, i32p,
                                      ctypes.POINTER(la_layer_strides), vp]
+        lib.la_step_select.restype = ctypes.c_int
+        lib.la_step_select.argtypes = [ctypes.c_int32, ctypes.c_int32] + [vp] * 7
+        for fn in (lib.la_speedup_step_sync, lib.la_speedup_step_async, lib.la_speedup_token):
+            fn.restype = ctypes.c_int
+            fn.argtypes = [ctypes.c_double, ctypes.c_double, ctypes.c_int32, ctypes.POINTER(ctypes.c_double)]
+        lib.la_plan_budget.restype = ctypes.c_int
+        lib.la_plan_budget.argtypes = [ctypes.POINTER(la_plan_desc), ctypes.POINTER(ctypes.c_int32),
+                                       ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double)]
         lib.la_spec_accept_workspace.restype = ctypes.c_int
         lib.la_spec_accept_workspace.argtypes = [ctypes.POINTER(la_accept_desc), ctypes.POINTER(ctypes.c_size_t)]
         lib.la_spec_accept.restype = ctypes.c_int
@@ -186,6 +200,52 @@ def la_kv_commit(desc: la_attn_desc, k_cache, v_cache, block_tables, prefix_lens
                              ctypes.byref(layers) if layers is not None else None, _stream())
     if st:
         raise LaError(st, "la_kv_commit")
+
+
+def la_step_select(verdicts, chain_vis, own_len):
+    """Host arrays in, host arrays out: ``verdicts`` [B, nb-1] (truthy = accepted), ``chain_vis`` / ``own_len``
+    [B, nb] ints.  Returns numpy int32 arrays ``(j_star, src_branch, n_chain, n_own)``, each [B]."""
+    import numpy as np
+    vis = np.ascontiguousarray(chain_vis, dtype=np.int32)
+    own = np.ascontiguousarray(own_len, dtype=np.int32)
+    nreq, nb = vis.shape
+    v = np.ascontiguousarray(np.asarray(verdicts, dtype=bool).reshape(nreq, nb - 1), dtype=np.uint8)
+    outs = [np.empty(nreq, dtype=np.int32) for _ in range(4)]
+    st = load().la_step_select(nreq, nb, v.ctypes.data if v.size else None, vis.ctypes.data, own.ctypes.data,
+                               *(o.ctypes.data for o in outs))
+    if st:
+        raise LaError(st, "la_step_select")
+    return tuple(outs)
+
+
+def _speedup(fn_name: str, alpha: float, c: float, k: int) -> float:
+    out = ctypes.c_double()
+    st = getattr(load(), fn_name)(alpha, c, k, ctypes.byref(out))
+    if st:
+        raise LaError(st, fn_name)
+    return out.value
+
+
+def la_speedup_step_sync(alpha1: float, c1: float, k1: int) -> float:
+    return _speedup("la_speedup_step_sync", alpha1, c1, k1)
+
+
+def la_speedup_step_async(alpha1: float, c1: float, k1: int) -> float:
+    return _speedup("la_speedup_step_async", alpha1, c1, k1)
+
+
+def la_speedup_token(alpha2: float, c2: float, k2: int) -> float:
+    return _speedup("la_speedup_token", alpha2, c2, k2)
+
+
+def la_plan_budget(alpha1: float, c1: float, alpha2: float, c2: float, budget: int, asynchronous: bool):
+    """Returns ``(k1, k2, speedup)``."""
+    d = la_plan_desc(alpha1, c1, alpha2, c2, budget, 1 if asynchronous else 0)
+    k1, k2, h = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_double()
+    st = load().la_plan_budget(ctypes.byref(d), ctypes.byref(k1), ctypes.byref(k2), ctypes.byref(h))
+    if st:
+        raise LaError(st, "la_plan_budget")
+    return k1.value, k2.value, h.value
 
 
 def make_accept_desc(*, num_branches, num_draft, vocab, logits_dtype, temperature=1.0, top_k=0,
