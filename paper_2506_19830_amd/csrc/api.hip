@@ -98,8 +98,13 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, Attn
     const int64_t base_wgs = (int64_t)d->num_kv_heads * ((R + tile_m - 1) / tile_m);
     const double t_tile = per_cu > 1 ? 2.25 : 1.87;  // per workgroup and 64-key tile, the CU shared by per_cu
     const double t_fixed = per_cu > 1 ? 8.0 : 9.0;
+    // the workgroup of a request's last chunk also runs the branch-private tiles (masked, not pipelined: about
+    // three times the cost of a prefix tile each), so the last chunk is made that much shorter than the others
+    const int priv_tokens = tile_m / G + d->branch_len < d->gamma * d->branch_len ? tile_m / G + d->branch_len
+                                                                                 : d->gamma * d->branch_len;
+    const int64_t extra_tiles = 3 * (int64_t)((priv_tokens + 63) / 64);
     for (int n = 1; n <= 512; ++n) {
-      int64_t len = max_p > 0 ? (max_p + n - 1) / n : 64;
+      int64_t len = max_p > 0 ? (max_p + (n > 1 ? extra_tiles * 64 : 0) + n - 1) / n : 64;
       len = ((len + 63) / 64) * 64;
       if (d->kv_split_tokens) len = d->kv_split_tokens;
       int64_t units = 0;
@@ -107,7 +112,10 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, Attn
       const int64_t slots = (int64_t)kNumCUs * per_cu;
       const int64_t rounds = (base_wgs * units + slots - 1) / slots;
       const double merge_us = 3.0 + (double)units * n_rows * (d->head_dim + 2) * 4.0 / 3.0e6;  // read at ~3 TB/s
-      const double cost = (double)rounds * ((double)len / 64 * t_tile + t_fixed) + merge_us;
+      const int64_t n_max = attn_num_chunks((int)max_p, (int)len);
+      const int64_t last_tiles = (max_p - (n_max - 1) * len + 63) / 64 + extra_tiles;  // of the longest request
+      const int64_t wg_tiles = n_max > 1 && len / 64 > last_tiles ? len / 64 : last_tiles;
+      const double cost = (double)rounds * ((double)wg_tiles * t_tile + t_fixed) + merge_us;
       if (best_shape < 0 || cost < best_cost) best_cost = cost, best_len = (int)len, best_shape = shape;
       if (len <= 64 || d->kv_split_tokens) break;
     }

@@ -566,6 +566,9 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
   }
   const int P = p.prefix_lens[b];
   const int n_chunks = attn_num_chunks(P, p.chunk_len);
+  // workgroups are dispatched in blockIdx order: the last chunk, which also carries the chain and branch-private
+  // tiles and so runs longest, goes first instead of into the tail of the launch
+  c = n_chunks - 1 - c;
   const int k_begin = c * p.chunk_len;
   const int k_end = min(P, k_begin + p.chunk_len);
   const int n_full = k_end > k_begin ? (k_end - k_begin) / kTileN : 0;          // unmasked prefix tiles
