@@ -47,6 +47,7 @@ def _load():
         _lib = ctypes.CDLL(override if override else str(build()))
         _lib.lao_verify_attention.restype = ctypes.c_int
         _lib.lao_verify_attention_nested.restype = ctypes.c_int
+        _lib.lao_verify_attention_tree.restype = ctypes.c_int
         _lib.lao_attention_row_weights.restype = ctypes.c_int
         _lib.lao_spec_accept.restype = ctypes.c_int
         _lib.lao_spec_accept_warped.restype = ctypes.c_int
@@ -132,10 +133,12 @@ def _attn_args(q, k_cache, v_cache, block_tables, prefix_lens, k_branch, v_branc
 
 def verify_attention(q, k_cache, v_cache, block_tables, prefix_lens, k_branch, v_branch, k_scale=None, v_scale=None,
                      *, q_dtype, kv_dtype, branch_kv_dtype, block_size, scale, row_ids=None, k_chain=None,
-                     v_chain=None, chain_vis=None):
+                     v_chain=None, chain_vis=None, k_pool=None, v_pool=None, pool_seg=None, seg_mask=None):
     """Attention of every branch token over ``prefix ++ own branch`` (causal inside the branch).  Nested form:
     with ``k_chain``/``v_chain`` ``[B, C, Hkv, D]`` (branch storage dtype) and ``chain_vis`` ``[B, gamma]``, branch g
-    sees ``prefix ++ chain[:chain_vis[b, g]] ++ own branch``.
+    sees ``prefix ++ chain[:chain_vis[b, g]] ++ own branch``.  Tree form: with ``k_pool``/``v_pool``
+    ``[B, C, Hkv, D]``, ``pool_seg`` ``[B, C]`` (segment 0..63 of every pool token) and ``seg_mask`` ``[B, gamma]``
+    (uint64), branch g sees the pool tokens whose segment bit is set in its mask, in pool order.
 
     Returns ``(out, lse)`` in fp64.  Without ``row_ids`` the shapes are
     ``[B, gamma, L, Hq, D]`` and ``[B, gamma, L, Hq]``; with ``row_ids`` (flat
@@ -155,6 +158,23 @@ def verify_attention(q, k_cache, v_cache, block_tables, prefix_lens, k_branch, v
         n = ids.size
         out = np.empty((n, D), dtype=np.float64)
         lse = np.empty((n,), dtype=np.float64)
+    if k_pool is not None:
+        if k_chain is not None:
+            raise ValueError("give a chain or a pool, not both")
+        kp = _storage(k_pool, branch_kv_dtype, "k_pool")
+        vp = _storage(v_pool, branch_kv_dtype, "v_pool")
+        C = kp.shape[1]
+        seg = np.ascontiguousarray(pool_seg, dtype=np.int32)
+        mask = np.ascontiguousarray(seg_mask, dtype=np.uint64)
+        if seg.shape != (B, C) or mask.shape != (B, gamma) or kp.shape != vp.shape or kp.shape[0] != B or \
+                kp.shape[3] != D:
+            raise ValueError("k_pool/v_pool must be [B, C, Hkv, D], pool_seg [B, C], seg_mask [B, gamma]")
+        rc = _load().lao_verify_attention_tree(*head, ctypes.c_int(C), _ptr(kp), _ptr(vp), _ptr(seg), _ptr(mask),
+                                               _ptr(ids), ctypes.c_int64(n), _ptr(out), _ptr(lse))
+        del keep
+        if rc:
+            raise ValueError("lao_verify_attention_tree rejected its arguments")
+        return out, lse
     if k_chain is None:
         C, kc, vc, vis = 0, None, None, None
     else:

@@ -17,6 +17,12 @@
  *       Nested form (Algorithm 1: x'_j = x (+) s^_0 .. s^_{j-1}): the drafted
  *       steps form one chain of C tokens; branch g additionally sees the
  *       first chain_vis[g] chain tokens, between the prefix and its own tokens.
+ *       Tree form (Section 3.1, "Multi-Branch Drafting": W alternative steps
+ *       per position, a tree of drafted steps): the drafted steps of a request
+ *       form a pool of C tokens, token c belonging to step (segment)
+ *       pool_seg[c] in 0..63; branch g sees exactly the pool tokens whose
+ *       segment bit is set in seg_mask[g] (the steps on its path from the
+ *       root), in pool order, between the prefix and its own tokens.
  *   lao_attention_row_weights -- the softmax weights of one row (test hook
  *       for the "rows sum to one" pin).
  *   lao_spec_accept -- Section 2 ("Speculative Decoding"): the drafted tokens
@@ -137,10 +143,26 @@ typedef struct {
   int C;
   const void *k_chain, *v_chain;
   const int32_t *chain_vis;
+  /* tree form (pool_seg != NULL): the C tokens are a pool, token c of request b belongs to segment
+   * pool_seg[b*C + c] in 0..63, and branch g sees the tokens whose segment bit is set in seg_mask[b*gamma + g] */
+  const int32_t *pool_seg;
+  const uint64_t *seg_mask;
 } attn_problem;
 
+/* does branch g of request b see chain / pool token c? */
+static int sees_token(const attn_problem *a, int b, int g, int c) {
+  if (a->pool_seg) {
+    const int seg = a->pool_seg[(int64_t)b * a->C + c];
+    return (int)((a->seg_mask[(int64_t)b * a->gamma + g] >> seg) & 1u);
+  }
+  return c < a->chain_vis[(int64_t)b * a->gamma + g];
+}
+
+/* number of chain / pool tokens branch g of request b sees */
 static int visible_chain(const attn_problem *a, int b, int g) {
-  return a->C > 0 ? a->chain_vis[(int64_t)b * a->gamma + g] : 0;
+  int n = 0;
+  for (int c = 0; c < a->C; ++c) n += sees_token(a, b, g, c);
+  return n;
 }
 
 /* Writes the key and value sequence seen by branch g of request b on kv head
@@ -163,13 +185,15 @@ static void concat_branch_kv(const attn_problem *a, int b, int g, int hk, double
   }
   const double bks = (a->k_scale && a->br_dtype == LAO_FP8_E4M3) ? (double)a->k_scale[hk] : 1.0;
   const double bvs = (a->v_scale && a->br_dtype == LAO_FP8_E4M3) ? (double)a->v_scale[hk] : 1.0;
-  const int vis = visible_chain(a, b, g);
-  for (int c = 0; c < vis; ++c) {
+  int vis = 0; /* visible tokens written so far; they keep their order */
+  for (int c = 0; c < a->C; ++c) {
+    if (!sees_token(a, b, g, c)) continue;
     int64_t base = (((int64_t)b * a->C + c) * a->Hkv + hk) * D;
     for (int d = 0; d < D; ++d) {
-      kcat[(int64_t)(P + c) * D + d] = load_elem(a->k_chain, a->br_dtype, base + d) * bks;
-      vcat[(int64_t)(P + c) * D + d] = load_elem(a->v_chain, a->br_dtype, base + d) * bvs;
+      kcat[(int64_t)(P + vis) * D + d] = load_elem(a->k_chain, a->br_dtype, base + d) * bks;
+      vcat[(int64_t)(P + vis) * D + d] = load_elem(a->v_chain, a->br_dtype, base + d) * bvs;
     }
+    ++vis;
   }
   for (int i = 0; i < a->L; ++i) {
     int64_t base = ((((int64_t)b * a->gamma + g) * a->L + i) * a->Hkv + hk) * D;
@@ -217,25 +241,25 @@ static int check_problem(const attn_problem *a) {
   }
   if (a->C < 0) return 1;
   if (a->C > 0) {
-    if (!a->k_chain || !a->v_chain || !a->chain_vis) return 1;
-    for (int64_t t = 0; t < (int64_t)a->B * a->gamma; ++t)
-      if (a->chain_vis[t] < 0 || a->chain_vis[t] > a->C) return 1;
+    if (!a->k_chain || !a->v_chain) return 1;
+    if (a->pool_seg) {
+      if (!a->seg_mask) return 1;
+      for (int64_t t = 0; t < (int64_t)a->B * a->C; ++t)
+        if (a->pool_seg[t] < 0 || a->pool_seg[t] > 63) return 1;
+    } else {
+      if (!a->chain_vis) return 1;
+      for (int64_t t = 0; t < (int64_t)a->B * a->gamma; ++t)
+        if (a->chain_vis[t] < 0 || a->chain_vis[t] > a->C) return 1;
+    }
   }
   return 0;
 }
 
 /* out: [n_rows, D] fp64, lse: [n_rows] fp64 or NULL.  row_ids == NULL means
  * every row in order (n_rows must then equal B*gamma*L*Hq). */
-int lao_verify_attention_nested(int B, int gamma, int L, int Hq, int Hkv, int D, int block_size, int max_blocks,
-                                int q_dtype, int kv_dtype, int br_dtype, double scale, const void *q,
-                                const void *k_cache, const void *v_cache, const int32_t *block_tables,
-                                const int32_t *prefix_lens, const void *k_branch, const void *v_branch,
-                                const float *k_scale, const float *v_scale, int chain_len, const void *k_chain,
-                                const void *v_chain, const int32_t *chain_vis, const int64_t *row_ids, int64_t n_rows,
-                                double *out, double *lse) {
-  attn_problem a = {B,  gamma,   L,       Hq,       Hkv,      D,           block_size, max_blocks, q_dtype, kv_dtype, br_dtype,
-                    scale, q, k_cache, v_cache, k_branch, v_branch, block_tables, prefix_lens, k_scale, v_scale,
-                    chain_len, k_chain, v_chain, chain_vis};
+static int verify_attention(attn_problem a, const int64_t *row_ids, int64_t n_rows, double *out, double *lse) {
+  const int B = a.B, gamma = a.gamma, L = a.L, Hq = a.Hq, Hkv = a.Hkv, D = a.D;
+  const int32_t *prefix_lens = a.prefix_lens;
   if (check_problem(&a) || !out) return 1;
   const int64_t total = (int64_t)B * gamma * L * Hq;
   if (!row_ids && n_rows != total) return 1;
@@ -300,6 +324,33 @@ int lao_verify_attention_nested(int B, int gamma, int L, int Hq, int Hkv, int D,
   return failed;
 }
 
+int lao_verify_attention_nested(int B, int gamma, int L, int Hq, int Hkv, int D, int block_size, int max_blocks,
+                                int q_dtype, int kv_dtype, int br_dtype, double scale, const void *q,
+                                const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                                const int32_t *prefix_lens, const void *k_branch, const void *v_branch,
+                                const float *k_scale, const float *v_scale, int chain_len, const void *k_chain,
+                                const void *v_chain, const int32_t *chain_vis, const int64_t *row_ids, int64_t n_rows,
+                                double *out, double *lse) {
+  attn_problem a = {B,  gamma,   L,       Hq,       Hkv,      D,           block_size, max_blocks, q_dtype, kv_dtype, br_dtype,
+                    scale, q, k_cache, v_cache, k_branch, v_branch, block_tables, prefix_lens, k_scale, v_scale,
+                    chain_len, k_chain, v_chain, chain_vis, NULL, NULL};
+  return verify_attention(a, row_ids, n_rows, out, lse);
+}
+
+int lao_verify_attention_tree(int B, int gamma, int L, int Hq, int Hkv, int D, int block_size, int max_blocks,
+                              int q_dtype, int kv_dtype, int br_dtype, double scale, const void *q,
+                              const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                              const int32_t *prefix_lens, const void *k_branch, const void *v_branch,
+                              const float *k_scale, const float *v_scale, int pool_len, const void *k_pool,
+                              const void *v_pool, const int32_t *pool_seg, const uint64_t *seg_mask,
+                              const int64_t *row_ids, int64_t n_rows, double *out, double *lse) {
+  attn_problem a = {B,  gamma,   L,       Hq,       Hkv,      D,           block_size, max_blocks, q_dtype, kv_dtype, br_dtype,
+                    scale, q, k_cache, v_cache, k_branch, v_branch, block_tables, prefix_lens, k_scale, v_scale,
+                    pool_len, k_pool, v_pool, NULL, pool_seg, seg_mask};
+  if (pool_len > 0 && !pool_seg) return 1;
+  return verify_attention(a, row_ids, n_rows, out, lse);
+}
+
 int lao_verify_attention(int B, int gamma, int L, int Hq, int Hkv, int D, int block_size, int max_blocks, int q_dtype,
                          int kv_dtype, int br_dtype, double scale, const void *q, const void *k_cache,
                          const void *v_cache, const int32_t *block_tables, const int32_t *prefix_lens,
@@ -319,7 +370,7 @@ int lao_attention_row_weights(int B, int gamma, int L, int Hq, int Hkv, int D, i
                               const float *k_scale, const float *v_scale, int64_t row_id, double *w) {
   attn_problem a = {B,  gamma,   L,       Hq,       Hkv,      D,           block_size, max_blocks, q_dtype, kv_dtype, br_dtype,
                     scale, q, k_cache, v_cache, k_branch, v_branch, block_tables, prefix_lens, k_scale, v_scale,
-                    0, NULL, NULL, NULL};
+                    0, NULL, NULL, NULL, NULL, NULL};
   if (check_problem(&a) || !w) return 1;
   if (row_id < 0 || row_id >= (int64_t)B * gamma * L * Hq) return 1;
   const int h = (int)(row_id % Hq);

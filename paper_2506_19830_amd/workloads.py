@@ -298,6 +298,48 @@ def make_chain_inputs(case: AttnCase, chain_len: int, inp: Dict[str, Optional[np
             "chain_vis": np.asarray(chain_vis, dtype=np.int32)}
 
 
+def make_tree_inputs(case: AttnCase, width: int, depth: int, step_len: int,
+                     inp: Dict[str, Optional[np.ndarray]]) -> Dict[str, np.ndarray]:
+    """A draft tree (Section 3.1, multi-branch drafting): ``width`` alternative steps per position, ``depth``
+    positions, every step ``step_len`` tokens of K/V ~ N(0,1).  The nodes are stored level by level (node ids 0..:
+    the ``width`` children of node n follow each other), one segment per node, ``[B, nodes*step_len, Hkv, D]`` in
+    the branch storage type.  Branch g is given the root path of node ``(3 g + b) mod (nodes + 1)`` (the extra
+    value = no node: it sees only the prefix), i.e. ``seg_mask`` has the bits of that node and all its ancestors.
+    Needs at most 64 nodes."""
+    c = case
+    nodes, level, parent = 0, [None], {}
+    for _ in range(depth):
+        nxt = []
+        for par in level:
+            for _ in range(width):
+                parent[nodes] = par
+                nxt.append(nodes)
+                nodes += 1
+        level = nxt
+    if nodes > 64:
+        raise ValueError("at most 64 nodes")
+    C = nodes * step_len
+    s0 = 16 * c.layer
+    kp = _rng(c.seed, s0 + 11).standard_normal((c.B, C, c.Hkv, c.D), dtype=np.float32)
+    vp = _rng(c.seed, s0 + 12).standard_normal((c.B, C, c.Hkv, c.D), dtype=np.float32)
+    if c.branch_kv_dtype == "fp8_e4m3":
+        kp = kp / inp["k_scale"][None, None, :, None]
+        vp = vp / inp["v_scale"][None, None, :, None]
+    seg = np.tile(np.repeat(np.arange(nodes, dtype=np.int32), step_len), (c.B, 1))
+    mask = np.zeros((c.B, c.gamma), dtype=np.uint64)
+    for b in range(c.B):
+        for g in range(c.gamma):
+            node = (3 * g + b) % (nodes + 1)
+            node = None if node == nodes else node
+            m = 0
+            while node is not None:
+                m |= 1 << node
+                node = parent[node]
+            mask[b, g] = m
+    return {"k_pool": encode(kp, c.branch_kv_dtype), "v_pool": encode(vp, c.branch_kv_dtype), "pool_seg": seg,
+            "seg_mask": mask}
+
+
 def make_commit_inputs(case: AttnCase, chain_len: int, decisions=None) -> Dict[str, np.ndarray]:
     """What a verification pass decided per request, for the KV commit: which branch survives (``src_branch``), how
     many tokens of the drafted chain (``n_chain``, 0..chain_len) and then of that branch (``n_own``, 0..L) are

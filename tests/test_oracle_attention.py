@@ -359,3 +359,78 @@ def test_nested_chain_visibility(oracle):
     np.testing.assert_array_equal(out[1], base[1])
     with pytest.raises(ValueError):
         run(oracle, case, inp, **{**chain, "chain_vis": np.full((2, 3), 7, dtype=np.int32)})   # more than C
+
+
+# ------------------------------------------------------------------------------------------ tree form
+
+def as_chain_seen_by(tree, b, g):
+    """The pool tokens branch g of request b sees, in pool order, as a chain that is seen in full."""
+    seg, mask = tree["pool_seg"][b], int(tree["seg_mask"][b, g])
+    keep = np.array([(mask >> int(s)) & 1 for s in seg], dtype=bool)
+    return {"k_chain": tree["k_pool"][b:b + 1, keep], "v_chain": tree["v_pool"][b:b + 1, keep],
+            "chain_vis": np.array([[int(keep.sum())]], dtype=np.int32)}
+
+
+@pytest.mark.parametrize("dtypes", [("f32", "f32", "f32"), ("bf16", "fp8_e4m3", "fp8_e4m3"), ("bf16", "bf16", "bf16")])
+def test_tree_equals_flat_with_the_path_appended_to_the_prefix(oracle, dtypes):
+    """Every branch of the tree problem equals a flat one-branch problem whose prefix is extended by the pool tokens
+    on the branch's root path, in pool order (bit for bit; only the pinned flat path is used for the reference)."""
+    qd, kvd, brd = dtypes
+    case = W.AttnCase("tree", (37, 0), 5, 4, 4, 2, 32, qd, kvd, brd, "f32", paged=True, seed=41)
+    inp = W.make_attention_inputs(case)
+    tree = W.make_tree_inputs(case, 2, 3, 3, inp)                  # 2 + 4 + 8 = 14 nodes of 3 tokens
+    tree["seg_mask"][1, 4] = 0                                     # one branch that sees no drafted step at all
+    # request 1 numbers its segments the other way round (segment ids are per request)
+    tree["pool_seg"][1] = 13 - tree["pool_seg"][1]
+    tree["seg_mask"][1] = [sum(1 << (13 - s) for s in range(14) if (int(m) >> s) & 1) for m in tree["seg_mask"][1]]
+    out, lse = run(oracle, case, inp, **tree)
+    seen = set()
+    for b in range(case.B):
+        for g in range(case.gamma):
+            chain = as_chain_seen_by(tree, b, g)
+            seen.add(int(chain["chain_vis"][0, 0]))
+            # flat_problem_with_extended_prefix reads request b's prefix and branch g of the chain dict's request 0
+            sub_chain = {"k_chain": np.repeat(chain["k_chain"], case.B, axis=0),
+                         "v_chain": np.repeat(chain["v_chain"], case.B, axis=0),
+                         "chain_vis": np.full((case.B, case.gamma), chain["chain_vis"][0, 0], dtype=np.int32)}
+            sub, sub_inp = flat_problem_with_extended_prefix(case, inp, sub_chain, b, g)
+            ref, ref_lse = run(oracle, sub, sub_inp)
+            np.testing.assert_array_equal(out[b, g], ref[0, 0])
+            np.testing.assert_array_equal(lse[b, g], ref_lse[0, 0])
+    assert {0, 3, 6, 9} <= seen                                     # paths of depth 0..3 all occur
+
+
+def test_tree_whose_masks_are_leading_parts_is_the_nested_form(oracle):
+    case = W.AttnCase("tree_chain", (19, 6), 4, 3, 4, 2, 32, "f32", "f32", "f32", "f32", seed=42)
+    inp = W.make_attention_inputs(case)
+    tree = W.make_tree_inputs(case, 1, 5, 2, inp)                  # width 1: a chain of 5 steps of 2 tokens
+    tree["seg_mask"] = np.array([[0, 0b1, 0b111, 0b11111], [0b11, 0, 0b1111, 0b1]], dtype=np.uint64)
+    vis = np.array([[0, 2, 6, 10], [4, 0, 8, 2]], dtype=np.int32)
+    a, la = run(oracle, case, inp, **tree)
+    b, lb = run(oracle, case, inp, k_chain=tree["k_pool"], v_chain=tree["v_pool"], chain_vis=vis)
+    np.testing.assert_array_equal(a, b)
+    np.testing.assert_array_equal(la, lb)
+
+
+def test_tree_visibility_follows_the_mask_and_nothing_else(oracle):
+    case = W.AttnCase("tree_vis", (8, 8), 3, 2, 2, 1, 16, "f32", "f32", "f32", "f32", seed=43)
+    inp = W.make_attention_inputs(case)
+    tree = W.make_tree_inputs(case, 2, 2, 2, inp)                  # nodes 0,1 | 2,3 (of 0), 4,5 (of 1)
+    tree["seg_mask"] = np.array([[0b000101, 0b100010, 0], [0b001001, 0b000010, 0b110010]], dtype=np.uint64)
+    base, _ = run(oracle, case, inp, **tree)
+    pert = {k: v.copy() for k, v in tree.items()}
+    pert["k_pool"][0, 4:6] += 1.0                                   # request 0, node 2: on the path of branch 0 only
+    pert["v_pool"][0, 4:6] -= 1.0
+    out, _ = run(oracle, case, inp, **pert)
+    assert not np.array_equal(out[0, 0], base[0, 0])
+    np.testing.assert_array_equal(out[0, 1:], base[0, 1:])
+    np.testing.assert_array_equal(out[1], base[1])
+    # relabelling the segments together with the masks changes nothing
+    relabel = {k: v.copy() for k, v in tree.items()}
+    relabel["pool_seg"] = 63 - tree["pool_seg"]
+    relabel["seg_mask"] = np.array([[sum(1 << (63 - s) for s in range(6) if (int(m) >> s) & 1) for m in row]
+                                    for row in tree["seg_mask"]], dtype=np.uint64)
+    out, _ = run(oracle, case, inp, **relabel)
+    np.testing.assert_array_equal(out, base)
+    with pytest.raises(ValueError):
+        run(oracle, case, inp, **{**tree, "pool_seg": tree["pool_seg"] + 60})    # segment ids past 63

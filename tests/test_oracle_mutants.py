@@ -17,8 +17,17 @@ MUTANTS = {
     "chain_not_counted": ("const int64_t n = (int64_t)P + vis + i + 1;", "const int64_t n = (int64_t)P + i + 1;"),
     "chain_of_wrong_request": ("int64_t base = (((int64_t)b * a->C + c) * a->Hkv + hk) * D;",
                                "int64_t base = (((int64_t)0 * a->C + c) * a->Hkv + hk) * D;"),
-    "chain_vis_of_wrong_branch": ("return a->C > 0 ? a->chain_vis[(int64_t)b * a->gamma + g] : 0;",
-                                  "return a->C > 0 ? a->chain_vis[(int64_t)b * a->gamma + 0] : 0;"),
+    "chain_vis_of_wrong_branch": ("  return c < a->chain_vis[(int64_t)b * a->gamma + g];",
+                                  "  return c < a->chain_vis[(int64_t)b * a->gamma + 0];"),
+    "tree_mask_of_wrong_branch": ("return (int)((a->seg_mask[(int64_t)b * a->gamma + g] >> seg) & 1u);",
+                                  "return (int)((a->seg_mask[(int64_t)b * a->gamma + 0] >> seg) & 1u);"),
+    "tree_segment_of_wrong_request": ("    const int seg = a->pool_seg[(int64_t)b * a->C + c];",
+                                      "    const int seg = a->pool_seg[(int64_t)0 * a->C + c];"),
+    "tree_mask_bit_off_by_one": ("return (int)((a->seg_mask[(int64_t)b * a->gamma + g] >> seg) & 1u);",
+                                 "return (int)((a->seg_mask[(int64_t)b * a->gamma + g] >> (seg + 1)) & 1u);"),
+    "tree_mask_truncated_to_32_bits": ("return (int)((a->seg_mask[(int64_t)b * a->gamma + g] >> seg) & 1u);",
+                                       "return (int)(((uint32_t)a->seg_mask[(int64_t)b * a->gamma + g] >> (seg & 31)) & 1u);"),
+    "visible_tokens_all_in_one_slot": ("    ++vis;\n", ""),
     "own_tokens_overwrite_chain": ("kcat[(int64_t)(P + vis + i) * D + d] = load_elem(a->k_branch",
                                    "kcat[(int64_t)(P + i) * D + d] = load_elem(a->k_branch"),
     "scale_dropped": ("    s *= a->scale;\n", ""),
