@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--chain-len", type=int, default=0,
                     help="nested branches: a drafted chain of this many tokens per request, of which branch g sees "
                          "the first g/gamma (la_verify_attention_nested); 0 = the flat form, the headline workload")
+    ap.add_argument("--tree", type=str, default=None, metavar="W,DEPTH,STEP",
+                    help="draft tree: W alternative steps per position, DEPTH positions, STEP tokens per step "
+                         "(la_verify_attention_tree); branch g is given the root path of a node")
     ap.add_argument("--kv-commit", action="store_true",
                     help="measure la_kv_commit instead (the step after the pass: all layers' surviving K/V appended "
                          "to the paged cache in one launch) and print its JSON line")
@@ -61,6 +64,12 @@ def read_traffic(name: str):
         if line.startswith("traffic_bytes_per_launch:"):
             return float(line.split(":", 1)[1])
     return None
+
+
+def replace_case_for_structure(case):
+    """make_tree_inputs draws K/V on the host as well; for the structure alone a one-head, tiny-D copy is enough."""
+    from dataclasses import replace
+    return replace(case, Hkv=1, Hq=1, D=8, branch_kv_dtype="f32")
 
 
 def bench_commit(args):
@@ -303,6 +312,28 @@ def main():
         vis_host = [[(g * C) // attn_case.gamma for g in range(attn_case.gamma)] for _ in range(attn_case.B)]
         vis_dev = torch.tensor(vis_host, dtype=torch.int32, device=dev)
 
+    tree = None
+    if args.tree:
+        if C > 0:
+            print("bench.py: --tree and --chain-len exclude each other", file=sys.stderr)
+            return 2
+        width, depth, step_len = (int(x) for x in args.tree.split(","))
+        tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch.float8_e4m3fn}[attn_case.branch_kv_dtype]
+        # structure (segments, masks) from the seeded generator; the pool's K/V are drawn on the device per layer
+        shape_only = W.make_tree_inputs(replace_case_for_structure(attn_case), width, depth, step_len,
+                                        {"k_scale": np.ones(attn_case.Hkv, np.float32),
+                                         "v_scale": np.ones(attn_case.Hkv, np.float32)})
+        seg_np, mask_np = shape_only["pool_seg"], shape_only["seg_mask"]
+        pool_len = seg_np.shape[1]
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(4343)
+        shape = (attn_case.B, pool_len, attn_case.Hkv, attn_case.D)
+        pools = [tuple(torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(tdt) for _ in "kv")
+                 for _ in range(n_layers)]
+        tree = {"seg_dev": torch.from_numpy(seg_np).to(dev), "seg_host": seg_np.tolist(),
+                "mask_dev": torch.from_numpy(mask_np.view(np.int64)).to(dev), "seg_np": seg_np, "mask_np": mask_np,
+                "pool_len": pool_len}
+
     acc_np = W.make_accept_inputs(acc_case)
     acc = {
         "target_logits": B.to_device(acc_np["target_logits"], acc_case.logits_dtype, dev),
@@ -320,6 +351,12 @@ def main():
     def step():
         for l in range(n_layers):
             t = layers[l]
+            if tree is not None:
+                B.la_verify_attention_tree(desc, t["q"], t["k_cache"], t["v_cache"], t["block_tables"],
+                                           t["prefix_lens"], lens, t["k_branch"], t["v_branch"], pools[l][0],
+                                           pools[l][1], tree["seg_dev"], tree["seg_host"], tree["mask_dev"],
+                                           t["k_scale"], t["v_scale"], outs[l], None, ws)
+                continue
             if C > 0:
                 B.la_verify_attention_nested(desc, t["q"], t["k_cache"], t["v_cache"], t["block_tables"],
                                              t["prefix_lens"], lens, t["k_branch"], t["v_branch"], chains[l][0],
@@ -374,6 +411,10 @@ def main():
     flops = attn_case.flops()
     if C > 0:   # 4*D flops per (query row, visible chain key) pair on top of the flat form's
         flops += sum(4.0 * attn_case.D * attn_case.L * attn_case.Hq * v for row in vis_host for v in row)
+    if tree is not None:   # likewise for the pool tokens on each branch's root path
+        seen = [[sum((int(m) >> int(sg)) & 1 for sg in tree["seg_np"][b]) for m in tree["mask_np"][b]]
+                for b in range(attn_case.B)]
+        flops += sum(4.0 * attn_case.D * attn_case.L * attn_case.Hq * v for row in seen for v in row)
     achieved_tflops = flops / (kern_avg_ms * 1e-3) / 1e12
     alg_bytes = attn_case.algorithmic_bytes()
     attn_ms = sum(prof_all[k][1] for k in ("attn_mfma", "attn_merge"))
@@ -403,6 +444,7 @@ def main():
             "branch_tokens_per_step": branch_tokens,
             "kv_split_tokens": args.kv_split_tokens,
             "chain_len": C,
+            "tree": args.tree, "pool_len": None if tree is None else tree["pool_len"],
         },
         "roofline": {
             "kernel": "attn_mfma_kernel",
@@ -436,6 +478,10 @@ def main():
         D = attn_case.D
         for l in sample_layers:
             host = W.device_inputs_to_numpy(attn_case, layers[l])
+            if tree is not None:
+                host.update(k_pool=W.device_bits(pools[l][0], attn_case.branch_kv_dtype),
+                            v_pool=W.device_bits(pools[l][1], attn_case.branch_kv_dtype),
+                            pool_seg=tree["seg_np"], seg_mask=tree["mask_np"])
             if C > 0:
                 host.update(k_chain=W.device_bits(chains[l][0], attn_case.branch_kv_dtype),
                             v_chain=W.device_bits(chains[l][1], attn_case.branch_kv_dtype),

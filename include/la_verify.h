@@ -133,6 +133,29 @@ LA_API la_status la_verify_attention_nested(
     const float *k_scale, const float *v_scale, void *out, float *lse,
     void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Draft trees (Section 3.1, "Multi-Branch Drafting": W alternative steps per
+ * position, so the drafted steps of a request form a tree).  The drafted
+ * tokens of all tree nodes lie in one pool of pool_len tokens per request;
+ * pool token c belongs to segment (tree node) pool_seg[b][c] in 0..63, and
+ * branch g sees exactly the pool tokens whose segment bit is set in
+ * seg_mask[b][g] -- the steps on its path from the root -- after the prefix
+ * and before its own tokens (no mask inside what it sees: all of it precedes
+ * the branch's own tokens).  At most 64 segments per request.  pool_len == 0
+ * is la_verify_attention.  Same workspace as la_verify_attention. */
+LA_API la_status la_verify_attention_tree(
+    const la_attn_desc *desc, const void *q, const void *k_cache, const void *v_cache,
+    const int32_t *block_tables, const int32_t *prefix_lens, const int32_t *prefix_lens_host,
+    const void *k_branch, const void *v_branch,
+    const void *k_pool,              /* dev [B, pool_len, Hkv, D]  branch_kv_dtype (fp8: the cache's
+                                        scales); NULL when pool_len == 0                            */
+    const void *v_pool,              /* dev, same shape                                           */
+    int32_t pool_len,
+    const int32_t *pool_seg,         /* dev [B, pool_len], each in 0..63                          */
+    const int32_t *pool_seg_host,    /* host [B, pool_len], same values (validated)               */
+    const uint64_t *seg_mask,        /* dev [B, gamma]                                            */
+    const float *k_scale, const float *v_scale, void *out, float *lse,
+    void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* ------------------------------------------------------------------------- *
  *  la_kv_commit
  *

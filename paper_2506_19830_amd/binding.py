@@ -24,7 +24,7 @@ DTYPE_CODES = {"f32": LA_F32, "bf16": LA_BF16, "fp8_e4m3": LA_FP8_E4M3}
 _TORCH_DTYPES = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch.float8_e4m3fn}
 
 EXPORTED_SYMBOLS = (
-    "la_verify_attention_workspace", "la_verify_attention", "la_verify_attention_nested", "la_kv_commit",
+    "la_verify_attention_workspace", "la_verify_attention", "la_verify_attention_nested", "la_verify_attention_tree", "la_kv_commit",
     "la_step_select", "la_speedup_step_sync", "la_speedup_step_async", "la_speedup_token", "la_plan_budget",
     "la_spec_accept_workspace",
     "la_spec_accept",
@@ -87,6 +87,11 @@ def load() -> ctypes.CDLL:
                                                    ctypes.POINTER(ctypes.c_int32), vp, vp, vp, vp, ctypes.c_int32, i32p,
                                                    ctypes.POINTER(ctypes.c_int32), vp, vp, vp, vp, vp, ctypes.c_size_t,
                                                    vp]
+        lib.la_verify_attention_tree.restype = ctypes.c_int
+        lib.la_verify_attention_tree.argtypes = [ctypes.POINTER(la_attn_desc), vp, vp, vp, i32p, i32p,
+                                                 ctypes.POINTER(ctypes.c_int32), vp, vp, vp, vp, ctypes.c_int32, i32p,
+                                                 ctypes.POINTER(ctypes.c_int32), vp, vp, vp, vp, vp, vp,
+                                                 ctypes.c_size_t, vp]
         lib.la_kv_commit.restype = ctypes.c_int
         lib.la_kv_commit.argtypes = [ctypes.POINTER(la_attn_desc), vp, vp, i32p, i32p, ctypes.POINTER(ctypes.c_int32),
                                      vp, vp, vp, vp, ctypes.c_int32, i32p, i32p, i32p, vp, vp, i32p,
@@ -182,6 +187,26 @@ def la_verify_attention_nested(desc: la_attn_desc, q, k_cache, v_cache, block_ta
                                            _ptr(out), _ptr(lse), _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream())
     if st:
         raise LaError(st, "la_verify_attention_nested")
+
+
+def la_verify_attention_tree(desc: la_attn_desc, q, k_cache, v_cache, block_tables, prefix_lens, prefix_lens_host,
+                             k_branch, v_branch, k_pool, v_pool, pool_seg, pool_seg_host, seg_mask, k_scale, v_scale,
+                             out, lse, workspace) -> None:
+    """As la_verify_attention, with the pool of drafted tokens ``k_pool``/``v_pool`` [B, C, Hkv, D], ``pool_seg``
+    [B, C] (device int32; ``pool_seg_host``: nested sequence of ints, same values) and ``seg_mask`` [B, gamma]
+    (device, 64-bit: torch.int64 holding the bit pattern)."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    C = 0 if k_pool is None else int(k_pool.shape[1])
+    flat = [int(x) for row in pool_seg_host for x in row] if C else []
+    seg_host = (ctypes.c_int32 * max(1, len(flat)))(*flat)
+    st = load().la_verify_attention_tree(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                         _ptr(block_tables), _ptr(prefix_lens), _host_lens(prefix_lens_host),
+                                         _ptr(k_branch), _ptr(v_branch), _ptr(k_pool), _ptr(v_pool),
+                                         ctypes.c_int32(C), _ptr(pool_seg), seg_host, _ptr(seg_mask), _ptr(k_scale),
+                                         _ptr(v_scale), _ptr(out), _ptr(lse), _ptr(workspace),
+                                         ctypes.c_size_t(ws_bytes), _stream())
+    if st:
+        raise LaError(st, "la_verify_attention_tree")
 
 
 def la_kv_commit(desc: la_attn_desc, k_cache, v_cache, block_tables, prefix_lens, prefix_lens_host, k_branch, v_branch,

@@ -231,13 +231,16 @@ la_status la_verify_attention_workspace(const la_attn_desc *desc, const int32_t 
   return LA_OK;
 }
 
-la_status la_verify_attention_nested(const la_attn_desc *desc, const void *q, const void *k_cache,
-                                     const void *v_cache, const int32_t *block_tables, const int32_t *prefix_lens,
-                                     const int32_t *prefix_lens_host, const void *k_branch, const void *v_branch,
-                                     const void *k_chain, const void *v_chain, int32_t chain_len,
-                                     const int32_t *chain_vis, const int32_t *chain_vis_host, const float *k_scale,
-                                     const float *v_scale, void *out, float *lse, void *workspace,
-                                     size_t workspace_bytes, void *hip_stream) {
+// Shared by the three attention entry points.  chain_len tokens of extra K/V per request: a chain with a visible
+// leading part per branch (chain_vis), or a pool with segment labels and a segment mask per branch (pool_seg).
+static la_status verify_attention(const la_attn_desc *desc, const void *q, const void *k_cache, const void *v_cache,
+                                  const int32_t *block_tables, const int32_t *prefix_lens,
+                                  const int32_t *prefix_lens_host, const void *k_branch, const void *v_branch,
+                                  const void *k_chain, const void *v_chain, int32_t chain_len,
+                                  const int32_t *chain_vis, const int32_t *chain_vis_host, const int32_t *pool_seg,
+                                  const int32_t *pool_seg_host, const uint64_t *seg_mask, const float *k_scale,
+                                  const float *v_scale, void *out, float *lse, void *workspace,
+                                  size_t workspace_bytes, void *hip_stream) {
   AttnPlan plan;
   la_status st = make_plan(desc, prefix_lens_host, &plan);
   if (st != LA_OK) return st;
@@ -249,11 +252,18 @@ la_status la_verify_attention_nested(const la_attn_desc *desc, const void *q, co
       !aligned16(out) || !aligned16(workspace))
     return LA_ERR_INVALID_ARG;
   if (chain_len < 0) return LA_ERR_INVALID_ARG;
+  const bool tree = pool_seg != nullptr || pool_seg_host != nullptr || seg_mask != nullptr;
   if (chain_len > 0) {
-    if (!k_chain || !v_chain || !chain_vis || !chain_vis_host || !aligned16(k_chain) || !aligned16(v_chain))
-      return LA_ERR_INVALID_ARG;
-    for (int64_t t = 0; t < (int64_t)desc->num_requests * desc->gamma; ++t)
-      if (chain_vis_host[t] < 0 || chain_vis_host[t] > chain_len) return LA_ERR_INVALID_ARG;
+    if (!k_chain || !v_chain || !aligned16(k_chain) || !aligned16(v_chain)) return LA_ERR_INVALID_ARG;
+    if (tree) {
+      if (!pool_seg || !pool_seg_host || !seg_mask || ((uintptr_t)seg_mask & 7)) return LA_ERR_INVALID_ARG;
+      for (int64_t t = 0; t < (int64_t)desc->num_requests * chain_len; ++t)
+        if (pool_seg_host[t] < 0 || pool_seg_host[t] > 63) return LA_ERR_INVALID_ARG;
+    } else {
+      if (!chain_vis || !chain_vis_host) return LA_ERR_INVALID_ARG;
+      for (int64_t t = 0; t < (int64_t)desc->num_requests * desc->gamma; ++t)
+        if (chain_vis_host[t] < 0 || chain_vis_host[t] > chain_len) return LA_ERR_INVALID_ARG;
+    }
   }
   const size_t need = plan.path == PATH_MFMA ? plan.part_o_bytes + plan.part_ml_bytes : 0;
   if (need > 0 && (!workspace || workspace_bytes < need)) return LA_ERR_WORKSPACE_TOO_SMALL;
@@ -262,6 +272,7 @@ la_status la_verify_attention_nested(const la_attn_desc *desc, const void *q, co
   memset(&p, 0, sizeof p);
   p.q = q, p.k_cache = k_cache, p.v_cache = v_cache, p.k_branch = k_branch, p.v_branch = v_branch;
   p.k_chain = k_chain, p.v_chain = v_chain, p.chain_vis = chain_vis, p.C = chain_len;
+  if (chain_len > 0 && tree) p.pool_seg = pool_seg, p.seg_mask = seg_mask;
   p.block_tables = block_tables, p.prefix_lens = prefix_lens;
   p.k_scale = k_scale, p.v_scale = v_scale;
   p.out = out, p.lse = lse;
@@ -291,9 +302,35 @@ la_status la_verify_attention(const la_attn_desc *desc, const void *q, const voi
                               const int32_t *prefix_lens_host, const void *k_branch, const void *v_branch,
                               const float *k_scale, const float *v_scale, void *out, float *lse, void *workspace,
                               size_t workspace_bytes, void *hip_stream) {
-  return la_verify_attention_nested(desc, q, k_cache, v_cache, block_tables, prefix_lens, prefix_lens_host, k_branch,
-                                    v_branch, nullptr, nullptr, 0, nullptr, nullptr, k_scale, v_scale, out, lse,
-                                    workspace, workspace_bytes, hip_stream);
+  return verify_attention(desc, q, k_cache, v_cache, block_tables, prefix_lens, prefix_lens_host, k_branch, v_branch,
+                          nullptr, nullptr, 0, nullptr, nullptr, nullptr, nullptr, nullptr, k_scale, v_scale, out, lse,
+                          workspace, workspace_bytes, hip_stream);
+}
+
+la_status la_verify_attention_nested(const la_attn_desc *desc, const void *q, const void *k_cache,
+                                     const void *v_cache, const int32_t *block_tables, const int32_t *prefix_lens,
+                                     const int32_t *prefix_lens_host, const void *k_branch, const void *v_branch,
+                                     const void *k_chain, const void *v_chain, int32_t chain_len,
+                                     const int32_t *chain_vis, const int32_t *chain_vis_host, const float *k_scale,
+                                     const float *v_scale, void *out, float *lse, void *workspace,
+                                     size_t workspace_bytes, void *hip_stream) {
+  return verify_attention(desc, q, k_cache, v_cache, block_tables, prefix_lens, prefix_lens_host, k_branch, v_branch,
+                          k_chain, v_chain, chain_len, chain_vis, chain_vis_host, nullptr, nullptr, nullptr, k_scale,
+                          v_scale, out, lse, workspace, workspace_bytes, hip_stream);
+}
+
+la_status la_verify_attention_tree(const la_attn_desc *desc, const void *q, const void *k_cache, const void *v_cache,
+                                   const int32_t *block_tables, const int32_t *prefix_lens,
+                                   const int32_t *prefix_lens_host, const void *k_branch, const void *v_branch,
+                                   const void *k_pool, const void *v_pool, int32_t pool_len, const int32_t *pool_seg,
+                                   const int32_t *pool_seg_host, const uint64_t *seg_mask, const float *k_scale,
+                                   const float *v_scale, void *out, float *lse, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream) {
+  if (pool_len > 0 && (!pool_seg || !pool_seg_host || !seg_mask)) return LA_ERR_INVALID_ARG;
+  return verify_attention(desc, q, k_cache, v_cache, block_tables, prefix_lens, prefix_lens_host, k_branch, v_branch,
+                          k_pool, v_pool, pool_len, nullptr, nullptr, pool_len > 0 ? pool_seg : nullptr,
+                          pool_len > 0 ? pool_seg_host : nullptr, pool_len > 0 ? seg_mask : nullptr, k_scale, v_scale,
+                          out, lse, workspace, workspace_bytes, hip_stream);
 }
 
 la_status la_kv_commit(const la_attn_desc *desc, void *k_cache, void *v_cache, const int32_t *block_tables,

@@ -30,7 +30,11 @@ __global__ __launch_bounds__(64 * kWaves) void attn_f32_kernel(const AttnParams 
   const int i = t % p.L, bstart = t - i;
   const int kvh = h / p.G;
   const int P = p.prefix_lens[b];
-  const int vis = p.C > 0 ? p.chain_vis[b * p.gamma + t / p.L] : 0;
+  // nested form: the first `vis` chain tokens are keys.  Tree form: all C pool tokens are walked and the ones
+  // whose segment the branch does not see score -inf.
+  const bool tree = p.pool_seg != nullptr;
+  const int vis = p.C > 0 ? (tree ? p.C : p.chain_vis[b * p.gamma + t / p.L]) : 0;
+  const uint64_t seen = tree ? p.seg_mask[b * p.gamma + t / p.L] : 0;
   const int n_keys = P + vis + i + 1;
 
   const float *q = (const float *)p.q + grow * D;
@@ -70,16 +74,19 @@ __global__ __launch_bounds__(64 * kWaves) void attn_f32_kernel(const AttnParams 
 #pragma unroll 8
       for (int d = 0; d < D; ++d) dot = __builtin_fmaf(q_lds[wave][d], krow[d], dot);
       s = dot * p.scale_log2;
+      if (tree && key >= P && key < P + vis && !((seen >> p.pool_seg[(size_t)b * p.C + (key - P)]) & 1)) s = -INFINITY;
     }
     float mx = s;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-    const float m_new = fmaxf(m_run, mx);  // finite: key k0 is always visible
-    const float pr = __builtin_amdgcn_exp2f(s - m_new);
+    // finite unless nothing has been visible so far (tree form: a group of unseen pool tokens and no prefix)
+    const float m_new = fmaxf(m_run, mx);
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;
+    const float pr = __builtin_amdgcn_exp2f(s - m_use);
     float sum = pr;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
     l_run = l_run * alpha + sum;
     m_run = m_new;
 #pragma unroll

@@ -8,7 +8,8 @@
 // chunk of a request also reduces the branch-private keys under the mask
 // "same branch and key position <= query position" and, for nested branches
 // (x'_j = x (+) s^_0 .. s^_{j-1}), the part of the request's drafted chain that each
-// branch sees.
+// branch sees, or for a draft tree (W alternative steps per position) the pool tokens
+// of the steps on each branch's root path.
 //
 // Per 64-key tile and wavefront (RB blocks of 32 rows each):
 //   S^T = K Q^T      v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = Q (registers)
@@ -240,9 +241,12 @@ struct RowState {
   float base[RB];    // == m_run once a maximum exists, 0 before
   float m_run[RB], l_run[RB];
   int row_tok[RB], row_bstart[RB];
+  // tree form only: the segments the row's branch sees, and (lane k) the segment of key k of the current pool tile
+  uint64_t row_mask[RB];
+  int tile_seg;
 };
 
-enum MaskMode { MASK_NONE = 0, MASK_TAIL = 1, MASK_BRANCH = 2 };
+enum MaskMode { MASK_NONE = 0, MASK_TAIL = 1, MASK_BRANCH = 2, MASK_TREE = 3 };
 
 // sched_group_barrier masks
 constexpr int kSgMfma = 0x008, kSgValu = 0x002, kSgSalu = 0x004, kSgVmemRead = 0x020, kSgDsRead = 0x100;
@@ -267,6 +271,17 @@ __device__ __forceinline__ void mask_block(f32x16 (&s)[RB], const RowState<RB> &
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
         if (tk > st.row_tok[rb] || tk < st.row_bstart[rb]) s[rb][j] = -INFINITY;
+    }
+  } else if constexpr (MASK == MASK_TREE) {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int ka = kb * 32 + (j >> 2) * 8 + (j & 3);  // this register's key in the lower lane half; upper: + 4
+      const int sa = __builtin_amdgcn_readlane(st.tile_seg, ka), sb = __builtin_amdgcn_readlane(st.tile_seg, ka + 4);
+      const int seg = lh ? sb : sa;
+      const bool past = first + ka + lh * 4 >= limit;
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+        if (past || !((st.row_mask[rb] >> seg) & 1)) s[rb][j] = -INFINITY;
     }
   }
 }
@@ -347,6 +362,7 @@ __device__ __forceinline__ void block_probs(const f32x16 (&s)[RB], float crel, c
 //     O += V1^T P1                   |  tail()  (the caller's LDS stores of the next tile)
 //   first / limit   MASK_TAIL: keys with first + key >= limit are masked
 //                   MASK_BRANCH: key token first + key is visible to a row iff row_bstart <= token <= row_tok
+//                   MASK_TREE: pool token first + key (< limit) is visible to a row iff its segment is in row_mask
 //   crel            score scale of this key segment relative to the prefix scale that Q already carries (1 for prefix
 //                   tiles); voff/lmul move a differently scaled V segment into the accumulator's units
 //                   (p' = p * 2^voff, l += sum(p') * lmul)
@@ -541,9 +557,10 @@ __device__ __forceinline__ void compute_tile(const uint8_t *kt, const uint8_t *n
 //   2: tile i is computed on while tile i+1 is written and tiles i+2, i+3 are in flight from HBM; two workgroups
 //      share a CU, which hides the start-up and per-tile latencies when the row count is small and the KV
 //      stream is the limit.
-//   NESTED: the call carries a drafted chain.  A build switch rather than a run-time test so that the flat kernels
-//   keep the register allocation they were tuned with.
-template <bool KV_FP8, bool BR_FP8, int NW, int RB, int STAGES, bool NESTED>
+//   EXTRA: 0 = flat call, 1 = the call carries a drafted chain (nested form), 2 = a pool of drafted tokens with
+//   segment masks (tree form).  A build switch rather than a run-time test so that the flat kernels keep the
+//   register allocation they were tuned with.
+template <bool KV_FP8, bool BR_FP8, int NW, int RB, int STAGES, int EXTRA>
 __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_kernel(const AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   constexpr int NT = 64 * NW;
@@ -774,12 +791,43 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
                                                 [] {});
     __syncthreads();
   }
+  // ---- phase 3 (tree form): the pool of drafted tokens under the segment masks (last chunk only) ----------------
+  if constexpr (EXTRA == 2) {
+    if (c == n_chunks - 1) {
+      uint64_t seen_any = 0;  // wavefront-uniform: segments seen by any branch of this row tile
+      for (int g = t_lo / p.L; g <= t_hi / p.L; ++g) seen_any |= p.seg_mask[b * p.gamma + g];
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) st.row_mask[rb] = p.seg_mask[b * p.gamma + st.row_tok[rb] / p.L];
+      TileSrc pool = brs;
+      const size_t pool_off = ((size_t)b * p.C * p.Hkv + kvh) * br_row;
+      pool.k_base = (const uint8_t *)p.k_chain + pool_off;
+      pool.v_base = (const uint8_t *)p.v_chain + pool_off;
+      pool.limit = p.C;
+      for (int first = 0; first < p.C; first += kTileN) {
+        // lane k of every wavefront: segment of pool token first + k.  A tile none of whose tokens any branch of
+        // the row tile sees is skipped (the same decision in every wavefront: same data).
+        const int tok = first + lane;
+        const int seg = p.pool_seg[(size_t)b * p.C + min(tok, p.C - 1)];
+        st.tile_seg = seg;
+        if (__builtin_amdgcn_ballot_w64(tok < p.C && ((seen_any >> seg) & 1)) == 0) continue;
+        TileRegs<BR_FP8, NT> regs;
+        pool.first = first;
+        tile_load<BR_FP8, false, false, NT>(p, pool, tid, regs);
+        tile_store<BR_FP8, NT>(lds, tid, regs);
+        __syncthreads();
+        if (active)
+          compute_tile<RB, MASK_TREE, false, false>(lds, nullptr, k0, st, ln, lh, first, p.C, crel_branch, voff_branch,
+                                                    lmul_branch, [] {});
+        __syncthreads();
+      }
+    }
+  }
   // ---- phase 3: the drafted chain of a nested problem, then the branch-private tiles (last chunk only) ----------
   // Branch g sees chain tokens 0 .. vis[g]-1: that is the branch mask with the window [0, vis-1], so the rows'
   // windows are swapped for it while the chain tiles run and both segments share one loop.
   int n_chain = 0;
   TileSrc chn = brs;
-  if (NESTED && c == n_chunks - 1) {
+  if (EXTRA == 1 && c == n_chunks - 1) {
     int vmax = 0;  // wavefront-uniform: the longest visible part among the branches of this row tile
     for (int g = t_lo / p.L; g <= t_hi / p.L; ++g) vmax = max(vmax, p.chain_vis[b * p.gamma + g]);
     vmax = min(vmax, p.C);
@@ -797,7 +845,7 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
     }
   }
   for (int it = 0; it < n_chain + n_priv; ++it) {
-    if (NESTED && it == n_chain && n_chain > 0) {  // back to the rows' own windows
+    if (EXTRA == 1 && it == n_chain && n_chain > 0) {  // back to the rows' own windows
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         st.row_tok[rb] = min(row[rb], p.R - 1) / p.G;
@@ -815,7 +863,7 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
                                                   lmul_branch, [] {});
     __syncthreads();
   }
-  if (NESTED && n_chain > 0 && n_priv == 0) {  // not reached (the last chunk always has private tiles); keeps row_tok honest
+  if (EXTRA == 1 && n_chain > 0 && n_priv == 0) {  // not reached (the last chunk always has private tiles); keeps row_tok honest
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) st.row_tok[rb] = min(row[rb], p.R - 1) / p.G;
   }
@@ -843,10 +891,10 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
   }
 }
 
-template <bool KV_FP8, bool BR_FP8, int NW, int RB, int STAGES, bool NESTED>
+template <bool KV_FP8, bool BR_FP8, int NW, int RB, int STAGES, int EXTRA>
 hipError_t launch_variant(const AttnParams &p, hipStream_t stream) {
   const int grid = p.Hkv * p.n_row_tiles * p.total_units;
-  auto kern = attn_mfma_kernel<KV_FP8, BR_FP8, NW, RB, STAGES, NESTED>;
+  auto kern = attn_mfma_kernel<KV_FP8, BR_FP8, NW, RB, STAGES, EXTRA>;
   static bool configured = false;  // per template instance
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
@@ -862,15 +910,21 @@ hipError_t launch_variant(const AttnParams &p, hipStream_t stream) {
 
 template <int NW, int RB, int STAGES>
 hipError_t launch_shape(const AttnParams &p, bool kv_fp8, bool br_fp8, hipStream_t stream) {
-  if (p.C > 0) {
-    if (kv_fp8 && br_fp8) return launch_variant<true, true, NW, RB, STAGES, true>(p, stream);
-    if (kv_fp8 && !br_fp8) return launch_variant<true, false, NW, RB, STAGES, true>(p, stream);
-    if (!kv_fp8 && !br_fp8) return launch_variant<false, false, NW, RB, STAGES, true>(p, stream);
+  if (p.C > 0 && p.pool_seg) {
+    if (kv_fp8 && br_fp8) return launch_variant<true, true, NW, RB, STAGES, 2>(p, stream);
+    if (kv_fp8 && !br_fp8) return launch_variant<true, false, NW, RB, STAGES, 2>(p, stream);
+    if (!kv_fp8 && !br_fp8) return launch_variant<false, false, NW, RB, STAGES, 2>(p, stream);
     return hipErrorInvalidValue;
   }
-  if (kv_fp8 && br_fp8) return launch_variant<true, true, NW, RB, STAGES, false>(p, stream);
-  if (kv_fp8 && !br_fp8) return launch_variant<true, false, NW, RB, STAGES, false>(p, stream);
-  if (!kv_fp8 && !br_fp8) return launch_variant<false, false, NW, RB, STAGES, false>(p, stream);
+  if (p.C > 0) {
+    if (kv_fp8 && br_fp8) return launch_variant<true, true, NW, RB, STAGES, 1>(p, stream);
+    if (kv_fp8 && !br_fp8) return launch_variant<true, false, NW, RB, STAGES, 1>(p, stream);
+    if (!kv_fp8 && !br_fp8) return launch_variant<false, false, NW, RB, STAGES, 1>(p, stream);
+    return hipErrorInvalidValue;
+  }
+  if (kv_fp8 && br_fp8) return launch_variant<true, true, NW, RB, STAGES, 0>(p, stream);
+  if (kv_fp8 && !br_fp8) return launch_variant<true, false, NW, RB, STAGES, 0>(p, stream);
+  if (!kv_fp8 && !br_fp8) return launch_variant<false, false, NW, RB, STAGES, 0>(p, stream);
   return hipErrorInvalidValue;
 }
 

@@ -27,6 +27,10 @@ struct AttnParams {
   const void *k_chain, *v_chain;
   const int32_t *chain_vis;
   int C;
+  // tree form (pool_seg != nullptr): the C tokens are a pool; token c of request b belongs to segment
+  // pool_seg[b*C + c] (0..63) and branch g sees the tokens whose segment bit is set in seg_mask[b*gamma + g]
+  const int32_t *pool_seg;
+  const uint64_t *seg_mask;
   const int32_t *block_tables, *prefix_lens;
   const float *k_scale, *v_scale;
   float *part_o;   // [B, s_max, n_rows, D]

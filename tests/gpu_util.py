@@ -69,6 +69,27 @@ def run_attention_nested(case: W.AttnCase, inp: dict, chain: dict, kv_split_toke
     return out.double().cpu().numpy(), lse.double().cpu().numpy()
 
 
+def run_attention_tree(case: W.AttnCase, inp: dict, tree: dict, kv_split_tokens: int = 0):
+    """la_verify_attention_tree on ``inp`` plus the pool ``tree`` (k_pool, v_pool, pool_seg, seg_mask)."""
+    dev = upload_attention(case, inp)
+    desc = attn_desc(case, kv_split_tokens)
+    lens = [int(x) for x in inp["prefix_lens"]]
+    ws = torch.empty(max(B.la_verify_attention_workspace(desc, lens), 16), dtype=torch.uint8, device="cuda")
+    out = B.empty_out((case.B, case.gamma, case.L, case.Hq, case.D), case.out_dtype)
+    out.fill_(float("nan"))
+    lse = torch.full((case.B, case.gamma, case.L, case.Hq), float("nan"), dtype=torch.float32, device="cuda")
+    has = tree["k_pool"].shape[1] > 0
+    kp = B.to_device(tree["k_pool"], case.branch_kv_dtype) if has else None
+    vp = B.to_device(tree["v_pool"], case.branch_kv_dtype) if has else None
+    seg = torch.from_numpy(tree["pool_seg"]).cuda() if has else None
+    mask = torch.from_numpy(tree["seg_mask"].view(np.int64)).cuda() if has else None
+    B.la_verify_attention_tree(desc, dev["q"], dev["k_cache"], dev["v_cache"], dev["block_tables"],
+                               dev["prefix_lens"], lens, dev["k_branch"], dev["v_branch"], kp, vp, seg,
+                               tree["pool_seg"].tolist(), mask, dev["k_scale"], dev["v_scale"], out, lse, ws)
+    torch.cuda.synchronize()
+    return out.double().cpu().numpy(), lse.double().cpu().numpy()
+
+
 def row_errors(got: np.ndarray, ref: np.ndarray):
     """Per output row: max |got-ref| over D divided by max |ref| over D.  Returns the vector of row errors."""
     D = ref.shape[-1]

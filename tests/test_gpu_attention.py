@@ -173,6 +173,112 @@ def test_nested_rejects_bad_visibility():
             run_attention_nested(case, inp, W.make_chain_inputs(case, 10, inp, vis))
 
 
+# ----------------------------------------------------------------------------------------- draft trees
+
+def check_tree(oracle, case, width, depth, step_len, tol, kv_split_tokens=0, edit=None):
+    from gpu_util import row_errors, run_attention_tree
+    inp = W.make_attention_inputs(case)
+    tree = W.make_tree_inputs(case, width, depth, step_len, inp)
+    if edit is not None:
+        edit(tree)
+    print(f"tree case {case.name} prefix={case.prefix_lens} gamma={case.gamma} L={case.L} W={width} depth={depth} "
+          f"step={step_len} masks={[[hex(int(m)) for m in row] for row in tree['seg_mask']]} kv={case.kv_dtype} "
+          f"br={case.branch_kv_dtype} split={kv_split_tokens}", flush=True)
+    got, lse = run_attention_tree(case, inp, tree, kv_split_tokens)
+    ref, ref_lse = oracle.verify_attention(**inp, **tree, q_dtype=case.q_dtype, kv_dtype=case.kv_dtype,
+                                           branch_kv_dtype=case.branch_kv_dtype, block_size=case.block_size,
+                                           scale=case.scale)
+    assert np.isfinite(got).all()
+    err = row_errors(got, ref)
+    assert err.max() <= tol, f"max row error {err.max():.3e} at row {err.argmax()}"
+    assert np.abs(lse - ref_lse).max() <= (1e-5 if tol == TOL_F32 else 1e-2)
+    return got
+
+
+def high_segments(tree):
+    """Move the segment ids to the top of the 64-bit mask (ids 63, 62, ...): the upper mask word is exercised."""
+    n = int(tree["pool_seg"].max()) + 1
+    tree["pool_seg"][:] = 63 - tree["pool_seg"]
+    tree["seg_mask"][:] = [[sum(1 << (63 - s) for s in range(n) if (int(m) >> s) & 1) for m in row]
+                           for row in tree["seg_mask"]]
+
+
+TREE_CASES = [
+    # (case, width, depth, tokens per step, edit)
+    (W.AttnCase("tree_f32", (77, 0, 130), 5, 5, 6, 2, 128, "f32", "f32", "f32", "f32", seed=51), 2, 3, 7, None),
+    (W.AttnCase("tree_f32_no_prefix_high_ids", (0, 3), 4, 9, 8, 2, 64, "f32", "f32", "f32", "f32", paged=True,
+                seed=52), 3, 2, 30, high_segments),
+    # W = 2, three positions: 14 nodes of 20 tokens = 280 pool tokens (more than four key tiles, ragged tail)
+    (W.AttnCase("tree_bf16_w2", (1000,), 6, 20, 16, 2, 128, seed=53), 2, 3, 20, None),
+    # row tiles straddle branches (L*G = 210); W = 3, two positions: 12 nodes
+    (W.AttnCase("tree_bf16_w3_paged", (130, 515), 5, 70, 6, 2, 128, paged=True, seed=54), 3, 2, 11, high_segments),
+    (W.AttnCase("tree_fp8", (900,), 4, 33, 10, 2, 128, "bf16", "fp8_e4m3", "fp8_e4m3", "bf16", seed=55), 2, 4, 9,
+     None),
+    (W.AttnCase("tree_fp8_bf16_branch", (515, 64), 3, 40, 8, 1, 128, "bf16", "fp8_e4m3", "bf16", "f32", paged=True,
+                seed=56), 2, 2, 40, None),
+    (W.AttnCase("tree_bf16_no_prefix", (0,), 4, 8, 8, 2, 128, seed=57), 2, 2, 5, None),
+    # 62 nodes of 3 tokens: nearly every bit of the mask in use
+    (W.AttnCase("tree_bf16_62_nodes", (321,), 8, 1, 40, 8, 128, seed=58), 2, 5, 3, None),
+]
+
+
+@pytest.mark.parametrize("case,width,depth,step_len,edit", TREE_CASES, ids=lambda x: getattr(x, "name", None))
+def test_tree_small_cases(oracle, case, width, depth, step_len, edit):
+    tol = TOL_F32 if case.kv_dtype == "f32" else TOL_LOWP
+    for split in ((0,) if case.kv_dtype == "f32" else (0, 64, 256)):
+        check_tree(oracle, case, width, depth, step_len, tol, split, edit)
+
+
+@pytest.mark.parametrize("shape", [0, 1])
+def test_tree_every_kernel_shape(oracle, shape, monkeypatch):
+    monkeypatch.setenv("LA_ATTN_SHAPE", str(shape))
+    for case, width, depth, step_len, edit in (TREE_CASES[2], TREE_CASES[3], TREE_CASES[4]):
+        for split in (0, 192):
+            check_tree(oracle, case, width, depth, step_len, TOL_LOWP, split, edit)
+
+
+def test_tree_whose_masks_are_leading_parts_equals_the_nested_call():
+    """The same visibility said in both vocabularies: the two entry points must agree bit for bit."""
+    from gpu_util import run_attention_nested, run_attention_tree
+    case = W.AttnCase("tree_chain", (300, 70), 4, 12, 8, 2, 128, seed=59)
+    inp = W.make_attention_inputs(case)
+    tree = W.make_tree_inputs(case, 1, 6, 25, inp)                 # a chain of 6 steps of 25 tokens
+    tree["seg_mask"][:] = [[0, 0b1, 0b111, 0b111111], [0b11, 0, 0b1111, 0b11111]]
+    vis = np.array([[0, 25, 75, 150], [50, 0, 100, 125]], dtype=np.int32)
+    a, la = run_attention_tree(case, inp, tree)
+    b, lb = run_attention_nested(case, inp, {"k_chain": tree["k_pool"], "v_chain": tree["v_pool"], "chain_vis": vis})
+    assert np.array_equal(a, b) and np.array_equal(la, lb)
+
+
+def test_tree_with_empty_masks_is_the_flat_call():
+    """MFMA path: pool tiles nobody sees are skipped, so the result is the flat call's bit for bit.  fp32 path: the
+    unseen tokens are walked with weight zero, which regroups the 64-key steps of the running softmax: equal up to
+    fp32 rounding."""
+    from gpu_util import row_errors, run_attention, run_attention_tree
+    for case in (TREE_CASES[0][0], TREE_CASES[2][0]):
+        inp = W.make_attention_inputs(case)
+        flat, flat_lse = run_attention(case, inp)
+        tree = W.make_tree_inputs(case, 2, 2, 10, inp)
+        tree["seg_mask"][:] = 0
+        got, lse = run_attention_tree(case, inp, tree)
+        if case.kv_dtype == "f32":
+            assert row_errors(got, flat).max() < 1e-6 and np.abs(lse - flat_lse).max() < 1e-6
+        else:
+            assert np.array_equal(got, flat) and np.array_equal(lse, flat_lse)
+
+
+def test_tree_rejects_bad_segments():
+    from gpu_util import run_attention_tree
+    from paper_2506_19830_amd import binding as B
+    case = TREE_CASES[0][0]
+    inp = W.make_attention_inputs(case)
+    for bad in (64, -1):
+        tree = W.make_tree_inputs(case, 2, 2, 4, inp)
+        tree["pool_seg"][1, 3] = bad
+        with pytest.raises(B.LaError):
+            run_attention_tree(case, inp, tree)
+
+
 def test_mfma_fp32_output_is_tight(oracle):
     """With fp32 output the low-precision steps left are P rounded to bf16 and Q rounded to bf16 again after the
     score scale is folded in: errors stay at a few 1e-3, well inside the 2e-2 bar."""
