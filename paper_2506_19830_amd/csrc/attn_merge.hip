@@ -86,11 +86,65 @@ __global__ __launch_bounds__(64 * kWaves) void attn_merge_kernel(const AttnParam
   if (p.lse && lane == 0) p.lse[grow] = 0.69314718055994530942f * (m_all + __builtin_log2f(denom));
 }
 
+// Few chunks (at most kFew per request), the usual case with many query rows: 32 threads own one row, four output
+// columns each.  Every thread forms the weights of its row itself (the (m, l) pairs are one broadcast load each) and
+// has all its 16-byte partial loads in flight at once; nothing is exchanged between lanes.
+constexpr int kFew = 8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+
+__global__ __launch_bounds__(256) void attn_merge_few_kernel(const AttnParams p) {
+  const size_t grow = (size_t)blockIdx.x * 8 + (threadIdx.x >> 5);  // row over all requests
+  if (grow >= (size_t)p.B * p.n_rows) return;
+  const int col = (threadIdx.x & 31) * 4;
+  const int b = (int)(grow / p.n_rows);
+  const int r = (int)(grow % p.n_rows);
+  const int n_s = attn_num_chunks(p.prefix_lens[b], p.chunk_len);  // <= kFew (checked by the host)
+  const size_t slot0 = (size_t)b * p.s_max;
+  const size_t stride = (size_t)p.n_rows * kD;
+  const float *po = p.part_o + (slot0 * p.n_rows + r) * kD + col;
+  const float *pml = p.part_ml + (slot0 * p.n_rows + r) * 2;
+
+  f32x4 o[kFew];
+  float m[kFew], l[kFew];
+#pragma unroll
+  for (int s = 0; s < kFew; ++s) {
+    const int sc = s < n_s ? s : n_s - 1;  // surplus slots repeat the last chunk with weight zero
+    o[s] = *(const f32x4 *)(po + (size_t)sc * stride);
+    const f32x2 ml = *(const f32x2 *)(pml + (size_t)sc * p.n_rows * 2);
+    m[s] = s < n_s ? ml.x : -INFINITY;
+    l[s] = ml.y;
+  }
+  float m_all = m[0];
+#pragma unroll
+  for (int s = 1; s < kFew; ++s) m_all = fmaxf(m_all, m[s]);
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  float denom = 0.f;
+#pragma unroll
+  for (int s = 0; s < kFew; ++s) {
+    const float w = __builtin_amdgcn_exp2f(m[s] - m_all);  // 0 for surplus slots
+    denom = __builtin_fmaf(w, l[s], denom);
+    acc += o[s] * w;
+  }
+  const float inv = 1.0f / denom;
+  acc *= inv;
+  const size_t orow = grow * kD + col;
+  if (p.out_f32)
+    *(f32x4 *)((float *)p.out + orow) = acc;
+  else
+    *(bf16x4 *)((__bf16 *)p.out + orow) = __builtin_convertvector(acc, bf16x4);
+  if (p.lse && col == 0) p.lse[grow] = 0.69314718055994530942f * (m_all + __builtin_log2f(denom));
+}
+
 }  // namespace
 
 hipError_t launch_attn_merge(const AttnParams &p, hipStream_t stream) {
   ProfileScope scope(SLOT_ATTN_MERGE, stream);
   const size_t rows = (size_t)p.B * p.n_rows;
+  if (p.s_max <= kFew) {
+    hipLaunchKernelGGL(attn_merge_few_kernel, dim3((unsigned)((rows + 7) / 8)), dim3(256), 0, stream, p);
+    return hipGetLastError();
+  }
   const int grid = (int)((rows + kWaves - 1) / kWaves);
   hipLaunchKernelGGL(attn_merge_kernel, dim3(grid), dim3(64 * kWaves), 0, stream, p);
   return hipGetLastError();
