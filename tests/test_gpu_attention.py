@@ -389,3 +389,43 @@ def test_full_size_configs_on_sampled_rows(oracle, n):
     err = row_errors(got.reshape(-1, case.D)[ids], ref)
     assert err.max() <= TOL_LOWP, f"max row error {err.max():.3e}"
     assert np.abs(lse.reshape(-1)[ids] - ref_lse).max() <= 1e-2
+
+
+# ----------------------------------------------------------------------------------------- random shapes
+
+def random_case(rng, idx):
+    """A small random problem: every structural parameter drawn, sizes kept to what the oracle does in a second."""
+    dt = [("bf16", "bf16", "bf16", "bf16"), ("bf16", "fp8_e4m3", "fp8_e4m3", "bf16"),
+          ("bf16", "fp8_e4m3", "bf16", "f32"), ("bf16", "bf16", "bf16", "f32"), ("f32", "f32", "f32", "f32")][idx % 5]
+    hkv = int(rng.choice([1, 2, 4, 8]))
+    g = int(rng.choice([1, 2, 5, 8, 16]))
+    nreq = int(rng.choice([1, 2, 3, 6]))
+    gamma = int(rng.choice([1, 2, 3, 5, 8]))
+    L = int(rng.choice([1, 2, 7, 16, 33, 64, 90]))
+    while nreq * gamma * L * hkv * g > 6000:          # rows; keeps the oracle quick
+        L = max(1, L // 2)
+    bs = int(rng.choice([16, 32, 64, 128]))
+    prefix = tuple(int(x) for x in rng.choice([0, 1, 15, 64, 65, 200, 513, 1100, 2500], size=nreq))
+    D = 128 if dt[0] != "f32" else int(rng.choice([64, 128, 256]))
+    return W.AttnCase(f"rand{idx}", prefix, gamma, L, hkv * g, hkv, D, *dt, block_size=bs,
+                      paged=bool(rng.integers(0, 2)), seed=100 + idx)
+
+
+@pytest.mark.parametrize("idx", range(30))
+def test_random_shapes(oracle, idx):
+    """Flat, nested and tree calls on randomly drawn shapes (heads, group size, requests, branches, branch length,
+    block size, ragged prefixes, paging, dtypes, split), each against the oracle."""
+    rng = np.random.default_rng(1000 + idx)
+    case = random_case(rng, idx)
+    tol = TOL_F32 if case.kv_dtype == "f32" else TOL_LOWP
+    split = 0 if case.kv_dtype == "f32" else int(rng.choice([0, 64, 128, 448]))
+    kind = idx % 3
+    if kind == 0:
+        check_full(oracle, case, tol, kv_split_tokens=split)
+    elif kind == 1:
+        C = int(rng.choice([1, 5, 64, 65, 130]))
+        vis = rng.integers(0, C + 1, size=(case.B, case.gamma))
+        check_nested(oracle, case, C, tol, vis, split)
+    else:
+        width, depth = [(1, 4), (2, 2), (2, 3), (3, 2), (4, 2)][int(rng.integers(0, 5))]
+        check_tree(oracle, case, width, depth, int(rng.choice([1, 4, 17, 40])), tol, split)
