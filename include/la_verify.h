@@ -323,6 +323,22 @@ LA_API la_status la_speedup_token(double alpha2, double c2, int32_t k2, double *
 LA_API la_status la_plan_budget(const la_plan_desc *desc, int32_t *k1, int32_t *k2, double *speedup);
 
 /* ------------------------------------------------------------------------- *
+ *  Calibration (benchmark aid, not part of the verification path): what the
+ *  chip at hand reaches on a pure bf16 MFMA loop and on a pure streaming read,
+ *  to quote a roofline fraction against the achievable rate beside the
+ *  published peak.  Both only enqueue a kernel; time them with la_profile_*
+ *  (slots "calib_mfma", "calib_read") or with events of your own.
+ *
+ *  la_calibrate_mfma: `workgroups` x 8 wavefronts, each `iters` rounds of four
+ *  independent v_mfma_f32_32x32x16_bf16; *flops (host) receives the launch's
+ *  flop count.  sink: dev, workgroups * 512 floats, written.
+ *  la_calibrate_read: reads `bytes` (a multiple of 16 is read) from src (dev,
+ *  16-byte aligned) once; sink: dev, one word (written practically never).
+ * ------------------------------------------------------------------------- */
+LA_API la_status la_calibrate_mfma(int32_t workgroups, int32_t iters, float *sink, double *flops, void *hip_stream);
+LA_API la_status la_calibrate_read(const void *src, size_t bytes, uint32_t *sink, void *hip_stream);
+
+/* ------------------------------------------------------------------------- *
  *  Diagnostics
  * ------------------------------------------------------------------------- */
 LA_API const char *la_status_string(la_status s);

@@ -25,7 +25,7 @@ _TORCH_DTYPES = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch
 
 EXPORTED_SYMBOLS = (
     "la_verify_attention_workspace", "la_verify_attention", "la_verify_attention_nested", "la_verify_attention_tree", "la_kv_commit",
-    "la_step_select", "la_speedup_step_sync", "la_speedup_step_async", "la_speedup_token", "la_plan_budget",
+    "la_calibrate_mfma", "la_calibrate_read", "la_step_select", "la_speedup_step_sync", "la_speedup_step_async", "la_speedup_token", "la_plan_budget",
     "la_spec_accept_workspace",
     "la_spec_accept",
     "la_status_string", "la_profile_enable", "la_profile_select", "la_profile_collect", "la_profile_num_kernels", "la_profile_get",
@@ -96,6 +96,10 @@ def load() -> ctypes.CDLL:
         lib.la_kv_commit.argtypes = [ctypes.POINTER(la_attn_desc), vp, vp, i32p, i32p, ctypes.POINTER(ctypes.c_int32),
                                      vp, vp, vp, vp, ctypes.c_int32, i32p, i32p, i32p, vp, vp, i32p,
                                      ctypes.POINTER(la_layer_strides), vp]
+        lib.la_calibrate_mfma.restype = ctypes.c_int
+        lib.la_calibrate_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
+        lib.la_calibrate_read.restype = ctypes.c_int
+        lib.la_calibrate_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         lib.la_step_select.restype = ctypes.c_int
         lib.la_step_select.argtypes = [ctypes.c_int32, ctypes.c_int32] + [vp] * 7
         for fn in (lib.la_speedup_step_sync, lib.la_speedup_step_async, lib.la_speedup_token):
@@ -225,6 +229,26 @@ def la_kv_commit(desc: la_attn_desc, k_cache, v_cache, block_tables, prefix_lens
                              ctypes.byref(layers) if layers is not None else None, _stream())
     if st:
         raise LaError(st, "la_kv_commit")
+
+
+def la_calibrate_mfma(workgroups: int, iters: int, sink) -> float:
+    """Enqueue the pure-MFMA calibration kernel; returns the launch's flop count."""
+    if sink.numel() < workgroups * 512:
+        raise ValueError("sink must hold workgroups * 512 floats")
+    flops = ctypes.c_double()
+    st = load().la_calibrate_mfma(workgroups, iters, _ptr(sink), ctypes.byref(flops), _stream())
+    if st:
+        raise LaError(st, "la_calibrate_mfma")
+    return flops.value
+
+
+def la_calibrate_read(src, sink) -> int:
+    """Enqueue the streaming-read calibration kernel over the whole of ``src``; returns the bytes it reads."""
+    nbytes = src.numel() * src.element_size()
+    st = load().la_calibrate_read(_ptr(src), ctypes.c_size_t(nbytes), _ptr(sink), _stream())
+    if st:
+        raise LaError(st, "la_calibrate_read")
+    return nbytes // 16 * 16
 
 
 def la_step_select(verdicts, chain_vis, own_len):

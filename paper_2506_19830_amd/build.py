@@ -19,7 +19,7 @@ OBJ = HERE / "_build"
 LIB = HERE / "libla_verify.so"
 
 SOURCES = ["api.hip", "attn_mfma.hip", "attn_merge.hip", "attn_f32.hip", "accept.hip", "kv_commit.hip",
-           "controller.hip"]
+           "controller.hip", "calibrate.hip"]
 # -fno-honor-nans: no NaN can arise in these kernels (masked scores are -inf, handled explicitly); without it
 # every fmaxf is preceded by a canonicalising v_max(x, x).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-fno-honor-nans", "-Wall",

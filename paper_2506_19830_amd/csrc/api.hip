@@ -149,7 +149,8 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, Attn
 
 // ---- profiling ---------------------------------------------------------------------------------
 const char *kSlotNames[SLOT_COUNT] = {"attn_mfma",     "attn_merge",   "attn_f32",   "accept_stats", "accept_warp",
-                                      "accept_decide", "accept_resid", "accept_pick", "kv_commit"};
+                                      "accept_decide", "accept_resid", "accept_pick", "kv_commit",
+                                      "calib_mfma",    "calib_read"};
 struct ProfileRecord {
   int slot;
   hipEvent_t start, stop;

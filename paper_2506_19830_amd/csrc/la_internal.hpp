@@ -64,6 +64,8 @@ enum KernelSlot {
   SLOT_ACCEPT_RESID,
   SLOT_ACCEPT_PICK,
   SLOT_KV_COMMIT,
+  SLOT_CALIB_MFMA,
+  SLOT_CALIB_READ,
   SLOT_COUNT
 };
 
