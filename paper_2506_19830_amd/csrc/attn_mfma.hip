@@ -844,6 +844,15 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
       }
     }
   }
+  // the loads of tile it+1 are in flight while tile it is computed on
+  TileRegs<BR_FP8, NT> bregs;
+  auto load_extra = [&](int it) {
+    TileSrc src = it < n_chain ? chn : brs;
+    src.first = it < n_chain ? it * kTileN : tk0 + (it - n_chain) * kTileN;
+    tile_load<BR_FP8, false, false, NT>(p, src, tid, bregs);
+    return src.first;
+  };
+  int first_cur = n_chain + n_priv > 0 ? load_extra(0) : 0;
   for (int it = 0; it < n_chain + n_priv; ++it) {
     if (EXTRA == 1 && it == n_chain && n_chain > 0) {  // back to the rows' own windows
 #pragma unroll
@@ -852,14 +861,12 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
         st.row_bstart[rb] = (st.row_tok[rb] / p.L) * p.L;
       }
     }
-    TileRegs<BR_FP8, NT> regs;
-    TileSrc src = it < n_chain ? chn : brs;
-    src.first = it < n_chain ? it * kTileN : tk0 + (it - n_chain) * kTileN;
-    tile_load<BR_FP8, false, false, NT>(p, src, tid, regs);
-    tile_store<BR_FP8, NT>(lds, tid, regs);
+    tile_store<BR_FP8, NT>(lds, tid, bregs);
     __syncthreads();
+    const int first = first_cur;
+    if (it + 1 < n_chain + n_priv) first_cur = load_extra(it + 1);
     if (active)
-      compute_tile<RB, MASK_BRANCH, false, false>(lds, nullptr, k0, st, ln, lh, src.first, 0, crel_branch, voff_branch,
+      compute_tile<RB, MASK_BRANCH, false, false>(lds, nullptr, k0, st, ln, lh, first, 0, crel_branch, voff_branch,
                                                   lmul_branch, [] {});
     __syncthreads();
   }
