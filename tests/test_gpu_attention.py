@@ -391,6 +391,33 @@ def test_full_size_configs_on_sampled_rows(oracle, n):
     assert np.abs(lse.reshape(-1)[ids] - ref_lse).max() <= 1e-2
 
 
+def test_very_long_ragged_paged_prefix_on_sampled_rows(oracle, monkeypatch):
+    """A 300001-token paged fp8 prefix next to a short one, through both kernel shapes: automatic splits, a chunk at
+    the limit of block ids a workgroup keeps in LDS (4092 of 4096), many short chunks (74 per request: the general
+    merge form)."""
+    from gpu_util import row_errors, run_attention
+    case = W.AttnCase("long_prefix", (300001, 777), 2, 5, 8, 2, 128, "bf16", "fp8_e4m3", "fp8_e4m3", "bf16",
+                      paged=True, seed=61)
+    import torch
+    dev = W.make_attention_inputs_device(case)
+    inp = W.device_inputs_to_numpy(case, dev)
+    ids = sampled_rows(case, 100)
+    ref, ref_lse = oracle_attention(oracle, case, inp, row_ids=ids)
+    for shape, split in ((0, 0), (1, 0), (0, 65472), (1, 4096)):
+        monkeypatch.setenv("LA_ATTN_SHAPE", str(shape))
+        print(f"long prefix: shape {shape} split {split}", flush=True)
+        got, lse = run_attention(case, inp, split, dev=dev)
+        err = row_errors(got.reshape(-1, case.D)[ids], ref)
+        assert err.max() <= TOL_LOWP, f"max row error {err.max():.3e}"
+        assert np.abs(lse.reshape(-1)[ids] - ref_lse).max() <= 1e-2
+    # a chunk longer than the block ids a workgroup can hold is refused when it is asked for explicitly
+    from paper_2506_19830_amd import binding as B
+    with pytest.raises(B.LaError):
+        run_attention(case, inp, 65536, dev=dev)
+    del dev
+    torch.cuda.empty_cache()
+
+
 # ----------------------------------------------------------------------------------------- random shapes
 
 def random_case(rng, idx):
