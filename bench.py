@@ -43,6 +43,9 @@ def parse_args():
     ap.add_argument("--tree", type=str, default=None, metavar="W,DEPTH,STEP",
                     help="draft tree: W alternative steps per position, DEPTH positions, STEP tokens per step "
                          "(la_verify_attention_tree); branch g is given the root path of a node")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the step (all layers' attention and merge launches and the accept call) in one HIP "
+                         "graph and time its replays; the per-kernel timings then come from an untimed eager pass")
     ap.add_argument("--kv-commit", action="store_true",
                     help="measure la_kv_commit instead (the step after the pass: all layers' surviving K/V appended "
                          "to the paged cache in one launch) and print its JSON line")
@@ -391,13 +394,29 @@ def main():
     #      step would show in the wall time) and the accept scan.
     B.la_profile_reset()
     B.la_profile_select(["attn_mfma", "accept_stats"], stride=4 if n_layers >= 8 else 1)
-    B.la_profile_enable(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
+    if args.graph:
+        # the library only enqueues kernels, so the whole step is capturable; events cannot be part of the graph
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        B.la_profile_enable(True)      # the dominant kernel's duration: one untimed eager pass
         step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+        torch.cuda.synchronize()
+    else:
+        B.la_profile_enable(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
     B.la_profile_enable(False)
     prof = B.la_profile_collect()
     # one more, untimed pass with every kernel bracketed, for the per-kernel breakdown
@@ -452,6 +471,7 @@ def main():
             "kv_split_tokens": args.kv_split_tokens,
             "chain_len": C,
             "tree": args.tree, "pool_len": None if tree is None else tree["pool_len"],
+            "hip_graph": bool(args.graph),
         },
         "roofline": {
             "kernel": "attn_mfma_kernel",
