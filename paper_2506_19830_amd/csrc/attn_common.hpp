@@ -32,9 +32,6 @@ __device__ __forceinline__ int vt_pos(int kq) { return 16 * (kq >> 2) + 8 * (kq 
 
 // LDS row of head-dim column d in the V^T tile: block d%4, row d/4 inside the block
 __device__ __forceinline__ int vt_row(int d) { return (d & 3) * 32 + (d >> 2); }
-// bf16 V loads: lane -> column pair so that lanes 0..31 hold the even pairs and lanes 32..63 the odd ones; the
-// transposed LDS writes of a half wavefront then land in consecutive rows
-__device__ __forceinline__ int v_pair_of_lane(int lane) { return 2 * (lane & 31) + (lane >> 5); }
 
 // max / sum of a value with its partner in the other half of the wavefront (lane ^ 32)
 __device__ __forceinline__ float xhalf_max(float v) {

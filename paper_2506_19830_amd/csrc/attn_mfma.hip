@@ -47,13 +47,15 @@ struct TileSrc {
   int limit;                       // keys >= limit are zero filled
 };
 
-// Staging registers of one K tile and one V tile per thread: 16-byte pieces of K rows, 4-byte pieces of V rows.
+// Staging registers of one K tile and one V tile per thread: 16-byte pieces of K rows; of V, four consecutive
+// head-dim columns (4 bytes fp8, 8 bytes bf16) of the four keys of a key quad.
 template <bool FP8, int NT>
 struct TileRegs {
   static constexpr int kNK = (FP8 ? 512 : 1024) / NT;  // K pieces per thread
-  static constexpr int kNV = (FP8 ? 512 : 1024) / NT;  // V key quads per thread
+  static constexpr int kNV = 512 / NT;                 // V key quads per thread
+  static constexpr int kVW = FP8 ? 1 : 2;              // dwords per key of a quad
   u32x4 k[kNK];
-  uint32_t v[4 * kNV];
+  uint32_t v[4 * kNV * kVW];
 };
 
 // Address of key row `tok`.  Cache blocks are [block][Hkv][block_size][D]: inside a block consecutive tokens of
@@ -74,7 +76,6 @@ __device__ __forceinline__ const uint8_t *key_row(const AttnParams &p, const Til
 // last valid key and the values zeroed, so the loads stay unconditional and in bounds.
 template <bool FP8, bool PREFIX, bool FULL, int NT>
 __device__ __forceinline__ void tile_load(const AttnParams &p, const TileSrc &s, int tid, TileRegs<FP8, NT> &r) {
-  constexpr int row_bytes = kD * (FP8 ? 1 : 2);
   constexpr int k_piece_shift = FP8 ? 3 : 4;  // 16-byte pieces per key row: 8 (fp8) or 16 (bf16)
 #pragma unroll
   for (int e = 0; e < TileRegs<FP8, NT>::kNK; ++e) {
@@ -85,24 +86,22 @@ __device__ __forceinline__ void tile_load(const AttnParams &p, const TileSrc &s,
     if (!FULL && tok >= s.limit) val = u32x4{0, 0, 0, 0};
     r.k[e] = val;
   }
-  constexpr int v_quad_shift = FP8 ? 5 : 6;  // 4-byte pieces per key row: 32 (fp8) or 64 (bf16)
+  constexpr int kVW = TileRegs<FP8, NT>::kVW;
 #pragma unroll
   for (int e = 0; e < TileRegs<FP8, NT>::kNV; ++e) {
     const int idx = tid + NT * e;
-    const int kq = idx >> v_quad_shift;
-    const int piece = FP8 ? (idx & 31) : v_pair_of_lane(idx & 63);
+    const int kq = idx >> 5;            // 32 pieces of four columns per key row
+    const int piece = idx & 31;
     const int tok0 = s.first + 4 * kq;  // the four keys of a quad share a cache block (block_size % 16 == 0)
-    if constexpr (FULL && PREFIX) {
-      const uint8_t *row = key_row<FP8, PREFIX>(p, s, s.v_base, tok0) + piece * 4;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) r.v[4 * e + c] = *(const uint32_t *)(row + c * row_bytes);
-    } else {
+    for (int c = 0; c < 4; ++c) {
+      const int tok = tok0 + c;
+      const int tc = (FULL && PREFIX) ? tok : min(tok, s.limit - 1);
+      const uint8_t *src = key_row<FP8, PREFIX>(p, s, s.v_base, tc) + piece * 4 * kVW;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const int tok = tok0 + c;
-        const int tc = min(tok, s.limit - 1);
-        const uint32_t val = *(const uint32_t *)(key_row<FP8, PREFIX>(p, s, s.v_base, tc) + piece * 4);
-        r.v[4 * e + c] = tok < s.limit ? val : 0u;
+      for (int w = 0; w < kVW; ++w) {
+        const uint32_t val = *(const uint32_t *)(src + 4 * w);
+        r.v[(4 * e + c) * kVW + w] = ((FULL && PREFIX) || tok < s.limit) ? val : 0u;
       }
     }
   }
@@ -116,7 +115,7 @@ __device__ __forceinline__ void tile_load(const AttnParams &p, const TileSrc &s,
 // which leaves one LDS read of the block id and one 64-bit multiply-add per load.
 template <bool FP8, int NT>
 struct PrefixLoader {
-  static constexpr int kNK = TileRegs<FP8, NT>::kNK, kNV = TileRegs<FP8, NT>::kNV;
+  static constexpr int kNK = TileRegs<FP8, NT>::kNK, kNV = TileRegs<FP8, NT>::kNV, kVW = TileRegs<FP8, NT>::kVW;
   static constexpr int row_bytes = kD * (FP8 ? 1 : 2);
   const int32_t *blk;                        // LDS: block ids of the chunk
   int slot_k[kNK], slot_v[kNV];              // tl >> shift: block slot relative to the tile's first block
@@ -138,14 +137,12 @@ struct PrefixLoader {
       slot_k[e] = tl >> shift;
       base_k[e] = s.k_base + (size_t)(tl & bs_mask) * row_bytes + (idx & ((1 << k_piece_shift) - 1)) * 16;
     }
-    constexpr int v_quad_shift = FP8 ? 5 : 6;
 #pragma unroll
     for (int e = 0; e < kNV; ++e) {
       const int idx = tid + NT * e;
-      const int tl = 4 * (idx >> v_quad_shift);
-      const int piece = FP8 ? (idx & 31) : v_pair_of_lane(idx & 63);
+      const int tl = 4 * (idx >> 5);
       slot_v[e] = tl >> shift;
-      base_v[e] = s.v_base + (size_t)(tl & bs_mask) * row_bytes + piece * 4;
+      base_v[e] = s.v_base + (size_t)(tl & bs_mask) * row_bytes + (idx & 31) * 4 * kVW;
     }
   }
   // `first`: first token of the tile (a multiple of 64, every key of the tile valid)
@@ -159,7 +156,15 @@ struct PrefixLoader {
     for (int e = 0; e < kNV; ++e) {
       const uint8_t *row = base_v[e] + (size_t)(uint32_t)blk[rel + slot_v[e]] * blk_stride + inside;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) r.v[4 * e + c] = *(const uint32_t *)(row + c * row_bytes);
+      for (int c = 0; c < 4; ++c) {
+        if constexpr (kVW == 1) {
+          r.v[4 * e + c] = *(const uint32_t *)(row + c * row_bytes);
+        } else {
+          const u32x2 pair = *(const u32x2 *)(row + c * row_bytes);
+          r.v[(4 * e + c) * 2] = pair[0];
+          r.v[(4 * e + c) * 2 + 1] = pair[1];
+        }
+      }
     }
   }
 };
@@ -179,14 +184,20 @@ __device__ __forceinline__ void tile_store(uint8_t *stage, int tid, const TileRe
 #pragma unroll
     for (int e = 0; e < TileRegs<FP8, NT>::kNV; ++e) {
       const int idx = tid + NT * e;
-      const int kq = idx >> 6;
-      const int dp = v_pair_of_lane(idx & 63);  // this thread holds columns 2dp, 2dp+1 of the quad's 4 keys
-      const uint32_t a = r.v[4 * e + 0], b = r.v[4 * e + 1], c = r.v[4 * e + 2], d = r.v[4 * e + 3];
-      // low halves hold column 2dp of keys (a,b,c,d), high halves column 2dp+1
-      u32x2 lo = {__builtin_amdgcn_perm(b, a, 0x05040100u), __builtin_amdgcn_perm(d, c, 0x05040100u)};
-      u32x2 hi = {__builtin_amdgcn_perm(b, a, 0x07060302u), __builtin_amdgcn_perm(d, c, 0x07060302u)};
-      *(u32x2 *)(vt + vt_row(2 * dp) * kVRow + vt_pos(kq) * 2) = lo;
-      *(u32x2 *)(vt + vt_row(2 * dp + 1) * kVRow + vt_pos(kq) * 2) = hi;
+      const int kq = idx >> 5;
+      const int d0 = 4 * (idx & 31);
+      // of key c: bf16 pairs (d0, d0+1) in v[2(4e+c)] and (d0+2, d0+3) in v[2(4e+c)+1]; columns d0..d0+3 live in
+      // rows (d0/4) + 32*{0,1,2,3}: consecutive lanes write consecutive rows
+      const uint32_t *lo = &r.v[8 * e], *hi = &r.v[8 * e + 1];  // stride 2 between keys
+      uint8_t *dst = vt + (d0 >> 2) * kVRow + vt_pos(kq) * 2;
+      *(u32x2 *)(dst) = u32x2{__builtin_amdgcn_perm(lo[2], lo[0], 0x05040100u),
+                              __builtin_amdgcn_perm(lo[6], lo[4], 0x05040100u)};
+      *(u32x2 *)(dst + 32 * kVRow) = u32x2{__builtin_amdgcn_perm(lo[2], lo[0], 0x07060302u),
+                                           __builtin_amdgcn_perm(lo[6], lo[4], 0x07060302u)};
+      *(u32x2 *)(dst + 64 * kVRow) = u32x2{__builtin_amdgcn_perm(hi[2], hi[0], 0x05040100u),
+                                           __builtin_amdgcn_perm(hi[6], hi[4], 0x05040100u)};
+      *(u32x2 *)(dst + 96 * kVRow) = u32x2{__builtin_amdgcn_perm(hi[2], hi[0], 0x07060302u),
+                                           __builtin_amdgcn_perm(hi[6], hi[4], 0x07060302u)};
     }
   } else {
 #pragma unroll
