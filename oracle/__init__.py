@@ -54,6 +54,7 @@ def _load():
         _lib.lao_warp_probs.restype = ctypes.c_int
         _lib.lao_widen.restype = ctypes.c_int
         _lib.lao_kv_commit.restype = ctypes.c_int
+        _lib.lao_kv_commit_tree.restype = ctypes.c_int
         _lib.lao_quantize_fp8_e4m3.restype = ctypes.c_int
         _lib.lao_num_threads.restype = ctypes.c_int
     return _lib
@@ -209,13 +210,9 @@ def attention_row_weights(q, k_cache, v_cache, block_tables, prefix_lens, k_bran
     return w
 
 
-def kv_commit(k_cache, v_cache, block_tables, prefix_lens, k_branch, v_branch, k_chain, v_chain, src_branch, n_chain,
-              n_own, k_scale=None, v_scale=None, *, kv_dtype, branch_kv_dtype, block_size):
-    """Append, per request, the first ``n_chain[b]`` tokens of the drafted chain and then the first ``n_own[b]``
-    tokens of branch ``src_branch[b]`` behind the prefix (Algorithm 1, once j* is known).
-
-    Returns ``(k_cache, v_cache, new_prefix_lens)``: updated *copies* of the caches (storage bit patterns) and the
-    grown prefix lengths.  ``k_chain`` may be ``None`` (no chain: ``n_chain`` must be all zero)."""
+def _commit_operands(k_cache, v_cache, block_tables, prefix_lens, k_branch, v_branch, k_drafted, v_drafted, k_scale,
+                     v_scale, kv_dtype, branch_kv_dtype, block_size):
+    """Argument marshalling shared by the two commit wrappers (no arithmetic)."""
     kc = _storage(k_cache, kv_dtype, "k_cache").copy()
     vc = _storage(v_cache, kv_dtype, "v_cache").copy()
     kb = _storage(k_branch, branch_kv_dtype, "k_branch")
@@ -231,28 +228,64 @@ def kv_commit(k_cache, v_cache, block_tables, prefix_lens, k_branch, v_branch, k
         max_blocks = kc.shape[0] // B
     if kc.shape[1:] != (Hkv, block_size, D) or vc.shape != kc.shape:
         raise ValueError("cache must be [num_blocks, Hkv, block_size, D]")
-    if k_chain is None:
-        C, kch, vch = 0, None, None
+    if k_drafted is None:
+        C, kd, vd = 0, None, None
     else:
-        kch = _storage(k_chain, branch_kv_dtype, "k_chain")
-        vch = _storage(v_chain, branch_kv_dtype, "v_chain")
-        C = kch.shape[1]
-        if kch.shape != (B, C, Hkv, D) or vch.shape != kch.shape:
-            raise ValueError("k_chain/v_chain must be [B, C, Hkv, D]")
+        kd = _storage(k_drafted, branch_kv_dtype, "k_chain")
+        vd = _storage(v_drafted, branch_kv_dtype, "v_chain")
+        C = kd.shape[1]
+        if kd.shape != (B, C, Hkv, D) or vd.shape != kd.shape:
+            raise ValueError("drafted K/V must be [B, C, Hkv, D]")
+    ks = None if k_scale is None else np.ascontiguousarray(k_scale, dtype=np.float32)
+    vs = None if v_scale is None else np.ascontiguousarray(v_scale, dtype=np.float32)
+    shape = [ctypes.c_int(x) for x in (B, gamma, L, Hkv, D, block_size, max_blocks, DTYPE_CODES[kv_dtype],
+                                       DTYPE_CODES[branch_kv_dtype])]
+    return shape, kc, vc, block_tables, lens, kb, vb, C, kd, vd, ks, vs
+
+
+def kv_commit(k_cache, v_cache, block_tables, prefix_lens, k_branch, v_branch, k_chain, v_chain, src_branch, n_chain,
+              n_own, k_scale=None, v_scale=None, *, kv_dtype, branch_kv_dtype, block_size):
+    """Append, per request, the first ``n_chain[b]`` tokens of the drafted chain and then the first ``n_own[b]``
+    tokens of branch ``src_branch[b]`` behind the prefix (Algorithm 1, once j* is known).
+
+    Returns ``(k_cache, v_cache, new_prefix_lens)``: updated *copies* of the caches (storage bit patterns) and the
+    grown prefix lengths.  ``k_chain`` may be ``None`` (no chain: ``n_chain`` must be all zero)."""
+    shape, kc, vc, tables, lens, kb, vb, C, kch, vch, ks, vs = _commit_operands(
+        k_cache, v_cache, block_tables, prefix_lens, k_branch, v_branch, k_chain, v_chain, k_scale, v_scale, kv_dtype,
+        branch_kv_dtype, block_size)
     sb = np.ascontiguousarray(src_branch, dtype=np.int32)
     nc = np.ascontiguousarray(n_chain, dtype=np.int32)
     no = np.ascontiguousarray(n_own, dtype=np.int32)
-    ks = None if k_scale is None else np.ascontiguousarray(k_scale, dtype=np.float32)
-    vs = None if v_scale is None else np.ascontiguousarray(v_scale, dtype=np.float32)
-    new_lens = np.empty((B,), dtype=np.int32)
-    rc = _load().lao_kv_commit(ctypes.c_int(B), ctypes.c_int(gamma), ctypes.c_int(L), ctypes.c_int(Hkv),
-                               ctypes.c_int(D), ctypes.c_int(block_size), ctypes.c_int(max_blocks),
-                               ctypes.c_int(DTYPE_CODES[kv_dtype]), ctypes.c_int(DTYPE_CODES[branch_kv_dtype]),
-                               _ptr(kc), _ptr(vc), _ptr(block_tables), _ptr(lens), _ptr(kb), _ptr(vb),
+    new_lens = np.empty(lens.shape, dtype=np.int32)
+    rc = _load().lao_kv_commit(*shape, _ptr(kc), _ptr(vc), _ptr(tables), _ptr(lens), _ptr(kb), _ptr(vb),
                                ctypes.c_int(C), _ptr(kch), _ptr(vch), _ptr(sb), _ptr(nc), _ptr(no), _ptr(ks),
                                _ptr(vs), _ptr(new_lens))
     if rc:
         raise ValueError(f"lao_kv_commit rejected its arguments (status {rc})")
+    return kc, vc, new_lens
+
+
+def kv_commit_tree(k_cache, v_cache, block_tables, prefix_lens, k_branch, v_branch, k_pool, v_pool, pool_seg,
+                   commit_mask, src_branch, n_own, k_scale=None, v_scale=None, *, kv_dtype, branch_kv_dtype,
+                   block_size):
+    """Tree form of :func:`kv_commit` (Section 3.1, "Multi-Branch Drafting"): the pool tokens whose node
+    (``pool_seg[b][c]``) has its bit set in ``commit_mask[b]`` are appended in pool order, then the first
+    ``n_own[b]`` tokens of branch ``src_branch[b]``."""
+    shape, kc, vc, tables, lens, kb, vb, C, kp, vp, ks, vs = _commit_operands(
+        k_cache, v_cache, block_tables, prefix_lens, k_branch, v_branch, k_pool, v_pool, k_scale, v_scale, kv_dtype,
+        branch_kv_dtype, block_size)
+    seg = None if pool_seg is None else np.ascontiguousarray(pool_seg, dtype=np.int32)
+    if C and (seg is None or seg.shape != (lens.shape[0], C)):
+        raise ValueError("pool_seg must be [B, C]")
+    cm = np.ascontiguousarray(commit_mask, dtype=np.uint64)
+    sb = np.ascontiguousarray(src_branch, dtype=np.int32)
+    no = np.ascontiguousarray(n_own, dtype=np.int32)
+    new_lens = np.empty(lens.shape, dtype=np.int32)
+    rc = _load().lao_kv_commit_tree(*shape, _ptr(kc), _ptr(vc), _ptr(tables), _ptr(lens), _ptr(kb), _ptr(vb),
+                                    ctypes.c_int(C), _ptr(kp), _ptr(vp), _ptr(seg), _ptr(cm), _ptr(sb), _ptr(no),
+                                    _ptr(ks), _ptr(vs), _ptr(new_lens))
+    if rc:
+        raise ValueError(f"lao_kv_commit_tree rejected its arguments (status {rc})")
     return kc, vc, new_lens
 
 

@@ -638,6 +638,37 @@ static int commit_row(const void *src, int src_dtype, int64_t src_idx, void *dst
 /* k_cache / v_cache are updated in place.  src_branch [B] in 0..gamma-1, n_chain [B] in 0..C, n_own [B] in 0..L.
  * new_prefix_lens [B] receives prefix_lens + n_chain + n_own.  The block table must already map every position
  * that is written. */
+/* One request's appended sequence, shared by the chain and the tree form: `n_drafted` drafted tokens (their row
+ * numbers inside the request's chain / pool are drafted[0..n_drafted)), then own tokens 0..n_own-1 of src_branch. */
+static int commit_request(int b, int gamma, int L, int Hkv, int D, int block_size, int max_blocks, int kv_dtype,
+                          int br_dtype, void *k_cache, void *v_cache, const int32_t *block_tables, int pos,
+                          const void *k_branch, const void *v_branch, int C, const void *k_drafted,
+                          const void *v_drafted, const int *drafted, int n_drafted, int src_branch, int n_own,
+                          const float *k_scale, const float *v_scale) {
+  for (int t = 0; t < n_drafted + n_own; ++t, ++pos) {
+    const int from_drafted = t < n_drafted;
+    const int64_t logical_block = pos / block_size;
+    const int64_t phys = block_tables ? (int64_t)block_tables[(int64_t)b * max_blocks + logical_block]
+                                      : (int64_t)b * max_blocks + logical_block;
+    for (int hk = 0; hk < Hkv; ++hk) {
+      const int64_t dst = ((phys * Hkv + hk) * block_size + (pos % block_size)) * D;
+      int64_t src;
+      const void *ks, *vs;
+      if (from_drafted) {
+        src = (((int64_t)b * C + drafted[t]) * Hkv + hk) * D;
+        ks = k_drafted, vs = v_drafted;
+      } else {
+        const int i = t - n_drafted;
+        src = ((((int64_t)b * gamma + src_branch) * L + i) * Hkv + hk) * D;
+        ks = k_branch, vs = v_branch;
+      }
+      if (commit_row(ks, br_dtype, src, k_cache, kv_dtype, dst, D, k_scale, hk)) return 2;
+      if (commit_row(vs, br_dtype, src, v_cache, kv_dtype, dst, D, v_scale, hk)) return 2;
+    }
+  }
+  return 0;
+}
+
 int lao_kv_commit(int B, int gamma, int L, int Hkv, int D, int block_size, int max_blocks, int kv_dtype, int br_dtype,
                   void *k_cache, void *v_cache, const int32_t *block_tables, const int32_t *prefix_lens,
                   const void *k_branch, const void *v_branch, int C, const void *k_chain, const void *v_chain,
@@ -654,32 +685,56 @@ int lao_kv_commit(int B, int gamma, int L, int Hkv, int D, int block_size, int m
       return 1;
     if ((int64_t)prefix_lens[b] + n_chain[b] + n_own[b] > (int64_t)max_blocks * block_size) return 1;
   }
-  for (int b = 0; b < B; ++b) {
-    int pos = prefix_lens[b]; /* next free position of the request */
-    for (int t = 0; t < n_chain[b] + n_own[b]; ++t, ++pos) {
-      const int from_chain = t < n_chain[b];
-      const int64_t logical_block = pos / block_size;
-      const int64_t phys = block_tables ? (int64_t)block_tables[(int64_t)b * max_blocks + logical_block]
-                                        : (int64_t)b * max_blocks + logical_block;
-      for (int hk = 0; hk < Hkv; ++hk) {
-        const int64_t dst = ((phys * Hkv + hk) * block_size + (pos % block_size)) * D;
-        int64_t src;
-        const void *ks, *vs;
-        if (from_chain) {
-          src = (((int64_t)b * C + t) * Hkv + hk) * D;
-          ks = k_chain, vs = v_chain;
-        } else {
-          const int i = t - n_chain[b];
-          src = ((((int64_t)b * gamma + src_branch[b]) * L + i) * Hkv + hk) * D;
-          ks = k_branch, vs = v_branch;
-        }
-        if (commit_row(ks, br_dtype, src, k_cache, kv_dtype, dst, D, k_scale, hk)) return 2;
-        if (commit_row(vs, br_dtype, src, v_cache, kv_dtype, dst, D, v_scale, hk)) return 2;
-      }
-    }
-    new_prefix_lens[b] = pos;
+  int *rows = (int *)malloc(sizeof(int) * (size_t)(C > 0 ? C : 1));
+  if (!rows) return 3;
+  for (int c = 0; c < C; ++c) rows[c] = c; /* the accepted part of a chain is its first n_chain tokens */
+  int rc = 0;
+  for (int b = 0; b < B && !rc; ++b) {
+    rc = commit_request(b, gamma, L, Hkv, D, block_size, max_blocks, kv_dtype, br_dtype, k_cache, v_cache,
+                        block_tables, prefix_lens[b], k_branch, v_branch, C, k_chain, v_chain, rows, n_chain[b],
+                        src_branch[b], n_own[b], k_scale, v_scale);
+    new_prefix_lens[b] = prefix_lens[b] + n_chain[b] + n_own[b];
   }
-  return 0;
+  free(rows);
+  return rc;
+}
+
+/* Tree form (Section 3.1, "Multi-Branch Drafting": of the alternatives drafted for a position the accepted one is
+ * kept, the others are discarded).  The drafted tokens of all tree nodes lie in one pool [B, C, Hkv, D]; pool token c
+ * belongs to node pool_seg[b][c] in 0..63.  commit_mask[b] has the bits of the accepted nodes (the path the verifier
+ * walked); their tokens are appended in pool order, then own tokens 0..n_own-1 of src_branch. */
+int lao_kv_commit_tree(int B, int gamma, int L, int Hkv, int D, int block_size, int max_blocks, int kv_dtype,
+                       int br_dtype, void *k_cache, void *v_cache, const int32_t *block_tables,
+                       const int32_t *prefix_lens, const void *k_branch, const void *v_branch, int C,
+                       const void *k_pool, const void *v_pool, const int32_t *pool_seg, const uint64_t *commit_mask,
+                       const int32_t *src_branch, const int32_t *n_own, const float *k_scale, const float *v_scale,
+                       int32_t *new_prefix_lens) {
+  if (B < 1 || gamma < 1 || L < 1 || Hkv < 1 || D < 1 || block_size < 1 || C < 0) return 1;
+  if (!k_cache || !v_cache || !prefix_lens || !k_branch || !v_branch || !src_branch || !commit_mask || !n_own ||
+      !new_prefix_lens)
+    return 1;
+  if (C > 0 && (!k_pool || !v_pool || !pool_seg)) return 1;
+  for (int64_t i = 0; i < (int64_t)B * C; ++i)
+    if (pool_seg[i] < 0 || pool_seg[i] > 63) return 1;
+  int *rows = (int *)malloc(sizeof(int) * (size_t)(C > 0 ? C : 1));
+  if (!rows) return 3;
+  int rc = 0;
+  for (int b = 0; b < B && !rc; ++b) {
+    int kept = 0;
+    for (int c = 0; c < C; ++c)
+      if ((commit_mask[b] >> pool_seg[(int64_t)b * C + c]) & 1u) rows[kept++] = c;
+    if (src_branch[b] < 0 || src_branch[b] >= gamma || n_own[b] < 0 || n_own[b] > L ||
+        (int64_t)prefix_lens[b] + kept + n_own[b] > (int64_t)max_blocks * block_size) {
+      rc = 1;
+      break;
+    }
+    rc = commit_request(b, gamma, L, Hkv, D, block_size, max_blocks, kv_dtype, br_dtype, k_cache, v_cache,
+                        block_tables, prefix_lens[b], k_branch, v_branch, C, k_pool, v_pool, rows, kept,
+                        src_branch[b], n_own[b], k_scale, v_scale);
+    new_prefix_lens[b] = prefix_lens[b] + kept + n_own[b];
+  }
+  free(rows);
+  return rc;
 }
 
 /* Test hook: the quantiser alone, n fp32 values divided by `scale`. */

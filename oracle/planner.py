@@ -6,6 +6,10 @@ Everything is written from the *process* the paper describes, not from its close
 
 * Algorithm 1, verification and output construction: ``j*`` is the first draft step the verifier rejects (or the
   number of drafts when none is), the output is the accepted drafts followed by the target's step ``j*``.
+* Section 3.1, "Multi-Branch Drafting": several alternative drafts per position; the target's step for a position is
+  checked against every alternative drafted behind the accepted path, one that matches is kept and the walk goes on
+  below it, the others are discarded.  Which of several matching alternatives is kept the paper does not say: the
+  one drafted first (smallest node number).
 * Section 3.2 / Appendix B, step-level speedups.  ``X`` = number of consecutively accepted drafts,
   ``P(X = n) = alpha^n (1 - alpha)``.
     - sync, ``k`` target steps in parallel (so ``k - 1`` drafts, generated one after the other): a cycle costs
@@ -42,6 +46,26 @@ def output_construction(verdicts: Sequence[Sequence[bool]], chain_vis: Sequence[
     for v, vis, own in zip(verdicts, chain_vis, own_len):
         j = first_rejection(v)
         out.append((j, j, int(vis[j]), int(own[j])))
+    return out
+
+
+def tree_output_construction(parent: Sequence[int], verdicts: Sequence[Sequence[bool]],
+                             own_len: Sequence[Sequence[int]]) -> List[Tuple[int, int, int, int]]:
+    """Draft tree: node n hangs below node ``parent[n]`` (-1 = directly below the accepted text).  Branch 0 is the
+    target's step after the bare prefix, branch 1 + n its step after the path ending in node n; ``verdicts[b][n]``
+    says whether draft n matched the target's step of branch ``1 + parent[n]``.  Per request:
+    (accepted depth, surviving branch, bit set of the accepted nodes, own tokens kept)."""
+    out = []
+    for v, own in zip(verdicts, own_len):
+        here, accepted = -1, []
+        while True:
+            alternatives = [n for n in range(len(parent)) if parent[n] == here]
+            matching = [n for n in alternatives if v[n]]
+            if not matching:
+                break
+            here = min(matching)
+            accepted.append(here)
+        out.append((len(accepted), here + 1, sum(1 << n for n in accepted), int(own[here + 1])))
     return out
 
 

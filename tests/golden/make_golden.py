@@ -70,6 +70,18 @@ def compute():
                               "v_bytes_sum": int(vc.astype(np.int64).sum()),
                               "k_token_21_head_0": kc[1, 0, 21 - 16].tolist(),   # first appended token of request 0
                               "v_token_5_head_1_req_1": vc[cc.max_blocks, 1, 5].tolist()}
+    tree = W.make_tree_inputs(cc, 2, 2, 2, inp)                                      # 6 nodes of 2 tokens
+    kc, vc, new_lens = oracle.kv_commit_tree(inp["k_cache"], inp["v_cache"], None, inp["prefix_lens"], inp["k_branch"],
+                                             inp["v_branch"], tree["k_pool"], tree["v_pool"], tree["pool_seg"],
+                                             [0b100010, 0b000001], [1, 0], [5, 3], inp["k_scale"], inp["v_scale"],
+                                             kv_dtype="fp8_e4m3", branch_kv_dtype="bf16", block_size=cc.block_size)
+    out["commit"][cc.name + "_tree"] = {"new_lens": new_lens.tolist(), "k_bytes_sum": int(kc.astype(np.int64).sum()),
+                                        "v_bytes_sum": int(vc.astype(np.int64).sum()),
+                                        "k_token_23_head_0": kc[1, 0, 23 - 16].tolist()}   # first token of node 5
+    walks = planner.tree_output_construction([-1, -1, 0, 0, 1, 1], [[0, 1, 1, 1, 0, 1], [1, 1, 0, 0, 1, 1]],
+                                             [[3, 4, 5, 6, 7, 8, 9]] * 2)
+    out["planner"]["tree_walk"] = {k: [w[i] for w in walks]
+                                   for i, k in enumerate(("depth", "src_branch", "commit_mask", "n_own"))}
     # controller / planner (Section 3.2, 3.3): the parameters of the theorem's range and one outside it
     for name, (a1, c1, a2, c2, m, asyn) in {"hybrid_async": (0.7, 0.2, 0.65, 0.1, 16, True),
                                             "hybrid_sync": (0.7, 0.2, 0.65, 0.1, 16, False),

@@ -183,3 +183,113 @@ def test_commit_into_an_fp8_cache_from_bf16_branches(oracle):
             deq = oracle.widen(want, "fp8_e4m3") * scale[None, :, None]
             step = np.maximum(np.abs(src) * 2.0 ** -4, scale[None, :, None] * 2.0 ** -10)   # half a step, or subnormal
             assert (np.abs(deq - src) <= step).all()
+
+
+# ------------------------------------------------------------------------------------------ draft trees
+
+def commit_tree(oracle, case, inp, tree, commit_mask, src, nown):
+    return oracle.kv_commit_tree(inp["k_cache"], inp["v_cache"], inp["block_tables"], inp["prefix_lens"],
+                                 inp["k_branch"], inp["v_branch"], tree["k_pool"], tree["v_pool"], tree["pool_seg"],
+                                 commit_mask, src, nown, inp["k_scale"], inp["v_scale"], kv_dtype=case.kv_dtype,
+                                 branch_kv_dtype=case.branch_kv_dtype, block_size=case.block_size)
+
+
+def ragged_tree(case, inp, seed):
+    """make_tree_inputs' pool (width 2, depth 2: 6 nodes of 4 tokens) with the node labels shuffled per request, so
+    that nodes are interleaved in the pool, differ between requests, and some labels are large."""
+    tree = W.make_tree_inputs(case, 2, 2, 4, inp)
+    rng = np.random.default_rng(seed)
+    seg = tree["pool_seg"].copy()
+    for b in range(case.B):
+        rng.shuffle(seg[b])
+        seg[b] = np.where(seg[b] == 5, 63, seg[b])
+    return dict(tree, pool_seg=seg)
+
+
+TREE_CASES = [c for c, _ in CASES]
+
+
+@pytest.mark.parametrize("case", TREE_CASES, ids=lambda c: c.name)
+def test_attention_over_the_tree_committed_cache_equals_the_tree_row_that_saw_the_same_tokens(oracle, case):
+    """As for the chain: a branch of the tree problem whose seg_mask is the committed set sees
+    prefix ++ (kept pool tokens, pool order) ++ own[0..n_own]; after the commit a one-token branch sees the same
+    sequence through the cache.  Any subset of nodes is tried, not only root paths."""
+    inp = W.make_attention_inputs(case)
+    tree = ragged_tree(case, inp, case.seed)
+    rng = np.random.default_rng(case.seed + 100)
+    b_idx = np.arange(case.B)
+    for trial in range(4):
+        src = rng.integers(0, case.gamma, size=case.B)
+        nown = rng.integers(0, case.L, size=case.B)
+        cm = rng.integers(0, 64, size=case.B).astype(np.uint64)            # bits of nodes 0..4 and of node 5 (as 63)
+        cm = np.where(cm & np.uint64(32), (cm & np.uint64(31)) | np.uint64(1 << 63), cm).astype(np.uint64)
+        if trial == 0:
+            cm[:] = 0                                                      # nothing accepted
+        masks = tree["seg_mask"].copy()
+        masks[b_idx, src] = cm
+        ref, ref_lse = oracle.verify_attention(**inp, **dict(tree, seg_mask=masks), **attn_kwargs(case))
+        kc, vc, new_lens = commit_tree(oracle, case, inp, tree, cm, src, nown)
+        kept = np.array([sum(int(cm[b]) >> int(s) & 1 for s in tree["pool_seg"][b]) for b in range(case.B)])
+        assert np.array_equal(new_lens, inp["prefix_lens"] + kept + nown)
+        after = dict(inp, k_cache=kc, v_cache=vc, prefix_lens=new_lens,
+                     q=inp["q"][b_idx, src, nown][:, None, None],
+                     k_branch=inp["k_branch"][b_idx, src, nown][:, None, None],
+                     v_branch=inp["v_branch"][b_idx, src, nown][:, None, None])
+        got, got_lse = oracle.verify_attention(**after, **attn_kwargs(case))
+        for b in range(case.B):
+            assert np.array_equal(got[b, 0, 0], ref[b, src[b], nown[b]]), (trial, b)
+            assert np.array_equal(got_lse[b, 0, 0], ref_lse[b, src[b], nown[b]])
+
+
+@pytest.mark.parametrize("case", TREE_CASES, ids=lambda c: c.name)
+def test_tree_commit_changes_only_the_appended_positions(oracle, case):
+    inp = W.make_attention_inputs(case)
+    tree = ragged_tree(case, inp, case.seed + 1)
+    cm = np.full(case.B, 0b10110, dtype=np.uint64)
+    src = np.arange(case.B) % case.gamma
+    nown = np.full(case.B, case.L)
+    kc, vc, new_lens = commit_tree(oracle, case, inp, tree, cm, src, nown)
+    assert np.array_equal(new_lens, inp["prefix_lens"] + 3 * 4 + case.L)     # three nodes of four tokens
+    changed = np.zeros(inp["k_cache"].shape[:1] + inp["k_cache"].shape[2:3], dtype=bool)
+    bs = case.block_size
+    for b in range(case.B):
+        for pos in range(int(inp["prefix_lens"][b]), int(new_lens[b])):
+            blk = inp["block_tables"][b, pos // bs] if inp["block_tables"] is not None else b * case.max_blocks + pos // bs
+            changed[blk, pos % bs] = True
+    for new, old in ((kc, inp["k_cache"]), (vc, inp["v_cache"])):
+        same = (new == old).all(axis=(1, 3))
+        assert same[~changed].all() and not same[changed].any()
+
+
+def test_tree_commit_of_a_chain_shaped_pool_is_the_chain_commit(oracle):
+    """Nodes stored one after the other, the first j accepted: the kept tokens are the chain's first tokens."""
+    case, _ = CASES[1]
+    inp = W.make_attention_inputs(case)
+    tree = W.make_tree_inputs(case, 1, 5, 6, inp)                            # 5 steps of 6 tokens
+    chain = {"k_chain": tree["k_pool"], "v_chain": tree["v_pool"]}
+    for accepted in ([0, 0], [3, 5], [5, 1]):
+        acc = np.array(accepted)
+        src, nown = np.array([1, 3]), np.array([case.L, 2])
+        cm = ((1 << acc) - 1).astype(np.uint64)
+        a = commit_tree(oracle, case, inp, tree, cm, src, nown)
+        b = commit(oracle, case, inp, chain, W.make_commit_inputs(case, 30, (src, acc * 6, nown)))
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+
+
+def test_tree_commit_rejects_what_does_not_fit(oracle):
+    case, _ = CASES[1]
+    inp = W.make_attention_inputs(case)
+    tree = W.make_tree_inputs(case, 2, 2, 4, inp)
+    zeros, full = np.zeros(case.B, dtype=np.int32), np.full(case.B, 63, dtype=np.uint64)
+    commit_tree(oracle, case, inp, tree, full, zeros, zeros + case.L)
+    with pytest.raises(ValueError):
+        commit_tree(oracle, case, inp, dict(tree, pool_seg=tree["pool_seg"] + 60), full, zeros, zeros)
+    with pytest.raises(ValueError):
+        commit_tree(oracle, case, inp, tree, full, zeros + case.gamma, zeros)
+    with pytest.raises(ValueError):
+        commit_tree(oracle, case, inp, tree, full, zeros, zeros + case.L + 1)
+    tight = replace(case, spare_tokens=10)                                   # 24 pool tokens do not fit
+    inp = W.make_attention_inputs(tight)
+    with pytest.raises(ValueError):
+        commit_tree(oracle, tight, inp, W.make_tree_inputs(tight, 2, 2, 4, inp), full, zeros, zeros)

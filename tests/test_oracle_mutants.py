@@ -67,24 +67,40 @@ MUTANTS = {
 
 # KV commit: checked by its own pin file only
 COMMIT_MUTANTS = {
-    "commit_position_off_by_one": ("    int pos = prefix_lens[b]; /* next free position of the request */",
-                                   "    int pos = prefix_lens[b] + 1;"),
-    "commit_own_before_chain": ("      const int from_chain = t < n_chain[b];",
-                                "      const int from_chain = t >= n_own[b];"),
-    "commit_own_index_not_rebased": ("          const int i = t - n_chain[b];", "          const int i = t;"),
-    "commit_wrong_branch": ("src = ((((int64_t)b * gamma + src_branch[b]) * L + i) * Hkv + hk) * D;",
+    "commit_position_off_by_one": ("block_tables, prefix_lens[b], k_branch, v_branch, C, k_chain, v_chain, rows, n_chain[b],",
+                                   "block_tables, prefix_lens[b] + 1, k_branch, v_branch, C, k_chain, v_chain, rows, n_chain[b],"),
+    "commit_own_before_chain": ("    const int from_drafted = t < n_drafted;",
+                                "    const int from_drafted = t >= n_own;"),
+    "commit_own_index_not_rebased": ("        const int i = t - n_drafted;", "        const int i = t;"),
+    "commit_wrong_branch": ("src = ((((int64_t)b * gamma + src_branch) * L + i) * Hkv + hk) * D;",
                             "src = ((((int64_t)b * gamma + 0) * L + i) * Hkv + hk) * D;"),
-    "commit_chain_of_wrong_request": ("          src = (((int64_t)b * C + t) * Hkv + hk) * D;",
-                                      "          src = (((int64_t)0 * C + t) * Hkv + hk) * D;"),
-    "commit_block_table_ignored": ("      const int64_t phys = block_tables ? (int64_t)block_tables[(int64_t)b * max_blocks + logical_block]",
-                                   "      const int64_t phys = 0 ? (int64_t)block_tables[(int64_t)b * max_blocks + logical_block]"),
+    "commit_chain_of_wrong_request": ("        src = (((int64_t)b * C + drafted[t]) * Hkv + hk) * D;",
+                                      "        src = (((int64_t)0 * C + drafted[t]) * Hkv + hk) * D;"),
+    "commit_chain_reversed": ("  for (int c = 0; c < C; ++c) rows[c] = c;", "  for (int c = 0; c < C; ++c) rows[c] = C - 1 - c;"),
+    "commit_block_table_ignored": ("    const int64_t phys = block_tables ? (int64_t)block_tables[(int64_t)b * max_blocks + logical_block]",
+                                   "    const int64_t phys = 0 ? (int64_t)block_tables[(int64_t)b * max_blocks + logical_block]"),
     "commit_slot_in_block": ("const int64_t dst = ((phys * Hkv + hk) * block_size + (pos % block_size)) * D;",
                              "const int64_t dst = ((phys * Hkv + hk) * block_size + (t % block_size)) * D;"),
     "commit_v_from_k": ("if (commit_row(vs, br_dtype, src, v_cache, kv_dtype, dst, D, v_scale, hk)) return 2;",
                         "if (commit_row(ks, br_dtype, src, v_cache, kv_dtype, dst, D, v_scale, hk)) return 2;"),
     "commit_k_scale_on_v": ("if (commit_row(vs, br_dtype, src, v_cache, kv_dtype, dst, D, v_scale, hk)) return 2;",
                             "if (commit_row(vs, br_dtype, src, v_cache, kv_dtype, dst, D, k_scale, hk)) return 2;"),
-    "commit_new_len_without_chain": ("    new_prefix_lens[b] = pos;", "    new_prefix_lens[b] = prefix_lens[b] + n_own[b];"),
+    "commit_new_len_without_chain": ("    new_prefix_lens[b] = prefix_lens[b] + n_chain[b] + n_own[b];",
+                                     "    new_prefix_lens[b] = prefix_lens[b] + n_own[b];"),
+    "tree_commit_keeps_the_discarded": ("      if ((commit_mask[b] >> pool_seg[(int64_t)b * C + c]) & 1u) rows[kept++] = c;",
+                                        "      if (1) rows[kept++] = c;"),
+    "tree_commit_keeps_the_complement": ("      if ((commit_mask[b] >> pool_seg[(int64_t)b * C + c]) & 1u) rows[kept++] = c;",
+                                         "      if (!((commit_mask[b] >> pool_seg[(int64_t)b * C + c]) & 1u)) rows[kept++] = c;"),
+    "tree_commit_mask_of_request_0": ("      if ((commit_mask[b] >> pool_seg[(int64_t)b * C + c]) & 1u) rows[kept++] = c;",
+                                      "      if ((commit_mask[0] >> pool_seg[(int64_t)b * C + c]) & 1u) rows[kept++] = c;"),
+    "tree_commit_nodes_of_request_0": ("      if ((commit_mask[b] >> pool_seg[(int64_t)b * C + c]) & 1u) rows[kept++] = c;",
+                                       "      if ((commit_mask[b] >> pool_seg[(int64_t)0 * C + c]) & 1u) rows[kept++] = c;"),
+    "tree_commit_mask_truncated_to_32_bits": ("      if ((commit_mask[b] >> pool_seg[(int64_t)b * C + c]) & 1u) rows[kept++] = c;",
+                                              "      if (((uint32_t)commit_mask[b] >> (pool_seg[(int64_t)b * C + c] & 31)) & 1u) rows[kept++] = c;"),
+    "tree_commit_rows_not_the_kept_ones": ("      if ((commit_mask[b] >> pool_seg[(int64_t)b * C + c]) & 1u) rows[kept++] = c;",
+                                           "      if ((commit_mask[b] >> pool_seg[(int64_t)b * C + c]) & 1u) rows[kept] = kept, ++kept;"),
+    "tree_commit_new_len_without_pool": ("    new_prefix_lens[b] = prefix_lens[b] + kept + n_own[b];",
+                                         "    new_prefix_lens[b] = prefix_lens[b] + n_own[b];"),
     "quantiser_multiplies": ("      const float y = x / s; /* fp32 quotient, correctly rounded */",
                              "      const float y = x * s;"),
     "quantiser_scale_of_head_0": ("    const float s = scale ? scale[hk] : 1.0f;", "    const float s = scale ? scale[0] : 1.0f;"),
@@ -122,6 +138,17 @@ PLANNER_SRC = (ROOT / "oracle" / "planner.py").read_text()
 PLANNER_MUTANTS = {
     "first_rejection_returns_last": ("        if not ok:\n            return j\n", "        if not ok:\n            last = j\n"),
     "all_accepted_off_by_one": ("    return len(verdicts)\n", "    return len(verdicts) - 1\n"),
+    "tree_walk_takes_last_matching": ("            here = min(matching)\n", "            here = max(matching)\n"),
+    "tree_walk_stops_after_one_step": ("            here = min(matching)\n            accepted.append(here)\n",
+                                       "            here = min(matching)\n            accepted.append(here)\n            break\n"),
+    "tree_walk_looks_at_all_nodes": ("alternatives = [n for n in range(len(parent)) if parent[n] == here]",
+                                     "alternatives = [n for n in range(len(parent)) if parent[n] >= here]"),
+    "tree_walk_branch_of_parent": ("out.append((len(accepted), here + 1, sum(1 << n for n in accepted), int(own[here + 1])))",
+                                   "out.append((len(accepted), here, sum(1 << n for n in accepted), int(own[here + 1])))"),
+    "tree_walk_own_of_root": ("out.append((len(accepted), here + 1, sum(1 << n for n in accepted), int(own[here + 1])))",
+                              "out.append((len(accepted), here + 1, sum(1 << n for n in accepted), int(own[0])))"),
+    "tree_walk_mask_is_depth_bits": ("out.append((len(accepted), here + 1, sum(1 << n for n in accepted), int(own[here + 1])))",
+                                     "out.append((len(accepted), here + 1, (1 << len(accepted)) - 1, int(own[here + 1])))"),
     "output_keeps_own_of_next_branch": ("out.append((j, j, int(vis[j]), int(own[j])))",
                                         "out.append((j, j, int(vis[j]), int(own[min(j + 1, len(own) - 1)])))"),
     "output_chain_of_previous_branch": ("out.append((j, j, int(vis[j]), int(own[j])))",

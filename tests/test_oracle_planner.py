@@ -135,6 +135,86 @@ def test_output_construction_follows_the_accepted_prefix():
     assert P.output_construction([[False, True, True]], vis, own) == [(0, 0, 0, 6)]
 
 
+# ---- Section 3.1, multi-branch drafting: the walk over a draft tree ---------------------------------------------
+
+def full_tree(width, depth):
+    """Parents of a tree with ``width`` alternatives per position, stored level by level."""
+    par, level = [], [-1]
+    for _ in range(depth):
+        nxt = []
+        for p in level:
+            for _ in range(width):
+                nxt.append(len(par))
+                par.append(p)
+        level = nxt
+    return par
+
+
+def test_tree_walk_worked_example():
+    # position 0: drafts 0, 1;  below 0: drafts 2, 3;  below 1: drafts 4, 5.  own[j] = tokens of the target's step
+    # that continues the bare prefix (j = 0) or the path ending in node j - 1
+    par, own = [-1, -1, 0, 0, 1, 1], [[10, 11, 12, 13, 14, 15, 16]]
+    walk = lambda v: P.tree_output_construction(par, [v], own)[0]
+    assert walk([0, 0, 1, 1, 1, 1]) == (0, 0, 0, 10)                      # nothing at position 0 matched
+    assert walk([0, 1, 1, 1, 0, 0]) == (1, 2, 0b000010, 12)               # node 1, none of its children (4, 5)
+    assert walk([0, 1, 1, 1, 0, 1]) == (2, 6, 0b100010, 16)               # node 1 then node 5
+    assert walk([1, 1, 0, 1, 1, 1]) == (2, 4, 0b001001, 14)               # 0 and 1 both match: 0; then 3
+    assert walk([1, 0, 1, 1, 0, 0]) == (2, 3, 0b000101, 13)               # 2 and 3 both match: 2
+
+
+def test_a_tree_of_width_one_is_algorithm_1s_chain():
+    rng = np.random.default_rng(11)
+    for drafts in (0, 1, 4, 9):
+        par = list(range(-1, drafts - 1))
+        v = (rng.random((50, drafts)) < 0.7).tolist()
+        own = rng.integers(1, 30, size=(50, drafts + 1)).tolist()
+        vis = [list(range(drafts + 1))] * 50                          # one token per draft: vis = number accepted
+        chain = P.output_construction(v, vis, own)
+        tree = P.tree_output_construction(par, v, own)
+        for (j, src, nch, nown), (d, tsrc, mask, town) in zip(chain, tree):
+            assert (d, tsrc, town) == (j, src, nown)
+            assert mask == (1 << j) - 1 and nch == j
+
+
+@pytest.mark.parametrize("width,depth", [(2, 2), (3, 2), (2, 3)])
+def test_tree_walk_is_the_unique_greedy_path(width, depth):
+    """Stated without the walk: the accepted set is a path from the top (every member's parent is the previous
+    member), each member matched and no earlier sibling did, and nothing below the last member matched."""
+    par = full_tree(width, depth)
+    n = len(par)
+    rng = np.random.default_rng(width * 10 + depth)
+    for _ in range(300):
+        v = (rng.random(n) < 0.5).tolist()
+        d, src, mask, own = P.tree_output_construction(par, [v], [list(range(100, 101 + n))])[0]
+        members = [i for i in range(n) if mask >> i & 1]
+        assert len(members) == d and own == 100 + src
+        prev = -1
+        for m in members:
+            assert par[m] == prev and v[m]
+            assert not any(v[s] for s in range(m) if par[s] == prev)
+            prev = m
+        assert src == prev + 1
+        assert not any(v[c] for c in range(n) if par[c] == prev)
+
+
+@pytest.mark.parametrize("width,depth", [(1, 3), (2, 2), (3, 2), (2, 3)])
+def test_accepted_depth_under_independent_verdicts(width, depth):
+    """Every draft matching independently with probability a: a position succeeds when any of its ``width``
+    alternatives matches, so P(depth >= d) = (1 - (1 - a)^width)^d (the reason for drafting several alternatives).
+    Checked by summing over all verdict patterns."""
+    par = full_tree(width, depth)
+    n, a = len(par), 0.37
+    reach = [0.0] * (depth + 1)
+    for pattern in range(1 << n):
+        v = [(pattern >> i) & 1 for i in range(n)]
+        w = np.prod([a if x else 1 - a for x in v])
+        d = P.tree_output_construction(par, [v], [[1] * (n + 1)])[0][0]
+        for k in range(d + 1):
+            reach[k] += w
+    for d in range(depth + 1):
+        assert reach[d] == pytest.approx((1 - (1 - a) ** width) ** d, rel=1e-12)
+
+
 # ---- Section 3.3 -----------------------------------------------------------------------------------------------
 
 def test_plan_respects_the_budget_and_is_the_maximum():
