@@ -95,9 +95,11 @@ def bench_commit(args):
     sz = {"f32": 4, "bf16": 2, "fp8_e4m3": 1}
     tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch.float8_e4m3fn}
     results = {}
-    for label, br_dtype in (("same_dtype", base.branch_kv_dtype), ("quantising", "bf16")):
+    for label, br_dtype in (("same_dtype", base.branch_kv_dtype), ("quantising", "bf16"),
+                            ("tree_same_dtype", base.branch_kv_dtype)):
         if label == "quantising" and base.kv_dtype != "fp8_e4m3":
             continue
+        is_tree = label.startswith("tree")
         case = replace(base, branch_kv_dtype=br_dtype, spare_tokens=C + base.L)
         nb = case.B * case.max_blocks
         gen = torch.Generator(device=dev)
@@ -131,6 +133,20 @@ def bench_commit(args):
         nch = torch.full((case.B,), C, dtype=torch.int32, device=dev)
         nown = torch.full((case.B,), case.L, dtype=torch.int32, device=dev)
         new_lens = torch.zeros((case.B,), dtype=torch.int32, device=dev)
+        if is_tree:
+            # the chain tensors read as a draft tree: 2 alternatives per position, 3 positions (14 nodes), the pool
+            # cut into 14 equal steps; request b's accepted path ends in leaf 6 + b % 8
+            parent = W.tree_parents(2, 3)
+            seg_np = np.tile(np.minimum(np.arange(C) // max(1, C // 14), 13).astype(np.int32), (case.B, 1))
+            cm_np = np.zeros(case.B, dtype=np.uint64)
+            for b in range(case.B):
+                node = 6 + b % 8
+                while node >= 0:
+                    cm_np[b] |= np.uint64(1) << np.uint64(node)
+                    node = int(parent[node])
+            seg_d = torch.from_numpy(seg_np).to(dev)
+            cm_d = torch.from_numpy(cm_np.view(np.int64)).to(dev)
+            kept = int(sum(((int(cm_np[b]) >> seg_np[b]) & 1).sum() for b in range(case.B)))
         desc = B.make_attn_desc(num_requests=case.B, num_q_heads=case.Hq, num_kv_heads=case.Hkv, head_dim=case.D,
                                 gamma=case.gamma, branch_len=case.L, block_size=case.block_size,
                                 max_blocks_per_request=case.max_blocks, q_dtype=case.q_dtype, kv_dtype=case.kv_dtype,
@@ -145,8 +161,12 @@ def bench_commit(args):
         def step():
             t = sets[calls[0] % n_sets]
             calls[0] += 1
-            B.la_kv_commit(desc, t["kc"], t["vc"], None, d_lens, lens, t["kb"], t["vb"], t["kch"], t["vch"], src, nch,
-                           nown, ks, vs, new_lens, strides)
+            if is_tree:
+                B.la_kv_commit_tree(desc, t["kc"], t["vc"], None, d_lens, lens, t["kb"], t["vb"], t["kch"], t["vch"],
+                                    seg_d, cm_d, src, nown, ks, vs, new_lens, strides)
+            else:
+                B.la_kv_commit(desc, t["kc"], t["vc"], None, d_lens, lens, t["kb"], t["vb"], t["kch"], t["vch"], src,
+                               nch, nown, ks, vs, new_lens, strides)
 
         for _ in range(max(args.warmup, n_sets)):
             step()
@@ -162,7 +182,7 @@ def bench_commit(args):
         B.la_profile_enable(False)
         launches, ms = B.la_profile_collect()["kv_commit"]
         B.la_profile_reset()
-        tokens = case.B * (C + case.L)
+        tokens = kept + case.B * case.L if is_tree else case.B * (C + case.L)
         alg_bytes = 2.0 * tokens * case.Hkv * case.D * (sz[br_dtype] + sz[case.kv_dtype]) * n_layers
         avg_ms = ms / max(1, launches)
         res = {"avg_launch_ms": avg_ms, "wall_ms_per_call": (t1 - t0) * 1e3 / args.steps,
@@ -174,11 +194,12 @@ def bench_commit(args):
             t_cpu, ok = 0.0, True
             for l, (k0, v0) in before.items():
                 t0 = time.perf_counter()
-                rk, rv, rl = oracle.kv_commit(
+                decided = ((seg_np, cm_np, src.cpu().numpy(), nown.cpu().numpy()) if is_tree else
+                           (src.cpu().numpy(), nch.cpu().numpy(), nown.cpu().numpy()))
+                rk, rv, rl = (oracle.kv_commit_tree if is_tree else oracle.kv_commit)(
                     k0, v0, None, np.array(lens, dtype=np.int32), W.device_bits(kb[l], br_dtype),
                     W.device_bits(vb[l], br_dtype), W.device_bits(kch[l], br_dtype), W.device_bits(vch[l], br_dtype),
-                    src.cpu().numpy(), nch.cpu().numpy(), nown.cpu().numpy(),
-                    None if ks is None else ks[l].cpu().numpy(), None if vs is None else vs[l].cpu().numpy(),
+                    *decided, None if ks is None else ks[l].cpu().numpy(), None if vs is None else vs[l].cpu().numpy(),
                     kv_dtype=case.kv_dtype, branch_kv_dtype=br_dtype, block_size=case.block_size)
                 t_cpu += time.perf_counter() - t0
                 ok &= bool(np.array_equal(W.device_bits(kc[l], case.kv_dtype), rk))

@@ -222,6 +222,33 @@ LA_API la_status la_kv_commit(
     const la_layer_strides *layers,  /* host, or NULL                                              */
     void *hip_stream);
 
+/* la_kv_commit for a draft tree (Section 3.1, "Multi-Branch Drafting": of the
+ * alternatives drafted for a position the accepted one is kept, the others
+ * are discarded).  The drafted tokens lie in the pool of
+ * la_verify_attention_tree; commit_mask[b] has the bits of the accepted nodes
+ * (the path the verifier walked, see la_step_select_tree).  Per request the
+ * pool tokens whose node is in commit_mask[b] are appended in pool order, then
+ * the first n_own[b] tokens of branch src_branch[b];
+ * new_prefix_lens[b] = prefix_lens[b] + (kept pool tokens) + n_own[b].
+ * A pool_seg value outside 0..63 is never kept.  The block table must map
+ * room for prefix_lens_host[b] + pool_len + branch_len positions.  Everything
+ * else (storage pairs, layers, clamping, aliasing) is as in la_kv_commit;
+ * chain_stride is the pool's layer stride. */
+LA_API la_status la_kv_commit_tree(
+    const la_attn_desc *desc, void *k_cache, void *v_cache, const int32_t *block_tables,
+    const int32_t *prefix_lens, const int32_t *prefix_lens_host,
+    const void *k_branch, const void *v_branch,
+    const void *k_pool,              /* dev [B, pool_len, Hkv, D] per layer; NULL if pool_len 0    */
+    const void *v_pool,
+    int32_t pool_len,
+    const int32_t *pool_seg,         /* dev [B, pool_len]; NULL if pool_len 0                      */
+    const uint64_t *commit_mask,     /* dev [B]                                                     */
+    const int32_t *src_branch,       /* dev [B]                                                     */
+    const int32_t *n_own,            /* dev [B]                                                     */
+    const float *k_scale, const float *v_scale,
+    int32_t *new_prefix_lens,        /* dev [B], written                                           */
+    const la_layer_strides *layers, void *hip_stream);
+
 /* ------------------------------------------------------------------------- *
  *  la_spec_accept
  *
@@ -290,6 +317,21 @@ LA_API la_status la_spec_accept(
  *  src_branch / n_chain / n_own may be NULL; chain_vis / own_len may be NULL
  *  when the output they feed is.
  *
+ *  la_step_select_tree -- the same walk over a draft tree (Section 3.1,
+ *  "Multi-Branch Drafting").  The tree has num_nodes <= 64 drafted steps, the
+ *  same shape for every request: parent[n] in -1..n-1 (-1: a child of the
+ *  root, i.e. an alternative for position 0), parents before children.  The
+ *  target generates one step per tree prefix: branch 0 continues the bare
+ *  prefix, branch 1+n continues the path that ends in node n (num_nodes + 1
+ *  branches).  verdicts[b][n] != 0: the verifier accepted drafted step n as
+ *  equivalent to the target's step of branch 1+parent[n].  The walk starts at
+ *  the root and moves to an accepted child while there is one (several
+ *  accepted alternatives: the one with the smallest node number); depth = the
+ *  number of accepted steps, commit_mask = their node bits, src_branch = the
+ *  branch of the node where the walk ended, n_own = own_len[b][src_branch].
+ *  These are the arguments of la_kv_commit_tree.  A chain (parent[n] = n-1)
+ *  gives la_step_select's result.
+ *
  *  la_speedup_* -- closed forms, alpha in (0,1) the acceptance rate, c in
  *  (0,1) the draft's cost relative to the target, k >= 1 the depth:
  *    step level, sync  (Section 3.2):  (1-a^k) / ((1-a)(1-c+ck))
@@ -317,6 +359,13 @@ LA_API la_status la_step_select(int32_t num_requests, int32_t num_branches,
                                 const int32_t *own_len,    /* [B, num_branches]   */
                                 int32_t *j_star,           /* [B] out             */
                                 int32_t *src_branch, int32_t *n_chain, int32_t *n_own /* [B] out, optional */);
+LA_API la_status la_step_select_tree(int32_t num_requests, int32_t num_nodes,
+                                     const int32_t *parent,    /* [num_nodes]          */
+                                     const uint8_t *verdicts,  /* [B, num_nodes]       */
+                                     const int32_t *own_len,   /* [B, num_nodes + 1]   */
+                                     int32_t *depth,           /* [B] out              */
+                                     uint64_t *commit_mask,    /* [B] out              */
+                                     int32_t *src_branch, int32_t *n_own /* [B] out, optional */);
 LA_API la_status la_speedup_step_sync(double alpha1, double c1, int32_t k1, double *speedup);
 LA_API la_status la_speedup_step_async(double alpha1, double c1, int32_t k1, double *speedup);
 LA_API la_status la_speedup_token(double alpha2, double c2, int32_t k2, double *speedup);

@@ -25,6 +25,7 @@ _TORCH_DTYPES = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch
 
 EXPORTED_SYMBOLS = (
     "la_verify_attention_workspace", "la_verify_attention", "la_verify_attention_nested", "la_verify_attention_tree", "la_kv_commit",
+    "la_kv_commit_tree", "la_step_select_tree",
     "la_calibrate_mfma", "la_calibrate_read", "la_step_select", "la_speedup_step_sync", "la_speedup_step_async", "la_speedup_token", "la_plan_budget",
     "la_spec_accept_workspace",
     "la_spec_accept",
@@ -96,12 +97,18 @@ def load() -> ctypes.CDLL:
         lib.la_kv_commit.argtypes = [ctypes.POINTER(la_attn_desc), vp, vp, i32p, i32p, ctypes.POINTER(ctypes.c_int32),
                                      vp, vp, vp, vp, ctypes.c_int32, i32p, i32p, i32p, vp, vp, i32p,
                                      ctypes.POINTER(la_layer_strides), vp]
+        lib.la_kv_commit_tree.restype = ctypes.c_int
+        lib.la_kv_commit_tree.argtypes = [ctypes.POINTER(la_attn_desc), vp, vp, i32p, i32p,
+                                          ctypes.POINTER(ctypes.c_int32), vp, vp, vp, vp, ctypes.c_int32, i32p, vp,
+                                          i32p, i32p, vp, vp, i32p, ctypes.POINTER(la_layer_strides), vp]
         lib.la_calibrate_mfma.restype = ctypes.c_int
         lib.la_calibrate_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
         lib.la_calibrate_read.restype = ctypes.c_int
         lib.la_calibrate_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         lib.la_step_select.restype = ctypes.c_int
         lib.la_step_select.argtypes = [ctypes.c_int32, ctypes.c_int32] + [vp] * 7
+        lib.la_step_select_tree.restype = ctypes.c_int
+        lib.la_step_select_tree.argtypes = [ctypes.c_int32, ctypes.c_int32] + [vp] * 7
         for fn in (lib.la_speedup_step_sync, lib.la_speedup_step_async, lib.la_speedup_token):
             fn.restype = ctypes.c_int
             fn.argtypes = [ctypes.c_double, ctypes.c_double, ctypes.c_int32, ctypes.POINTER(ctypes.c_double)]
@@ -231,6 +238,21 @@ def la_kv_commit(desc: la_attn_desc, k_cache, v_cache, block_tables, prefix_lens
         raise LaError(st, "la_kv_commit")
 
 
+def la_kv_commit_tree(desc: la_attn_desc, k_cache, v_cache, block_tables, prefix_lens, prefix_lens_host, k_branch,
+                      v_branch, k_pool, v_pool, pool_seg, commit_mask, src_branch, n_own, k_scale, v_scale,
+                      new_prefix_lens, layers: Optional[la_layer_strides] = None) -> None:
+    """Tree form of :func:`la_kv_commit`: the pool tokens whose node bit is set in ``commit_mask`` (int64 tensor
+    holding the 64-bit masks) are appended in pool order, then ``n_own`` tokens of ``src_branch``."""
+    C = 0 if k_pool is None else int(k_pool.shape[-3])
+    st = load().la_kv_commit_tree(ctypes.byref(desc), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+                                  _ptr(prefix_lens), _host_lens(prefix_lens_host), _ptr(k_branch), _ptr(v_branch),
+                                  _ptr(k_pool), _ptr(v_pool), ctypes.c_int32(C), _ptr(pool_seg), _ptr(commit_mask),
+                                  _ptr(src_branch), _ptr(n_own), _ptr(k_scale), _ptr(v_scale), _ptr(new_prefix_lens),
+                                  ctypes.byref(layers) if layers is not None else None, _stream())
+    if st:
+        raise LaError(st, "la_kv_commit_tree")
+
+
 def la_calibrate_mfma(workgroups: int, iters: int, sink) -> float:
     """Enqueue the pure-MFMA calibration kernel; returns the launch's flop count."""
     if sink.numel() < workgroups * 512:
@@ -265,6 +287,27 @@ def la_step_select(verdicts, chain_vis, own_len):
     if st:
         raise LaError(st, "la_step_select")
     return tuple(outs)
+
+
+def la_step_select_tree(parent, verdicts, own_len):
+    """Host arrays: ``parent`` [nodes] (-1 = child of the root), ``verdicts`` [B, nodes] (truthy = accepted),
+    ``own_len`` [B, nodes + 1].  Returns ``(depth, commit_mask, src_branch, n_own)``: int32 [B], uint64 [B],
+    int32 [B], int32 [B]."""
+    import numpy as np
+    par = np.ascontiguousarray(parent, dtype=np.int32)
+    own = np.ascontiguousarray(own_len, dtype=np.int32)
+    nreq, nodes = own.shape[0], par.shape[0]
+    if own.shape[1] != nodes + 1:
+        raise ValueError("own_len must be [B, nodes + 1]")
+    v = np.ascontiguousarray(np.asarray(verdicts, dtype=bool).reshape(nreq, nodes), dtype=np.uint8)
+    depth, src, n_own = (np.empty(nreq, dtype=np.int32) for _ in range(3))
+    mask = np.empty(nreq, dtype=np.uint64)
+    st = load().la_step_select_tree(nreq, nodes, par.ctypes.data if nodes else None, v.ctypes.data if nodes else None,
+                                    own.ctypes.data, depth.ctypes.data, mask.ctypes.data, src.ctypes.data,
+                                    n_own.ctypes.data)
+    if st:
+        raise LaError(st, "la_step_select_tree")
+    return depth, mask, src, n_own
 
 
 def _speedup(fn_name: str, alpha: float, c: float, k: int) -> float:

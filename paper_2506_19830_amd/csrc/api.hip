@@ -334,19 +334,23 @@ la_status la_verify_attention_tree(const la_attn_desc *desc, const void *q, cons
                           out, lse, workspace, workspace_bytes, hip_stream);
 }
 
-la_status la_kv_commit(const la_attn_desc *desc, void *k_cache, void *v_cache, const int32_t *block_tables,
-                       const int32_t *prefix_lens, const int32_t *prefix_lens_host, const void *k_branch,
-                       const void *v_branch, const void *k_chain, const void *v_chain, int32_t chain_len,
-                       const int32_t *src_branch, const int32_t *n_chain, const int32_t *n_own, const float *k_scale,
-                       const float *v_scale, int32_t *new_prefix_lens, const la_layer_strides *layers,
-                       void *hip_stream) {
+// Shared by la_kv_commit (pool_seg == nullptr: the first n_chain tokens of the chain are kept) and
+// la_kv_commit_tree (the pool tokens whose node has its bit in commit_mask are kept; n_chain == nullptr).
+static la_status kv_commit(const la_attn_desc *desc, void *k_cache, void *v_cache, const int32_t *block_tables,
+                           const int32_t *prefix_lens, const int32_t *prefix_lens_host, const void *k_branch,
+                           const void *v_branch, const void *k_chain, const void *v_chain, int32_t chain_len,
+                           const int32_t *pool_seg, const uint64_t *commit_mask, const int32_t *src_branch,
+                           const int32_t *n_chain, const int32_t *n_own, const float *k_scale, const float *v_scale,
+                           int32_t *new_prefix_lens, const la_layer_strides *layers, void *hip_stream) {
+  const bool tree = commit_mask != nullptr;
   la_status st = validate_desc(desc);
   if (st != LA_OK) return st;
   if (!k_cache || !v_cache || !prefix_lens || !prefix_lens_host || !k_branch || !v_branch || !src_branch ||
-      !n_chain || !n_own || !new_prefix_lens)
+      (!tree && !n_chain) || !n_own || !new_prefix_lens)
     return LA_ERR_INVALID_ARG;
   if (new_prefix_lens == prefix_lens) return LA_ERR_INVALID_ARG;  // read by every workgroup while one writes
   if (chain_len < 0 || (chain_len > 0 && (!k_chain || !v_chain))) return LA_ERR_INVALID_ARG;
+  if (tree && ((chain_len > 0 && !pool_seg) || ((uintptr_t)commit_mask & 7))) return LA_ERR_INVALID_ARG;
   if (!aligned16(k_cache) || !aligned16(v_cache) || !aligned16(k_branch) || !aligned16(v_branch) ||
       !aligned16(k_chain) || !aligned16(v_chain))
     return LA_ERR_INVALID_ARG;
@@ -378,6 +382,8 @@ la_status la_kv_commit(const la_attn_desc *desc, void *k_cache, void *v_cache, c
   p.k_branch = k_branch, p.v_branch = v_branch, p.k_chain = k_chain, p.v_chain = v_chain;
   p.block_tables = block_tables, p.prefix_lens = prefix_lens;
   p.src_branch = src_branch, p.n_chain = n_chain, p.n_own = n_own;
+  p.pool_seg = tree && chain_len > 0 ? pool_seg : nullptr;  // an empty pool is the chain form with nothing kept
+  p.commit_mask = commit_mask;
   p.k_scale = k_scale, p.v_scale = v_scale;
   p.new_prefix_lens = new_prefix_lens;
   p.B = desc->num_requests, p.Hkv = desc->num_kv_heads, p.D = desc->head_dim, p.gamma = desc->gamma;
@@ -391,6 +397,30 @@ la_status la_kv_commit(const la_attn_desc *desc, void *k_cache, void *v_cache, c
     p.chain_stride = layers->chain_stride, p.scale_stride = layers->scale_stride;
   }
   return launch_kv_commit(p, elem_bytes[br], quantise, (hipStream_t)hip_stream) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
+la_status la_kv_commit(const la_attn_desc *desc, void *k_cache, void *v_cache, const int32_t *block_tables,
+                       const int32_t *prefix_lens, const int32_t *prefix_lens_host, const void *k_branch,
+                       const void *v_branch, const void *k_chain, const void *v_chain, int32_t chain_len,
+                       const int32_t *src_branch, const int32_t *n_chain, const int32_t *n_own, const float *k_scale,
+                       const float *v_scale, int32_t *new_prefix_lens, const la_layer_strides *layers,
+                       void *hip_stream) {
+  if (!n_chain) return LA_ERR_INVALID_ARG;
+  return kv_commit(desc, k_cache, v_cache, block_tables, prefix_lens, prefix_lens_host, k_branch, v_branch, k_chain,
+                   v_chain, chain_len, nullptr, nullptr, src_branch, n_chain, n_own, k_scale, v_scale,
+                   new_prefix_lens, layers, hip_stream);
+}
+
+la_status la_kv_commit_tree(const la_attn_desc *desc, void *k_cache, void *v_cache, const int32_t *block_tables,
+                            const int32_t *prefix_lens, const int32_t *prefix_lens_host, const void *k_branch,
+                            const void *v_branch, const void *k_pool, const void *v_pool, int32_t pool_len,
+                            const int32_t *pool_seg, const uint64_t *commit_mask, const int32_t *src_branch,
+                            const int32_t *n_own, const float *k_scale, const float *v_scale,
+                            int32_t *new_prefix_lens, const la_layer_strides *layers, void *hip_stream) {
+  if (!commit_mask) return LA_ERR_INVALID_ARG;
+  return kv_commit(desc, k_cache, v_cache, block_tables, prefix_lens, prefix_lens_host, k_branch, v_branch, k_pool,
+                   v_pool, pool_len, pool_seg, commit_mask, src_branch, nullptr, n_own, k_scale, v_scale,
+                   new_prefix_lens, layers, hip_stream);
 }
 
 static la_status validate_accept(const la_accept_desc *d) {

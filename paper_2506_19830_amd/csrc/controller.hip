@@ -3,6 +3,7 @@
 //
 //   la_step_select      Algorithm 1, verification and output construction: j* = first draft step the verifier
 //                       rejected (all accepted: the target's bonus step), and what la_kv_commit has to append for it.
+//   la_step_select_tree the same walk over a draft tree (Section 3.1, multi-branch drafting).
 //   la_speedup_*        Section 3.2 (step level, sync and async) and Section 3.3 (token level) closed forms.
 //   la_plan_budget      Section 3.3: argmax over (k1, k2) of f(k1) g(k2) under ParallelDim_f * k2 <= M.
 #include <math.h>
@@ -56,6 +57,35 @@ la_status la_step_select(int32_t num_requests, int32_t num_branches, const uint8
     if (src_branch) src_branch[b] = j;
     if (n_chain) n_chain[b] = chain_vis[(size_t)b * num_branches + j];
     if (n_own) n_own[b] = own_len[(size_t)b * num_branches + j];
+  }
+  return LA_OK;
+}
+
+la_status la_step_select_tree(int32_t num_requests, int32_t num_nodes, const int32_t *parent,
+                              const uint8_t *verdicts, const int32_t *own_len, int32_t *depth,
+                              uint64_t *commit_mask, int32_t *src_branch, int32_t *n_own) {
+  if (num_requests < 1 || num_nodes < 0 || num_nodes > 64) return LA_ERR_INVALID_ARG;
+  if ((num_nodes > 0 && (!parent || !verdicts)) || !depth || !commit_mask || (n_own && !own_len))
+    return LA_ERR_INVALID_ARG;
+  for (int n = 0; n < num_nodes; ++n)
+    if (parent[n] < -1 || parent[n] >= n) return LA_ERR_INVALID_ARG;
+  for (int b = 0; b < num_requests; ++b) {
+    const uint8_t *v = verdicts + (size_t)b * num_nodes;
+    int at = -1, steps = 0;  // -1: the root (nothing drafted accepted yet)
+    uint64_t mask = 0;
+    // parents come before children, so one sweep in node order follows the path downwards and meets the
+    // alternatives of each position in ascending order: the first accepted one wins
+    for (int n = 0; n < num_nodes; ++n) {
+      if (parent[n] == at && v[n]) {
+        at = n;
+        mask |= (uint64_t)1 << n;
+        ++steps;
+      }
+    }
+    depth[b] = steps;
+    commit_mask[b] = mask;
+    if (src_branch) src_branch[b] = at + 1;
+    if (n_own) n_own[b] = own_len[(size_t)b * (num_nodes + 1) + at + 1];
   }
   return LA_OK;
 }

@@ -119,6 +119,10 @@ struct CommitParams {
   const void *k_branch, *v_branch, *k_chain, *v_chain;
   const int32_t *block_tables, *prefix_lens, *src_branch, *n_chain, *n_own;
   const float *k_scale, *v_scale;
+  // tree form: k_chain / v_chain are the pool, pool_seg [B, C] the node of each pool token, commit_mask [B] the
+  // accepted nodes; n_chain is unused.  pool_seg == nullptr selects the chain form.
+  const int32_t *pool_seg;
+  const uint64_t *commit_mask;
   int32_t *new_prefix_lens;
   int B, Hkv, D, gamma, L, C, block_size, block_shift, max_blocks, num_layers;
   int capacity;                                                     // max_blocks * block_size

@@ -340,6 +340,19 @@ def make_tree_inputs(case: AttnCase, width: int, depth: int, step_len: int,
             "seg_mask": mask}
 
 
+def tree_parents(width: int, depth: int) -> np.ndarray:
+    """Parent of every node of :func:`make_tree_inputs`'s tree (same numbering), -1 for the nodes of position 0."""
+    par, level = [], [-1]
+    for _ in range(depth):
+        nxt = []
+        for p in level:
+            for _ in range(width):
+                nxt.append(len(par))
+                par.append(p)
+        level = nxt
+    return np.array(par, dtype=np.int32)
+
+
 def make_commit_inputs(case: AttnCase, chain_len: int, decisions=None) -> Dict[str, np.ndarray]:
     """What a verification pass decided per request, for the KV commit: which branch survives (``src_branch``), how
     many tokens of the drafted chain (``n_chain``, 0..chain_len) and then of that branch (``n_own``, 0..L) are

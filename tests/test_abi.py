@@ -147,6 +147,28 @@ def test_kv_commit_rejects_before_launch():
     assert call(roomy, strides=odd) == 1                         # layer 1 of the branch tensors would be unaligned
 
 
+def test_kv_commit_tree_rejects_before_launch():
+    lib = B.load()
+    vp = ctypes.c_void_p
+    lens = (ctypes.c_int32 * 1)(32768)
+
+    def call(desc, pool_len=8, **ptrs):
+        g = lambda k, dflt=256: vp(ptrs.get(k, dflt))
+        return lib.la_kv_commit_tree(ctypes.byref(desc), g("kc"), g("vc"), vp(0), g("lens"), lens, g("kb"), g("vb"),
+                                     g("kp"), g("vp"), ctypes.c_int32(pool_len), g("seg"), g("mask"), g("src"),
+                                     g("nown"), vp(0), vp(0), g("new", 512), None, vp(0))
+
+    roomy = good_desc(max_blocks_per_request=2048 + 8)
+    assert call(good_desc()) == 1                                # no room behind the prefix
+    assert call(roomy, mask=0) == 1
+    assert call(roomy, mask=260) == 1                            # 64-bit masks on a 4-byte boundary
+    assert call(roomy, seg=0) == 1                               # a pool without node labels
+    assert call(roomy, kp=0) == 1
+    assert call(roomy, pool_len=-1) == 1
+    assert call(roomy, src=0) == 1
+    assert call(roomy, new=256, lens=256) == 1
+
+
 def test_accept_rejects_bad_arguments():
     for kw, status in [(dict(num_branches=0), 1), (dict(num_draft=0), 1), (dict(vocab=0), 1),
                        (dict(temperature=0.0), 1), (dict(logits_dtype="fp8_e4m3"), 2),

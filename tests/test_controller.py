@@ -38,6 +38,52 @@ def test_step_select_edge_cases():
     assert (j[0], src[0], nch[0], nown[0]) == (0, 0, 0, 6)
 
 
+def random_tree(rng, nodes):
+    """Any tree with parents before children (not only the full ones the generators make)."""
+    return [int(rng.integers(-1, n)) for n in range(nodes)]
+
+
+def test_tree_select_matches_the_oracle_on_random_trees():
+    rng = np.random.default_rng(4)
+    for nodes in (0, 1, 2, 7, 30, 64):
+        for accept in (0.3, 0.7, 0.95):
+            par = random_tree(rng, nodes)
+            nreq = 40
+            verdicts = rng.random((nreq, nodes)) < accept
+            own = rng.integers(1, 65, size=(nreq, nodes + 1))
+            depth, mask, src, nown = B.la_step_select_tree(par, verdicts, own)
+            want = P.tree_output_construction(par, verdicts.tolist(), own.tolist())
+            assert [tuple(int(x) for x in t) for t in zip(depth, src, mask, nown)] == want
+
+
+def test_tree_select_of_a_chain_is_step_select():
+    rng = np.random.default_rng(5)
+    drafts, nreq = 6, 50
+    verdicts = rng.random((nreq, drafts)) < 0.8
+    own = rng.integers(1, 20, size=(nreq, drafts + 1))
+    vis = np.tile(np.arange(drafts + 1), (nreq, 1))
+    j, src, nch, nown = B.la_step_select(verdicts, vis, own)
+    depth, mask, tsrc, town = B.la_step_select_tree(np.arange(-1, drafts - 1), verdicts, own)
+    assert np.array_equal(depth, j) and np.array_equal(tsrc, src) and np.array_equal(town, nown)
+    assert np.array_equal(mask, (np.uint64(1) << j.astype(np.uint64)) - np.uint64(1))
+
+
+def test_tree_select_uses_all_64_bits():
+    par = list(range(-1, 63))                                      # a chain of 64 drafts, all accepted
+    depth, mask, src, nown = B.la_step_select_tree(par, np.ones((1, 64), bool), np.arange(65)[None])
+    assert depth[0] == 64 and mask[0] == np.uint64(2 ** 64 - 1) and src[0] == 64 and nown[0] == 64
+
+
+def test_tree_select_rejects_malformed_trees():
+    own = np.ones((1, 4), dtype=np.int32)
+    v = np.ones((1, 3), dtype=bool)
+    for par in ([-1, 1, 0], [-1, 0, 2], [-2, 0, 1], [0, 0, 1]):       # a node that is its own ancestor / child first
+        with pytest.raises(B.LaError):
+            B.la_step_select_tree(par, v, own)
+    with pytest.raises(B.LaError):
+        B.la_step_select_tree(list(range(-1, 64)), np.ones((1, 65), bool), np.ones((1, 66), np.int32))   # 65 nodes
+
+
 PLAN_GRID = [(a1, c1, a2, c2, M, asyn) for a1 in (0.3, 0.6, 0.79, 0.95) for c1 in (0.04, 0.2, 0.33, 0.6)
              for a2 in (0.4, 0.7) for c2 in (0.05, 0.3) for M in (1, 4, 16, 33) for asyn in (False, True)]
 
