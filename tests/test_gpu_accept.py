@@ -134,3 +134,33 @@ def test_warped_target(oracle, case):
         p, _ = oracle.warp_probs(row, logits_dtype=case.logits_dtype, temperature=case.temperature, top_k=case.top_k,
                                  top_p=float(np.float32(case.top_p)))
         assert p[got["next_token"][nb]] > 0
+
+
+# ------------------------------------------------------------------------------------------ random shapes
+
+def random_accept_case(idx):
+    rng = np.random.default_rng(3000 + idx)
+    V = int(rng.choice([2, 7, 64, 511, 1000, 4097, 8191, 8192, 8200, 16385, 32000, 50257, 100003, 151936, 152064]))
+    K = int(rng.choice([1, 2, 3, 5, 8, 13]))
+    NB = int(rng.choice([1, 2, 5, 16, 33, 100]))
+    while NB * (2 * K + 1) * V > 12_000_000 and NB > 1:             # keeps the oracle quick
+        NB = max(1, NB // 2)
+    while (2 * K + 1) * V > 12_000_000:
+        K = max(1, K // 2)
+    point_mass = bool(rng.integers(0, 3) == 0)
+    top_k = int(rng.choice([0, 0, 1, 5, 20, 50]))
+    top_p = float(rng.choice([1.0, 1.0, 0.95, 0.8, 0.5]))
+    return W.AcceptCase(f"rand_accept{idx}", NB, K, V, str(rng.choice(["f32", "bf16"])),
+                        target_std=float(rng.choice([1.0, 2.0, 3.0])),
+                        draft_noise_std=float(rng.choice([0.1, 0.5, 1.0])),
+                        temperature=float(rng.choice([1.0, 0.6, 1.5])), seed=3000 + idx, top_k=top_k, top_p=top_p,
+                        point_mass=point_mass, peak=float(rng.choice([2.0, 6.0, 11.0])))
+
+
+@pytest.mark.parametrize("idx", range(24))
+def test_accept_random_shapes(oracle, idx):
+    """Branch count, draft length, vocabulary (around the slice and vector sizes and the real ones), dtype,
+    temperature, top-k / top-p and dense or point-mass drafts drawn at random, each against the oracle."""
+    case = random_accept_case(idx)
+    print(f"  top_k={case.top_k} top_p={case.top_p} point_mass={case.point_mass}", flush=True)
+    check(oracle, case)
