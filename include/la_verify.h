@@ -26,6 +26,15 @@
  *   - Results are deterministic: the same inputs give bit-identical outputs.
  *   - Indices handed in by the caller (block ids, drafted token ids) are not
  *     range-checked on the device; out-of-range values are undefined behaviour.
+ *   - Where an argument exists as a device array and as a host copy
+ *     (prefix_lens / prefix_lens_host, chain_vis / chain_vis_host, pool_seg /
+ *     pool_seg_host) the host copy is what is validated and what the launch
+ *     and the workspace are sized from, and the kernels read the device array
+ *     without checking it again: the two must hold the same values when the
+ *     work runs, anything else is undefined behaviour.  (la_kv_commit's
+ *     decisions are device-only and therefore clamped by the kernel.)
+ *   - Not thread-safe with respect to the la_profile_* calls, which keep
+ *     process-wide state; the compute calls themselves keep none.
  */
 #ifndef LA_VERIFY_H
 #define LA_VERIFY_H
