@@ -41,7 +41,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 
 constexpr int kThreads = 256;
-constexpr int kFinePer = 8;                 // tokens per lane in the fp64 kernels
+constexpr int kFinePer = 8;                 // tokens per lane in the fp64 kernels (load_fine reads eight)
 constexpr int kFine = kThreads * kFinePer;  // 2048 tokens per fine slice
 
 // (bit-casting a vector element in place, __builtin_bit_cast(float, w[k]), reads element 0 with this compiler;
@@ -172,9 +172,66 @@ __device__ __forceinline__ uint32_t order_key(float x) {
   return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
 }
 
+// exp(y) in fp64 for the arguments met here (y = (x - max)/T <= 0 up to rounding; the result only has to be the same
+// function of y everywhere it is used, and within an ulp or two of the true value).  y = k ln2 + r with |r| <= ln2/2
+// by a two-term reduction (k * ln2_hi is exact for |k| < 2^11), e^r by its Taylor polynomial of degree 13
+// (remainder < 5e-18), then the scaling by 2^k, which also takes results below the normal range to denormals / zero.
+// About 20 fp64 instructions, against several times that for the general library routine.
+__device__ __forceinline__ double exp64(double y) {
+  y = fmin(fmax(y, -750.0), 709.0);
+  const double k = __builtin_rint(y * 1.4426950408889634074);
+  double r = __builtin_fma(-k, 6.93147180369123816490e-01, y);
+  r = __builtin_fma(-k, 1.90821492927058770002e-10, r);
+  double q = 1.0 / 6227020800.0;
+  q = __builtin_fma(q, r, 1.0 / 479001600.0);
+  q = __builtin_fma(q, r, 1.0 / 39916800.0);
+  q = __builtin_fma(q, r, 1.0 / 3628800.0);
+  q = __builtin_fma(q, r, 1.0 / 362880.0);
+  q = __builtin_fma(q, r, 1.0 / 40320.0);
+  q = __builtin_fma(q, r, 1.0 / 5040.0);
+  q = __builtin_fma(q, r, 1.0 / 720.0);
+  q = __builtin_fma(q, r, 1.0 / 120.0);
+  q = __builtin_fma(q, r, 1.0 / 24.0);
+  q = __builtin_fma(q, r, 1.0 / 6.0);
+  q = __builtin_fma(q, r, 0.5);
+  q = __builtin_fma(q, r, 1.0);
+  q = __builtin_fma(q, r, 1.0);
+  return __builtin_ldexp(q, (int)k);
+}
+
 // fp64 probability mass (unnormalised) of one logit: exp(x/T - max/T)
 __device__ __forceinline__ double mass64(float x, double mx_over_t, double inv_temp) {
-  return exp((double)x * inv_temp - mx_over_t);
+  return exp64((double)x * inv_temp - mx_over_t);
+}
+
+// The kFinePer consecutive logits of a row that a lane of the fp64 kernels owns, from token v (a multiple of
+// kFinePer) on; tokens at or past V read as -inf.  vec: every row starts on a 16-byte boundary, so the eight values
+// are one (bf16) or two (fp32) 16-byte loads.
+template <bool BF16>
+__device__ __forceinline__ void load_fine(const void *base, size_t row_off, int v, int V, bool vec, float (&x)[8]) {
+  if (vec && v + 8 <= V) {
+    if constexpr (BF16) {
+      const u32x4 w = *(const u32x4 *)((const uint16_t *)base + row_off + v);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t word = w[k];
+        x[2 * k] = bf16_lo(word);
+        x[2 * k + 1] = bf16_hi(word);
+      }
+    } else {
+      const u32x4 w0 = *(const u32x4 *)((const float *)base + row_off + v);
+      const u32x4 w1 = *(const u32x4 *)((const float *)base + row_off + v + 4);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t a = w0[k], b = w1[k];
+        x[k] = as_f32(a);
+        x[4 + k] = as_f32(b);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = v + e < V ? load_logit<BF16>(base, row_off + v + e) : -INFINITY;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -391,31 +448,74 @@ __global__ __launch_bounds__(kWarpThreads) void accept_warp_kernel(const AcceptP
 template <bool BF16>
 __global__ __launch_bounds__(kThreads) void accept_decide_kernel(const AcceptParams p) {
   constexpr int kPass = 64;                       // drafted positions examined per pass
+  constexpr int kStage = 2048;                    // slice statistics (max, sum) staged in LDS per pass
   __shared__ float sm[2][kPass], sz[2][kPass];    // [target|draft][position in pass]: folded row statistics
+  __shared__ f32x2 s_stat[kStage];
   __shared__ float s_top[2];                      // maxima of the resampling rows
-  __shared__ int s_first;
+  __shared__ float s_bonus;                       // maximum of target row K
+  __shared__ int s_first, s_have_bonus;
   __shared__ double red[2][kThreads / 64];
   const int c = blockIdx.x, nb = blockIdx.y, tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int n_t = p.NB * (p.K + 1);
-  if (tid == 0) s_first = p.K;
+  const int n_which = p.draft ? 2 : 1;   // point-mass draft: there are no draft rows
+  if (tid == 0) s_first = p.K, s_have_bonus = 0;
   __syncthreads();
   int i0 = 0;
   for (; i0 < p.K; i0 += kPass) {   // a later pass cannot lower the first rejection found in an earlier one
     const int cnt = min(kPass, p.K - i0);
-    const int n_which = p.draft ? 2 : 1;   // point-mass draft: there are no draft rows
-    for (int slot = wave; slot < n_which * cnt; slot += kThreads / 64) {   // wavefront per row
+    // what a position's test needs from global memory besides the row statistics; issued first so that the two
+    // dependent round trips (token, then its two logits) overlap the fold below
+    int x = 0;
+    float tx = 0.f, dx = 0.f, u = 0.f;
+    if (tid < cnt) {
+      const int i = i0 + tid;
+      x = p.tokens[(size_t)nb * p.K + i];
+      u = p.u_accept[(size_t)nb * p.K + i];
+      tx = load_logit<BF16>(p.target, ((size_t)nb * (p.K + 1) + i) * p.V + x);
+      if (p.draft) dx = load_logit<BF16>(p.draft, ((size_t)nb * p.K + i) * p.V + x);
+    }
+    // rows folded in this pass: cnt target rows, cnt draft rows and, in the last pass, target row K (the bonus row)
+    const int bonus = i0 + cnt == p.K ? 1 : 0;
+    const int n_rows = n_which * cnt + bonus;
+    auto row_of = [&](int slot) {
+      if (slot == n_which * cnt) return nb * (p.K + 1) + p.K;
       const int which = slot >= cnt, j = slot - which * cnt;
-      const int rw = which ? n_t + nb * p.K + i0 + j : nb * (p.K + 1) + i0 + j;
-      float m, z;
-      wave_fold_row(p, rw, lane, m, z);
-      if (lane == 0) sm[which][j] = m, sz[which][j] = z;
+      return which ? n_t + nb * p.K + i0 + j : nb * (p.K + 1) + i0 + j;
+    };
+    if (n_rows * p.n_chunks <= kStage) {
+      // all slice statistics in one round of loads, then one lane per row folds its slices from LDS
+      for (int idx = tid; idx < n_rows * p.n_chunks; idx += kThreads) {
+        const int slot = idx / p.n_chunks, ch = idx - slot * p.n_chunks;
+        s_stat[idx] = *(const f32x2 *)(p.stats + ((size_t)row_of(slot) * p.n_chunks + ch) * 2);
+      }
+      __syncthreads();
+      if (tid < n_rows) {
+        const f32x2 *st = s_stat + tid * p.n_chunks;
+        float m = -INFINITY;
+        for (int ch = 0; ch < p.n_chunks; ++ch) m = fmaxf(m, st[ch][0]);
+        float z = 0.f;
+        for (int ch = 0; ch < p.n_chunks; ++ch)
+          z += st[ch][1] * __builtin_amdgcn_exp2f((st[ch][0] - m) * p.inv_temp_log2);
+        if (tid == n_which * cnt) {
+          s_bonus = m;
+          s_have_bonus = 1;
+        } else {
+          const int which = tid >= cnt, j = tid - which * cnt;
+          sm[which][j] = m, sz[which][j] = z;
+        }
+      }
+    } else {
+      for (int slot = wave; slot < n_which * cnt; slot += kThreads / 64) {   // wavefront per row
+        const int which = slot >= cnt, j = slot - which * cnt;
+        float m, z;
+        wave_fold_row(p, row_of(slot), lane, m, z);
+        if (lane == 0) sm[which][j] = m, sz[which][j] = z;
+      }
     }
     __syncthreads();
     if (tid < cnt) {
       const int i = i0 + tid;
-      const int x = p.tokens[(size_t)nb * p.K + i];
-      const float tx = load_logit<BF16>(p.target, ((size_t)nb * (p.K + 1) + i) * p.V + x);
       float px = __builtin_amdgcn_exp2f((tx - sm[0][tid]) * p.inv_temp_log2) / sz[0][tid];
       if (p.warp_key) {  // warped target: x has mass only if its row keeps it, normalised by the kept mass
         const int wr = nb * (p.K + 1) + i;
@@ -424,11 +524,7 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(const AcceptPar
                  : 0.f;
       }
       float qx = 1.0f;   // point-mass draft at x
-      if (p.draft) {
-        const float dx = load_logit<BF16>(p.draft, ((size_t)nb * p.K + i) * p.V + x);
-        qx = __builtin_amdgcn_exp2f((dx - sm[1][tid]) * p.inv_temp_log2) / sz[1][tid];
-      }
-      const float u = p.u_accept[(size_t)nb * p.K + i];
+      if (p.draft) qx = __builtin_amdgcn_exp2f((dx - sm[1][tid]) * p.inv_temp_log2) / sz[1][tid];
       if (!(u * qx < px)) atomicMin(&s_first, i);
       if (c == 0 && p.ratio) p.ratio[(size_t)nb * p.K + i] = px / qx;
     }
@@ -440,6 +536,8 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(const AcceptPar
   // target row K alone when everything was accepted
   if (n < p.K) {
     if (tid == 0) s_top[0] = sm[0][n - i0], s_top[1] = p.draft ? sm[1][n - i0] : 0.f;
+  } else if (s_have_bonus) {
+    if (tid == 0) s_top[0] = s_bonus, s_top[1] = 0.f;
   } else if (wave == 0) {
     float m, z;
     wave_fold_row(p, nb * (p.K + 1) + p.K, lane, m, z);
@@ -458,12 +556,17 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(const AcceptPar
   const size_t drow = ((size_t)nb * p.K + (n < p.K ? n : 0)) * p.V;
   const double mt_t = (double)mt * p.inv_temp, mq_t = (double)mq * p.inv_temp;
   double st = 0.0, sq = 0.0;
+  const bool vec = ((size_t)p.V * (BF16 ? 2 : 4)) % 16 == 0;
+  const bool with_draft = n < p.K && p.draft;
+  const int vb = v0 + tid * kFinePer;
+  float tx[kFinePer], dx[kFinePer];
+  load_fine<BF16>(p.target, trow, vb, p.V, vec, tx);
+  if (with_draft) load_fine<BF16>(p.draft, drow, vb, p.V, vec, dx);
 #pragma unroll
   for (int e = 0; e < kFinePer; ++e) {
-    const int v = v0 + tid * kFinePer + e;
-    if (v < v1) {
-      st += mass64(load_logit<BF16>(p.target, trow + v), mt_t, p.inv_temp);
-      if (n < p.K && p.draft) sq += mass64(load_logit<BF16>(p.draft, drow + v), mq_t, p.inv_temp);
+    if (vb + e < v1) {
+      st += mass64(tx[e], mt_t, p.inv_temp);
+      if (with_draft) sq += mass64(dx[e], mq_t, p.inv_temp);
     }
   }
   st = wave_sum(st);
@@ -478,18 +581,22 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(const AcceptPar
 
 constexpr int kMaxFine = 1024;   // fine slices per row the fp64 kernels can stage in LDS (vocab <= 2M)
 
-// Sum of n <= kMaxFine doubles in index order, the same value in every lane of the workgroup: all lanes stage the
-// terms in LDS, lane 0 adds them in order.
+// Sum of n <= kMaxFine doubles, the same value in every lane of the workgroup and in every workgroup that folds the
+// same terms (fixed association: per lane its terms in index order, a butterfly inside each wavefront, the
+// wavefronts in order).  The terms are also left in buf[0..n).
 __device__ __forceinline__ double fold64_block(const double *v, int n, double *buf, double *slot) {
-  for (int c = threadIdx.x; c < n; c += kThreads) buf[c] = v[c];
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    double s = 0.0;
-    for (int c = 0; c < n; ++c) s += buf[c];
-    *slot = s;
+  __shared__ double fold_red[kThreads / 64];
+  double acc = 0.0;
+  for (int c = threadIdx.x; c < n; c += kThreads) {
+    const double t = v[c];
+    buf[c] = t;
+    acc += t;
   }
+  acc = wave_sum(acc);
+  __syncthreads();   // fold_red free again (a previous call's readers are past their reads)
+  if ((threadIdx.x & 63) == 0) fold_red[threadIdx.x >> 6] = acc;
   __syncthreads();
-  return *slot;
+  return (fold_red[0] + fold_red[1]) + (fold_red[2] + fold_red[3]);
 }
 
 // residual mass and target mass of the tokens of branch nb at position n, fp64
@@ -497,16 +604,16 @@ template <bool BF16>
 struct ResidCtx {
   const void *target, *draft;
   size_t trow, drow;
-  double mt, mq, zt, zq, inv_temp;
+  double mt, mq, inv_zt, inv_zq, inv_temp;   // maxima over T, reciprocals of the normalisers, 1/T
   bool has_draft;
   int removed;   // point-mass draft after a rejection: the drafted token, which has no residual mass; else -1
   uint32_t key_min;   // warped target: smallest key the row keeps (0: everything)
-  __device__ __forceinline__ void eval(int v, double &r, double &pm) const {
-    const float tx = load_logit<BF16>(target, trow + v);
-    pm = order_key(tx) >= key_min ? mass64(tx, mt, inv_temp) / zt : 0.0;
+  // tx, dx: the target and draft logit of token v (dx is read only with a draft row)
+  __device__ __forceinline__ void eval(int v, float tx, float dx, double &r, double &pm) const {
+    pm = order_key(tx) >= key_min ? mass64(tx, mt, inv_temp) * inv_zt : 0.0;
     r = v == removed ? 0.0 : pm;
     if (has_draft) {
-      const double qm = mass64(load_logit<BF16>(draft, drow + v), mq, inv_temp) / zq;
+      const double qm = mass64(dx, mq, inv_temp) * inv_zq;
       r = pm - qm;
       if (r < 0.0) r = 0.0;
     }
@@ -526,14 +633,16 @@ __device__ __forceinline__ ResidCtx<BF16> make_ctx(const AcceptParams &p, int nb
   x.inv_temp = p.inv_temp;
   x.mt = (double)p.rowmax[2 * nb] * p.inv_temp;
   x.mq = (double)p.rowmax[2 * nb + 1] * p.inv_temp;
-  x.zt = fold64_block(p.zsum + ((size_t)nb * 2 + 0) * p.n_fine, p.n_fine, buf, slots);
-  x.zq = fold64_block(p.zsum + ((size_t)nb * 2 + 1) * p.n_fine, p.n_fine, buf, slots + 1);
-  if (!x.has_draft) x.zq = 1.0;
+  double zt = fold64_block(p.zsum + ((size_t)nb * 2 + 0) * p.n_fine, p.n_fine, buf, slots);
+  double zq = fold64_block(p.zsum + ((size_t)nb * 2 + 1) * p.n_fine, p.n_fine, buf, slots + 1);
+  if (!x.has_draft) zq = 1.0;
   x.key_min = 0;
   if (p.warp_key) {   // the kept mass replaces the row's full normaliser
     x.key_min = p.warp_key[nb * (p.K + 1) + n];
-    x.zt = p.warp_z[nb * (p.K + 1) + n];
+    zt = p.warp_z[nb * (p.K + 1) + n];
   }
+  x.inv_zt = 1.0 / zt;
+  x.inv_zq = 1.0 / zq;
   return x;
 }
 
@@ -549,12 +658,16 @@ __global__ __launch_bounds__(kThreads) void accept_resid_kernel(const AcceptPara
   const ResidCtx<BF16> ctx = make_ctx<BF16>(p, nb, buf, slots);
   const int v0 = c * kFine, v1 = min(p.V, v0 + kFine);
   double sr = 0.0, sp = 0.0;
+  const bool vec = ((size_t)p.V * (BF16 ? 2 : 4)) % 16 == 0;
+  const int vb = v0 + tid * kFinePer;
+  float tx[kFinePer], dx[kFinePer];
+  load_fine<BF16>(ctx.target, ctx.trow, vb, p.V, vec, tx);
+  if (ctx.has_draft) load_fine<BF16>(ctx.draft, ctx.drow, vb, p.V, vec, dx);
 #pragma unroll
   for (int e = 0; e < kFinePer; ++e) {
-    const int v = v0 + tid * kFinePer + e;
-    if (v < v1) {
+    if (vb + e < v1) {
       double r, pm;
-      ctx.eval(v, r, pm);
+      ctx.eval(vb + e, tx[e], ctx.has_draft ? dx[e] : 0.f, r, pm);
       sr += r;
       sp += pm;
     }
@@ -594,23 +707,43 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(const AcceptParam
     S = fold64_block(p.rsum + ((size_t)nb * 2 + 1) * p.n_fine, p.n_fine, buf, slots);
   }
   const double thr = u * S;
-  if (tid == 0) {
+  if (wave == 0) {
     // slice in which the running sum (buf still holds the slice sums) first exceeds thr; the last slice with mass
-    // if rounding hides the crossing
-    int cs = -1, last = 0;
-    double acc = 0.0, before = 0.0, before_last = 0.0;
-    for (int c = 0; c < p.n_fine; ++c) {
+    // if rounding hides the crossing.  Lane j owns `per` consecutive slices; an exclusive scan over the lanes gives
+    // the mass before its first one.
+    const int per = (p.n_fine + 63) / 64;
+    const int c0 = min(p.n_fine, lane * per), c1 = min(p.n_fine, c0 + per);
+    double own = 0.0;
+    for (int c = c0; c < c1; ++c) own += buf[c];
+    double incl = own;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const double up = __shfl_up(incl, off);
+      if (lane >= off) incl += up;
+    }
+    const double prev = __shfl_up(incl, 1);
+    double acc = lane ? prev : 0.0;
+    int cross = INT_MAX, last = -1;
+    double before = 0.0, before_last = 0.0;
+    for (int c = c0; c < c1; ++c) {
       const double r = buf[c];
       if (r > 0.0) last = c, before_last = acc;
-      if (acc + r > thr) {
-        cs = c;
-        before = acc;
-        break;
-      }
+      if (cross == INT_MAX && acc + r > thr) cross = c, before = acc;
       acc += r;
     }
-    if (cs < 0) cs = last, before = before_last;
-    s_before = before, s_slice = cs, s_lane = INT_MAX, s_last_lane = -1;
+    const uint64_t hit = __ballot(cross != INT_MAX), has = __ballot(last >= 0);
+    int cs = 0;
+    double bef = 0.0;
+    if (hit) {
+      const int src = __ffsll((unsigned long long)hit) - 1;
+      cs = __shfl(cross, src);
+      bef = __shfl(before, src);
+    } else if (has) {
+      const int src = 63 - __clzll((long long)has);
+      cs = __shfl(last, src);
+      bef = __shfl(before_last, src);
+    }
+    if (lane == 0) s_before = bef, s_slice = cs, s_lane = INT_MAX, s_last_lane = -1;
   }
   __syncthreads();
   const int cs = s_slice;
@@ -641,7 +774,8 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(const AcceptParam
       const int v = v0 + e;
       if (v >= v1) break;
       double r, pm;
-      ctx.eval(v, r, pm);
+      ctx.eval(v, load_logit<BF16>(ctx.target, ctx.trow + v),
+               ctx.has_draft ? load_logit<BF16>(ctx.draft, ctx.drow + v) : 0.f, r, pm);
       const double mass = mode ? pm : r;
       run += mass;
       if (mass > 0.0) {
