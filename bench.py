@@ -52,6 +52,11 @@ def parse_args():
     ap.add_argument("--planner", action="store_true",
                     help="time the host-only budget planner (la_plan_budget) and the step selection instead; no GPU "
                          "work; prints its own JSON line")
+    ap.add_argument("--paper-sampling", choices=("qwen3", "r1"), default=None,
+                    help="run the accept call with the sampling settings of the paper's experiments (Section 4, Setup) "
+                         "and prompt-lookup drafts (tokens only, no draft logits) instead of the configuration's plain "
+                         "softmax over dense draft logits: qwen3 = temperature 0.6, top-p 0.95, top-k 20; r1 = "
+                         "temperature 0.6, top-p 0.95")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (three times) before the timed region, so that a counter "
                          "run can scale FETCH_SIZE / WRITE_SIZE by what they read for a kernel of known traffic")
@@ -306,6 +311,10 @@ def main():
     torch.cuda.set_device(0)
 
     attn_case, acc_case = W.config(args.config)
+    if args.paper_sampling:
+        from dataclasses import replace
+        acc_case = replace(acc_case, name=f"{acc_case.name}_{args.paper_sampling}_sampling", temperature=0.6,
+                           top_k=20 if args.paper_sampling == "qwen3" else 0, top_p=0.95, point_mass=True, peak=9.0)
     if args.branch_len is not None:
         from dataclasses import replace
         attn_case = replace(attn_case, L=args.branch_len, name=f"{attn_case.name}_L{args.branch_len}")
@@ -368,13 +377,15 @@ def main():
     acc_np = W.make_accept_inputs(acc_case)
     acc = {
         "target_logits": B.to_device(acc_np["target_logits"], acc_case.logits_dtype, dev),
-        "draft_logits": B.to_device(acc_np["draft_logits"], acc_case.logits_dtype, dev),
+        "draft_logits": None if acc_np["draft_logits"] is None
+        else B.to_device(acc_np["draft_logits"], acc_case.logits_dtype, dev),
         "draft_tokens": torch.from_numpy(acc_np["draft_tokens"]).to(dev),
         "u_accept": torch.from_numpy(acc_np["u_accept"]).to(dev),
         "u_sample": torch.from_numpy(acc_np["u_sample"]).to(dev),
     }
     adesc = B.make_accept_desc(num_branches=acc_case.NB, num_draft=acc_case.K, vocab=acc_case.V,
-                               logits_dtype=acc_case.logits_dtype, temperature=acc_case.temperature)
+                               logits_dtype=acc_case.logits_dtype, temperature=acc_case.temperature,
+                               top_k=acc_case.top_k, top_p=acc_case.top_p)
     aws = torch.empty(max(16, B.la_spec_accept_workspace(adesc)), dtype=torch.uint8, device=dev)
     n_acc = torch.empty(acc_case.NB, dtype=torch.int32, device=dev)
     nxt = torch.empty(acc_case.NB, dtype=torch.int32, device=dev)
@@ -465,7 +476,8 @@ def main():
     achieved_tflops = flops / (kern_avg_ms * 1e-3) / 1e12
     alg_bytes = attn_case.algorithmic_bytes()
     attn_ms = sum(prof_all[k][1] for k in ("attn_mfma", "attn_merge"))
-    accept_ms = sum(prof_all[k][1] for k in ("accept_stats", "accept_decide", "accept_resid", "accept_pick"))
+    accept_ms = sum(prof_all[k][1] for k in ("accept_stats", "accept_warp", "accept_decide", "accept_resid",
+                                             "accept_pick") if k in prof_all)
     stats_launches, stats_ms = prof["accept_stats"]
     stats_gbs = acc_case.algorithmic_bytes() / (stats_ms / max(1, stats_launches) * 1e-3) / 1e9
 
@@ -486,7 +498,9 @@ def main():
             "workload": f"config {args.config}: {attn_case.name}, {n_layers} layers, prefix {lens}, gamma "
                         f"{attn_case.gamma} x L {attn_case.L}, {attn_case.Hq}q/{attn_case.Hkv}kv heads, D "
                         f"{attn_case.D}, KV {attn_case.kv_dtype}, Q {attn_case.q_dtype}; accept NB {acc_case.NB} "
-                        f"K {acc_case.K} V {acc_case.V} {acc_case.logits_dtype}",
+                        f"K {acc_case.K} V {acc_case.V} {acc_case.logits_dtype}"
+                        + (f", T {acc_case.temperature} top-k {acc_case.top_k} top-p {acc_case.top_p}, prompt-lookup "
+                           f"drafts" if args.paper_sampling else ""),
             "layers": n_layers,
             "branch_tokens_per_step": branch_tokens,
             "kv_split_tokens": args.kv_split_tokens,
@@ -549,7 +563,7 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         oracle.build()
-        sample_layers = sorted({0, n_layers - 1})        # first and last layer of the sweep, each in full
+        sample_layers = sorted({0, n_layers // 2, n_layers - 1})   # three layers of the sweep, each in full (~10 s)
         t_attn, worst = 0.0, 0.0
         D = attn_case.D
         for l in sample_layers:
@@ -572,7 +586,8 @@ def main():
             worst = max(worst, float(err.max()))
         t_layer = t_attn / len(sample_layers)
         t0 = time.perf_counter()
-        aref = oracle.spec_accept(**acc_np, logits_dtype=acc_case.logits_dtype, temperature=acc_case.temperature)
+        aref = oracle.spec_accept(**acc_np, logits_dtype=acc_case.logits_dtype, temperature=acc_case.temperature,
+                                  top_k=acc_case.top_k, top_p=float(np.float32(acc_case.top_p)))
         t_acc = time.perf_counter() - t0
         cpu_pass_s = t_layer * n_layers + t_acc
         near = np.array([(m[np.isfinite(m)] <= 1e-6).any() for m in aref["margin"]])

@@ -168,7 +168,7 @@ __device__ __forceinline__ void wave_fold_row(const AcceptParams &p, int rw, int
 
 // Order-preserving key of an fp32 value: larger value <=> larger key (as unsigned).
 __device__ __forceinline__ uint32_t order_key(float x) {
-  const uint32_t b = __builtin_bit_cast(uint32_t, x);
+  const uint32_t b = __builtin_bit_cast(uint32_t, x + 0.0f);   // -0 and +0 are one value: (-0) + (+0) = +0
   return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
 }
 
@@ -241,22 +241,23 @@ constexpr int kWarpThreads = 1024;
 constexpr int kRep = 16;   // histogram copies per workgroup
 
 // Calls f(x) for every logit of a row, the workgroup's lanes striding over it, with several loads in flight per
-// lane (16-byte loads when the row allows: four per lane and batch).
+// lane (16-byte loads when the row allows: eight per lane and batch).
 template <bool BF16, typename F>
 __device__ __forceinline__ void row_foreach(const void *row, int V, F &&f) {
   constexpr int kPerVec = BF16 ? 8 : 4;
+  constexpr int kInFlight = 8;   // 16-byte loads per lane and batch
   const int tid = threadIdx.x;
   if (V % kPerVec == 0) {   // then every row starts on a 16-byte boundary
     const int n_vec = V / kPerVec;
-    for (int i0 = tid; i0 < n_vec; i0 += 4 * kWarpThreads) {
-      u32x4 w[4];
+    for (int i0 = tid; i0 < n_vec; i0 += kInFlight * kWarpThreads) {
+      u32x4 w[kInFlight];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < kInFlight; ++j) {
         const int i = i0 + j * kWarpThreads;
         w[j] = *(const u32x4 *)((const uint8_t *)row + (size_t)(i < n_vec ? i : i0) * 16);
       }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < kInFlight; ++j) {
         if (i0 + j * kWarpThreads >= n_vec) break;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -405,6 +406,147 @@ __device__ __forceinline__ double kept_mass(const void *row, int V, double mx_ov
   return out;
 }
 
+// The logit an order-preserving key came from.
+__device__ __forceinline__ float key_value(uint32_t key) {
+  return __builtin_bit_cast(float, (key >> 31) ? key ^ 0x80000000u : ~key);
+}
+
+constexpr int kSmallK = 128;   // largest top_k the candidate-list path takes
+constexpr int kCand = 2048;    // its candidate list (LDS)
+
+// top-k with a small k, then top-p, in two passes over the row and without a histogram.  Pass 1: every lane keeps
+// the largest key among its tokens; the k-th largest of these lane maxima (found bit by bit with ballot counts) is a
+// lower bound of the row's k-th largest key, because at least k tokens reach it.  Pass 2: the keys at or above that
+// bound go to a list in LDS (a few dozen for random logits; when more than kCand qualify, e.g. a row of equal
+// logits, the caller takes the histogram path instead: returns false, the same decision in every lane).  The list is
+// sorted by rank counting (the order of equal keys does not matter: they are the same value), and one lane walks it
+// in descending order exactly as the definition reads: the tokens down to the k-th largest value stay, Z_k is their
+// mass, then value groups are taken while the mass above them is below top_p * Z_k.
+template <bool BF16>
+__device__ __forceinline__ bool warp_small_k(const AcceptParams &p, const void *row, uint32_t *cand, uint32_t *sorted,
+                                             double *cmass, float *row_max_out, uint32_t *key_min_out,
+                                             double *z_out) {
+  __shared__ int s_cnt[2][kWarpThreads / 64];
+  __shared__ float s_wmax[kWarpThreads / 64];
+  __shared__ int s_n;
+  __shared__ uint32_t s_key;
+  __shared__ double s_z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int k = p.top_k;
+  float mx = -INFINITY;   // a lane without tokens counts as holding -inf
+  row_foreach<BF16>(row, p.V, [&](float x) { mx = fmaxf(mx, x); });
+  const uint32_t mk = order_key(mx);
+  {   // the row maximum falls out of the same pass (made visible by the first barrier of the search below)
+    const float wm = wave_max(mx);
+    if (lane == 0) s_wmax[wave] = wm;
+  }
+  uint32_t lo = 0;   // invariant: at least k lanes have mk >= lo (k <= kSmallK < the number of lanes)
+  // (a bf16 logit's key has sixteen equal low bits, so its sixteen high bits decide)
+  for (int bit = 31; bit >= (BF16 ? 16 : 0); --bit) {
+    const uint32_t c = lo | (1u << bit);
+    const int n_w = __popcll(__ballot(mk >= c));
+    if (lane == 0) s_cnt[bit & 1][wave] = n_w;
+    __syncthreads();
+    int tot = 0;
+#pragma unroll
+    for (int w = 0; w < kWarpThreads / 64; ++w) tot += s_cnt[bit & 1][w];
+    if (tot >= k) lo = c;
+  }
+  float row_max = s_wmax[0];
+#pragma unroll
+  for (int w = 1; w < kWarpThreads / 64; ++w) row_max = fmaxf(row_max, s_wmax[w]);
+  *row_max_out = row_max;
+  const double mx_over_t = (double)row_max * p.inv_temp;
+  if (BF16 && !(lo >> 31)) lo |= 0xFFFFu;   // the low bits of a negative bf16 value's key: lo is that key itself
+  const float lo_val = key_value(lo);        // the k-th largest lane maximum (-inf when fewer than k lanes own a token)
+  if (tid == 0) s_n = 0;
+  __syncthreads();
+  // comparing the values is comparing the keys (no NaNs; -0 == +0 on both sides)
+  row_foreach<BF16>(row, p.V, [&](float x) {
+    if (x >= lo_val) {
+      const int i = atomicAdd(&s_n, 1);
+      if (i < kCand) cand[i] = order_key(x);
+    }
+  });
+  __syncthreads();
+  const int n_c = s_n;   // >= k
+  if (n_c > kCand) return false;
+  for (int i = tid; i < n_c; i += kWarpThreads) {
+    const uint32_t ki = cand[i];
+    int rank = 0;
+    for (int j = 0; j < n_c; ++j) {
+      const uint32_t kj = cand[j];
+      rank += (kj > ki || (kj == ki && j < i)) ? 1 : 0;
+    }
+    sorted[rank] = ki;
+  }
+  __syncthreads();
+  const uint32_t kth = sorted[k - 1];
+  for (int i = tid; i < n_c; i += kWarpThreads)
+    cmass[i] = sorted[i] >= kth ? mass64(key_value(sorted[i]), mx_over_t, p.inv_temp) : 0.0;
+  __syncthreads();
+  if (n_c <= 64) {
+    // the usual case: the whole list fits one wavefront, lane j holding the j-th largest key and its mass
+    if (wave == 0) {
+      const bool in = lane < n_c;
+      const uint32_t key = in ? sorted[lane] : 0u;
+      const bool by_k = in && key >= kth;                 // kept by top-k: a leading part of the lanes
+      const double mj = by_k ? cmass[lane] : 0.0;
+      const uint64_t kmask = __ballot(by_k);
+      int kept = __popcll(kmask);
+      if (p.top_p < 1.0f) {
+        const double zk = wave_sum(mj);
+        const double target = (double)p.top_p * zk;
+        double incl = mj;                                   // inclusive running mass in descending order
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+          const double up = __shfl_up(incl, off);
+          if (lane >= off) incl += up;
+        }
+        const double before = __shfl_up(incl, 1);
+        const double excl = lane ? before : 0.0;
+        // mass above a token = running mass before the first lane of its value group
+        const uint32_t prev_key = __shfl_up(key, 1);
+        const uint64_t starts = __ballot(lane == 0 || key != prev_key);
+        const uint64_t upto = starts & (lane == 63 ? ~0ull : ((2ull << lane) - 1));
+        const int g = 63 - __clzll((long long)upto);
+        const double above = __shfl(excl, g);
+        kept = __popcll(__ballot(by_k && above < target));   // a leading part as well: `above` never falls
+      }
+      const double z = wave_sum(lane < kept ? mj : 0.0);
+      const uint32_t key_last = __shfl(key, kept - 1);
+      if (lane == 0) s_key = key_last, s_z = z;
+    }
+  } else if (tid == 0) {
+    int n_k = k;
+    while (n_k < n_c && sorted[n_k] == kth) ++n_k;   // ties with the k-th largest stay
+    int kept = n_k;
+    if (p.top_p < 1.0f) {
+      double zk = 0.0;
+      for (int j = 0; j < n_k; ++j) zk += cmass[j];
+      const double target = (double)p.top_p * zk;
+      double above = 0.0;
+      int j = 0;
+      while (j < n_k && above < target) {   // the tokens of one value stay or go together
+        int e = j;
+        double group = 0.0;
+        while (e < n_k && sorted[e] == sorted[j]) group += cmass[e++];
+        above += group;
+        j = e;
+      }
+      kept = j;
+    }
+    double z = 0.0;
+    for (int j = 0; j < kept; ++j) z += cmass[j];
+    s_key = sorted[kept - 1];
+    s_z = z;
+  }
+  __syncthreads();
+  *key_min_out = s_key;
+  *z_out = s_z;
+  return true;
+}
+
 template <bool BF16>
 __global__ __launch_bounds__(kWarpThreads) void accept_warp_kernel(const AcceptParams p) {
   __shared__ double mass[256 * kRep];                 // the count histogram shares this storage
@@ -416,24 +558,32 @@ __global__ __launch_bounds__(kWarpThreads) void accept_warp_kernel(const AcceptP
   const int rw = blockIdx.x;   // target row nb*(K+1) + i
   const int tid = threadIdx.x;
   const uint8_t *row = (const uint8_t *)p.target + (size_t)rw * p.V * (BF16 ? 2 : 4);
-  if (tid < 64) {
-    float m, z;
-    wave_fold_row(p, rw, tid, m, z);
-    if (tid == 0) s_m = m;
-  }
-  __syncthreads();
-  const float m = s_m;
-  const double mx_over_t = (double)m * p.inv_temp;
   auto each_of_row = [&](auto &&f) { row_foreach<BF16>(row, p.V, f); };
   uint32_t key_min = 0;
-  if (p.top_k > 0 && p.top_k < p.V)
-    key_min = radix_select<BF16, false>(each_of_row, 0.0, 0.0, 0u, p.top_k, 0.0, cnt, mass, &s_pick, &s_above);
-  if (p.top_p < 1.0f) {
-    const double zk = kept_mass<BF16>(row, p.V, mx_over_t, p.inv_temp, key_min, red, &s_slot);
-    key_min = radix_select<BF16, true>(each_of_row, mx_over_t, p.inv_temp, key_min, 0, (double)p.top_p * zk, cnt, mass,
-                                       &s_pick, &s_above);
+  double zw = 0.0;
+  float m = 0.f;
+  bool done = false;
+  if (p.top_k > 0 && p.top_k < p.V && p.top_k <= kSmallK)   // the candidate list lives in the histogram's storage
+    done = warp_small_k<BF16>(p, row, cnt, cnt + kCand, mass + kCand, &m, &key_min, &zw);
+  if (!done) {
+    if (tid < 64) {
+      float z;
+      wave_fold_row(p, rw, tid, m, z);
+      if (tid == 0) s_m = m;
+    }
+    __syncthreads();
+    m = s_m;
+    const double mx_over_t = (double)m * p.inv_temp;
+    key_min = 0;
+    if (p.top_k > 0 && p.top_k < p.V)
+      key_min = radix_select<BF16, false>(each_of_row, 0.0, 0.0, 0u, p.top_k, 0.0, cnt, mass, &s_pick, &s_above);
+    if (p.top_p < 1.0f) {
+      const double zk = kept_mass<BF16>(row, p.V, mx_over_t, p.inv_temp, key_min, red, &s_slot);
+      key_min = radix_select<BF16, true>(each_of_row, mx_over_t, p.inv_temp, key_min, 0, (double)p.top_p * zk, cnt,
+                                         mass, &s_pick, &s_above);
+    }
+    zw = kept_mass<BF16>(row, p.V, mx_over_t, p.inv_temp, key_min, red, &s_slot);
   }
-  const double zw = kept_mass<BF16>(row, p.V, mx_over_t, p.inv_temp, key_min, red, &s_slot);
   if (tid == 0) {
     p.warp_key[rw] = key_min;
     p.warp_z[rw] = zw;

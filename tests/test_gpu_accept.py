@@ -136,6 +136,48 @@ def test_warped_target(oracle, case):
         assert p[got["next_token"][nb]] > 0
 
 
+def check_inputs(oracle, case, inp):
+    from gpu_util import compare_accept, run_accept
+    got = run_accept(case, inp)
+    ref = oracle.spec_accept(**inp, logits_dtype=case.logits_dtype, temperature=case.temperature, top_k=case.top_k,
+                             top_p=float(np.float32(case.top_p)))
+    bad_n, bad_tok, near = compare_accept(got, ref)
+    print(f"  {case.name}: near-threshold branches set aside: {near} of {case.NB}", flush=True)
+    assert bad_n == 0 and bad_tok == 0, f"{bad_n} accepted lengths, {bad_tok} tokens differ"
+    assert near < case.NB // 2
+    return got, ref
+
+
+def test_warp_large_top_k(oracle):
+    """A top_k above what the candidate-list path of the warp kernel takes: the histogram selection runs."""
+    check(oracle, W.AcceptCase("warp_topk_200", 40, 3, 4096, "f32", temperature=0.8, top_k=200, top_p=0.9, seed=31))
+    check(oracle, W.AcceptCase("warp_topk_129_bf16", 24, 2, 20000, "bf16", top_k=129, top_p=0.97, seed=32))
+    check(oracle, W.AcceptCase("warp_topk_128_bf16", 24, 2, 20000, "bf16", top_k=128, top_p=0.97, seed=33))
+
+
+@pytest.mark.parametrize("std,top_k,dtype", [(3.0, 20, "bf16"), (3.0, 20, "f32"), (0.5, 50, "bf16"), (0.5, 50, "f32"),
+                                             (0.0, 5, "f32")])
+def test_warp_tied_logits(oracle, std, top_k, dtype):
+    """Target logits rounded to whole numbers, so that many tokens tie at every value: ties with the k-th largest
+    value all stay, and a value group stays or goes as one under top-p.  With std 3 the candidate list of the warp
+    kernel holds a few hundred tied keys; with std 0.5 the k-th value is shared by thousands of tokens, more than the
+    list takes, and with std 0 by the whole row: the histogram path takes over."""
+    case = W.AcceptCase(f"warp_ties_{std}_{top_k}_{dtype}", 12, 3, 20000, dtype, target_std=max(std, 1.0),
+                        temperature=0.7, top_k=top_k, top_p=0.9, point_mass=True, peak=0.0, seed=int(40 + std * 10))
+    inp = W.make_accept_inputs(case)
+    x = W._decode_for_sampling(inp["target_logits"], dtype)
+    x = np.rint(x * (std / max(std, 1.0)))
+    x[:, :, ::2] += 0.0          # every other zero a negative zero: the same value as +0 for both filters
+    inp["target_logits"] = W.encode(x.astype(np.float32), dtype)
+    got, ref = check_inputs(oracle, case, inp)
+    # what was drawn has mass under the warped row
+    for nb in range(case.NB):
+        n = int(ref["accepted_len"][nb])
+        p, _ = oracle.warp_probs(inp["target_logits"][nb, n], logits_dtype=dtype, temperature=case.temperature,
+                                 top_k=case.top_k, top_p=float(np.float32(case.top_p)))
+        assert p[got["next_token"][nb]] > 0
+
+
 # ------------------------------------------------------------------------------------------ random shapes
 
 def random_accept_case(idx):
