@@ -239,6 +239,8 @@ __device__ __forceinline__ void load_fine(const void *base, size_t row_off, int 
 // ---------------------------------------------------------------------------------------------
 constexpr int kWarpThreads = 1024;
 constexpr int kRep = 16;   // histogram copies per workgroup
+constexpr int kHist = 257; // elements between two copies: one more than the buckets, so that the same bucket of
+                           // different copies lies in different LDS banks
 
 // Calls f(x) for every logit of a row, the workgroup's lanes striding over it, with several loads in flight per
 // lane (16-byte loads when the row allows: eight per lane and batch).
@@ -306,14 +308,14 @@ __device__ __forceinline__ uint32_t radix_select(Each &&each, double mx_over_t, 
     const int shift = 24 - 8 * round;
     // kRep copies of the histogram, chosen by lane: the logits of a row crowd into a few of the 256 buckets of the
     // leading byte, and LDS serialises atomics of one instruction that hit the same address
-    for (int i = tid; i < 256 * kRep; i += kWarpThreads) {
+    for (int i = tid; i < kHist * kRep; i += kWarpThreads) {
       if constexpr (BY_MASS)
         mass[i] = 0.0;
       else
         cnt[i] = 0;
     }
     __syncthreads();
-    const int rep = (tid & (kRep - 1)) * 256;
+    const int rep = (tid & (kRep - 1)) * kHist;
     each([&](float x) {
       const uint32_t key = order_key(x);
       const bool in_range = round == 0 || (key >> (shift + 8)) == (prefix >> (shift + 8));
@@ -327,11 +329,11 @@ __device__ __forceinline__ uint32_t radix_select(Each &&each, double mx_over_t, 
     if (tid < 256) {   // fold the copies, in order
       if constexpr (BY_MASS) {
         double t = 0.0;
-        for (int r = 0; r < kRep; ++r) t += mass[r * 256 + tid];
+        for (int r = 0; r < kRep; ++r) t += mass[r * kHist + tid];
         mass[tid] = t;
       } else {
         uint32_t t = 0;
-        for (int r = 0; r < kRep; ++r) t += cnt[r * 256 + tid];
+        for (int r = 0; r < kRep; ++r) t += cnt[r * kHist + tid];
         cnt[tid] = t;
       }
     }
@@ -414,6 +416,83 @@ __device__ __forceinline__ float key_value(uint32_t key) {
 constexpr int kSmallK = 128;   // largest top_k the candidate-list path takes
 constexpr int kCand = 2048;    // its candidate list (LDS)
 
+// The k-th largest of the workgroup's per-lane keys mk (k <= number of lanes), found bit by bit with ballot counts:
+// the largest value lo such that at least k lanes have mk >= lo.  The same value in every lane.  One barrier per
+// bit; s_cnt is scratch of 2 x (wavefronts) ints.
+template <bool BF16>
+__device__ __forceinline__ uint32_t kth_largest_lane_key(uint32_t mk, int k, int (*s_cnt)[kWarpThreads / 64]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t lo = 0;
+  // (a bf16 logit's key has sixteen equal low bits, so its sixteen high bits decide)
+  for (int bit = 31; bit >= (BF16 ? 16 : 0); --bit) {
+    const uint32_t c = lo | (1u << bit);
+    const int n_w = __popcll(__ballot(mk >= c));
+    if (lane == 0) s_cnt[bit & 1][wave] = n_w;
+    __syncthreads();
+    int tot = 0;
+#pragma unroll
+    for (int w = 0; w < kWarpThreads / 64; ++w) tot += s_cnt[bit & 1][w];
+    if (tot >= k) lo = c;
+  }
+  if (BF16 && !(lo >> 31)) lo |= 0xFFFFu;   // the low bits of a negative bf16 value's key: lo is that key itself
+  return lo;
+}
+
+// Append `key` to list[] (capacity cap, length *n in LDS) for the lanes with take set: one LDS atomic per wavefront
+// and call instead of one per lane.  *n counts every qualifying token, also past the capacity.
+__device__ __forceinline__ void list_append(bool take, uint32_t key, uint32_t *list, int cap, int *n) {
+  const uint64_t who = __ballot(take);
+  if (!who) return;
+  const int lane = threadIdx.x & 63, leader = __ffsll((unsigned long long)who) - 1;
+  int base = 0;
+  if (lane == leader) base = atomicAdd(n, __popcll(who));
+  base = __shfl(base, leader);
+  if (take) {
+    const int i = base + __popcll(who & ((1ull << lane) - 1));
+    if (i < cap) list[i] = key;
+  }
+}
+
+// Bitonic sort of list[0..n) in descending order, in place, by the whole workgroup; n <= kCand.  Entries n..N-1 (N
+// the next power of two) are filled with 0, which is below every key.
+__device__ __forceinline__ void sort_desc(uint32_t *list, int n) {
+  int N = 64;
+  while (N < n) N <<= 1;
+  for (int i = n + threadIdx.x; i < N; i += kWarpThreads) list[i] = 0u;
+  __syncthreads();
+  for (int k = 2; k <= N; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int i = threadIdx.x; i < N; i += kWarpThreads) {
+        const int o = i ^ j;
+        if (o > i) {
+          const uint32_t a = list[i], b = list[o];
+          const bool desc = (i & k) == 0;
+          if (desc ? a < b : a > b) list[i] = b, list[o] = a;
+        }
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// Sort the n <= kCand keys of cand[] into sorted[] in descending order by rank counting (equal keys are the same
+// value, so their mutual order does not matter) and put the exact fp64 mass of sorted[i] into cmass[i].
+__device__ __forceinline__ void sort_list_with_masses(const uint32_t *cand, int n, uint32_t *sorted, double *cmass,
+                                                      double mx_over_t, double inv_temp) {
+  for (int i = threadIdx.x; i < n; i += kWarpThreads) {
+    const uint32_t ki = cand[i];
+    int rank = 0;
+    for (int j = 0; j < n; ++j) {
+      const uint32_t kj = cand[j];
+      rank += (kj > ki || (kj == ki && j < i)) ? 1 : 0;
+    }
+    sorted[rank] = ki;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < n; i += kWarpThreads) cmass[i] = mass64(key_value(sorted[i]), mx_over_t, inv_temp);
+  __syncthreads();
+}
+
 // top-k with a small k, then top-p, in two passes over the row and without a histogram.  Pass 1: every lane keeps
 // the largest key among its tokens; the k-th largest of these lane maxima (found bit by bit with ballot counts) is a
 // lower bound of the row's k-th largest key, because at least k tokens reach it.  Pass 2: the keys at or above that
@@ -440,51 +519,22 @@ __device__ __forceinline__ bool warp_small_k(const AcceptParams &p, const void *
     const float wm = wave_max(mx);
     if (lane == 0) s_wmax[wave] = wm;
   }
-  uint32_t lo = 0;   // invariant: at least k lanes have mk >= lo (k <= kSmallK < the number of lanes)
-  // (a bf16 logit's key has sixteen equal low bits, so its sixteen high bits decide)
-  for (int bit = 31; bit >= (BF16 ? 16 : 0); --bit) {
-    const uint32_t c = lo | (1u << bit);
-    const int n_w = __popcll(__ballot(mk >= c));
-    if (lane == 0) s_cnt[bit & 1][wave] = n_w;
-    __syncthreads();
-    int tot = 0;
-#pragma unroll
-    for (int w = 0; w < kWarpThreads / 64; ++w) tot += s_cnt[bit & 1][w];
-    if (tot >= k) lo = c;
-  }
+  const uint32_t lo = kth_largest_lane_key<BF16>(mk, k, s_cnt);   // k <= kSmallK < the number of lanes
   float row_max = s_wmax[0];
 #pragma unroll
   for (int w = 1; w < kWarpThreads / 64; ++w) row_max = fmaxf(row_max, s_wmax[w]);
   *row_max_out = row_max;
   const double mx_over_t = (double)row_max * p.inv_temp;
-  if (BF16 && !(lo >> 31)) lo |= 0xFFFFu;   // the low bits of a negative bf16 value's key: lo is that key itself
   const float lo_val = key_value(lo);        // the k-th largest lane maximum (-inf when fewer than k lanes own a token)
   if (tid == 0) s_n = 0;
   __syncthreads();
   // comparing the values is comparing the keys (no NaNs; -0 == +0 on both sides)
-  row_foreach<BF16>(row, p.V, [&](float x) {
-    if (x >= lo_val) {
-      const int i = atomicAdd(&s_n, 1);
-      if (i < kCand) cand[i] = order_key(x);
-    }
-  });
+  row_foreach<BF16>(row, p.V, [&](float x) { list_append(x >= lo_val, order_key(x), cand, kCand, &s_n); });
   __syncthreads();
   const int n_c = s_n;   // >= k
   if (n_c > kCand) return false;
-  for (int i = tid; i < n_c; i += kWarpThreads) {
-    const uint32_t ki = cand[i];
-    int rank = 0;
-    for (int j = 0; j < n_c; ++j) {
-      const uint32_t kj = cand[j];
-      rank += (kj > ki || (kj == ki && j < i)) ? 1 : 0;
-    }
-    sorted[rank] = ki;
-  }
-  __syncthreads();
+  sort_list_with_masses(cand, n_c, sorted, cmass, mx_over_t, p.inv_temp);
   const uint32_t kth = sorted[k - 1];
-  for (int i = tid; i < n_c; i += kWarpThreads)
-    cmass[i] = sorted[i] >= kth ? mass64(key_value(sorted[i]), mx_over_t, p.inv_temp) : 0.0;
-  __syncthreads();
   if (n_c <= 64) {
     // the usual case: the whole list fits one wavefront, lane j holding the j-th largest key and its mass
     if (wave == 0) {
@@ -547,9 +597,101 @@ __device__ __forceinline__ bool warp_small_k(const AcceptParams &p, const void *
   return true;
 }
 
+// top-p without top-k through a candidate list.  One pass gives the exact fp64 mass zk of the whole row (per lane in
+// token order, a butterfly per wavefront, the wavefronts in order) and every lane's largest logit.  The
+// kListRank-th largest of the lane maxima is a value that a bounded number of tokens reach (a rank statistic: about
+// 1400 of a long row whatever the logits' law, when tokens of all sizes are spread evenly over the lanes); the tokens
+// at or above it are listed in a second pass, sorted, given their exact masses, and the kept set is read off the list
+// as the definition says: value groups in descending order while the mass above them is below top_p * zk.  The list
+// is checked exactly: it must hold at least top_p * zk (then every token outside it has at least that much mass
+// above it and is dropped).  When it does not, or when more than kCand tokens qualify, the caller takes the
+// histogram path (returns false, the same in every lane); zk is returned in either case.
+constexpr int kListRank = 768;
+
+template <bool BF16>
+__device__ __forceinline__ bool warp_top_p_list(const AcceptParams &p, const void *row, double mx_over_t, double *red,
+                                                uint32_t *list, double *cmass, double *zk_out, uint32_t *key_min_out,
+                                                double *z_out) {
+  __shared__ int s_cnt[2][kWarpThreads / 64];
+  __shared__ int s_n, s_ok;
+  __shared__ uint32_t s_key;
+  __shared__ double s_z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float mx = -INFINITY;
+  double acc = 0.0;
+  row_foreach<BF16>(row, p.V, [&](float x) {
+    mx = fmaxf(mx, x);
+    acc += mass64(x, mx_over_t, p.inv_temp);
+  });
+  acc = wave_sum(acc);
+  if (lane == 0) red[wave] = acc;
+  const uint32_t lo = kth_largest_lane_key<BF16>(order_key(mx), kListRank, s_cnt);   // (its barriers publish red[])
+  double zk = 0.0;
+#pragma unroll
+  for (int w = 0; w < kWarpThreads / 64; ++w) zk += red[w];
+  *zk_out = zk;
+  const float lo_val = key_value(lo);   // -inf when fewer than kListRank lanes own a token: the whole row is listed
+  if (tid == 0) s_n = 0;
+  __syncthreads();
+  row_foreach<BF16>(row, p.V, [&](float x) { list_append(x >= lo_val, order_key(x), list, kCand, &s_n); });
+  __syncthreads();
+  const int n_c = s_n;
+  if (n_c > kCand || n_c < 1) return false;
+  sort_desc(list, n_c);
+  for (int i = tid; i < n_c; i += kWarpThreads) cmass[i] = mass64(key_value(list[i]), mx_over_t, p.inv_temp);
+  __syncthreads();
+  if (wave == 0) {
+    // lane l owns the list entries [l*per, (l+1)*per); running masses in descending order of the keys
+    const double target = (double)p.top_p * zk;
+    const int per = (n_c + 63) / 64;
+    const int i0 = min(n_c, lane * per), i1 = min(n_c, i0 + per);
+    double own = 0.0;
+    for (int i = i0; i < i1; ++i) own += cmass[i];
+    double incl = own;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const double up = __shfl_up(incl, off);
+      if (lane >= off) incl += up;
+    }
+    const double total = __shfl(incl, 63);
+    const double before = __shfl_up(incl, 1);
+    // first entry with at least `target` of mass before it (n_c if none): the entries before it stay whatever
+    // their value groups; if it lies inside a value group, that group stays as a whole
+    double run = lane ? before : 0.0;
+    int cross = INT_MAX;
+    for (int i = i0; i < i1; ++i) {
+      if (cross == INT_MAX && !(run < target)) cross = i;
+      run += cmass[i];
+    }
+    const uint64_t hits = __ballot(cross != INT_MAX);
+    int first = n_c;
+    if (hits) first = __shfl(cross, __ffsll((unsigned long long)hits) - 1);
+    const uint32_t kref = list[first - 1];   // first >= 1: nothing lies before entry 0
+    int end = INT_MAX;
+    for (int i = max(i0, first); i < i1; ++i)
+      if (end == INT_MAX && list[i] != kref) end = i;
+    const uint64_t ends = __ballot(end != INT_MAX);
+    int kept = n_c;
+    if (ends) kept = __shfl(end, __ffsll((unsigned long long)ends) - 1);
+    double zl = 0.0;
+    for (int i = i0; i < min(i1, kept); ++i) zl += cmass[i];
+    const double z = wave_sum(zl);
+    if (lane == 0) {
+      s_ok = total >= target ? 1 : 0;   // otherwise the kept set continues below the listed tokens
+      s_key = list[kept - 1];
+      s_z = z;
+    }
+  }
+  __syncthreads();
+  if (!s_ok) return false;
+  *key_min_out = s_key;
+  *z_out = s_z;
+  return true;
+}
+
 template <bool BF16>
 __global__ __launch_bounds__(kWarpThreads) void accept_warp_kernel(const AcceptParams p) {
-  __shared__ double mass[256 * kRep];                 // the count histogram shares this storage
+  __shared__ double mass[kHist * kRep];               // the count histogram shares this storage
   uint32_t *cnt = (uint32_t *)mass;
   __shared__ uint32_t s_pick;
   __shared__ double s_above, s_slot;
@@ -575,14 +717,21 @@ __global__ __launch_bounds__(kWarpThreads) void accept_warp_kernel(const AcceptP
     m = s_m;
     const double mx_over_t = (double)m * p.inv_temp;
     key_min = 0;
-    if (p.top_k > 0 && p.top_k < p.V)
+    const bool use_k = p.top_k > 0 && p.top_k < p.V;
+    if (use_k)
       key_min = radix_select<BF16, false>(each_of_row, 0.0, 0.0, 0u, p.top_k, 0.0, cnt, mass, &s_pick, &s_above);
+    bool listed = false;
     if (p.top_p < 1.0f) {
-      const double zk = kept_mass<BF16>(row, p.V, mx_over_t, p.inv_temp, key_min, red, &s_slot);
-      key_min = radix_select<BF16, true>(each_of_row, mx_over_t, p.inv_temp, key_min, 0, (double)p.top_p * zk, cnt,
-                                         mass, &s_pick, &s_above);
+      double zk = 0.0;
+      if (!use_k)   // (the candidate list lives in the histogram's storage)
+        listed = warp_top_p_list<BF16>(p, row, mx_over_t, red, cnt, mass + kCand, &zk, &key_min, &zw);
+      else
+        zk = kept_mass<BF16>(row, p.V, mx_over_t, p.inv_temp, key_min, red, &s_slot);
+      if (!listed)
+        key_min = radix_select<BF16, true>(each_of_row, mx_over_t, p.inv_temp, key_min, 0, (double)p.top_p * zk, cnt,
+                                           mass, &s_pick, &s_above);
     }
-    zw = kept_mass<BF16>(row, p.V, mx_over_t, p.inv_temp, key_min, red, &s_slot);
+    if (!listed) zw = kept_mass<BF16>(row, p.V, mx_over_t, p.inv_temp, key_min, red, &s_slot);
   }
   if (tid == 0) {
     p.warp_key[rw] = key_min;

@@ -156,12 +156,14 @@ def test_warp_large_top_k(oracle):
 
 
 @pytest.mark.parametrize("std,top_k,dtype", [(3.0, 20, "bf16"), (3.0, 20, "f32"), (0.5, 50, "bf16"), (0.5, 50, "f32"),
-                                             (0.0, 5, "f32")])
+                                             (0.0, 5, "f32"), (3.0, 0, "bf16"), (3.0, 0, "f32"), (0.5, 0, "f32"),
+                                             (0.0, 0, "bf16")])
 def test_warp_tied_logits(oracle, std, top_k, dtype):
     """Target logits rounded to whole numbers, so that many tokens tie at every value: ties with the k-th largest
     value all stay, and a value group stays or goes as one under top-p.  With std 3 the candidate list of the warp
     kernel holds a few hundred tied keys; with std 0.5 the k-th value is shared by thousands of tokens, more than the
-    list takes, and with std 0 by the whole row: the histogram path takes over."""
+    list takes, and with std 0 by the whole row: the histogram path takes over.  top_k 0: top-p alone, whose
+    candidate list is proposed by an fp32 histogram and checked exactly."""
     case = W.AcceptCase(f"warp_ties_{std}_{top_k}_{dtype}", 12, 3, 20000, dtype, target_std=max(std, 1.0),
                         temperature=0.7, top_k=top_k, top_p=0.9, point_mass=True, peak=0.0, seed=int(40 + std * 10))
     inp = W.make_accept_inputs(case)
