@@ -24,7 +24,7 @@ def test_more_than_one_gpu_is_refused_with_a_message(n):
 
 
 @pytest.mark.skipif(torch.cuda.is_available(), reason="checks the behaviour of a machine without a GPU")
-@pytest.mark.parametrize("args", [(), ("--kv-commit",), ("--config", "3")])
+@pytest.mark.parametrize("args", [(), ("--kv-commit",), ("--config", "3"), ("--paper-sampling", "qwen3")])
 def test_without_a_gpu_the_compute_legs_fail_loudly(args):
     r = bench(*args)
     assert r.returncode == 2
@@ -41,3 +41,8 @@ def test_planner_leg_prints_one_json_line():
                 "vs_baseline", "dtype", "data", "config", "cpu_baseline"):
         assert key in out
     assert out["value"] > 0 and out["cpu_baseline"]["kind"] == "oracle" and "workload" in out["config"]
+
+
+def test_unknown_sampling_setting_is_refused():
+    r = bench("--paper-sampling", "llama")
+    assert r.returncode == 2 and "invalid choice" in r.stderr and r.stdout.strip() == ""
