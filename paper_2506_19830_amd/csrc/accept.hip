@@ -453,25 +453,88 @@ __device__ __forceinline__ void list_append(bool take, uint32_t key, uint32_t *l
   }
 }
 
+// The tokens of a row with value >= lo_val appended to list[] as keys (see list_append), for bounds that about one
+// token in a hundred reaches, so that nearly every wavefront-wide step of a plain scan would find one.  On 16-byte aligned rows a
+// lane first marks the qualifying ones among the up to 64 tokens of its eight loads in a bit mask (one compare and
+// one bit operation per token); then the marked tokens are appended in rounds, one per lane and round, their values
+// read again (few, and just loaded).
+template <bool BF16>
+__device__ __forceinline__ void row_collect(const void *row, int V, float lo_val, uint32_t *list, int cap, int *n) {
+  constexpr int kPerVec = BF16 ? 8 : 4;
+  constexpr int kInFlight = 8;
+  const int tid = threadIdx.x;
+  if (V % kPerVec != 0) {
+    row_foreach<BF16>(row, V, [&](float x) { list_append(x >= lo_val, order_key(x), list, cap, n); });
+    return;
+  }
+  const int n_vec = V / kPerVec;
+  for (int i0 = tid; i0 < n_vec; i0 += kInFlight * kWarpThreads) {
+    u32x4 w[kInFlight];
+#pragma unroll
+    for (int j = 0; j < kInFlight; ++j) {
+      const int i = i0 + j * kWarpThreads;
+      w[j] = *(const u32x4 *)((const uint8_t *)row + (size_t)(i < n_vec ? i : i0) * 16);
+    }
+    uint64_t marks = 0;   // bit j*kPerVec + e: element e of load j qualifies
+#pragma unroll
+    for (int j = 0; j < kInFlight; ++j) {
+      const bool in = i0 + j * kWarpThreads < n_vec;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t word = w[j][k];
+        if constexpr (BF16) {
+          if (in && bf16_lo(word) >= lo_val) marks |= 1ull << (j * 8 + 2 * k);
+          if (in && bf16_hi(word) >= lo_val) marks |= 1ull << (j * 8 + 2 * k + 1);
+        } else {
+          if (in && as_f32(word) >= lo_val) marks |= 1ull << (j * 4 + k);
+        }
+      }
+    }
+    while (__ballot(marks != 0)) {
+      const bool take = marks != 0;
+      const int bit = take ? __ffsll((unsigned long long)marks) - 1 : 0;
+      marks &= marks - 1;
+      const int j = bit / kPerVec, e = bit - j * kPerVec;
+      const size_t v = (size_t)(i0 + j * kWarpThreads) * kPerVec + e;
+      const float x = take ? load_logit<BF16>(row, v) : 0.f;
+      list_append(take, order_key(x), list, cap, n);
+    }
+  }
+}
+
 // Bitonic sort of list[0..n) in descending order, in place, by the whole workgroup; n <= kCand.  Entries n..N-1 (N
-// the next power of two) are filled with 0, which is below every key.
+// the next power of two, at least 128) are filled with 0, which is below every key.  Compare-exchange steps whose
+// partners are at least 128 apart involve the whole workgroup and end in a barrier; the steps below that stay inside
+// 128-entry blocks, one block per wavefront and one comparator per lane, and need no barrier between them (a
+// wavefront's LDS accesses are carried out in order).
 __device__ __forceinline__ void sort_desc(uint32_t *list, int n) {
-  int N = 64;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int N = 128;
   while (N < n) N <<= 1;
   for (int i = n + threadIdx.x; i < N; i += kWarpThreads) list[i] = 0u;
   __syncthreads();
+  auto exchange = [&](int i, int o, int k) {
+    const uint32_t a = list[i], b = list[o];
+    const bool desc = (i & k) == 0;
+    if (desc ? a < b : a > b) list[i] = b, list[o] = a;
+  };
   for (int k = 2; k <= N; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int i = threadIdx.x; i < N; i += kWarpThreads) {
-        const int o = i ^ j;
-        if (o > i) {
-          const uint32_t a = list[i], b = list[o];
-          const bool desc = (i & k) == 0;
-          if (desc ? a < b : a > b) list[i] = b, list[o] = a;
-        }
+    int j = k >> 1;
+    for (; j >= 128; j >>= 1) {
+      for (int c = threadIdx.x; c < N / 2; c += kWarpThreads) {   // comparator c: a zero bit inserted at j
+        const int i = ((c & ~(j - 1)) << 1) | (c & (j - 1));
+        exchange(i, i | j, k);
       }
       __syncthreads();
     }
+    if (wave * 128 < N) {
+      for (; j > 0; j >>= 1) {
+        const int i = wave * 128 + (((lane & ~(j - 1)) << 1) | (lane & (j - 1)));
+        exchange(i, i | j, k);
+        __builtin_amdgcn_wave_barrier();
+      }
+    }
+    __syncthreads();
   }
 }
 
@@ -529,6 +592,7 @@ __device__ __forceinline__ bool warp_small_k(const AcceptParams &p, const void *
   if (tid == 0) s_n = 0;
   __syncthreads();
   // comparing the values is comparing the keys (no NaNs; -0 == +0 on both sides)
+  // (few tokens qualify here: testing them one by one is cheaper than row_collect's marking)
   row_foreach<BF16>(row, p.V, [&](float x) { list_append(x >= lo_val, order_key(x), cand, kCand, &s_n); });
   __syncthreads();
   const int n_c = s_n;   // >= k
@@ -597,32 +661,32 @@ __device__ __forceinline__ bool warp_small_k(const AcceptParams &p, const void *
   return true;
 }
 
-// top-p without top-k through a candidate list.  One pass gives the exact fp64 mass zk of the whole row (per lane in
-// token order, a butterfly per wavefront, the wavefronts in order) and every lane's largest logit.  The
-// kListRank-th largest of the lane maxima is a value that a bounded number of tokens reach (a rank statistic: about
-// 1400 of a long row whatever the logits' law, when tokens of all sizes are spread evenly over the lanes); the tokens
-// at or above it are listed in a second pass, sorted, given their exact masses, and the kept set is read off the list
-// as the definition says: value groups in descending order while the mass above them is below top_p * zk.  The list
-// is checked exactly: it must hold at least top_p * zk (then every token outside it has at least that much mass
-// above it and is dropped).  When it does not, or when more than kCand tokens qualify, the caller takes the
-// histogram path (returns false, the same in every lane); zk is returned in either case.
+// top-p without top-k through a candidate list.  zk, the exact fp64 mass of the whole row, is the fold of the row's
+// fine-slice sums (accept_rowz_kernel).  One pass gives every lane's largest logit.  The kListRank-th largest of the
+// lane maxima is a value that a bounded number of tokens reach (a rank statistic: about 1400 of a long row whatever
+// the logits' law, when tokens of all sizes are spread evenly over the lanes); the tokens at or above it are listed
+// in a second pass, sorted, given their exact masses, and the kept set is read off the list as the definition says:
+// value groups in descending order while the mass above them is below top_p * zk.  The list is checked exactly: it
+// must hold at least top_p * zk (then every token outside it has at least that much mass above it and is dropped).
+// When it does not, or when more than kCand tokens qualify, the caller takes the histogram path (returns false, the
+// same in every lane); zk is returned in either case.
 constexpr int kListRank = 768;
 
 template <bool BF16>
-__device__ __forceinline__ bool warp_top_p_list(const AcceptParams &p, const void *row, double mx_over_t, double *red,
-                                                uint32_t *list, double *cmass, double *zk_out, uint32_t *key_min_out,
-                                                double *z_out) {
+__device__ __forceinline__ bool warp_top_p_list(const AcceptParams &p, const void *row, const double *zs,
+                                                double mx_over_t, double *red, uint32_t *list, double *cmass,
+                                                double *zk_out, uint32_t *key_min_out, double *z_out) {
   __shared__ int s_cnt[2][kWarpThreads / 64];
   __shared__ int s_n, s_ok;
   __shared__ uint32_t s_key;
   __shared__ double s_z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   float mx = -INFINITY;
+  row_foreach<BF16>(row, p.V, [&](float x) { mx = fmaxf(mx, x); });
+  // zk from the row's fine-slice sums (accept_rowz_kernel), in a fixed order: slice t in lane t, a butterfly per
+  // wavefront, the wavefronts in order
   double acc = 0.0;
-  row_foreach<BF16>(row, p.V, [&](float x) {
-    mx = fmaxf(mx, x);
-    acc += mass64(x, mx_over_t, p.inv_temp);
-  });
+  for (int t = tid; t < p.n_fine; t += kWarpThreads) acc += zs[t];
   acc = wave_sum(acc);
   if (lane == 0) red[wave] = acc;
   const uint32_t lo = kth_largest_lane_key<BF16>(order_key(mx), kListRank, s_cnt);   // (its barriers publish red[])
@@ -633,7 +697,7 @@ __device__ __forceinline__ bool warp_top_p_list(const AcceptParams &p, const voi
   const float lo_val = key_value(lo);   // -inf when fewer than kListRank lanes own a token: the whole row is listed
   if (tid == 0) s_n = 0;
   __syncthreads();
-  row_foreach<BF16>(row, p.V, [&](float x) { list_append(x >= lo_val, order_key(x), list, kCand, &s_n); });
+  row_collect<BF16>(row, p.V, lo_val, list, kCand, &s_n);
   __syncthreads();
   const int n_c = s_n;
   if (n_c > kCand || n_c < 1) return false;
@@ -689,6 +753,38 @@ __device__ __forceinline__ bool warp_top_p_list(const AcceptParams &p, const voi
   return true;
 }
 
+// rowz: grid (n_fine, NB*(K+1)).  fp64 sum of exp((x - max)/T) over one 2048-token fine slice of one target row, for
+// top-p without top-k, whose threshold is a share of the row's whole mass: the row's exponentials are spread over
+// the chip here instead of being one workgroup's pass in the warp kernel.
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void accept_rowz_kernel(const AcceptParams p) {
+  __shared__ float s_wm[kThreads / 64];
+  __shared__ double red[kThreads / 64];
+  const int c = blockIdx.x, rw = blockIdx.y, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  // the row maximum from the slice statistics (exact, so the same value in every workgroup and in the warp kernel)
+  const float *st = p.stats + (size_t)rw * p.n_chunks * 2;
+  float m = -INFINITY;
+  for (int ch = tid; ch < p.n_chunks; ch += kThreads) m = fmaxf(m, st[2 * ch]);
+  m = wave_max(m);
+  if (lane == 0) s_wm[wave] = m;
+  const bool vec = ((size_t)p.V * (BF16 ? 2 : 4)) % 16 == 0;
+  const int vb = c * kFine + tid * kFinePer, v1 = min(p.V, c * kFine + kFine);
+  float x[kFinePer];
+  load_fine<BF16>(p.target, (size_t)rw * p.V, vb, p.V, vec, x);
+  __syncthreads();
+  m = fmaxf(fmaxf(s_wm[0], s_wm[1]), fmaxf(s_wm[2], s_wm[3]));
+  const double mx_over_t = (double)m * p.inv_temp;
+  double acc = 0.0;
+#pragma unroll
+  for (int e = 0; e < kFinePer; ++e)
+    if (vb + e < v1) acc += mass64(x[e], mx_over_t, p.inv_temp);
+  acc = wave_sum(acc);
+  if (lane == 0) red[wave] = acc;
+  __syncthreads();
+  if (tid == 0) p.warp_zs[(size_t)rw * p.n_fine + c] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
 template <bool BF16>
 __global__ __launch_bounds__(kWarpThreads) void accept_warp_kernel(const AcceptParams p) {
   __shared__ double mass[kHist * kRep];               // the count histogram shares this storage
@@ -724,7 +820,8 @@ __global__ __launch_bounds__(kWarpThreads) void accept_warp_kernel(const AcceptP
     if (p.top_p < 1.0f) {
       double zk = 0.0;
       if (!use_k)   // (the candidate list lives in the histogram's storage)
-        listed = warp_top_p_list<BF16>(p, row, mx_over_t, red, cnt, mass + kCand, &zk, &key_min, &zw);
+        listed = warp_top_p_list<BF16>(p, row, p.warp_zs + (size_t)rw * p.n_fine, mx_over_t, red, cnt, mass + kCand,
+                                       &zk, &key_min, &zw);
       else
         zk = kept_mass<BF16>(row, p.V, mx_over_t, p.inv_temp, key_min, red, &s_slot);
       if (!listed)
@@ -1103,6 +1200,11 @@ hipError_t launch_typed(const AcceptParams &p, hipStream_t stream) {
   }
   if (p.warp_key) {
     ProfileScope scope(SLOT_ACCEPT_WARP, stream);
+    if (p.top_p < 1.0f && !(p.top_k > 0 && p.top_k < p.V)) {   // top-p alone needs every target row's whole mass
+      hipLaunchKernelGGL(accept_rowz_kernel<BF16>, dim3(p.n_fine, p.NB * (p.K + 1)), dim3(kThreads), 0, stream, p);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL(accept_warp_kernel<BF16>, dim3(p.NB * (p.K + 1)), dim3(kWarpThreads), 0, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -1144,6 +1246,7 @@ size_t accept_workspace_bytes(int NB, int K, int V, bool bf16, int *n_chunks_out
   b += align_up((size_t)NB * (K + 1) * sizeof(uint32_t));                  // warp_key
   b += align_up((size_t)NB * (K + 1) * sizeof(double));                    // warp_z
   b += align_up((size_t)NB * (K + 1) * sizeof(float));                     // warp_max
+  b += align_up((size_t)NB * (K + 1) * n_fine * sizeof(double));           // warp_zs
   return b;
 }
 
@@ -1167,6 +1270,8 @@ void accept_carve_workspace(AcceptParams &p, void *ws) {
   p.warp_z = warp ? (double *)at : nullptr;
   at += align_up((size_t)p.NB * (p.K + 1) * sizeof(double));
   p.warp_max = warp ? (float *)at : nullptr;
+  at += align_up((size_t)p.NB * (p.K + 1) * sizeof(float));
+  p.warp_zs = warp ? (double *)at : nullptr;
 }
 
 hipError_t launch_accept(const AcceptParams &p, hipStream_t stream) {

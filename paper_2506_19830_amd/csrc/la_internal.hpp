@@ -105,6 +105,7 @@ struct AcceptParams {
   uint32_t *warp_key;          // [NB*(K+1)] order-preserving key of the smallest logit a row keeps
   double *warp_z;              // [NB*(K+1)] sum exp((x - max)/T) over the kept tokens
   float *warp_max;             // [NB*(K+1)] row maximum (raw logits)
+  double *warp_zs;             // [NB*(K+1), n_fine] fp64 slice sums of exp((x - max)/T) of every target row (top-p alone)
 };
 
 size_t accept_workspace_bytes(int NB, int K, int V, bool bf16, int *n_chunks_out, int *n_fine_out);
