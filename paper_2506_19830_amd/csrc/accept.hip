@@ -177,26 +177,38 @@ __device__ __forceinline__ uint32_t order_key(float x) {
 // by a two-term reduction (k * ln2_hi is exact for |k| < 2^11), e^r by its Taylor polynomial of degree 13
 // (remainder < 5e-18), then the scaling by 2^k, which also takes results below the normal range to denormals / zero.
 // About 20 fp64 instructions, against several times that for the general library routine.
+// a * b + c with the constant c read from scalar registers (left to itself the compiler copies every constant of the
+// polynomial into a vector register pair first, two moves per step, to use the two-address form of the instruction)
+__device__ __forceinline__ double fma_const(double a, double b, double c) {
+  double d;
+  asm("v_fma_f64 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "s"(c));
+  return d;
+}
+
 __device__ __forceinline__ double exp64(double y) {
-  y = fmin(fmax(y, -750.0), 709.0);
-  const double k = __builtin_rint(y * 1.4426950408889634074);
+  y = fmax(y, -750.0);   // (y <= 0 up to rounding: x never exceeds the row maximum)
+  // k = nearest integer to y * log2(e): adding 1.5 * 2^52 leaves it in the low bits of the sum (as a double by taking
+  // the constant off again, as an integer in the low word of the bit pattern); the rounding and conversion
+  // instructions this replaces run at a quarter of the rate of an addition
+  const double shifted = __builtin_fma(y, 1.4426950408889634074, 6755399441055744.0);
+  const double k = shifted - 6755399441055744.0;
+  const int ki = (int)(uint32_t)__builtin_bit_cast(uint64_t, shifted);
   double r = __builtin_fma(-k, 6.93147180369123816490e-01, y);
   r = __builtin_fma(-k, 1.90821492927058770002e-10, r);
-  double q = 1.0 / 6227020800.0;
-  q = __builtin_fma(q, r, 1.0 / 479001600.0);
-  q = __builtin_fma(q, r, 1.0 / 39916800.0);
-  q = __builtin_fma(q, r, 1.0 / 3628800.0);
-  q = __builtin_fma(q, r, 1.0 / 362880.0);
-  q = __builtin_fma(q, r, 1.0 / 40320.0);
-  q = __builtin_fma(q, r, 1.0 / 5040.0);
-  q = __builtin_fma(q, r, 1.0 / 720.0);
-  q = __builtin_fma(q, r, 1.0 / 120.0);
-  q = __builtin_fma(q, r, 1.0 / 24.0);
-  q = __builtin_fma(q, r, 1.0 / 6.0);
+  double q = fma_const(r, 1.0 / 6227020800.0, 1.0 / 479001600.0);
+  q = fma_const(q, r, 1.0 / 39916800.0);
+  q = fma_const(q, r, 1.0 / 3628800.0);
+  q = fma_const(q, r, 1.0 / 362880.0);
+  q = fma_const(q, r, 1.0 / 40320.0);
+  q = fma_const(q, r, 1.0 / 5040.0);
+  q = fma_const(q, r, 1.0 / 720.0);
+  q = fma_const(q, r, 1.0 / 120.0);
+  q = fma_const(q, r, 1.0 / 24.0);
+  q = fma_const(q, r, 1.0 / 6.0);
   q = __builtin_fma(q, r, 0.5);
   q = __builtin_fma(q, r, 1.0);
   q = __builtin_fma(q, r, 1.0);
-  return __builtin_ldexp(q, (int)k);
+  return __builtin_ldexp(q, ki);
 }
 
 // fp64 probability mass (unnormalised) of one logit: exp(x/T - max/T)
@@ -753,14 +765,18 @@ __device__ __forceinline__ bool warp_top_p_list(const AcceptParams &p, const voi
   return true;
 }
 
-// rowz: grid (n_fine, NB*(K+1)).  fp64 sum of exp((x - max)/T) over one 2048-token fine slice of one target row, for
-// top-p without top-k, whose threshold is a share of the row's whole mass: the row's exponentials are spread over
-// the chip here instead of being one workgroup's pass in the warp kernel.
+// rowz: grid (groups of kRowzGroup fine slices, NB*(K+1)).  fp64 sum of exp((x - max)/T) over each 2048-token fine
+// slice of one target row, for top-p without top-k, whose threshold is a share of the row's whole mass: the row's
+// exponentials are spread over the chip here instead of being one workgroup's pass in the warp kernel.  A workgroup
+// takes several slices so that its start-up (the row maximum from the slice statistics) is shared and all its loads
+// are in flight together.
+constexpr int kRowzGroup = 4;
+
 template <bool BF16>
 __global__ __launch_bounds__(kThreads) void accept_rowz_kernel(const AcceptParams p) {
   __shared__ float s_wm[kThreads / 64];
-  __shared__ double red[kThreads / 64];
-  const int c = blockIdx.x, rw = blockIdx.y, tid = threadIdx.x;
+  __shared__ double red[kRowzGroup][kThreads / 64];
+  const int c0 = blockIdx.x * kRowzGroup, rw = blockIdx.y, tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   // the row maximum from the slice statistics (exact, so the same value in every workgroup and in the warp kernel)
   const float *st = p.stats + (size_t)rw * p.n_chunks * 2;
@@ -769,20 +785,24 @@ __global__ __launch_bounds__(kThreads) void accept_rowz_kernel(const AcceptParam
   m = wave_max(m);
   if (lane == 0) s_wm[wave] = m;
   const bool vec = ((size_t)p.V * (BF16 ? 2 : 4)) % 16 == 0;
-  const int vb = c * kFine + tid * kFinePer, v1 = min(p.V, c * kFine + kFine);
-  float x[kFinePer];
-  load_fine<BF16>(p.target, (size_t)rw * p.V, vb, p.V, vec, x);
+  float x[kRowzGroup][kFinePer];
+#pragma unroll
+  for (int g = 0; g < kRowzGroup; ++g)   // (slices past the row read as -inf)
+    load_fine<BF16>(p.target, (size_t)rw * p.V, (c0 + g) * kFine + tid * kFinePer, p.V, vec, x[g]);
   __syncthreads();
   m = fmaxf(fmaxf(s_wm[0], s_wm[1]), fmaxf(s_wm[2], s_wm[3]));
   const double mx_over_t = (double)m * p.inv_temp;
-  double acc = 0.0;
 #pragma unroll
-  for (int e = 0; e < kFinePer; ++e)
-    if (vb + e < v1) acc += mass64(x[e], mx_over_t, p.inv_temp);
-  acc = wave_sum(acc);
-  if (lane == 0) red[wave] = acc;
+  for (int g = 0; g < kRowzGroup; ++g) {
+    double acc = 0.0;
+#pragma unroll
+    for (int e = 0; e < kFinePer; ++e) acc += mass64(x[g][e], mx_over_t, p.inv_temp);   // (past V: -inf, mass 0)
+    acc = wave_sum(acc);
+    if (lane == 0) red[g][wave] = acc;
+  }
   __syncthreads();
-  if (tid == 0) p.warp_zs[(size_t)rw * p.n_fine + c] = (red[0] + red[1]) + (red[2] + red[3]);
+  if (tid < kRowzGroup && c0 + tid < p.n_fine)
+    p.warp_zs[(size_t)rw * p.n_fine + c0 + tid] = (red[tid][0] + red[tid][1]) + (red[tid][2] + red[tid][3]);
 }
 
 template <bool BF16>
@@ -947,7 +967,7 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(const AcceptPar
     p.rowmax[2 * nb] = mt;
     p.rowmax[2 * nb + 1] = mq;
   }
-  const int v0 = c * kFine, v1 = min(p.V, v0 + kFine);
+  const int v0 = c * kFine;
   const size_t trow = ((size_t)nb * (p.K + 1) + n) * p.V;
   const size_t drow = ((size_t)nb * p.K + (n < p.K ? n : 0)) * p.V;
   const double mt_t = (double)mt * p.inv_temp, mq_t = (double)mq * p.inv_temp;
@@ -959,11 +979,11 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(const AcceptPar
   load_fine<BF16>(p.target, trow, vb, p.V, vec, tx);
   if (with_draft) load_fine<BF16>(p.draft, drow, vb, p.V, vec, dx);
 #pragma unroll
+  // no bounds test per token: load_fine gives -inf past V, whose mass is exactly 0, and the eight exponentials of a
+  // lane can then be evaluated side by side instead of one dependent chain after the other
   for (int e = 0; e < kFinePer; ++e) {
-    if (vb + e < v1) {
-      st += mass64(tx[e], mt_t, p.inv_temp);
-      if (with_draft) sq += mass64(dx[e], mq_t, p.inv_temp);
-    }
+    st += mass64(tx[e], mt_t, p.inv_temp);
+    if (with_draft) sq += mass64(dx[e], mq_t, p.inv_temp);
   }
   st = wave_sum(st);
   sq = wave_sum(sq);
@@ -1052,7 +1072,7 @@ __global__ __launch_bounds__(kThreads) void accept_resid_kernel(const AcceptPara
   __shared__ double red[2][kThreads / 64];
   const int c = blockIdx.x, nb = blockIdx.y, tid = threadIdx.x;
   const ResidCtx<BF16> ctx = make_ctx<BF16>(p, nb, buf, slots);
-  const int v0 = c * kFine, v1 = min(p.V, v0 + kFine);
+  const int v0 = c * kFine;
   double sr = 0.0, sp = 0.0;
   const bool vec = ((size_t)p.V * (BF16 ? 2 : 4)) % 16 == 0;
   const int vb = v0 + tid * kFinePer;
@@ -1060,13 +1080,11 @@ __global__ __launch_bounds__(kThreads) void accept_resid_kernel(const AcceptPara
   load_fine<BF16>(ctx.target, ctx.trow, vb, p.V, vec, tx);
   if (ctx.has_draft) load_fine<BF16>(ctx.draft, ctx.drow, vb, p.V, vec, dx);
 #pragma unroll
-  for (int e = 0; e < kFinePer; ++e) {
-    if (vb + e < v1) {
-      double r, pm;
-      ctx.eval(vb + e, tx[e], ctx.has_draft ? dx[e] : 0.f, r, pm);
-      sr += r;
-      sp += pm;
-    }
+  for (int e = 0; e < kFinePer; ++e) {   // (past V: -inf, no mass of either kind)
+    double r, pm;
+    ctx.eval(vb + e, tx[e], ctx.has_draft ? dx[e] : 0.f, r, pm);
+    sr += r;
+    sp += pm;
   }
   double *ls = p.lane_sums + (((size_t)nb * p.n_fine + c) * kThreads + tid) * 2;
   ls[0] = sr;
@@ -1201,7 +1219,8 @@ hipError_t launch_typed(const AcceptParams &p, hipStream_t stream) {
   if (p.warp_key) {
     ProfileScope scope(SLOT_ACCEPT_WARP, stream);
     if (p.top_p < 1.0f && !(p.top_k > 0 && p.top_k < p.V)) {   // top-p alone needs every target row's whole mass
-      hipLaunchKernelGGL(accept_rowz_kernel<BF16>, dim3(p.n_fine, p.NB * (p.K + 1)), dim3(kThreads), 0, stream, p);
+      hipLaunchKernelGGL(accept_rowz_kernel<BF16>, dim3((p.n_fine + kRowzGroup - 1) / kRowzGroup, p.NB * (p.K + 1)),
+                         dim3(kThreads), 0, stream, p);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
     }
