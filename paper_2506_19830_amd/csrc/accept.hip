@@ -93,7 +93,7 @@ struct StatsShape {
 };
 
 template <bool BF16, bool VEC>
-__global__ __launch_bounds__(kThreads) void accept_stats_kernel(const AcceptParams p) {
+__global__ __launch_bounds__(kThreads, 6) void accept_stats_kernel(const AcceptParams p) {
   using Sh = StatsShape<BF16>;
   __shared__ float red[2][kThreads / 64];
   const int c = blockIdx.x, rw = blockIdx.y;
