@@ -119,6 +119,9 @@ WARP_CASES = [
     W.AcceptCase("warp_r1_setting", 8, 8, 152064, "bf16", temperature=0.6, top_p=0.95, point_mass=True, peak=11.0,
                  seed=28),
     W.AcceptCase("warp_dense_152k_f32", 4, 4, 152064, "f32", temperature=0.6, top_k=20, top_p=0.95, seed=29),
+    # top-p alone on fp32 logits and dense drafts at full vocabulary (the slice-sum kernel and the 32-bit key search)
+    W.AcceptCase("warp_topp_152k_f32", 4, 4, 152064, "f32", temperature=0.6, top_p=0.95, seed=30),
+    W.AcceptCase("warp_topp_flat_152k_bf16", 4, 3, 152064, "bf16", target_std=1.0, temperature=1.0, top_p=0.9, seed=34),
 ]
 
 
