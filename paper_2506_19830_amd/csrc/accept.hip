@@ -21,12 +21,16 @@
 //           then the lane inside it (scan of the stored per-lane sums), then the token
 //           among that lane's 8 (re-evaluated by one lane).
 //   warp    (only with top-k / top-p) one workgroup per target row: the smallest logit the row keeps and the
-//           mass of the kept tokens, by two radix selections over an order-preserving key of the logit: the
-//           k-th largest by count, then among those the value at which the descending cumulative mass reaches
-//           top_p of the kept mass.  Both filters are predicates on a token's value (keep v iff fewer than k
+//           mass of the kept tokens.  Both filters are predicates on a token's value (keep v iff fewer than k
 //           tokens are larger; keep v iff the mass of the larger kept tokens is below top_p * Z_k), so equal
-//           logits are never split and nothing has to be sorted.  decide / resid / pick then use
+//           logits are never split.  With a small k, or with top-p alone, a bound taken from the lanes' largest
+//           logits leaves a short list of candidate tokens, which is sorted and walked in descending order;
+//           otherwise (and whenever such a list overflows or falls short) two radix selections over an
+//           order-preserving key of the logit: the k-th largest by count, then among those the value at which
+//           the descending cumulative mass reaches top_p of the kept mass.  decide / resid / pick then use
 //           p(v) = [key(v) >= key_min] * exp((x_v - max)/T) / Z_kept for the target rows.
+//   rowz    (only with top-p alone) grid (fine-slice groups, target rows): the fp64 mass of every target row in
+//           fine slices, which warp folds: top-p's threshold is a share of the whole row's mass.
 // The two resampling rows are re-read twice (2 of the 2K+1 rows of a branch; cache hits).
 // fp64 there makes the blocked running sum agree with a sequential one to ~1e-16, so the
 // drawn token does not depend on the summation order.
