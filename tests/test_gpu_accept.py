@@ -183,6 +183,33 @@ def test_warp_tied_logits(oracle, std, top_k, dtype):
         assert p[got["next_token"][nb]] > 0
 
 
+def random_warp_case(idx):
+    rng = np.random.default_rng(7000 + idx)
+    V = int(rng.choice([1000, 6000, 8192, 20000, 50257, 152064]))
+    K = int(rng.choice([1, 2, 4]))
+    NB = int(rng.choice([2, 5, 12])) if V <= 20000 else int(rng.choice([1, 3]))
+    top_k = int(rng.choice([0, 0, 3, 64, 128, 129, 1000]))
+    top_p = float(rng.choice([1.0, 0.999, 0.95, 0.7, 0.3, 0.05]))
+    if top_k == 0 and top_p == 1.0:
+        top_p = 0.9
+    return W.AcceptCase(f"rand_warp{idx}", NB, K, V, str(rng.choice(["f32", "bf16"])),
+                        target_std=float(rng.choice([0.5, 1.0, 3.0, 6.0])),
+                        draft_noise_std=float(rng.choice([0.3, 1.0])),
+                        temperature=float(rng.choice([1.0, 0.6, 1.5, 0.3])), seed=7000 + idx, top_k=top_k, top_p=top_p,
+                        point_mass=bool(rng.integers(0, 2)), peak=float(rng.choice([0.0, 4.0, 9.0])))
+
+
+@pytest.mark.parametrize("idx", range(28))
+def test_warp_random_settings(oracle, idx):
+    """Vocabulary, dtype, spread of the logits (a flat row keeps thousands of tokens under top-p, a peaked one a
+    handful), temperature, top_k on both sides of the candidate-list limit and top_p from nearly nothing to nearly
+    everything, drawn at random: whichever form of the warp kernel a row takes, the result is the oracle's."""
+    case = random_warp_case(idx)
+    print(f"  top_k={case.top_k} top_p={case.top_p} std={case.target_std} T={case.temperature} "
+          f"point_mass={case.point_mass}", flush=True)
+    check(oracle, case)
+
+
 # ------------------------------------------------------------------------------------------ random shapes
 
 def random_accept_case(idx):
