@@ -470,10 +470,10 @@ __device__ __forceinline__ void list_append(bool take, uint32_t key, uint32_t *l
 }
 
 // The tokens of a row with value >= lo_val appended to list[] as keys (see list_append), for bounds that about one
-// token in a hundred reaches, so that nearly every wavefront-wide step of a plain scan would find one.  On 16-byte aligned rows a
-// lane first marks the qualifying ones among the up to 64 tokens of its eight loads in a bit mask (one compare and
-// one bit operation per token); then the marked tokens are appended in rounds, one per lane and round, their values
-// read again (few, and just loaded).
+// token in a hundred reaches, so that nearly every wavefront-wide step of a plain scan would find one.  On 16-byte
+// aligned rows a lane first marks the qualifying ones among the up to 64 tokens of its eight loads in a bit mask (one
+// compare and one bit operation per token); then the marked tokens are appended in rounds, one per lane and round,
+// their values read again (few, and just loaded).
 template <bool BF16>
 __device__ __forceinline__ void row_collect(const void *row, int V, float lo_val, uint32_t *list, int cap, int *n) {
   constexpr int kPerVec = BF16 ? 8 : 4;
