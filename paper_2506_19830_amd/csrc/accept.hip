@@ -1001,23 +1001,42 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(const AcceptPar
 
 constexpr int kMaxFine = 1024;   // fine slices per row the fp64 kernels can stage in LDS (vocab <= 2M)
 
-// Sum of n <= kMaxFine doubles, the same value in every lane of the workgroup and in every workgroup that folds the
-// same terms (fixed association: per lane its terms in index order, a butterfly inside each wavefront, the
-// wavefronts in order).  The terms are also left in buf[0..n).
-__device__ __forceinline__ double fold64_block(const double *v, int n, double *buf, double *slot) {
-  __shared__ double fold_red[kThreads / 64];
-  double acc = 0.0;
-  for (int c = threadIdx.x; c < n; c += kThreads) {
-    const double t = v[c];
-    buf[c] = t;
-    acc += t;
+// Two rows of n <= kMaxFine doubles each, folded together so that their loads are one round trip.  load: a lane's
+// terms (index tid + kThreads*j) into registers.  sum: the two sums, the same values in every lane of the workgroup
+// and in every workgroup that folds the same terms (fixed association: per lane its terms in index order, a
+// butterfly inside each wavefront, the wavefronts in order); with buf0 / buf1 given the terms are also left there.
+struct FoldPair {
+  double a[kMaxFine / kThreads], b[kMaxFine / kThreads];
+  __device__ __forceinline__ void load(const double *v0, const double *v1, int n) {
+#pragma unroll
+    for (int j = 0; j < kMaxFine / kThreads; ++j) {
+      const int c = threadIdx.x + kThreads * j;
+      a[j] = c < n ? v0[c] : 0.0;
+      b[j] = c < n ? v1[c] : 0.0;
+    }
   }
-  acc = wave_sum(acc);
-  __syncthreads();   // fold_red free again (a previous call's readers are past their reads)
-  if ((threadIdx.x & 63) == 0) fold_red[threadIdx.x >> 6] = acc;
-  __syncthreads();
-  return (fold_red[0] + fold_red[1]) + (fold_red[2] + fold_red[3]);
-}
+  __device__ __forceinline__ void sum(int n, double *buf0, double *buf1, double *s0, double *s1) const {
+    __shared__ double fold_red[2][kThreads / 64];
+    double x = 0.0, y = 0.0;
+#pragma unroll
+    for (int j = 0; j < kMaxFine / kThreads; ++j) {
+      const int c = threadIdx.x + kThreads * j;
+      if (c < n) {
+        if (buf0) buf0[c] = a[j];
+        if (buf1) buf1[c] = b[j];
+        x += a[j];
+        y += b[j];
+      }
+    }
+    x = wave_sum(x);
+    y = wave_sum(y);
+    __syncthreads();   // fold_red free again (a previous call's readers are past their reads)
+    if ((threadIdx.x & 63) == 0) fold_red[0][threadIdx.x >> 6] = x, fold_red[1][threadIdx.x >> 6] = y;
+    __syncthreads();
+    *s0 = (fold_red[0][0] + fold_red[0][1]) + (fold_red[0][2] + fold_red[0][3]);
+    *s1 = (fold_red[1][0] + fold_red[1][1]) + (fold_red[1][2] + fold_red[1][3]);
+  }
+};
 
 // residual mass and target mass of the tokens of branch nb at position n, fp64
 template <bool BF16>
@@ -1041,8 +1060,10 @@ struct ResidCtx {
 };
 
 template <bool BF16>
-__device__ __forceinline__ ResidCtx<BF16> make_ctx(const AcceptParams &p, int nb, double *buf, double *slots) {
+__device__ __forceinline__ ResidCtx<BF16> make_ctx(const AcceptParams &p, int nb) {
   ResidCtx<BF16> x;
+  FoldPair zs;   // the slice shares of the two normalisers: requested together with everything else below
+  zs.load(p.zsum + ((size_t)nb * 2 + 0) * p.n_fine, p.zsum + ((size_t)nb * 2 + 1) * p.n_fine, p.n_fine);
   const int n = p.n_acc[nb];
   x.target = p.target;
   x.draft = p.draft;
@@ -1053,8 +1074,8 @@ __device__ __forceinline__ ResidCtx<BF16> make_ctx(const AcceptParams &p, int nb
   x.inv_temp = p.inv_temp;
   x.mt = (double)p.rowmax[2 * nb] * p.inv_temp;
   x.mq = (double)p.rowmax[2 * nb + 1] * p.inv_temp;
-  double zt = fold64_block(p.zsum + ((size_t)nb * 2 + 0) * p.n_fine, p.n_fine, buf, slots);
-  double zq = fold64_block(p.zsum + ((size_t)nb * 2 + 1) * p.n_fine, p.n_fine, buf, slots + 1);
+  double zt, zq;
+  zs.sum(p.n_fine, nullptr, nullptr, &zt, &zq);
   if (!x.has_draft) zq = 1.0;
   x.key_min = 0;
   if (p.warp_key) {   // the kept mass replaces the row's full normaliser
@@ -1071,11 +1092,9 @@ __device__ __forceinline__ ResidCtx<BF16> make_ctx(const AcceptParams &p, int nb
 // ---------------------------------------------------------------------------------------------
 template <bool BF16>
 __global__ __launch_bounds__(kThreads) void accept_resid_kernel(const AcceptParams p) {
-  __shared__ double slots[2];
-  __shared__ double buf[kMaxFine];
   __shared__ double red[2][kThreads / 64];
   const int c = blockIdx.x, nb = blockIdx.y, tid = threadIdx.x;
-  const ResidCtx<BF16> ctx = make_ctx<BF16>(p, nb, buf, slots);
+  const ResidCtx<BF16> ctx = make_ctx<BF16>(p, nb);
   const int v0 = c * kFine;
   double sr = 0.0, sp = 0.0;
   const bool vec = ((size_t)p.V * (BF16 ? 2 : 4)) % 16 == 0;
@@ -1108,21 +1127,25 @@ __global__ __launch_bounds__(kThreads) void accept_resid_kernel(const AcceptPara
 // ---------------------------------------------------------------------------------------------
 template <bool BF16>
 __global__ __launch_bounds__(kThreads) void accept_pick_kernel(const AcceptParams p) {
-  __shared__ double slots[2];
-  __shared__ double buf[kMaxFine];
+  __shared__ double buf0[kMaxFine], buf1[kMaxFine];   // slice sums of the residual and of p
   __shared__ double s_before;
   __shared__ double wave_tot[kThreads / 64];
   __shared__ int s_slice, s_lane, s_last_lane;
   const int nb = blockIdx.x, tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const ResidCtx<BF16> ctx = make_ctx<BF16>(p, nb, buf, slots);
+  FoldPair rs;   // requested before the context's own loads, so that both arrive in one round trip
+  rs.load(p.rsum + ((size_t)nb * 2 + 0) * p.n_fine, p.rsum + ((size_t)nb * 2 + 1) * p.n_fine, p.n_fine);
   const double u = (double)p.u_sample[nb];
+  const ResidCtx<BF16> ctx = make_ctx<BF16>(p, nb);
   // total residual mass; without mass (rounding only) the draw is from p_n itself
+  double S, Sp;
+  rs.sum(p.n_fine, buf0, buf1, &S, &Sp);
   int mode = 0;
-  double S = fold64_block(p.rsum + ((size_t)nb * 2 + 0) * p.n_fine, p.n_fine, buf, slots);
+  const double *buf = buf0;
   if (!(S > 0.0)) {   // uniform
     mode = 1;
-    S = fold64_block(p.rsum + ((size_t)nb * 2 + 1) * p.n_fine, p.n_fine, buf, slots);
+    S = Sp;
+    buf = buf1;
   }
   const double thr = u * S;
   if (wave == 0) {
@@ -1185,20 +1208,28 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(const AcceptParam
   __syncthreads();
   const int pick_lane = s_lane != INT_MAX ? s_lane : s_last_lane;
   if (tid == pick_lane) {
-    const int v0 = cs * kFine + tid * kFinePer, v1 = min(p.V, cs * kFine + kFine);
+    // the lane's eight tokens once more: all loads first, then the eight masses side by side (tokens past V read as
+    // -inf and have no mass), then the walk
+    const int v0 = cs * kFine + tid * kFinePer;
+    const bool vec = ((size_t)p.V * (BF16 ? 2 : 4)) % 16 == 0;
+    float tx[kFinePer], dx[kFinePer];
+    load_fine<BF16>(ctx.target, ctx.trow, v0, p.V, vec, tx);
+    if (ctx.has_draft) load_fine<BF16>(ctx.draft, ctx.drow, v0, p.V, vec, dx);
+    double mass[kFinePer];
+#pragma unroll
+    for (int e = 0; e < kFinePer; ++e) {
+      double r, pm;
+      ctx.eval(v0 + e, tx[e], ctx.has_draft ? dx[e] : 0.f, r, pm);
+      mass[e] = mode ? pm : r;
+    }
     double run = lo;
     int tok = -1, last = -1;
+#pragma unroll
     for (int e = 0; e < kFinePer; ++e) {
-      const int v = v0 + e;
-      if (v >= v1) break;
-      double r, pm;
-      ctx.eval(v, load_logit<BF16>(ctx.target, ctx.trow + v),
-               ctx.has_draft ? load_logit<BF16>(ctx.draft, ctx.drow + v) : 0.f, r, pm);
-      const double mass = mode ? pm : r;
-      run += mass;
-      if (mass > 0.0) {
-        last = v;
-        if (tok < 0 && run > thr) tok = v;
+      run += mass[e];
+      if (mass[e] > 0.0) {
+        last = v0 + e;
+        if (tok < 0 && run > thr) tok = v0 + e;
       }
     }
     p.next_token[nb] = tok >= 0 ? tok : last;
