@@ -210,6 +210,27 @@ def test_warp_random_settings(oracle, idx):
     check(oracle, case)
 
 
+@pytest.mark.parametrize("case", [
+    W.AcceptCase("huge_vocab_dense", 2, 2, 600_000, "bf16", seed=51),                       # 293 fine slices
+    W.AcceptCase("max_vocab_dense", 1, 1, 1 << 21, "f32", seed=52),                         # 1024 fine slices: the limit
+    W.AcceptCase("max_vocab_lookup_topk", 1, 2, 1 << 21, "bf16", temperature=0.6, top_k=20, top_p=0.95,
+                 point_mass=True, peak=9.0, seed=53),
+    W.AcceptCase("huge_vocab_lookup_topp", 2, 1, 600_000, "f32", temperature=0.6, top_p=0.9, point_mass=True,
+                 peak=9.0, seed=54),
+], ids=lambda c: c.name)
+def test_accept_largest_vocabularies(oracle, case):
+    """Vocabularies with more fine slices than a workgroup has lanes, up to the largest one the library takes: the
+    folds and scans over the slice sums then run several terms per lane."""
+    check(oracle, case)
+
+
+def test_vocabulary_above_the_limit_is_refused():
+    from paper_2506_19830_amd import binding as B
+    desc = B.make_accept_desc(num_branches=1, num_draft=1, vocab=(1 << 21) + 1, logits_dtype="bf16")
+    with pytest.raises(B.LaError):
+        B.la_spec_accept_workspace(desc)
+
+
 # ------------------------------------------------------------------------------------------ random shapes
 
 def random_accept_case(idx):
