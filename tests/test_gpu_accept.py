@@ -213,6 +213,8 @@ def test_warp_random_settings(oracle, idx):
 @pytest.mark.parametrize("case", [
     W.AcceptCase("huge_vocab_dense", 2, 2, 600_000, "bf16", seed=51),                       # 293 fine slices
     W.AcceptCase("max_vocab_dense", 1, 1, 1 << 21, "f32", seed=52),                         # 1024 fine slices: the limit
+    # nine rows of 256 statistics slices: more than a workgroup of the decide kernel stages in LDS at once
+    W.AcceptCase("max_vocab_dense_k4", 1, 4, 1 << 21, "f32", draft_noise_std=0.3, seed=55),
     W.AcceptCase("max_vocab_lookup_topk", 1, 2, 1 << 21, "bf16", temperature=0.6, top_k=20, top_p=0.95,
                  point_mass=True, peak=9.0, seed=53),
     W.AcceptCase("huge_vocab_lookup_topp", 2, 1, 600_000, "f32", temperature=0.6, top_p=0.9, point_mass=True,
