@@ -397,6 +397,16 @@ LA_API la_status la_calibrate_mfma(int32_t workgroups, int32_t iters, float *sin
 LA_API la_status la_calibrate_read(const void *src, size_t bytes, uint32_t *sink, void *hip_stream);
 
 /* ------------------------------------------------------------------------- *
+ *  Self-test hook (not part of the verification path): out[i] = exp(y[i]) as
+ *  the fp64 resampling path of la_spec_accept evaluates it (its own routine:
+ *  two-term argument reduction, degree-13 polynomial, ldexp; meant for
+ *  y <= 0, arguments below -750 give 0), so that its accuracy can be checked
+ *  against a reference exponential.  y, out: dev, n doubles each, n >= 1.
+ *  Only enqueues a kernel.
+ * ------------------------------------------------------------------------- */
+LA_API la_status la_selftest_exp64(const double *y, double *out, size_t n, void *hip_stream);
+
+/* ------------------------------------------------------------------------- *
  *  Diagnostics
  * ------------------------------------------------------------------------- */
 LA_API const char *la_status_string(la_status s);

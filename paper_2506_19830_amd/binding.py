@@ -26,7 +26,7 @@ _TORCH_DTYPES = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch
 EXPORTED_SYMBOLS = (
     "la_verify_attention_workspace", "la_verify_attention", "la_verify_attention_nested", "la_verify_attention_tree", "la_kv_commit",
     "la_kv_commit_tree", "la_step_select_tree",
-    "la_calibrate_mfma", "la_calibrate_read", "la_step_select", "la_speedup_step_sync", "la_speedup_step_async", "la_speedup_token", "la_plan_budget",
+    "la_calibrate_mfma", "la_calibrate_read", "la_selftest_exp64", "la_step_select", "la_speedup_step_sync", "la_speedup_step_async", "la_speedup_token", "la_plan_budget",
     "la_spec_accept_workspace",
     "la_spec_accept",
     "la_status_string", "la_profile_enable", "la_profile_select", "la_profile_collect", "la_profile_num_kernels", "la_profile_get",
@@ -105,6 +105,8 @@ def load() -> ctypes.CDLL:
         lib.la_calibrate_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
         lib.la_calibrate_read.restype = ctypes.c_int
         lib.la_calibrate_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+        lib.la_selftest_exp64.restype = ctypes.c_int
+        lib.la_selftest_exp64.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.la_step_select.restype = ctypes.c_int
         lib.la_step_select.argtypes = [ctypes.c_int32, ctypes.c_int32] + [vp] * 7
         lib.la_step_select_tree.restype = ctypes.c_int
@@ -271,6 +273,13 @@ def la_calibrate_read(src, sink) -> int:
     if st:
         raise LaError(st, "la_calibrate_read")
     return nbytes // 16 * 16
+
+
+def la_selftest_exp64(y, out) -> None:
+    """``out[i] = exp(y[i])`` as the fp64 resampling path of ``la_spec_accept`` evaluates it (device float64 tensors)."""
+    st = load().la_selftest_exp64(_ptr(y), _ptr(out), ctypes.c_size_t(out.numel()), _stream())
+    if st:
+        raise LaError(st, "la_selftest_exp64")
 
 
 def la_step_select(verdicts, chain_vis, own_len):

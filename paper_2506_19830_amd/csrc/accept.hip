@@ -1328,6 +1328,19 @@ void accept_carve_workspace(AcceptParams &p, void *ws) {
   p.warp_zs = warp ? (double *)at : nullptr;
 }
 
+namespace {
+__global__ __launch_bounds__(kThreads) void exp64_probe_kernel(const double *y, double *out, size_t n) {
+  const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < n) out[i] = exp64(y[i]);
+}
+}  // namespace
+
+hipError_t launch_exp64_probe(const double *y, double *out, size_t n, hipStream_t stream) {
+  hipLaunchKernelGGL(exp64_probe_kernel, dim3((unsigned)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream, y, out,
+                     n);
+  return hipGetLastError();
+}
+
 hipError_t launch_accept(const AcceptParams &p, hipStream_t stream) {
   return p.bf16 ? launch_typed<true>(p, stream) : launch_typed<false>(p, stream);
 }

@@ -435,6 +435,11 @@ static la_status validate_accept(const la_accept_desc *d) {
   return LA_OK;
 }
 
+la_status la_selftest_exp64(const double *y, double *out, size_t n, void *hip_stream) {
+  if (!y || !out || n < 1 || n > ((size_t)1 << 30)) return LA_ERR_INVALID_ARG;
+  return launch_exp64_probe(y, out, n, (hipStream_t)hip_stream) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
 la_status la_spec_accept_workspace(const la_accept_desc *desc, size_t *bytes_out) {
   la_status st = validate_accept(desc);
   if (st != LA_OK) return st;

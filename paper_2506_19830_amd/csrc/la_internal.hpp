@@ -111,6 +111,8 @@ struct AcceptParams {
 size_t accept_workspace_bytes(int NB, int K, int V, bool bf16, int *n_chunks_out, int *n_fine_out);
 void accept_carve_workspace(AcceptParams &p, void *ws);
 hipError_t launch_accept(const AcceptParams &p, hipStream_t stream);
+// out[i] = the accept path's own fp64 exponential of y[i] (self-test hook)
+hipError_t launch_exp64_probe(const double *y, double *out, size_t n, hipStream_t stream);
 
 // ----------------------------------------------------------------------------
 // KV commit.

@@ -31,3 +31,32 @@ def test_calibration_kernels_run_and_are_timed():
         B.la_calibrate_mfma(65, 10, sink)                          # sink too small for 65 workgroups
     with pytest.raises(B.LaError):
         B.la_calibrate_read(src[1:17], word)                       # not 16-byte aligned
+
+
+def test_device_exponential_of_the_accept_path_is_accurate():
+    """The fp64 exponential the resampling kernels use (their own routine) against numpy's over the range they meet:
+    within two units in the last place for normal results, exact zero far below the range, denormal results to an
+    absolute 1e-320."""
+    import numpy as np
+    rng = np.random.default_rng(5)
+    y = np.concatenate([-rng.random(400_000) * 40.0,                  # the bulk of a row: masses down to e^-40
+                        -rng.random(200_000) * 700.0,                 # the whole normal range
+                        -np.logspace(-18, 0, 20_000),                 # next to 0
+                        np.array([0.0, -0.0, -1e-300, -708.3, -745.0, -750.0, -1e4, -1e300, -np.inf]),
+                        -(np.arange(2000) + 0.5) * np.log(2.0),       # half-way points of the argument reduction
+                        -700.0 - rng.random(10_000) * 45.0])          # into the denormals
+    dev = torch.from_numpy(y).cuda()
+    out = torch.full_like(dev, float("nan"))
+    B.la_selftest_exp64(dev, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    with np.errstate(under="ignore"):
+        ref = np.exp(y)
+    assert np.isfinite(got).all() and (got >= 0).all()
+    normal = ref >= 2.3e-308
+    ulp = np.spacing(ref[normal])
+    assert (np.abs(got[normal] - ref[normal]) <= 2 * ulp).all(), float((np.abs(got[normal] - ref[normal]) / ulp).max())
+    assert (np.abs(got[~normal] - ref[~normal]) <= 1e-320).all()
+    assert (got[y <= -750.0] == 0.0).all() and got[y == 0.0].tolist() == [1.0, 1.0]
+    with pytest.raises(B.LaError):
+        B.la_selftest_exp64(None, out)
