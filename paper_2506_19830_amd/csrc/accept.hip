@@ -518,6 +518,52 @@ __device__ __forceinline__ void row_collect(const void *row, int V, float lo_val
   }
 }
 
+// The same for bounds that only a few dozen tokens of the row reach: a lane first takes the largest of the tokens of
+// one 16-byte load; only when some lane of the wavefront has one at or above the bound are that load's tokens tested
+// and appended one by one.
+template <bool BF16>
+__device__ __forceinline__ void row_collect_sparse(const void *row, int V, float lo_val, uint32_t *list, int cap,
+                                                   int *n) {
+  constexpr int kPerVec = BF16 ? 8 : 4;
+  constexpr int kInFlight = 8;
+  const int tid = threadIdx.x;
+  if (V % kPerVec != 0) {
+    row_foreach<BF16>(row, V, [&](float x) { list_append(x >= lo_val, order_key(x), list, cap, n); });
+    return;
+  }
+  const int n_vec = V / kPerVec;
+  for (int i0 = tid; i0 < n_vec; i0 += kInFlight * kWarpThreads) {
+    u32x4 w[kInFlight];
+#pragma unroll
+    for (int j = 0; j < kInFlight; ++j) {
+      const int i = i0 + j * kWarpThreads;
+      w[j] = *(const u32x4 *)((const uint8_t *)row + (size_t)(i < n_vec ? i : i0) * 16);
+    }
+#pragma unroll
+    for (int j = 0; j < kInFlight; ++j) {
+      const bool in = i0 + j * kWarpThreads < n_vec;
+      float x[kPerVec];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t word = w[j][k];
+        if constexpr (BF16) {
+          x[2 * k] = bf16_lo(word);
+          x[2 * k + 1] = bf16_hi(word);
+        } else {
+          x[k] = as_f32(word);
+        }
+      }
+      float top = x[0];
+#pragma unroll
+      for (int e = 1; e < kPerVec; ++e) top = fmaxf(top, x[e]);
+      if (__ballot(in && top >= lo_val)) {
+#pragma unroll
+        for (int e = 0; e < kPerVec; ++e) list_append(in && x[e] >= lo_val, order_key(x[e]), list, cap, n);
+      }
+    }
+  }
+}
+
 // Bitonic sort of list[0..n) in descending order, in place, by the whole workgroup; n <= kCand.  Entries n..N-1 (N
 // the next power of two, at least 128) are filled with 0, which is below every key.  Compare-exchange steps whose
 // partners are at least 128 apart involve the whole workgroup and end in a barrier; the steps below that stay inside
@@ -608,8 +654,7 @@ __device__ __forceinline__ bool warp_small_k(const AcceptParams &p, const void *
   if (tid == 0) s_n = 0;
   __syncthreads();
   // comparing the values is comparing the keys (no NaNs; -0 == +0 on both sides)
-  // (few tokens qualify here: testing them one by one is cheaper than row_collect's marking)
-  row_foreach<BF16>(row, p.V, [&](float x) { list_append(x >= lo_val, order_key(x), cand, kCand, &s_n); });
+  row_collect_sparse<BF16>(row, p.V, lo_val, cand, kCand, &s_n);
   __syncthreads();
   const int n_c = s_n;   // >= k
   if (n_c > kCand) return false;
