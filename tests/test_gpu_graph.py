@@ -70,3 +70,49 @@ def test_captured_step_replays_like_eager():
             assert torch.equal(g.view(torch.uint8) if g.dtype == torch.float8_e4m3fn else g,
                                e.view(torch.uint8) if e.dtype == torch.float8_e4m3fn else e), f"replay {replay}"
         assert graph_bufs[4].tolist() == [700 + 6 + 9, 64 + 13 + 4]
+
+
+@pytest.mark.parametrize("top_k", [20, 0])
+def test_captured_accept_with_warped_targets_replays_like_eager(top_k):
+    """la_spec_accept with temperature, top-k / top-p and prompt-lookup drafts (the slice-sum kernel, the candidate
+    lists in LDS, the list sort) captured once and replayed on uniforms and logits changed in place: every replay
+    equals an eager run, and they are not all the same."""
+    from gpu_util import upload_accept
+    acase = W.AcceptCase("graph_warp", 6, 3, 40000, "bf16", temperature=0.6, top_k=top_k, top_p=0.95, point_mass=True,
+                         peak=6.0, seed=83)
+    acc = upload_accept(acase, W.make_accept_inputs(acase))
+    adesc = B.make_accept_desc(num_branches=acase.NB, num_draft=acase.K, vocab=acase.V, logits_dtype="bf16",
+                               temperature=acase.temperature, top_k=acase.top_k, top_p=acase.top_p)
+    aws = torch.empty(max(16, B.la_spec_accept_workspace(adesc)), dtype=torch.uint8, device="cuda")
+
+    def step(n_acc, tok, ratio):
+        B.la_spec_accept(adesc, acc["target_logits"], acc["draft_logits"], acc["draft_tokens"], acc["u_accept"],
+                         acc["u_sample"], n_acc, tok, ratio, aws)
+
+    def buffers():
+        return (torch.zeros(acase.NB, dtype=torch.int32, device="cuda"),
+                torch.zeros(acase.NB, dtype=torch.int32, device="cuda"),
+                torch.zeros((acase.NB, acase.K), dtype=torch.float32, device="cuda"))
+
+    graph_bufs, eager_bufs = buffers(), buffers()
+    step(*graph_bufs)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(*graph_bufs)
+    rng = np.random.default_rng(1)
+    seen = set()
+    for replay in range(4):
+        acc["u_accept"].copy_(torch.from_numpy(rng.random((acase.NB, acase.K), dtype=np.float32)).cuda())
+        acc["u_sample"].copy_(torch.from_numpy(rng.random(acase.NB, dtype=np.float32)).cuda())
+        acc["target_logits"].copy_(acc["target_logits"].roll(replay + 1, dims=0))     # the branches' rows change places
+        for t in graph_bufs + eager_bufs:
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        step(*eager_bufs)
+        torch.cuda.synchronize()
+        for g, e in zip(graph_bufs, eager_bufs):
+            assert torch.equal(g, e), f"replay {replay}"
+        seen.add((tuple(graph_bufs[0].tolist()), tuple(graph_bufs[1].tolist())))
+    assert len(seen) > 1
