@@ -310,6 +310,26 @@ LA_API la_status la_spec_accept(
                                     every position (also those after the rejection)      */
     void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* la_spec_accept for callers that cannot allocate device memory or bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and kernels as la_spec_accept,
+ * minus the workspace: the kernels use a scratch array of
+ * LA_SPEC_ACCEPT_STATIC_MAX_BYTES that is part of the library's device image
+ * (every GPU the library runs on holds its own copy until the process ends).
+ * The call allocates and frees nothing; its first call on a device looks the
+ * array's address up (do that once outside any capture).  A descriptor whose
+ * la_spec_accept_workspace size exceeds the maximum is rejected with
+ * LA_ERR_WORKSPACE_TOO_SMALL before anything is launched (NB = 32, K = 8,
+ * V = 152064 needs 10.3 MB).  All calls on one GPU share that GPU's array:
+ * calls that overlap on one GPU (two streams, two threads) race; calls on one
+ * stream are ordered and need nothing cleared in between.  Leave
+ * la_profile_enable off for such callers (event timing creates events). */
+#define LA_SPEC_ACCEPT_STATIC_MAX_BYTES (16u << 20)
+LA_API la_status la_spec_accept_static(
+    const la_accept_desc *desc, const void *target_logits, const void *draft_logits,
+    const int32_t *draft_tokens, const float *u_accept, const float *u_sample,
+    int32_t *accepted_len, int32_t *next_token, float *accept_ratio, void *hip_stream);
+
 /* ------------------------------------------------------------------------- *
  *  Step-level controller and budget planner (host only: every pointer below
  *  is a host pointer, nothing touches the GPU).

@@ -28,7 +28,7 @@ EXPORTED_SYMBOLS = (
     "la_kv_commit_tree", "la_step_select_tree",
     "la_calibrate_mfma", "la_calibrate_read", "la_selftest_exp64", "la_step_select", "la_speedup_step_sync", "la_speedup_step_async", "la_speedup_token", "la_plan_budget",
     "la_spec_accept_workspace",
-    "la_spec_accept",
+    "la_spec_accept", "la_spec_accept_static",
     "la_status_string", "la_profile_enable", "la_profile_select", "la_profile_collect", "la_profile_num_kernels", "la_profile_get",
     "la_profile_reset",
 )
@@ -122,6 +122,8 @@ def load() -> ctypes.CDLL:
         lib.la_spec_accept.restype = ctypes.c_int
         lib.la_spec_accept.argtypes = [ctypes.POINTER(la_accept_desc), vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                        ctypes.c_size_t, vp]
+        lib.la_spec_accept_static.restype = ctypes.c_int
+        lib.la_spec_accept_static.argtypes = [ctypes.POINTER(la_accept_desc)] + [vp] * 9
         lib.la_status_string.restype = ctypes.c_char_p
         lib.la_status_string.argtypes = [ctypes.c_int]
         lib.la_profile_enable.restype = ctypes.c_int
@@ -370,6 +372,16 @@ def la_spec_accept(desc: la_accept_desc, target_logits, draft_logits, draft_toke
                                _ptr(accept_ratio), _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream())
     if st:
         raise LaError(st, "la_spec_accept")
+
+
+def la_spec_accept_static(desc: la_accept_desc, target_logits, draft_logits, draft_tokens, u_accept, u_sample,
+                          accepted_len, next_token, accept_ratio) -> None:
+    """``la_spec_accept`` on the library's own scratch array (no workspace, nothing allocated)."""
+    st = load().la_spec_accept_static(ctypes.byref(desc), _ptr(target_logits), _ptr(draft_logits),
+                                      _ptr(draft_tokens), _ptr(u_accept), _ptr(u_sample), _ptr(accepted_len),
+                                      _ptr(next_token), _ptr(accept_ratio), _stream())
+    if st:
+        raise LaError(st, "la_spec_accept_static")
 
 
 # ------------------------------------------------------------------------------------------- profiling

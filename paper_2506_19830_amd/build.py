@@ -18,7 +18,7 @@ CSRC = HERE / "csrc"
 OBJ = HERE / "_build"
 LIB = HERE / "libla_verify.so"
 
-SOURCES = ["api.hip", "attn_mfma.hip", "attn_merge.hip", "attn_f32.hip", "accept.hip", "kv_commit.hip",
+SOURCES = ["api.hip", "attn_mfma.hip", "attn_merge.hip", "attn_f32.hip", "accept.hip", "accept_static.hip", "kv_commit.hip",
            "controller.hip", "calibrate.hip"]
 # -fno-honor-nans: no NaN can arise in these kernels (masked scores are -inf, handled explicitly); without it
 # every fmaxf is preceded by a canonicalising v_max(x, x).
