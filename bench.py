@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--kv-split-tokens", type=int, default=0)
     ap.add_argument("--branch-len", type=int, default=None,
                     help="override L, the tokens per branch (branch-length sweep at the configuration's shape)")
+    ap.add_argument("--gamma", type=int, default=None, help="override the configuration's number of branches")
+    ap.add_argument("--kernel-shape", type=int, default=0,
+                    help="force a kernel shape of the attention call (la_attn_desc.kernel_shape; 0 = the library's choice)")
     ap.add_argument("--chain-len", type=int, default=0,
                     help="nested branches: a drafted chain of this many tokens per request, of which branch g sees "
                          "the first g/gamma (la_verify_attention_nested); 0 = the flat form, the headline workload")
@@ -91,6 +94,7 @@ def bench_commit(args):
     from paper_2506_19830_amd import binding as B
     from paper_2506_19830_amd import workloads as W
 
+    B.select_library("bench")
     B.load()
     dev = "cuda:0"
     torch.cuda.set_device(0)
@@ -306,7 +310,10 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
-    B.load()   # raises if the HIP library was not built: there is no fallback
+    # the benchmark build of the library: the product library's objects plus the per-kernel event timing that the
+    # roofline figure below is measured with (raises if it was not built: there is no fallback)
+    B.select_library("bench")
+    B.load()
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
@@ -318,6 +325,9 @@ def main():
     if args.branch_len is not None:
         from dataclasses import replace
         attn_case = replace(attn_case, L=args.branch_len, name=f"{attn_case.name}_L{args.branch_len}")
+    if args.gamma is not None:
+        from dataclasses import replace
+        attn_case = replace(attn_case, gamma=args.gamma, name=f"{attn_case.name}_g{args.gamma}")
     if args.layers is not None:
         n_layers = args.layers
     elif args.config == 5:
@@ -335,7 +345,9 @@ def main():
                             block_size=attn_case.block_size, max_blocks_per_request=attn_case.max_blocks,
                             q_dtype=attn_case.q_dtype, kv_dtype=attn_case.kv_dtype,
                             branch_kv_dtype=attn_case.branch_kv_dtype, out_dtype=attn_case.out_dtype,
-                            softmax_scale=attn_case.scale, kv_split_tokens=args.kv_split_tokens)
+                            softmax_scale=attn_case.scale, kv_split_tokens=args.kv_split_tokens,
+                            kernel_shape=args.kernel_shape)
+    plan = B.la_verify_attention_plan(desc, lens, 1 if (args.chain_len > 0 or args.tree) else 0)
     ws = torch.empty(max(16, B.la_verify_attention_workspace(desc, lens)), dtype=torch.uint8, device=dev)
     outs = [B.empty_out((attn_case.B, attn_case.gamma, attn_case.L, attn_case.Hq, attn_case.D), attn_case.out_dtype,
                         dev) for _ in range(n_layers)]
@@ -504,6 +516,7 @@ def main():
             "layers": n_layers,
             "branch_tokens_per_step": branch_tokens,
             "kv_split_tokens": args.kv_split_tokens,
+            "plan": plan,
             "chain_len": C,
             "tree": args.tree, "pool_len": None if tree is None else tree["pool_len"],
             "hip_graph": bool(args.graph),

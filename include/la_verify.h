@@ -33,8 +33,14 @@
  *     without checking it again: the two must hold the same values when the
  *     work runs, anything else is undefined behaviour.  (la_kv_commit's
  *     decisions are device-only and therefore clamped by the kernel.)
- *   - Not thread-safe with respect to the la_profile_* calls, which keep
- *     process-wide state; the compute calls themselves keep none.
+ *   - The library keeps no state between calls (what it caches -- the
+ *     compute-unit count, per-kernel launch attributes, the address of
+ *     la_spec_accept_static's scratch array -- is written once, under a lock,
+ *     and only read afterwards), so calls may come from several host threads.
+ *   - Benchmark aids (per-kernel event timing, calibration kernels, a self-test
+ *     hook) are not part of this library: they are declared in
+ *     la_verify_bench.h and exist only in libla_verify_bench.so, the same
+ *     objects linked together with them.
  */
 #ifndef LA_VERIFY_H
 #define LA_VERIFY_H
@@ -95,12 +101,37 @@ typedef struct {
   int32_t kv_split_tokens;         /* 0 = let the library choose how the prefix is cut
                                       into independently reduced chunks; otherwise the
                                       chunk length in tokens (multiple of 64)           */
+  int32_t kernel_shape;            /* 0 = let the library choose the kernel shape of the
+                                      bf16/fp8 path; k > 0 forces shape k (testing and
+                                      tuning; numbering as la_attn_plan.kernel_shape
+                                      reports it; LA_ERR_UNSUPPORTED when that shape
+                                      cannot run the problem, LA_ERR_INVALID_ARG when
+                                      there is no such shape)                           */
 } la_attn_desc;
 
 /* Bytes of device workspace la_verify_attention needs for this descriptor and
  * these prefix lengths (host array [B]).  0 is a valid answer. */
 LA_API la_status la_verify_attention_workspace(const la_attn_desc *desc, const int32_t *prefix_lens_host,
                                         size_t *bytes_out);
+
+/* What the library would launch for this descriptor and these prefix lengths
+ * (host array [B]); chain_len > 0 asks for the nested / tree form.  A pure
+ * function of its arguments and of the device's compute-unit count; nothing
+ * is launched.  The answer is what the compute calls use, so a caller can
+ * log it or size a sweep with it. */
+typedef struct {
+  int32_t path;               /* 1 = fp32 kernel, 2 = bf16/fp8 MFMA kernels                      */
+  int32_t kernel_shape;       /* MFMA path: 1 = 256-row tiles, 3 LDS stages; 2 = 128-row tiles,
+                                 2 stages; 3.. = streaming shapes (32-row blocks x key slices:
+                                 3 = 2 x 4, 4 = 4 x 2, 5 = 8 x 1), few rows per KV head          */
+  int32_t rows_per_workgroup; /* query rows (of one KV head) a workgroup owns                    */
+  int32_t row_tiles;          /* workgroups per (KV head, chunk)                                 */
+  int32_t chunk_tokens;       /* prefix tokens per independently reduced chunk                   */
+  int32_t chunks_total;       /* chunks summed over the requests                                 */
+  int32_t workgroups;         /* of the attention kernel                                         */
+} la_attn_plan;
+LA_API la_status la_verify_attention_plan(const la_attn_desc *desc, const int32_t *prefix_lens_host,
+                                          int32_t chain_len, la_attn_plan *out);
 
 LA_API la_status la_verify_attention(
     const la_attn_desc *desc,
@@ -401,55 +432,9 @@ LA_API la_status la_speedup_token(double alpha2, double c2, int32_t k2, double *
 LA_API la_status la_plan_budget(const la_plan_desc *desc, int32_t *k1, int32_t *k2, double *speedup);
 
 /* ------------------------------------------------------------------------- *
- *  Calibration (benchmark aid, not part of the verification path): what the
- *  chip at hand reaches on a pure bf16 MFMA loop and on a pure streaming read,
- *  to quote a roofline fraction against the achievable rate beside the
- *  published peak.  Both only enqueue a kernel; time them with la_profile_*
- *  (slots "calib_mfma", "calib_read") or with events of your own.
- *
- *  la_calibrate_mfma: `workgroups` x 8 wavefronts, each `iters` rounds of four
- *  independent v_mfma_f32_32x32x16_bf16; *flops (host) receives the launch's
- *  flop count.  sink: dev, workgroups * 512 floats, written.
- *  la_calibrate_read: reads `bytes` (a multiple of 16 is read) from src (dev,
- *  16-byte aligned) once; sink: dev, one word (written practically never).
- * ------------------------------------------------------------------------- */
-LA_API la_status la_calibrate_mfma(int32_t workgroups, int32_t iters, float *sink, double *flops, void *hip_stream);
-LA_API la_status la_calibrate_read(const void *src, size_t bytes, uint32_t *sink, void *hip_stream);
-
-/* ------------------------------------------------------------------------- *
- *  Self-test hook (not part of the verification path): out[i] = exp(y[i]) as
- *  the fp64 resampling path of la_spec_accept evaluates it (its own routine:
- *  two-term argument reduction, degree-13 polynomial, ldexp; meant for
- *  y <= 0, arguments below -750 give 0), so that its accuracy can be checked
- *  against a reference exponential.  y, out: dev, n doubles each, n >= 1.
- *  Only enqueues a kernel.
- * ------------------------------------------------------------------------- */
-LA_API la_status la_selftest_exp64(const double *y, double *out, size_t n, void *hip_stream);
-
-/* ------------------------------------------------------------------------- *
  *  Diagnostics
  * ------------------------------------------------------------------------- */
 LA_API const char *la_status_string(la_status s);
-
-/* Per-kernel timing for benchmarks.  While enabled, every kernel the library
- * launches is bracketed by HIP events on the caller's stream (process-wide
- * state, not thread-safe; at most LA_PROFILE_MAX_RECORDS launches are kept,
- * later ones are dropped).  la_profile_collect synchronises on the recorded
- * events and accumulates them; la_profile_get then reports, per kernel slot,
- * its name, number of timed launches and their total duration.
- * la_profile_select narrows what is bracketed: bit k of slot_mask selects
- * kernel slot k (default: all), and of a selected slot's launches only every
- * stride-th one is timed (default 1); the event pairs cost a few microseconds
- * each on the stream, so a benchmark that wants its wall time undisturbed
- * times only the kernel it reports and a sample of its launches.  Returns
- * LA_ERR_INVALID_ARG for stride < 1. */
-#define LA_PROFILE_MAX_RECORDS 8192
-LA_API la_status la_profile_enable(int on);
-LA_API la_status la_profile_select(uint32_t slot_mask, int32_t stride);
-LA_API la_status la_profile_collect(void);
-LA_API int32_t la_profile_num_kernels(void);
-LA_API la_status la_profile_get(int32_t slot, const char **name, int64_t *launches, double *total_ms);
-LA_API la_status la_profile_reset(void);
 
 #ifdef __cplusplus
 }

@@ -1,0 +1,67 @@
+/*
+ * la_verify_bench.h -- benchmark aids of the verification library: per-kernel
+ * event timing, two calibration kernels and a self-test hook.  None of them is
+ * part of the verification path.  They exist only in libla_verify_bench.so,
+ * which is libla_verify.so's objects linked together with these aids (same
+ * kernels, same entry points); the product library does not contain them and
+ * keeps no state.
+ */
+#ifndef LA_VERIFY_BENCH_H
+#define LA_VERIFY_BENCH_H
+
+#include "la_verify.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ------------------------------------------------------------------------- *
+ *  Calibration (benchmark aid, not part of the verification path): what the
+ *  chip at hand reaches on a pure bf16 MFMA loop and on a pure streaming read,
+ *  to quote a roofline fraction against the achievable rate beside the
+ *  published peak.  Both only enqueue a kernel; time them with la_profile_*
+ *  (slots "calib_mfma", "calib_read") or with events of your own.
+ *
+ *  la_calibrate_mfma: `workgroups` x 8 wavefronts, each `iters` rounds of four
+ *  independent v_mfma_f32_32x32x16_bf16; *flops (host) receives the launch's
+ *  flop count.  sink: dev, workgroups * 512 floats, written.
+ *  la_calibrate_read: reads `bytes` (a multiple of 16 is read) from src (dev,
+ *  16-byte aligned) once; sink: dev, one word (written practically never).
+ * ------------------------------------------------------------------------- */
+LA_API la_status la_calibrate_mfma(int32_t workgroups, int32_t iters, float *sink, double *flops, void *hip_stream);
+LA_API la_status la_calibrate_read(const void *src, size_t bytes, uint32_t *sink, void *hip_stream);
+
+/* ------------------------------------------------------------------------- *
+ *  Self-test hook (not part of the verification path): out[i] = exp(y[i]) as
+ *  the fp64 resampling path of la_spec_accept evaluates it (its own routine:
+ *  two-term argument reduction, degree-13 polynomial, ldexp; meant for
+ *  y <= 0, arguments below -750 give 0), so that its accuracy can be checked
+ *  against a reference exponential.  y, out: dev, n doubles each, n >= 1.
+ *  Only enqueues a kernel.
+ * ------------------------------------------------------------------------- */
+LA_API la_status la_selftest_exp64(const double *y, double *out, size_t n, void *hip_stream);
+
+/* Per-kernel timing for benchmarks.  While enabled, every kernel the library
+ * launches is bracketed by HIP events on the caller's stream (process-wide
+ * state, not thread-safe; at most LA_PROFILE_MAX_RECORDS launches are kept,
+ * later ones are dropped).  la_profile_collect synchronises on the recorded
+ * events and accumulates them; la_profile_get then reports, per kernel slot,
+ * its name, number of timed launches and their total duration.
+ * la_profile_select narrows what is bracketed: bit k of slot_mask selects
+ * kernel slot k (default: all), and of a selected slot's launches only every
+ * stride-th one is timed (default 1); the event pairs cost a few microseconds
+ * each on the stream, so a benchmark that wants its wall time undisturbed
+ * times only the kernel it reports and a sample of its launches.  Returns
+ * LA_ERR_INVALID_ARG for stride < 1. */
+#define LA_PROFILE_MAX_RECORDS 8192
+LA_API la_status la_profile_enable(int on);
+LA_API la_status la_profile_select(uint32_t slot_mask, int32_t stride);
+LA_API la_status la_profile_collect(void);
+LA_API int32_t la_profile_num_kernels(void);
+LA_API la_status la_profile_get(int32_t slot, const char **name, int64_t *launches, double *total_ms);
+LA_API la_status la_profile_reset(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LA_VERIFY_BENCH_H */

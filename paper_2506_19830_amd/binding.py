@@ -14,23 +14,25 @@ from typing import Optional, Sequence
 import torch
 
 _HERE = Path(__file__).resolve().parent
-import os as _os
 
-# LA_VERIFY_LIB: load another build of the library (kernel experiments); default is the in-tree build
-LIB_PATH = Path(_os.environ.get("LA_VERIFY_LIB", _HERE / "libla_verify.so"))
+# The product library, and the same objects linked together with the benchmark aids (la_verify_bench.h).
+LIB_PATH = _HERE / "libla_verify.so"
+BENCH_LIB_PATH = _HERE / "libla_verify_bench.so"
 
 LA_F32, LA_BF16, LA_FP8_E4M3 = 0, 1, 2
 DTYPE_CODES = {"f32": LA_F32, "bf16": LA_BF16, "fp8_e4m3": LA_FP8_E4M3}
 _TORCH_DTYPES = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch.float8_e4m3fn}
 
 EXPORTED_SYMBOLS = (
-    "la_verify_attention_workspace", "la_verify_attention", "la_verify_attention_nested", "la_verify_attention_tree", "la_kv_commit",
-    "la_kv_commit_tree", "la_step_select_tree",
-    "la_calibrate_mfma", "la_calibrate_read", "la_selftest_exp64", "la_step_select", "la_speedup_step_sync", "la_speedup_step_async", "la_speedup_token", "la_plan_budget",
-    "la_spec_accept_workspace",
-    "la_spec_accept", "la_spec_accept_static",
-    "la_status_string", "la_profile_enable", "la_profile_select", "la_profile_collect", "la_profile_num_kernels", "la_profile_get",
-    "la_profile_reset",
+    "la_verify_attention_workspace", "la_verify_attention_plan", "la_verify_attention", "la_verify_attention_nested",
+    "la_verify_attention_tree", "la_kv_commit", "la_kv_commit_tree", "la_step_select_tree", "la_step_select",
+    "la_speedup_step_sync", "la_speedup_step_async", "la_speedup_token", "la_plan_budget",
+    "la_spec_accept_workspace", "la_spec_accept", "la_spec_accept_static", "la_status_string",
+)
+# what libla_verify_bench.so exports on top of those (la_verify_bench.h)
+BENCH_SYMBOLS = (
+    "la_calibrate_mfma", "la_calibrate_read", "la_selftest_exp64", "la_profile_enable", "la_profile_select",
+    "la_profile_collect", "la_profile_num_kernels", "la_profile_get", "la_profile_reset",
 )
 
 
@@ -38,7 +40,12 @@ class la_attn_desc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "num_requests", "num_q_heads", "num_kv_heads", "head_dim", "gamma", "branch_len", "block_size",
         "max_blocks_per_request", "q_dtype", "kv_dtype", "branch_kv_dtype", "out_dtype")] + [
-        ("softmax_scale", ctypes.c_float), ("kv_split_tokens", ctypes.c_int32)]
+        ("softmax_scale", ctypes.c_float), ("kv_split_tokens", ctypes.c_int32), ("kernel_shape", ctypes.c_int32)]
+
+
+class la_attn_plan(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "path", "kernel_shape", "rows_per_workgroup", "row_tiles", "chunk_tokens", "chunks_total", "workgroups")]
 
 
 class la_accept_desc(ctypes.Structure):
@@ -63,18 +70,30 @@ class LaError(RuntimeError):
         super().__init__(f"{where}: {status_string(status)} (status {status})")
 
 
-_lib = None
+_libs = {}
+_active = "product"
 
 
-def load() -> ctypes.CDLL:
+def select_library(kind: str) -> None:
+    """Route every call of this module through the product library (``"product"``, the default) or through the
+    benchmark build (``"bench"``: the same objects plus the aids of ``la_verify_bench.h``; needed for
+    ``la_profile_*`` to see the launches)."""
+    global _active
+    if kind not in ("product", "bench"):
+        raise ValueError(kind)
+    _active = kind
+
+
+def load(kind: Optional[str] = None) -> ctypes.CDLL:
     """Load the HIP library; raises if it was not built (there is no other implementation)."""
-    global _lib
-    if _lib is None:
-        if not LIB_PATH.exists():
+    kind = kind or _active
+    if kind not in _libs:
+        path = LIB_PATH if kind == "product" else BENCH_LIB_PATH
+        if not path.exists():
             raise FileNotFoundError(
-                f"{LIB_PATH} is missing: build it first (python -m paper_2506_19830_amd.build or "
+                f"{path} is missing: build it first (python -m paper_2506_19830_amd.build or "
                 "__graft_entry__.build()); the verification path has no fallback")
-        lib = ctypes.CDLL(str(LIB_PATH))
+        lib = ctypes.CDLL(str(path))
         vp, i32p = ctypes.c_void_p, ctypes.c_void_p
         lib.la_verify_attention_workspace.restype = ctypes.c_int
         lib.la_verify_attention_workspace.argtypes = [ctypes.POINTER(la_attn_desc), ctypes.POINTER(ctypes.c_int32),
@@ -101,12 +120,9 @@ def load() -> ctypes.CDLL:
         lib.la_kv_commit_tree.argtypes = [ctypes.POINTER(la_attn_desc), vp, vp, i32p, i32p,
                                           ctypes.POINTER(ctypes.c_int32), vp, vp, vp, vp, ctypes.c_int32, i32p, vp,
                                           i32p, i32p, vp, vp, i32p, ctypes.POINTER(la_layer_strides), vp]
-        lib.la_calibrate_mfma.restype = ctypes.c_int
-        lib.la_calibrate_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
-        lib.la_calibrate_read.restype = ctypes.c_int
-        lib.la_calibrate_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
-        lib.la_selftest_exp64.restype = ctypes.c_int
-        lib.la_selftest_exp64.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        lib.la_verify_attention_plan.restype = ctypes.c_int
+        lib.la_verify_attention_plan.argtypes = [ctypes.POINTER(la_attn_desc), ctypes.POINTER(ctypes.c_int32),
+                                                 ctypes.c_int32, ctypes.POINTER(la_attn_plan)]
         lib.la_step_select.restype = ctypes.c_int
         lib.la_step_select.argtypes = [ctypes.c_int32, ctypes.c_int32] + [vp] * 7
         lib.la_step_select_tree.restype = ctypes.c_int
@@ -126,18 +142,25 @@ def load() -> ctypes.CDLL:
         lib.la_spec_accept_static.argtypes = [ctypes.POINTER(la_accept_desc)] + [vp] * 9
         lib.la_status_string.restype = ctypes.c_char_p
         lib.la_status_string.argtypes = [ctypes.c_int]
-        lib.la_profile_enable.restype = ctypes.c_int
-        lib.la_profile_enable.argtypes = [ctypes.c_int]
-        lib.la_profile_select.restype = ctypes.c_int
-        lib.la_profile_select.argtypes = [ctypes.c_uint32, ctypes.c_int32]
-        lib.la_profile_collect.restype = ctypes.c_int
-        lib.la_profile_reset.restype = ctypes.c_int
-        lib.la_profile_num_kernels.restype = ctypes.c_int32
-        lib.la_profile_get.restype = ctypes.c_int
-        lib.la_profile_get.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_char_p),
-                                       ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_double)]
-        _lib = lib
-    return _lib
+        if kind == "bench":
+            lib.la_calibrate_mfma.restype = ctypes.c_int
+            lib.la_calibrate_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
+            lib.la_calibrate_read.restype = ctypes.c_int
+            lib.la_calibrate_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+            lib.la_selftest_exp64.restype = ctypes.c_int
+            lib.la_selftest_exp64.argtypes = [vp, vp, ctypes.c_size_t, vp]
+            lib.la_profile_enable.restype = ctypes.c_int
+            lib.la_profile_enable.argtypes = [ctypes.c_int]
+            lib.la_profile_select.restype = ctypes.c_int
+            lib.la_profile_select.argtypes = [ctypes.c_uint32, ctypes.c_int32]
+            lib.la_profile_collect.restype = ctypes.c_int
+            lib.la_profile_reset.restype = ctypes.c_int
+            lib.la_profile_num_kernels.restype = ctypes.c_int32
+            lib.la_profile_get.restype = ctypes.c_int
+            lib.la_profile_get.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_char_p),
+                                           ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_double)]
+        _libs[kind] = lib
+    return _libs[kind]
 
 
 def status_string(status: int) -> str:
@@ -154,10 +177,11 @@ def _stream() -> ctypes.c_void_p:
 
 def make_attn_desc(*, num_requests, num_q_heads, num_kv_heads, head_dim, gamma, branch_len, block_size,
                    max_blocks_per_request, q_dtype, kv_dtype, branch_kv_dtype, out_dtype, softmax_scale,
-                   kv_split_tokens=0) -> la_attn_desc:
+                   kv_split_tokens=0, kernel_shape=0) -> la_attn_desc:
     return la_attn_desc(num_requests, num_q_heads, num_kv_heads, head_dim, gamma, branch_len, block_size,
                         max_blocks_per_request, DTYPE_CODES[q_dtype], DTYPE_CODES[kv_dtype],
-                        DTYPE_CODES[branch_kv_dtype], DTYPE_CODES[out_dtype], softmax_scale, kv_split_tokens)
+                        DTYPE_CODES[branch_kv_dtype], DTYPE_CODES[out_dtype], softmax_scale, kv_split_tokens,
+                        kernel_shape)
 
 
 def _host_lens(prefix_lens_host: Sequence[int]):
@@ -171,6 +195,16 @@ def la_verify_attention_workspace(desc: la_attn_desc, prefix_lens_host: Sequence
     if st:
         raise LaError(st, "la_verify_attention_workspace")
     return int(out.value)
+
+
+def la_verify_attention_plan(desc: la_attn_desc, prefix_lens_host: Sequence[int], chain_len: int = 0) -> dict:
+    """What the library would launch for this problem (kernel shape, chunking, workgroups), as a dict."""
+    out = la_attn_plan()
+    st = load().la_verify_attention_plan(ctypes.byref(desc), _host_lens(prefix_lens_host), int(chain_len),
+                                         ctypes.byref(out))
+    if st:
+        raise LaError(st, "la_verify_attention_plan")
+    return {name: int(getattr(out, name)) for name, _ in la_attn_plan._fields_}
 
 
 def la_verify_attention(desc: la_attn_desc, q, k_cache, v_cache, block_tables, prefix_lens, prefix_lens_host,
@@ -262,7 +296,7 @@ def la_calibrate_mfma(workgroups: int, iters: int, sink) -> float:
     if sink.numel() < workgroups * 512:
         raise ValueError("sink must hold workgroups * 512 floats")
     flops = ctypes.c_double()
-    st = load().la_calibrate_mfma(workgroups, iters, _ptr(sink), ctypes.byref(flops), _stream())
+    st = load("bench").la_calibrate_mfma(workgroups, iters, _ptr(sink), ctypes.byref(flops), _stream())
     if st:
         raise LaError(st, "la_calibrate_mfma")
     return flops.value
@@ -271,7 +305,7 @@ def la_calibrate_mfma(workgroups: int, iters: int, sink) -> float:
 def la_calibrate_read(src, sink) -> int:
     """Enqueue the streaming-read calibration kernel over the whole of ``src``; returns the bytes it reads."""
     nbytes = src.numel() * src.element_size()
-    st = load().la_calibrate_read(_ptr(src), ctypes.c_size_t(nbytes), _ptr(sink), _stream())
+    st = load("bench").la_calibrate_read(_ptr(src), ctypes.c_size_t(nbytes), _ptr(sink), _stream())
     if st:
         raise LaError(st, "la_calibrate_read")
     return nbytes // 16 * 16
@@ -279,7 +313,7 @@ def la_calibrate_read(src, sink) -> int:
 
 def la_selftest_exp64(y, out) -> None:
     """``out[i] = exp(y[i])`` as the fp64 resampling path of ``la_spec_accept`` evaluates it (device float64 tensors)."""
-    st = load().la_selftest_exp64(_ptr(y), _ptr(out), ctypes.c_size_t(out.numel()), _stream())
+    st = load("bench").la_selftest_exp64(_ptr(y), _ptr(out), ctypes.c_size_t(out.numel()), _stream())
     if st:
         raise LaError(st, "la_selftest_exp64")
 
@@ -387,12 +421,12 @@ def la_spec_accept_static(desc: la_accept_desc, target_logits, draft_logits, dra
 # ------------------------------------------------------------------------------------------- profiling
 
 def la_profile_enable(on: bool) -> None:
-    load().la_profile_enable(int(bool(on)))
+    load("bench").la_profile_enable(int(bool(on)))
 
 
 def la_profile_select(kernels=None, stride: int = 1) -> None:
     """Time only the named kernels (None = all), and of their launches every ``stride``-th one."""
-    lib = load()
+    lib = load("bench")
     mask = 0xFFFFFFFF
     if kernels is not None:
         names = {}
@@ -409,12 +443,12 @@ def la_profile_select(kernels=None, stride: int = 1) -> None:
 
 
 def la_profile_reset() -> None:
-    load().la_profile_reset()
+    load("bench").la_profile_reset()
 
 
 def la_profile_collect() -> dict:
     """Synchronise on the recorded events; returns {kernel: (launches, total_ms)} since the last reset."""
-    lib = load()
+    lib = load("bench")
     st = lib.la_profile_collect()
     if st:
         raise LaError(st, "la_profile_collect")

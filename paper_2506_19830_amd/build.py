@@ -18,13 +18,17 @@ CSRC = HERE / "csrc"
 OBJ = HERE / "_build"
 LIB = HERE / "libla_verify.so"
 
-SOURCES = ["api.hip", "attn_mfma.hip", "attn_merge.hip", "attn_f32.hip", "accept.hip", "accept_static.hip", "kv_commit.hip",
-           "controller.hip", "calibrate.hip"]
+SOURCES = ["api.hip", "attn_mfma.hip", "attn_stream.hip", "attn_merge.hip", "attn_f32.hip", "accept.hip",
+           "accept_static.hip", "kv_commit.hip", "controller.hip"]
+# benchmark aids (per-kernel event timing, calibration kernels, a self-test hook): only in libla_verify_bench.so,
+# which is the product library's objects linked together with these
+BENCH_SOURCES = ["bench_aids.hip", "calibrate.hip"]
+BENCH_LIB = HERE / "libla_verify_bench.so"
 # -fno-honor-nans: no NaN can arise in these kernels (masked scores are -inf, handled explicitly); without it
 # every fmaxf is preceded by a canonicalising v_max(x, x).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-fno-honor-nans", "-Wall",
          "-Wextra",
-         "-Wno-unused-parameter", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wno-unused-parameter", "-Wno-inline-asm", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          f"-I{ROOT / 'include'}", f"-I{CSRC}"]
 
 
@@ -35,8 +39,8 @@ def _hipcc() -> str:
     return "hipcc"
 
 
-def build(verbose: bool = False, extra_flags=(), lib: Path = LIB) -> Path:
-    LIB_OUT = lib
+def build(verbose: bool = False, extra_flags=(), lib: Path = LIB, bench_lib: Path = BENCH_LIB) -> Path:
+    """Compile every translation unit once and link the product library and the benchmark library from them."""
     OBJ.mkdir(exist_ok=True)
     hipcc = _hipcc()
 
@@ -52,15 +56,21 @@ def build(verbose: bool = False, extra_flags=(), lib: Path = LIB) -> Path:
             print(err, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
-        objs = list(pool.map(compile_one, SOURCES))
-    tmp = LIB_OUT.with_suffix(".so.tmp%d" % os.getpid())
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(tmp), *map(str, objs)]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError(f"link failed:\n{r.stderr}")
-    os.replace(tmp, LIB_OUT)
-    return LIB_OUT
+    all_sources = SOURCES + BENCH_SOURCES
+    with ThreadPoolExecutor(max_workers=min(8, len(all_sources))) as pool:
+        objs = list(pool.map(compile_one, all_sources))
+
+    def link(out: Path, objects) -> None:
+        tmp = out.with_suffix(".so.tmp%d" % os.getpid())
+        cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(tmp), *map(str, objects)]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"link failed:\n{r.stderr}")
+        os.replace(tmp, out)
+
+    link(lib, objs[:len(SOURCES)])
+    link(bench_lib, objs)
+    return lib
 
 
 if __name__ == "__main__":

@@ -4,6 +4,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "la_internal.hpp"
@@ -12,17 +13,60 @@
 namespace la {
 namespace {
 
-constexpr int kNumCUs = 256;  // MI355X
+// Compute units of the current device, asked once (256 on MI355X, also the fallback when no device answers, e.g. a
+// workspace query on a machine without a GPU).
+int num_cus() {
+  static std::once_flag once;
+  static int cus = 256;
+  std::call_once(once, [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cus = n;
+  });
+  return cus;
+}
 
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 enum AttnPath { PATH_NONE = 0, PATH_F32, PATH_MFMA };
 
+// Kernel shapes of the MFMA path, numbered as la_attn_desc.kernel_shape - 1 numbers them: the row-tile shapes of
+// attn_mfma_kernel first, then the streaming shapes of attn_stream_kernel.
+struct ShapeInfo {
+  bool stream;
+  int local;       // index inside its kernel's own shape table
+  int tile_m;      // query rows per workgroup
+  int per_cu;      // workgroups that share a CU
+  int step_keys;   // keys a workgroup advances per pipeline step
+  double t_step;   // microseconds per step of one workgroup with the CU shared by per_cu (fitted)
+  double t_fixed;  // microseconds of start-up and write-out per workgroup (fitted)
+};
+int num_shapes() { return attn_mfma_num_shapes() + attn_stream_num_shapes(); }
+ShapeInfo shape_info(int shape) {
+  ShapeInfo s{};
+  if (shape < attn_mfma_num_shapes()) {
+    s.stream = false, s.local = shape;
+    s.tile_m = attn_mfma_tile_m(shape), s.per_cu = attn_mfma_wgs_per_cu(shape), s.step_keys = 64;
+    s.t_step = s.per_cu > 1 ? 2.25 : 1.87;
+    s.t_fixed = s.per_cu > 1 ? 8.0 : 9.0;
+  } else {
+    s.stream = true, s.local = shape - attn_mfma_num_shapes();
+    s.tile_m = attn_stream_tile_m(s.local), s.per_cu = 1;
+    s.step_keys = attn_stream_step_keys(s.local);
+    // every wavefront reduces one 64-key tile for its 32 rows per step, whatever the shape: the time of a step is
+    // the time of two such units on one SIMD
+    s.t_step = s.tile_m == 64 ? 3.0 : s.tile_m == 128 ? 2.6 : 2.8;
+    s.t_fixed = 5.0;
+  }
+  return s;
+}
+
 struct AttnPlan {
   AttnPath path;
   bool kv_fp8, br_fp8;
-  int shape, tile_m, n_row_tiles, chunk_len, s_max, total_units;
+  int shape, tile_m, n_row_tiles, chunk_len, last_short, s_max, total_units;
   size_t part_o_bytes, part_ml_bytes;
 };
 
@@ -36,6 +80,7 @@ la_status validate_desc(const la_attn_desc *d) {
   if (d->max_blocks_per_request < 0) return LA_ERR_INVALID_ARG;
   if (!(d->softmax_scale > 0.f) || !isfinite(d->softmax_scale)) return LA_ERR_INVALID_ARG;
   if (d->kv_split_tokens < 0 || d->kv_split_tokens % 64) return LA_ERR_INVALID_ARG;
+  if (d->kernel_shape < 0 || d->kernel_shape > num_shapes()) return LA_ERR_INVALID_ARG;
   const int32_t dts[4] = {d->q_dtype, d->kv_dtype, d->branch_kv_dtype, d->out_dtype};
   for (int i = 0; i < 4; ++i)
     if (dts[i] < LA_F32 || dts[i] > LA_FP8_E4M3) return LA_ERR_INVALID_ARG;
@@ -46,7 +91,8 @@ la_status validate_desc(const la_attn_desc *d) {
   return LA_OK;
 }
 
-la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, AttnPlan *plan) {
+// extra: the call carries a drafted chain or pool (nested / tree form)
+la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, bool extra, AttnPlan *plan) {
   la_status st = validate_desc(d);
   if (st != LA_OK) return st;
   if (!prefix_lens_host) return LA_ERR_INVALID_ARG;
@@ -76,61 +122,65 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, Attn
   const int G = d->num_q_heads / d->num_kv_heads;
   const int R = d->gamma * d->branch_len * G;
   const size_t n_rows = (size_t)d->gamma * d->branch_len * d->num_q_heads;
+  // the streaming shapes exist for an fp8 cache with fp8 branch K/V, flat calls
+  const bool stream_ok = plan->kv_fp8 && plan->br_fp8 && !extra &&
+                         (int64_t)d->num_kv_heads * d->block_size * d->head_dim < ((int64_t)1 << 32);
+  if (d->kernel_shape > 0 && shape_info(d->kernel_shape - 1).stream && !stream_ok) return LA_ERR_UNSUPPORTED;
 
-  // Choose the kernel shape and the chunk length that minimise a simple cost model (microseconds, constants
+  // Choose the kernel shape and the number of chunks that minimise a simple cost model (microseconds, constants
   // fitted to measurements on MI355X):
-  //   rounds of workgroups over the CU slots  x  (tiles per chunk x time per 64-key tile + fixed start-up)
+  //   rounds of workgroups over the CU slots  x  (steps per chunk x time per step + fixed start-up)
   //   + the merge of the partials (rows x (D+2) floats per chunk, written once and read once).
   // Few long chunks keep the partial traffic small, many short ones fill the chip when there are few rows.
-  // Candidates: the 256-row shape (one workgroup per CU) and the 128-row two-stage shape (two per CU).
-  const int candidates[2] = {0, 1};
-  int forced = -1;
-  if (const char *e = getenv("LA_ATTN_SHAPE")) {  // tuning override: index into the kernel's shape table
-    const int v = atoi(e);
-    if (v >= 0 && v < attn_mfma_num_shapes()) forced = v;
-  }
+  // A request's key tiles are dealt out evenly over its chunks (attn_chunk_range); the workgroup of the last chunk
+  // also runs the branch-private tiles (masked, general form: about three prefix tiles each in the row-tile
+  // shapes, two in the streaming shapes), which count as `last_short` tiles of its share.
   double best_cost = 0.0;
-  int best_len = 0, best_shape = -1;
-  for (int ci = 0; ci < (forced >= 0 ? 1 : 2); ++ci) {
-    const int shape = forced >= 0 ? forced : candidates[ci];
-    const int tile_m = attn_mfma_tile_m(shape);
-    const int per_cu = attn_mfma_wgs_per_cu(shape);
-    const int64_t base_wgs = (int64_t)d->num_kv_heads * ((R + tile_m - 1) / tile_m);
-    const double t_tile = per_cu > 1 ? 2.25 : 1.87;  // per workgroup and 64-key tile, the CU shared by per_cu
-    const double t_fixed = per_cu > 1 ? 8.0 : 9.0;
-    // the workgroup of a request's last chunk also runs the branch-private tiles (masked, not pipelined: about
-    // three times the cost of a prefix tile each), so the last chunk is made that much shorter than the others
-    const int priv_tokens = tile_m / G + d->branch_len < d->gamma * d->branch_len ? tile_m / G + d->branch_len
-                                                                                 : d->gamma * d->branch_len;
-    const int64_t extra_tiles = 3 * (int64_t)((priv_tokens + 63) / 64);
+  int best_len = 0, best_shape = -1, best_short = 0;
+  const int64_t T = (max_p + 63) / 64;
+  for (int shape = 0; shape < num_shapes(); ++shape) {
+    if (d->kernel_shape > 0 && shape != d->kernel_shape - 1) continue;
+    const ShapeInfo si = shape_info(shape);
+    if (si.stream && !stream_ok) continue;
+    const int64_t base_wgs = (int64_t)d->num_kv_heads * ((R + si.tile_m - 1) / si.tile_m);
+    const int priv_tokens = si.tile_m / G + d->branch_len < d->gamma * d->branch_len ? si.tile_m / G + d->branch_len
+                                                                                     : d->gamma * d->branch_len;
+    const int last_short = (si.stream ? 2 : 3) * ((priv_tokens + 63) / 64);
+    const int64_t slots = (int64_t)num_cus() * si.per_cu;
+    // the block ids of one chunk live in LDS (-2: a chunk need not start on a block boundary)
+    const int blk_cap = si.stream ? attn_stream_max_chunk_blocks() : attn_mfma_max_chunk_blocks();
+    const int64_t max_chunk = ((int64_t)(blk_cap - 2) * d->block_size - 64 * (last_short + 2)) / 64 * 64;
+    if (max_chunk < 64 || d->kv_split_tokens > max_chunk) continue;
+    double prev_cost = 0.0;
     for (int n = 1; n <= 512; ++n) {
-      int64_t len = max_p > 0 ? (max_p + (n > 1 ? extra_tiles * 64 : 0) + n - 1) / n : 64;
+      int64_t len = max_p > 0 ? (max_p + n - 1) / n : 64;
       len = ((len + 63) / 64) * 64;
+      if (len > max_chunk) len = max_chunk;
       if (d->kv_split_tokens) len = d->kv_split_tokens;
       int64_t units = 0;
       for (int b = 0; b < d->num_requests; ++b) units += attn_num_chunks(prefix_lens_host[b], (int)len);
-      const int64_t slots = (int64_t)kNumCUs * per_cu;
       const int64_t rounds = (base_wgs * units + slots - 1) / slots;
       const double merge_us = 3.0 + (double)units * n_rows * (d->head_dim + 2) * 4.0 / 3.0e6;  // read at ~3 TB/s
       const int64_t n_max = attn_num_chunks((int)max_p, (int)len);
-      const int64_t last_tiles = (max_p - (n_max - 1) * len + 63) / 64 + extra_tiles;  // of the longest request
-      const int64_t wg_tiles = n_max > 1 && len / 64 > last_tiles ? len / 64 : last_tiles;
-      const double cost = (double)rounds * ((double)wg_tiles * t_tile + t_fixed) + merge_us;
-      if (best_shape < 0 || cost < best_cost) best_cost = cost, best_len = (int)len, best_shape = shape;
+      const int64_t wg_tiles = (T + last_short + n_max - 1) / n_max;  // of the longest request
+      const int64_t wg_steps = (wg_tiles * 64 + si.step_keys - 1) / si.step_keys;
+      const double cost = (double)rounds * ((double)wg_steps * si.t_step + si.t_fixed) + merge_us;
+      if (best_shape < 0 || cost < best_cost)
+        best_cost = cost, best_len = (int)len, best_shape = shape, best_short = last_short;
       if (len <= 64 || d->kv_split_tokens) break;
+      // once every slot is used and the cost has started to rise, more chunks only add partials
+      if (n > 1 && rounds > 1 && cost > prev_cost && base_wgs * units > 4 * slots) break;
+      prev_cost = cost;
     }
   }
+  if (best_shape < 0) return LA_ERR_UNSUPPORTED;
+  const ShapeInfo si = shape_info(best_shape);
   plan->shape = best_shape;
-  plan->tile_m = attn_mfma_tile_m(plan->shape);
+  plan->tile_m = si.tile_m;
   plan->n_row_tiles = (R + plan->tile_m - 1) / plan->tile_m;
-  int chunk = best_len;
-  // the block ids of one chunk live in LDS
-  const int64_t max_chunk = (int64_t)(attn_mfma_max_chunk_blocks() - 1) * d->block_size;  // -1: unaligned chunk start
-  if (chunk > max_chunk) {
-    if (d->kv_split_tokens) return LA_ERR_UNSUPPORTED;
-    chunk = (int)(max_chunk / 64 * 64);
-  }
+  const int chunk = best_len;
   plan->chunk_len = chunk;
+  plan->last_short = best_short;
   int s_max = 1, total = 0;
   for (int b = 0; b < d->num_requests; ++b) {
     const int nc = attn_num_chunks(prefix_lens_host[b], chunk);
@@ -141,69 +191,10 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, Attn
   plan->total_units = total;
   plan->part_o_bytes = align_up((size_t)d->num_requests * s_max * n_rows * d->head_dim * sizeof(float));
   plan->part_ml_bytes = align_up((size_t)d->num_requests * s_max * n_rows * 2 * sizeof(float));
-  if (getenv("LA_DEBUG_PLAN"))
-    fprintf(stderr, "la plan: shape %d (tile_m %d) row_tiles %d chunk_len %d units %d s_max %d\n", plan->shape,
-            plan->tile_m, plan->n_row_tiles, plan->chunk_len, plan->total_units, plan->s_max);
   return LA_OK;
 }
 
-// ---- profiling ---------------------------------------------------------------------------------
-const char *kSlotNames[SLOT_COUNT] = {"attn_mfma",     "attn_merge",   "attn_f32",   "accept_stats", "accept_warp",
-                                      "accept_decide", "accept_resid", "accept_pick", "kv_commit",
-                                      "calib_mfma",    "calib_read"};
-struct ProfileRecord {
-  int slot;
-  hipEvent_t start, stop;
-};
-bool g_profile_on = false;
-uint32_t g_profile_mask = 0xffffffffu;      // slots that are timed
-int g_profile_stride = 1;                   // of their launches, every stride-th one
-int64_t g_seen[SLOT_COUNT];                 // launches of a slot seen while enabled
-std::vector<ProfileRecord> g_records;       // pending (not yet collected)
-std::vector<hipEvent_t> g_free_events;
-int64_t g_launches[SLOT_COUNT];
-double g_total_ms[SLOT_COUNT];
-hipEvent_t g_open_start;                    // start event of the scope being recorded
-bool g_open = false;
-
-hipEvent_t take_event() {
-  if (!g_free_events.empty()) {
-    hipEvent_t e = g_free_events.back();
-    g_free_events.pop_back();
-    return e;
-  }
-  hipEvent_t e = nullptr;
-  if (hipEventCreate(&e) != hipSuccess) return nullptr;
-  return e;
-}
-
 }  // namespace
-
-void profile_before(int slot, hipStream_t stream) {
-  g_open = false;
-  if (!g_profile_on || !((g_profile_mask >> slot) & 1u)) return;
-  if ((g_seen[slot]++ % g_profile_stride) != 0 || g_records.size() >= LA_PROFILE_MAX_RECORDS) return;
-  hipEvent_t e = take_event();
-  if (!e) return;
-  if (hipEventRecord(e, stream) != hipSuccess) {
-    g_free_events.push_back(e);
-    return;
-  }
-  g_open_start = e;
-  g_open = true;
-}
-
-void profile_after(int slot, hipStream_t stream) {
-  if (!g_open) return;
-  g_open = false;
-  hipEvent_t e = take_event();
-  if (!e || hipEventRecord(e, stream) != hipSuccess) {
-    if (e) g_free_events.push_back(e);
-    g_free_events.push_back(g_open_start);
-    return;
-  }
-  g_records.push_back({slot, g_open_start, e});
-}
 
 }  // namespace la
 
@@ -225,10 +216,36 @@ const char *la_status_string(la_status s) {
 la_status la_verify_attention_workspace(const la_attn_desc *desc, const int32_t *prefix_lens_host,
                                         size_t *bytes_out) {
   if (!bytes_out) return LA_ERR_INVALID_ARG;
+  // one size serves the flat, nested and tree calls (their plans may differ)
+  size_t bytes = 0;
+  for (int extra = 0; extra < 2; ++extra) {
+    AttnPlan plan;
+    la_status st = make_plan(desc, prefix_lens_host, extra != 0, &plan);
+    if (extra && st == LA_ERR_UNSUPPORTED) continue;  // a forced shape that only runs flat calls
+    if (st != LA_OK) return st;
+    const size_t need = plan.path == PATH_MFMA ? plan.part_o_bytes + plan.part_ml_bytes : 0;
+    bytes = need > bytes ? need : bytes;
+  }
+  *bytes_out = bytes;
+  return LA_OK;
+}
+
+la_status la_verify_attention_plan(const la_attn_desc *desc, const int32_t *prefix_lens_host, int32_t chain_len,
+                                   la_attn_plan *out) {
+  if (!out || chain_len < 0) return LA_ERR_INVALID_ARG;
   AttnPlan plan;
-  la_status st = make_plan(desc, prefix_lens_host, &plan);
+  la_status st = make_plan(desc, prefix_lens_host, chain_len > 0, &plan);
   if (st != LA_OK) return st;
-  *bytes_out = plan.path == PATH_MFMA ? plan.part_o_bytes + plan.part_ml_bytes : 0;
+  memset(out, 0, sizeof *out);
+  out->path = (int32_t)plan.path;
+  if (plan.path == PATH_MFMA) {
+    out->kernel_shape = plan.shape + 1;
+    out->rows_per_workgroup = plan.tile_m;
+    out->row_tiles = plan.n_row_tiles;
+    out->chunk_tokens = plan.chunk_len;
+    out->chunks_total = plan.total_units;
+    out->workgroups = desc->num_kv_heads * plan.n_row_tiles * plan.total_units;
+  }
   return LA_OK;
 }
 
@@ -243,7 +260,7 @@ static la_status verify_attention(const la_attn_desc *desc, const void *q, const
                                   const float *v_scale, void *out, float *lse, void *workspace,
                                   size_t workspace_bytes, void *hip_stream) {
   AttnPlan plan;
-  la_status st = make_plan(desc, prefix_lens_host, &plan);
+  la_status st = make_plan(desc, prefix_lens_host, chain_len > 0, &plan);
   if (st != LA_OK) return st;
   if (!q || !prefix_lens || !k_branch || !v_branch || !out) return LA_ERR_INVALID_ARG;
   bool any_prefix = false;
@@ -290,10 +307,28 @@ static la_status verify_attention(const la_attn_desc *desc, const void *q, const
   if (plan.path == PATH_F32) return launch_attn_f32(p, stream) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 
   p.n_row_tiles = plan.n_row_tiles, p.chunk_len = plan.chunk_len, p.s_max = plan.s_max;
+  p.last_short = plan.last_short;
   p.total_units = plan.total_units;
   p.part_o = (float *)workspace;
   p.part_ml = (float *)((uint8_t *)workspace + plan.part_o_bytes);
-  if (launch_attn_mfma(p, plan.shape, plan.kv_fp8, plan.br_fp8, stream) != hipSuccess) return LA_ERR_LAUNCH;
+  if (p.B <= kMaxInlineLens) {
+    p.n_inline = p.B;
+    for (int b = 0; b < p.B; ++b) {
+      AttnParams::Req &rq = p.req[b];
+      rq.P = prefix_lens_host[b];
+      rq.n = attn_num_chunks(rq.P, p.chunk_len);
+      const int64_t tv = ((int64_t)rq.P + 63) / 64 + p.last_short;
+      rq.q = (int)(tv / rq.n), rq.r = (int)(tv % rq.n);
+      // n == 1: r == 0, the quotient is never needed.  The multiply-shift is exact for x < 2^32 / n; the kernel
+      // applies it to x <= n * r < n^2, so very many chunks take the kernel's general path instead.
+      rq.inv = rq.n > 1 ? (uint32_t)(((uint64_t)1 << 32) / (uint64_t)rq.n) + 1u : 0u;
+      if (rq.n > 1024) p.n_inline = 0;
+    }
+  }
+  const ShapeInfo si = shape_info(plan.shape);
+  const hipError_t e =
+      si.stream ? launch_attn_stream(p, si.local, stream) : launch_attn_mfma(p, si.local, plan.kv_fp8, plan.br_fp8, stream);
+  if (e != hipSuccess) return LA_ERR_LAUNCH;
   if (launch_attn_merge(p, stream) != hipSuccess) return LA_ERR_LAUNCH;
   return LA_OK;
 }
@@ -435,11 +470,6 @@ static la_status validate_accept(const la_accept_desc *d) {
   return LA_OK;
 }
 
-la_status la_selftest_exp64(const double *y, double *out, size_t n, void *hip_stream) {
-  if (!y || !out || n < 1 || n > ((size_t)1 << 30)) return LA_ERR_INVALID_ARG;
-  return launch_exp64_probe(y, out, n, (hipStream_t)hip_stream) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
-}
-
 la_status la_spec_accept_workspace(const la_accept_desc *desc, size_t *bytes_out) {
   la_status st = validate_accept(desc);
   if (st != LA_OK) return st;
@@ -474,51 +504,6 @@ la_status la_spec_accept(const la_accept_desc *desc, const void *target_logits, 
   p.top_k = desc->top_k, p.top_p = desc->top_p;
   accept_carve_workspace(p, workspace);
   return launch_accept(p, (hipStream_t)hip_stream) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
-}
-
-la_status la_profile_select(uint32_t slot_mask, int32_t stride) {
-  if (stride < 1) return LA_ERR_INVALID_ARG;
-  g_profile_mask = slot_mask;
-  g_profile_stride = stride;
-  return LA_OK;
-}
-
-la_status la_profile_enable(int on) {
-  g_profile_on = on != 0;
-  return LA_OK;
-}
-
-la_status la_profile_collect(void) {
-  la_status st = LA_OK;
-  for (const ProfileRecord &r : g_records) {
-    float ms = 0.f;
-    if (hipEventSynchronize(r.stop) == hipSuccess && hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
-      g_launches[r.slot] += 1;
-      g_total_ms[r.slot] += ms;
-    } else {
-      st = LA_ERR_LAUNCH;
-    }
-    g_free_events.push_back(r.start);
-    g_free_events.push_back(r.stop);
-  }
-  g_records.clear();
-  return st;
-}
-
-int32_t la_profile_num_kernels(void) { return SLOT_COUNT; }
-
-la_status la_profile_get(int32_t slot, const char **name, int64_t *launches, double *total_ms) {
-  if (slot < 0 || slot >= SLOT_COUNT) return LA_ERR_INVALID_ARG;
-  if (name) *name = kSlotNames[slot];
-  if (launches) *launches = g_launches[slot];
-  if (total_ms) *total_ms = g_total_ms[slot];
-  return LA_OK;
-}
-
-la_status la_profile_reset(void) {
-  la_status st = la_profile_collect();
-  for (int i = 0; i < SLOT_COUNT; ++i) g_launches[i] = 0, g_total_ms[i] = 0.0, g_seen[i] = 0;
-  return st;
 }
 
 }  // extern "C"

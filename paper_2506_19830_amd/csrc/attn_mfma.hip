@@ -22,6 +22,8 @@
 //                    free and the four db accumulators of a lane adjacent columns),
 //                    B = P^T (registers, bf16)
 // Everything is kept in log2 units: p = 2^(s*c - m).
+#include <mutex>
+
 #include "attn_common.hpp"
 
 namespace la {
@@ -240,131 +242,6 @@ __device__ __forceinline__ void tile_store(uint8_t *stage, int tid, const TileRe
   }
 }
 
-
-// Per-wavefront state of RB blocks of 32 query rows.
-template <int RB>
-struct RowState {
-  bf16x8 qf[RB][8];  // Q^T operand, already multiplied by the prefix score scale (log2 units): row ln of block rb,
-                     // d = 16t + 8*lh .. +8
-  f32x16 o[4][RB];   // O^T accumulators: d block db, row block rb
-  f32x16 negb[RB];   // every element = -base: the accumulator a full prefix tile's S^T starts from, so that the
-                     // MFMAs deliver s - base directly
-  float base[RB];    // == m_run once a maximum exists, 0 before
-  float m_run[RB], l_run[RB];
-  int row_tok[RB], row_bstart[RB];
-  // tree form only: the segments the row's branch sees, and (lane k) the segment of key k of the current pool tile
-  uint64_t row_mask[RB];
-  int tile_seg;
-};
-
-enum MaskMode { MASK_NONE = 0, MASK_TAIL = 1, MASK_BRANCH = 2, MASK_TREE = 3 };
-
-// sched_group_barrier masks
-constexpr int kSgMfma = 0x008, kSgValu = 0x002, kSgSalu = 0x004, kSgVmemRead = 0x020, kSgDsRead = 0x100;
-
-// Mask the scores of one 32-key block: register j holds key  kb*32 + (j/4)*8 + lh*4 + j%4  of the tile.
-template <int RB, int MASK>
-__device__ __forceinline__ void mask_block(f32x16 (&s)[RB], const RowState<RB> &st, int kb, int lh, int first,
-                                           int limit) {
-  if constexpr (MASK == MASK_TAIL) {
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const int key = first + kb * 32 + (j >> 2) * 8 + lh * 4 + (j & 3);
-      if (key >= limit) {
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) s[rb][j] = -INFINITY;
-      }
-    }
-  } else if constexpr (MASK == MASK_BRANCH) {
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const int tk = first + kb * 32 + (j >> 2) * 8 + lh * 4 + (j & 3);
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-        if (tk > st.row_tok[rb] || tk < st.row_bstart[rb]) s[rb][j] = -INFINITY;
-    }
-  } else if constexpr (MASK == MASK_TREE) {
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const int ka = kb * 32 + (j >> 2) * 8 + (j & 3);  // this register's key in the lower lane half; upper: + 4
-      const int sa = __builtin_amdgcn_readlane(st.tile_seg, ka), sb = __builtin_amdgcn_readlane(st.tile_seg, ka + 4);
-      const int seg = lh ? sb : sa;
-      const bool past = first + ka + lh * 4 >= limit;
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-        if (past || !((st.row_mask[rb] >> seg) & 1)) s[rb][j] = -INFINITY;
-    }
-  }
-}
-
-// Absolute maximum (log2 units) of one 32-key block per row.  The scores arrive as x with absolute value
-// x*crel + binit (binit: what the accumulators were started from, per lane).
-template <int RB>
-__device__ __forceinline__ void block_max(const f32x16 (&s)[RB], float crel, const float (&binit)[RB],
-                                          float (&mt)[RB]) {
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    float ma = fmaxf(fmaxf(s[rb][0], s[rb][1]), s[rb][2]);
-    float mb = fmaxf(fmaxf(s[rb][8], s[rb][9]), s[rb][10]);
-    ma = fmaxf(fmaxf(ma, s[rb][3]), s[rb][4]);
-    mb = fmaxf(fmaxf(mb, s[rb][11]), s[rb][12]);
-    ma = fmaxf(fmaxf(ma, s[rb][5]), s[rb][6]);
-    mb = fmaxf(fmaxf(mb, s[rb][13]), s[rb][14]);
-    const float m0 = fmaxf(fmaxf(ma, s[rb][7]), fmaxf(mb, s[rb][15]));
-    mt[rb] = __builtin_fmaf(xhalf_max(m0), crel, binit[rb]);
-  }
-}
-
-// Fold the block maxima into the running maxima.  A lane raises its maximum only when the block exceeds it by more
-// than kRaise; alpha is the factor its old accumulators must then be multiplied by (1 for lanes that keep their
-// maximum).  Returns whether any lane of the wavefront raised (wavefront-uniform).
-template <int RB>
-__device__ __forceinline__ bool raise_max(const float (&mt)[RB], RowState<RB> &st, float (&alpha)[RB]) {
-  bool raise = false;
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    const bool up = mt[rb] > st.m_run[rb] + kRaise;   // false for mt = -inf; true for the first finite block
-    const float m_new = up ? mt[rb] : st.m_run[rb];
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    alpha[rb] = up ? __builtin_amdgcn_exp2f(st.m_run[rb] - m_use) : 1.0f;   // 0 when m_run was -inf
-    st.m_run[rb] = m_new;
-    raise |= up;
-  }
-  return __builtin_amdgcn_ballot_w64(raise) != 0;
-}
-
-template <int RB>
-__device__ __forceinline__ void rescale(RowState<RB> &st, const float (&alpha)[RB]) {
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    st.l_run[rb] *= alpha[rb];
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int j = 0; j < 16; ++j) st.o[db][rb][j] *= alpha[rb];
-  }
-}
-
-// p = 2^(x*crel + off) for one 32-key block, rounded to bf16 pairs; also the fp32 row sums.  off = binit + voff - m
-// per lane.  FAST: crel == 1 and off == 0 for every lane (accumulators started from -m), so p = 2^x.
-template <int RB, bool FAST>
-__device__ __forceinline__ void block_probs(const f32x16 (&s)[RB], float crel, const float (&off)[RB],
-                                            uint32_t (&pb)[RB][8], float (&sum)[RB]) {
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    float acc = 0.f;
-#pragma unroll
-    for (int j = 0; j < 16; j += 2) {
-      const float p0 = __builtin_amdgcn_exp2f(FAST ? s[rb][j] : __builtin_fmaf(s[rb][j], crel, off[rb]));
-      const float p1 = __builtin_amdgcn_exp2f(FAST ? s[rb][j + 1] : __builtin_fmaf(s[rb][j + 1], crel, off[rb]));
-      pb[rb][j >> 1] = pack_bf16(p0, p1);
-      // (a v_dot2c_f32_bf16 on the packed pair would sum the rounded values in one instruction, but on gfx950 it
-      // stalls against the MFMAs in flight: measured slower than the two adds)
-      acc += p0 + p1;
-    }
-    sum[rb] = acc;
-  }
-}
 
 // One 64-key tile from an LDS stage, as two 32-key blocks whose MFMA and VALU work is interleaved:
 //     S0 = K0 Q^T                    |
@@ -597,8 +474,8 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
   // workgroups are dispatched in blockIdx order: the last chunk, which also carries the chain and branch-private
   // tiles and so runs longest, goes first instead of into the tail of the launch
   c = n_chunks - 1 - c;
-  const int k_begin = c * p.chunk_len;
-  const int k_end = min(P, k_begin + p.chunk_len);
+  int k_begin, k_end;
+  attn_chunk_range(P, p.chunk_len, p.last_short, c, &k_begin, &k_end);
   const int n_full = k_end > k_begin ? (k_end - k_begin) / kTileN : 0;          // unmasked prefix tiles
   const bool has_tail = k_end > k_begin && ((k_end - k_begin) % kTileN) != 0;  // one partly filled prefix tile
 
@@ -913,14 +790,14 @@ template <bool KV_FP8, bool BR_FP8, int NW, int RB, int STAGES, int EXTRA>
 hipError_t launch_variant(const AttnParams &p, hipStream_t stream) {
   const int grid = p.Hkv * p.n_row_tiles * p.total_units;
   auto kern = attn_mfma_kernel<KV_FP8, BR_FP8, NW, RB, STAGES, EXTRA>;
-  static bool configured = false;  // per template instance
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static std::once_flag once;  // per template instance
+  static hipError_t configured = hipSuccess;
+  std::call_once(once, [&] {
+    configured = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
+  });
+  if (configured != hipSuccess) return configured;
   // the tile stages plus the block ids of one chunk (a chunk that does not start on a block boundary spans one more)
-  const int blk_entries = (p.chunk_len >> p.block_shift) + 2;
+  const int blk_entries = (attn_max_chunk_tokens(p.chunk_len, p.last_short) >> p.block_shift) + 2;
   const int lds_bytes = STAGES * kStageBytes + (blk_entries < kMaxChunkBlocks ? blk_entries : kMaxChunkBlocks) * 4;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NW), lds_bytes, stream, p);
   return hipGetLastError();

@@ -1,0 +1,551 @@
+// Shared-prefix verify attention, streaming shape (gfx950): few query rows per KV head.
+//
+// With few rows R = gamma*L*G per KV head the pass is bound by the K/V stream of the shared prefix (Algorithm 1:
+// every candidate x'_j re-reads x_{1:t}), not by the matrix cores.  This shape is built around keeping that
+// stream saturated:
+//   * K/V tiles go global -> LDS directly (global_load_lds_dwordx4, 16 bytes per lane, no staging registers), as
+//     stored (fp8 stays fp8), NST stages deep, issued NST-1 steps ahead of their use;
+//   * the MFMA operands are formed at the fragment read: K rows as they lie (the contraction runs over d),
+//     V through the transposing LDS read (ds_read_b64_tr_b8: each lane receives one head-dim column of eight
+//     keys), fp8 widened to bf16 in registers (exact);
+//   * a workgroup is eight wavefronts = NRB row blocks of 32 rows x KSL = 8/NRB key slices: per pipeline step of
+//     KSL consecutive 64-key tiles, wavefront (rb, ks) reduces tile ks for its 32 rows, so that two wavefronts
+//     per SIMD work even when there are only 64 rows; the slices of a row block are folded through LDS at the
+//     end and leave one partial per row;
+//   * Q comes through LDS as well (one direct load per MFMA step, each lane fetching exactly the fragment it
+//     later reads back), so that every vector memory operation of the kernel is a direct load whose completion
+//     the kernel counts itself.
+// The last chunk's workgroup also reduces the branch-private keys (causal inside the branch), as further steps
+// of the same pipeline.
+//
+// LDS layout of a tile half (K or V, 64 key rows of 128 bytes): a wavefront-wide load lands as 1 KiB in lane
+// order, i.e. eight key rows x eight 16-byte pieces.  Piece p of key k is stored in slot p ^ swz(k); the
+// swizzle is applied to the *global* address a lane fetches, and chosen such that the fragment reads
+// (16 consecutive keys at one piece for K; eight keys x two pieces for V) spread over all banks.
+#include <mutex>
+
+#include "attn_common.hpp"
+
+namespace la {
+namespace {
+
+constexpr int kD = 128;
+constexpr int kTileN = 64;
+constexpr int kRowBytes = kD;                  // fp8
+constexpr int kHalfBytes = kTileN * kRowBytes;  // K (or V) part of a tile
+constexpr int kTileBytes = 2 * kHalfBytes;      // 16 KiB
+constexpr int kInstPerHalf = 8;                 // 1 KiB loads per tile half
+constexpr int kMaxBlkLds = 2048;                // block ids of one chunk kept in LDS
+constexpr int kWaves = 8;
+
+#define LA_LDS __attribute__((address_space(3)))
+typedef __attribute__((ext_vector_type(2))) int i32x2;
+
+__device__ __forceinline__ int swz_k(int key) { return (key >> 1) & 7; }
+__device__ __forceinline__ int swz_v(int key) { return (((key >> 1) & 1) << 1) | (((key >> 3) & 1) << 2) | ((key >> 2) & 1); }
+
+// s_waitcnt vmcnt(n) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, the other counters left at their maxima)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0070 | 0x0F00);
+}
+
+// 16 bytes per lane global -> LDS: the wavefront's 64 pieces land at lds_addr + 16*lane.  Issued from inline
+// assembly so that the compiler does not see an LDS write in flight (it would otherwise put a full vmcnt(0) wait
+// in front of the transposing LDS reads, which carry no address information for it, and so drain the whole prefetch
+// queue in every tile); the kernel orders these loads against its LDS reads itself (wait_vmcnt + s_barrier; the
+// barrier is also what keeps the compiler from moving LDS accesses across a pipeline step, so the statement needs
+// no memory clobber -- with one, every local whose address a lambda captured would be pinned to scratch memory).
+__device__ __forceinline__ void load_lds16(const void *src, uint32_t lds_addr) {
+  lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);  // wavefront-uniform by construction; pin it to a scalar register
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "m0");
+}
+
+// eight fp8 (two words) -> eight bf16
+__device__ __forceinline__ bf16x8 widen8(uint32_t w0, uint32_t w1) {
+  u32x4 v = {fp8x2_to_bf16x2<false>(w0), fp8x2_to_bf16x2<true>(w0), fp8x2_to_bf16x2<false>(w1),
+             fp8x2_to_bf16x2<true>(w1)};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// s_waitcnt vmcnt(later * IPW) for a run-time `later` in 0..MAXL (wavefront-uniform)
+template <int IPW, int MAXL>
+__device__ __forceinline__ void wait_later(int later) {
+  if constexpr (MAXL == 0) {
+    wait_vmcnt<0>();
+  } else {
+    if (later >= MAXL)
+      wait_vmcnt<MAXL * IPW>();
+    else
+      wait_later<IPW, MAXL - 1>(later);
+  }
+}
+
+// One 64-key tile (fp8, in LDS) against the wavefront's 32 rows, as two 32-key blocks whose MFMA and VALU work
+// alternate (S0; S1 next to P0; O += V0 P0 next to P1; O += V1 P1).  Same arithmetic as the row-tile kernel:
+// S^T = K Q^T, p = 2^(s - m) with the maximum folded into the accumulator start for unmasked tiles, O^T += V^T P^T.
+//   kt        the K half of the tile; the V half lies kHalfBytes on
+//   koff[u]   lane's byte offset for piece 2u + lh of key ln (key block 0; block 1 is 32 rows on)
+//   voff[db]  lane's byte offset for the transposing read of head-dim block db (first 16 keys; the others 16 rows on)
+//   qfrag     the lane's Q fragments in LDS: fragment s (MFMA step s) lies s KiB on
+template <int MASK>
+__device__ __forceinline__ void stream_tile(const uint8_t *kt, const uint8_t *qfrag, RowState<1> &st,
+                                            const int (&koff)[4], const int (&voff)[4], int lh, int first,
+                                            int limit) {
+  const uint8_t *vt = kt + kHalfBytes;
+  constexpr bool kFastable = MASK == MASK_NONE;
+  float binit[1] = {kFastable ? st.base[0] : 0.f};
+  auto pv = [&](int kb, const uint32_t (&pb)[1][8]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2) {
+      const u32x4 pw = {pb[0][4 * t2], pb[0][4 * t2 + 1], pb[0][4 * t2 + 2], pb[0][4 * t2 + 3]};
+      const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
+      u32x2 vraw[4];
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+        vraw[db] = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr8_b64_v2i32((LA_LDS i32x2 *)(
+                                                 vt + (kb * 32 + t2 * 16) * kRowBytes + voff[db])));
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+        st.o[db][0] =
+            __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen8(vraw[db][0], vraw[db][1]), pf, st.o[db][0], 0, 0, 0);
+    }
+  };
+  auto exp_offset = [&](float (&off)[1]) __attribute__((always_inline)) {
+    off[0] = binit[0] - ((st.m_run[0] == -INFINITY) ? 0.f : st.m_run[0]);
+  };
+
+  f32x16 s0[1], s1[1];
+  uint32_t p0[1][8], p1[1][8];
+  float sum0[1], sum1[1], mt[1], alpha[1], off[1];
+  // S^T = K Q^T of both key blocks: MFMA step 2u + e contracts over d = 32u + 16lh + 8e .. +8, the two halves of
+  // one 16-byte K piece; the Q fragments (already scaled, bf16) are read from LDS as they are needed rather than held
+  // in 32 registers (two wavefronts per SIMD leave 256 each).  Unmasked tiles start the accumulators from -base
+  // (== the running maximum once one exists), so that the MFMAs deliver s - m and a probability is one exponential.
+  {
+    const float nb = kFastable ? -st.base[0] : 0.f;
+    s0[0] = f32x16{nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb};
+    s1[0] = s0[0];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const bf16x8 qa = *(const bf16x8 *)(qfrag + (2 * u) * 1024);
+      const bf16x8 qb = *(const bf16x8 *)(qfrag + (2 * u + 1) * 1024);
+      const u32x4 r0 = *(const u32x4 *)(kt + koff[u]);
+      const u32x4 r1 = *(const u32x4 *)(kt + 32 * kRowBytes + koff[u]);
+      s0[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen8(r0[0], r0[1]), qa, s0[0], 0, 0, 0);
+      s1[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen8(r1[0], r1[1]), qa, s1[0], 0, 0, 0);
+      s0[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen8(r0[2], r0[3]), qb, s0[0], 0, 0, 0);
+      s1[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen8(r1[2], r1[3]), qb, s1[0], 0, 0, 0);
+    }
+  }
+  mask_block<1, MASK>(s0, st, 0, lh, first, limit);
+  if constexpr (kFastable) block_probs<1, true>(s0, 1.f, off, p0, sum0);
+  block_max<1>(s0, 1.f, binit, mt);
+  const bool raise0 = raise_max<1>(mt, st, alpha);
+  if (!kFastable || raise0) {
+    if (raise0) rescale<1>(st, alpha);
+    exp_offset(off);
+    block_probs<1, false>(s0, 1.f, off, p0, sum0);
+  }
+  st.l_run[0] += sum0[0];
+  pv(0, p0);
+  __builtin_amdgcn_sched_barrier(0);
+  mask_block<1, MASK>(s1, st, 1, lh, first, limit);
+  if constexpr (kFastable) block_probs<1, true>(s1, 1.f, off, p1, sum1);
+  block_max<1>(s1, 1.f, binit, mt);
+  const bool raise1 = raise_max<1>(mt, st, alpha);  // the accumulators now hold block 0 in the old units
+  if (!kFastable || raise0 || raise1) {  // after a raise in block 0, S1 is no longer relative to the maximum
+    if (raise1) rescale<1>(st, alpha);
+    exp_offset(off);
+    block_probs<1, false>(s1, 1.f, off, p1, sum1);
+  }
+  if (raise0 || raise1) st.base[0] = (st.m_run[0] == -INFINITY) ? 0.f : st.m_run[0];  // base == running maximum
+  st.l_run[0] += sum1[0];
+  pv(1, p1);
+}
+
+// The direct K/V loads of one wavefront.  A step is KSL tiles x (8 + 8) loads of 1 KiB (eight key rows each);
+// wavefront w issues loads w*IPW .. w*IPW + IPW-1 of every step.  Lane l fetches 16 bytes of key row l/8 of those
+// eight: slot l%8, i.e. global piece (l%8) ^ swz(key).  Every wavefront issues exactly IPW loads per step, so the
+// load counter advances uniformly; where a step reaches past the end of its key range (a ragged last tile, a tile
+// slot that has no tile) the tokens are clamped to the last valid one and all addresses stay in bounds.
+// (A plain struct of values rather than a capturing lambda: captured locals would be pinned to scratch memory.)
+template <int KSL, int NST, int IPW>
+struct StreamLoader {
+  uint32_t ring;                 // LDS address of the ring
+  int wave;
+  const int32_t *blk;            // LDS: block ids of the chunk (paged), or null: block = ident + logical block
+  int first_lb, ident, shift, bs_mask;
+  uint32_t blk_stride, br_stride;  // bytes between cache blocks / between branch tokens
+  const uint8_t *k_pre, *v_pre, *k_br, *v_br;
+  int key[IPW], goff[IPW];       // per lane: key inside the tile, byte offset inside the key row
+
+  __device__ __forceinline__ void init_lane(int lane) {
+#pragma unroll
+    for (int j = 0; j < IPW; ++j) {
+      const int r = (wave * IPW + j) & 15, half = r >> 3;
+      const int k = 8 * (r & 7) + (lane >> 3);
+      key[j] = k;
+      goff[j] = ((lane & 7) ^ (half ? swz_v(k) : swz_k(k))) * 16;
+    }
+  }
+  // PREFIX: cache tokens first0 .. (through the block table); else branch tokens.  CLAMP: tokens above `last`
+  // repeat token `last`.
+  template <bool PREFIX, bool CLAMP>
+  __device__ __forceinline__ void issue(int slot, int first0, int last) const {
+    const uint32_t stage = ring + slot * (KSL * kTileBytes);
+#pragma unroll
+    for (int j = 0; j < IPW; ++j) {
+      const int ii = wave * IPW + j;  // wavefront-uniform: which 1 KiB of the step
+      const int tile = ii >> 4, half = (ii >> 3) & 1, r8 = ii & 7;
+      int tok = first0 + tile * kTileN + key[j];
+      if (CLAMP) tok = min(tok, last);
+      const uint8_t *src;
+      if (PREFIX) {
+        const int lb = tok >> shift;
+        const uint32_t b = blk ? (uint32_t)blk[lb - first_lb] : (uint32_t)(ident + lb);
+        const uint32_t inner = ((uint32_t)(tok & bs_mask) << 7) + (uint32_t)goff[j];
+        src = (half ? v_pre : k_pre) + ((uint64_t)b * blk_stride + inner);  // one 32 x 32 + 64 multiply-add
+      } else {
+        src = (half ? v_br : k_br) + ((uint64_t)(uint32_t)tok * br_stride + (uint32_t)goff[j]);
+      }
+      load_lds16(src, stage + tile * kTileBytes + half * kHalfBytes + r8 * 1024);
+    }
+  }
+};
+
+// NRB row blocks of 32 rows per workgroup; KSL = 8/NRB tiles per pipeline step; a ring of kSlots tile slots behind
+// the Q fragments.
+template <int NRB>
+struct StreamShape {
+  static constexpr int KSL = kWaves / NRB;
+  static constexpr int kQBytes = NRB * 8192;         // Q of the row blocks, as MFMA fragments
+  static constexpr int kRingOff = kQBytes;
+  static constexpr int kSlots = ((152 * 1024 - kQBytes) / kTileBytes) / KSL * KSL;
+  static constexpr int NST = kSlots / KSL;           // steps the ring holds
+  static constexpr int IPW = 16 * KSL / kWaves;      // direct loads per wavefront and step
+  static constexpr int kBlkOff = kRingOff + kSlots * kTileBytes;
+  static constexpr int kLdsMax = kBlkOff + kMaxBlkLds * 4;
+  static_assert(NST >= 2, "one step in flight while another is computed on");
+  static_assert(kLdsMax <= 160 * 1024, "LDS of one CU");
+  static constexpr int kFoldBytes = kWaves * 66 * 64 * 4;  // the fold of the key slices reuses the whole space
+  static_assert(kFoldBytes <= kLdsMax, "fold space");
+};
+
+template <int NRB>
+__global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnParams p) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  using S = StreamShape<NRB>;
+  constexpr int KSL = S::KSL, NST = S::NST, IPW = S::IPW;
+  constexpr int NT = 64 * kWaves;
+  constexpr int kTileM = 32 * NRB;
+  constexpr int kStepBytes = KSL * kTileBytes;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ln = lane & 31, lh = lane >> 5;
+  const int rb = wave % NRB, ks = wave / NRB;
+
+  // ---- which (kv head, row tile, request, chunk) -------------------------------------------
+  // (integer divisions run in vector registers; pinning the results to scalar registers keeps what depends on
+  // them -- the scale loads among it -- on the scalar side, away from the vector memory counter)
+  int id = blockIdx.x;
+  const int kvh = __builtin_amdgcn_readfirstlane(id % p.Hkv);
+  id = __builtin_amdgcn_readfirstlane(id / p.Hkv);
+  const int row_tile = __builtin_amdgcn_readfirstlane(id % p.n_row_tiles);
+  int c = __builtin_amdgcn_readfirstlane(id / p.n_row_tiles);
+  int b = 0, P = 0, n_chunks = 1, k_begin, k_end;
+  if (p.n_inline) {
+    // few requests: everything comes from the kernel arguments (indexed with constants only, so that it stays in
+    // scalar registers), no load and no division
+    int q = 0, r = 0;
+    uint32_t inv = 0;
+    bool found = false;
+#pragma unroll
+    for (int i = 0; i < kMaxInlineLens; ++i) {
+      if (!found && i < p.B) {
+        if (c < p.req[i].n || i == p.B - 1) {
+          b = i, P = p.req[i].P, n_chunks = p.req[i].n, q = p.req[i].q, r = p.req[i].r, inv = p.req[i].inv;
+          found = true;
+        } else {
+          c -= p.req[i].n;
+        }
+      }
+    }
+    c = n_chunks - 1 - c;  // the last chunk (it also carries the private tiles) is dispatched first
+    // attn_chunk_range with floor(c * (q*n + r) / n) = c*q + floor(c*r / n) and the quotient by multiply-shift
+    const int T = (P + 63) >> 6;
+    const int t0 = min(T, c * q + (int)__umulhi((uint32_t)(c * r), inv));
+    const int t1 = c == n_chunks - 1 ? T : min(T, (c + 1) * q + (int)__umulhi((uint32_t)((c + 1) * r), inv));
+    k_begin = t0 * 64;
+    k_end = min(P, t1 * 64);
+  } else {
+    for (; b < p.B - 1; ++b) {
+      const int nc = attn_num_chunks(p.prefix_lens[b], p.chunk_len);
+      if (c < nc) break;
+      c -= nc;
+    }
+    P = p.prefix_lens[b];
+    n_chunks = attn_num_chunks(P, p.chunk_len);
+    c = n_chunks - 1 - c;
+    attn_chunk_range(P, p.chunk_len, p.last_short, c, &k_begin, &k_end);
+  }
+  const int n_pre_tiles = (k_end - k_begin + kTileN - 1) / kTileN;
+  const int n_pre_steps = (n_pre_tiles + KSL - 1) / KSL;
+  const int n_full_steps = (k_end - k_begin) / (KSL * kTileN);  // steps all of whose keys exist
+
+  const int r0 = row_tile * kTileM;
+  const int r1 = min(p.R, r0 + kTileM);
+  const int gl = p.gamma * p.L;
+  // (integer divisions run in vector registers; these values are the same in every lane)
+  const int t_lo = __builtin_amdgcn_readfirstlane(r0 / p.G), t_hi = __builtin_amdgcn_readfirstlane((r1 - 1) / p.G);
+  const int tk0 = __builtin_amdgcn_readfirstlane((t_lo / p.L) * p.L);
+  const int n_priv = (c == n_chunks - 1) ? (t_hi - tk0 + 1 + kTileN - 1) / kTileN : 0;
+  const int n_steps = n_pre_steps + (n_priv + KSL - 1) / KSL;
+
+  // ---- physical block ids of this chunk -> LDS (paged caches only) ------------------------------
+  int32_t *blk_lds = (int32_t *)(lds + S::kBlkOff);
+  const int first_lb = k_begin >> p.block_shift;
+  const int32_t *table = p.block_tables ? p.block_tables + (size_t)b * p.max_blocks : nullptr;
+  if (table) {  // (uniform over the workgroup)
+    if (k_end > k_begin) {
+      const int n_blk = ((k_end - 1) >> p.block_shift) - first_lb + 1;  // <= kMaxBlkLds (host guarantees)
+      for (int i = tid; i < n_blk; i += NT) blk_lds[i] = table[first_lb + i];
+    }
+    __syncthreads();
+  }
+  const uint32_t lds0 = (uint32_t)(size_t)(LA_LDS uint8_t *)lds;
+
+  // ---- Q -> LDS: wavefront rb < NRB fetches the fragments of row block rb, lane (ln, lh) exactly the 16 bytes
+  //      of its row that it (and the same lane of every wavefront of that row block) reads back for MFMA step s:
+  //      d = 32*(s/2) + 16*lh + 8*(s%2) .. +8, the halves of the K piece the lane reads.  Rows past R repeat
+  //      row R-1 (their fragments are zeroed after the read-back).
+  const int row = r0 + rb * 32 + ln;
+  const int rr = min(row, p.R - 1);
+  const int row_tok = rr / p.G;
+  if (wave < NRB) {
+    const uint8_t *qrow = (const uint8_t *)p.q + (((size_t)b * gl + row_tok) * p.Hq + kvh * p.G + (rr % p.G)) * (size_t)(kD * 2);
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+      load_lds16(qrow + (32 * (s >> 1) + 16 * lh + 8 * (s & 1)) * 2, lds0 + wave * 8192 + s * 1024);
+  }
+
+  // ---- the direct K/V loads of this wavefront; the stream starts now ----------------------------------
+  const size_t br_off = ((size_t)b * gl * p.Hkv + kvh) * kRowBytes;
+  StreamLoader<KSL, NST, IPW> ld;
+  ld.ring = lds0 + S::kRingOff, ld.wave = wave;
+  ld.blk = table ? blk_lds : nullptr;
+  ld.first_lb = first_lb, ld.ident = b * p.max_blocks, ld.shift = p.block_shift, ld.bs_mask = p.block_size - 1;
+  ld.blk_stride = (uint32_t)((p.Hkv << p.block_shift) * kRowBytes), ld.br_stride = (uint32_t)(p.Hkv * kRowBytes);
+  ld.k_pre = (const uint8_t *)p.k_cache + ((size_t)kvh << p.block_shift) * kRowBytes;
+  ld.v_pre = (const uint8_t *)p.v_cache + ((size_t)kvh << p.block_shift) * kRowBytes;
+  ld.k_br = (const uint8_t *)p.k_branch + br_off;
+  ld.v_br = (const uint8_t *)p.v_branch + br_off;
+  ld.init_lane(lane);
+  auto issue = [&](int step) __attribute__((always_inline)) {
+    const int slot = step % NST;
+    if (step < n_full_steps)
+      ld.template issue<true, false>(slot, k_begin + step * (KSL * kTileN), 0);
+    else if (step < n_pre_steps)
+      ld.template issue<true, true>(slot, k_begin + step * (KSL * kTileN), k_end - 1);
+    else
+      ld.template issue<false, true>(slot, tk0 + (step - n_pre_steps) * (KSL * kTileN), t_hi);
+  };
+  for (int s = 0; s < NST - 1; ++s)
+    if (s < n_steps) issue(s);
+
+  // ---- scales, fragment read offsets ---------------------------------------------------------------
+  float c_prefix = p.scale_log2;
+  float v_out = 1.0f;
+  {
+    // read through the constant address space: a wavefront-uniform load from there is a scalar load, which the
+    // vector memory counter (the direct loads in flight) does not see
+    typedef const __attribute__((address_space(4))) float *cfloat_ptr;
+    const float ksc = p.k_scale ? ((cfloat_ptr)(uintptr_t)p.k_scale)[kvh] : 1.0f;
+    const float vsc = p.v_scale ? ((cfloat_ptr)(uintptr_t)p.v_scale)[kvh] : 1.0f;
+    c_prefix *= ksc;
+    v_out = vsc;
+  }
+  int koff[4], voff[4];
+  {
+    const int fk = swz_k(ln);  // keys ln and 32 + ln share the swizzle
+#pragma unroll
+    for (int u = 0; u < 4; ++u) koff[u] = ln * kRowBytes + (((2 * u + lh) ^ fk) * 16);
+    // transposing read: the 16 lanes of a group address eight keys x two 8-byte halves of one 16-byte piece; lane i
+    // of the group then holds column i of those eight keys
+    const int grp = lane >> 4, a = lane & 15, j = a >> 1;
+    const int keyl = 8 * (j >> 2) + 4 * (grp >> 1) + (j & 3);
+    const int fv = swz_v(keyl);  // the same for the key groups 16, 32, 48 rows on
+#pragma unroll
+    for (int db = 0; db < 4; ++db) voff[db] = keyl * kRowBytes + (((2 * db + (grp & 1)) ^ fv) * 16) + 8 * (a & 1);
+  }
+  RowState<1> st;
+  st.row_tok[0] = row_tok;
+  st.row_bstart[0] = (row_tok / p.L) * p.L;
+  st.m_run[0] = -INFINITY;
+  st.l_run[0] = 0.f;
+  st.base[0] = 0.f;
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) st.o[db][0][j] = 0.f;
+
+  // ---- the pipeline -------------------------------------------------------------------------------
+  const bool active = r0 + rb * 32 < p.R;
+  for (int step = 0; step < n_steps; ++step) {
+    // own loads of this step have landed (the steps issued after it may still be in flight) ...
+    wait_later<IPW, NST - 2>(min(n_steps - 1, step + NST - 2) - step);
+    __builtin_amdgcn_s_barrier();  // ... and so have everyone else's; the slots read in the previous step are free
+    if (step + NST - 1 < n_steps) issue(step + NST - 1);
+    if (step == 0) {
+      // The Q fragments have landed (they were requested before any K/V): multiply by the prefix score scale (log2
+      // units, k_scale folded in), round to bf16 again and put them back, each key slice of the row block a share
+      // of the eight fragments; one more barrier makes them visible to the others.
+#pragma unroll
+      for (int i = 0; i < 8 / KSL; ++i) {
+        uint8_t *at = lds + rb * 8192 + (ks * (8 / KSL) + i) * 1024 + lane * 16;
+        u32x4 v = *(const u32x4 *)at;
+        if (row >= p.R) v = u32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const uint32_t word = v[w];
+          const uint32_t wl = word << 16, wh = word & 0xffff0000u;
+          v[w] = pack_bf16(__builtin_bit_cast(float, wl) * c_prefix, __builtin_bit_cast(float, wh) * c_prefix);
+        }
+        *(u32x4 *)at = v;
+      }
+      __syncthreads();
+    }
+    if (!active) continue;
+    const uint8_t *kt = lds + S::kRingOff + (step % NST) * kStepBytes + ks * kTileBytes;
+    const uint8_t *qfrag = lds + rb * 8192 + lane * 16;
+    if (step < n_pre_steps) {
+      const int first = k_begin + (step * KSL + ks) * kTileN;
+      if (first + kTileN <= k_end)
+        stream_tile<MASK_NONE>(kt, qfrag, st, koff, voff, lh, 0, 0);
+      else if (first < k_end)
+        stream_tile<MASK_TAIL>(kt, qfrag, st, koff, voff, lh, first, k_end);
+    } else {
+      const int first = tk0 + ((step - n_pre_steps) * KSL + ks) * kTileN;
+      if (first <= t_hi) stream_tile<MASK_BRANCH>(kt, qfrag, st, koff, voff, lh, first, 0);
+    }
+  }
+  wait_vmcnt<0>();  // no direct load may still be on its way to LDS when the workgroup gives its LDS back
+
+  // ---- fold the key slices of a row block through LDS, every wavefront a share of the columns ----------------
+  // All 8/NRB slices of a row block leave (O, m, l) per lane in LDS, layout [wavefront][value 0..65][lane];
+  // wavefront `slice` of the row block then combines accumulator registers slice*kPer .. +kPer of all slices and
+  // writes those columns of the partial.  Register i = 16*db + j of a lane is head-dim column
+  // 32*db + 8*(j/4) + 4*lh + j%4 of its row.
+  constexpr int kSlices = kWaves / NRB, kPer = 64 / kSlices;
+  const size_t slot = (size_t)b * p.s_max + c;
+  const size_t out_row = slot * p.n_rows + (size_t)row_tok * p.Hq + kvh * p.G + (row % p.G);
+  float *po = p.part_o + out_row * kD;
+  if constexpr (kSlices == 1) {  // one slice: the registers are the partial
+    const float l_tot = xhalf_sum(st.l_run[0]);
+    if (row < p.R) {
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 v = {st.o[db][0][4 * q] * v_out, st.o[db][0][4 * q + 1] * v_out,
+                           st.o[db][0][4 * q + 2] * v_out, st.o[db][0][4 * q + 3] * v_out};
+          *(f32x4 *)(po + 32 * db + 8 * q + 4 * lh) = v;
+        }
+      if (lh == 0) {
+        const f32x2 ml = {st.m_run[0], l_tot};
+        *(f32x2 *)(p.part_ml + out_row * 2) = ml;
+      }
+    }
+  } else {
+    __builtin_amdgcn_s_barrier();  // every wavefront is done with the ring
+    float *fold = (float *)lds;
+    {
+      float *dst = fold + (size_t)wave * 66 * 64 + lane;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) dst[(db * 16 + j) * 64] = st.o[db][0][j];
+      dst[64 * 64] = st.m_run[0];
+      dst[65 * 64] = st.l_run[0];
+    }
+    __syncthreads();
+    const int slice = ks;
+    float w[kSlices], m_all = -INFINITY, l_all = 0.f;
+#pragma unroll
+    for (int s = 0; s < kSlices; ++s) {
+      w[s] = fold[(size_t)(s * NRB + rb) * 66 * 64 + 64 * 64 + lane];
+      m_all = fmaxf(m_all, w[s]);
+    }
+    const float m_use = (m_all == -INFINITY) ? 0.f : m_all;
+#pragma unroll
+    for (int s = 0; s < kSlices; ++s) {
+      w[s] = __builtin_amdgcn_exp2f(w[s] - m_use);  // 0 for a slice that saw no key
+      l_all = __builtin_fmaf(w[s], fold[(size_t)(s * NRB + rb) * 66 * 64 + 65 * 64 + lane], l_all);
+    }
+    float acc[kPer];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int s = 0; s < kSlices; ++s) {
+      const float *src = fold + ((size_t)(s * NRB + rb) * 66 + slice * kPer) * 64 + lane;
+#pragma unroll
+      for (int i = 0; i < kPer; ++i) acc[i] = __builtin_fmaf(w[s], src[i * 64], acc[i]);
+    }
+    const float l_tot = xhalf_sum(l_all);
+    if (row < p.R) {
+#pragma unroll
+      for (int i = 0; i < kPer; i += 4) {
+        const int reg = slice * kPer + i;  // (wavefront-uniform)
+        const f32x4 v = {acc[i] * v_out, acc[i + 1] * v_out, acc[i + 2] * v_out, acc[i + 3] * v_out};
+        *(f32x4 *)(po + 32 * (reg >> 4) + 8 * ((reg & 15) >> 2) + 4 * lh) = v;
+      }
+      if (slice == 0 && lh == 0) {
+        const f32x2 ml = {m_all, l_tot};
+        *(f32x2 *)(p.part_ml + out_row * 2) = ml;
+      }
+    }
+  }
+}
+
+template <int NRB>
+hipError_t launch_stream_variant(const AttnParams &p, hipStream_t stream) {
+  using S = StreamShape<NRB>;
+  const int grid = p.Hkv * p.n_row_tiles * p.total_units;
+  auto kern = attn_stream_kernel<NRB>;
+  const int blk_entries =
+      p.block_tables ? (attn_max_chunk_tokens(p.chunk_len, p.last_short) >> p.block_shift) + 2 : 0;
+  if (blk_entries > kMaxBlkLds) return hipErrorInvalidValue;
+  const int lds_bytes = S::kBlkOff + blk_entries * 4 > S::kFoldBytes ? S::kBlkOff + blk_entries * 4 : S::kFoldBytes;
+  static std::once_flag once;
+  static hipError_t configured = hipSuccess;
+  std::call_once(once, [&] {
+    configured = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::kLdsMax);
+  });
+  if (configured != hipSuccess) return configured;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * kWaves), lds_bytes, stream, p);
+  return hipGetLastError();
+}
+
+// row blocks per workgroup of the shapes
+constexpr int kStreamNrb[] = {2, 4, 8};
+constexpr int kNumStreamShapes = 3;
+
+}  // namespace
+
+int attn_stream_num_shapes() { return kNumStreamShapes; }
+int attn_stream_tile_m(int shape) { return 32 * kStreamNrb[shape]; }
+int attn_stream_step_keys(int shape) { return kTileN * kWaves / kStreamNrb[shape]; }
+int attn_stream_max_chunk_blocks() { return kMaxBlkLds; }
+
+hipError_t launch_attn_stream(const AttnParams &p, int shape, hipStream_t stream) {
+  ProfileScope scope(SLOT_ATTN_MFMA, stream);
+  switch (shape) {
+    case 0: return launch_stream_variant<2>(p, stream);
+    case 1: return launch_stream_variant<4>(p, stream);
+    case 2: return launch_stream_variant<8>(p, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace la

@@ -2,6 +2,7 @@
 // pure bf16 MFMA loop and on a pure streaming read, so that a roofline fraction can be quoted against the
 // achievable rate next to the published peak.
 #include "la_internal.hpp"
+#include "la_verify_bench.h"
 
 namespace la {
 namespace {

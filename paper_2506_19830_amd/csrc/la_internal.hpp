@@ -42,16 +42,49 @@ struct AttnParams {
   int R;            // gamma*L*G
   int n_rows;       // gamma*L*Hq
   int n_row_tiles;  // ceil(R / tile_m)
-  int chunk_len;    // prefix tokens per chunk, multiple of 64
+  int chunk_len;    // nominal prefix tokens per chunk, multiple of 64 (see attn_chunk_range)
+  int last_short;   // tiles of other work the last chunk is counted as carrying
   int s_max;        // partial slots per request = max_b n_chunks(b)
   int total_units;  // sum_b n_chunks(b)
   int out_f32;      // output dtype: 1 = fp32, 0 = bf16
   float scale_log2; // softmax_scale * log2(e)
+  // With few requests what a workgroup needs to find its chunk travels in the kernel arguments, prepared by the host
+  // from its copy of the prefix lengths, so that no kernel start waits on a dependent load of prefix_lens or on
+  // integer divisions: n_inline = B if B <= kMaxInlineLens, else 0.
+  int n_inline;
+  struct Req {
+    int P;          // prefix length
+    int n;          // chunks
+    int q, r;       // (tiles + last_short) = q*n + r
+    uint32_t inv;   // floor(2^32 / n) + 1: floor(x / n) == (x * inv) >> 32 for x < 2^32 / n
+  } req[8];
 };
+constexpr int kMaxInlineLens = 8;
 
 __host__ __device__ inline int attn_num_chunks(int prefix_len, int chunk_len) {
   int n = (prefix_len + chunk_len - 1) / chunk_len;
   return n < 1 ? 1 : n;
+}
+
+// Token range [*k_begin, *k_end) of chunk c of a prefix of P tokens.  chunk_len only fixes the number of chunks
+// n = attn_num_chunks(P, chunk_len); the T = ceil(P/64) key tiles are then dealt out evenly (sizes differ by at most
+// one tile), with the last chunk, whose workgroup also reduces the branch-private keys, counted as carrying
+// `last_short` tiles of other work.  A chunk may come out empty (k_begin == k_end) when n is close to T.
+__host__ __device__ inline void attn_chunk_range(int P, int chunk_len, int last_short, int c, int *k_begin,
+                                                 int *k_end) {
+  const long long n = attn_num_chunks(P, chunk_len);
+  const long long T = ((long long)P + 63) / 64;
+  const long long Tv = T + last_short;
+  long long t0 = c * Tv / n, t1 = (c + 1) * Tv / n;
+  if (t0 > T) t0 = T;
+  if (t1 > T || c == n - 1) t1 = T;
+  const long long e = t1 * 64 < P ? t1 * 64 : P;
+  *k_begin = (int)(t0 * 64);
+  *k_end = (int)e;
+}
+// upper bound of a chunk's length in tokens under attn_chunk_range
+__host__ __device__ inline int attn_max_chunk_tokens(int chunk_len, int last_short) {
+  return chunk_len + 64 * (last_short + 2);
 }
 
 enum KernelSlot {
@@ -75,6 +108,12 @@ int attn_mfma_tile_m(int shape);   // rows per workgroup of a shape
 int attn_mfma_wgs_per_cu(int shape);  // workgroups of a shape that fit on one CU (LDS)
 int attn_mfma_max_chunk_blocks();  // a chunk may span at most this many cache blocks
 hipError_t launch_attn_mfma(const AttnParams &p, int shape, bool kv_fp8, bool br_fp8, hipStream_t stream);
+// The streaming shapes (few rows per KV head; fp8 cache and fp8 branch K/V, flat calls): row blocks x key slices.
+int attn_stream_num_shapes();
+int attn_stream_tile_m(int shape);
+int attn_stream_step_keys(int shape);  // keys a workgroup advances per pipeline step
+int attn_stream_max_chunk_blocks();
+hipError_t launch_attn_stream(const AttnParams &p, int shape, hipStream_t stream);
 hipError_t launch_attn_merge(const AttnParams &p, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnParams &p, hipStream_t stream);
 
@@ -135,16 +174,21 @@ struct CommitParams {
 hipError_t launch_kv_commit(const CommitParams &p, int src_bytes, bool quantise, hipStream_t stream);
 
 // ----------------------------------------------------------------------------
-// Optional per-kernel event timing (see la_profile_* in the public header).
+// Optional per-kernel event timing.  The two hooks are defined only in the benchmark build of the library
+// (bench_aids.hip, see la_verify_bench.h); in the product library they are absent, the references below resolve
+// to null and a launch does nothing beside launching.
 // ----------------------------------------------------------------------------
-void profile_before(int slot, hipStream_t stream);
-void profile_after(int slot, hipStream_t stream);
+__attribute__((weak)) void *profile_before(int slot, hipStream_t stream);            // start event, or null
+__attribute__((weak)) void profile_after(int slot, hipStream_t stream, void *start);
 
 struct ProfileScope {
   int slot;
   hipStream_t stream;
-  ProfileScope(int s, hipStream_t st) : slot(s), stream(st) { profile_before(slot, stream); }
-  ~ProfileScope() { profile_after(slot, stream); }
+  void *start;
+  ProfileScope(int s, hipStream_t st) : slot(s), stream(st), start(profile_before ? profile_before(s, st) : nullptr) {}
+  ~ProfileScope() {
+    if (start && profile_after) profile_after(slot, stream, start);
+  }
 };
 
 }  // namespace la

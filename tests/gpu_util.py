@@ -24,8 +24,12 @@ def upload_attention(case: W.AttnCase, inp: dict) -> dict:
     return dev
 
 
+# kernel shape every descriptor built here asks for (0: the library chooses); tests that walk the shapes patch it
+KERNEL_SHAPE = 0
+
+
 def attn_desc(case: W.AttnCase, kv_split_tokens: int = 0, scale=None):
-    return B.make_attn_desc(num_requests=case.B, num_q_heads=case.Hq, num_kv_heads=case.Hkv, head_dim=case.D,
+    return B.make_attn_desc(kernel_shape=KERNEL_SHAPE, num_requests=case.B, num_q_heads=case.Hq, num_kv_heads=case.Hkv, head_dim=case.D,
                             gamma=case.gamma, branch_len=case.L, block_size=case.block_size,
                             max_blocks_per_request=case.max_blocks, q_dtype=case.q_dtype, kv_dtype=case.kv_dtype,
                             branch_kv_dtype=case.branch_kv_dtype, out_dtype=case.out_dtype,

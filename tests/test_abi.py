@@ -19,17 +19,35 @@ def good_desc(**kw):
     return B.make_attn_desc(**d)
 
 
+def _declared(header_name):
+    header = (ROOT / "include" / header_name).read_text()
+    return set(re.findall(r"LA_API[^;(]*?\b(la_\w+)\s*\(", header))
+
+
+def _exported(path):
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", str(path)], capture_output=True, text=True, check=True).stdout
+    return {line.split()[-1] for line in out.splitlines() if " T " in line}
+
+
 def test_library_exports_every_declared_symbol():
-    header = (ROOT / "include" / "la_verify.h").read_text()
-    declared = set(re.findall(r"LA_API[^;(]*?\b(la_\w+)\s*\(", header))
-    assert declared == set(B.EXPORTED_SYMBOLS)
-    lib = B.load()
+    """The product library exports exactly what la_verify.h declares; the benchmark library that and the aids of
+    la_verify_bench.h; neither exports anything else."""
+    declared = _declared("la_verify.h")
+    aids = _declared("la_verify_bench.h")
+    assert declared == set(B.EXPORTED_SYMBOLS) and aids == set(B.BENCH_SYMBOLS)
+    lib, bench = B.load("product"), B.load("bench")
     for name in declared:
-        assert hasattr(lib, name), name
+        assert hasattr(lib, name) and hasattr(bench, name), name
+    for name in aids:
+        assert hasattr(bench, name) and not hasattr(lib, name), name
+    assert _exported(B.LIB_PATH) == declared
+    assert _exported(B.BENCH_LIB_PATH) == declared | aids
 
 
 def test_struct_layouts_match_the_header():
-    assert ctypes.sizeof(B.la_attn_desc) == 14 * 4
+    assert ctypes.sizeof(B.la_attn_desc) == 15 * 4
+    assert ctypes.sizeof(B.la_attn_plan) == 7 * 4
     assert ctypes.sizeof(B.la_accept_desc) == 7 * 4
     assert ctypes.sizeof(B.la_layer_strides) == 8 + 4 * 8        # int32 padded to the int64 that follows
 

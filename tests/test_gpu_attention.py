@@ -84,11 +84,46 @@ def test_mfma_small_cases(oracle, case, split):
 @pytest.mark.parametrize("case", [MFMA_CASES[0], MFMA_CASES[2], MFMA_CASES[3], MFMA_CASES[5]], ids=lambda c: c.name)
 def test_every_kernel_shape(oracle, case, shape, monkeypatch):
     """The planner picks one of the kernel's (wavefronts, row blocks, LDS stages) shapes by a cost model; here
-    each is forced in turn (the library reads LA_ATTN_SHAPE when it plans a call), with long and short chunks
+    each is forced in turn (the descriptor's kernel_shape field), with long and short chunks
     (odd and even tile counts per chunk, chunks shorter than the prefetch distance)."""
-    monkeypatch.setenv("LA_ATTN_SHAPE", str(shape))
+    monkeypatch.setattr("gpu_util.KERNEL_SHAPE", shape + 1)
     for split in (0, 64, 192, 320):
         check_full(oracle, case, TOL_LOWP, kv_split_tokens=split)
+
+
+STREAM_CASES = [
+    # few rows per KV head (the regime the streaming shapes are for): R = 8*1*5 = 40, 6*9*5 = 270, ragged prefixes
+    W.AttnCase("fp8_stream_l1", (1000,), 8, 1, 40, 8, 128, "bf16", "fp8_e4m3", "fp8_e4m3", "bf16", seed=71),
+    W.AttnCase("fp8_stream_paper_step", (2077,), 6, 9, 40, 8, 128, "bf16", "fp8_e4m3", "fp8_e4m3", "bf16", seed=72),
+    # paged, several requests with empty / tiny / ragged prefixes, fp32 out, branches longer than a key tile
+    W.AttnCase("fp8_stream_paged_multi", (777, 0, 5, 2049), 2, 17, 8, 2, 128, "bf16", "fp8_e4m3", "fp8_e4m3", "f32",
+               paged=True, seed=73),
+    W.AttnCase("fp8_stream_long_branch", (130,), 2, 150, 4, 2, 128, "bf16", "fp8_e4m3", "fp8_e4m3", "bf16", seed=74),
+    W.AttnCase("fp8_stream_block64", (700,), 2, 8, 4, 4, 128, "bf16", "fp8_e4m3", "fp8_e4m3", "bf16", block_size=64,
+               paged=True, seed=75),
+    W.AttnCase("fp8_stream_no_prefix", (0,), 3, 70, 2, 2, 128, "bf16", "fp8_e4m3", "fp8_e4m3", "bf16", seed=76),
+]
+
+
+@pytest.mark.parametrize("shape", [2, 3, 4])
+@pytest.mark.parametrize("case", STREAM_CASES, ids=lambda c: c.name)
+def test_every_streaming_shape(oracle, case, shape, monkeypatch):
+    """The streaming shapes (direct global -> LDS loads, transposing LDS reads, row blocks x key slices) forced in
+    turn: automatic chunking, one tile per chunk, chunks whose tile count is odd / not a multiple of the key
+    slices / shorter than the prefetch depth."""
+    monkeypatch.setattr("gpu_util.KERNEL_SHAPE", shape + 1)
+    for split in (0, 64, 192, 320, 1024):
+        check_full(oracle, case, TOL_LOWP, kv_split_tokens=split)
+
+
+def test_streaming_shape_is_refused_where_it_cannot_run(monkeypatch):
+    from gpu_util import run_attention
+    from paper_2506_19830_amd import binding as B
+    monkeypatch.setattr("gpu_util.KERNEL_SHAPE", 3)
+    case = MFMA_CASES[0]                                    # bf16 cache: no streaming shape
+    with pytest.raises(B.LaError) as e:
+        run_attention(case, W.make_attention_inputs(case))
+    assert e.value.status == 2
 
 
 # ----------------------------------------------------------------------------------------- nested branches
@@ -140,7 +175,7 @@ def test_nested_small_cases(oracle, case, chain_len, vis):
 
 @pytest.mark.parametrize("shape", [0, 1])
 def test_nested_every_kernel_shape(oracle, shape, monkeypatch):
-    monkeypatch.setenv("LA_ATTN_SHAPE", str(shape))
+    monkeypatch.setattr("gpu_util.KERNEL_SHAPE", shape + 1)
     for case, chain_len, vis in (NESTED_CASES[2], NESTED_CASES[3], NESTED_CASES[4]):
         for split in (0, 192):
             check_nested(oracle, case, chain_len, TOL_LOWP, None if vis is None else np.array(vis), split)
@@ -231,7 +266,7 @@ def test_tree_small_cases(oracle, case, width, depth, step_len, edit):
 
 @pytest.mark.parametrize("shape", [0, 1])
 def test_tree_every_kernel_shape(oracle, shape, monkeypatch):
-    monkeypatch.setenv("LA_ATTN_SHAPE", str(shape))
+    monkeypatch.setattr("gpu_util.KERNEL_SHAPE", shape + 1)
     for case, width, depth, step_len, edit in (TREE_CASES[2], TREE_CASES[3], TREE_CASES[4]):
         for split in (0, 192):
             check_tree(oracle, case, width, depth, step_len, TOL_LOWP, split, edit)
@@ -392,9 +427,9 @@ def test_full_size_configs_on_sampled_rows(oracle, n):
 
 
 def test_very_long_ragged_paged_prefix_on_sampled_rows(oracle, monkeypatch):
-    """A 300001-token paged fp8 prefix next to a short one, through both kernel shapes: automatic splits, a chunk at
-    the limit of block ids a workgroup keeps in LDS (4092 of 4096), many short chunks (74 per request: the general
-    merge form)."""
+    """A 300001-token paged fp8 prefix next to a short one, through both row-tile kernel shapes: automatic splits, the
+    longest chunk the block ids a workgroup keeps in LDS allow (4072 blocks nominal, a few more once the tiles are
+    dealt out evenly; 4096 slots), many short chunks (74 per request: the general merge form)."""
     from gpu_util import row_errors, run_attention
     case = W.AttnCase("long_prefix", (300001, 777), 2, 5, 8, 2, 128, "bf16", "fp8_e4m3", "fp8_e4m3", "bf16",
                       paged=True, seed=61)
@@ -403,8 +438,8 @@ def test_very_long_ragged_paged_prefix_on_sampled_rows(oracle, monkeypatch):
     inp = W.device_inputs_to_numpy(case, dev)
     ids = sampled_rows(case, 100)
     ref, ref_lse = oracle_attention(oracle, case, inp, row_ids=ids)
-    for shape, split in ((0, 0), (1, 0), (0, 65472), (1, 4096)):
-        monkeypatch.setenv("LA_ATTN_SHAPE", str(shape))
+    for shape, split in ((0, 0), (1, 0), (0, 65152), (1, 4096)):
+        monkeypatch.setattr("gpu_util.KERNEL_SHAPE", shape + 1)
         print(f"long prefix: shape {shape} split {split}", flush=True)
         got, lse = run_attention(case, inp, split, dev=dev)
         err = row_errors(got.reshape(-1, case.D)[ids], ref)
