@@ -591,7 +591,6 @@ int lao_spec_accept(int NB, int K, int V, int logits_dtype, double temperature, 
                                 u_accept, u_sample, accepted_len, next_token, ratio, margin, cdf_lo, cdf_hi, NULL);
 }
 
-/* Number of OpenMP threads a parallel region will use (for reporting). */
 /* ---- KV commit ------------------------------------------------------------------ */
 
 /* Nearest e4m3fn code of y (finite): candidates are the 127 non-negative finite values, the nearest wins, a tie goes

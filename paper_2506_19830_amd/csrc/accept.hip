@@ -142,8 +142,11 @@ __global__ __launch_bounds__(kThreads, 6) void accept_stats_kernel(const AcceptP
   m = wave_max(m);
   if ((tid & 63) == 0) red[0][tid >> 6] = m;
   __syncthreads();
-  m = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));  // slice maximum (finite: slice not empty)
-  const float cm = -m * p.inv_temp_log2;
+  m = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));  // slice maximum
+  // a slice whose logits are all -inf (a masked part of the vocabulary) has mass 0: the exponent offset is taken
+  // from 0 instead of from -inf, which would turn -inf - (-inf) into a NaN; the slice is recorded as (-inf, 0) and
+  // drops out of every fold (weight 2^(-inf - row maximum) = 0)
+  const float cm = -((m == -INFINITY) ? 0.f : m) * p.inv_temp_log2;
   float s = 0.f;
 #pragma unroll
   for (int e = 0; e < Sh::kPer; ++e) s += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], p.inv_temp_log2, cm));
@@ -310,11 +313,17 @@ __device__ __forceinline__ void row_foreach(const void *row, int V, F &&f) {
 // stays below target, floor_key.  BF16 values have 16 significant key bits: two rounds instead of four.
 // `each(f)` calls f(x) for every value of the set, the workgroup's lanes sharing the work; values with a key below
 // floor_key take no part (the caller guarantees that the answer lies at or above it).
+// The mass histogram is accumulated in 64-bit fixed point (masses are at most 1, at most 2^21 of them; 40 fraction
+// bits, each mass rounded to nearest): integer atomics add in any order to the same bits, so the selection is the
+// same in every run, which floating-point atomics would not give.  The 2^-41 rounding per term moves a bucket's
+// mass by a few 1e-10 of the row's mass at most, inside the margin within which a top-p decision counts as open.
 template <bool BF16, bool BY_MASS, typename Each>
 __device__ __forceinline__ uint32_t radix_select(Each &&each, double mx_over_t, double inv_temp, uint32_t floor_key,
                                                  int k, double target, uint32_t *cnt, double *mass,
                                                  uint32_t *s_pick, double *s_above) {
   constexpr int kRounds = BF16 ? 2 : 4;
+  constexpr double kFix = 1099511627776.0;   // 2^40
+  unsigned long long *imass = (unsigned long long *)mass;
   const int tid = threadIdx.x;
   uint32_t prefix = 0;          // the bits chosen so far (high bits of the key)
   double above = 0.0;           // BY_MASS: mass of the keys above the chosen prefix range
@@ -326,7 +335,7 @@ __device__ __forceinline__ uint32_t radix_select(Each &&each, double mx_over_t, 
     // leading byte, and LDS serialises atomics of one instruction that hit the same address
     for (int i = tid; i < kHist * kRep; i += kWarpThreads) {
       if constexpr (BY_MASS)
-        mass[i] = 0.0;
+        imass[i] = 0;
       else
         cnt[i] = 0;
     }
@@ -337,16 +346,17 @@ __device__ __forceinline__ uint32_t radix_select(Each &&each, double mx_over_t, 
       const bool in_range = round == 0 || (key >> (shift + 8)) == (prefix >> (shift + 8));
       if (!in_range || key < floor_key) return;
       if constexpr (BY_MASS)
-        atomicAdd(&mass[rep + ((key >> shift) & 255)], mass64(x, mx_over_t, inv_temp));
+        atomicAdd(&imass[rep + ((key >> shift) & 255)],
+                  (unsigned long long)__builtin_llrint(mass64(x, mx_over_t, inv_temp) * kFix));
       else
         atomicAdd(&cnt[rep + ((key >> shift) & 255)], 1u);
     });
     __syncthreads();
     if (tid < 256) {   // fold the copies, in order
       if constexpr (BY_MASS) {
-        double t = 0.0;
-        for (int r = 0; r < kRep; ++r) t += mass[r * kHist + tid];
-        mass[tid] = t;
+        unsigned long long t = 0;
+        for (int r = 0; r < kRep; ++r) t += imass[r * kHist + tid];
+        imass[tid] = t;
       } else {
         uint32_t t = 0;
         for (int r = 0; r < kRep; ++r) t += cnt[r * kHist + tid];
@@ -359,18 +369,20 @@ __device__ __forceinline__ uint32_t radix_select(Each &&each, double mx_over_t, 
       if constexpr (BY_MASS) {
         double m = above;
         int lowest = -1;
+        double low_mass = 0.0;
         for (int b = 255; b >= 0; --b) {
-          if (!(mass[b] > 0.0)) continue;
-          if (m + mass[b] >= target) {
+          if (imass[b] == 0) continue;
+          const double mb = (double)imass[b] * (1.0 / kFix);
+          if (m + mb >= target) {
             pick = b;
             break;
           }
-          lowest = b;
-          m += mass[b];
+          lowest = b, low_mass = mb;
+          m += mb;
         }
-        // below the first round the parent bucket did cross; if the regrouped sums miss that by a rounding, the
-        // crossing is in the lowest bucket with mass
-        if (pick < 0 && round > 0) pick = lowest, m -= mass[lowest];
+        // below the first round the parent bucket did cross; if the running sum misses that by a rounding of its
+        // additions, the crossing is in the lowest bucket with mass
+        if (pick < 0 && round > 0) pick = lowest, m -= low_mass;
         *s_above = m;
       } else {
         int c = 0;
@@ -927,6 +939,7 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(const AcceptPar
   if (tid == 0) s_first = p.K, s_have_bonus = 0;
   __syncthreads();
   int i0 = 0;
+  bool have_top = false;
   for (; i0 < p.K; i0 += kPass) {   // a later pass cannot lower the first rejection found in an earlier one
     const int cnt = min(kPass, p.K - i0);
     // what a position's test needs from global memory besides the row statistics; issued first so that the two
@@ -994,13 +1007,20 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(const AcceptPar
       if (c == 0 && p.ratio) p.ratio[(size_t)nb * p.K + i] = px / qx;
     }
     __syncthreads();
-    if (s_first < p.K) break;  // uniform: the first rejection lies in this pass
+    if (s_first < p.K) {  // uniform: the first rejection lies in this pass
+      // exact maxima of the resampling rows: target row n and draft row n, both folded in this pass
+      if (!have_top && tid == 0) s_top[0] = sm[0][s_first - i0], s_top[1] = p.draft ? sm[1][s_first - i0] : 0.f;
+      have_top = true;
+      // the workgroup that reports the ratios goes on through the remaining passes (every position gets its ratio,
+      // also those behind the rejection); s_first cannot change any more, atomicMin only lowers it to values < i
+      if (!(c == 0 && p.ratio)) break;
+    }
+    __syncthreads();  // sm / sz free for the next pass
   }
   const int n = s_first;
-  // exact maxima of the resampling rows: target row n and draft row n (both folded in the pass that found n), or
-  // target row K alone when everything was accepted
+  // everything accepted: the maximum of target row K alone
   if (n < p.K) {
-    if (tid == 0) s_top[0] = sm[0][n - i0], s_top[1] = p.draft ? sm[1][n - i0] : 0.f;
+    // s_top was set in the pass that found n
   } else if (s_have_bonus) {
     if (tid == 0) s_top[0] = s_bonus, s_top[1] = 0.f;
   } else if (wave == 0) {

@@ -101,6 +101,25 @@ def row_errors(got: np.ndarray, ref: np.ndarray):
     return np.abs(g - r).max(axis=1) / np.abs(r).max(axis=1)
 
 
+def elem_errors(got: np.ndarray, ref: np.ndarray, floor: float = 1e-3):
+    """Element-wise relative error |got-ref| / max(|ref|, floor * max|ref| over the row), the companion figure of
+    the row error: reported, not bounded (an element a thousand times smaller than its row's largest is compared
+    against that floor).  Returns the array of element errors."""
+    D = ref.shape[-1]
+    g, r = got.reshape(-1, D), ref.reshape(-1, D)
+    den = np.maximum(np.abs(r), floor * np.abs(r).max(axis=1, keepdims=True))
+    return np.abs(g - r) / den
+
+
+def error_report(got: np.ndarray, ref: np.ndarray) -> dict:
+    """Both error figures of one comparison, for logs and the benchmark's JSON."""
+    row = row_errors(got, ref)
+    el = elem_errors(got, ref)
+    return {"rows": int(row.size), "max_row_err": float(row.max()), "mean_row_err": float(row.mean()),
+            "max_elem_rel_err_floor_1e-3": float(el.max()), "p999_elem_rel_err": float(np.quantile(el, 0.999)),
+            "median_elem_rel_err": float(np.median(el))}
+
+
 def upload_accept(case: W.AcceptCase, inp: dict) -> dict:
     return {
         "target_logits": B.to_device(inp["target_logits"], case.logits_dtype),

@@ -77,6 +77,124 @@ def test_identical_models_accept_everything():
     np.testing.assert_allclose(got["ratio"], 1.0, rtol=1e-6)
 
 
+def test_ratio_is_reported_at_every_position_also_behind_the_rejection(oracle):
+    """accept_ratio holds p_i(x_i)/q_i(x_i) for every drafted position, not only the examined ones, also when the
+    positions take several 64-position passes and the rejection lies in the first.  The oracle only evaluates what it
+    examines, so its ratios come from a second run in which every draw accepts (u = 0); the ratio does not depend
+    on the draw."""
+    from gpu_util import run_accept
+    for case in (W.AcceptCase("ratio_k70", 6, 70, 700, "f32", target_std=1.0, draft_noise_std=0.3, seed=41),
+                 W.AcceptCase("ratio_k150", 4, 150, 3000, "bf16", target_std=2.0, draft_noise_std=0.5, seed=42),
+                 W.AcceptCase("ratio_k9", 16, 9, 20000, "bf16", seed=43)):
+        inp = W.make_accept_inputs(case)
+        got = run_accept(case, inp)
+        ref = oracle.spec_accept(**inp, logits_dtype=case.logits_dtype)
+        every = dict(inp, u_accept=np.zeros_like(inp["u_accept"]))
+        ref_all = oracle.spec_accept(**every, logits_dtype=case.logits_dtype)
+        assert (ref_all["accepted_len"] == case.K).all()              # every position examined
+        assert (ref["accepted_len"] < min(case.K, 64)).any()          # the real draws stop early somewhere
+        np.testing.assert_array_equal(got["accepted_len"], ref["accepted_len"])
+        np.testing.assert_array_equal(got["next_token"], ref["next_token"])
+        assert np.isfinite(got["ratio"]).all()
+        np.testing.assert_allclose(got["ratio"], ref_all["ratio"], rtol=2e-4)
+
+
+def _mask_logits(case, inp, rng, frac, span, target_only_frac):
+    """-inf logits: a constrained vocabulary (the same positions in the target and the draft rows: a random
+    fraction plus one whole span), and some more positions in the target rows alone."""
+    neg = {"f32": np.float32(-np.inf), "bf16": np.uint16(0xFF80)}[case.logits_dtype]
+    both = rng.random(case.V) < frac
+    both[span[0]:span[1]] = True
+    both[rng.integers(0, case.V)] = False                        # never everything
+    t, d = inp["target_logits"].copy(), None if inp["draft_logits"] is None else inp["draft_logits"].copy()
+    t[:, :, both] = neg
+    if d is not None:
+        d[:, :, both] = neg
+    only_t = (rng.random(t.shape) < target_only_frac) & ~both[None, None, :]
+    t[only_t] = neg
+    # every fourth branch: the target masks the first drafted token itself (p = 0 at a token the draft proposed)
+    for nb in range(1, case.NB, 4):
+        t[nb, 0, inp["draft_tokens"][nb, 0]] = neg
+    return dict(inp, target_logits=t, draft_logits=d)
+
+
+@pytest.mark.parametrize("case,span", [
+    # a whole 16384-logit statistics slice of bf16 rows (and whole 2048-token slices of the fp64 path) masked
+    (W.AcceptCase("masked_bf16", 24, 4, 40000, "bf16", seed=44), (16384, 32768)),
+    # fp32: statistics slices hold 8192 logits
+    (W.AcceptCase("masked_f32", 24, 3, 20000, "f32", seed=45), (8192, 16384)),
+    (W.AcceptCase("masked_small", 64, 4, 700, "f32", target_std=1.5, seed=46), (100, 300)),
+    (W.AcceptCase("masked_lookup_warped", 24, 4, 40000, "bf16", temperature=0.6, top_k=20, top_p=0.95,
+                  point_mass=True, peak=9.0, seed=47), (16384, 32768)),
+    (W.AcceptCase("masked_top_p", 12, 3, 40000, "bf16", temperature=0.8, top_p=0.9, seed=48), (16384, 32768)),
+], ids=lambda x: getattr(x, "name", None))
+def test_minus_infinity_logits(oracle, case, span):
+    """Masked vocabulary entries (logit -inf) have probability exactly zero on both sides: they are never drawn, a
+    drafted token the target masks is rejected (p = 0), one that both mask is rejected too (p = q = 0), whole
+    statistics slices of -inf drop out of the row sums without a NaN."""
+    from gpu_util import compare_accept, run_accept
+    rng = np.random.default_rng(case.seed)
+    inp = _mask_logits(case, W.make_accept_inputs(case), rng, 0.05, span, 0.02)
+    got = run_accept(case, inp)
+    ref = oracle.spec_accept(**inp, logits_dtype=case.logits_dtype, temperature=case.temperature, top_k=case.top_k,
+                             top_p=float(np.float32(case.top_p)))
+    bad_n, bad_tok, near = compare_accept(got, ref)
+    assert bad_n == 0 and bad_tok == 0, f"{bad_n} lengths, {bad_tok} tokens differ ({near} set aside)"
+    assert near <= 2
+    examined = np.isfinite(ref["ratio"])
+    np.testing.assert_allclose(got["ratio"][examined], ref["ratio"][examined], rtol=2e-4)
+    # no returned token is a masked one
+    t = inp["target_logits"]
+    neg = t == ({"f32": np.float32(-np.inf), "bf16": np.uint16(0xFF80)}[case.logits_dtype])
+    for nb in range(case.NB):
+        assert not neg[nb, got["accepted_len"][nb], got["next_token"][nb]]
+    # the walk met drafted tokens the target masks (p = 0: rejected on the spot) as well as ordinary ones
+    assert (ref["accepted_len"][1::4] == 0).all()
+    assert (ref["ratio"][examined] > 0).any()
+    if not case.point_mass:
+        assert (ref["accepted_len"] > 0).any()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_measure_zero_cases_of_the_accept_rule(oracle, dtype):
+    """The cases the rule's wording leaves open, fixed by declaration and the same on both sides: q(x) = 0 < p(x)
+    accepts whatever the draw; p(x) = q(x) = 0 rejects; a rejection after which the residual max(0, p - q) has no
+    mass (p == q wherever either has mass) draws from p itself."""
+    from gpu_util import run_accept
+    V, K, NB = 8, 2, 4
+    ninf = -np.inf
+    base = np.array([0.5, -1.0, 2.0, 0.25, 1.5, -0.5, 0.0, 1.0], dtype=np.float32)
+    t = np.tile(base, (NB, K + 1, 1))
+    d = np.tile(base, (NB, K, 1))
+    tok = np.zeros((NB, K), dtype=np.int32)
+    # branch 0: token 3 has no draft mass, the target gives it some: accepted at any u; position 1 ordinary
+    d[0, 0, 3] = ninf
+    tok[0] = (3, 2)
+    # branch 1: token 3 masked on both sides, the rows agree elsewhere: rejected, residual empty, drawn from p_0
+    t[1, 0, 3] = ninf
+    d[1, 0, 3] = ninf
+    tok[1] = (3, 2)
+    # branch 2: token 5 masked on both sides, rows differ: rejected, ordinary residual
+    t[2, 0, 5] = ninf
+    d[2, 0, 5] = ninf
+    d[2, 0, :5] += np.float32(0.5)
+    tok[2] = (5, 1)
+    # branch 3: identical rows, nothing masked: everything accepted, bonus token from row K
+    tok[3] = (2, 4)
+    u_acc = np.array([[0.999, 0.1], [0.0, 0.5], [0.0, 0.5], [0.99, 0.99]], dtype=np.float32)
+    u_smp = np.array([0.3, 0.77, 0.41, 0.05], dtype=np.float32)
+    inp = {"target_logits": W.encode(t, dtype), "draft_logits": W.encode(d, dtype), "draft_tokens": tok,
+           "u_accept": u_acc, "u_sample": u_smp}
+    case = W.AcceptCase("measure_zero", NB, K, V, dtype)
+    ref = oracle.spec_accept(**inp, logits_dtype=dtype)
+    got = run_accept(case, inp)
+    np.testing.assert_array_equal(ref["accepted_len"], [2, 0, 0, 2])
+    np.testing.assert_array_equal(got["accepted_len"], ref["accepted_len"])
+    np.testing.assert_array_equal(got["next_token"], ref["next_token"])
+    assert got["next_token"][1] != 3 and got["next_token"][2] != 5      # a token without mass is never drawn
+    assert np.isinf(got["ratio"][0, 0]) and np.isnan(got["ratio"][1, 0])  # p/q as computed: x/0 and 0/0
+
+
 # ------------------------------------------------------------------------------------------ point-mass draft
 POINT_MASS_CASES = [
     W.AcceptCase("pm_small", 400, 4, 512, "f32", target_std=2.0, point_mass=True, peak=7.0, seed=11),

@@ -23,7 +23,7 @@ def oracle_attention(oracle, case, inp, row_ids=None, scale=None):
 
 
 def check_full(oracle, case, tol, kv_split_tokens=0, lse_tol=None):
-    from gpu_util import row_errors, run_attention
+    from gpu_util import error_report, row_errors, run_attention
     print(f"case {case.name} prefix={case.prefix_lens} gamma={case.gamma} L={case.L} Hq={case.Hq} Hkv={case.Hkv} "
           f"D={case.D} kv={case.kv_dtype} br={case.branch_kv_dtype} paged={case.paged} split={kv_split_tokens}",
           flush=True)
@@ -32,6 +32,7 @@ def check_full(oracle, case, tol, kv_split_tokens=0, lse_tol=None):
     ref, ref_lse = oracle_attention(oracle, case, inp)
     assert np.isfinite(got).all()
     err = row_errors(got, ref)
+    print(f"  errors: {error_report(got, ref)}", flush=True)
     assert err.max() <= tol, f"max row error {err.max():.3e} at row {err.argmax()}"
     # bf16 path: Q is rounded to bf16 once more after the score scale is folded into it, which moves every score by
     # up to 2^-9 of sum|q_d k_d|*scale (about 1e-3 rms, a few 1e-3 at worst for these inputs); LSE inherits that
@@ -407,6 +408,14 @@ def sampled_rows(case, n_random, seed=0):
     total = case.B * case.gamma * case.L * case.Hq
     ids.extend(np.random.default_rng(seed).integers(0, total, size=n_random).tolist())
     return np.unique(np.asarray(ids, dtype=np.int64))
+
+
+@pytest.mark.parametrize("n", [3, 4])
+def test_full_size_configs_every_row(oracle, n):
+    """Configurations 3 and 4 at full size, in the launch configuration the benchmark uses, every output row against
+    the oracle (configuration 4: about a teraflop of fp64 on the host cores)."""
+    case, _ = W.config(n)
+    check_full(oracle, case, TOL_LOWP)
 
 
 @pytest.mark.parametrize("n", [3, 4, 5])

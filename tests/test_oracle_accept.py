@@ -206,6 +206,35 @@ def test_ratio_matches_independent_softmax(oracle):
     np.testing.assert_array_equal(r["accepted_len"], expect)
 
 
+def test_masked_logits_have_exactly_zero_mass(oracle):
+    """-inf logits (a constrained vocabulary): the ratios equal an independent softmax over the unmasked entries, a
+    drafted token the target masks is rejected, and over many draws no masked token is ever emitted while the
+    emitted tokens follow the target restricted to its support."""
+    import torch
+    rng = np.random.default_rng(5)
+    V, K, NB = 12, 1, 40000
+    t1 = rng.normal(size=V).astype(np.float32)
+    d1 = (t1 + rng.normal(scale=0.7, size=V)).astype(np.float32)
+    t1[[2, 7]] = -np.inf                        # masked in the target: p = 0
+    d1[[7, 9]] = -np.inf                        # masked in the draft: q = 0
+    p = torch.softmax(torch.from_numpy(t1).double(), -1).numpy()
+    q = torch.softmax(torch.from_numpy(d1).double(), -1).numpy()
+    assert p[2] == 0 and p[7] == 0 and q[9] == 0
+    tok = rng.choice(V, size=(NB, K), p=q).astype(np.int32)          # x ~ q: never 7 or 9
+    t = np.tile(t1, (NB, K + 1, 1))
+    d = np.tile(d1, (NB, K, 1))
+    r = oracle.spec_accept(t, d, tok, rng.random((NB, K), dtype=np.float32), rng.random(NB, dtype=np.float32),
+                           logits_dtype="f32")
+    np.testing.assert_allclose(r["ratio"][:, 0], p[tok[:, 0]] / q[tok[:, 0]], rtol=1e-12)
+    assert (r["accepted_len"][tok[:, 0] == 2] == 0).all()              # p(x) = 0: always rejected
+    emitted = np.where(r["accepted_len"] >= 1, tok[:, 0], r["next_token"])
+    counts = np.bincount(emitted, minlength=V)
+    assert counts[2] == 0 and counts[7] == 0                           # no mass, never emitted
+    keep = p > 0
+    chi2 = (((counts[keep] - NB * p[keep]) ** 2) / (NB * p[keep])).sum()
+    assert chi2 < 40.0                                                 # 9 degrees of freedom; P(chi2 > 40) < 1e-5
+
+
 def test_rejects_bad_arguments(oracle):
     t = np.zeros((1, 2, 4), np.float32)
     d = np.zeros((1, 1, 4), np.float32)
