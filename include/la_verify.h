@@ -434,7 +434,8 @@ LA_API la_status la_plan_budget(const la_plan_desc *desc, int32_t *k1, int32_t *
 /* ------------------------------------------------------------------------- *
  *  Diagnostics
  * ------------------------------------------------------------------------- */
-LA_API const char *la_status_string(la_status s);
+/* Text of a status code; any integer is accepted (unknown ones give "unknown status"). */
+LA_API const char *la_status_string(int32_t status);
 
 #ifdef __cplusplus
 }

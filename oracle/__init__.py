@@ -37,6 +37,15 @@ def build(force: bool = False) -> Path:
     return _LIB
 
 
+def build_sanitized(out: Path) -> Path:
+    """``la_oracle.c`` with gcc's address and undefined-behaviour sanitizers, for the test that runs the pins
+    under them (load it with ``LA_ORACLE_LIB`` and gcc's libasan preloaded)."""
+    cmd = ["gcc", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", str(out), str(_SRC), "-lm"]
+    subprocess.run(cmd, check=True)
+    return out
+
+
 _lib = None
 
 

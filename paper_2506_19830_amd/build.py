@@ -73,5 +73,51 @@ def build(verbose: bool = False, extra_flags=(), lib: Path = LIB, bench_lib: Pat
     return lib
 
 
+# Host-side translation units: argument validation, planning, the step-level controller, the scratch look-up of
+# la_spec_accept_static.  build_host_sanitized() recompiles these with the host sanitizers (device code is compiled
+# as always) and links them with the other, unchanged objects into a library for the CPU test that exercises
+# every host path under AddressSanitizer and UndefinedBehaviorSanitizer.
+HOST_SOURCES = ["api.hip", "controller.hip", "accept_static.hip"]
+
+
+def asan_runtime() -> Path:
+    """The shared AddressSanitizer runtime of hipcc's clang (to be preloaded into the process that loads the library)."""
+    hipcc = _hipcc()
+    r = subprocess.run([hipcc, "-print-file-name=libclang_rt.asan-x86_64.so"], capture_output=True, text=True)
+    cand = Path(r.stdout.strip())
+    if cand.is_file():
+        return cand
+    for cand in Path("/opt/rocm/lib/llvm/lib/clang").glob("*/lib/linux/libclang_rt.asan-x86_64.so"):
+        return cand
+    raise FileNotFoundError("libclang_rt.asan-x86_64.so")
+
+
+def build_host_sanitized(out: Path) -> Path:
+    """``out``: the library with its host-only translation units built with -fsanitize=address,undefined."""
+    if not all((OBJ / (src + ".o")).exists() for src in SOURCES):
+        build()
+    hipcc = _hipcc()
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+           "-fno-sanitize-recover=undefined", "-g"]
+    objs = []
+    for src in SOURCES:
+        if src not in HOST_SOURCES:
+            objs.append(OBJ / (src + ".o"))
+            continue
+        obj = out.parent / (src + ".san.o")
+        flags = [f for f in FLAGS if f != "-O3"] + ["-O1"]
+        r = subprocess.run([hipcc, *flags, *san, "-c", str(CSRC / src), "-o", str(obj)], capture_output=True,
+                           text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc (sanitized) failed on {src}:\n{r.stderr}")
+        objs.append(obj)
+    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address",
+                        "-fsanitize=undefined", "-shared-libsan", "-o", str(out), *map(str, objs)],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"link (sanitized) failed:\n{r.stderr}")
+    return out
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

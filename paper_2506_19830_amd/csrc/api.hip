@@ -202,8 +202,8 @@ using namespace la;
 
 extern "C" {
 
-const char *la_status_string(la_status s) {
-  switch (s) {
+const char *la_status_string(int32_t status) {
+  switch (status) {
     case LA_OK: return "ok";
     case LA_ERR_INVALID_ARG: return "invalid argument";
     case LA_ERR_UNSUPPORTED: return "unsupported shape or dtype combination";
