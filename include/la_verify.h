@@ -85,7 +85,11 @@ typedef enum {
  *      q bf16, cache bf16, branch bf16, out bf16|f32   head_dim 128
  *      q bf16, cache fp8,  branch fp8|bf16, out bf16|f32  head_dim 128
  *  fp8 storage is multiplied by k_scale[kv_head] / v_scale[kv_head]; a branch
- *  K/V stored as fp8 uses the same scales as the cache.
+ *  K/V stored as fp8 uses the same scales as the cache.  The scales are device
+ *  arrays the host cannot inspect: they must be positive and finite (a zero,
+ *  negative or non-finite scale gives undefined results, not an error code).
+ *  Every query row must see at least one key (always true: a token sees
+ *  itself), and K, V, Q must be finite.
  * ------------------------------------------------------------------------- */
 typedef struct {
   int32_t num_requests;            /* B >= 1                                           */
@@ -312,6 +316,11 @@ LA_API la_status la_kv_commit_tree(
  *
  *  The accept test runs in fp32; the resampling row and the top-p masses are
  *  evaluated in fp64.
+ *
+ *  Logits may be -inf (a masked / constrained vocabulary): such a token has
+ *  probability exactly 0, is never drawn, and is rejected when drafted
+ *  (p = 0; also p = q = 0).  Every row must keep at least one finite logit;
+ *  +inf and NaN logits give undefined results.
  * ------------------------------------------------------------------------- */
 typedef struct {
   int32_t num_branches;   /* NB >= 1                                   */

@@ -144,10 +144,13 @@ def run_accept(case: W.AcceptCase, inp: dict, dev=None):
     return {"accepted_len": n.cpu().numpy(), "next_token": tok.cpu().numpy(), "ratio": ratio.double().cpu().numpy()}
 
 
-def compare_accept(got: dict, ref: dict, threshold_eps: float = 1e-6, edge_eps: float = 1e-6):
-    """Bit-exact comparison of (n, token) with the oracle, setting aside branches whose decisive draw lies within
-    threshold_eps of the p/q threshold (or whose sampling draw lies within edge_eps of a CDF edge of the
-    returned token).  Returns (mismatches, n_near_threshold, n_near_edge)."""
+def compare_accept(got: dict, ref: dict, threshold_eps: float = 1e-6):
+    """Bit-exact comparison of (n, token) with the oracle.  A branch is set aside (counted, not compared) when one of
+    its examined accept draws lies within threshold_eps of the min(1, p/q) threshold in the oracle's fp64 -- the
+    benchmark's stated exception -- or when a top-p cut of one of its target rows lies within 1e-9 (relative mass) of
+    a token boundary, where two fp64 summation orders may differ.  The sampled token needs no exception: both sides
+    walk the resampling row in fp64.  Returns (branches whose n differs, branches with equal n whose token differs,
+    branches set aside)."""
     NB = ref["accepted_len"].shape[0]
     near_thr = np.zeros(NB, dtype=bool)
     for nb in range(NB):

@@ -265,7 +265,7 @@ def check_inputs(oracle, case, inp):
     bad_n, bad_tok, near = compare_accept(got, ref)
     print(f"  {case.name}: near-threshold branches set aside: {near} of {case.NB}", flush=True)
     assert bad_n == 0 and bad_tok == 0, f"{bad_n} accepted lengths, {bad_tok} tokens differ"
-    assert near < case.NB // 2
+    assert near <= 2 + case.NB // 50      # a draw within 1e-6 of its threshold is a one-in-a-million event per position
     return got, ref
 
 
