@@ -38,6 +38,11 @@ def parse_args():
                          "configuration 5's shape")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--kv-split-tokens", type=int, default=0)
+    ap.add_argument("--zero-inputs", choices=("none", "kv", "all"), default="none",
+                    help="diagnostic, not a benchmark: the same launches on an all-zero K/V cache (kv) or on all-zero "
+                         "Q, K, V (all).  The instruction stream and the memory traffic do not change, only how many "
+                         "bits toggle in the matrix pipeline: the difference to the normal run is what the chip's "
+                         "power management takes (parity is not checked on such a run)")
     ap.add_argument("--branch-len", type=int, default=None,
                     help="override L, the tokens per branch (branch-length sweep at the configuration's shape)")
     ap.add_argument("--gamma", type=int, default=None, help="override the configuration's number of branches")
@@ -364,6 +369,11 @@ def main():
 
     # ---- inputs (resident in HBM before anything is timed) -------------------------------------------------
     layers = [W.make_attention_inputs_device(W.with_layer(attn_case, l), dev) for l in range(n_layers)]
+    if args.zero_inputs != "none":
+        args.no_cpu_baseline = True   # nothing to compare: the inputs are not the workload's
+        for t in layers:
+            for name in ("k_cache", "v_cache") + (("q", "k_branch", "v_branch") if args.zero_inputs == "all" else ()):
+                t[name].zero_()
     lens = [int(x) for x in attn_case.prefix_lens]
     desc = B.make_attn_desc(num_requests=attn_case.B, num_q_heads=attn_case.Hq, num_kv_heads=attn_case.Hkv,
                             head_dim=attn_case.D, gamma=attn_case.gamma, branch_len=attn_case.L,
@@ -547,6 +557,7 @@ def main():
             "layers": n_layers,
             "branch_tokens_per_step": branch_tokens,
             "kv_split_tokens": args.kv_split_tokens,
+            "zero_inputs": args.zero_inputs,
             "plan": plan,
             "chain_len": C,
             "tree": args.tree, "pool_len": None if tree is None else tree["pool_len"],

@@ -126,8 +126,9 @@ LA_API la_status la_verify_attention_workspace(const la_attn_desc *desc, const i
 typedef struct {
   int32_t path;               /* 1 = fp32 kernel, 2 = bf16/fp8 MFMA kernels                      */
   int32_t kernel_shape;       /* MFMA path: 1 = 256-row tiles, 3 LDS stages; 2 = 128-row tiles,
-                                 2 stages; 3.. = streaming shapes (32-row blocks x key slices:
-                                 3 = 2 x 4, 4 = 4 x 2, 5 = 8 x 1), few rows per KV head          */
+                                 2 stages; 3.. = streaming shapes (32-row blocks x key slices;
+                                 fp8 cache and branch K/V: 3 = 2 x 4, 4 = 4 x 2, 5 = 8 x 1;
+                                 bf16 cache and branch K/V: 6 = 8 x 1, 7 = 4 x 2)                */
   int32_t rows_per_workgroup; /* query rows (of one KV head) a workgroup owns                    */
   int32_t row_tiles;          /* workgroups per (KV head, chunk)                                 */
   int32_t chunk_tokens;       /* prefix tokens per independently reduced chunk                   */

@@ -36,6 +36,7 @@ enum AttnPath { PATH_NONE = 0, PATH_F32, PATH_MFMA };
 // attn_mfma_kernel first, then the streaming shapes of attn_stream_kernel.
 struct ShapeInfo {
   bool stream;
+  bool fp8;        // streaming shapes: storage type of cache and branch K/V the shape is built for
   int local;       // index inside its kernel's own shape table
   int tile_m;      // query rows per workgroup
   int per_cu;      // workgroups that share a CU
@@ -57,7 +58,11 @@ ShapeInfo shape_info(int shape) {
     s.step_keys = attn_stream_step_keys(s.local);
     // every wavefront reduces one 64-key tile for its 32 rows per step, whatever the shape: the time of a step is
     // the time of two such units on one SIMD
-    s.t_step = s.tile_m == 64 ? 3.0 : s.tile_m == 128 ? 2.6 : 2.8;
+    s.fp8 = attn_stream_shape_is_fp8(s.local);
+    if (s.fp8)
+      s.t_step = s.tile_m == 64 ? 3.0 : s.tile_m == 128 ? 2.6 : 2.8;
+    else
+      s.t_step = s.tile_m == 256 ? 2.45 : 2.6;
     s.t_fixed = 5.0;
   }
   return s;
@@ -122,10 +127,15 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, bool
   const int G = d->num_q_heads / d->num_kv_heads;
   const int R = d->gamma * d->branch_len * G;
   const size_t n_rows = (size_t)d->gamma * d->branch_len * d->num_q_heads;
-  // the streaming shapes exist for an fp8 cache with fp8 branch K/V, flat calls
-  const bool stream_ok = plan->kv_fp8 && plan->br_fp8 && !extra &&
-                         (int64_t)d->num_kv_heads * d->block_size * d->head_dim < ((int64_t)1 << 32);
-  if (d->kernel_shape > 0 && shape_info(d->kernel_shape - 1).stream && !stream_ok) return LA_ERR_UNSUPPORTED;
+  // the streaming shapes exist for flat calls with cache and branch K/V of one storage type
+  auto stream_ok = [&](const ShapeInfo &si) {
+    return !extra && plan->kv_fp8 == si.fp8 && plan->br_fp8 == si.fp8 &&
+           (int64_t)d->num_kv_heads * d->block_size * d->head_dim * (si.fp8 ? 1 : 2) < ((int64_t)1 << 32);
+  };
+  if (d->kernel_shape > 0) {
+    const ShapeInfo forced = shape_info(d->kernel_shape - 1);
+    if (forced.stream && !stream_ok(forced)) return LA_ERR_UNSUPPORTED;
+  }
 
   // Choose the kernel shape and the number of chunks that minimise a simple cost model (microseconds, constants
   // fitted to measurements on MI355X):
@@ -141,7 +151,7 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, bool
   for (int shape = 0; shape < num_shapes(); ++shape) {
     if (d->kernel_shape > 0 && shape != d->kernel_shape - 1) continue;
     const ShapeInfo si = shape_info(shape);
-    if (si.stream && !stream_ok) continue;
+    if (si.stream && !stream_ok(si)) continue;
     const int64_t base_wgs = (int64_t)d->num_kv_heads * ((R + si.tile_m - 1) / si.tile_m);
     const int priv_tokens = si.tile_m / G + d->branch_len < d->gamma * d->branch_len ? si.tile_m / G + d->branch_len
                                                                                      : d->gamma * d->branch_len;

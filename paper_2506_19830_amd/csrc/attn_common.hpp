@@ -128,14 +128,15 @@ __device__ __forceinline__ void block_max(const f32x16 (&s)[RB], float crel, con
 }
 
 // Fold the block maxima into the running maxima.  A lane raises its maximum only when the block exceeds it by more
-// than kRaise; alpha is the factor its old accumulators must then be multiplied by (1 for lanes that keep their
+// than `threshold`; alpha is the factor its old accumulators must then be multiplied by (1 for lanes that keep their
 // maximum).  Returns whether any lane of the wavefront raised (wavefront-uniform).
 template <int RB>
-__device__ __forceinline__ bool raise_max(const float (&mt)[RB], RowState<RB> &st, float (&alpha)[RB]) {
+__device__ __forceinline__ bool raise_max(const float (&mt)[RB], RowState<RB> &st, float (&alpha)[RB],
+                                          float threshold = kRaise) {
   bool raise = false;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    const bool up = mt[rb] > st.m_run[rb] + kRaise;   // false for mt = -inf; true for the first finite block
+    const bool up = mt[rb] > st.m_run[rb] + threshold;   // false for mt = -inf; true for the first finite block
     const float m_new = up ? mt[rb] : st.m_run[rb];
     const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
     alpha[rb] = up ? __builtin_amdgcn_exp2f(st.m_run[rb] - m_use) : 1.0f;   // 0 when m_run was -inf
@@ -176,6 +177,58 @@ __device__ __forceinline__ void block_probs(const f32x16 (&s)[RB], float crel, c
     }
     sum[rb] = acc;
   }
+}
+
+
+// Which request and which of its chunks workgroup-unit `unit` (counted over the chunks of all requests, request by
+// request) reduces, and that chunk's key range.  Chunks are numbered from the end: the last chunk of a request (it also
+// carries the branch-private tiles and so runs longest) comes first in dispatch order.
+struct ChunkSel {
+  int b, P, n_chunks, c, k_begin, k_end;
+};
+__device__ __forceinline__ ChunkSel attn_select_chunk(const AttnParams &p, int unit) {
+  ChunkSel s;
+  s.b = 0, s.P = 0, s.n_chunks = 1;
+  int c = unit;
+  if (p.n_inline) {
+    // few requests: everything comes from the kernel arguments (indexed with constants only, so that it stays in
+    // scalar registers), no load and no division
+    int q = 0, r = 0;
+    uint32_t inv = 0;
+    bool found = false;
+#pragma unroll
+    for (int i = 0; i < kMaxInlineLens; ++i) {
+      if (!found && i < p.B) {
+        if (c < p.req[i].n || i == p.B - 1) {
+          s.b = i, s.P = p.req[i].P, s.n_chunks = p.req[i].n, q = p.req[i].q, r = p.req[i].r, inv = p.req[i].inv;
+          found = true;
+        } else {
+          c -= p.req[i].n;
+        }
+      }
+    }
+    c = s.n_chunks - 1 - c;
+    // attn_chunk_range with floor(c * (q*n + r) / n) = c*q + floor(c*r / n) and the quotient by multiply-shift
+    const int T = (s.P + 63) >> 6;
+    const int t0 = min(T, c * q + (int)__umulhi((uint32_t)(c * r), inv));
+    const int t1 = c == s.n_chunks - 1 ? T : min(T, (c + 1) * q + (int)__umulhi((uint32_t)((c + 1) * r), inv));
+    s.k_begin = t0 * 64;
+    s.k_end = min(s.P, t1 * 64);
+  } else {
+    int b = 0;
+    for (; b < p.B - 1; ++b) {
+      const int nc = attn_num_chunks(p.prefix_lens[b], p.chunk_len);
+      if (c < nc) break;
+      c -= nc;
+    }
+    s.b = b;
+    s.P = p.prefix_lens[b];
+    s.n_chunks = attn_num_chunks(s.P, p.chunk_len);
+    c = s.n_chunks - 1 - c;
+    attn_chunk_range(s.P, p.chunk_len, p.last_short, c, &s.k_begin, &s.k_end);
+  }
+  s.c = c;
+  return s;
 }
 
 }  // namespace

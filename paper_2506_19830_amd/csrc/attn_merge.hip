@@ -53,23 +53,22 @@ __global__ __launch_bounds__(64 * kWaves) void attn_merge_kernel(const AttnParam
     m_all = m_new;
     const float *po = p.part_o + ((slot0 + s0) * p.n_rows + r) * kD + 2 * lane;
     const size_t stride = (size_t)p.n_rows * kD;  // between the partials of consecutive chunks
-    int s = 0;
-    for (; s + 8 <= cnt; s += 8) {  // eight independent loads in flight: with many chunks this loop is latency bound
-      f32x2 o[8];
+    // with many chunks this loop is bound by the latency of its loads, so a whole group of 32 partial rows is
+    // requested before the first is used (64 registers)
+#pragma unroll 1
+    for (int g = 0; g < cnt; g += 32) {
+      f32x2 o[32];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) o[j] = *(const f32x2 *)(po + (size_t)(s + j) * stride);
+      for (int j = 0; j < 32; ++j) {
+        const int sj = g + j < cnt ? g + j : cnt - 1;   // surplus slots repeat the last chunk with weight zero
+        o[j] = *(const f32x2 *)(po + (size_t)sj * stride);
+      }
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float ws = __shfl(w, s + j);
+      for (int j = 0; j < 32; ++j) {
+        const float ws = g + j < cnt ? __shfl(w, g + j) : 0.f;
         acc0 = __builtin_fmaf(ws, o[j].x, acc0);
         acc1 = __builtin_fmaf(ws, o[j].y, acc1);
       }
-    }
-    for (; s < cnt; ++s) {
-      const float ws = __shfl(w, s);
-      const f32x2 o = *(const f32x2 *)(po + (size_t)s * stride);
-      acc0 = __builtin_fmaf(ws, o.x, acc0);
-      acc1 = __builtin_fmaf(ws, o.y, acc1);
     }
   }
   const float inv = 1.0f / denom;

@@ -37,8 +37,9 @@ constexpr int kKTileBytes = kTileN * kKRow;  // 17408
 constexpr int kVTileBytes = kD * kVRow;      // 18432
 constexpr int kStageBytes = kKTileBytes + kVTileBytes;
 constexpr int kMaxChunkBlocks = 4096;        // block ids of one chunk kept in LDS
-constexpr int kMaxStages = 3;
-constexpr int kLdsTotal = kMaxStages * kStageBytes + kMaxChunkBlocks * 4;  // stages + block ids: 123904
+constexpr int kMaxStages = 4;
+constexpr int kLdsTotal = kMaxStages * kStageBytes + kMaxChunkBlocks * 4;  // stages + block ids: 159744
+static_assert(kLdsTotal <= 160 * 1024, "LDS of one CU");
 
 // Where the keys of one tile come from.
 struct TileSrc {
@@ -149,14 +150,31 @@ struct PrefixLoader {
   }
   // `first`: first token of the tile (a multiple of 64, every key of the tile valid)
   __device__ __forceinline__ void load(int first, TileRegs<FP8, NT> &r) const {
+    int ids[kNK + kNV];
+    fetch_ids(first, ids);
+    load_k(first, ids, r);
+    load_v(first, ids, r);
+  }
+  // The same in three steps, for a caller that spreads them between other work: the block ids from LDS, then the K
+  // loads, then the V loads.
+  __device__ __forceinline__ void fetch_ids(int first, int (&ids)[kNK + kNV]) const {
     const int rel = (first >> shift) - first_lb;
+#pragma unroll
+    for (int e = 0; e < kNK; ++e) ids[e] = blk[rel + slot_k[e]];
+#pragma unroll
+    for (int e = 0; e < kNV; ++e) ids[kNK + e] = blk[rel + slot_v[e]];
+  }
+  __device__ __forceinline__ void load_k(int first, const int (&ids)[kNK + kNV], TileRegs<FP8, NT> &r) const {
     const size_t inside = (size_t)(first & bs_mask) * row_bytes;
 #pragma unroll
     for (int e = 0; e < kNK; ++e)
-      r.k[e] = *(const u32x4 *)(base_k[e] + (size_t)(uint32_t)blk[rel + slot_k[e]] * blk_stride + inside);
+      r.k[e] = *(const u32x4 *)(base_k[e] + (size_t)(uint32_t)ids[e] * blk_stride + inside);
+  }
+  __device__ __forceinline__ void load_v(int first, const int (&ids)[kNK + kNV], TileRegs<FP8, NT> &r) const {
+    const size_t inside = (size_t)(first & bs_mask) * row_bytes;
 #pragma unroll
     for (int e = 0; e < kNV; ++e) {
-      const uint8_t *row = base_v[e] + (size_t)(uint32_t)blk[rel + slot_v[e]] * blk_stride + inside;
+      const uint8_t *row = base_v[e] + (size_t)(uint32_t)ids[kNK + e] * blk_stride + inside;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         if constexpr (kVW == 1) {
@@ -172,39 +190,17 @@ struct PrefixLoader {
 };
 
 // Registers -> LDS stage: K rows as they are, V transposed ([d][key], keys permuted by vt_pos); fp8 is widened to
-// bf16 on the way (exact: every e4m3 value is a bf16 value).
+// bf16 on the way (exact: every e4m3 value is a bf16 value).  In three pieces (K; V columns d0, d0+1; V columns d0+2,
+// d0+3) so that a caller can spread them between other work.
 template <bool FP8, int NT>
-__device__ __forceinline__ void tile_store(uint8_t *stage, int tid, const TileRegs<FP8, NT> &r) {
+__device__ __forceinline__ void tile_store_k(uint8_t *stage, int tid, const TileRegs<FP8, NT> &r) {
   uint8_t *kt = stage;
-  uint8_t *vt = stage + kKTileBytes;
-  if constexpr (!FP8) {
 #pragma unroll
-    for (int e = 0; e < TileRegs<FP8, NT>::kNK; ++e) {
-      const int idx = tid + NT * e;
+  for (int e = 0; e < TileRegs<FP8, NT>::kNK; ++e) {
+    const int idx = tid + NT * e;
+    if constexpr (!FP8) {
       *(u32x4 *)(kt + (idx >> 4) * kKRow + (idx & 15) * 16) = r.k[e];
-    }
-#pragma unroll
-    for (int e = 0; e < TileRegs<FP8, NT>::kNV; ++e) {
-      const int idx = tid + NT * e;
-      const int kq = idx >> 5;
-      const int d0 = 4 * (idx & 31);
-      // of key c: bf16 pairs (d0, d0+1) in v[2(4e+c)] and (d0+2, d0+3) in v[2(4e+c)+1]; columns d0..d0+3 live in
-      // rows (d0/4) + 32*{0,1,2,3}: consecutive lanes write consecutive rows
-      const uint32_t *lo = &r.v[8 * e], *hi = &r.v[8 * e + 1];  // stride 2 between keys
-      uint8_t *dst = vt + (d0 >> 2) * kVRow + vt_pos(kq) * 2;
-      *(u32x2 *)(dst) = u32x2{__builtin_amdgcn_perm(lo[2], lo[0], 0x05040100u),
-                              __builtin_amdgcn_perm(lo[6], lo[4], 0x05040100u)};
-      *(u32x2 *)(dst + 32 * kVRow) = u32x2{__builtin_amdgcn_perm(lo[2], lo[0], 0x07060302u),
-                                           __builtin_amdgcn_perm(lo[6], lo[4], 0x07060302u)};
-      *(u32x2 *)(dst + 64 * kVRow) = u32x2{__builtin_amdgcn_perm(hi[2], hi[0], 0x05040100u),
-                                           __builtin_amdgcn_perm(hi[6], hi[4], 0x05040100u)};
-      *(u32x2 *)(dst + 96 * kVRow) = u32x2{__builtin_amdgcn_perm(hi[2], hi[0], 0x07060302u),
-                                           __builtin_amdgcn_perm(hi[6], hi[4], 0x07060302u)};
-    }
-  } else {
-#pragma unroll
-    for (int e = 0; e < TileRegs<FP8, NT>::kNK; ++e) {
-      const int idx = tid + NT * e;
+    } else {
       uint32_t out[8];
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
@@ -216,30 +212,38 @@ __device__ __forceinline__ void tile_store(uint8_t *stage, int tid, const TileRe
       *(u32x4 *)(dst) = u32x4{out[0], out[1], out[2], out[3]};
       *(u32x4 *)(dst + 16) = u32x4{out[4], out[5], out[6], out[7]};
     }
-#pragma unroll
-    for (int e = 0; e < TileRegs<FP8, NT>::kNV; ++e) {
-      const int idx = tid + NT * e;
-      const int kq = idx >> 5;
-      const int d0 = 4 * (idx & 31);
-      uint32_t lo[4], hi[4];  // of key c: bf16 pairs (d0, d0+1) and (d0+2, d0+3)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        lo[c] = fp8x2_to_bf16x2<false>(r.v[4 * e + c]);
-        hi[c] = fp8x2_to_bf16x2<true>(r.v[4 * e + c]);
-      }
-      // columns d0..d0+3 live in rows (d0/4) + 32*{0,1,2,3}: consecutive lanes write consecutive rows
-      uint8_t *dst = vt + (d0 >> 2) * kVRow + vt_pos(kq) * 2;
-      // column d0: low halves of lo[0..3]; column d0+1: high halves; columns d0+2, d0+3 likewise from hi[]
-      *(u32x2 *)(dst) = u32x2{__builtin_amdgcn_perm(lo[1], lo[0], 0x05040100u),
-                              __builtin_amdgcn_perm(lo[3], lo[2], 0x05040100u)};
-      *(u32x2 *)(dst + 32 * kVRow) = u32x2{__builtin_amdgcn_perm(lo[1], lo[0], 0x07060302u),
-                                           __builtin_amdgcn_perm(lo[3], lo[2], 0x07060302u)};
-      *(u32x2 *)(dst + 64 * kVRow) = u32x2{__builtin_amdgcn_perm(hi[1], hi[0], 0x05040100u),
-                                           __builtin_amdgcn_perm(hi[3], hi[2], 0x05040100u)};
-      *(u32x2 *)(dst + 96 * kVRow) = u32x2{__builtin_amdgcn_perm(hi[1], hi[0], 0x07060302u),
-                                           __builtin_amdgcn_perm(hi[3], hi[2], 0x07060302u)};
-    }
   }
+}
+// HALF 0: head-dim columns d0, d0+1 of the thread's four keys; HALF 1: columns d0+2, d0+3
+template <bool FP8, int NT, int HALF>
+__device__ __forceinline__ void tile_store_v(uint8_t *stage, int tid, const TileRegs<FP8, NT> &r) {
+  uint8_t *vt = stage + kKTileBytes;
+#pragma unroll
+  for (int e = 0; e < TileRegs<FP8, NT>::kNV; ++e) {
+    const int idx = tid + NT * e;
+    const int kq = idx >> 5;
+    const int d0 = 4 * (idx & 31);
+    // of key c: the bf16 pair (d0 + 2 HALF, d0 + 2 HALF + 1).  Columns d0..d0+3 live in rows (d0/4) + 32*{0,1,2,3}:
+    // consecutive lanes write consecutive rows
+    uint32_t w[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      if constexpr (FP8)
+        w[c] = fp8x2_to_bf16x2<HALF != 0>(r.v[4 * e + c]);
+      else
+        w[c] = r.v[8 * e + 2 * c + HALF];
+    }
+    uint8_t *dst = vt + ((d0 >> 2) + 64 * HALF) * kVRow + vt_pos(kq) * 2;
+    *(u32x2 *)(dst) = u32x2{__builtin_amdgcn_perm(w[1], w[0], 0x05040100u), __builtin_amdgcn_perm(w[3], w[2], 0x05040100u)};
+    *(u32x2 *)(dst + 32 * kVRow) =
+        u32x2{__builtin_amdgcn_perm(w[1], w[0], 0x07060302u), __builtin_amdgcn_perm(w[3], w[2], 0x07060302u)};
+  }
+}
+template <bool FP8, int NT>
+__device__ __forceinline__ void tile_store(uint8_t *stage, int tid, const TileRegs<FP8, NT> &r) {
+  tile_store_k<FP8, NT>(stage, tid, r);
+  tile_store_v<FP8, NT, 0>(stage, tid, r);
+  tile_store_v<FP8, NT, 1>(stage, tid, r);
 }
 
 
@@ -439,9 +443,153 @@ __device__ __forceinline__ void compute_tile(const uint8_t *kt, const uint8_t *n
   tail();
 }
 
+// ---- block-pipelined steady state (four LDS stages, one 32-row block per wavefront) ----------------------------
+// The full prefix tiles of a chunk are reduced as a stream of 32-key blocks b = 0, 1, 2, ... in a three-deep software
+// pipeline: in slot b the MFMAs of S^T_{b+1} = K_{b+1} Q^T and of O^T += V_{b-1}^T P_{b-1}^T run while the VALU turns
+// S^T_b into P^T_b.  Every slot therefore carries 16 MFMAs and one block's worth of exponentials, at every point of
+// the loop, instead of MFMA-only and VALU-heavy stretches taking turns: a wavefront issues roughly one instruction
+// per seven cycles, so the two wavefronts of a SIMD keep the matrix pipe busy only if neither of them ever has long
+// runs of one kind.  The price is a fourth LDS stage (the V rows of the previous tile's second block are still read
+// while the tile after next is written) and that the block maximum is not known when P is formed: P is computed as
+// 2^(s - base) against the base the S^T accumulators were started from; the row sum doubles as the overflow guard (a
+// sum above kTrigger sends the wavefront through the general form, which finds the true maximum and moves the base).
+constexpr float kTrigger = 1024.0f;
+constexpr int kAhead = 3;  // LDS fragment reads run this many MFMAs of their kind ahead of their use
+
+struct PipeCarry {
+  f32x16 s0[1];      // S^T of key block 0 of the tile about to be reduced (its MFMAs ran during the previous tile)
+  float bs0;         // the base s0 was started from
+  bool stale0;       // wavefront-uniform: the base has moved since s0 was started (or there is none yet)
+  uint32_t pq[1][8]; // P^T of key block 1 of the previous tile, not yet multiplied into O (zero before the first)
+  bf16x8 kf[kAhead]; // the first K fragments of the block whose S^T runs in the next slot
+  bf16x8 vf[kAhead]; // the first V^T fragments of the block that is multiplied into O in the next slot
+};
+
+// One slot.  hook(i), i = 0..15, is called once per MFMA.  kS: the lane's K row of the block whose S^T accumulates (fragment t lies 32t bytes on); vP: the lane's
+// V^T row of the block multiplied into O (fragment (db, t2) at db*32*kVRow + 32*t2); kS_next / vP_next: the same for
+// the next slot, whose fragments 0..3 are left in kf / vf.  sc: the complete S^T (relative to its base) of the block
+// in between; its probabilities go to pc (bf16 pairs), their fp32 sum to acc.
+template <bool DO_S, bool NEXT_K, bool NEXT_V, int PRIO, typename Hook>
+__device__ __forceinline__ void pipe_slot(const uint8_t *kS, const uint8_t *vP, const uint8_t *kS_next,
+                                          const uint8_t *vP_next, bf16x8 (&kf)[kAhead], bf16x8 (&vf)[kAhead],
+                                          const bf16x8 (&qf)[8], const f32x16 &c_init, f32x16 &s_new,
+                                          const f32x16 &sc, const uint32_t (&pp)[8], f32x16 (&o)[4][1],
+                                          uint32_t (&pc)[8], float &acc, Hook &&hook) {
+  // fragment windows: entries 0..7 belong to this slot (0..kAhead-1 arrive in kf / vf), 8.. to the next one; the
+  // fragment kAhead places further on is read behind every MFMA
+  bf16x8 ka[8 + kAhead], va[8 + kAhead];
+#pragma unroll
+  for (int j = 0; j < kAhead; ++j) ka[j] = kf[j], va[j] = vf[j];
+  float e_prev = 0.f, sum = 0.f;
+  const u32x4 pw0 = {pp[0], pp[1], pp[2], pp[3]}, pw1 = {pp[4], pp[5], pp[6], pp[7]};
+  const bf16x8 pf0 = __builtin_bit_cast(bf16x8, pw0), pf1 = __builtin_bit_cast(bf16x8, pw1);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int t = i >> 1, n = t + kAhead;
+    // Issue priority falls with progress through the tile (3, 2 in slot A; 1, 0 in slot B): of the two wavefronts of a
+    // SIMD the one that is behind wins the arbitration, so they stay within a quarter of a tile of each other and
+    // neither is left to finish alone before the barrier (a lone wavefront keeps the matrix pipe only half busy).
+    if (i == 0) __builtin_amdgcn_s_setprio(PRIO);
+    if (i == 8) __builtin_amdgcn_s_setprio(PRIO - 1);
+    if ((i & 1) == 0) {
+      if constexpr (DO_S)
+        s_new = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t], qf[t], t == 0 ? c_init : s_new, 0, 0, 0);
+      if (n < 8) {
+        if constexpr (DO_S) ka[n] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(kS + n * 32));
+      } else {
+        if constexpr (NEXT_K) ka[n] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(kS_next + (n - 8) * 32));
+      }
+    } else {
+      // V^T fragment u: head-dim block u % 4, keys 16 (u / 4) .. +16 of the block
+      o[t & 3][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[t], t < 4 ? pf0 : pf1, o[t & 3][0], 0, 0, 0);
+      if (n < 8) {
+        va[n] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(vP + (n & 3) * 32 * kVRow + (n >> 2) * 32));
+      } else {
+        if constexpr (NEXT_V)
+          va[n] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(vP_next + ((n - 8) & 3) * 32 * kVRow + ((n - 8) >> 2) * 32));
+      }
+    }
+    const float e = __builtin_amdgcn_exp2f(sc[i]);
+    if (i & 1) {
+      pc[i >> 1] = pack_bf16(e_prev, e);
+      sum += e_prev + e;
+      asm volatile("" : "+v"(sum), "+v"(pc[i >> 1]));  // here, not wherever the value is first needed
+    } else {
+      e_prev = e;
+    }
+    hook(i);  // the caller's share of other work for this MFMA (staging of later tiles)
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  acc = sum;
+#pragma unroll
+  for (int j = 0; j < kAhead; ++j) {
+    if constexpr (NEXT_K) kf[j] = ka[8 + j];
+    if constexpr (NEXT_V) vf[j] = va[8 + j];
+  }
+}
+
+// The general form of one block after the fact: true maximum, base moved to it when it is above the base, P and its
+// sum again.  binit: the base the scores in s are relative to.  Returns whether any lane moved its base.
+__device__ __forceinline__ bool pipe_redo_block(const f32x16 (&s)[1], float binit, RowState<1> &st, uint32_t (&pc)[1][8],
+                                                float &acc) {
+  const float bi[1] = {binit};
+  float mt[1], alpha[1], off[1], sum[1];
+  block_max<1>(s, 1.f, bi, mt);
+  const bool raised = raise_max<1>(mt, st, alpha, 0.f);
+  const float m_use = (st.m_run[0] == -INFINITY) ? 0.f : st.m_run[0];
+  if (raised) {
+    rescale<1>(st, alpha);
+    st.base[0] = m_use;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) st.negb[0][j] = -m_use;
+  }
+  off[0] = binit - m_use;
+  block_probs<1, false>(s, 1.f, off, pc, sum);
+  acc = sum[0];
+  return raised;
+}
+
+// One 64-key tile of the pipelined steady state: slot A (S^T of the tile's block 1, P of block 0, O += block 1 of
+// the previous tile) and slot B (S^T of block 0 of the next tile, P of block 1, O += block 0).
+//   prev / cur / next: the LDS stages of the three tiles (prev == cur for the first tile, whose pq is zero)
+//   hook_a(i), hook_b(i): the caller's work beside MFMA i of slot A / slot B
+template <bool NEXT, typename HookA, typename HookB>
+__device__ __forceinline__ void pipe_tile(const uint8_t *prev, const uint8_t *cur, const uint8_t *next, PipeCarry &cy,
+                                          RowState<1> &st, int ln, int lh, HookA &&hook_a, HookB &&hook_b) {
+  const int k_lane = ln * kKRow + lh * 16, v_lane = kKTileBytes + ln * kVRow + lh * 16;
+  f32x16 s1[1];
+  uint32_t p0[1][8], p1[1][8];
+  float acc0, acc1;
+  // ---- slot A
+  const float base_a = st.base[0];
+  pipe_slot<true, NEXT, true, 3>(cur + k_lane + 32 * kKRow, prev + v_lane + 64, next + k_lane, cur + v_lane, cy.kf, cy.vf,
+                              st.qf[0], st.negb[0], s1[0], cy.s0[0], cy.pq[0], st.o, p0[0], acc0, hook_a);
+  bool raised_a = false;
+  const bool trig_a = __builtin_amdgcn_ballot_w64(acc0 > kTrigger) != 0;
+  if (cy.stale0 | trig_a) raised_a = pipe_redo_block(cy.s0, cy.bs0, st, p0, acc0);
+  st.l_run[0] += acc0;
+  // ---- slot B
+  const float base_b = st.base[0];
+  f32x16 s0n[1];
+  pipe_slot<NEXT, NEXT, true, 1>(next + k_lane, cur + v_lane, next + k_lane + 32 * kKRow, cur + v_lane + 64, cy.kf, cy.vf,
+                              st.qf[0], st.negb[0], s0n[0], s1[0], p0[0], st.o, p1[0], acc1, hook_b);
+  bool raised_b = false;
+  const bool trig_b = __builtin_amdgcn_ballot_w64(acc1 > kTrigger) != 0;
+  if (raised_a | trig_b) raised_b = pipe_redo_block(s1, base_a, st, p1, acc1);
+  st.l_run[0] += acc1;
+  if constexpr (NEXT) cy.s0[0] = s0n[0];
+  cy.bs0 = base_b;
+  cy.stale0 = raised_b;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) cy.pq[0][j] = p1[0][j];
+}
+
 // NW wavefronts of RB 32-row blocks each: a row tile of 32*NW*RB rows.  STAGES LDS stages per workgroup:
+//   4: fp8 cache, one row block per wavefront: the block-pipelined loop (pipe_tile) over the full prefix tiles; one
+//      workgroup per CU.  The shape for large row counts on an fp8 cache.
 //   3: tile i is computed on while tile i+1 is resident (its first K fragments are fetched early) and tile i+2 is
-//      written; one workgroup per CU.  The shape for large row counts, where the matrix cores are the limit.
+//      written; one workgroup per CU.  The shape for large row counts on a bf16 cache (whose staging registers leave
+//      no room for the pipelined loop's second register set).
 //   2: tile i is computed on while tile i+1 is written and tiles i+2, i+3 are in flight from HBM; two workgroups
 //      share a CU, which hides the start-up and per-tile latencies when the row count is small and the KV
 //      stream is the limit.
@@ -462,20 +610,8 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
   const int kvh = id % p.Hkv;
   id /= p.Hkv;
   const int row_tile = id % p.n_row_tiles;
-  int c = id / p.n_row_tiles;
-  int b = 0;
-  for (; b < p.B - 1; ++b) {
-    const int nc = attn_num_chunks(p.prefix_lens[b], p.chunk_len);
-    if (c < nc) break;
-    c -= nc;
-  }
-  const int P = p.prefix_lens[b];
-  const int n_chunks = attn_num_chunks(P, p.chunk_len);
-  // workgroups are dispatched in blockIdx order: the last chunk, which also carries the chain and branch-private
-  // tiles and so runs longest, goes first instead of into the tail of the launch
-  c = n_chunks - 1 - c;
-  int k_begin, k_end;
-  attn_chunk_range(P, p.chunk_len, p.last_short, c, &k_begin, &k_end);
+  const ChunkSel sel = attn_select_chunk(p, id / p.n_row_tiles);
+  const int b = sel.b, n_chunks = sel.n_chunks, c = sel.c, k_begin = sel.k_begin, k_end = sel.k_end;
   const int n_full = k_end > k_begin ? (k_end - k_begin) / kTileN : 0;          // unmasked prefix tiles
   const bool has_tail = k_end > k_begin && ((k_end - k_begin) % kTileN) != 0;  // one partly filled prefix tile
 
@@ -514,7 +650,7 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
   brs.limit = t_hi + 1;
 
   // two-stage shape: a wavefront whose rows all lie past R stages tiles but computes nothing
-  const bool active = STAGES == 3 || r0 + wave * RB * 32 < p.R;
+  const bool active = STAGES >= 3 || r0 + wave * RB * 32 < p.R;
 
   // Score scales of the two key segments, in log2 units.  Q is multiplied by the prefix scale when it is loaded
   // (and rounded to bf16 again), so prefix scores leave the MFMAs ready for the exponential; a branch segment with
@@ -574,7 +710,103 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
 
   // ---- phase 1: the unmasked prefix tiles -----------------------------------------------------
   bf16x8 k0[8];
-  if constexpr (STAGES == 3) {
+  if constexpr (STAGES == 4) {
+    // ring of four stages, block-pipelined (see pipe_tile).  Iteration i: the global loads of tile i+2 are in flight;
+    // K of tile i (block 1) and of tile i+1 (block 0), V of tile i-1 (block 1) and of tile i (block 0) are read; tile
+    // i+2 is written to stage (i+2)%4, which held tile i-2.
+    static_assert(STAGES != 4 || RB == 1, "the pipelined loop keeps one row block per wavefront");
+    if (n_full > 0) {
+      TileRegs<KV_FP8, NT> regs;
+      PrefixLoader<KV_FP8, NT> loader;
+      loader.init(p, pre, tid);
+      auto gload = [&](int it) { loader.load(k_begin + it * kTileN, regs); };
+      gload(0);
+      tile_store<KV_FP8, NT>(lds, tid, regs);
+      if (n_full > 1) {
+        gload(1);
+        tile_store<KV_FP8, NT>(lds + kStageBytes, tid, regs);
+      }
+      __syncthreads();
+      PipeCarry cy;
+      {  // S^T of block 0 of tile 0, and the first fragments of slot A of tile 0
+        const uint8_t *krow = lds + ln * kKRow + lh * 16;
+        const uint8_t *vrow = lds + kKTileBytes + ln * kVRow + lh * 16;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) k0[t] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(krow + t * 32));
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+          cy.s0[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0[t], st.qf[0][t], t == 0 ? st.negb[0] : cy.s0[0], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < kAhead; ++t) {
+          cy.kf[t] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(krow + 32 * kKRow + t * 32));
+          cy.vf[t] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(vrow + 64 + (t & 3) * 32 * kVRow + (t >> 2) * 32));
+        }
+        cy.bs0 = 0.f;
+        cy.stale0 = true;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) cy.pq[0][j] = 0u;
+      }
+      auto stage = [&](int it) { return lds + (it & 3) * kStageBytes; };
+      // Staging beside the MFMAs: iteration i requests tile i+3 from global memory during its slot A (block ids from
+      // LDS, then the K load, then the V loads) and writes tile i+2, requested an iteration earlier into the other
+      // register set, to its stage during slot B; the loads have more than a tile time to arrive.
+      TileRegs<KV_FP8, NT> regs2;
+      int ids[PrefixLoader<KV_FP8, NT>::kNK + PrefixLoader<KV_FP8, NT>::kNV];
+      auto no_hook = [](int) {};
+      constexpr int kLoads = PrefixLoader<KV_FP8, NT>::kNK + 4 * PrefixLoader<KV_FP8, NT>::kNV;  // per tile and thread
+      // one steady-state iteration: the loads of tile it+3 go to `ld`, tile it+2 is written from `stq`
+      auto steady = [&](int it, TileRegs<KV_FP8, NT> &ld, const TileRegs<KV_FP8, NT> &stq) __attribute__((always_inline)) {
+        const int first = k_begin + (it + 3) * kTileN;
+        uint8_t *dst = lds + ((it + 2) & 3) * kStageBytes;
+        pipe_tile<true>(
+            stage(it > 0 ? it - 1 : 0), stage(it), stage(it + 1), cy, st, ln, lh,
+            [&](int i) __attribute__((always_inline)) {
+              if (i == 1) loader.fetch_ids(first, ids);
+              if (i == 6) loader.load_k(first, ids, ld);
+              if (i == 8) loader.load_v(first, ids, ld);
+            },
+            [&](int i) __attribute__((always_inline)) {
+              // the loads into stq are older than the kLoads loads into ld just issued; loads return in order
+              if (i == 6) {
+                __builtin_amdgcn_s_waitcnt((kLoads & 15) | ((kLoads >> 4) << 14) | 0x70 | 0xF00);  // vmcnt(kLoads)
+                tile_store_k<KV_FP8, NT>(dst, tid, stq);
+              }
+              if (i == 9) tile_store_v<KV_FP8, NT, 0>(dst, tid, stq);
+              if (i == 12) tile_store_v<KV_FP8, NT, 1>(dst, tid, stq);
+            });
+        __syncthreads();
+      };
+      if (n_full > 2) gload(2);  // into regs
+      int it = 0;
+      for (; it + 4 < n_full; it += 2) {  // steady state, two tiles per trip (the register sets alternate)
+        steady(it, regs2, regs);
+        steady(it + 1, regs, regs2);
+      }
+      // the last tiles that still have something to write (regs holds tile it+2), then the second to last tile
+      for (; it + 1 < n_full; ++it) {
+        pipe_tile<true>(stage(it > 0 ? it - 1 : 0), stage(it), stage(it + 1), cy, st, ln, lh, no_hook, no_hook);
+        if (it + 2 < n_full) {
+          tile_store<KV_FP8, NT>(lds + ((it + 2) & 3) * kStageBytes, tid, regs);
+          if (it + 3 < n_full) gload(it + 3);
+          __syncthreads();
+        }
+      }
+      pipe_tile<false>(stage(it > 0 ? it - 1 : 0), stage(it), stage(it), cy, st, ln, lh, no_hook, no_hook);
+      {  // drain: block 1 of the last tile into O
+        const uint8_t *vrow = stage(it) + kKTileBytes + ln * kVRow + lh * 16 + 64;
+        const u32x4 pw0 = {cy.pq[0][0], cy.pq[0][1], cy.pq[0][2], cy.pq[0][3]};
+        const u32x4 pw1 = {cy.pq[0][4], cy.pq[0][5], cy.pq[0][6], cy.pq[0][7]};
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const bf16x8 vu = u < kAhead ? cy.vf[u < kAhead ? u : 0]
+                                       : __builtin_bit_cast(bf16x8, *(const u32x4 *)(vrow + (u & 3) * 32 * kVRow + (u >> 2) * 32));
+          st.o[u & 3][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vu, __builtin_bit_cast(bf16x8, u < 4 ? pw0 : pw1),
+                                                                   st.o[u & 3][0], 0, 0, 0);
+        }
+      }
+      __syncthreads();
+    }
+  } else if constexpr (STAGES == 3) {
     // ring of three stages.  iteration i: global loads of tile i+2 are in flight, tile i is computed from stage
     // i%3 (its block-0 K fragments were fetched while tile i-1 finished), the block-0 fragments of tile i+1 are
     // fetched from stage (i+1)%3, and tile i+2 is written to stage (i+2)%3, which every wavefront stopped
@@ -803,22 +1035,25 @@ hipError_t launch_variant(const AttnParams &p, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// STAGES: LDS stages with a bf16 cache; an fp8 cache (half the staging registers) with three or more stages runs
+// the block-pipelined loop on four stages instead.
 template <int NW, int RB, int STAGES>
 hipError_t launch_shape(const AttnParams &p, bool kv_fp8, bool br_fp8, hipStream_t stream) {
+  constexpr int kFp8Stages = (STAGES >= 3 && RB == 1) ? 4 : STAGES;
   if (p.C > 0 && p.pool_seg) {
-    if (kv_fp8 && br_fp8) return launch_variant<true, true, NW, RB, STAGES, 2>(p, stream);
-    if (kv_fp8 && !br_fp8) return launch_variant<true, false, NW, RB, STAGES, 2>(p, stream);
+    if (kv_fp8 && br_fp8) return launch_variant<true, true, NW, RB, kFp8Stages, 2>(p, stream);
+    if (kv_fp8 && !br_fp8) return launch_variant<true, false, NW, RB, kFp8Stages, 2>(p, stream);
     if (!kv_fp8 && !br_fp8) return launch_variant<false, false, NW, RB, STAGES, 2>(p, stream);
     return hipErrorInvalidValue;
   }
   if (p.C > 0) {
-    if (kv_fp8 && br_fp8) return launch_variant<true, true, NW, RB, STAGES, 1>(p, stream);
-    if (kv_fp8 && !br_fp8) return launch_variant<true, false, NW, RB, STAGES, 1>(p, stream);
+    if (kv_fp8 && br_fp8) return launch_variant<true, true, NW, RB, kFp8Stages, 1>(p, stream);
+    if (kv_fp8 && !br_fp8) return launch_variant<true, false, NW, RB, kFp8Stages, 1>(p, stream);
     if (!kv_fp8 && !br_fp8) return launch_variant<false, false, NW, RB, STAGES, 1>(p, stream);
     return hipErrorInvalidValue;
   }
-  if (kv_fp8 && br_fp8) return launch_variant<true, true, NW, RB, STAGES, 0>(p, stream);
-  if (kv_fp8 && !br_fp8) return launch_variant<true, false, NW, RB, STAGES, 0>(p, stream);
+  if (kv_fp8 && br_fp8) return launch_variant<true, true, NW, RB, kFp8Stages, 0>(p, stream);
+  if (kv_fp8 && !br_fp8) return launch_variant<true, false, NW, RB, kFp8Stages, 0>(p, stream);
   if (!kv_fp8 && !br_fp8) return launch_variant<false, false, NW, RB, STAGES, 0>(p, stream);
   return hipErrorInvalidValue;
 }

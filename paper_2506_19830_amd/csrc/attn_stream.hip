@@ -34,15 +34,34 @@ constexpr int kTileN = 64;
 constexpr int kRowBytes = kD;                  // fp8
 constexpr int kHalfBytes = kTileN * kRowBytes;  // K (or V) part of a tile
 constexpr int kTileBytes = 2 * kHalfBytes;      // 16 KiB
-constexpr int kInstPerHalf = 8;                 // 1 KiB loads per tile half
 constexpr int kMaxBlkLds = 2048;                // block ids of one chunk kept in LDS
 constexpr int kWaves = 8;
 
+// Tile geometry by storage type.  A wavefront-wide direct load is 1 KiB: kRows key rows x kPieces 16-byte pieces.
+template <bool FP8>
+struct Geo {
+  static constexpr int kRow = kD * (FP8 ? 1 : 2);     // bytes per key row
+  static constexpr int kPieces = kRow / 16;           // 8 / 16
+  static constexpr int kRows = 1024 / kRow;           // key rows per load: 8 / 4
+  static constexpr int kHalf = kTileN * kRow;         // K (or V) part of a tile: 8 / 16 KiB
+  static constexpr int kTile = 2 * kHalf;
+  static constexpr int kLoadsPerHalf = kTileN / kRows;  // 8 / 16
+};
+
 #define LA_LDS __attribute__((address_space(3)))
 typedef __attribute__((ext_vector_type(2))) int i32x2;
+typedef __attribute__((ext_vector_type(4))) short i16x4;
 
+// fp8 tiles (8 pieces per row, two rows per 256 bytes of banks)
 __device__ __forceinline__ int swz_k(int key) { return (key >> 1) & 7; }
 __device__ __forceinline__ int swz_v(int key) { return (((key >> 1) & 1) << 1) | (((key >> 3) & 1) << 2) | ((key >> 2) & 1); }
+// bf16 tiles (16 pieces per row = all banks once): one swizzle serves the K reads (16 consecutive keys at one piece
+// need 16 different slots) and the transposing V reads (four consecutive keys x an aligned group of four pieces)
+__device__ __forceinline__ int swz_16(int key) { return ((key & 3) << 2) | ((key >> 2) & 3); }
+template <bool FP8>
+__device__ __forceinline__ int swz(int key, int half) {
+  return FP8 ? (half ? swz_v(key) : swz_k(key)) : swz_16(key);
+}
 
 // s_waitcnt vmcnt(n) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, the other counters left at their maxima)
 template <int N>
@@ -171,8 +190,9 @@ __device__ __forceinline__ void stream_tile(const uint8_t *kt, const uint8_t *qf
 // load counter advances uniformly; where a step reaches past the end of its key range (a ragged last tile, a tile
 // slot that has no tile) the tokens are clamped to the last valid one and all addresses stay in bounds.
 // (A plain struct of values rather than a capturing lambda: captured locals would be pinned to scratch memory.)
-template <int KSL, int NST, int IPW>
+template <int KSL, int NST, int IPW, bool FP8 = true>
 struct StreamLoader {
+  using G = Geo<FP8>;
   uint32_t ring;                 // LDS address of the ring
   int wave;
   const int32_t *blk;            // LDS: block ids of the chunk (paged), or null: block = ident + logical block
@@ -184,33 +204,34 @@ struct StreamLoader {
   __device__ __forceinline__ void init_lane(int lane) {
 #pragma unroll
     for (int j = 0; j < IPW; ++j) {
-      const int r = (wave * IPW + j) & 15, half = r >> 3;
-      const int k = 8 * (r & 7) + (lane >> 3);
+      const int ii = wave * IPW + j;
+      const int half = (ii / G::kLoadsPerHalf) & 1, r = ii % G::kLoadsPerHalf;
+      const int k = G::kRows * r + lane / G::kPieces;
       key[j] = k;
-      goff[j] = ((lane & 7) ^ (half ? swz_v(k) : swz_k(k))) * 16;
+      goff[j] = ((lane % G::kPieces) ^ swz<FP8>(k, half)) * 16;
     }
   }
   // PREFIX: cache tokens first0 .. (through the block table); else branch tokens.  CLAMP: tokens above `last`
   // repeat token `last`.
   template <bool PREFIX, bool CLAMP>
   __device__ __forceinline__ void issue(int slot, int first0, int last) const {
-    const uint32_t stage = ring + slot * (KSL * kTileBytes);
+    const uint32_t stage = ring + slot * (KSL * G::kTile);
 #pragma unroll
     for (int j = 0; j < IPW; ++j) {
       const int ii = wave * IPW + j;  // wavefront-uniform: which 1 KiB of the step
-      const int tile = ii >> 4, half = (ii >> 3) & 1, r8 = ii & 7;
+      const int tile = ii / (2 * G::kLoadsPerHalf), half = (ii / G::kLoadsPerHalf) & 1, r = ii % G::kLoadsPerHalf;
       int tok = first0 + tile * kTileN + key[j];
       if (CLAMP) tok = min(tok, last);
       const uint8_t *src;
       if (PREFIX) {
         const int lb = tok >> shift;
         const uint32_t b = blk ? (uint32_t)blk[lb - first_lb] : (uint32_t)(ident + lb);
-        const uint32_t inner = ((uint32_t)(tok & bs_mask) << 7) + (uint32_t)goff[j];
+        const uint32_t inner = (uint32_t)(tok & bs_mask) * G::kRow + (uint32_t)goff[j];
         src = (half ? v_pre : k_pre) + ((uint64_t)b * blk_stride + inner);  // one 32 x 32 + 64 multiply-add
       } else {
         src = (half ? v_br : k_br) + ((uint64_t)(uint32_t)tok * br_stride + (uint32_t)goff[j]);
       }
-      load_lds16(src, stage + tile * kTileBytes + half * kHalfBytes + r8 * 1024);
+      load_lds16(src, stage + tile * G::kTile + half * G::kHalf + r * 1024);
     }
   }
 };
@@ -254,42 +275,9 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnPara
   id = __builtin_amdgcn_readfirstlane(id / p.Hkv);
   const int row_tile = __builtin_amdgcn_readfirstlane(id % p.n_row_tiles);
   int c = __builtin_amdgcn_readfirstlane(id / p.n_row_tiles);
-  int b = 0, P = 0, n_chunks = 1, k_begin, k_end;
-  if (p.n_inline) {
-    // few requests: everything comes from the kernel arguments (indexed with constants only, so that it stays in
-    // scalar registers), no load and no division
-    int q = 0, r = 0;
-    uint32_t inv = 0;
-    bool found = false;
-#pragma unroll
-    for (int i = 0; i < kMaxInlineLens; ++i) {
-      if (!found && i < p.B) {
-        if (c < p.req[i].n || i == p.B - 1) {
-          b = i, P = p.req[i].P, n_chunks = p.req[i].n, q = p.req[i].q, r = p.req[i].r, inv = p.req[i].inv;
-          found = true;
-        } else {
-          c -= p.req[i].n;
-        }
-      }
-    }
-    c = n_chunks - 1 - c;  // the last chunk (it also carries the private tiles) is dispatched first
-    // attn_chunk_range with floor(c * (q*n + r) / n) = c*q + floor(c*r / n) and the quotient by multiply-shift
-    const int T = (P + 63) >> 6;
-    const int t0 = min(T, c * q + (int)__umulhi((uint32_t)(c * r), inv));
-    const int t1 = c == n_chunks - 1 ? T : min(T, (c + 1) * q + (int)__umulhi((uint32_t)((c + 1) * r), inv));
-    k_begin = t0 * 64;
-    k_end = min(P, t1 * 64);
-  } else {
-    for (; b < p.B - 1; ++b) {
-      const int nc = attn_num_chunks(p.prefix_lens[b], p.chunk_len);
-      if (c < nc) break;
-      c -= nc;
-    }
-    P = p.prefix_lens[b];
-    n_chunks = attn_num_chunks(P, p.chunk_len);
-    c = n_chunks - 1 - c;
-    attn_chunk_range(P, p.chunk_len, p.last_short, c, &k_begin, &k_end);
-  }
+  const ChunkSel sel = attn_select_chunk(p, c);
+  const int b = sel.b, n_chunks = sel.n_chunks, k_begin = sel.k_begin, k_end = sel.k_end;
+  c = sel.c;
   const int n_pre_tiles = (k_end - k_begin + kTileN - 1) / kTileN;
   const int n_pre_steps = (n_pre_tiles + KSL - 1) / KSL;
   const int n_full_steps = (k_end - k_begin) / (KSL * kTileN);  // steps all of whose keys exist
@@ -508,6 +496,301 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnPara
   }
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// bf16 cache and branch K/V: the same pipeline without any conversion.  K fragments are 16-byte LDS reads (the
+// contraction runs over d, MFMA step t takes d = 16t + 8lh .. +8 of key ln), V^T fragments two transposing reads
+// (ds_read_b64_tr_b16: four keys of one head-dim column each).  Used with many rows per KV head (256-row or
+// 128-row workgroups), where it replaces the register-staged row-tile kernel: no staging instructions at all, no
+// vector memory wait inside the loop.  Q lives in registers (loaded before the stream starts).
+//   koff0         lane's byte offset for piece lh of key ln (key block 0; block 1 is 32 rows on)
+//   voff[a][db]   lane's byte offset for the transposing read of keys 8a + 4lh .. +4 of head-dim block db (key group 0
+//                 of key block 0; the others 16 / 32 rows on)
+template <int MASK>
+__device__ __forceinline__ void stream_tile16(const uint8_t *kt, RowState<1> &st, int koff0,
+                                              const int (&voff)[2][4], int lh, int first, int limit) {
+  using G = Geo<false>;
+  const uint8_t *vt = kt + G::kHalf;
+  constexpr bool kFastable = MASK == MASK_NONE;
+  float binit[1] = {kFastable ? st.base[0] : 0.f};
+  auto pv = [&](int kb, const uint32_t (&pb)[1][8]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2) {
+      const u32x4 pw = {pb[0][4 * t2], pb[0][4 * t2 + 1], pb[0][4 * t2 + 2], pb[0][4 * t2 + 3]};
+      const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
+      u32x2 lo[4], hi[4];
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        const uint8_t *at = vt + (kb * 32 + t2 * 16) * G::kRow;
+        lo[db] = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LA_LDS i16x4 *)(at + voff[0][db])));
+        hi[db] = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LA_LDS i16x4 *)(at + voff[1][db])));
+      }
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        const u32x4 vw = {lo[db][0], lo[db][1], hi[db][0], hi[db][1]};
+        st.o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vw), pf, st.o[db][0], 0, 0, 0);
+      }
+    }
+  };
+  auto exp_offset = [&](float (&off)[1]) __attribute__((always_inline)) {
+    off[0] = binit[0] - ((st.m_run[0] == -INFINITY) ? 0.f : st.m_run[0]);
+  };
+
+  f32x16 s0[1], s1[1];
+  uint32_t p0[1][8], p1[1][8];
+  float sum0[1], sum1[1], mt[1], alpha[1], off[1];
+  {
+    const float nb = kFastable ? -st.base[0] : 0.f;
+    s0[0] = f32x16{nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb};
+    s1[0] = s0[0];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const int ko = koff0 ^ (32 * t);  // piece 2t + lh under the swizzle: the swizzle is an exclusive or
+      const bf16x8 k0 = *(const bf16x8 *)(kt + ko);
+      const bf16x8 k1 = *(const bf16x8 *)(kt + 32 * G::kRow + ko);
+      s0[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, st.qf[0][t], s0[0], 0, 0, 0);
+      s1[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, st.qf[0][t], s1[0], 0, 0, 0);
+    }
+  }
+  mask_block<1, MASK>(s0, st, 0, lh, first, limit);
+  if constexpr (kFastable) block_probs<1, true>(s0, 1.f, off, p0, sum0);
+  block_max<1>(s0, 1.f, binit, mt);
+  const bool raise0 = raise_max<1>(mt, st, alpha);
+  if (!kFastable || raise0) {
+    if (raise0) rescale<1>(st, alpha);
+    exp_offset(off);
+    block_probs<1, false>(s0, 1.f, off, p0, sum0);
+  }
+  st.l_run[0] += sum0[0];
+  pv(0, p0);
+  __builtin_amdgcn_sched_barrier(0);
+  mask_block<1, MASK>(s1, st, 1, lh, first, limit);
+  if constexpr (kFastable) block_probs<1, true>(s1, 1.f, off, p1, sum1);
+  block_max<1>(s1, 1.f, binit, mt);
+  const bool raise1 = raise_max<1>(mt, st, alpha);  // the accumulators now hold block 0 in the old units
+  if (!kFastable || raise0 || raise1) {  // after a raise in block 0, S1 is no longer relative to the maximum
+    if (raise1) rescale<1>(st, alpha);
+    exp_offset(off);
+    block_probs<1, false>(s1, 1.f, off, p1, sum1);
+  }
+  if (raise0 || raise1) st.base[0] = (st.m_run[0] == -INFINITY) ? 0.f : st.m_run[0];  // base == running maximum
+  st.l_run[0] += sum1[0];
+  pv(1, p1);
+}
+
+template <int NRB>
+struct Stream16Shape {
+  using G = Geo<false>;
+  static constexpr int KSL = kWaves / NRB;
+  static constexpr int kSlots = 4;                   // 128 KiB of ring
+  static constexpr int NST = kSlots / KSL;
+  static constexpr int IPW = 2 * G::kLoadsPerHalf * KSL / kWaves;
+  static constexpr int kBlkOff = kSlots * G::kTile;
+  static constexpr int kLdsMax = kBlkOff + kMaxBlkLds * 4;
+  static constexpr int kFoldBytes = kWaves * 66 * 64 * 4;
+  static_assert(NST >= 2 && kLdsMax <= 160 * 1024 && kFoldBytes <= kLdsMax, "LDS of one CU");
+};
+
+template <int NRB>
+__global__ __launch_bounds__(64 * kWaves) void attn_stream16_kernel(const AttnParams p) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  using S = Stream16Shape<NRB>;
+  using G = Geo<false>;
+  constexpr int KSL = S::KSL, NST = S::NST, IPW = S::IPW;
+  constexpr int NT = 64 * kWaves;
+  constexpr int kTileM = 32 * NRB;
+  constexpr int kStepBytes = KSL * G::kTile;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ln = lane & 31, lh = lane >> 5;
+  const int rb = wave % NRB, ks = wave / NRB;
+
+  int id = blockIdx.x;
+  const int kvh = __builtin_amdgcn_readfirstlane(id % p.Hkv);
+  id = __builtin_amdgcn_readfirstlane(id / p.Hkv);
+  const int row_tile = __builtin_amdgcn_readfirstlane(id % p.n_row_tiles);
+  const ChunkSel sel = attn_select_chunk(p, __builtin_amdgcn_readfirstlane(id / p.n_row_tiles));
+  const int b = sel.b, n_chunks = sel.n_chunks, c = sel.c, k_begin = sel.k_begin, k_end = sel.k_end;
+  const int n_pre_tiles = (k_end - k_begin + kTileN - 1) / kTileN;
+  const int n_pre_steps = (n_pre_tiles + KSL - 1) / KSL;
+  const int n_full_steps = (k_end - k_begin) / (KSL * kTileN);
+
+  const int r0 = row_tile * kTileM;
+  const int r1 = min(p.R, r0 + kTileM);
+  const int gl = p.gamma * p.L;
+  const int t_lo = __builtin_amdgcn_readfirstlane(r0 / p.G), t_hi = __builtin_amdgcn_readfirstlane((r1 - 1) / p.G);
+  const int tk0 = __builtin_amdgcn_readfirstlane((t_lo / p.L) * p.L);
+  const int n_priv = (c == n_chunks - 1) ? (t_hi - tk0 + 1 + kTileN - 1) / kTileN : 0;
+  const int n_steps = n_pre_steps + (n_priv + KSL - 1) / KSL;
+
+  // ---- Q -> registers (before the stream starts, so that the only vector memory operations in flight later are
+  //      the direct loads the kernel counts itself), times the score scale in log2 units, rounded to bf16 again
+  RowState<1> st;
+  const int row = r0 + rb * 32 + ln;
+  {
+    const int rr = min(row, p.R - 1);
+    st.row_tok[0] = rr / p.G;
+    st.row_bstart[0] = (st.row_tok[0] / p.L) * p.L;
+    const uint8_t *qrow =
+        (const uint8_t *)p.q + (((size_t)b * gl + st.row_tok[0]) * p.Hq + kvh * p.G + (rr % p.G)) * (size_t)(kD * 2);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      u32x4 v = *(const u32x4 *)(qrow + (16 * t + 8 * lh) * 2);
+      if (row >= p.R) v = u32x4{0, 0, 0, 0};
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const uint32_t word = v[w];
+        const uint32_t wl = word << 16, wh = word & 0xffff0000u;
+        v[w] = pack_bf16(__builtin_bit_cast(float, wl) * p.scale_log2, __builtin_bit_cast(float, wh) * p.scale_log2);
+      }
+      st.qf[0][t] = __builtin_bit_cast(bf16x8, v);
+    }
+    st.m_run[0] = -INFINITY, st.l_run[0] = 0.f, st.base[0] = 0.f;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) st.o[db][0][j] = 0.f;
+  }
+
+  // ---- physical block ids of this chunk -> LDS (paged caches only) ------------------------------
+  int32_t *blk_lds = (int32_t *)(lds + S::kBlkOff);
+  const int first_lb = k_begin >> p.block_shift;
+  const int32_t *table = p.block_tables ? p.block_tables + (size_t)b * p.max_blocks : nullptr;
+  if (table && k_end > k_begin) {
+    const int n_blk = ((k_end - 1) >> p.block_shift) - first_lb + 1;  // <= kMaxBlkLds (host guarantees)
+    for (int i = tid; i < n_blk; i += NT) blk_lds[i] = table[first_lb + i];
+  }
+  __syncthreads();  // (also: every wavefront holds its Q, nothing else is in flight)
+  const uint32_t lds0 = (uint32_t)(size_t)(LA_LDS uint8_t *)lds;
+
+  const size_t br_off = ((size_t)b * gl * p.Hkv + kvh) * G::kRow;
+  StreamLoader<KSL, NST, IPW, false> ld;
+  ld.ring = lds0, ld.wave = wave;
+  ld.blk = table ? blk_lds : nullptr;
+  ld.first_lb = first_lb, ld.ident = b * p.max_blocks, ld.shift = p.block_shift, ld.bs_mask = p.block_size - 1;
+  ld.blk_stride = (uint32_t)((p.Hkv << p.block_shift) * G::kRow), ld.br_stride = (uint32_t)(p.Hkv * G::kRow);
+  ld.k_pre = (const uint8_t *)p.k_cache + ((size_t)kvh << p.block_shift) * G::kRow;
+  ld.v_pre = (const uint8_t *)p.v_cache + ((size_t)kvh << p.block_shift) * G::kRow;
+  ld.k_br = (const uint8_t *)p.k_branch + br_off;
+  ld.v_br = (const uint8_t *)p.v_branch + br_off;
+  ld.init_lane(lane);
+  auto issue = [&](int step) __attribute__((always_inline)) {
+    const int slot = step % NST;
+    if (step < n_full_steps)
+      ld.template issue<true, false>(slot, k_begin + step * (KSL * kTileN), 0);
+    else if (step < n_pre_steps)
+      ld.template issue<true, true>(slot, k_begin + step * (KSL * kTileN), k_end - 1);
+    else
+      ld.template issue<false, true>(slot, tk0 + (step - n_pre_steps) * (KSL * kTileN), t_hi);
+  };
+  for (int s = 0; s < NST - 1; ++s)
+    if (s < n_steps) issue(s);
+
+  int koff0, voff[2][4];
+  {
+    koff0 = ln * G::kRow + ((lh ^ swz_16(ln)) * 16);  // keys ln and 32 + ln share the swizzle
+    // transposing read: the 16 lanes of a group address four keys x four 8-byte pieces (two neighbouring 16-byte
+    // slots); lane i of the group then holds column i of those four keys
+    const int grp = lane >> 4, a = lane & 15, j = a >> 2, cc = a & 3;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int keyl = 8 * half + 4 * (grp >> 1) + j;
+      const int sv = swz_16(keyl);
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+        voff[half][db] = keyl * G::kRow + (((4 * db + 2 * (grp & 1) + (cc >> 1)) ^ sv) * 16) + 8 * (cc & 1);
+    }
+  }
+
+  const bool active = r0 + rb * 32 < p.R;
+  for (int step = 0; step < n_steps; ++step) {
+    wait_later<IPW, NST - 2>(min(n_steps - 1, step + NST - 2) - step);
+    __builtin_amdgcn_s_barrier();
+    if (step + NST - 1 < n_steps) issue(step + NST - 1);
+    if (!active) continue;
+    const uint8_t *kt = lds + (step % NST) * kStepBytes + ks * G::kTile;
+    if (step < n_pre_steps) {
+      const int first = k_begin + (step * KSL + ks) * kTileN;
+      if (first + kTileN <= k_end)
+        stream_tile16<MASK_NONE>(kt, st, koff0, voff, lh, 0, 0);
+      else if (first < k_end)
+        stream_tile16<MASK_TAIL>(kt, st, koff0, voff, lh, first, k_end);
+    } else {
+      const int first = tk0 + ((step - n_pre_steps) * KSL + ks) * kTileN;
+      if (first <= t_hi) stream_tile16<MASK_BRANCH>(kt, st, koff0, voff, lh, first, 0);
+    }
+  }
+  wait_vmcnt<0>();  // no direct load may still be on its way to LDS when the workgroup gives its LDS back
+
+  // ---- the partial: one key slice per row block writes its registers, two are folded through LDS first ---------
+  const size_t slot = (size_t)b * p.s_max + c;
+  const size_t out_row = slot * p.n_rows + (size_t)st.row_tok[0] * p.Hq + kvh * p.G + (row % p.G);
+  float *po = p.part_o + out_row * kD;
+  if constexpr (KSL > 1) {
+    __builtin_amdgcn_s_barrier();
+    float *fold = (float *)lds;
+    if (ks > 0) {
+      float *dst = fold + (size_t)((ks - 1) * NRB + rb) * 66 * 64 + lane;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) dst[(db * 16 + j) * 64] = st.o[db][0][j];
+      dst[64 * 64] = st.m_run[0];
+      dst[65 * 64] = st.l_run[0];
+    }
+    __syncthreads();
+    if (ks > 0) return;
+#pragma unroll 1
+    for (int s = 1; s < KSL; ++s) {
+      const float *src = fold + (size_t)((s - 1) * NRB + rb) * 66 * 64 + lane;
+      const float m2 = src[64 * 64], l2 = src[65 * 64];
+      const float m_new = fmaxf(st.m_run[0], m2);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float a1 = __builtin_amdgcn_exp2f(st.m_run[0] - m_use);
+      const float a2 = __builtin_amdgcn_exp2f(m2 - m_use);
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) st.o[db][0][j] = st.o[db][0][j] * a1 + src[(db * 16 + j) * 64] * a2;
+      st.l_run[0] = st.l_run[0] * a1 + l2 * a2;
+      st.m_run[0] = m_new;
+    }
+  }
+  const float l_tot = xhalf_sum(st.l_run[0]);
+  if (row < p.R) {
+    // accumulator register j of d block db is head-dim column 32*db + 8*(j/4) + 4*lh + j%4
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const f32x4 v = {st.o[db][0][4 * q], st.o[db][0][4 * q + 1], st.o[db][0][4 * q + 2], st.o[db][0][4 * q + 3]};
+        *(f32x4 *)(po + 32 * db + 8 * q + 4 * lh) = v;
+      }
+    if (lh == 0) {
+      const f32x2 ml = {st.m_run[0], l_tot};
+      *(f32x2 *)(p.part_ml + out_row * 2) = ml;
+    }
+  }
+}
+
+template <int NRB>
+hipError_t launch_stream16_variant(const AttnParams &p, hipStream_t stream) {
+  using S = Stream16Shape<NRB>;
+  const int grid = p.Hkv * p.n_row_tiles * p.total_units;
+  auto kern = attn_stream16_kernel<NRB>;
+  const int blk_entries =
+      p.block_tables ? (attn_max_chunk_tokens(p.chunk_len, p.last_short) >> p.block_shift) + 2 : 0;
+  if (blk_entries > kMaxBlkLds) return hipErrorInvalidValue;
+  const int lds_bytes = S::kBlkOff + blk_entries * 4 > S::kFoldBytes ? S::kBlkOff + blk_entries * 4 : S::kFoldBytes;
+  static std::once_flag once;
+  static hipError_t configured = hipSuccess;
+  std::call_once(once, [&] {
+    configured = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::kLdsMax);
+  });
+  if (configured != hipSuccess) return configured;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * kWaves), lds_bytes, stream, p);
+  return hipGetLastError();
+}
+
 template <int NRB>
 hipError_t launch_stream_variant(const AttnParams &p, hipStream_t stream) {
   using S = StreamShape<NRB>;
@@ -527,9 +810,9 @@ hipError_t launch_stream_variant(const AttnParams &p, hipStream_t stream) {
   return hipGetLastError();
 }
 
-// row blocks per workgroup of the shapes
-constexpr int kStreamNrb[] = {2, 4, 8};
-constexpr int kNumStreamShapes = 3;
+// row blocks per workgroup of the shapes: three for an fp8 cache, then two for a bf16 cache
+constexpr int kStreamNrb[] = {2, 4, 8, 8, 4};
+constexpr int kNumStreamShapes = 5;
 
 }  // namespace
 
@@ -537,6 +820,7 @@ int attn_stream_num_shapes() { return kNumStreamShapes; }
 int attn_stream_tile_m(int shape) { return 32 * kStreamNrb[shape]; }
 int attn_stream_step_keys(int shape) { return kTileN * kWaves / kStreamNrb[shape]; }
 int attn_stream_max_chunk_blocks() { return kMaxBlkLds; }
+bool attn_stream_shape_is_fp8(int shape) { return shape < 3; }
 
 hipError_t launch_attn_stream(const AttnParams &p, int shape, hipStream_t stream) {
   ProfileScope scope(SLOT_ATTN_MFMA, stream);
@@ -544,6 +828,8 @@ hipError_t launch_attn_stream(const AttnParams &p, int shape, hipStream_t stream
     case 0: return launch_stream_variant<2>(p, stream);
     case 1: return launch_stream_variant<4>(p, stream);
     case 2: return launch_stream_variant<8>(p, stream);
+    case 3: return launch_stream16_variant<8>(p, stream);
+    case 4: return launch_stream16_variant<4>(p, stream);
   }
   return hipErrorInvalidValue;
 }

@@ -113,6 +113,7 @@ int attn_stream_num_shapes();
 int attn_stream_tile_m(int shape);
 int attn_stream_step_keys(int shape);  // keys a workgroup advances per pipeline step
 int attn_stream_max_chunk_blocks();
+bool attn_stream_shape_is_fp8(int shape);  // else: bf16 cache and branch K/V
 hipError_t launch_attn_stream(const AttnParams &p, int shape, hipStream_t stream);
 hipError_t launch_attn_merge(const AttnParams &p, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnParams &p, hipStream_t stream);

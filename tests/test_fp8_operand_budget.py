@@ -1,0 +1,58 @@
+"""Why the MFMA operands are bf16 although the cache is fp8 (CPU only, numpy emulation).
+
+The fp8 MFMA instructions of gfx950 take both operands in fp8, so using them on Q K^T or on P V means rounding Q
+(scaled per row) or the probabilities P to e4m3 -- three mantissa bits.  On inputs shaped like the benchmark's
+(K, V, Q ~ N(0, 1), scores ~ N(0, 1), long prefixes) an output element is a weighted mean of thousands of unit-variance
+values, i.e. small against its inputs, and the operand rounding noise is averaged by the same factor: the error of a
+row relative to its largest element is then about the relative rounding error of one operand, whatever the prefix
+length.  This test measures that on an emulation of the kernel's arithmetic (exact fp8 cache, fp64 accumulation, the
+operand rounded as the MFMA would see it): bf16 operands stay far inside the benchmark's 2e-2 bound, an fp8 operand on
+either contraction breaks it.  It documents the decision; it does not touch the library."""
+import numpy as np
+
+
+def _e4m3(x):
+    """Round to the nearest e4m3fn value (normals and subnormals, saturating at 448)."""
+    a = np.abs(x)
+    e = np.clip(np.floor(np.log2(np.maximum(a, 1e-300))), -6, 8)
+    step = 2.0 ** (e - 3)
+    return np.sign(x) * np.minimum(np.round(a / step) * step, 448.0)
+
+
+def _bf16(x):
+    u = np.asarray(x, dtype=np.float32).view(np.uint32)
+    u = ((u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000).astype(np.uint32)
+    return u.view(np.float32).astype(np.float64)
+
+
+def _row_errors(q_round, p_round, seed=0, D=128, P=8192, R=256):
+    rng = np.random.default_rng(seed)
+    q = _bf16(rng.standard_normal((R, D)))
+    k, v = rng.standard_normal((P, D)), rng.standard_normal((P, D))
+    ks, vs = np.abs(k).max() / 448, np.abs(v).max() / 448
+    k8, v8 = _e4m3(k / ks) * ks, _e4m3(v / vs) * vs          # the cache as stored: the same bytes on both sides
+    c = D ** -0.5
+    s = (q @ k8.T) * c
+    p = np.exp(s - s.max(1, keepdims=True))
+    ref = (p @ v8) / p.sum(1, keepdims=True)
+    qs = q * c
+    if q_round == "bf16":
+        qq = _bf16(qs)
+    else:                                                    # per-row power-of-two scale, as the scaled MFMA allows
+        sc = 2.0 ** np.ceil(np.log2(np.abs(qs).max(1, keepdims=True) / 448))
+        qq = _e4m3(qs / sc) * sc
+    s = qq @ k8.T
+    p = np.exp(s - s.max(1, keepdims=True))
+    pr = _bf16(p) if p_round == "bf16" else _e4m3(p * 256) / 256
+    out = (pr @ v8) / p.sum(1, keepdims=True)
+    return np.abs(out - ref).max(1) / np.abs(ref).max(1)
+
+
+def test_bf16_operands_keep_the_bound_fp8_operands_break_it():
+    tol = 2e-2
+    both_bf16 = _row_errors("bf16", "bf16")
+    assert both_bf16.max() < tol / 3                     # observed 4e-3: the margin the real kernel works with
+    for q_round, p_round in (("fp8", "bf16"), ("bf16", "fp8"), ("fp8", "fp8")):
+        e = _row_errors(q_round, p_round)
+        print(f"Q {q_round} P {p_round}: max row error {e.max():.4f}, mean {e.mean():.4f}")
+        assert e.mean() > tol and e.max() > 2 * tol      # observed mean 2.7e-2 .. 3.8e-2, max 4.4e-2 .. 6.2e-2

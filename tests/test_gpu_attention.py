@@ -117,11 +117,37 @@ def test_every_streaming_shape(oracle, case, shape, monkeypatch):
         check_full(oracle, case, TOL_LOWP, kv_split_tokens=split)
 
 
+def _as_bf16(case, name):
+    import dataclasses
+    return dataclasses.replace(case, name=name, kv_dtype="bf16", branch_kv_dtype="bf16")
+
+
+STREAM16_CASES = [_as_bf16(c, c.name.replace("fp8_", "bf16_")) for c in STREAM_CASES] + [
+    # many rows per KV head (what these shapes are for): R = 8*16*4 = 512 spans two 256-row workgroups, ragged
+    W.AttnCase("bf16_stream_rows512", (1500, 300), 8, 16, 8, 2, 128, "bf16", "bf16", "bf16", "bf16", paged=True,
+               seed=77),
+]
+
+
+@pytest.mark.parametrize("shape", [5, 6])
+@pytest.mark.parametrize("case", STREAM16_CASES, ids=lambda c: c.name)
+def test_every_bf16_streaming_shape(oracle, case, shape, monkeypatch):
+    """The streaming shapes for a bf16 cache (no conversion anywhere; transposing 16-bit LDS reads), forced."""
+    monkeypatch.setattr("gpu_util.KERNEL_SHAPE", shape + 1)
+    for split in (0, 64, 192, 320, 1024):
+        check_full(oracle, case, TOL_LOWP, kv_split_tokens=split)
+
+
 def test_streaming_shape_is_refused_where_it_cannot_run(monkeypatch):
     from gpu_util import run_attention
     from paper_2506_19830_amd import binding as B
     monkeypatch.setattr("gpu_util.KERNEL_SHAPE", 3)
-    case = MFMA_CASES[0]                                    # bf16 cache: no streaming shape
+    case = MFMA_CASES[0]                                    # bf16 cache: no fp8 streaming shape
+    with pytest.raises(B.LaError) as e:
+        run_attention(case, W.make_attention_inputs(case))
+    assert e.value.status == 2
+    monkeypatch.setattr("gpu_util.KERNEL_SHAPE", 6)
+    case = STREAM_CASES[0]                                  # fp8 cache: no bf16 streaming shape
     with pytest.raises(B.LaError) as e:
         run_attention(case, W.make_attention_inputs(case))
     assert e.value.status == 2
@@ -182,11 +208,17 @@ def test_nested_every_kernel_shape(oracle, shape, monkeypatch):
             check_nested(oracle, case, chain_len, TOL_LOWP, None if vis is None else np.array(vis), split)
 
 
+@pytest.mark.parametrize("shape", [1, 2])
 @pytest.mark.parametrize("case", [NESTED_CASES[0][0], NESTED_CASES[3][0]], ids=lambda c: c.name)
-def test_nested_with_nothing_visible_is_the_flat_call_bit_for_bit(case):
+def test_nested_with_nothing_visible_is_the_flat_call_bit_for_bit(case, shape, monkeypatch):
     """A chain no branch sees (all of chain_vis zero), and an empty chain, must reproduce la_verify_attention
-    exactly: no tile of the chain is touched."""
+    exactly when both run the same kernel shape (the flat call alone may also choose a streaming shape): no tile of
+    the chain is touched."""
     from gpu_util import run_attention, run_attention_nested
+    if case.kv_dtype != "f32":
+        monkeypatch.setattr("gpu_util.KERNEL_SHAPE", shape)
+    elif shape != 1:
+        pytest.skip("one fp32 kernel")
     inp = W.make_attention_inputs(case)
     flat, flat_lse = run_attention(case, inp)
     chain = W.make_chain_inputs(case, 40, inp, np.zeros((case.B, case.gamma), dtype=np.int32))
@@ -286,12 +318,13 @@ def test_tree_whose_masks_are_leading_parts_equals_the_nested_call():
     assert np.array_equal(a, b) and np.array_equal(la, lb)
 
 
-def test_tree_with_empty_masks_is_the_flat_call():
-    """MFMA path: pool tiles nobody sees are skipped, so the result is the flat call's bit for bit.  fp32 path: the
-    unseen tokens are walked with weight zero, which regroups the 64-key steps of the running softmax: equal up to
-    fp32 rounding."""
+def test_tree_with_empty_masks_is_the_flat_call(monkeypatch):
+    """MFMA path: pool tiles nobody sees are skipped, so the result is the flat call's bit for bit when both run the
+    same kernel shape (the flat call alone may also choose a streaming shape).  fp32 path: the unseen tokens are
+    walked with weight zero, which regroups the 64-key steps of the running softmax: equal up to fp32 rounding."""
     from gpu_util import row_errors, run_attention, run_attention_tree
     for case in (TREE_CASES[0][0], TREE_CASES[2][0]):
+        monkeypatch.setattr("gpu_util.KERNEL_SHAPE", 0 if case.kv_dtype == "f32" else 2)
         inp = W.make_attention_inputs(case)
         flat, flat_lse = run_attention(case, inp)
         tree = W.make_tree_inputs(case, 2, 2, 10, inp)
