@@ -24,6 +24,7 @@ sys.path.insert(0, str(ROOT))
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0
+CLOCK_GHZ = 2.4                  # MI355X peak engine clock
 
 
 def parse_args():
@@ -68,6 +69,10 @@ def parse_args():
                          "and prompt-lookup drafts (tokens only, no draft logits) instead of the configuration's plain "
                          "softmax over dense draft logits: qwen3 = temperature 0.6, top-p 0.95, top-k 20; r1 = "
                          "temperature 0.6, top-p 0.95")
+    ap.add_argument("--calibrate-issue", action="store_true",
+                    help="run the instruction-mix probe of the benchmark library instead (how fast one and two "
+                         "wavefronts per SIMD issue adds, exponentials, MFMAs and the attention kernels' mix of "
+                         "them); prints a small table and its own JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (three times) before the timed region, so that a counter "
                          "run can scale FETCH_SIZE / WRITE_SIZE by what they read for a kernel of known traffic")
@@ -316,10 +321,54 @@ def bench_planner(args):
     return 0
 
 
+ISSUE_MIXES = ["v_add_f32", "v_exp_f32", "v_cvt_pk_bf16_f32", "mfma 32x32x16 bf16, one operand pair",
+               "mfma, eight operand pairs", "mfma + 4 v_add_f32", "mfma + 8 v_add_f32",
+               "mfma + exp + (cvt_pk + 2 add)/2: the kernels' softmax share"]
+
+
+def bench_issue(args):
+    """Cycles per slot of the instruction-mix probe, at the clock the chip holds during each probe (unknown: the
+    figures assume CLOCK_GHZ, so a pure-MFMA slot reading above 32 cycles is the chip running below that clock)."""
+    import torch
+    B.select_library("bench")
+    torch.cuda.set_device(0)
+    sink = torch.empty(256 * 512, dtype=torch.float32, device="cuda")
+    iters = 20000
+    rows = []
+
+    def probe(mix, second, waves):
+        B.la_calibrate_issue(mix, second, waves, 256, 200, sink)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        B.la_calibrate_issue(mix, second, waves, 256, iters, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 * CLOCK_GHZ * 1e9 / (iters * 16.0)
+
+    for mix, name in enumerate(ISSUE_MIXES):
+        one, two = probe(mix, -1, 4), probe(mix, -1, 8)
+        rows.append({"mix": name, "cycles_per_slot_one_wavefront": round(one, 2),
+                     "cycles_per_slot_two_wavefronts": round(two, 2)})
+        print(f"{name:62s} 1 wavefront/SIMD {one:7.2f}   2 wavefronts/SIMD {two:7.2f} cycles per slot",
+              file=sys.stderr)
+    for second in (0, 1):
+        both = probe(3, second, 8)
+        rows.append({"mix": f"first wavefront mfma, second {ISSUE_MIXES[second]}",
+                     "cycles_per_slot_two_wavefronts": round(both, 2)})
+        print(f"first wavefront: mfma | second: {ISSUE_MIXES[second]:30s} {both:7.2f} cycles per slot",
+              file=sys.stderr)
+    print(json.dumps({"metric": "instruction-mix probe", "unit": f"cycles per slot at {CLOCK_GHZ} GHz", "n_gpus": 1,
+                      "iters": iters, "rows": rows}))
+    return 0
+
+
 def main():
     args = parse_args()
     if args.planner:
         return bench_planner(args)
+    if args.calibrate_issue:
+        return bench_issue(args)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
               file=sys.stderr)

@@ -31,6 +31,23 @@ extern "C" {
 LA_API la_status la_calibrate_mfma(int32_t workgroups, int32_t iters, float *sink, double *flops, void *hip_stream);
 LA_API la_status la_calibrate_read(const void *src, size_t bytes, uint32_t *sink, void *hip_stream);
 
+/* Instruction-mix probe: `workgroups` workgroups of `waves` (4 or 8: one or two
+ * per SIMD) wavefronts, each running `iters` rounds of a body of 16 slots of
+ * mix `mix`:
+ *   0 v_add_f32   1 v_exp_f32   2 v_cvt_pk_bf16_f32
+ *   3 v_mfma_f32_32x32x16_bf16 (four accumulators in turn, one operand pair)
+ *   4 the same with eight different operand register pairs
+ *   5 MFMA + 4 v_add_f32        6 MFMA + 8 v_add_f32
+ *   7 MFMA + v_exp_f32 + (every other slot) v_cvt_pk_bf16_f32 + 2 v_add_f32,
+ *     the softmax share of one MFMA in the attention kernels.
+ * mix_second >= 0 (only with waves == 8, and only 3 with 0 or 1): the second
+ * wavefront of every SIMD runs that mix instead.  Time the launch with events
+ * of your own: duration x clock / (iters x 16) is cycles per slot.  sink: dev,
+ * workgroups * 512 floats, written.  Only enqueues a kernel.
+ * LA_ERR_UNSUPPORTED for a pair of mixes that is not built. */
+LA_API la_status la_calibrate_issue(int32_t mix, int32_t mix_second, int32_t waves, int32_t workgroups,
+                                    int32_t iters, float *sink, void *hip_stream);
+
 /* ------------------------------------------------------------------------- *
  *  Self-test hook (not part of the verification path): out[i] = exp(y[i]) as
  *  the fp64 resampling path of la_spec_accept evaluates it (its own routine:

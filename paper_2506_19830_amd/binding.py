@@ -31,7 +31,7 @@ EXPORTED_SYMBOLS = (
 )
 # what libla_verify_bench.so exports on top of those (la_verify_bench.h)
 BENCH_SYMBOLS = (
-    "la_calibrate_mfma", "la_calibrate_read", "la_selftest_exp64", "la_profile_enable", "la_profile_select",
+    "la_calibrate_mfma", "la_calibrate_read", "la_calibrate_issue", "la_selftest_exp64", "la_profile_enable", "la_profile_select",
     "la_profile_collect", "la_profile_num_kernels", "la_profile_get", "la_profile_reset",
 )
 
@@ -145,6 +145,8 @@ def load(kind: Optional[str] = None) -> ctypes.CDLL:
         if kind == "bench":
             lib.la_calibrate_mfma.restype = ctypes.c_int
             lib.la_calibrate_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
+            lib.la_calibrate_issue.restype = ctypes.c_int
+            lib.la_calibrate_issue.argtypes = [ctypes.c_int32] * 5 + [vp, vp]
             lib.la_calibrate_read.restype = ctypes.c_int
             lib.la_calibrate_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
             lib.la_selftest_exp64.restype = ctypes.c_int
@@ -300,6 +302,13 @@ def la_calibrate_mfma(workgroups: int, iters: int, sink) -> float:
     if st:
         raise LaError(st, "la_calibrate_mfma")
     return flops.value
+
+
+def la_calibrate_issue(mix: int, mix_second: int, waves: int, workgroups: int, iters: int, sink) -> None:
+    """Enqueue the instruction-mix probe (see la_verify_bench.h); sink: workgroups * 512 floats."""
+    st = load("bench").la_calibrate_issue(mix, mix_second, waves, workgroups, iters, _ptr(sink), _stream())
+    if st:
+        raise LaError(st, "la_calibrate_issue")
 
 
 def la_calibrate_read(src, sink) -> int:

@@ -649,8 +649,9 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
   brs.first_lb = 0;
   brs.limit = t_hi + 1;
 
-  // two-stage shape: a wavefront whose rows all lie past R stages tiles but computes nothing
-  const bool active = STAGES >= 3 || r0 + wave * RB * 32 < p.R;
+  // a wavefront whose rows all lie past R stages tiles but computes nothing (two- and four-stage loops; the
+  // three-stage loop computes on every wavefront)
+  const bool active = STAGES == 3 || r0 + wave * RB * 32 < p.R;
 
   // Score scales of the two key segments, in log2 units.  Q is multiplied by the prefix scale when it is loaded
   // (and rounded to bf16 again), so prefix scores leave the MFMAs ready for the exponential; a branch segment with
@@ -720,15 +721,16 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
       PrefixLoader<KV_FP8, NT> loader;
       loader.init(p, pre, tid);
       auto gload = [&](int it) { loader.load(k_begin + it * kTileN, regs); };
+      TileRegs<KV_FP8, NT> regs2;
+      // the first tiles are requested together (one round trip to memory, not one per tile)
       gload(0);
+      if (n_full > 1) loader.load(k_begin + kTileN, regs2);
       tile_store<KV_FP8, NT>(lds, tid, regs);
-      if (n_full > 1) {
-        gload(1);
-        tile_store<KV_FP8, NT>(lds + kStageBytes, tid, regs);
-      }
+      if (n_full > 2) gload(2);  // stays in regs until the loop writes it
+      if (n_full > 1) tile_store<KV_FP8, NT>(lds + kStageBytes, tid, regs2);
       __syncthreads();
       PipeCarry cy;
-      {  // S^T of block 0 of tile 0, and the first fragments of slot A of tile 0
+      if (active) {  // S^T of block 0 of tile 0, and the first fragments of slot A of tile 0
         const uint8_t *krow = lds + ln * kKRow + lh * 16;
         const uint8_t *vrow = lds + kKTileBytes + ln * kVRow + lh * 16;
 #pragma unroll
@@ -750,7 +752,6 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
       // Staging beside the MFMAs: iteration i requests tile i+3 from global memory during its slot A (block ids from
       // LDS, then the K load, then the V loads) and writes tile i+2, requested an iteration earlier into the other
       // register set, to its stage during slot B; the loads have more than a tile time to arrive.
-      TileRegs<KV_FP8, NT> regs2;
       int ids[PrefixLoader<KV_FP8, NT>::kNK + PrefixLoader<KV_FP8, NT>::kNV];
       auto no_hook = [](int) {};
       constexpr int kLoads = PrefixLoader<KV_FP8, NT>::kNK + 4 * PrefixLoader<KV_FP8, NT>::kNV;  // per tile and thread
@@ -758,25 +759,28 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
       auto steady = [&](int it, TileRegs<KV_FP8, NT> &ld, const TileRegs<KV_FP8, NT> &stq) __attribute__((always_inline)) {
         const int first = k_begin + (it + 3) * kTileN;
         uint8_t *dst = lds + ((it + 2) & 3) * kStageBytes;
-        pipe_tile<true>(
-            stage(it > 0 ? it - 1 : 0), stage(it), stage(it + 1), cy, st, ln, lh,
-            [&](int i) __attribute__((always_inline)) {
-              if (i == 1) loader.fetch_ids(first, ids);
-              if (i == 6) loader.load_k(first, ids, ld);
-              if (i == 8) loader.load_v(first, ids, ld);
-            },
-            [&](int i) __attribute__((always_inline)) {
-              // the loads into stq are older than the kLoads loads into ld just issued; loads return in order
-              if (i == 6) {
-                __builtin_amdgcn_s_waitcnt((kLoads & 15) | ((kLoads >> 4) << 14) | 0x70 | 0xF00);  // vmcnt(kLoads)
-                tile_store_k<KV_FP8, NT>(dst, tid, stq);
-              }
-              if (i == 9) tile_store_v<KV_FP8, NT, 0>(dst, tid, stq);
-              if (i == 12) tile_store_v<KV_FP8, NT, 1>(dst, tid, stq);
-            });
+        auto hook_a = [&](int i) __attribute__((always_inline)) {
+          if (i == 1) loader.fetch_ids(first, ids);
+          if (i == 6) loader.load_k(first, ids, ld);
+          if (i == 8) loader.load_v(first, ids, ld);
+        };
+        auto hook_b = [&](int i) __attribute__((always_inline)) {
+          // the loads into stq are older than the kLoads loads into ld just issued; loads return in order
+          if (i == 6) {
+            __builtin_amdgcn_s_waitcnt((kLoads & 15) | ((kLoads >> 4) << 14) | 0x70 | 0xF00);  // vmcnt(kLoads)
+            tile_store_k<KV_FP8, NT>(dst, tid, stq);
+          }
+          if (i == 9) tile_store_v<KV_FP8, NT, 0>(dst, tid, stq);
+          if (i == 12) tile_store_v<KV_FP8, NT, 1>(dst, tid, stq);
+        };
+        if (active) {
+          pipe_tile<true>(stage(it > 0 ? it - 1 : 0), stage(it), stage(it + 1), cy, st, ln, lh, hook_a, hook_b);
+        } else {  // no rows: only the wavefront's share of the staging
+          hook_a(1), hook_a(6), hook_a(8);
+          hook_b(6), hook_b(9), hook_b(12);
+        }
         __syncthreads();
       };
-      if (n_full > 2) gload(2);  // into regs
       int it = 0;
       for (; it + 4 < n_full; it += 2) {  // steady state, two tiles per trip (the register sets alternate)
         steady(it, regs2, regs);
@@ -784,15 +788,16 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
       }
       // the last tiles that still have something to write (regs holds tile it+2), then the second to last tile
       for (; it + 1 < n_full; ++it) {
-        pipe_tile<true>(stage(it > 0 ? it - 1 : 0), stage(it), stage(it + 1), cy, st, ln, lh, no_hook, no_hook);
+        if (active)
+          pipe_tile<true>(stage(it > 0 ? it - 1 : 0), stage(it), stage(it + 1), cy, st, ln, lh, no_hook, no_hook);
         if (it + 2 < n_full) {
           tile_store<KV_FP8, NT>(lds + ((it + 2) & 3) * kStageBytes, tid, regs);
           if (it + 3 < n_full) gload(it + 3);
           __syncthreads();
         }
       }
-      pipe_tile<false>(stage(it > 0 ? it - 1 : 0), stage(it), stage(it), cy, st, ln, lh, no_hook, no_hook);
-      {  // drain: block 1 of the last tile into O
+      if (active) pipe_tile<false>(stage(it > 0 ? it - 1 : 0), stage(it), stage(it), cy, st, ln, lh, no_hook, no_hook);
+      if (active) {  // drain: block 1 of the last tile into O
         const uint8_t *vrow = stage(it) + kKTileBytes + ln * kVRow + lh * 16 + 64;
         const u32x4 pw0 = {cy.pq[0][0], cy.pq[0][1], cy.pq[0][2], cy.pq[0][3]};
         const u32x4 pw1 = {cy.pq[0][4], cy.pq[0][5], cy.pq[0][6], cy.pq[0][7]};

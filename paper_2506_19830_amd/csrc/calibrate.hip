@@ -1,6 +1,7 @@
-// Two calibration kernels for the benchmark (not part of the verification path): what this very chip reaches on a
+// Calibration kernels for the benchmark (not part of the verification path): what this very chip reaches on a
 // pure bf16 MFMA loop and on a pure streaming read, so that a roofline fraction can be quoted against the
-// achievable rate next to the published peak.
+// achievable rate next to the published peak; and an instruction-mix probe (la_calibrate_issue) that measures how
+// fast a wavefront, and two wavefronts sharing a SIMD, issue the instruction kinds the attention kernels are made of.
 #include "la_internal.hpp"
 #include "la_verify_bench.h"
 
@@ -56,6 +57,100 @@ __global__ __launch_bounds__(256) void calib_read_kernel(const u32x4 *src, size_
   if (w == 0x9e3779b9u) sink[0] = w;  // practically never: keeps the loads alive without a store on the real path
 }
 
+// ---- instruction-mix probe ------------------------------------------------------------------------------------------
+// 4 or 8 wavefronts per workgroup (one or two per SIMD), one workgroup per CU.  Every wavefront runs `iters` rounds of a
+// body of 16 slots; what a slot holds depends on the mix.  With 8 wavefronts the second wavefront of each SIMD
+// (wavefronts 4..7) may run another mix than the first.  No memory access besides one store per lane at the end.
+enum IssueMix {
+  MIX_ADD = 0,        // slot = v_add_f32
+  MIX_EXP,            // slot = v_exp_f32
+  MIX_CVT,            // slot = v_cvt_pk_bf16_f32
+  MIX_MFMA,           // slot = MFMA, four accumulators in turn, one pair of operand registers
+  MIX_MFMA_OPERANDS,  // slot = MFMA, four accumulators in turn, eight different operand register pairs
+  MIX_MFMA_ADD4,      // slot = MFMA + 4 v_add_f32
+  MIX_MFMA_ADD8,      // slot = MFMA + 8 v_add_f32
+  MIX_MFMA_SOFTMAX,   // slot = MFMA + v_exp_f32 + (every other slot) v_cvt_pk_bf16_f32 + 2 v_add_f32
+  MIX_COUNT
+};
+
+#define LA_REP8(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7)
+
+template <int MIX>
+__device__ __forceinline__ void issue_body(float (&x)[8], f32x16 (&acc)[4], const bf16x8 (&av)[8], const bf16x8 (&bv)[8]) {
+  if constexpr (MIX == MIX_ADD) {
+#define X(i) asm volatile("v_add_f32 %0, %0, %1" : "+v"(x[i]) : "v"(x[(i + 1) & 7]));
+    LA_REP8(X) LA_REP8(X)
+#undef X
+  } else if constexpr (MIX == MIX_EXP) {
+#define X(i) asm volatile("v_exp_f32 %0, %0" : "+v"(x[i]));
+    LA_REP8(X) LA_REP8(X)
+#undef X
+  } else if constexpr (MIX == MIX_CVT) {
+#define X(i) asm volatile("v_cvt_pk_bf16_f32 %0, %0, %1" : "+v"(x[i]) : "v"(x[(i + 1) & 7]));
+    LA_REP8(X) LA_REP8(X)
+#undef X
+  } else {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int r = MIX == MIX_MFMA ? 0 : (i & 7);
+      acc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[r], bv[(r + 3) & 7], acc[i & 3], 0, 0, 0);
+      asm volatile("" : "+v"(acc[i & 3]));
+      if constexpr (MIX == MIX_MFMA_ADD4 || MIX == MIX_MFMA_ADD8) {
+#define X(j) \
+  if (j < (MIX == MIX_MFMA_ADD4 ? 4 : 8)) asm volatile("v_add_f32 %0, %0, %1" : "+v"(x[j]) : "v"(x[(j + 1) & 7]));
+        LA_REP8(X)
+#undef X
+      }
+      if constexpr (MIX == MIX_MFMA_SOFTMAX) {
+        asm volatile("v_exp_f32 %0, %0" : "+v"(x[i & 1]));
+        if (i & 1) {
+          asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(x[2]) : "v"(x[0]), "v"(x[1]));
+          asm volatile("v_add_f32 %0, %1, %2" : "=v"(x[3]) : "v"(x[0]), "v"(x[1]));
+          asm volatile("v_add_f32 %0, %0, %1" : "+v"(x[4]) : "v"(x[3]));
+        }
+      }
+    }
+  }
+}
+
+template <int MIX_A, int MIX_B>
+__global__ __launch_bounds__(512) void calib_issue_kernel(float *sink, int iters) {
+  float x[8];
+  f32x16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) x[i] = -1.0f - (float)(threadIdx.x & 15) * 1e-3f - (float)i;
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[c][j] = 0.f;
+  bf16x8 av[8], bv[8];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      av[r][i] = (__bf16)(0.01f + 0.001f * (float)r);
+      bv[r][i] = (__bf16)(0.02f - 0.001f * (float)r);
+    }
+    asm volatile("" : "+v"(av[r]), "+v"(bv[r]));
+  }
+  if ((threadIdx.x >> 6) < 4) {
+    for (int it = 0; it < iters; ++it) issue_body<MIX_A>(x, acc, av, bv);
+  } else {
+    for (int it = 0; it < iters; ++it) issue_body<MIX_B>(x, acc, av, bv);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) s += x[i];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) s += acc[c][0] + acc[c][7];
+  sink[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
+}
+
+template <int A, int B>
+void launch_issue(int workgroups, int waves, int iters, float *sink, hipStream_t stream) {
+  hipLaunchKernelGGL((calib_issue_kernel<A, B>), dim3(workgroups), dim3(64 * waves), 0, stream, sink, iters);
+}
+
 }  // namespace
 }  // namespace la
 
@@ -70,6 +165,34 @@ la_status la_calibrate_mfma(int32_t workgroups, int32_t iters, float *sink, doub
     hipLaunchKernelGGL(calib_mfma_kernel, dim3(workgroups), dim3(512), 0, (hipStream_t)hip_stream, sink, iters);
   }
   *flops = (double)workgroups * 8 * kCalibChains * (double)iters * 2.0 * 32 * 32 * 16;
+  return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
+la_status la_calibrate_issue(int32_t mix, int32_t mix_second, int32_t waves, int32_t workgroups, int32_t iters,
+                             float *sink, void *hip_stream) {
+  if (mix < 0 || mix >= MIX_COUNT || (waves != 4 && waves != 8) || workgroups < 1 || workgroups > (1 << 20) ||
+      iters < 1 || !sink)
+    return LA_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (mix_second < 0) mix_second = mix;
+  if (mix_second == mix) {
+    switch (mix) {
+      case MIX_ADD: launch_issue<MIX_ADD, MIX_ADD>(workgroups, waves, iters, sink, st); break;
+      case MIX_EXP: launch_issue<MIX_EXP, MIX_EXP>(workgroups, waves, iters, sink, st); break;
+      case MIX_CVT: launch_issue<MIX_CVT, MIX_CVT>(workgroups, waves, iters, sink, st); break;
+      case MIX_MFMA: launch_issue<MIX_MFMA, MIX_MFMA>(workgroups, waves, iters, sink, st); break;
+      case MIX_MFMA_OPERANDS: launch_issue<MIX_MFMA_OPERANDS, MIX_MFMA_OPERANDS>(workgroups, waves, iters, sink, st); break;
+      case MIX_MFMA_ADD4: launch_issue<MIX_MFMA_ADD4, MIX_MFMA_ADD4>(workgroups, waves, iters, sink, st); break;
+      case MIX_MFMA_ADD8: launch_issue<MIX_MFMA_ADD8, MIX_MFMA_ADD8>(workgroups, waves, iters, sink, st); break;
+      case MIX_MFMA_SOFTMAX: launch_issue<MIX_MFMA_SOFTMAX, MIX_MFMA_SOFTMAX>(workgroups, waves, iters, sink, st); break;
+    }
+  } else if (mix == MIX_MFMA && mix_second == MIX_ADD && waves == 8) {
+    launch_issue<MIX_MFMA, MIX_ADD>(workgroups, waves, iters, sink, st);
+  } else if (mix == MIX_MFMA && mix_second == MIX_EXP && waves == 8) {
+    launch_issue<MIX_MFMA, MIX_EXP>(workgroups, waves, iters, sink, st);
+  } else {
+    return LA_ERR_UNSUPPORTED;
+  }
   return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }
 
