@@ -330,6 +330,9 @@ def bench_issue(args):
     """Cycles per slot of the instruction-mix probe, at the clock the chip holds during each probe (unknown: the
     figures assume CLOCK_GHZ, so a pure-MFMA slot reading above 32 cycles is the chip running below that clock)."""
     import torch
+
+    from paper_2506_19830_amd import binding as B
+
     B.select_library("bench")
     torch.cuda.set_device(0)
     sink = torch.empty(256 * 512, dtype=torch.float32, device="cuda")
@@ -576,7 +579,8 @@ def main():
     hbm_bound = flops / alg_bytes < PEAK_BF16_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
     traffic, traffic_source = read_traffic(f"attn_mfma_config{args.config}_traffic.txt") \
         if (args.branch_len is None and args.gamma is None and C == 0 and tree is None) else (None, "no summary for this variant")
-    kernel_name = "attn_stream_kernel" if plan["kernel_shape"] >= 3 else "attn_mfma_kernel"
+    kernel_name = ("attn_mfma_kernel" if plan["kernel_shape"] < 3 else
+                   "attn_stream_kernel" if plan["kernel_shape"] < 6 else "attn_stream16_kernel")
     attn_ms = sum(prof_all[k][1] for k in ("attn_mfma", "attn_merge"))
     accept_ms = sum(prof_all[k][1] for k in ("accept_stats", "accept_warp", "accept_decide", "accept_resid",
                                              "accept_pick") if k in prof_all)
