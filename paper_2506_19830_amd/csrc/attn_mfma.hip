@@ -18,8 +18,10 @@
 //   O^T += V^T P^T   A = V^T from LDS (stored transposed, keys permuted inside groups
 //                    of 16 so that the accumulator registers of S^T are already the
 //                    B operand; row 32*db + m of the LDS tile holds head-dim column
-//                    4*m + db, which makes the transposing LDS writes bank-conflict
-//                    free and the four db accumulators of a lane adjacent columns),
+//                    4*m + db, so that consecutive lanes of the transposing writes hit
+//                    consecutive rows and the four db accumulators of a lane are
+//                    adjacent columns; the fragment reads are bank-conflict free, the
+//                    8-byte writes are four-way conflicted at the 144-byte row pitch),
 //                    B = P^T (registers, bf16)
 // Everything is kept in log2 units: p = 2^(s*c - m).
 #include <mutex>

@@ -485,7 +485,11 @@ def test_very_long_ragged_paged_prefix_on_sampled_rows(oracle, monkeypatch):
         print(f"long prefix: shape {shape} split {split}", flush=True)
         got, lse = run_attention(case, inp, split, dev=dev)
         err = row_errors(got.reshape(-1, case.D)[ids], ref)
-        assert err.max() <= TOL_LOWP, f"max row error {err.max():.3e}"
+        print(f"long prefix: max row error {err.max():.3e}", flush=True)
+        # the roundings of the path (Q times the score scale to bf16 a second time, P to bf16, the output to bf16) are
+        # per element and do not accumulate with the prefix length: at 300001 tokens the error must still leave 40 %
+        # of the 2e-2 bound unused
+        assert err.max() <= 1.2e-2, f"max row error {err.max():.3e}"
         assert np.abs(lse.reshape(-1)[ids] - ref_lse).max() <= 1e-2
     # a chunk longer than the block ids a workgroup can hold is refused when it is asked for explicitly
     from paper_2506_19830_amd import binding as B
