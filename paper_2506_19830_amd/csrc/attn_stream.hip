@@ -184,6 +184,145 @@ __device__ __forceinline__ void stream_tile(const uint8_t *kt, const uint8_t *qf
   pv(1, p1);
 }
 
+// The unmasked tile again, scheduled by hand: the tile's 32 MFMAs in a fixed order (S^T of block 0; S^T of block 1 next
+// to the probabilities of block 0; O += block 0 next to the probabilities of block 1; O += block 1), each followed by
+// one LDS fragment read (issued kReadAhead MFMAs before its use), the four conversions of the next MFMA's fp8 operand,
+// its share of the exponentials, and a scheduling fence.  A wavefront issues about one instruction per seven cycles and
+// an LDS read returns after a hundred or more, so what the compiler's own order loses is waiting: every fragment must
+// already be on its way when the previous MFMA is issued.  The Q fragments are read once per tile and held while both
+// S^T chains run.  As in the row-tile kernel's pipelined loop the probabilities are formed against the base the
+// accumulators were started from, and the row sum doubles as the overflow guard (a sum above kTrigger, or no base yet:
+// the block is redone in the general form, which finds the maximum and moves the base).
+constexpr float kTrigger = 1024.0f;
+constexpr int kReadAhead = 7;
+
+__device__ __forceinline__ bool stream_redo_block(const f32x16 (&s)[1], float binit, RowState<1> &st,
+                                                  uint32_t (&pc)[1][8], float &acc) {
+  const float bi[1] = {binit};
+  float mt[1], alpha[1], off[1], sum[1];
+  block_max<1>(s, 1.f, bi, mt);
+  const bool raised = raise_max<1>(mt, st, alpha, 0.f);
+  const float m_use = (st.m_run[0] == -INFINITY) ? 0.f : st.m_run[0];
+  if (raised) {
+    rescale<1>(st, alpha);
+    st.base[0] = m_use;
+  }
+  off[0] = binit - m_use;
+  block_probs<1, false>(s, 1.f, off, pc, sum);
+  acc = sum[0];
+  return raised;
+}
+
+//   ISSUE: the wavefront's direct loads of a later (full prefix) step are issued between the MFMAs, one every
+//   32 / IPW of them, instead of in one run before the tile: `ld`, `slot`, `first0` as for StreamLoader::issue.
+template <bool ISSUE, typename Loader>
+__device__ __forceinline__ void stream_tile_fast(const uint8_t *kt, const uint8_t *qfrag, RowState<1> &st,
+                                                 const int (&koff)[4], const int (&voff)[4], const Loader &ld, int slot,
+                                                 int first0) {
+  constexpr int kIssueEvery = 32 / Loader::kLoadsPerStep;
+  // per MFMA: this wavefront's share of the next loads, and an issue priority that falls with progress through the
+  // tile, so that of the two wavefronts of a SIMD the one that is behind wins the arbitration
+  auto group_extra = [&](int g) __attribute__((always_inline)) {
+    if (g == 0) __builtin_amdgcn_s_setprio(3);
+    if (g == 8) __builtin_amdgcn_s_setprio(2);
+    if (g == 16) __builtin_amdgcn_s_setprio(1);
+    if (g == 24) __builtin_amdgcn_s_setprio(0);
+    if constexpr (ISSUE) {
+      if (g % kIssueEvery == 0) ld.template issue_one<true, false>(g / kIssueEvery, slot, first0, 0);
+    }
+  };
+  const uint8_t *vt = kt + kHalfBytes;
+  // the 32 fragment reads of the tile in the order of their use:
+  //   0..11   q0 k00 q1 q2 k01 q3 q4 k02 q5 q6 k03 q7   (Q fragment j: MFMA step j of both chains; K piece u of
+  //           block 0: steps 2u, 2u+1 of the first chain)
+  //   12..15  K pieces 0..3 of block 1
+  //   16..23  V^T fragments of block 0 (keys 16 t2 .. +16, head-dim block db; index 4 t2 + db), 24..31 of block 1
+  bf16x8 q[8];
+  u32x4 kr[2][4];
+  u32x2 vr[2][8];
+  auto read = [&](int i) __attribute__((always_inline)) {
+    if (i < 12) {
+      const int u = i / 3, w = i % 3;  // per K piece u: q(2u), k(0,u), q(2u+1)
+      if (w == 0) q[2 * u] = *(const bf16x8 *)(qfrag + (2 * u) * 1024);
+      if (w == 1) kr[0][u] = *(const u32x4 *)(kt + koff[u]);
+      if (w == 2) q[2 * u + 1] = *(const bf16x8 *)(qfrag + (2 * u + 1) * 1024);
+    } else if (i < 16) {
+      kr[1][i - 12] = *(const u32x4 *)(kt + 32 * kRowBytes + koff[i - 12]);
+    } else if (i < 32) {
+      const int kb = (i - 16) >> 3, t2 = ((i - 16) >> 2) & 1, db = (i - 16) & 3;
+      vr[kb][(i - 16) & 7] = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr8_b64_v2i32((LA_LDS i32x2 *)(
+                                                         vt + (kb * 32 + t2 * 16) * kRowBytes + voff[db])));
+    }
+  };
+#pragma unroll
+  for (int i = 0; i < kReadAhead; ++i) read(i);
+  const float base_in = st.base[0];
+  const float nb = -base_in;
+  const f32x16 c_init = {nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb};
+  f32x16 s0[1], s1[1];
+  uint32_t p0[1][8], p1[1][8];
+  float sum0 = 0.f, sum1 = 0.f;
+  bool raised0 = false;
+  // the S^T operand of MFMA step j from K piece j / 2: its low or high eight bytes
+  auto k_operand = [&](int kb, int j) __attribute__((always_inline)) {
+    const u32x4 r = kr[kb][j >> 1];
+    return (j & 1) ? widen8(r[2], r[3]) : widen8(r[0], r[1]);
+  };
+  auto softmax_share = [&](const f32x16 &sc, int pair, uint32_t (&pc)[8], float &sum) __attribute__((always_inline)) {
+    const float e0 = __builtin_amdgcn_exp2f(sc[2 * pair]), e1 = __builtin_amdgcn_exp2f(sc[2 * pair + 1]);
+    pc[pair] = pack_bf16(e0, e1);
+    sum += e0 + e1;
+    asm volatile("" : "+v"(sum), "+v"(pc[pair]));  // here, not wherever the value is first needed
+  };
+#pragma unroll
+  for (int g = 0; g < 16; ++g) {  // S^T of block 0, then S^T of block 1 beside the probabilities of block 0
+    if (g + kReadAhead < 32) read(g + kReadAhead);
+    if (g < 8) {
+      s0[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_operand(0, g), q[g], g == 0 ? c_init : s0[0], 0, 0, 0);
+    } else {
+      s1[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_operand(1, g - 8), q[g - 8], g == 8 ? c_init : s1[0], 0, 0, 0);
+      softmax_share(s0[0], g - 8, p0[0], sum0);
+    }
+    group_extra(g);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  {
+    const bool none_yet = __builtin_amdgcn_ballot_w64(st.m_run[0] == -INFINITY) != 0;
+    const bool trig = __builtin_amdgcn_ballot_w64(sum0 > kTrigger) != 0;
+    if (none_yet | trig) raised0 = stream_redo_block(s0, base_in, st, p0, sum0);
+  }
+  st.l_run[0] += sum0;
+  const u32x4 pa0 = {p0[0][0], p0[0][1], p0[0][2], p0[0][3]}, pa1 = {p0[0][4], p0[0][5], p0[0][6], p0[0][7]};
+#pragma unroll
+  for (int g = 16; g < 24; ++g) {  // O += block 0 beside the probabilities of block 1
+    if (g + kReadAhead < 32) read(g + kReadAhead);
+    const int u = g - 16;
+    st.o[u & 3][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen8(vr[0][u][0], vr[0][u][1]),
+                                                             __builtin_bit_cast(bf16x8, u < 4 ? pa0 : pa1), st.o[u & 3][0],
+                                                             0, 0, 0);
+    softmax_share(s1[0], u, p1[0], sum1);
+    group_extra(g);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  {
+    const bool trig = __builtin_amdgcn_ballot_w64(sum1 > kTrigger) != 0;
+    if (raised0 | trig) stream_redo_block(s1, base_in, st, p1, sum1);
+  }
+  st.l_run[0] += sum1;
+  const u32x4 pb0 = {p1[0][0], p1[0][1], p1[0][2], p1[0][3]}, pb1 = {p1[0][4], p1[0][5], p1[0][6], p1[0][7]};
+#pragma unroll
+  for (int g = 24; g < 32; ++g) {  // O += block 1
+    if (g + kReadAhead < 32) read(g + kReadAhead);
+    const int u = g - 24;
+    st.o[u & 3][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen8(vr[1][u][0], vr[1][u][1]),
+                                                             __builtin_bit_cast(bf16x8, u < 4 ? pb0 : pb1), st.o[u & 3][0],
+                                                             0, 0, 0);
+    group_extra(g);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  __builtin_amdgcn_s_setprio(0);
+}
+
 // The direct K/V loads of one wavefront.  A step is KSL tiles x (8 + 8) loads of 1 KiB (eight key rows each);
 // wavefront w issues loads w*IPW .. w*IPW + IPW-1 of every step.  Lane l fetches 16 bytes of key row l/8 of those
 // eight: slot l%8, i.e. global piece (l%8) ^ swz(key).  Every wavefront issues exactly IPW loads per step, so the
@@ -199,6 +338,7 @@ struct StreamLoader {
   int first_lb, ident, shift, bs_mask;
   uint32_t blk_stride, br_stride;  // bytes between cache blocks / between branch tokens
   const uint8_t *k_pre, *v_pre, *k_br, *v_br;
+  static constexpr int kLoadsPerStep = IPW;
   int key[IPW], goff[IPW];       // per lane: key inside the tile, byte offset inside the key row
 
   __device__ __forceinline__ void init_lane(int lane) {
@@ -215,9 +355,14 @@ struct StreamLoader {
   // repeat token `last`.
   template <bool PREFIX, bool CLAMP>
   __device__ __forceinline__ void issue(int slot, int first0, int last) const {
-    const uint32_t stage = ring + slot * (KSL * G::kTile);
 #pragma unroll
-    for (int j = 0; j < IPW; ++j) {
+    for (int j = 0; j < IPW; ++j) issue_one<PREFIX, CLAMP>(j, slot, first0, last);
+  }
+  // load j (0 .. IPW-1) of the step alone, for a caller that spreads a step's loads between other work
+  template <bool PREFIX, bool CLAMP>
+  __device__ __forceinline__ void issue_one(int j, int slot, int first0, int last) const {
+    const uint32_t stage = ring + slot * (KSL * G::kTile);
+    {
       const int ii = wave * IPW + j;  // wavefront-uniform: which 1 KiB of the step
       const int tile = ii / (2 * G::kLoadsPerHalf), half = (ii / G::kLoadsPerHalf) & 1, r = ii % G::kLoadsPerHalf;
       int tok = first0 + tile * kTileN + key[j];
@@ -384,7 +529,12 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnPara
     // own loads of this step have landed (the steps issued after it may still be in flight) ...
     wait_later<IPW, NST - 2>(min(n_steps - 1, step + NST - 2) - step);
     __builtin_amdgcn_s_barrier();  // ... and so have everyone else's; the slots read in the previous step are free
-    if (step + NST - 1 < n_steps) issue(step + NST - 1);
+    // the loads of step + NST - 1: between the MFMAs of this step's tile where both are plain full prefix steps, in
+    // one run here otherwise
+    const int nxt = step + NST - 1;
+    const bool tile_full = step < n_pre_steps && k_begin + (step * KSL + ks + 1) * kTileN <= k_end;
+    const bool inline_issue = active && tile_full && nxt < n_full_steps && step > 0;
+    if (nxt < n_steps && !inline_issue) issue(nxt);
     if (step == 0) {
       // The Q fragments have landed (they were requested before any K/V): multiply by the prefix score scale (log2
       // units, k_scale folded in), round to bf16 again and put them back, each key slice of the row block a share
@@ -409,8 +559,10 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnPara
     const uint8_t *qfrag = lds + rb * 8192 + lane * 16;
     if (step < n_pre_steps) {
       const int first = k_begin + (step * KSL + ks) * kTileN;
-      if (first + kTileN <= k_end)
-        stream_tile<MASK_NONE>(kt, qfrag, st, koff, voff, lh, 0, 0);
+      if (inline_issue)
+        stream_tile_fast<true>(kt, qfrag, st, koff, voff, ld, nxt % NST, k_begin + nxt * (KSL * kTileN));
+      else if (first + kTileN <= k_end)
+        stream_tile_fast<false>(kt, qfrag, st, koff, voff, ld, 0, 0);
       else if (first < k_end)
         stream_tile<MASK_TAIL>(kt, qfrag, st, koff, voff, lh, first, k_end);
     } else {
