@@ -81,9 +81,13 @@ typedef enum {
  *  every query head of the group.
  *
  *  Supported combinations (anything else: LA_ERR_UNSUPPORTED)
- *      q f32,  cache f32,  branch f32,  out f32        head_dim 64 / 128 / 256
- *      q bf16, cache bf16, branch bf16, out bf16|f32   head_dim 128
- *      q bf16, cache fp8,  branch fp8|bf16, out bf16|f32  head_dim 128
+ *      q f32,  cache f32,  branch f32,  out f32           head_dim 64 / 128 / 256
+ *      q bf16, cache bf16, branch bf16, out bf16|f32      head_dim 64 / 128 / 256
+ *      q bf16, cache fp8,  branch fp8|bf16, out bf16|f32  head_dim 64 / 128 / 256
+ *  The bf16 / fp8 combinations run on the MFMA kernels at head_dim 128 and,
+ *  like fp32 tensors, on the general kernel (fp32 arithmetic on exactly widened
+ *  inputs, one wavefront per query row, no workspace) at head_dim 64 and 256;
+ *  kernel_shape must be 0 there.
  *  fp8 storage is multiplied by k_scale[kv_head] / v_scale[kv_head]; a branch
  *  K/V stored as fp8 uses the same scales as the cache.  The scales are device
  *  arrays the host cannot inspect: they must be positive and finite (a zero,

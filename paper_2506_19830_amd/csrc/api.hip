@@ -119,7 +119,15 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, bool
   const bool bf16_all = d->q_dtype == LA_BF16 && d->kv_dtype == LA_BF16 && d->branch_kv_dtype == LA_BF16;
   const bool fp8_kv = d->q_dtype == LA_BF16 && d->kv_dtype == LA_FP8_E4M3 &&
                       (d->branch_kv_dtype == LA_FP8_E4M3 || d->branch_kv_dtype == LA_BF16);
-  if (!out_ok || !(bf16_all || fp8_kv) || d->head_dim != 128) return LA_ERR_UNSUPPORTED;
+  if (!out_ok || !(bf16_all || fp8_kv)) return LA_ERR_UNSUPPORTED;
+  if (d->head_dim != 128) {
+    // the MFMA and streaming kernels are written for head dimension 128; 64 and 256 run on the general kernel
+    // (fp32 arithmetic on exactly widened inputs, one wavefront per query row)
+    if (d->head_dim != 64 && d->head_dim != 256) return LA_ERR_UNSUPPORTED;
+    if (d->kernel_shape > 0) return LA_ERR_UNSUPPORTED;
+    plan->path = PATH_F32;
+    return LA_OK;
+  }
   plan->path = PATH_MFMA;
   plan->kv_fp8 = d->kv_dtype == LA_FP8_E4M3;
   plan->br_fp8 = d->branch_kv_dtype == LA_FP8_E4M3;
@@ -311,6 +319,7 @@ static la_status verify_attention(const la_attn_desc *desc, const void *q, const
   p.R = p.gamma * p.L * p.G;
   p.n_rows = p.gamma * p.L * p.Hq;
   p.out_f32 = desc->out_dtype == LA_F32;
+  p.q_type = desc->q_dtype, p.kv_type = desc->kv_dtype, p.br_type = desc->branch_kv_dtype;
   p.scale_log2 = desc->softmax_scale * 1.44269504088896340736f;
   hipStream_t stream = (hipStream_t)hip_stream;
 

@@ -1,4 +1,6 @@
-// Verify attention for fp32 tensors (gfx950), the small-case / reference-precision path.
+// Verify attention, the general path (gfx950): fp32 tensors (the small-case / reference-precision configuration), and
+// bf16 / fp8-e4m3 storage at the head dimensions the MFMA kernels are not written for (64 and 256).  All arithmetic is
+// fp32 on exactly widened inputs.
 //
 // One wavefront owns one query row (request b, branch g, token i, head h) and walks
 // its visible keys -- the request's prefix through the block table, then the part of
@@ -16,7 +18,26 @@ namespace {
 
 constexpr int kWaves = 4;
 
-template <int D>
+// element i of a tensor stored as T, widened to fp32 (exact)
+template <int T>
+__device__ __forceinline__ float load_elem(const void *base, size_t i) {
+  if constexpr (T == LA_F32) {
+    return ((const float *)base)[i];
+  } else if constexpr (T == LA_BF16) {
+    const uint32_t w = (uint32_t)((const uint16_t *)base)[i] << 16;
+    return __builtin_bit_cast(float, w);
+  } else {
+    const auto v = __builtin_amdgcn_cvt_pk_f32_fp8((int)((const uint8_t *)base)[i], false);
+    return v[0];
+  }
+}
+__device__ __forceinline__ float load_elem_rt(int type, const void *base, size_t i) {
+  return type == LA_F32 ? load_elem<LA_F32>(base, i) : load_elem<LA_BF16>(base, i);
+}
+
+// D: head dimension; KV, BR: storage type of the prefix cache and of the branch / chain / pool K and V (compile time:
+// they sit in the inner loops); Q and output types are read from the parameters.
+template <int D, int KV, int BR>
 __global__ __launch_bounds__(64 * kWaves) void attn_f32_kernel(const AttnParams p) {
   __shared__ float q_lds[kWaves][D];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -37,26 +58,34 @@ __global__ __launch_bounds__(64 * kWaves) void attn_f32_kernel(const AttnParams 
   const uint64_t seen = tree ? p.seg_mask[b * p.gamma + t / p.L] : 0;
   const int n_keys = P + vis + i + 1;
 
-  const float *q = (const float *)p.q + grow * D;
-  for (int d = lane; d < D; d += 64) q_lds[wave][d] = q[d];
+  for (int d = lane; d < D; d += 64) q_lds[wave][d] = load_elem_rt(p.q_type, p.q, grow * D + d);
   __syncthreads();
 
-  const float *kc = (const float *)p.k_cache, *vc = (const float *)p.v_cache;
-  const float *kb = (const float *)p.k_branch + ((size_t)b * p.gamma * p.L * p.Hkv + kvh) * D;
-  const float *vb = (const float *)p.v_branch + ((size_t)b * p.gamma * p.L * p.Hkv + kvh) * D;
-  const float *kn = (const float *)p.k_chain + ((size_t)b * p.C * p.Hkv + kvh) * D;
-  const float *vn = (const float *)p.v_chain + ((size_t)b * p.C * p.Hkv + kvh) * D;
+  // an fp8 tensor is stored divided by its head's scale: K's scale multiplies the score, V's the weighted value
+  float ks_pre = 1.f, vs_pre = 1.f, ks_br = 1.f, vs_br = 1.f;
+  if (KV == LA_FP8_E4M3) ks_pre = p.k_scale ? p.k_scale[kvh] : 1.f, vs_pre = p.v_scale ? p.v_scale[kvh] : 1.f;
+  if (BR == LA_FP8_E4M3) ks_br = ks_pre, vs_br = vs_pre;
   const int32_t *table = p.block_tables ? p.block_tables + (size_t)b * p.max_blocks : nullptr;
 
-  // row of key `key` in the K tensors (k = true) or the V tensors
-  auto kv_row = [&](int key, bool k) -> const float * {
+  // element d of the row of key `key` in the K tensors (k = true) or the V tensors; the row's element index first
+  auto kv_index = [&](int key, int &seg) -> size_t {
     if (key < P) {
       const int lb = key / p.block_size;
       const int blk = table ? table[lb] : b * p.max_blocks + lb;
-      return (k ? kc : vc) + (((size_t)blk * p.Hkv + kvh) * p.block_size + key % p.block_size) * D;
+      seg = 0;
+      return (((size_t)blk * p.Hkv + kvh) * p.block_size + key % p.block_size) * D;
     }
-    if (key < P + vis) return (k ? kn : vn) + (size_t)(key - P) * p.Hkv * D;
-    return (k ? kb : vb) + (size_t)(bstart + key - P - vis) * p.Hkv * D;
+    if (key < P + vis) {
+      seg = 1;
+      return (((size_t)b * p.C + (key - P)) * p.Hkv + kvh) * D;
+    }
+    seg = 2;
+    return (((size_t)b * p.gamma * p.L + bstart + key - P - vis) * p.Hkv + kvh) * D;
+  };
+  auto kv_elem = [&](bool k, int seg, size_t idx) -> float {
+    if (seg == 0) return load_elem<KV>(k ? p.k_cache : p.v_cache, idx);
+    if (seg == 1) return load_elem<BR>(k ? p.k_chain : p.v_chain, idx);
+    return load_elem<BR>(k ? p.k_branch : p.v_branch, idx);
   };
 
   constexpr int E = D / 64;
@@ -69,11 +98,12 @@ __global__ __launch_bounds__(64 * kWaves) void attn_f32_kernel(const AttnParams 
     const int key = k0 + lane;
     float s = -INFINITY;
     if (key < n_keys) {
-      const float *krow = kv_row(key, true);
+      int seg;
+      const size_t krow = kv_index(key, seg);
       float dot = 0.f;
 #pragma unroll 8
-      for (int d = 0; d < D; ++d) dot = __builtin_fmaf(q_lds[wave][d], krow[d], dot);
-      s = dot * p.scale_log2;
+      for (int d = 0; d < D; ++d) dot = __builtin_fmaf(q_lds[wave][d], kv_elem(true, seg, krow + d), dot);
+      s = dot * p.scale_log2 * (seg == 0 ? ks_pre : ks_br);
       if (tree && key >= P && key < P + vis && !((seen >> p.pool_seg[(size_t)b * p.C + (key - P)]) & 1)) s = -INFINITY;
     }
     float mx = s;
@@ -93,40 +123,57 @@ __global__ __launch_bounds__(64 * kWaves) void attn_f32_kernel(const AttnParams 
     for (int e = 0; e < E; ++e) acc[e] *= alpha;
     const int cnt = min(64, n_keys - k0);
     for (int j = 0; j < cnt; ++j) {
-      const float pj = __shfl(pr, j);
-      const float *vrow = kv_row(k0 + j, false);
+      int seg;
+      const size_t vrow = kv_index(k0 + j, seg);
+      const float pj = __shfl(pr, j) * (seg == 0 ? vs_pre : vs_br);
 #pragma unroll
-      for (int e = 0; e < E; ++e) acc[e] = __builtin_fmaf(pj, vrow[lane + 64 * e], acc[e]);
+      for (int e = 0; e < E; ++e) acc[e] = __builtin_fmaf(pj, kv_elem(false, seg, vrow + lane + 64 * e), acc[e]);
     }
   }
   if (!valid) return;
   const float inv = 1.0f / l_run;
-  float *out = (float *)p.out + grow * D;
 #pragma unroll
-  for (int e = 0; e < E; ++e) out[lane + 64 * e] = acc[e] * inv;
+  for (int e = 0; e < E; ++e) {
+    const float o = acc[e] * inv;
+    if (p.out_f32) {
+      ((float *)p.out)[grow * D + lane + 64 * e] = o;
+    } else {  // bf16, round to nearest even
+      const uint32_t u = __builtin_bit_cast(uint32_t, o);
+      ((uint16_t *)p.out)[grow * D + lane + 64 * e] = (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+    }
+  }
   if (p.lse && lane == 0) p.lse[grow] = 0.69314718055994530942f * (m_run + __builtin_log2f(l_run));
+}
+
+template <int KV, int BR>
+hipError_t launch_typed(const AttnParams &p, hipStream_t stream) {
+  const size_t rows = (size_t)p.B * p.n_rows;
+  const int grid = (int)((rows + kWaves - 1) / kWaves);
+  switch (p.D) {
+    case 64:
+      hipLaunchKernelGGL((attn_f32_kernel<64, KV, BR>), dim3(grid), dim3(64 * kWaves), 0, stream, p);
+      break;
+    case 128:
+      hipLaunchKernelGGL((attn_f32_kernel<128, KV, BR>), dim3(grid), dim3(64 * kWaves), 0, stream, p);
+      break;
+    case 256:
+      hipLaunchKernelGGL((attn_f32_kernel<256, KV, BR>), dim3(grid), dim3(64 * kWaves), 0, stream, p);
+      break;
+    default:
+      return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_attn_f32(const AttnParams &p, hipStream_t stream) {
   ProfileScope scope(SLOT_ATTN_F32, stream);
-  const size_t rows = (size_t)p.B * p.n_rows;
-  const int grid = (int)((rows + kWaves - 1) / kWaves);
-  switch (p.D) {
-    case 64:
-      hipLaunchKernelGGL(attn_f32_kernel<64>, dim3(grid), dim3(64 * kWaves), 0, stream, p);
-      break;
-    case 128:
-      hipLaunchKernelGGL(attn_f32_kernel<128>, dim3(grid), dim3(64 * kWaves), 0, stream, p);
-      break;
-    case 256:
-      hipLaunchKernelGGL(attn_f32_kernel<256>, dim3(grid), dim3(64 * kWaves), 0, stream, p);
-      break;
-    default:
-      return hipErrorInvalidValue;
-  }
-  return hipGetLastError();
+  if (p.kv_type == LA_F32 && p.br_type == LA_F32) return launch_typed<LA_F32, LA_F32>(p, stream);
+  if (p.kv_type == LA_BF16 && p.br_type == LA_BF16) return launch_typed<LA_BF16, LA_BF16>(p, stream);
+  if (p.kv_type == LA_FP8_E4M3 && p.br_type == LA_FP8_E4M3) return launch_typed<LA_FP8_E4M3, LA_FP8_E4M3>(p, stream);
+  if (p.kv_type == LA_FP8_E4M3 && p.br_type == LA_BF16) return launch_typed<LA_FP8_E4M3, LA_BF16>(p, stream);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace la

@@ -47,6 +47,7 @@ struct AttnParams {
   int s_max;        // partial slots per request = max_b n_chunks(b)
   int total_units;  // sum_b n_chunks(b)
   int out_f32;      // output dtype: 1 = fp32, 0 = bf16
+  int q_type, kv_type, br_type;  // la_dtype of Q, of the prefix cache, of the branch / chain / pool K and V
   float scale_log2; // softmax_scale * log2(e)
   // With few requests what a workgroup needs to find its chunk travels in the kernel arguments, prepared by the host
   // from its copy of the prefix lengths, so that no kernel start waits on a dependent load of prefix_lens or on

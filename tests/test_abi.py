@@ -77,7 +77,8 @@ def test_workspace_query_and_plan():
     (dict(gamma=0), [100], 1),
     (dict(), [-1], 1),
     (dict(max_blocks_per_request=4), [65], 1),
-    (dict(head_dim=64), [100], 2),
+    (dict(head_dim=96), [100], 2),
+    (dict(head_dim=64, kernel_shape=1), [100], 2),
     (dict(q_dtype="f32"), [100], 2),
     (dict(kv_dtype="bf16", branch_kv_dtype="fp8_e4m3"), [100], 2),
     (dict(out_dtype="fp8_e4m3"), [100], 2),

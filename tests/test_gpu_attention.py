@@ -153,6 +153,38 @@ def test_streaming_shape_is_refused_where_it_cannot_run(monkeypatch):
     assert e.value.status == 2
 
 
+# ----------------------------------------------------------------------------------------- other head dimensions
+
+GENERAL_CASES = [
+    # bf16 / fp8 storage at head dimensions 64 and 256: the general kernel (fp32 arithmetic on exactly widened inputs)
+    W.AttnCase("bf16_d64_paged", (300, 17), 3, 5, 8, 2, 64, "bf16", "bf16", "bf16", "bf16", paged=True, seed=81),
+    W.AttnCase("fp8_d64", (515,), 2, 9, 6, 2, 64, "bf16", "fp8_e4m3", "fp8_e4m3", "f32", seed=82),
+    W.AttnCase("fp8_bf16_branch_d256", (130,), 2, 4, 4, 1, 256, "bf16", "fp8_e4m3", "bf16", "bf16", seed=83),
+    W.AttnCase("bf16_d256_no_prefix", (0,), 2, 70, 2, 2, 256, "bf16", "bf16", "bf16", "f32", seed=84),
+]
+
+
+@pytest.mark.parametrize("case", GENERAL_CASES, ids=lambda c: c.name)
+def test_other_head_dimensions(oracle, case):
+    """Inputs are widened exactly and everything is fp32, so with fp32 output the result is fp32-accurate; with bf16
+    output the only rounding is the output's own."""
+    from paper_2506_19830_amd import binding as B
+    desc_plan = B.la_verify_attention_plan(
+        B.make_attn_desc(num_requests=case.B, num_q_heads=case.Hq, num_kv_heads=case.Hkv, head_dim=case.D,
+                         gamma=case.gamma, branch_len=case.L, block_size=case.block_size,
+                         max_blocks_per_request=case.max_blocks, q_dtype=case.q_dtype, kv_dtype=case.kv_dtype,
+                         branch_kv_dtype=case.branch_kv_dtype, out_dtype=case.out_dtype, softmax_scale=case.scale),
+        [int(x) for x in case.prefix_lens])
+    assert desc_plan["path"] == 1
+    tol = 1e-5 if case.out_dtype == "f32" else 5e-3
+    check_full(oracle, case, tol, lse_tol=1e-5)
+
+
+def test_other_head_dimensions_nested_and_tree(oracle):
+    check_nested(oracle, GENERAL_CASES[1], 40, 1e-5)
+    check_tree(oracle, GENERAL_CASES[0], 2, 3, 6, 5e-3)
+
+
 # ----------------------------------------------------------------------------------------- nested branches
 
 def check_nested(oracle, case, chain_len, tol, chain_vis=None, kv_split_tokens=0):
