@@ -25,7 +25,7 @@
 //                    B = P^T (registers, bf16)
 // Everything is kept in log2 units: p = 2^(s*c - m).
 #include <mutex>
-
+#include <type_traits>
 #include "attn_common.hpp"
 
 namespace la {
@@ -758,7 +758,10 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
       auto no_hook = [](int) {};
       constexpr int kLoads = PrefixLoader<KV_FP8, NT>::kNK + 4 * PrefixLoader<KV_FP8, NT>::kNV;  // per tile and thread
       // one steady-state iteration: the loads of tile it+3 go to `ld`, tile it+2 is written from `stq`
-      auto steady = [&](int it, TileRegs<KV_FP8, NT> &ld, const TileRegs<KV_FP8, NT> &stq) __attribute__((always_inline)) {
+      // (ACT: the wavefront has rows.  A compile-time flag, and one loop per value below: in a loop shared by both
+      // kinds of wavefront the compiler hoists the staging conversions the two paths have in common above the branch,
+      // and with them the wait for the loads, to the top of the iteration)
+      auto steady = [&](auto act, int it, TileRegs<KV_FP8, NT> &ld, const TileRegs<KV_FP8, NT> &stq) __attribute__((always_inline)) {
         const int first = k_begin + (it + 3) * kTileN;
         uint8_t *dst = lds + ((it + 2) & 3) * kStageBytes;
         auto hook_a = [&](int i) __attribute__((always_inline)) {
@@ -775,7 +778,7 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
           if (i == 9) tile_store_v<KV_FP8, NT, 0>(dst, tid, stq);
           if (i == 12) tile_store_v<KV_FP8, NT, 1>(dst, tid, stq);
         };
-        if (active) {
+        if constexpr (decltype(act)::value) {
           pipe_tile<true>(stage(it > 0 ? it - 1 : 0), stage(it), stage(it + 1), cy, st, ln, lh, hook_a, hook_b);
         } else {  // no rows: only the wavefront's share of the staging
           hook_a(1), hook_a(6), hook_a(8);
@@ -784,9 +787,16 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
         __syncthreads();
       };
       int it = 0;
-      for (; it + 4 < n_full; it += 2) {  // steady state, two tiles per trip (the register sets alternate)
-        steady(it, regs2, regs);
-        steady(it + 1, regs, regs2);
+      if (active) {
+        for (; it + 4 < n_full; it += 2) {  // steady state, two tiles per trip (the register sets alternate)
+          steady(std::true_type{}, it, regs2, regs);
+          steady(std::true_type{}, it + 1, regs, regs2);
+        }
+      } else {
+        for (; it + 4 < n_full; it += 2) {
+          steady(std::false_type{}, it, regs2, regs);
+          steady(std::false_type{}, it + 1, regs, regs2);
+        }
       }
       // the last tiles that still have something to write (regs holds tile it+2), then the second to last tile
       for (; it + 1 < n_full; ++it) {
@@ -861,6 +871,11 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
     // iteration i-1) to the other stage and issues the loads of tile i+2.  Those loads have one tile time to
     // arrive, less than an HBM round trip under load, so every 128-byte line of a tile is touched four tiles
     // ahead with a one-word load whose value is only folded into a sink: the staging loads then hit L2.
+    // Loads return in order, so a touch must not be waited for before two more tiles have passed: its value is
+    // folded in two iterations later (two variables, the loop unrolled by two so that neither is ever copied),
+    // and there is one loop per kind of wavefront (with rows, or staging only): in a shared loop the fragment
+    // registers of the computing path and the staging registers of the other overlap, and the compiler then waits
+    // for every load in flight before the first fragment read of a tile.
     uint32_t sink = 0;
     if (n_full > 0) {
       TileRegs<KV_FP8, NT> regs;
@@ -870,38 +885,54 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
       constexpr int kLinesPerRow = kv_row / 128;       // 1 (fp8) or 2 (bf16)
       constexpr int kLines = kTileN * kLinesPerRow;    // lines of the K tile; the V tile has as many
       static_assert(2 * kLines <= NT, "one touch per thread");
+      // (unconditional: past the last tile the last one is touched again, and with more threads than lines the
+      // lines are touched twice; a load under a branch would have its value copied at the end of the iteration, and
+      // the copy waited for)
+      const int tline = tid % kLines;
+      const uint8_t *const tbase = ((tid / kLines) & 1) ? pre.v_base : pre.k_base;
       auto touch = [&](int it) -> uint32_t {
-        if (it >= n_full || tid >= 2 * kLines) return 0u;
-        pre.first = k_begin + it * kTileN;
-        const int line = tid % kLines;
-        const uint8_t *base = tid < kLines ? pre.k_base : pre.v_base;
-        return *(const uint32_t *)(key_row<KV_FP8, true>(p, pre, base, pre.first + line / kLinesPerRow) +
-                                   (line % kLinesPerRow) * 128);
+        const int first = k_begin + min(it, n_full - 1) * kTileN;
+        return *(const uint32_t *)(key_row<KV_FP8, true>(p, pre, tbase, first + tline / kLinesPerRow) +
+                                   (tline % kLinesPerRow) * 128);
       };
       const uint32_t t1 = touch(1), t2 = touch(2), t3 = touch(3);
       gload(0);
       tile_store<KV_FP8, NT>(lds, tid, regs);
       if (n_full > 1) gload(1);
-      uint32_t pf = t1 ^ t2 ^ t3;
+      uint32_t pfa = t1 ^ t2, pfb = t3;
       __syncthreads();
-      for (int it = 0; it < n_full; ++it) {
+      // SURE: tiles it+1 and it+2 exist
+      auto iter = [&](auto act, auto sure, int it, uint32_t &pf) __attribute__((always_inline)) {
         const uint8_t *cur = lds + (it & 1) * kStageBytes;
         uint8_t *other = lds + ((it + 1) & 1) * kStageBytes;
         auto tail = [&] {
-          if (it + 1 < n_full) {
+          if (decltype(sure)::value || it + 1 < n_full) {
             tile_store<KV_FP8, NT>(other, tid, regs);
-            if (it + 2 < n_full) gload(it + 2);
+            if (decltype(sure)::value || it + 2 < n_full) gload(it + 2);
           }
-          sink ^= pf;
+          sink ^= pf;  // requested two iterations ago
+          __builtin_amdgcn_sched_barrier(0);  // (the old value is dead before the new load is issued)
           pf = touch(it + 4);
         };
-        if (active)
+        if constexpr (decltype(act)::value)
           compute_tile<RB, MASK_NONE, false, false>(cur, nullptr, k0, st, ln, lh, 0, 0, 1.f, 0.f, 1.f, tail);
         else
           tail();
         __syncthreads();
-      }
-      sink ^= pf;
+      };
+      auto tiles = [&](auto act) __attribute__((always_inline)) {
+        int it = 0;
+        for (; it + 3 < n_full; it += 2) {  // steady state: no load is conditional
+          iter(act, std::true_type{}, it, pfa);
+          iter(act, std::true_type{}, it + 1, pfb);
+        }
+        for (; it < n_full; ++it) iter(act, std::false_type{}, it, (it & 1) ? pfb : pfa);
+      };
+      if (active)
+        tiles(std::true_type{});
+      else
+        tiles(std::false_type{});
+      sink ^= pfa ^ pfb;
     }
     // never true (R >= 1): keeps the touched words alive without a store on any real path
     if (p.R < 0) p.part_ml[0] = __builtin_bit_cast(float, sink);

@@ -117,6 +117,17 @@ def test_every_streaming_shape(oracle, case, shape, monkeypatch):
         check_full(oracle, case, TOL_LOWP, kv_split_tokens=split)
 
 
+@pytest.mark.parametrize("shape", [0, 1])
+@pytest.mark.parametrize("case", STREAM_CASES[:2], ids=lambda c: c.name)
+def test_row_tile_shapes_with_idle_wavefronts(oracle, case, shape, monkeypatch):
+    """Few rows on the row-tile shapes: wavefronts whose rows lie past R only stage tiles, in loops of their own
+    (R = 40: one computing wavefront; R = 270: a last row tile with 14 rows).  Chunks of one to seven full tiles
+    and the whole prefix, so that the steady-state loops and their tails run with every remainder."""
+    monkeypatch.setattr("gpu_util.KERNEL_SHAPE", shape + 1)
+    for split in (0, 64, 128, 192, 256, 320, 384, 448):
+        check_full(oracle, case, TOL_LOWP, kv_split_tokens=split)
+
+
 def _as_bf16(case, name):
     import dataclasses
     return dataclasses.replace(case, name=name, kv_dtype="bf16", branch_kv_dtype="bf16")
