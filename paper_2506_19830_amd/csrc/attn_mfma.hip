@@ -797,6 +797,10 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
           steady(std::false_type{}, it, regs2, regs);
           steady(std::false_type{}, it + 1, regs, regs2);
         }
+        // (no load of this loop is in flight past this point as far as the compiler can tell: it follows the two
+        // loops one after the other and would otherwise guard the other loop's registers against these loads with a
+        // full wait at the top of its every iteration)
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
       }
       // the last tiles that still have something to write (regs holds tile it+2), then the second to last tile
       for (; it + 1 < n_full; ++it) {
@@ -928,10 +932,12 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
         }
         for (; it < n_full; ++it) iter(act, std::false_type{}, it, (it & 1) ? pfb : pfa);
       };
-      if (active)
+      if (active) {
         tiles(std::true_type{});
-      else
+      } else {
         tiles(std::false_type{});
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): see the four-stage loop
+      }
       sink ^= pfa ^ pfb;
     }
     // never true (R >= 1): keeps the touched words alive without a store on any real path
