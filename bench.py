@@ -659,17 +659,31 @@ def main():
         calib_flops = B.la_calibrate_mfma(1024, 2000, sink)
         calib_bytes = B.la_calibrate_read(big, word)
     torch.cuda.synchronize()
-    B.la_profile_enable(False)
     cal = B.la_profile_collect()
     B.la_profile_reset()
     del big
+    # the same MFMA loop on operands that toggle like data (what the power-managed clock responds to)
+    B.la_calibrate_mfma(1024, 2000, sink, data=True)
+    torch.cuda.synchronize()
+    B.la_profile_collect()
+    B.la_profile_reset()
+    for _ in range(4):
+        data_flops = B.la_calibrate_mfma(1024, 2000, sink, data=True)
+    torch.cuda.synchronize()
+    B.la_profile_enable(False)
+    cal_data = B.la_profile_collect()
+    B.la_profile_reset()
     mfma_tflops = calib_flops / (cal["calib_mfma"][1] / cal["calib_mfma"][0] * 1e-3) / 1e12
+    mfma_data_tflops = data_flops / (cal_data["calib_mfma"][1] / cal_data["calib_mfma"][0] * 1e-3) / 1e12
     read_gbs = calib_bytes / (cal["calib_read"][1] / cal["calib_read"][0] * 1e-3) / 1e9
-    result["achievable"] = {"mfma_bf16_tflops": mfma_tflops, "hbm_read_gbs": read_gbs,
+    result["achievable"] = {"mfma_bf16_tflops": mfma_tflops, "mfma_bf16_tflops_random_operands": mfma_data_tflops,
+                            "hbm_read_gbs": read_gbs,
                             "roofline_frac_of_achievable_mfma": achieved_tflops / mfma_tflops,
+                            "roofline_frac_of_achievable_mfma_random_operands": achieved_tflops / mfma_data_tflops,
                             "accept_stats_frac_of_achievable_read": stats_gbs / read_gbs,
-                            "how": "pure v_mfma_f32_32x32x16_bf16 loop on all CUs; streaming read of 2 GiB; HIP events, "
-                                   "mean of 4 launches"}
+                            "how": "pure v_mfma_f32_32x32x16_bf16 loop on all CUs (nearly constant operands, and "
+                                   "pseudo-random operands in rotation); streaming read of 2 GiB; HIP events, mean of "
+                                   "4 launches"}
 
     # ---- CPU oracle on a bounded sample of the same workload (reported baseline, not a target) ----------------
     if not args.no_cpu_baseline:

@@ -25,10 +25,16 @@ extern "C" {
  *  la_calibrate_mfma: `workgroups` x 8 wavefronts, each `iters` rounds of four
  *  independent v_mfma_f32_32x32x16_bf16; *flops (host) receives the launch's
  *  flop count.  sink: dev, workgroups * 512 floats, written.
+ *  la_calibrate_mfma_data: the same loop (same arguments, `iters` even, same
+ *  profiling slot) on eight operand pairs per lane of pseudo-random bf16 values
+ *  used in rotation: the matrix pipeline's inputs toggle as on real data, which
+ *  is what a power-managed clock responds to.
  *  la_calibrate_read: reads `bytes` (a multiple of 16 is read) from src (dev,
  *  16-byte aligned) once; sink: dev, one word (written practically never).
  * ------------------------------------------------------------------------- */
 LA_API la_status la_calibrate_mfma(int32_t workgroups, int32_t iters, float *sink, double *flops, void *hip_stream);
+LA_API la_status la_calibrate_mfma_data(int32_t workgroups, int32_t iters, float *sink, double *flops,
+                                        void *hip_stream);
 LA_API la_status la_calibrate_read(const void *src, size_t bytes, uint32_t *sink, void *hip_stream);
 
 /* Instruction-mix probe: `workgroups` workgroups of `waves` (4 or 8: one or two

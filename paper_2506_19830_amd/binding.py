@@ -31,7 +31,7 @@ EXPORTED_SYMBOLS = (
 )
 # what libla_verify_bench.so exports on top of those (la_verify_bench.h)
 BENCH_SYMBOLS = (
-    "la_calibrate_mfma", "la_calibrate_read", "la_calibrate_issue", "la_selftest_exp64", "la_profile_enable", "la_profile_select",
+    "la_calibrate_mfma", "la_calibrate_mfma_data", "la_calibrate_read", "la_calibrate_issue", "la_selftest_exp64", "la_profile_enable", "la_profile_select",
     "la_profile_collect", "la_profile_num_kernels", "la_profile_get", "la_profile_reset",
 )
 
@@ -145,6 +145,8 @@ def load(kind: Optional[str] = None) -> ctypes.CDLL:
         if kind == "bench":
             lib.la_calibrate_mfma.restype = ctypes.c_int
             lib.la_calibrate_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
+            lib.la_calibrate_mfma_data.restype = ctypes.c_int
+            lib.la_calibrate_mfma_data.argtypes = lib.la_calibrate_mfma.argtypes
             lib.la_calibrate_issue.restype = ctypes.c_int
             lib.la_calibrate_issue.argtypes = [ctypes.c_int32] * 5 + [vp, vp]
             lib.la_calibrate_read.restype = ctypes.c_int
@@ -293,14 +295,16 @@ def la_kv_commit_tree(desc: la_attn_desc, k_cache, v_cache, block_tables, prefix
         raise LaError(st, "la_kv_commit_tree")
 
 
-def la_calibrate_mfma(workgroups: int, iters: int, sink) -> float:
-    """Enqueue the pure-MFMA calibration kernel; returns the launch's flop count."""
+def la_calibrate_mfma(workgroups: int, iters: int, sink, data: bool = False) -> float:
+    """Enqueue the pure-MFMA calibration kernel (data: on pseudo-random operands, la_calibrate_mfma_data); returns
+    the launch's flop count."""
     if sink.numel() < workgroups * 512:
         raise ValueError("sink must hold workgroups * 512 floats")
     flops = ctypes.c_double()
-    st = load("bench").la_calibrate_mfma(workgroups, iters, _ptr(sink), ctypes.byref(flops), _stream())
+    name = "la_calibrate_mfma_data" if data else "la_calibrate_mfma"
+    st = getattr(load("bench"), name)(workgroups, iters, _ptr(sink), ctypes.byref(flops), _stream())
     if st:
-        raise LaError(st, "la_calibrate_mfma")
+        raise LaError(st, name)
     return flops.value
 
 

@@ -20,8 +20,8 @@
 //                    B operand; row 32*db + m of the LDS tile holds head-dim column
 //                    4*m + db, so that consecutive lanes of the transposing writes hit
 //                    consecutive rows and the four db accumulators of a lane are
-//                    adjacent columns; the fragment reads are bank-conflict free, the
-//                    8-byte writes are four-way conflicted at the 144-byte row pitch),
+//                    adjacent columns; fragment reads and staging writes are bank-conflict
+//                    free, see v_piece_of and k_chunk_at),
 //                    B = P^T (registers, bf16)
 // Everything is kept in log2 units: p = 2^(s*c - m).
 #include <mutex>
@@ -52,6 +52,24 @@ struct TileSrc {
   int limit;                       // keys >= limit are zero filled
 };
 
+// With an fp8 cache, K rows in LDS hold their sixteen 16-byte chunks (eight head-dim columns each) in the order even
+// chunks, odd chunks: position q holds chunk k_chunk_at(q).  A thread staging an fp8 row piece owns chunks 2p and 2p+1, and its two 16-byte
+// stores go to positions p and 8 + p: eight consecutive lanes then write 128 contiguous bytes, which is what the LDS
+// takes per cycle (at positions 2p and 2p + 1 lanes p and p + 4 met on the same banks).  The contraction runs over the
+// head dimension, so the order is free as long as Q's fragments follow it (they are loaded in the same order).
+__device__ __forceinline__ constexpr int k_chunk_at(int q) { return ((q & 7) << 1) | (q >> 3); }
+
+// Which V piece a staging thread owns: key quad kq (keys 4kq .. 4kq+3) and column quad `piece` (columns 4 piece ..
+// +3) of element idx = tid + NT*e.  The transposing LDS stores write eight bytes per lane to row `piece` (+ a
+// constant) at the quad's place in the row.  LDS writes are served 128 bytes (16 lanes of eight bytes) per cycle over
+// 32 four-byte banks, and at the 144-byte row pitch row r+8 falls on the banks of row r: 16 lanes cover the banks
+// exactly when they are 8 consecutive rows times the two halves of a 16-byte chunk (key quads kq and kq ^ 2).
+// (Measured with an in-bounds probe: 16 consecutive rows per 16 lanes take 8 cycles per store, this order 4.)
+__device__ __forceinline__ void v_piece_of(int idx, int &kq, int &piece) {
+  piece = (idx & 7) | (((idx >> 4) & 3) << 3);
+  kq = (((idx >> 3) & 1) << 1) | ((idx >> 6) & 1) | ((idx >> 7) << 2);
+}
+
 // Staging registers of one K tile and one V tile per thread: 16-byte pieces of K rows; of V, four consecutive
 // head-dim columns (4 bytes fp8, 8 bytes bf16) of the four keys of a key quad.
 template <bool FP8, int NT>
@@ -79,7 +97,9 @@ __device__ __forceinline__ const uint8_t *key_row(const AttnParams &p, const Til
 
 // Global -> registers.  FULL: every key of the tile is below s.limit.  Otherwise addresses are clamped to the
 // last valid key and the values zeroed, so the loads stay unconditional and in bounds.
-template <bool FP8, bool PREFIX, bool FULL, int NT>
+//   KPERM (bf16 tiles): the tile goes to LDS in the chunk order of fp8 tiles (k_chunk_at), because it shares Q's
+//   fragments with an fp8 cache; a thread then fetches the chunk of the LDS position it writes.
+template <bool FP8, bool PREFIX, bool FULL, int NT, bool KPERM = false>
 __device__ __forceinline__ void tile_load(const AttnParams &p, const TileSrc &s, int tid, TileRegs<FP8, NT> &r) {
   constexpr int k_piece_shift = FP8 ? 3 : 4;  // 16-byte pieces per key row: 8 (fp8) or 16 (bf16)
 #pragma unroll
@@ -87,7 +107,9 @@ __device__ __forceinline__ void tile_load(const AttnParams &p, const TileSrc &s,
     const int idx = tid + NT * e;
     const int tok = s.first + (idx >> k_piece_shift);
     const int tc = FULL ? tok : min(tok, s.limit - 1);
-    u32x4 val = *(const u32x4 *)(key_row<FP8, PREFIX>(p, s, s.k_base, tc) + (idx & ((1 << k_piece_shift) - 1)) * 16);
+    const int piece = idx & ((1 << k_piece_shift) - 1);
+    u32x4 val =
+        *(const u32x4 *)(key_row<FP8, PREFIX>(p, s, s.k_base, tc) + ((FP8 || !KPERM) ? piece : k_chunk_at(piece)) * 16);
     if (!FULL && tok >= s.limit) val = u32x4{0, 0, 0, 0};
     r.k[e] = val;
   }
@@ -95,8 +117,8 @@ __device__ __forceinline__ void tile_load(const AttnParams &p, const TileSrc &s,
 #pragma unroll
   for (int e = 0; e < TileRegs<FP8, NT>::kNV; ++e) {
     const int idx = tid + NT * e;
-    const int kq = idx >> 5;            // 32 pieces of four columns per key row
-    const int piece = idx & 31;
+    int kq, piece;                      // 32 pieces of four columns per key row
+    v_piece_of(idx, kq, piece);
     const int tok0 = s.first + 4 * kq;  // the four keys of a quad share a cache block (block_size % 16 == 0)
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -145,9 +167,11 @@ struct PrefixLoader {
 #pragma unroll
     for (int e = 0; e < kNV; ++e) {
       const int idx = tid + NT * e;
-      const int tl = 4 * (idx >> 5);
+      int kq, piece;
+      v_piece_of(idx, kq, piece);
+      const int tl = 4 * kq;
       slot_v[e] = tl >> shift;
-      base_v[e] = s.v_base + (size_t)(tl & bs_mask) * row_bytes + (idx & 31) * 4 * kVW;
+      base_v[e] = s.v_base + (size_t)(tl & bs_mask) * row_bytes + piece * 4 * kVW;
     }
   }
   // `first`: first token of the tile (a multiple of 64, every key of the tile valid)
@@ -210,9 +234,9 @@ __device__ __forceinline__ void tile_store_k(uint8_t *stage, int tid, const Tile
         out[2 * w] = fp8x2_to_bf16x2<false>(word);
         out[2 * w + 1] = fp8x2_to_bf16x2<true>(word);
       }
-      uint8_t *dst = kt + (idx >> 3) * kKRow + (idx & 7) * 32;
+      uint8_t *dst = kt + (idx >> 3) * kKRow + (idx & 7) * 16;  // chunks 2p, 2p+1 -> positions p, 8 + p
       *(u32x4 *)(dst) = u32x4{out[0], out[1], out[2], out[3]};
-      *(u32x4 *)(dst + 16) = u32x4{out[4], out[5], out[6], out[7]};
+      *(u32x4 *)(dst + 128) = u32x4{out[4], out[5], out[6], out[7]};
     }
   }
 }
@@ -223,8 +247,9 @@ __device__ __forceinline__ void tile_store_v(uint8_t *stage, int tid, const Tile
 #pragma unroll
   for (int e = 0; e < TileRegs<FP8, NT>::kNV; ++e) {
     const int idx = tid + NT * e;
-    const int kq = idx >> 5;
-    const int d0 = 4 * (idx & 31);
+    int kq, piece;
+    v_piece_of(idx, kq, piece);
+    const int d0 = 4 * piece;
     // of key c: the bf16 pair (d0 + 2 HALF, d0 + 2 HALF + 1).  Columns d0..d0+3 live in rows (d0/4) + 32*{0,1,2,3}:
     // consecutive lanes write consecutive rows
     uint32_t w[4];
@@ -688,7 +713,8 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
         (const uint8_t *)p.q + (((size_t)b * gl + st.row_tok[rb]) * p.Hq + kvh * p.G + (rr % p.G)) * (size_t)(kD * 2);
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
-      u32x4 v = *(const u32x4 *)(qrow + (16 * t + 8 * lh) * 2);
+      // the chunk K holds at position 2t + lh
+      u32x4 v = *(const u32x4 *)(qrow + (KV_FP8 ? k_chunk_at(2 * t + lh) : 2 * t + lh) * 16);
       if (r >= p.R) v = u32x4{0, 0, 0, 0};
 #pragma unroll
       for (int w = 0; w < 4; ++w) {  // bf16 pair -> fp32, times the prefix scale, back to bf16 (round to nearest even)
@@ -976,7 +1002,7 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
         if (__builtin_amdgcn_ballot_w64(tok < p.C && ((seen_any >> seg) & 1)) == 0) continue;
         TileRegs<BR_FP8, NT> regs;
         pool.first = first;
-        tile_load<BR_FP8, false, false, NT>(p, pool, tid, regs);
+        tile_load<BR_FP8, false, false, NT, KV_FP8>(p, pool, tid, regs);
         tile_store<BR_FP8, NT>(lds, tid, regs);
         __syncthreads();
         if (active)
@@ -1013,7 +1039,7 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
   auto load_extra = [&](int it) {
     TileSrc src = it < n_chain ? chn : brs;
     src.first = it < n_chain ? it * kTileN : tk0 + (it - n_chain) * kTileN;
-    tile_load<BR_FP8, false, false, NT>(p, src, tid, bregs);
+    tile_load<BR_FP8, false, false, NT, KV_FP8>(p, src, tid, bregs);
     return src.first;
   };
   int first_cur = n_chain + n_priv > 0 ? load_extra(0) : 0;

@@ -40,6 +40,44 @@ __global__ __launch_bounds__(512) void calib_mfma_kernel(float *sink, int iters)
   sink[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
 }
 
+// The same loop on operands that look like data: eight operand pairs per lane, every element a different
+// pseudo-random bf16 in (-2, 2), used in rotation, so that the operand paths and multipliers of the matrix pipeline
+// toggle as they do on a real K/V stream.  On a chip whose clock is power-managed this is the rate to compare a
+// kernel's MFMA throughput with; the loop above (nearly constant operands) shows the top clock.
+__global__ __launch_bounds__(512) void calib_mfma_data_kernel(float *sink, int iters) {
+  bf16x8 a[8], b[8];
+  uint32_t h = (blockIdx.x * 512u + threadIdx.x) * 2654435761u + 12345u;
+#pragma unroll
+  for (int k = 0; k < 8; ++k)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      h = h * 1664525u + 1013904223u;  // a linear congruential step per element; the high bits are used
+      a[k][i] = (__bf16)((float)((int)(h >> 16) - 32768) * (1.0f / 16384.0f));
+      h = h * 1664525u + 1013904223u;
+      b[k][i] = (__bf16)((float)((int)(h >> 16) - 32768) * (1.0f / 16384.0f));
+    }
+  f32x16 acc[kCalibChains];
+#pragma unroll
+  for (int c = 0; c < kCalibChains; ++c)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[c][j] = 0.f;
+  for (int it = 0; it < iters; it += 2) {  // two rounds per trip: consecutive MFMAs never share an operand
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+      for (int c = 0; c < kCalibChains; ++c) {
+        constexpr int kB[8] = {3, 4, 5, 6, 7, 0, 1, 2};
+        acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c + 4 * r], b[kB[c + 4 * r]], acc[c], 0, 0, 0);
+      }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < kCalibChains; ++c)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) s += acc[c][j];
+  sink[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
+}
+
 // Grid-stride streaming read, eight 16-byte loads in flight per thread; the data only feeds an xor.
 __global__ __launch_bounds__(256) void calib_read_kernel(const u32x4 *src, size_t n16, uint32_t *sink) {
   const size_t stride = (size_t)gridDim.x * 256;
@@ -163,6 +201,16 @@ la_status la_calibrate_mfma(int32_t workgroups, int32_t iters, float *sink, doub
   {
     ProfileScope scope(SLOT_CALIB_MFMA, (hipStream_t)hip_stream);
     hipLaunchKernelGGL(calib_mfma_kernel, dim3(workgroups), dim3(512), 0, (hipStream_t)hip_stream, sink, iters);
+  }
+  *flops = (double)workgroups * 8 * kCalibChains * (double)iters * 2.0 * 32 * 32 * 16;
+  return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
+la_status la_calibrate_mfma_data(int32_t workgroups, int32_t iters, float *sink, double *flops, void *hip_stream) {
+  if (workgroups < 1 || workgroups > (1 << 20) || iters < 2 || (iters & 1) || !sink || !flops) return LA_ERR_INVALID_ARG;
+  {
+    ProfileScope scope(SLOT_CALIB_MFMA, (hipStream_t)hip_stream);
+    hipLaunchKernelGGL(calib_mfma_data_kernel, dim3(workgroups), dim3(512), 0, (hipStream_t)hip_stream, sink, iters);
   }
   *flops = (double)workgroups * 8 * kCalibChains * (double)iters * 2.0 * 32 * 32 * 16;
   return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;

@@ -27,6 +27,12 @@ def test_calibration_kernels_run_and_are_timed():
     assert prof["calib_read"][0] == 1 and prof["calib_read"][1] > 0
     assert torch.isfinite(sink).all() and (sink != 0).any()        # the accumulators were written out
     assert int(word[0]) == 0                                       # the read kernel stores nothing on its real path
+    sink.zero_()
+    assert B.la_calibrate_mfma(64, 100, sink, data=True) == flops     # the loop on pseudo-random operands
+    torch.cuda.synchronize()
+    assert torch.isfinite(sink).all() and (sink != 0).any()
+    with pytest.raises(B.LaError):
+        B.la_calibrate_mfma(64, 101, sink, data=True)              # an odd number of rounds
     with pytest.raises(ValueError):
         B.la_calibrate_mfma(65, 10, sink)                          # sink too small for 65 workgroups
     with pytest.raises(B.LaError):
