@@ -47,6 +47,9 @@ def parse_args():
     ap.add_argument("--branch-len", type=int, default=None,
                     help="override L, the tokens per branch (branch-length sweep at the configuration's shape)")
     ap.add_argument("--gamma", type=int, default=None, help="override the configuration's number of branches")
+    ap.add_argument("--prefix-len", type=int, default=None,
+                    help="override the prefix length of every request (kernel time against prefix length: what a "
+                         "launch costs before the first key and after the last, and the marginal rate per key)")
     ap.add_argument("--kernel-shape", type=int, default=0,
                     help="force a kernel shape of the attention call (la_attn_desc.kernel_shape; 0 = the library's choice)")
     ap.add_argument("--chain-len", type=int, default=0,
@@ -410,6 +413,10 @@ def main():
     if args.gamma is not None:
         from dataclasses import replace
         attn_case = replace(attn_case, gamma=args.gamma, name=f"{attn_case.name}_g{args.gamma}")
+    if args.prefix_len is not None:
+        from dataclasses import replace
+        attn_case = replace(attn_case, prefix_lens=tuple(args.prefix_len for _ in attn_case.prefix_lens),
+                            name=f"{attn_case.name}_P{args.prefix_len}")
     if args.layers is not None:
         n_layers = args.layers
     elif args.config in (5, 6):
@@ -578,7 +585,8 @@ def main():
     # which roofline binds: arithmetic intensity against the ridge of the published peaks
     hbm_bound = flops / alg_bytes < PEAK_BF16_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
     traffic, traffic_source = read_traffic(f"attn_mfma_config{args.config}_traffic.txt") \
-        if (args.branch_len is None and args.gamma is None and C == 0 and tree is None) else (None, "no summary for this variant")
+        if (args.branch_len is None and args.gamma is None and args.prefix_len is None and C == 0 and tree is None) \
+        else (None, "no summary for this variant")
     kernel_name = ("attn_mfma_kernel" if plan["kernel_shape"] < 3 else
                    "attn_stream_kernel" if plan["kernel_shape"] < 6 else "attn_stream16_kernel")
     attn_ms = sum(prof_all[k][1] for k in ("attn_mfma", "attn_merge"))

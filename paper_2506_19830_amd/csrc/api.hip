@@ -152,7 +152,7 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, bool
   // Few long chunks keep the partial traffic small, many short ones fill the chip when there are few rows.
   // A request's key tiles are dealt out evenly over its chunks (attn_chunk_range); the workgroup of the last chunk
   // also runs the branch-private tiles (masked, general form: about three prefix tiles each in the row-tile
-  // shapes, two in the streaming shapes), which count as `last_short` tiles of its share.
+  // shapes, whole pipeline steps in the streaming shapes), which count as `last_short` tiles of its share.
   double best_cost = 0.0;
   int best_len = 0, best_shape = -1, best_short = 0;
   const int64_t T = (max_p + 63) / 64;
@@ -163,7 +163,10 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, bool
     const int64_t base_wgs = (int64_t)d->num_kv_heads * ((R + si.tile_m - 1) / si.tile_m);
     const int priv_tokens = si.tile_m / G + d->branch_len < d->gamma * d->branch_len ? si.tile_m / G + d->branch_len
                                                                                      : d->gamma * d->branch_len;
-    const int last_short = (si.stream ? 2 : 3) * ((priv_tokens + 63) / 64);
+    // (a streaming shape advances whole steps: the private tiles are steps of their own, so the last chunk gets as
+    // many prefix steps fewer, or its workgroup would finish a step after all the others)
+    const int priv_tiles = (priv_tokens + 63) / 64, step_tiles = si.step_keys / 64;
+    const int last_short = si.stream ? step_tiles * ((priv_tiles + step_tiles - 1) / step_tiles) : 3 * priv_tiles;
     const int64_t slots = (int64_t)num_cus() * si.per_cu;
     // the block ids of one chunk live in LDS (-2: a chunk need not start on a block boundary)
     const int blk_cap = si.stream ? attn_stream_max_chunk_blocks() : attn_mfma_max_chunk_blocks();

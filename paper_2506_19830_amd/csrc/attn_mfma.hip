@@ -486,7 +486,8 @@ constexpr int kAhead = 3;  // LDS fragment reads run this many MFMAs of their ki
 struct PipeCarry {
   f32x16 s0[1];      // S^T of key block 0 of the tile about to be reduced (its MFMAs ran during the previous tile)
   float bs0;         // the base s0 was started from
-  bool stale0;       // wavefront-uniform: the base has moved since s0 was started (or there is none yet)
+  uint64_t stale0;   // all ones or zero (a lane mask, so that it stays in scalar registers): the base has moved since
+                     // s0 was started, or there is none yet
   uint32_t pq[1][8]; // P^T of key block 1 of the previous tile, not yet multiplied into O (zero before the first)
   bf16x8 kf[kAhead]; // the first K fragments of the block whose S^T runs in the next slot
   bf16x8 vf[kAhead]; // the first V^T fragments of the block that is multiplied into O in the next slot
@@ -591,18 +592,21 @@ __device__ __forceinline__ void pipe_tile(const uint8_t *prev, const uint8_t *cu
   const float base_a = st.base[0];
   pipe_slot<true, NEXT, true, 3>(cur + k_lane + 32 * kKRow, prev + v_lane + 64, next + k_lane, cur + v_lane, cy.kf, cy.vf,
                               st.qf[0], st.negb[0], s1[0], cy.s0[0], cy.pq[0], st.o, p0[0], acc0, hook_a);
-  bool raised_a = false;
-  const bool trig_a = __builtin_amdgcn_ballot_w64(acc0 > kTrigger) != 0;
-  if (cy.stale0 | trig_a) raised_a = pipe_redo_block(cy.s0, cy.bs0, st, p0, acc0);
+  // (the rare-path decisions as 64-bit lane masks: one compare, one scalar or, one branch)
+  uint64_t raised_a = 0;
+  const uint64_t trig_a = __builtin_amdgcn_ballot_w64(acc0 > kTrigger);
+  if ((cy.stale0 | trig_a) != 0) raised_a = pipe_redo_block(cy.s0, cy.bs0, st, p0, acc0) ? ~0ull : 0ull;
+  raised_a = (uint64_t)(int64_t)(int32_t)__builtin_amdgcn_readfirstlane((uint32_t)raised_a);  // (uniform: keep it scalar)
   st.l_run[0] += acc0;
   // ---- slot B
   const float base_b = st.base[0];
   f32x16 s0n[1];
   pipe_slot<NEXT, NEXT, true, 1>(next + k_lane, cur + v_lane, next + k_lane + 32 * kKRow, cur + v_lane + 64, cy.kf, cy.vf,
                               st.qf[0], st.negb[0], s0n[0], s1[0], p0[0], st.o, p1[0], acc1, hook_b);
-  bool raised_b = false;
-  const bool trig_b = __builtin_amdgcn_ballot_w64(acc1 > kTrigger) != 0;
-  if (raised_a | trig_b) raised_b = pipe_redo_block(s1, base_a, st, p1, acc1);
+  uint64_t raised_b = 0;
+  const uint64_t trig_b = __builtin_amdgcn_ballot_w64(acc1 > kTrigger);
+  if ((raised_a | trig_b) != 0) raised_b = pipe_redo_block(s1, base_a, st, p1, acc1) ? ~0ull : 0ull;
+  raised_b = (uint64_t)(int64_t)(int32_t)__builtin_amdgcn_readfirstlane((uint32_t)raised_b);
   st.l_run[0] += acc1;
   if constexpr (NEXT) cy.s0[0] = s0n[0];
   cy.bs0 = base_b;
@@ -772,7 +776,7 @@ __global__ __launch_bounds__(64 * NW, (NW * RB <= 4) ? 2 : 1) void attn_mfma_ker
           cy.vf[t] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(vrow + 64 + (t & 3) * 32 * kVRow + (t >> 2) * 32));
         }
         cy.bs0 = 0.f;
-        cy.stale0 = true;
+        cy.stale0 = ~0ull;
 #pragma unroll
         for (int j = 0; j < 8; ++j) cy.pq[0][j] = 0u;
       }
