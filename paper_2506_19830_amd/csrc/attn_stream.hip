@@ -81,6 +81,12 @@ __device__ __forceinline__ void load_lds16(const void *src, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "m0");
 }
 
+// the same with the address as a wavefront-uniform 64-bit base (scalar registers) plus a 32-bit byte offset per lane
+__device__ __forceinline__ void load_lds16(const void *base, uint32_t lane_off, uint32_t lds_addr) {
+  lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(base), "s"(lds_addr) : "m0");
+}
+
 // eight fp8 (two words) -> eight bf16
 __device__ __forceinline__ bf16x8 widen8(uint32_t w0, uint32_t w1) {
   u32x4 v = {fp8x2_to_bf16x2<false>(w0), fp8x2_to_bf16x2<true>(w0), fp8x2_to_bf16x2<false>(w1),
@@ -213,23 +219,15 @@ __device__ __forceinline__ bool stream_redo_block(const f32x16 (&s)[1], float bi
   return raised;
 }
 
-//   ISSUE: the wavefront's direct loads of a later (full prefix) step are issued between the MFMAs, one every
-//   32 / IPW of them, instead of in one run before the tile: `ld`, `slot`, `first0` as for StreamLoader::issue.
-template <bool ISSUE, typename Loader>
 __device__ __forceinline__ void stream_tile_fast(const uint8_t *kt, const uint8_t *qfrag, RowState<1> &st,
-                                                 const int (&koff)[4], const int (&voff)[4], const Loader &ld, int slot,
-                                                 int first0) {
-  constexpr int kIssueEvery = 32 / Loader::kLoadsPerStep;
-  // per MFMA: this wavefront's share of the next loads, and an issue priority that falls with progress through the
-  // tile, so that of the two wavefronts of a SIMD the one that is behind wins the arbitration
+                                                 const int (&koff)[4], const int (&voff)[4]) {
+  // per MFMA: an issue priority that falls with progress through the tile, so that of the two wavefronts of a SIMD
+  // the one that is behind wins the arbitration
   auto group_extra = [&](int g) __attribute__((always_inline)) {
     if (g == 0) __builtin_amdgcn_s_setprio(3);
     if (g == 8) __builtin_amdgcn_s_setprio(2);
     if (g == 16) __builtin_amdgcn_s_setprio(1);
     if (g == 24) __builtin_amdgcn_s_setprio(0);
-    if constexpr (ISSUE) {
-      if (g % kIssueEvery == 0) ld.template issue_one<true, false>(g / kIssueEvery, slot, first0, 0);
-    }
   };
   const uint8_t *vt = kt + kHalfBytes;
   // the 32 fragment reads of the tile in the order of their use:
@@ -338,8 +336,9 @@ struct StreamLoader {
   int first_lb, ident, shift, bs_mask;
   uint32_t blk_stride, br_stride;  // bytes between cache blocks / between branch tokens
   const uint8_t *k_pre, *v_pre, *k_br, *v_br;
-  static constexpr int kLoadsPerStep = IPW;
   int key[IPW], goff[IPW];       // per lane: key inside the tile, byte offset inside the key row
+  const int32_t *table;          // global: the request's block table (paged), or null
+  uint32_t row_off;              // per lane: byte offset of its key row inside the G::kRows rows of a load
 
   __device__ __forceinline__ void init_lane(int lane) {
 #pragma unroll
@@ -350,15 +349,35 @@ struct StreamLoader {
       key[j] = k;
       goff[j] = ((lane % G::kPieces) ^ swz<FP8>(k, half)) * 16;
     }
+    row_off = (uint32_t)(lane / G::kPieces) * G::kRow;
+  }
+  // Load j of a step all of whose keys are prefix keys.  The G::kRows key rows of a load start at a multiple of
+  // G::kRows tokens and a cache block holds a multiple of 16, so they lie in one block: block id and address base are
+  // wavefront-uniform and are formed by the scalar unit (the block id by a scalar load from the table), which leaves
+  // the vector ALU -- what the tile's conversions are bound by -- one addition per load.
+  __device__ __forceinline__ void issue_full_prefix(int j, int slot, int first0) const {
+    typedef const __attribute__((address_space(4))) int32_t *cint_ptr;
+    const int ii = wave * IPW + j;
+    const int tile = ii / (2 * G::kLoadsPerHalf), half = (ii / G::kLoadsPerHalf) & 1, r = ii % G::kLoadsPerHalf;
+    const int tok0 = __builtin_amdgcn_readfirstlane(first0 + tile * kTileN + G::kRows * r);
+    const int lb = tok0 >> shift;
+    const uint32_t b = table ? (uint32_t)((cint_ptr)(uintptr_t)table)[lb] : (uint32_t)(ident + lb);
+    const uint8_t *base = (half ? v_pre : k_pre) + ((uint64_t)b * blk_stride + (uint32_t)(tok0 & bs_mask) * G::kRow);
+    load_lds16(base, row_off + (uint32_t)goff[j], ring + slot * (KSL * G::kTile) + tile * G::kTile + half * G::kHalf + r * 1024);
   }
   // PREFIX: cache tokens first0 .. (through the block table); else branch tokens.  CLAMP: tokens above `last`
   // repeat token `last`.
   template <bool PREFIX, bool CLAMP>
   __device__ __forceinline__ void issue(int slot, int first0, int last) const {
 #pragma unroll
-    for (int j = 0; j < IPW; ++j) issue_one<PREFIX, CLAMP>(j, slot, first0, last);
+    for (int j = 0; j < IPW; ++j) {
+      if constexpr (PREFIX && !CLAMP)
+        issue_full_prefix(j, slot, first0);
+      else
+        issue_one<PREFIX, CLAMP>(j, slot, first0, last);
+    }
   }
-  // load j (0 .. IPW-1) of the step alone, for a caller that spreads a step's loads between other work
+  // load j (0 .. IPW-1) of a step in the general form (per-lane addresses: clamped tokens, branch tokens)
   template <bool PREFIX, bool CLAMP>
   __device__ __forceinline__ void issue_one(int j, int slot, int first0, int last) const {
     const uint32_t stage = ring + slot * (KSL * G::kTile);
@@ -467,7 +486,7 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnPara
   const size_t br_off = ((size_t)b * gl * p.Hkv + kvh) * kRowBytes;
   StreamLoader<KSL, NST, IPW> ld;
   ld.ring = lds0 + S::kRingOff, ld.wave = wave;
-  ld.blk = table ? blk_lds : nullptr;
+  ld.blk = table ? blk_lds : nullptr, ld.table = table;
   ld.first_lb = first_lb, ld.ident = b * p.max_blocks, ld.shift = p.block_shift, ld.bs_mask = p.block_size - 1;
   ld.blk_stride = (uint32_t)((p.Hkv << p.block_shift) * kRowBytes), ld.br_stride = (uint32_t)(p.Hkv * kRowBytes);
   ld.k_pre = (const uint8_t *)p.k_cache + ((size_t)kvh << p.block_shift) * kRowBytes;
@@ -529,12 +548,8 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnPara
     // own loads of this step have landed (the steps issued after it may still be in flight) ...
     wait_later<IPW, NST - 2>(min(n_steps - 1, step + NST - 2) - step);
     __builtin_amdgcn_s_barrier();  // ... and so have everyone else's; the slots read in the previous step are free
-    // the loads of step + NST - 1: between the MFMAs of this step's tile where both are plain full prefix steps, in
-    // one run here otherwise
-    const int nxt = step + NST - 1;
-    const bool tile_full = step < n_pre_steps && k_begin + (step * KSL + ks + 1) * kTileN <= k_end;
-    const bool inline_issue = active && tile_full && nxt < n_full_steps && step > 0;
-    if (nxt < n_steps && !inline_issue) issue(nxt);
+    // the loads of step + NST - 1, in one run: for a full prefix step they are scalar work (issue_full_prefix)
+    if (step + NST - 1 < n_steps) issue(step + NST - 1);
     if (step == 0) {
       // The Q fragments have landed (they were requested before any K/V): multiply by the prefix score scale (log2
       // units, k_scale folded in), round to bf16 again and put them back, each key slice of the row block a share
@@ -559,10 +574,8 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnPara
     const uint8_t *qfrag = lds + rb * 8192 + lane * 16;
     if (step < n_pre_steps) {
       const int first = k_begin + (step * KSL + ks) * kTileN;
-      if (inline_issue)
-        stream_tile_fast<true>(kt, qfrag, st, koff, voff, ld, nxt % NST, k_begin + nxt * (KSL * kTileN));
-      else if (first + kTileN <= k_end)
-        stream_tile_fast<false>(kt, qfrag, st, koff, voff, ld, 0, 0);
+      if (first + kTileN <= k_end)
+        stream_tile_fast(kt, qfrag, st, koff, voff);
       else if (first < k_end)
         stream_tile<MASK_TAIL>(kt, qfrag, st, koff, voff, lh, first, k_end);
     } else {
@@ -817,7 +830,7 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream16_kernel(const AttnPa
   const size_t br_off = ((size_t)b * gl * p.Hkv + kvh) * G::kRow;
   StreamLoader<KSL, NST, IPW, false> ld;
   ld.ring = lds0, ld.wave = wave;
-  ld.blk = table ? blk_lds : nullptr;
+  ld.blk = table ? blk_lds : nullptr, ld.table = table;
   ld.first_lb = first_lb, ld.ident = b * p.max_blocks, ld.shift = p.block_shift, ld.bs_mask = p.block_size - 1;
   ld.blk_stride = (uint32_t)((p.Hkv << p.block_shift) * G::kRow), ld.br_stride = (uint32_t)(p.Hkv * G::kRow);
   ld.k_pre = (const uint8_t *)p.k_cache + ((size_t)kvh << p.block_shift) * G::kRow;
