@@ -42,6 +42,8 @@ struct ShapeInfo {
   int per_cu;      // workgroups that share a CU
   int step_keys;   // keys a workgroup advances per pipeline step
   double t_step;   // microseconds per step of one workgroup with the CU shared by per_cu (fitted)
+  double t_step_shared;  // the same when several row tiles stream the same keys (streaming shapes: arithmetic-bound
+                         // steps; with one row tile a step is bound by its share of the HBM stream)
   double t_fixed;  // microseconds of start-up and write-out per workgroup (fitted)
 };
 int num_shapes() { return attn_mfma_num_shapes() + attn_stream_num_shapes(); }
@@ -50,7 +52,7 @@ ShapeInfo shape_info(int shape) {
   if (shape < attn_mfma_num_shapes()) {
     s.stream = false, s.local = shape;
     s.tile_m = attn_mfma_tile_m(shape), s.per_cu = attn_mfma_wgs_per_cu(shape), s.step_keys = 64;
-    s.t_step = s.per_cu > 1 ? 2.25 : 1.87;
+    s.t_step = s.t_step_shared = s.per_cu > 1 ? 2.25 : 1.87;
     s.t_fixed = s.per_cu > 1 ? 8.0 : 9.0;
   } else {
     s.stream = true, s.local = shape - attn_mfma_num_shapes();
@@ -59,10 +61,12 @@ ShapeInfo shape_info(int shape) {
     // every wavefront reduces one 64-key tile for its 32 rows per step, whatever the shape: the time of a step is
     // the time of two such units on one SIMD
     s.fp8 = attn_stream_shape_is_fp8(s.local);
-    if (s.fp8)
+    if (s.fp8) {
       s.t_step = s.tile_m == 64 ? 3.0 : s.tile_m == 128 ? 2.6 : 2.8;
-    else
-      s.t_step = s.tile_m == 256 ? 2.45 : 2.6;
+      s.t_step_shared = s.tile_m == 64 ? 2.5 : s.tile_m == 128 ? 2.3 : 2.1;
+    } else {
+      s.t_step = s.t_step_shared = s.tile_m == 256 ? 2.45 : 2.6;
+    }
     s.t_fixed = 5.0;
   }
   return s;
@@ -185,7 +189,8 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, bool
       const int64_t n_max = attn_num_chunks((int)max_p, (int)len);
       const int64_t wg_tiles = (T + last_short + n_max - 1) / n_max;  // of the longest request
       const int64_t wg_steps = (wg_tiles * 64 + si.step_keys - 1) / si.step_keys;
-      const double cost = (double)rounds * ((double)wg_steps * si.t_step + si.t_fixed) + merge_us;
+      const double t_step = R > si.tile_m ? si.t_step_shared : si.t_step;
+      const double cost = (double)rounds * ((double)wg_steps * t_step + si.t_fixed) + merge_us;
       if (best_shape < 0 || cost < best_cost)
         best_cost = cost, best_len = (int)len, best_shape = shape, best_short = last_short;
       if (len <= 64 || d->kv_split_tokens) break;
