@@ -64,6 +64,34 @@ LA_API la_status la_calibrate_issue(int32_t mix, int32_t mix_second, int32_t wav
  * ------------------------------------------------------------------------- */
 LA_API la_status la_selftest_exp64(const double *y, double *out, size_t n, void *hip_stream);
 
+/* ------------------------------------------------------------------------- *
+ *  Index checks (debug aid).  The compute calls trust the indices the caller
+ *  hands them -- cache block ids and drafted token ids are not range-checked
+ *  on the device -- and a checked build of an application can run these two
+ *  scans in front of them.  Each only enqueues small kernels on hip_stream and
+ *  writes three int32 to `report` (dev): the number of offending entries, and
+ *  the two coordinates of one of them (any one; -1, -1 when there is none).
+ *  Read `report` after the stream has been synchronised.
+ *
+ *  la_check_block_tables: the entries of block_tables (dev
+ *  [num_requests, max_blocks_per_request]) that a call with these prefix
+ *  lengths plus `extra_tokens` appended tokens per request would touch, i.e.
+ *  logical blocks 0 .. ceil((P_b + extra_tokens) / block_size) - 1 of request
+ *  b; an entry offends when it is outside [0, num_cache_blocks).  Coordinates:
+ *  request, logical block.  block_tables == NULL (contiguous cache): the
+ *  identity ids b*max_blocks + j are checked against num_cache_blocks instead.
+ *  LA_ERR_INVALID_ARG for a bad descriptor, a prefix (plus extra tokens) longer
+ *  than max_blocks_per_request blocks, extra_tokens < 0, num_cache_blocks < 0.
+ *
+ *  la_check_draft_tokens: draft_tokens (dev [num_branches, num_draft]); an
+ *  entry offends when it is outside [0, vocab).  Coordinates: branch, position.
+ * ------------------------------------------------------------------------- */
+LA_API la_status la_check_block_tables(const la_attn_desc *desc, const int32_t *block_tables,
+                                       const int32_t *prefix_lens_host, int32_t extra_tokens,
+                                       int64_t num_cache_blocks, int32_t *report, void *hip_stream);
+LA_API la_status la_check_draft_tokens(const la_accept_desc *desc, const int32_t *draft_tokens, int32_t *report,
+                                       void *hip_stream);
+
 /* Per-kernel timing for benchmarks.  While enabled, every kernel the library
  * launches is bracketed by HIP events on the caller's stream (process-wide
  * state, not thread-safe; at most LA_PROFILE_MAX_RECORDS launches are kept,

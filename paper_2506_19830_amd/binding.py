@@ -31,7 +31,8 @@ EXPORTED_SYMBOLS = (
 )
 # what libla_verify_bench.so exports on top of those (la_verify_bench.h)
 BENCH_SYMBOLS = (
-    "la_calibrate_mfma", "la_calibrate_mfma_data", "la_calibrate_read", "la_calibrate_issue", "la_selftest_exp64", "la_profile_enable", "la_profile_select",
+    "la_calibrate_mfma", "la_calibrate_mfma_data", "la_calibrate_read", "la_calibrate_issue", "la_selftest_exp64", "la_check_block_tables", "la_check_draft_tokens",
+    "la_profile_enable", "la_profile_select",
     "la_profile_collect", "la_profile_num_kernels", "la_profile_get", "la_profile_reset",
 )
 
@@ -153,6 +154,11 @@ def load(kind: Optional[str] = None) -> ctypes.CDLL:
             lib.la_calibrate_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
             lib.la_selftest_exp64.restype = ctypes.c_int
             lib.la_selftest_exp64.argtypes = [vp, vp, ctypes.c_size_t, vp]
+            lib.la_check_block_tables.restype = ctypes.c_int
+            lib.la_check_block_tables.argtypes = [ctypes.POINTER(la_attn_desc), vp, ctypes.POINTER(ctypes.c_int32),
+                                                  ctypes.c_int32, ctypes.c_int64, vp, vp]
+            lib.la_check_draft_tokens.restype = ctypes.c_int
+            lib.la_check_draft_tokens.argtypes = [ctypes.POINTER(la_accept_desc), vp, vp, vp]
             lib.la_profile_enable.restype = ctypes.c_int
             lib.la_profile_enable.argtypes = [ctypes.c_int]
             lib.la_profile_select.restype = ctypes.c_int
@@ -329,6 +335,24 @@ def la_selftest_exp64(y, out) -> None:
     st = load("bench").la_selftest_exp64(_ptr(y), _ptr(out), ctypes.c_size_t(out.numel()), _stream())
     if st:
         raise LaError(st, "la_selftest_exp64")
+
+
+def la_check_block_tables(desc: la_attn_desc, block_tables, prefix_lens_host: Sequence[int], num_cache_blocks: int,
+                          report, extra_tokens: int = 0) -> None:
+    """Debug aid: count the block-table entries a call would touch that lie outside ``[0, num_cache_blocks)`` into
+    ``report`` (device int32[3]: count, request, logical block of one offender)."""
+    st = load("bench").la_check_block_tables(ctypes.byref(desc), _ptr(block_tables), _host_lens(prefix_lens_host),
+                                             int(extra_tokens), int(num_cache_blocks), _ptr(report), _stream())
+    if st:
+        raise LaError(st, "la_check_block_tables")
+
+
+def la_check_draft_tokens(desc: la_accept_desc, draft_tokens, report) -> None:
+    """Debug aid: count the drafted token ids outside ``[0, vocab)`` into ``report`` (device int32[3]: count, branch,
+    position of one offender)."""
+    st = load("bench").la_check_draft_tokens(ctypes.byref(desc), _ptr(draft_tokens), _ptr(report), _stream())
+    if st:
+        raise LaError(st, "la_check_draft_tokens")
 
 
 def la_step_select(verdicts, chain_vis, own_len):

@@ -119,3 +119,90 @@ la_status la_profile_reset(void) {
 }
 
 }  // extern "C"
+
+// ---- index checks (debug aid) --------------------------------------------------------------------------------
+namespace la {
+namespace {
+
+__global__ void check_reset_kernel(int32_t *report) {
+  if (threadIdx.x == 0) report[0] = 0, report[1] = -1, report[2] = -1;
+}
+
+// entry (b, j) for j < used[b] (kMaxInline requests per launch: their block counts travel in the arguments)
+struct CheckTables {
+  const int32_t *tables;  // or null: identity
+  int32_t *report;
+  long long limit;        // ids must lie in [0, limit)
+  int max_blocks, first_request, n_requests;
+  int used[64];
+};
+__global__ __launch_bounds__(256) void check_tables_kernel(const CheckTables c) {
+  const int r = blockIdx.y;
+  if (r >= c.n_requests) return;
+  const int b = c.first_request + r;
+  for (int j = blockIdx.x * 256 + threadIdx.x; j < c.used[r]; j += gridDim.x * 256) {
+    const long long id = c.tables ? (long long)c.tables[(size_t)b * c.max_blocks + j] : (long long)b * c.max_blocks + j;
+    if (id < 0 || id >= c.limit) {
+      atomicAdd(&c.report[0], 1);
+      c.report[1] = b, c.report[2] = j;  // any one offender
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void check_tokens_kernel(const int32_t *tokens, int n, int k, int vocab,
+                                                           int32_t *report) {
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) {
+    const int t = tokens[i];
+    if (t < 0 || t >= vocab) {
+      atomicAdd(&report[0], 1);
+      report[1] = i / k, report[2] = i % k;
+    }
+  }
+}
+
+}  // namespace
+}  // namespace la
+
+extern "C" {
+
+la_status la_check_block_tables(const la_attn_desc *d, const int32_t *block_tables, const int32_t *prefix_lens_host,
+                                int32_t extra_tokens, int64_t num_cache_blocks, int32_t *report, void *hip_stream) {
+  if (!d || !prefix_lens_host || !report || extra_tokens < 0 || num_cache_blocks < 0) return LA_ERR_INVALID_ARG;
+  if (d->num_requests < 1 || d->block_size < 16 || (d->block_size & (d->block_size - 1)) || d->max_blocks_per_request < 0)
+    return LA_ERR_INVALID_ARG;
+  for (int b = 0; b < d->num_requests; ++b) {
+    const int64_t need = ((int64_t)prefix_lens_host[b] + extra_tokens + d->block_size - 1) / d->block_size;
+    if (prefix_lens_host[b] < 0 || need > d->max_blocks_per_request) return LA_ERR_INVALID_ARG;
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipLaunchKernelGGL(la::check_reset_kernel, dim3(1), dim3(64), 0, st, report);
+  for (int first = 0; first < d->num_requests; first += 64) {
+    la::CheckTables c{};
+    c.tables = block_tables, c.report = report, c.limit = num_cache_blocks, c.max_blocks = d->max_blocks_per_request;
+    c.first_request = first, c.n_requests = d->num_requests - first < 64 ? d->num_requests - first : 64;
+    int most = 0;
+    for (int r = 0; r < c.n_requests; ++r) {
+      c.used[r] = (int)(((int64_t)prefix_lens_host[first + r] + extra_tokens + d->block_size - 1) / d->block_size);
+      most = c.used[r] > most ? c.used[r] : most;
+    }
+    if (most == 0) continue;
+    const int gx = (most + 255) / 256 < 64 ? (most + 255) / 256 : 64;
+    hipLaunchKernelGGL(la::check_tables_kernel, dim3(gx, c.n_requests), dim3(256), 0, st, c);
+  }
+  return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
+la_status la_check_draft_tokens(const la_accept_desc *d, const int32_t *draft_tokens, int32_t *report,
+                                void *hip_stream) {
+  if (!d || !draft_tokens || !report || d->num_branches < 1 || d->num_draft < 1 || d->vocab < 1) return LA_ERR_INVALID_ARG;
+  const int64_t n = (int64_t)d->num_branches * d->num_draft;
+  if (n > ((int64_t)1 << 30)) return LA_ERR_UNSUPPORTED;
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipLaunchKernelGGL(la::check_reset_kernel, dim3(1), dim3(64), 0, st, report);
+  const int gx = (int)((n + 255) / 256 < 256 ? (n + 255) / 256 : 256);
+  hipLaunchKernelGGL(la::check_tokens_kernel, dim3(gx), dim3(256), 0, st, draft_tokens, (int)n, d->num_draft, d->vocab,
+                     report);
+  return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
+}  // extern "C"
