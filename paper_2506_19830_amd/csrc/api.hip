@@ -62,8 +62,8 @@ ShapeInfo shape_info(int shape) {
     // the time of two such units on one SIMD
     s.fp8 = attn_stream_shape_is_fp8(s.local);
     if (s.fp8) {
-      s.t_step = s.tile_m == 64 ? 3.0 : s.tile_m == 128 ? 2.6 : 2.8;
-      s.t_step_shared = s.tile_m == 64 ? 2.5 : s.tile_m == 128 ? 2.3 : 2.1;
+      s.t_step = s.tile_m == 64 ? 3.1 : s.tile_m == 128 ? 2.4 : 3.0;
+      s.t_step_shared = s.tile_m == 64 ? 2.35 : s.tile_m == 128 ? 2.05 : 2.2;
     } else {
       s.t_step = s.t_step_shared = s.tile_m == 256 ? 2.45 : 2.6;
     }
@@ -190,7 +190,10 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, bool
       const int64_t wg_tiles = (T + last_short + n_max - 1) / n_max;  // of the longest request
       const int64_t wg_steps = (wg_tiles * 64 + si.step_keys - 1) / si.step_keys;
       const double t_step = R > si.tile_m ? si.t_step_shared : si.t_step;
-      const double cost = (double)rounds * ((double)wg_steps * t_step + si.t_fixed) + merge_us;
+      // (a streaming plan of several rounds has measured at its model cost, the row-tile shapes it competes with there
+      // -- partly filled row tiles of 256 rows -- below theirs: the margin keeps those cases with the row tiles)
+      const double cost = (double)rounds * ((double)wg_steps * t_step + si.t_fixed) * (si.stream && rounds > 1 ? 1.06 : 1.0) +
+                          merge_us;
       if (best_shape < 0 || cost < best_cost)
         best_cost = cost, best_len = (int)len, best_shape = shape, best_short = last_short;
       if (len <= 64 || d->kv_split_tokens) break;

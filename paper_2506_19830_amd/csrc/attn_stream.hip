@@ -23,6 +23,7 @@
 // swizzle is applied to the *global* address a lane fetches, and chosen such that the fragment reads
 // (16 consecutive keys at one piece for K; eight keys x two pieces for V) spread over all banks.
 #include <mutex>
+#include <type_traits>
 
 #include "attn_common.hpp"
 
@@ -94,6 +95,24 @@ __device__ __forceinline__ bf16x8 widen8(uint32_t w0, uint32_t w1) {
   return __builtin_bit_cast(bf16x8, v);
 }
 
+// S^T += K Q^T over 64 head dimensions with both operands in fp8 (v_mfma_scale_f32_32x32x64_f8f6f4, e4m3 x e4m3).
+// A lane holds 32 bytes per operand: two 16-byte pieces of its key row, and the same head dimensions of its query row.
+// The query is a two-term fp8 expansion (hi + lo, see the kernel's first step) carrying a power-of-two block scale:
+// the instruction multiplies the products of bytes 0..15 of both lane halves by the scale byte (E8M0) of lane ln, those
+// of bytes 16..31 by that of lane 32 + ln; byte U of `qscale` is the lane's scale for head dimensions 64U .. 64U + 63.
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+template <int U>
+__device__ __forceinline__ f32x16 mfma_kq(const i32x8 &k, const i32x8 &q, const f32x16 &c, int qscale) {
+  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(k, q, c, 0, 0, 0, 127, U, qscale);
+}
+// two 16-byte LDS reads as one 32-byte operand (formed here, once, so that the operand's eight registers are the ones
+// the reads write)
+__device__ __forceinline__ i32x8 read_pair(const uint8_t *a, const uint8_t *b) {
+  typedef __attribute__((ext_vector_type(4))) int i32x4;
+  const i32x4 lo = *(const i32x4 *)a, hi = *(const i32x4 *)b;
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
 // s_waitcnt vmcnt(later * IPW) for a run-time `later` in 0..MAXL (wavefront-uniform)
 template <int IPW, int MAXL>
 __device__ __forceinline__ void wait_later(int later) {
@@ -113,9 +132,10 @@ __device__ __forceinline__ void wait_later(int later) {
 //   kt        the K half of the tile; the V half lies kHalfBytes on
 //   koff[u]   lane's byte offset for piece 2u + lh of key ln (key block 0; block 1 is 32 rows on)
 //   voff[db]  lane's byte offset for the transposing read of head-dim block db (first 16 keys; the others 16 rows on)
-//   qfrag     the lane's Q fragments in LDS: fragment s (MFMA step s) lies s KiB on
+//   qfrag     the lane's Q operands in LDS, eight 16-byte chunks 1 KiB apart: chunk 4U + 2t + hf = bytes 16hf .. +16
+//             of the hi (t = 0) or lo (t = 1) term for head dimensions 64U .. 64U + 63;  qscale: their block scales
 template <int MASK>
-__device__ __forceinline__ void stream_tile(const uint8_t *kt, const uint8_t *qfrag, RowState<1> &st,
+__device__ __forceinline__ void stream_tile(const uint8_t *kt, const uint8_t *qfrag, int qscale, RowState<1> &st,
                                             const int (&koff)[4], const int (&voff)[4], int lh, int first,
                                             int limit) {
   const uint8_t *vt = kt + kHalfBytes;
@@ -144,25 +164,28 @@ __device__ __forceinline__ void stream_tile(const uint8_t *kt, const uint8_t *qf
   f32x16 s0[1], s1[1];
   uint32_t p0[1][8], p1[1][8];
   float sum0[1], sum1[1], mt[1], alpha[1], off[1];
-  // S^T = K Q^T of both key blocks: MFMA step 2u + e contracts over d = 32u + 16lh + 8e .. +8, the two halves of
-  // one 16-byte K piece; the Q fragments (already scaled, bf16) are read from LDS as they are needed rather than held
-  // in 32 registers (two wavefronts per SIMD leave 256 each).  Unmasked tiles start the accumulators from -base
-  // (== the running maximum once one exists), so that the MFMAs deliver s - m and a probability is one exponential.
+  // S^T = K Q^T of both key blocks: per 64 head dimensions one fp8 MFMA with the hi term of Q and one with the lo term,
+  // on the two K pieces 4U + lh and 4U + 2 + lh of the lane's key as they lie in LDS.  Unmasked tiles start the
+  // accumulators from -base (== the running maximum once one exists), so that the MFMAs deliver s - m and a
+  // probability is one exponential.
   {
     const float nb = kFastable ? -st.base[0] : 0.f;
     s0[0] = f32x16{nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb};
     s1[0] = s0[0];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const bf16x8 qa = *(const bf16x8 *)(qfrag + (2 * u) * 1024);
-      const bf16x8 qb = *(const bf16x8 *)(qfrag + (2 * u + 1) * 1024);
-      const u32x4 r0 = *(const u32x4 *)(kt + koff[u]);
-      const u32x4 r1 = *(const u32x4 *)(kt + 32 * kRowBytes + koff[u]);
-      s0[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen8(r0[0], r0[1]), qa, s0[0], 0, 0, 0);
-      s1[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen8(r1[0], r1[1]), qa, s1[0], 0, 0, 0);
-      s0[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen8(r0[2], r0[3]), qb, s0[0], 0, 0, 0);
-      s1[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen8(r1[2], r1[3]), qb, s1[0], 0, 0, 0);
-    }
+    auto half = [&](auto uc) __attribute__((always_inline)) {
+      constexpr int U = decltype(uc)::value;
+      const i32x8 qh = read_pair(qfrag + (4 * U) * 1024, qfrag + (4 * U + 1) * 1024);
+      const i32x8 ql = read_pair(qfrag + (4 * U + 2) * 1024, qfrag + (4 * U + 3) * 1024);
+      const i32x8 ka = read_pair(kt + koff[2 * U], kt + koff[2 * U + 1]);
+      const i32x8 kb = read_pair(kt + 32 * kRowBytes + koff[2 * U], kt + 32 * kRowBytes + koff[2 * U + 1]);
+      s0[0] = mfma_kq<U>(ka, qh, s0[0], qscale);
+      s1[0] = mfma_kq<U>(kb, qh, s1[0], qscale);
+      s0[0] = mfma_kq<U>(ka, ql, s0[0], qscale);
+      s1[0] = mfma_kq<U>(kb, ql, s1[0], qscale);
+    };
+    half(std::integral_constant<int, 0>{});
+    __builtin_amdgcn_sched_barrier(0);  // (the operands of one half at a time: this form is short of registers, not of time)
+    half(std::integral_constant<int, 1>{});
   }
   mask_block<1, MASK>(s0, st, 0, lh, first, limit);
   if constexpr (kFastable) block_probs<1, true>(s0, 1.f, off, p0, sum0);
@@ -190,17 +213,33 @@ __device__ __forceinline__ void stream_tile(const uint8_t *kt, const uint8_t *qf
   pv(1, p1);
 }
 
-// The unmasked tile again, scheduled by hand: the tile's 32 MFMAs in a fixed order (S^T of block 0; S^T of block 1 next
-// to the probabilities of block 0; O += block 0 next to the probabilities of block 1; O += block 1), each followed by
-// one LDS fragment read (issued kReadAhead MFMAs before its use), the four conversions of the next MFMA's fp8 operand,
-// its share of the exponentials, and a scheduling fence.  A wavefront issues about one instruction per seven cycles and
-// an LDS read returns after a hundred or more, so what the compiler's own order loses is waiting: every fragment must
-// already be on its way when the previous MFMA is issued.  The Q fragments are read once per tile and held while both
-// S^T chains run.  As in the row-tile kernel's pipelined loop the probabilities are formed against the base the
-// accumulators were started from, and the row sum doubles as the overflow guard (a sum above kTrigger, or no base yet:
-// the block is redone in the general form, which finds the maximum and moves the base).
+// The unmasked tile again, scheduled by hand: the tile's 24 MFMAs in a fixed order (S^T of block 0: four fp8 MFMAs of
+// 64 cycles; S^T of block 1 next to the probabilities of block 0; O += block 0, eight bf16 MFMAs of 32 cycles, next
+// to the probabilities of block 1; O += block 1), each preceded by the LDS fragment reads that MFMAs starting up to
+// kAheadCycles later need, and followed by the conversions of the next V^T operand, its share of the exponentials,
+// and a scheduling fence.  A wavefront issues about one instruction per seven cycles and an LDS read returns after a
+// hundred or more, so what the compiler's own order loses is waiting: every fragment must already be on its way
+// when the MFMAs before its use are issued.  As in the row-tile kernel's pipelined loop the probabilities are formed
+// against the base the accumulators were started from, and the row sum doubles as the overflow guard (a sum above
+// kTrigger, or no base yet: the block is redone in the general form, which finds the maximum and moves the base).
 constexpr float kTrigger = 1024.0f;
-constexpr int kReadAhead = 7;
+constexpr int kAheadCycles = 224;
+// MFMA m of the tile: 0..7 S^T (block m / 4; head dimensions 64 ((m / 2) % 2) ..; hi or lo term m % 2), 8..23 O.
+constexpr int mfma_start(int m) { return m < 8 ? 64 * m : 512 + 32 * (m - 8); }
+// fragment reads in the order of their use, and how many of them MFMA m needs:
+//   0 hi term of Q, 1 K of block 0, 2 lo term of Q (each two 16-byte reads: head dimensions 0..63);  3, 4, 5 the same
+//   for head dimensions 64..127;  6, 7 K of block 1;  8..23 V^T fragments (keys 16 t2 .. +16, head-dim block db; 4 t2 + db)
+constexpr int reads_needed(int m) {
+  constexpr int upto[8] = {2, 3, 5, 6, 7, 7, 8, 8};
+  return m < 8 ? upto[m] : m + 1;
+}
+constexpr int reads_issued_by(int g) {  // before MFMA g is issued (g = -1: none)
+  int n = 0;
+  if (g < 0) return 0;
+  for (int m = 0; m < 24; ++m)
+    if (mfma_start(m) <= mfma_start(g) + kAheadCycles) n = reads_needed(m);
+  return n;
+}
 
 __device__ __forceinline__ bool stream_redo_block(const f32x16 (&s)[1], float binit, RowState<1> &st,
                                                   uint32_t (&pc)[1][8], float &acc) {
@@ -219,41 +258,40 @@ __device__ __forceinline__ bool stream_redo_block(const f32x16 (&s)[1], float bi
   return raised;
 }
 
-__device__ __forceinline__ void stream_tile_fast(const uint8_t *kt, const uint8_t *qfrag, RowState<1> &st,
+__device__ __forceinline__ void stream_tile_fast(const uint8_t *kt, const uint8_t *qfrag, int qscale, RowState<1> &st,
                                                  const int (&koff)[4], const int (&voff)[4]) {
   // per MFMA: an issue priority that falls with progress through the tile, so that of the two wavefronts of a SIMD
   // the one that is behind wins the arbitration
   auto group_extra = [&](int g) __attribute__((always_inline)) {
     if (g == 0) __builtin_amdgcn_s_setprio(3);
-    if (g == 8) __builtin_amdgcn_s_setprio(2);
-    if (g == 16) __builtin_amdgcn_s_setprio(1);
-    if (g == 24) __builtin_amdgcn_s_setprio(0);
+    if (g == 4) __builtin_amdgcn_s_setprio(2);
+    if (g == 8) __builtin_amdgcn_s_setprio(1);
+    if (g == 16) __builtin_amdgcn_s_setprio(0);
   };
   const uint8_t *vt = kt + kHalfBytes;
-  // the 32 fragment reads of the tile in the order of their use:
-  //   0..11   q0 k00 q1 q2 k01 q3 q4 k02 q5 q6 k03 q7   (Q fragment j: MFMA step j of both chains; K piece u of
-  //           block 0: steps 2u, 2u+1 of the first chain)
-  //   12..15  K pieces 0..3 of block 1
-  //   16..23  V^T fragments of block 0 (keys 16 t2 .. +16, head-dim block db; index 4 t2 + db), 24..31 of block 1
-  bf16x8 q[8];
-  u32x4 kr[2][4];
+  i32x8 q[4];     // 2U + t: hi (t = 0) and lo term for head dimensions 64U ..
+  i32x8 kr[2][2];  // block, U: K pieces 4U + lh and 4U + 2 + lh
   u32x2 vr[2][8];
   auto read = [&](int i) __attribute__((always_inline)) {
-    if (i < 12) {
-      const int u = i / 3, w = i % 3;  // per K piece u: q(2u), k(0,u), q(2u+1)
-      if (w == 0) q[2 * u] = *(const bf16x8 *)(qfrag + (2 * u) * 1024);
-      if (w == 1) kr[0][u] = *(const u32x4 *)(kt + koff[u]);
-      if (w == 2) q[2 * u + 1] = *(const bf16x8 *)(qfrag + (2 * u + 1) * 1024);
-    } else if (i < 16) {
-      kr[1][i - 12] = *(const u32x4 *)(kt + 32 * kRowBytes + koff[i - 12]);
-    } else if (i < 32) {
-      const int kb = (i - 16) >> 3, t2 = ((i - 16) >> 2) & 1, db = (i - 16) & 3;
-      vr[kb][(i - 16) & 7] = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr8_b64_v2i32((LA_LDS i32x2 *)(
-                                                         vt + (kb * 32 + t2 * 16) * kRowBytes + voff[db])));
+    if (i < 6) {
+      const int U = i / 3, w = i % 3;
+      if (w == 0) q[2 * U] = read_pair(qfrag + (4 * U) * 1024, qfrag + (4 * U + 1) * 1024);
+      if (w == 1) kr[0][U] = read_pair(kt + koff[2 * U], kt + koff[2 * U + 1]);
+      if (w == 2) q[2 * U + 1] = read_pair(qfrag + (4 * U + 2) * 1024, qfrag + (4 * U + 3) * 1024);
+    } else if (i < 8) {
+      const int U = i - 6;
+      kr[1][U] = read_pair(kt + 32 * kRowBytes + koff[2 * U], kt + 32 * kRowBytes + koff[2 * U + 1]);
+    } else if (i < 24) {
+      const int kb = (i - 8) >> 3, t2 = ((i - 8) >> 2) & 1, db = (i - 8) & 3;
+      vr[kb][(i - 8) & 7] = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr8_b64_v2i32((LA_LDS i32x2 *)(
+                                                        vt + (kb * 32 + t2 * 16) * kRowBytes + voff[db])));
     }
   };
+  auto reads_for = [&](auto gc) __attribute__((always_inline)) {
+    constexpr int g = decltype(gc)::value;
 #pragma unroll
-  for (int i = 0; i < kReadAhead; ++i) read(i);
+    for (int i = reads_issued_by(g - 1); i < reads_issued_by(g); ++i) read(i);
+  };
   const float base_in = st.base[0];
   const float nb = -base_in;
   const f32x16 c_init = {nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb};
@@ -261,63 +299,77 @@ __device__ __forceinline__ void stream_tile_fast(const uint8_t *kt, const uint8_
   uint32_t p0[1][8], p1[1][8];
   float sum0 = 0.f, sum1 = 0.f;
   bool raised0 = false;
-  // the S^T operand of MFMA step j from K piece j / 2: its low or high eight bytes
-  auto k_operand = [&](int kb, int j) __attribute__((always_inline)) {
-    const u32x4 r = kr[kb][j >> 1];
-    return (j & 1) ? widen8(r[2], r[3]) : widen8(r[0], r[1]);
-  };
   auto softmax_share = [&](const f32x16 &sc, int pair, uint32_t (&pc)[8], float &sum) __attribute__((always_inline)) {
     const float e0 = __builtin_amdgcn_exp2f(sc[2 * pair]), e1 = __builtin_amdgcn_exp2f(sc[2 * pair + 1]);
     pc[pair] = pack_bf16(e0, e1);
     sum += e0 + e1;
     asm volatile("" : "+v"(sum), "+v"(pc[pair]));  // here, not wherever the value is first needed
   };
-#pragma unroll
-  for (int g = 0; g < 16; ++g) {  // S^T of block 0, then S^T of block 1 beside the probabilities of block 0
-    if (g + kReadAhead < 32) read(g + kReadAhead);
-    if (g < 8) {
-      s0[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_operand(0, g), q[g], g == 0 ? c_init : s0[0], 0, 0, 0);
-    } else {
-      s1[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_operand(1, g - 8), q[g - 8], g == 8 ? c_init : s1[0], 0, 0, 0);
-      softmax_share(s0[0], g - 8, p0[0], sum0);
+  // S^T MFMA m (0..7)
+  auto s_mfma = [&](auto mc) __attribute__((always_inline)) {
+    constexpr int m = decltype(mc)::value, kb = m / 4, U = (m / 2) % 2, t = m % 2;
+    f32x16 &acc = kb ? s1[0] : s0[0];
+    acc = mfma_kq<U>(kr[kb][U], q[2 * U + t], (m % 4) == 0 ? c_init : acc, qscale);
+  };
+  auto s_group = [&](auto gc) __attribute__((always_inline)) {
+    constexpr int g = decltype(gc)::value;
+    reads_for(gc);
+    s_mfma(gc);
+    if constexpr (g >= 4) {  // the probabilities of block 0 beside S^T of block 1
+      softmax_share(s0[0], 2 * (g - 4), p0[0], sum0);
+      softmax_share(s0[0], 2 * (g - 4) + 1, p0[0], sum0);
     }
     group_extra(g);
     __builtin_amdgcn_sched_barrier(0);
-  }
+  };
+  s_group(std::integral_constant<int, 0>{});
+  s_group(std::integral_constant<int, 1>{});
+  s_group(std::integral_constant<int, 2>{});
+  s_group(std::integral_constant<int, 3>{});
+  s_group(std::integral_constant<int, 4>{});
+  s_group(std::integral_constant<int, 5>{});
+  s_group(std::integral_constant<int, 6>{});
+  s_group(std::integral_constant<int, 7>{});
+  asm volatile("" : "+v"(s1[0]));  // S^T of block 1 is issued here, not after the branch below
+  auto o_group = [&](auto gc, const u32x4 &plo, const u32x4 &phi) __attribute__((always_inline)) {
+    constexpr int g = decltype(gc)::value, kb = (g - 8) / 8, u = (g - 8) % 8;
+    reads_for(gc);
+    st.o[u & 3][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen8(vr[kb][u][0], vr[kb][u][1]),
+                                                             __builtin_bit_cast(bf16x8, u < 4 ? plo : phi), st.o[u & 3][0],
+                                                             0, 0, 0);
+    if constexpr (kb == 0) softmax_share(s1[0], u, p1[0], sum1);  // the probabilities of block 1 beside O += block 0
+    group_extra(g);
+    __builtin_amdgcn_sched_barrier(0);
+  };
   {
     const bool none_yet = __builtin_amdgcn_ballot_w64(st.m_run[0] == -INFINITY) != 0;
     const bool trig = __builtin_amdgcn_ballot_w64(sum0 > kTrigger) != 0;
-    if (none_yet | trig) raised0 = stream_redo_block(s0, base_in, st, p0, sum0);
+    if (__builtin_expect(none_yet | trig, 0)) raised0 = stream_redo_block(s0, base_in, st, p0, sum0);
   }
   st.l_run[0] += sum0;
   const u32x4 pa0 = {p0[0][0], p0[0][1], p0[0][2], p0[0][3]}, pa1 = {p0[0][4], p0[0][5], p0[0][6], p0[0][7]};
-#pragma unroll
-  for (int g = 16; g < 24; ++g) {  // O += block 0 beside the probabilities of block 1
-    if (g + kReadAhead < 32) read(g + kReadAhead);
-    const int u = g - 16;
-    st.o[u & 3][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen8(vr[0][u][0], vr[0][u][1]),
-                                                             __builtin_bit_cast(bf16x8, u < 4 ? pa0 : pa1), st.o[u & 3][0],
-                                                             0, 0, 0);
-    softmax_share(s1[0], u, p1[0], sum1);
-    group_extra(g);
-    __builtin_amdgcn_sched_barrier(0);
-  }
+  o_group(std::integral_constant<int, 8>{}, pa0, pa1);
+  o_group(std::integral_constant<int, 9>{}, pa0, pa1);
+  o_group(std::integral_constant<int, 10>{}, pa0, pa1);
+  o_group(std::integral_constant<int, 11>{}, pa0, pa1);
+  o_group(std::integral_constant<int, 12>{}, pa0, pa1);
+  o_group(std::integral_constant<int, 13>{}, pa0, pa1);
+  o_group(std::integral_constant<int, 14>{}, pa0, pa1);
+  o_group(std::integral_constant<int, 15>{}, pa0, pa1);
   {
     const bool trig = __builtin_amdgcn_ballot_w64(sum1 > kTrigger) != 0;
-    if (raised0 | trig) stream_redo_block(s1, base_in, st, p1, sum1);
+    if (__builtin_expect(raised0 | trig, 0)) stream_redo_block(s1, base_in, st, p1, sum1);
   }
   st.l_run[0] += sum1;
   const u32x4 pb0 = {p1[0][0], p1[0][1], p1[0][2], p1[0][3]}, pb1 = {p1[0][4], p1[0][5], p1[0][6], p1[0][7]};
-#pragma unroll
-  for (int g = 24; g < 32; ++g) {  // O += block 1
-    if (g + kReadAhead < 32) read(g + kReadAhead);
-    const int u = g - 24;
-    st.o[u & 3][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen8(vr[1][u][0], vr[1][u][1]),
-                                                             __builtin_bit_cast(bf16x8, u < 4 ? pb0 : pb1), st.o[u & 3][0],
-                                                             0, 0, 0);
-    group_extra(g);
-    __builtin_amdgcn_sched_barrier(0);
-  }
+  o_group(std::integral_constant<int, 16>{}, pb0, pb1);
+  o_group(std::integral_constant<int, 17>{}, pb0, pb1);
+  o_group(std::integral_constant<int, 18>{}, pb0, pb1);
+  o_group(std::integral_constant<int, 19>{}, pb0, pb1);
+  o_group(std::integral_constant<int, 20>{}, pb0, pb1);
+  o_group(std::integral_constant<int, 21>{}, pb0, pb1);
+  o_group(std::integral_constant<int, 22>{}, pb0, pb1);
+  o_group(std::integral_constant<int, 23>{}, pb0, pb1);
   __builtin_amdgcn_s_setprio(0);
 }
 
@@ -405,7 +457,8 @@ struct StreamLoader {
 template <int NRB>
 struct StreamShape {
   static constexpr int KSL = kWaves / NRB;
-  static constexpr int kQBytes = NRB * 8192;         // Q of the row blocks, as MFMA fragments
+  static constexpr int kScaleOff = NRB * 8192;       // behind Q of the row blocks (MFMA operands): their block scales,
+  static constexpr int kQBytes = kScaleOff + (NRB * 512 + 1023) / 1024 * 1024;  // [row block][U][lane] words
   static constexpr int kRingOff = kQBytes;
   static constexpr int kSlots = ((152 * 1024 - kQBytes) / kTileBytes) / KSL * KSL;
   static constexpr int NST = kSlots / KSL;           // steps the ring holds
@@ -542,6 +595,70 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnPara
 #pragma unroll
     for (int j = 0; j < 16; ++j) st.o[db][0][j] = 0.f;
 
+  // ---- Q as the fp8 MFMA's operand ------------------------------------------------------------------------
+  int qscale;
+  {
+    // Q was requested before any K/V, and loads complete in order: it has landed once no more loads are outstanding
+    // than the K/V loads issued since.
+    wait_later<IPW, NST - 1>(min(NST - 1, n_steps));
+    __syncthreads();
+    // Multiply by the prefix score scale (log2 units, k_scale folded in) and rewrite it as the fp8 MFMA's operand: per
+    // block of 32 head dimensions of a row (16 in this lane, 16 in the lane 32 on) a power-of-two scale 2^E that
+    // brings the block's largest magnitude into [128, 256), then x = q' 2^-E = hi + lo + (an error below 2^-8 |x|),
+    // hi = fp8(x), lo = fp8(x - hi) -- as good as the bf16 rounding it replaces.  Each key slice of the row block
+    // converts a share of the blocks: all read, then (barrier) all write, since the new layout overlaps the old
+    // one; one more barrier publishes it.  All of this runs while the first K/V tiles are still on their way.
+    constexpr int kNB = 4 / KSL;  // blocks per wavefront; block bi = 2U + hf is fragments 2bi, 2bi + 1
+    u32x4 hi[kNB], lo[kNB];
+    int ebyte[kNB];
+#pragma unroll
+    for (int i = 0; i < kNB; ++i) {
+      const int bi = ks * kNB + i;
+      const uint8_t *at = lds + rb * 8192 + (2 * bi) * 1024 + lane * 16;
+      u32x4 va = *(const u32x4 *)at, vb = *(const u32x4 *)(at + 1024);
+      if (row >= p.R) va = vb = u32x4{0, 0, 0, 0};
+      float x[16];
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        x[2 * w] = __builtin_bit_cast(float, va[w] << 16) * c_prefix;
+        x[2 * w + 1] = __builtin_bit_cast(float, va[w] & 0xffff0000u) * c_prefix;
+        x[8 + 2 * w] = __builtin_bit_cast(float, vb[w] << 16) * c_prefix;
+        x[8 + 2 * w + 1] = __builtin_bit_cast(float, vb[w] & 0xffff0000u) * c_prefix;
+      }
+      float mx = 0.f;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) mx = fmaxf(mx, fabsf(x[j]));
+      mx = xhalf_max(mx);
+      int e = (int)((__builtin_bit_cast(uint32_t, mx) >> 23) & 255u) - 127 - 7;
+      e = mx > 0.f ? max(-100, min(100, e)) : 0;
+      ebyte[i] = 127 + e;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float x0 = __builtin_ldexpf(x[4 * w], -e), x1 = __builtin_ldexpf(x[4 * w + 1], -e);
+        const float x2 = __builtin_ldexpf(x[4 * w + 2], -e), x3 = __builtin_ldexpf(x[4 * w + 3], -e);
+        int hw = __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, 0, false);
+        hw = __builtin_amdgcn_cvt_pk_fp8_f32(x2, x3, hw, true);
+        const f32x2 b0 = __builtin_amdgcn_cvt_pk_f32_fp8(hw, false), b1 = __builtin_amdgcn_cvt_pk_f32_fp8(hw, true);
+        int lw = __builtin_amdgcn_cvt_pk_fp8_f32(x0 - b0[0], x1 - b0[1], 0, false);
+        lw = __builtin_amdgcn_cvt_pk_fp8_f32(x2 - b1[0], x3 - b1[1], lw, true);
+        hi[i][w] = (uint32_t)hw, lo[i][w] = (uint32_t)lw;
+      }
+      __builtin_amdgcn_sched_barrier(0);  // one block at a time (up to four: their temporaries would not fit together)
+    }
+    __syncthreads();
+    int32_t *sc = (int32_t *)(lds + S::kScaleOff) + rb * 128;
+#pragma unroll
+    for (int i = 0; i < kNB; ++i) {
+      const int bi = ks * kNB + i, U = bi >> 1, hf = bi & 1;
+      uint8_t *to = lds + rb * 8192 + (4 * U + hf) * 1024 + lane * 16;
+      *(u32x4 *)to = hi[i];
+      *(u32x4 *)(to + 2048) = lo[i];
+      if (lh == 0) sc[U * 64 + hf * 32 + ln] = ebyte[i];
+    }
+    __syncthreads();
+    qscale = sc[lane] | (sc[64 + lane] << 8);
+  }
+
   // ---- the pipeline -------------------------------------------------------------------------------
   const bool active = r0 + rb * 32 < p.R;
   for (int step = 0; step < n_steps; ++step) {
@@ -550,37 +667,18 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnPara
     __builtin_amdgcn_s_barrier();  // ... and so have everyone else's; the slots read in the previous step are free
     // the loads of step + NST - 1, in one run: for a full prefix step they are scalar work (issue_full_prefix)
     if (step + NST - 1 < n_steps) issue(step + NST - 1);
-    if (step == 0) {
-      // The Q fragments have landed (they were requested before any K/V): multiply by the prefix score scale (log2
-      // units, k_scale folded in), round to bf16 again and put them back, each key slice of the row block a share
-      // of the eight fragments; one more barrier makes them visible to the others.
-#pragma unroll
-      for (int i = 0; i < 8 / KSL; ++i) {
-        uint8_t *at = lds + rb * 8192 + (ks * (8 / KSL) + i) * 1024 + lane * 16;
-        u32x4 v = *(const u32x4 *)at;
-        if (row >= p.R) v = u32x4{0, 0, 0, 0};
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          const uint32_t word = v[w];
-          const uint32_t wl = word << 16, wh = word & 0xffff0000u;
-          v[w] = pack_bf16(__builtin_bit_cast(float, wl) * c_prefix, __builtin_bit_cast(float, wh) * c_prefix);
-        }
-        *(u32x4 *)at = v;
-      }
-      __syncthreads();
-    }
     if (!active) continue;
     const uint8_t *kt = lds + S::kRingOff + (step % NST) * kStepBytes + ks * kTileBytes;
     const uint8_t *qfrag = lds + rb * 8192 + lane * 16;
     if (step < n_pre_steps) {
       const int first = k_begin + (step * KSL + ks) * kTileN;
       if (first + kTileN <= k_end)
-        stream_tile_fast(kt, qfrag, st, koff, voff);
+        stream_tile_fast(kt, qfrag, qscale, st, koff, voff);
       else if (first < k_end)
-        stream_tile<MASK_TAIL>(kt, qfrag, st, koff, voff, lh, first, k_end);
+        stream_tile<MASK_TAIL>(kt, qfrag, qscale, st, koff, voff, lh, first, k_end);
     } else {
       const int first = tk0 + ((step - n_pre_steps) * KSL + ks) * kTileN;
-      if (first <= t_hi) stream_tile<MASK_BRANCH>(kt, qfrag, st, koff, voff, lh, first, 0);
+      if (first <= t_hi) stream_tile<MASK_BRANCH>(kt, qfrag, qscale, st, koff, voff, lh, first, 0);
     }
   }
   wait_vmcnt<0>();  // no direct load may still be on its way to LDS when the workgroup gives its LDS back
