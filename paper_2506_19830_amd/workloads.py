@@ -90,6 +90,8 @@ class AttnCase:
     seed: int = 0
     layer: int = 0               # stream offset so that layers of a sweep differ
     spare_tokens: int = 0        # cache room (mapped by the block table) behind every prefix, for the KV commit
+    late_key_shift: float = 0.0  # nats by which every score against a key from token `late_from` on (branch keys
+    late_from: int = 64          # included) lies above N(0,1): a running maximum that jumps far, late in the prefix
 
     @property
     def B(self) -> int:
@@ -213,6 +215,19 @@ def make_attention_inputs(case: AttnCase) -> Dict[str, Optional[np.ndarray]]:
     vb = _rng(c.seed, s0 + 2).standard_normal((B, c.gamma, c.L, c.Hkv, c.D), dtype=np.float32)
     kc = _rng(c.seed, s0 + 3).standard_normal((num_blocks, c.Hkv, bs, c.D), dtype=np.float32)
     vc = _rng(c.seed, s0 + 4).standard_normal((num_blocks, c.Hkv, bs, c.D), dtype=np.float32)
+
+    if c.late_key_shift != 0.0:
+        # a +-1 direction u per KV head, added to every query (of the head's group) and, times shift / sqrt(D), to the
+        # late keys: q . k * D^-1/2 gains `shift` for those keys (and noise of the usual size)
+        u = np.where(_rng(c.seed, s0 + 8).random((c.Hkv, c.D)) < 0.5, -1.0, 1.0).astype(np.float32)
+        q += np.repeat(u, c.Hq // c.Hkv, axis=0)[None, None, None]
+        ku = u * np.float32(c.late_key_shift / math.sqrt(c.D))
+        kb += ku[None, None, None]
+        for b, plen in enumerate(c.prefix_lens):
+            for t0 in range((c.late_from // bs) * bs, plen, bs):
+                blk = tables[b, t0 // bs] if tables is not None else b * c.max_blocks + t0 // bs
+                lo = max(c.late_from - t0, 0)
+                kc[blk, :, lo:bs, :] += ku[:, None, :]
 
     k_scale = v_scale = None
     if c.kv_dtype == "fp8_e4m3":

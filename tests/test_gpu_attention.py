@@ -149,6 +149,25 @@ def test_every_bf16_streaming_shape(oracle, case, shape, monkeypatch):
         check_full(oracle, case, TOL_LOWP, kv_split_tokens=split)
 
 
+@pytest.mark.parametrize("shape,kv", [(0, "fp8_e4m3"), (1, "fp8_e4m3"), (2, "fp8_e4m3"), (3, "fp8_e4m3"), (4, "fp8_e4m3"),
+                                      (0, "bf16"), (1, "bf16"), (5, "bf16"), (6, "bf16")])
+@pytest.mark.parametrize("shift", [9.0, 45.0])
+def test_running_maximum_that_jumps_late(oracle, shape, kv, shift, monkeypatch):
+    """Scores that jump by `shift` nats (13 and 65 log2 units) somewhere behind the first key tile: inside the first
+    tile's second key block, on a tile boundary, inside a later tile, and in the branch keys only.  The unmasked tiles
+    of every kernel shape form their probabilities against a base that is only moved on a rare path (a row sum above a
+    trigger: the block is redone, the maximum raised, the accumulators rescaled); N(0,1) scores never take that path
+    after the first tile, these do -- once by a little (probabilities up to 2^13 before the trigger's threshold is
+    met in the next block) and once by more than an fp32 exponential would survive without it.  The shift is common
+    to all late keys, so its own rounding error (2^-9 of 45 nats) cancels in the output; the log-sum-exp carries it."""
+    monkeypatch.setattr("gpu_util.KERNEL_SHAPE", shape + 1)
+    for i, (prefix, late_from) in enumerate((((1000,), 40), ((1000,), 64), ((2077, 333), 300), ((130,), 10 ** 6))):
+        case = W.AttnCase(f"late_jump_{late_from}", prefix, 6, 9, 40, 8, 128, "bf16", kv, kv, "bf16", paged=(i == 2),
+                          seed=90 + i, late_key_shift=shift, late_from=late_from)
+        for split in (0, 192):
+            check_full(oracle, case, TOL_LOWP, kv_split_tokens=split, lse_tol=0.1)
+
+
 def test_streaming_shape_is_refused_where_it_cannot_run(monkeypatch):
     from gpu_util import run_attention
     from paper_2506_19830_amd import binding as B

@@ -84,3 +84,19 @@ def test_point_mass_accept_recipe():
     picked = np.take_along_axis(t[:, :3, :], tok[:, :, None], axis=2)[..., 0]
     assert picked.mean() > 6.0 and abs(float(np.median(t))) < 0.5      # N(0, 3^2) + 9 at the drafted tokens
     assert c.algorithmic_bytes() == 6 * 4 * 1000 * 4
+
+
+def test_late_key_shift_raises_the_scores_of_the_late_keys():
+    case = W.AttnCase("late", (300,), 2, 3, 4, 2, 128, "bf16", "bf16", "bf16", "bf16", late_key_shift=20.0, late_from=100)
+    inp = W.make_attention_inputs(case)
+    dec = lambda bits: (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    q, kc, kb = dec(inp["q"]), dec(inp["k_cache"]), dec(inp["k_branch"])
+    keys = kc.transpose(1, 0, 2, 3).reshape(2, -1, 128)[:, :300]            # contiguous cache: [Hkv, token, D]
+    for h in range(4):
+        s = keys[h // 2] @ q[0, 1, 2, h] * case.scale                        # one query row against the prefix
+        # (the row's own noise along u moves its shift by 20 / sqrt(128) = 1.8 rms)
+        assert abs(s[100:].mean() - s[:100].mean() - 20.0) < 6.0 and s[:100].std() < 2.5 and s[100:].std() < 2.5
+        sb = kb[0, 1, :, h // 2] @ q[0, 1, 2, h] * case.scale                # and against its branch's keys
+        assert abs(sb.mean() - s[100:].mean()) < 3.0
+    plain = W.make_attention_inputs(W.AttnCase("late", (300,), 2, 3, 4, 2, 128, "bf16", "bf16", "bf16", "bf16"))
+    np.testing.assert_array_equal(plain["v_cache"], inp["v_cache"])          # nothing else moves
