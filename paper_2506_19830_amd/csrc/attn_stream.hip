@@ -77,15 +77,17 @@ __device__ __forceinline__ void wait_vmcnt() {
 // queue in every tile); the kernel orders these loads against its LDS reads itself (wait_vmcnt + s_barrier; the
 // barrier is also what keeps the compiler from moving LDS accesses across a pipeline step, so the statement needs
 // no memory clobber -- with one, every local whose address a lambda captured would be pinned to scratch memory).
+// One wait state lies between the write of M0 and the load that reads it (required on this family for LDS-DMA loads;
+// the compiler's hazard handling does not look into an assembly statement).
 __device__ __forceinline__ void load_lds16(const void *src, uint32_t lds_addr) {
   lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);  // wavefront-uniform by construction; pin it to a scalar register
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "m0");
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "m0");
 }
 
 // the same with the address as a wavefront-uniform 64-bit base (scalar registers) plus a 32-bit byte offset per lane
 __device__ __forceinline__ void load_lds16(const void *base, uint32_t lane_off, uint32_t lds_addr) {
   lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
-  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(base), "s"(lds_addr) : "m0");
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(base), "s"(lds_addr) : "m0");
 }
 
 // eight fp8 (two words) -> eight bf16
@@ -219,10 +221,17 @@ __device__ __forceinline__ void stream_tile(const uint8_t *kt, const uint8_t *qf
 // kAheadCycles later need, and followed by the conversions of the next V^T operand, its share of the exponentials,
 // and a scheduling fence.  A wavefront issues about one instruction per seven cycles and an LDS read returns after a
 // hundred or more, so what the compiler's own order loses is waiting: every fragment must already be on its way
-// when the MFMAs before its use are issued.  As in the row-tile kernel's pipelined loop the probabilities are formed
-// against the base the accumulators were started from, and the row sum doubles as the overflow guard (a sum above
-// kTrigger, or no base yet: the block is redone in the general form, which finds the maximum and moves the base).
-constexpr float kTrigger = 1024.0f;
+// when the MFMAs before its use are issued.  The probabilities are formed against the base the accumulators were
+// started from, and that base is never moved here: this function does not rescale O.  (With code that rescales O
+// reachable from the end of its S^T phase, the register allocator keeps O in other registers during the O phases than
+// during the S^T phase and the common path pays 64 register copies per tile.)  Probabilities far above 1 are no
+// problem for bf16 operands and fp32 sums; what this form cannot do is left to others:
+//   * the wavefront's first tile (no base yet; O == 0, l == 0): the base becomes the row maximum over the tile, the
+//     probabilities of block 0 are formed again against it and S^T of block 1 is shifted by it;
+//   * a row sum above kTrigger = 2^60 (a score 60 log2 units above the first tile's maximum: the fp32 range is not
+//     far): the give-up flag of the workgroup is raised, and the kernel reduces the whole chunk again in the general
+//     form, which follows the maximum and rescales.  Whatever this form has accumulated by then is discarded.
+constexpr float kTrigger = 1152921504606846976.0f;
 constexpr int kAheadCycles = 224;
 // MFMA m of the tile: 0..7 S^T (block m / 4; head dimensions 64 ((m / 2) % 2) ..; hi or lo term m % 2), 8..23 O.
 constexpr int mfma_start(int m) { return m < 8 ? 64 * m : 512 + 32 * (m - 8); }
@@ -241,25 +250,8 @@ constexpr int reads_issued_by(int g) {  // before MFMA g is issued (g = -1: none
   return n;
 }
 
-__device__ __forceinline__ bool stream_redo_block(const f32x16 (&s)[1], float binit, RowState<1> &st,
-                                                  uint32_t (&pc)[1][8], float &acc) {
-  const float bi[1] = {binit};
-  float mt[1], alpha[1], off[1], sum[1];
-  block_max<1>(s, 1.f, bi, mt);
-  const bool raised = raise_max<1>(mt, st, alpha, 0.f);
-  const float m_use = (st.m_run[0] == -INFINITY) ? 0.f : st.m_run[0];
-  if (raised) {
-    rescale<1>(st, alpha);
-    st.base[0] = m_use;
-  }
-  off[0] = binit - m_use;
-  block_probs<1, false>(s, 1.f, off, pc, sum);
-  acc = sum[0];
-  return raised;
-}
-
 __device__ __forceinline__ void stream_tile_fast(const uint8_t *kt, const uint8_t *qfrag, int qscale, RowState<1> &st,
-                                                 const int (&koff)[4], const int (&voff)[4]) {
+                                                 const int (&koff)[4], const int (&voff)[4], int32_t *give_up) {
   // per MFMA: an issue priority that falls with progress through the tile, so that of the two wavefronts of a SIMD
   // the one that is behind wins the arbitration
   auto group_extra = [&](int g) __attribute__((always_inline)) {
@@ -292,13 +284,11 @@ __device__ __forceinline__ void stream_tile_fast(const uint8_t *kt, const uint8_
 #pragma unroll
     for (int i = reads_issued_by(g - 1); i < reads_issued_by(g); ++i) read(i);
   };
-  const float base_in = st.base[0];
-  const float nb = -base_in;
+  const float nb = -st.base[0];
   const f32x16 c_init = {nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb, nb};
   f32x16 s0[1], s1[1];
   uint32_t p0[1][8], p1[1][8];
   float sum0 = 0.f, sum1 = 0.f;
-  bool raised0 = false;
   auto softmax_share = [&](const f32x16 &sc, int pair, uint32_t (&pc)[8], float &sum) __attribute__((always_inline)) {
     const float e0 = __builtin_amdgcn_exp2f(sc[2 * pair]), e1 = __builtin_amdgcn_exp2f(sc[2 * pair + 1]);
     pc[pair] = pack_bf16(e0, e1);
@@ -341,11 +331,20 @@ __device__ __forceinline__ void stream_tile_fast(const uint8_t *kt, const uint8_
     group_extra(g);
     __builtin_amdgcn_sched_barrier(0);
   };
-  {
-    const bool none_yet = __builtin_amdgcn_ballot_w64(st.m_run[0] == -INFINITY) != 0;
-    const bool trig = __builtin_amdgcn_ballot_w64(sum0 > kTrigger) != 0;
-    if (__builtin_expect(none_yet | trig, 0)) raised0 = stream_redo_block(s0, base_in, st, p0, sum0);
+  if (__builtin_expect(__builtin_amdgcn_ballot_w64(st.m_run[0] == -INFINITY) != 0, 0)) {  // (all lanes or none)
+    float m = fmaxf(s0[0][0], s1[0][0]);  // (the base is still 0: these are the scores themselves)
+#pragma unroll
+    for (int j = 1; j < 16; ++j) m = fmaxf(m, fmaxf(s0[0][j], s1[0][j]));
+    m = xhalf_max(m);
+    st.m_run[0] = m, st.base[0] = m;
+    const float off[1] = {-m};
+    float sum[1];
+    block_probs<1, false>(s0, 1.f, off, p0, sum);
+    sum0 = sum[0];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) s1[0][j] -= m;
   }
+  if (!(sum0 <= kTrigger)) *(volatile int32_t *)give_up = 1;
   st.l_run[0] += sum0;
   const u32x4 pa0 = {p0[0][0], p0[0][1], p0[0][2], p0[0][3]}, pa1 = {p0[0][4], p0[0][5], p0[0][6], p0[0][7]};
   o_group(std::integral_constant<int, 8>{}, pa0, pa1);
@@ -356,10 +355,7 @@ __device__ __forceinline__ void stream_tile_fast(const uint8_t *kt, const uint8_
   o_group(std::integral_constant<int, 13>{}, pa0, pa1);
   o_group(std::integral_constant<int, 14>{}, pa0, pa1);
   o_group(std::integral_constant<int, 15>{}, pa0, pa1);
-  {
-    const bool trig = __builtin_amdgcn_ballot_w64(sum1 > kTrigger) != 0;
-    if (__builtin_expect(raised0 | trig, 0)) stream_redo_block(s1, base_in, st, p1, sum1);
-  }
+  if (!(sum1 <= kTrigger)) *(volatile int32_t *)give_up = 1;
   st.l_run[0] += sum1;
   const u32x4 pb0 = {p1[0][0], p1[0][1], p1[0][2], p1[0][3]}, pb1 = {p1[0][4], p1[0][5], p1[0][6], p1[0][7]};
   o_group(std::integral_constant<int, 16>{}, pb0, pb1);
@@ -379,7 +375,8 @@ __device__ __forceinline__ void stream_tile_fast(const uint8_t *kt, const uint8_
 // load counter advances uniformly; where a step reaches past the end of its key range (a ragged last tile, a tile
 // slot that has no tile) the tokens are clamped to the last valid one and all addresses stay in bounds.
 // (A plain struct of values rather than a capturing lambda: captured locals would be pinned to scratch memory.)
-template <int KSL, int NST, int IPW, bool FP8 = true>
+// SBASE: full prefix steps by issue_full_prefix (the second attempt does without: less code)
+template <int KSL, int NST, int IPW, bool FP8 = true, bool SBASE = true>
 struct StreamLoader {
   using G = Geo<FP8>;
   uint32_t ring;                 // LDS address of the ring
@@ -423,7 +420,7 @@ struct StreamLoader {
   __device__ __forceinline__ void issue(int slot, int first0, int last) const {
 #pragma unroll
     for (int j = 0; j < IPW; ++j) {
-      if constexpr (PREFIX && !CLAMP)
+      if constexpr (PREFIX && !CLAMP && SBASE)
         issue_full_prefix(j, slot, first0);
       else
         issue_one<PREFIX, CLAMP>(j, slot, first0, last);
@@ -458,7 +455,8 @@ template <int NRB>
 struct StreamShape {
   static constexpr int KSL = kWaves / NRB;
   static constexpr int kScaleOff = NRB * 8192;       // behind Q of the row blocks (MFMA operands): their block scales,
-  static constexpr int kQBytes = kScaleOff + (NRB * 512 + 1023) / 1024 * 1024;  // [row block][U][lane] words
+  static constexpr int kFlagOff = kScaleOff + NRB * 512;  // [row block][U][lane] words; then the give-up flag
+  static constexpr int kQBytes = kScaleOff + (NRB * 512 + 16 + 1023) / 1024 * 1024;
   static constexpr int kRingOff = kQBytes;
   static constexpr int kSlots = ((152 * 1024 - kQBytes) / kTileBytes) / KSL * KSL;
   static constexpr int NST = kSlots / KSL;           // steps the ring holds
@@ -471,9 +469,10 @@ struct StreamShape {
   static_assert(kFoldBytes <= kLdsMax, "fold space");
 };
 
-template <int NRB>
-__global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnParams p) {
-  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+// The work of one workgroup.  GENERAL: every tile in the general form (the second attempt; see stream_tile_fast).
+// Returns false if this attempt gave up (nothing has been written then).
+template <int NRB, bool GENERAL>
+__device__ __forceinline__ bool stream_chunk(const AttnParams &p, uint8_t *lds) {
   using S = StreamShape<NRB>;
   constexpr int KSL = S::KSL, NST = S::NST, IPW = S::IPW;
   constexpr int NT = 64 * kWaves;
@@ -520,6 +519,8 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnPara
     __syncthreads();
   }
   const uint32_t lds0 = (uint32_t)(size_t)(LA_LDS uint8_t *)lds;
+  int32_t *give_up = (int32_t *)(lds + S::kFlagOff);
+  if (tid == 0) *give_up = 0;  // (published by the barriers of the Q rewrite below)
 
   // ---- Q -> LDS: wavefront rb < NRB fetches the fragments of row block rb, lane (ln, lh) exactly the 16 bytes
   //      of its row that it (and the same lane of every wavefront of that row block) reads back for MFMA step s:
@@ -537,7 +538,7 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnPara
 
   // ---- the direct K/V loads of this wavefront; the stream starts now ----------------------------------
   const size_t br_off = ((size_t)b * gl * p.Hkv + kvh) * kRowBytes;
-  StreamLoader<KSL, NST, IPW> ld;
+  StreamLoader<KSL, NST, IPW, true, !GENERAL> ld;
   ld.ring = lds0 + S::kRingOff, ld.wave = wave;
   ld.blk = table ? blk_lds : nullptr, ld.table = table;
   ld.first_lb = first_lb, ld.ident = b * p.max_blocks, ld.shift = p.block_shift, ld.bs_mask = p.block_size - 1;
@@ -672,8 +673,8 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnPara
     const uint8_t *qfrag = lds + rb * 8192 + lane * 16;
     if (step < n_pre_steps) {
       const int first = k_begin + (step * KSL + ks) * kTileN;
-      if (first + kTileN <= k_end)
-        stream_tile_fast(kt, qfrag, qscale, st, koff, voff);
+      if (!GENERAL && first + kTileN <= k_end)
+        stream_tile_fast(kt, qfrag, qscale, st, koff, voff, give_up);
       else if (first < k_end)
         stream_tile<MASK_TAIL>(kt, qfrag, qscale, st, koff, voff, lh, first, k_end);
     } else {
@@ -682,6 +683,10 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnPara
     }
   }
   wait_vmcnt<0>();  // no direct load may still be on its way to LDS when the workgroup gives its LDS back
+  if constexpr (!GENERAL) {
+    __syncthreads();  // every wavefront's flag store has landed (the fence waits for it) before anyone reads the flag
+    if (__builtin_expect(*(volatile int32_t *)give_up != 0, 0)) return false;
+  }
 
   // ---- fold the key slices of a row block through LDS, every wavefront a share of the columns ----------------
   // All 8/NRB slices of a row block leave (O, m, l) per lane in LDS, layout [wavefront][value 0..65][lane];
@@ -757,6 +762,14 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnPara
       }
     }
   }
+  return true;
+}
+
+template <int NRB>
+__global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnParams p) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  // (the second attempt starts from the kernel's arguments again: nothing of the first is alive in it)
+  if (__builtin_expect(!stream_chunk<NRB, false>(p, lds), 0)) stream_chunk<NRB, true>(p, lds);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
