@@ -662,7 +662,23 @@ __device__ __forceinline__ bool stream_chunk(const AttnParams &p, uint8_t *lds) 
 
   // ---- the pipeline -------------------------------------------------------------------------------
   const bool active = r0 + rb * 32 < p.R;
-  for (int step = 0; step < n_steps; ++step) {
+  const uint8_t *qfrag = lds + rb * 8192 + lane * 16;
+  int step = 0;
+  // The steps all of whose tiles are full prefix tiles, in a loop of their own that holds nothing but the
+  // hand-scheduled tile: with a tile form that rescales O inside the same loop (the ragged last tile, the
+  // branch-private tiles) the register allocator settles O's place at the loop's end by what those forms leave,
+  // and the hand-scheduled tile pays 32 register copies per trip to get there.
+  if constexpr (!GENERAL) {
+    for (; step < n_full_steps; ++step) {
+      wait_later<IPW, NST - 2>(min(n_steps - 1, step + NST - 2) - step);
+      __builtin_amdgcn_s_barrier();
+      if (step + NST - 1 < n_steps) issue(step + NST - 1);
+      if (active)
+        stream_tile_fast(lds + S::kRingOff + (step % NST) * kStepBytes + ks * kTileBytes, qfrag, qscale, st, koff, voff,
+                         give_up);
+    }
+  }
+  for (; step < n_steps; ++step) {
     // own loads of this step have landed (the steps issued after it may still be in flight) ...
     wait_later<IPW, NST - 2>(min(n_steps - 1, step + NST - 2) - step);
     __builtin_amdgcn_s_barrier();  // ... and so have everyone else's; the slots read in the previous step are free
@@ -670,7 +686,6 @@ __device__ __forceinline__ bool stream_chunk(const AttnParams &p, uint8_t *lds) 
     if (step + NST - 1 < n_steps) issue(step + NST - 1);
     if (!active) continue;
     const uint8_t *kt = lds + S::kRingOff + (step % NST) * kStepBytes + ks * kTileBytes;
-    const uint8_t *qfrag = lds + rb * 8192 + lane * 16;
     if (step < n_pre_steps) {
       const int first = k_begin + (step * KSL + ks) * kTileN;
       if (!GENERAL && first + kTileN <= k_end)
