@@ -63,7 +63,7 @@ ShapeInfo shape_info(int shape) {
     s.fp8 = attn_stream_shape_is_fp8(s.local);
     if (s.fp8) {
       s.t_step = s.tile_m == 64 ? 3.1 : s.tile_m == 128 ? 2.3 : 3.0;
-      s.t_step_shared = s.tile_m == 64 ? 2.15 : s.tile_m == 128 ? 2.0 : 2.2;
+      s.t_step_shared = s.tile_m == 64 ? 2.15 : s.tile_m == 128 ? 2.05 : 2.2;
     } else {
       s.t_step = s.t_step_shared = s.tile_m == 256 ? 2.45 : 2.6;
     }

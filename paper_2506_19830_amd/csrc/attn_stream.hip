@@ -215,6 +215,55 @@ __device__ __forceinline__ void stream_tile(const uint8_t *kt, const uint8_t *qf
   pv(1, p1);
 }
 
+// The same tile once more, written for few registers and little code rather than for speed: one 32-key block after
+// the other in a loop that is not unrolled, no block's work overlapped with the other's.  This is the form of the
+// second attempt (see stream_tile_fast), which runs almost never; with the faster general form there the kernel would
+// need private memory for spilled registers, and a kernel that uses private memory at all streams a tenth slower at
+// few rows, whichever path is taken.
+template <int MASK>
+__device__ __forceinline__ void stream_tile_lean(const uint8_t *kt, const uint8_t *qfrag, int qscale, RowState<1> &st,
+                                                 const int (&koff)[4], const int (&voff)[4], int lh, int first,
+                                                 int limit) {
+  const uint8_t *vt = kt + kHalfBytes;
+#pragma clang loop unroll(disable)
+  for (int kb = 0; kb < 2; ++kb) {
+    const uint8_t *kblk = kt + kb * 32 * kRowBytes;
+    f32x16 s[1];
+    s[0] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    {
+      const i32x8 k0 = read_pair(kblk + koff[0], kblk + koff[1]);
+      s[0] = mfma_kq<0>(k0, read_pair(qfrag, qfrag + 1024), s[0], qscale);
+      s[0] = mfma_kq<0>(k0, read_pair(qfrag + 2 * 1024, qfrag + 3 * 1024), s[0], qscale);
+      const i32x8 k1 = read_pair(kblk + koff[2], kblk + koff[3]);
+      s[0] = mfma_kq<1>(k1, read_pair(qfrag + 4 * 1024, qfrag + 5 * 1024), s[0], qscale);
+      s[0] = mfma_kq<1>(k1, read_pair(qfrag + 6 * 1024, qfrag + 7 * 1024), s[0], qscale);
+    }
+    mask_block<1, MASK>(s, st, kb, lh, first, limit);
+    const float binit[1] = {0.f};
+    float mt[1], alpha[1], off[1], sum[1];
+    uint32_t pb[1][8];
+    block_max<1>(s, 1.f, binit, mt);
+    if (raise_max<1>(mt, st, alpha)) {
+      rescale<1>(st, alpha);
+      st.base[0] = (st.m_run[0] == -INFINITY) ? 0.f : st.m_run[0];  // base == running maximum
+    }
+    off[0] = -((st.m_run[0] == -INFINITY) ? 0.f : st.m_run[0]);
+    block_probs<1, false>(s, 1.f, off, pb, sum);
+    st.l_run[0] += sum[0];
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2) {
+      const u32x4 pw = {pb[0][4 * t2], pb[0][4 * t2 + 1], pb[0][4 * t2 + 2], pb[0][4 * t2 + 3]};
+      const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        const u32x2 vraw = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr8_b64_v2i32((LA_LDS i32x2 *)(
+                                                         vt + (kb * 32 + t2 * 16) * kRowBytes + voff[db])));
+        st.o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen8(vraw[0], vraw[1]), pf, st.o[db][0], 0, 0, 0);
+      }
+    }
+  }
+}
+
 // The unmasked tile again, scheduled by hand: the tile's 24 MFMAs in a fixed order (S^T of block 0: four fp8 MFMAs of
 // 64 cycles; S^T of block 1 next to the probabilities of block 0; O += block 0, eight bf16 MFMAs of 32 cycles, next
 // to the probabilities of block 1; O += block 1), each preceded by the LDS fragment reads that MFMAs starting up to
@@ -472,13 +521,13 @@ struct StreamShape {
 // The work of one workgroup.  GENERAL: every tile in the general form (the second attempt; see stream_tile_fast).
 // Returns false if this attempt gave up (nothing has been written then).
 template <int NRB, bool GENERAL>
-__device__ __forceinline__ bool stream_chunk(const AttnParams &p, uint8_t *lds) {
+__device__ __forceinline__ bool stream_chunk(const AttnParams &p, uint8_t *lds, int thread_id, int block_id) {
   using S = StreamShape<NRB>;
   constexpr int KSL = S::KSL, NST = S::NST, IPW = S::IPW;
   constexpr int NT = 64 * kWaves;
   constexpr int kTileM = 32 * NRB;
   constexpr int kStepBytes = KSL * kTileBytes;
-  const int tid = threadIdx.x;
+  const int tid = thread_id;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ln = lane & 31, lh = lane >> 5;
   const int rb = wave % NRB, ks = wave / NRB;
@@ -486,7 +535,7 @@ __device__ __forceinline__ bool stream_chunk(const AttnParams &p, uint8_t *lds) 
   // ---- which (kv head, row tile, request, chunk) -------------------------------------------
   // (integer divisions run in vector registers; pinning the results to scalar registers keeps what depends on
   // them -- the scale loads among it -- on the scalar side, away from the vector memory counter)
-  int id = blockIdx.x;
+  int id = block_id;
   const int kvh = __builtin_amdgcn_readfirstlane(id % p.Hkv);
   id = __builtin_amdgcn_readfirstlane(id / p.Hkv);
   const int row_tile = __builtin_amdgcn_readfirstlane(id % p.n_row_tiles);
@@ -688,13 +737,22 @@ __device__ __forceinline__ bool stream_chunk(const AttnParams &p, uint8_t *lds) 
     const uint8_t *kt = lds + S::kRingOff + (step % NST) * kStepBytes + ks * kTileBytes;
     if (step < n_pre_steps) {
       const int first = k_begin + (step * KSL + ks) * kTileN;
-      if (!GENERAL && first + kTileN <= k_end)
-        stream_tile_fast(kt, qfrag, qscale, st, koff, voff, give_up);
-      else if (first < k_end)
-        stream_tile<MASK_TAIL>(kt, qfrag, qscale, st, koff, voff, lh, first, k_end);
+      if constexpr (GENERAL) {
+        if (first < k_end) stream_tile_lean<MASK_TAIL>(kt, qfrag, qscale, st, koff, voff, lh, first, k_end);
+      } else {
+        if (first + kTileN <= k_end)
+          stream_tile_fast(kt, qfrag, qscale, st, koff, voff, give_up);
+        else if (first < k_end)
+          stream_tile<MASK_TAIL>(kt, qfrag, qscale, st, koff, voff, lh, first, k_end);
+      }
     } else {
       const int first = tk0 + ((step - n_pre_steps) * KSL + ks) * kTileN;
-      if (first <= t_hi) stream_tile<MASK_BRANCH>(kt, qfrag, qscale, st, koff, voff, lh, first, 0);
+      if (first <= t_hi) {
+        if constexpr (GENERAL)
+          stream_tile_lean<MASK_BRANCH>(kt, qfrag, qscale, st, koff, voff, lh, first, 0);
+        else
+          stream_tile<MASK_BRANCH>(kt, qfrag, qscale, st, koff, voff, lh, first, 0);
+      }
     }
   }
   wait_vmcnt<0>();  // no direct load may still be on its way to LDS when the workgroup gives its LDS back
@@ -783,8 +841,14 @@ __device__ __forceinline__ bool stream_chunk(const AttnParams &p, uint8_t *lds) 
 template <int NRB>
 __global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-  // (the second attempt starts from the kernel's arguments again: nothing of the first is alive in it)
-  if (__builtin_expect(!stream_chunk<NRB, false>(p, lds), 0)) stream_chunk<NRB, true>(p, lds);
+  if (__builtin_expect(!stream_chunk<NRB, false>(p, lds, threadIdx.x, blockIdx.x), 0)) {
+    // The second attempt starts from the kernel's arguments again, and from thread and workgroup ids the compiler
+    // cannot see through: whatever it shared between the two attempts stayed alive across the first one, in private
+    // memory (a kernel that uses private memory at all streams a tenth slower at few rows).
+    int thread_id = threadIdx.x, block_id = blockIdx.x;
+    asm volatile("" : "+v"(thread_id), "+s"(block_id));
+    stream_chunk<NRB, true>(p, lds, thread_id, block_id);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------------------------
