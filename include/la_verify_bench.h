@@ -65,6 +65,19 @@ LA_API la_status la_calibrate_issue(int32_t mix, int32_t mix_second, int32_t wav
 LA_API la_status la_selftest_exp64(const double *y, double *out, size_t n, void *hip_stream);
 
 /* ------------------------------------------------------------------------- *
+ *  Self-test hook for the streaming kernel shapes of an fp8 cache.  Their
+ *  unmasked tiles never move the base their probabilities are formed against
+ *  (Section 3.2's verification pass needs no such thing; it is this
+ *  implementation's way to keep the accumulators of O in place); a workgroup
+ *  that meets a score 60 log2 units above its base gives up and reduces its
+ *  chunk a second time in a general form.  With on != 0 every workgroup of
+ *  those shapes takes that second attempt in the la_verify_attention calls
+ *  that follow, whatever its scores, so that a test can compare the two.
+ *  Process-wide, host side only; 0 restores the normal behaviour.
+ * ------------------------------------------------------------------------- */
+LA_API la_status la_selftest_second_attempt(int on);
+
+/* ------------------------------------------------------------------------- *
  *  Index checks (debug aid).  The compute calls trust the indices the caller
  *  hands them -- cache block ids and drafted token ids are not range-checked
  *  on the device -- and a checked build of an application can run these two

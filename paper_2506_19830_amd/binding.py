@@ -31,7 +31,7 @@ EXPORTED_SYMBOLS = (
 )
 # what libla_verify_bench.so exports on top of those (la_verify_bench.h)
 BENCH_SYMBOLS = (
-    "la_calibrate_mfma", "la_calibrate_mfma_data", "la_calibrate_read", "la_calibrate_issue", "la_selftest_exp64", "la_check_block_tables", "la_check_draft_tokens",
+    "la_calibrate_mfma", "la_calibrate_mfma_data", "la_calibrate_read", "la_calibrate_issue", "la_selftest_exp64", "la_selftest_second_attempt", "la_check_block_tables", "la_check_draft_tokens",
     "la_profile_enable", "la_profile_select",
     "la_profile_collect", "la_profile_num_kernels", "la_profile_get", "la_profile_reset",
 )
@@ -335,6 +335,16 @@ def la_selftest_exp64(y, out) -> None:
     st = load("bench").la_selftest_exp64(_ptr(y), _ptr(out), ctypes.c_size_t(out.numel()), _stream())
     if st:
         raise LaError(st, "la_selftest_exp64")
+
+
+def la_selftest_second_attempt(on: bool) -> None:
+    """Make every workgroup of the fp8 streaming shapes take its second (general-form) attempt in the calls that follow."""
+    lib = load("bench")
+    lib.la_selftest_second_attempt.restype = ctypes.c_int
+    lib.la_selftest_second_attempt.argtypes = [ctypes.c_int]
+    st = lib.la_selftest_second_attempt(int(bool(on)))
+    if st:
+        raise LaError(st, "la_selftest_second_attempt")
 
 
 def la_check_block_tables(desc: la_attn_desc, block_tables, prefix_lens_host: Sequence[int], num_cache_blocks: int,

@@ -569,7 +569,7 @@ __device__ __forceinline__ bool stream_chunk(const AttnParams &p, uint8_t *lds, 
   }
   const uint32_t lds0 = (uint32_t)(size_t)(LA_LDS uint8_t *)lds;
   int32_t *give_up = (int32_t *)(lds + S::kFlagOff);
-  if (tid == 0) *give_up = 0;  // (published by the barriers of the Q rewrite below)
+  if (tid == 0) *give_up = GENERAL ? 0 : p.force_again;  // (published by the barriers of the Q rewrite below)
 
   // ---- Q -> LDS: wavefront rb < NRB fetches the fragments of row block rb, lane (ln, lh) exactly the 16 bytes
   //      of its row that it (and the same lane of every wavefront of that row block) reads back for MFMA step s:
@@ -1161,7 +1161,9 @@ hipError_t launch_stream_variant(const AttnParams &p, hipStream_t stream) {
     configured = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::kLdsMax);
   });
   if (configured != hipSuccess) return configured;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * kWaves), lds_bytes, stream, p);
+  AttnParams q = p;
+  q.force_again = selftest_force_second_attempt ? selftest_force_second_attempt() : 0;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * kWaves), lds_bytes, stream, q);
   return hipGetLastError();
 }
 

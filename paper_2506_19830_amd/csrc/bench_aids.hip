@@ -18,6 +18,7 @@ struct ProfileRecord {
 };
 // process-wide state of the timing aid (not thread-safe, as its header says)
 bool g_profile_on = false;
+int g_force_second_attempt = 0;
 uint32_t g_profile_mask = 0xffffffffu;      // slots that are timed
 int g_profile_stride = 1;                   // of their launches, every stride-th one
 int64_t g_seen[SLOT_COUNT];                 // launches of a slot seen while enabled
@@ -62,6 +63,8 @@ void profile_after(int slot, hipStream_t stream, void *start) {
   g_records.push_back({slot, (hipEvent_t)start, e});
 }
 
+int selftest_force_second_attempt() { return g_force_second_attempt; }
+
 }  // namespace la
 
 using namespace la;
@@ -71,6 +74,11 @@ extern "C" {
 la_status la_selftest_exp64(const double *y, double *out, size_t n, void *hip_stream) {
   if (!y || !out || n < 1 || n > ((size_t)1 << 30)) return LA_ERR_INVALID_ARG;
   return launch_exp64_probe(y, out, n, (hipStream_t)hip_stream) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
+la_status la_selftest_second_attempt(int on) {
+  g_force_second_attempt = on != 0;
+  return LA_OK;
 }
 
 la_status la_profile_select(uint32_t slot_mask, int32_t stride) {

@@ -49,6 +49,8 @@ struct AttnParams {
   int out_f32;      // output dtype: 1 = fp32, 0 = bf16
   int q_type, kv_type, br_type;  // la_dtype of Q, of the prefix cache, of the branch / chain / pool K and V
   float scale_log2; // softmax_scale * log2(e)
+  int force_again;  // streaming shapes (fp8): start with the give-up flag raised, so that every workgroup also runs its
+                    // second attempt (a self-test hook of the benchmark library; 0 otherwise)
   // With few requests what a workgroup needs to find its chunk travels in the kernel arguments, prepared by the host
   // from its copy of the prefix lengths, so that no kernel start waits on a dependent load of prefix_lens or on
   // integer divisions: n_inline = B if B <= kMaxInlineLens, else 0.
@@ -182,6 +184,8 @@ hipError_t launch_kv_commit(const CommitParams &p, int src_bytes, bool quantise,
 // ----------------------------------------------------------------------------
 __attribute__((weak)) void *profile_before(int slot, hipStream_t stream);            // start event, or null
 __attribute__((weak)) void profile_after(int slot, hipStream_t stream, void *start);
+// self-test hook of the benchmark library: nonzero = the fp8 streaming kernels run their second attempt everywhere
+__attribute__((weak)) int selftest_force_second_attempt();
 
 struct ProfileScope {
   int slot;
