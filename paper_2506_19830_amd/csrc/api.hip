@@ -65,9 +65,10 @@ ShapeInfo shape_info(int shape) {
       s.t_step = s.tile_m == 64 ? 3.1 : s.tile_m == 128 ? 2.3 : 3.0;
       s.t_step_shared = s.tile_m == 64 ? 2.15 : s.tile_m == 128 ? 2.05 : 2.2;
     } else {
-      s.t_step = s.t_step_shared = s.tile_m == 256 ? 2.45 : 2.6;
+      s.t_step = s.t_step_shared = s.tile_m == 256 ? 1.8 : 2.45;
     }
-    s.t_fixed = 5.0;
+    // (the 256-row bf16 shape: eight row blocks' Q into registers and a branch-private tile per wavefront at the end)
+    s.t_fixed = (!s.fp8 && s.tile_m == 256) ? 12.0 : 5.0;
   }
   return s;
 }
@@ -190,10 +191,54 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, bool
       const int64_t wg_tiles = (T + last_short + n_max - 1) / n_max;  // of the longest request
       const int64_t wg_steps = (wg_tiles * 64 + si.step_keys - 1) / si.step_keys;
       const double t_step = R > si.tile_m ? si.t_step_shared : si.t_step;
-      // (a streaming plan of several rounds has measured at its model cost, the row-tile shapes it competes with there
+      // (an fp8 streaming plan of several rounds has measured at its model cost, the row-tile shapes it competes with there
       // -- partly filled row tiles of 256 rows -- below theirs: the margin keeps those cases with the row tiles)
-      const double cost = (double)rounds * ((double)wg_steps * t_step + si.t_fixed) * (si.stream && rounds > 1 ? 1.06 : 1.0) +
-                          merge_us;
+      double busy_us = (double)rounds * ((double)wg_steps * t_step + si.t_fixed);
+      if (d->num_requests > 1 && rounds > 1 && units <= 256) {
+        // Several requests of different lengths in several rounds: rounds x the longest chunk is what the dispatch of
+        // equal workgroups gives; with unequal ones the workgroups are dealt out here as the hardware deals them, in
+        // launch order (all workgroups of a chunk, chunk after chunk, request after request), each to the slot that
+        // is free first.  (Measured at configuration 4's ragged batch: one chunk per request, 1.17 ms; chunks of
+        // 8192 keys, 1.04 ms, where rounds x longest saw the two as equal.)
+        struct Free { double t; int64_t n; };
+        std::vector<Free> free_at{{0.0, slots}}, next;
+        for (int b = 0; b < d->num_requests; ++b) {
+          const int64_t nc = attn_num_chunks(prefix_lens_host[b], (int)len);
+          const int64_t tiles_b = (prefix_lens_host[b] + 63) / 64 + last_short;
+          for (int64_t c = 0; c < nc; ++c) {
+            const int64_t tiles = tiles_b / nc + (c < tiles_b % nc ? 1 : 0);
+            const double dur = (double)((tiles * 64 + si.step_keys - 1) / si.step_keys) * t_step + si.t_fixed;
+            for (int64_t left = base_wgs; left > 0;) {
+            int64_t need = left < slots ? left : slots;  // (the slots always add up to `slots`)
+            left -= need;
+            size_t i = 0;
+            next.clear();
+            for (; need > 0 && i < free_at.size(); ++i) {
+              const int64_t k = need < free_at[i].n ? need : free_at[i].n;
+              next.push_back({free_at[i].t + dur, k});
+              free_at[i].n -= k, need -= k;
+              if (free_at[i].n > 0) break;
+            }
+            // what was not taken keeps its place; the slots just filled come free later, in the order they were taken
+            std::vector<Free> merged;
+            size_t a = i, bq = 0;
+            while (a < free_at.size() || bq < next.size()) {
+              if (bq >= next.size() || (a < free_at.size() && free_at[a].t <= next[bq].t)) {
+                if (free_at[a].n > 0) merged.push_back(free_at[a]);
+                ++a;
+              } else {
+                merged.push_back(next[bq++]);
+              }
+            }
+            free_at.swap(merged);
+            }
+          }
+        }
+        busy_us = free_at.back().t;
+      }
+      // (an fp8 streaming plan of several rounds has measured at its model cost, the row-tile shapes it competes with there
+      // -- partly filled row tiles of 256 rows -- below theirs: the margin keeps those cases with the row tiles)
+      const double cost = busy_us * (si.stream && si.fp8 && rounds > 1 ? 1.06 : 1.0) + merge_us;
       if (best_shape < 0 || cost < best_cost)
         best_cost = cost, best_len = (int)len, best_shape = shape, best_short = last_short;
       if (len <= 64 || d->kv_split_tokens) break;

@@ -860,9 +860,13 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream_kernel(const AttnPara
 //   koff0         lane's byte offset for piece lh of key ln (key block 0; block 1 is 32 rows on)
 //   voff[a][db]   lane's byte offset for the transposing read of keys 8a + 4lh .. +4 of head-dim block db (key group 0
 //                 of key block 0; the others 16 / 32 rows on)
-template <int MASK>
+// KEEP (unmasked tiles only): the base is never moved and O never rescaled, as in stream_tile_fast and for its
+// reason; `give_up` is the workgroup's flag.
+template <int MASK, bool KEEP = false>
 __device__ __forceinline__ void stream_tile16(const uint8_t *kt, RowState<1> &st, int koff0,
-                                              const int (&voff)[2][4], int lh, int first, int limit) {
+                                              const int (&voff)[2][4], int lh, int first, int limit,
+                                              int32_t *give_up = nullptr) {
+  static_assert(!KEEP || MASK == MASK_NONE, "only unmasked tiles keep their base");
   using G = Geo<false>;
   const uint8_t *vt = kt + G::kHalf;
   constexpr bool kFastable = MASK == MASK_NONE;
@@ -906,6 +910,29 @@ __device__ __forceinline__ void stream_tile16(const uint8_t *kt, RowState<1> &st
       s1[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, st.qf[0][t], s1[0], 0, 0, 0);
     }
   }
+  if constexpr (KEEP) {
+    block_probs<1, true>(s0, 1.f, off, p0, sum0);
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(st.m_run[0] == -INFINITY) != 0, 0)) {  // (all lanes or none)
+      float m = fmaxf(s0[0][0], s1[0][0]);  // (the base is still 0: these are the scores themselves)
+#pragma unroll
+      for (int j = 1; j < 16; ++j) m = fmaxf(m, fmaxf(s0[0][j], s1[0][j]));
+      m = xhalf_max(m);
+      st.m_run[0] = m, st.base[0] = m;
+      off[0] = -m;
+      block_probs<1, false>(s0, 1.f, off, p0, sum0);
+#pragma unroll
+      for (int j = 0; j < 16; ++j) s1[0][j] -= m;
+    }
+    if (!(sum0[0] <= kTrigger)) *(volatile int32_t *)give_up = 1;
+    st.l_run[0] += sum0[0];
+    pv(0, p0);
+    __builtin_amdgcn_sched_barrier(0);
+    block_probs<1, true>(s1, 1.f, off, p1, sum1);
+    if (!(sum1[0] <= kTrigger)) *(volatile int32_t *)give_up = 1;
+    st.l_run[0] += sum1[0];
+    pv(1, p1);
+    return;
+  }
   mask_block<1, MASK>(s0, st, 0, lh, first, limit);
   if constexpr (kFastable) block_probs<1, true>(s0, 1.f, off, p0, sum0);
   block_max<1>(s0, 1.f, binit, mt);
@@ -932,6 +959,48 @@ __device__ __forceinline__ void stream_tile16(const uint8_t *kt, RowState<1> &st
   pv(1, p1);
 }
 
+// The second attempt's form of the tile (see stream_tile_lean): one key block after the other, not unrolled.
+template <int MASK>
+__device__ __forceinline__ void stream_tile16_lean(const uint8_t *kt, RowState<1> &st, int koff0,
+                                                   const int (&voff)[2][4], int lh, int first, int limit) {
+  using G = Geo<false>;
+  const uint8_t *vt = kt + G::kHalf;
+#pragma clang loop unroll(disable)
+  for (int kb = 0; kb < 2; ++kb) {
+    f32x16 s[1];
+    s[0] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+      s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(kt + kb * 32 * G::kRow + (koff0 ^ (32 * t))),
+                                                     st.qf[0][t], s[0], 0, 0, 0);
+    mask_block<1, MASK>(s, st, kb, lh, first, limit);
+    const float binit[1] = {0.f};
+    float mt[1], alpha[1], off[1], sum[1];
+    uint32_t pb[1][8];
+    block_max<1>(s, 1.f, binit, mt);
+    if (raise_max<1>(mt, st, alpha)) {
+      rescale<1>(st, alpha);
+      st.base[0] = (st.m_run[0] == -INFINITY) ? 0.f : st.m_run[0];  // base == running maximum
+    }
+    off[0] = -((st.m_run[0] == -INFINITY) ? 0.f : st.m_run[0]);
+    block_probs<1, false>(s, 1.f, off, pb, sum);
+    st.l_run[0] += sum[0];
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2) {
+      const u32x4 pw = {pb[0][4 * t2], pb[0][4 * t2 + 1], pb[0][4 * t2 + 2], pb[0][4 * t2 + 3]};
+      const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
+      const uint8_t *at = vt + (kb * 32 + t2 * 16) * G::kRow;
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LA_LDS i16x4 *)(at + voff[0][db])));
+        const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LA_LDS i16x4 *)(at + voff[1][db])));
+        const u32x4 vw = {lo[0], lo[1], hi[0], hi[1]};
+        st.o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vw), pf, st.o[db][0], 0, 0, 0);
+      }
+    }
+  }
+}
+
 template <int NRB>
 struct Stream16Shape {
   using G = Geo<false>;
@@ -940,26 +1009,27 @@ struct Stream16Shape {
   static constexpr int NST = kSlots / KSL;
   static constexpr int IPW = 2 * G::kLoadsPerHalf * KSL / kWaves;
   static constexpr int kBlkOff = kSlots * G::kTile;
-  static constexpr int kLdsMax = kBlkOff + kMaxBlkLds * 4;
+  static constexpr int kFlagOff = kBlkOff + kMaxBlkLds * 4;  // the give-up flag (see stream_tile_fast)
+  static constexpr int kLdsMax = kFlagOff + 16;
   static constexpr int kFoldBytes = kWaves * 66 * 64 * 4;
-  static_assert(NST >= 2 && kLdsMax <= 160 * 1024 && kFoldBytes <= kLdsMax, "LDS of one CU");
+  static_assert(NST >= 2 && kLdsMax <= 160 * 1024 && kFoldBytes <= kFlagOff, "LDS of one CU");
 };
 
-template <int NRB>
-__global__ __launch_bounds__(64 * kWaves) void attn_stream16_kernel(const AttnParams p) {
-  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+// The work of one workgroup; GENERAL: the second attempt, every tile in the general form (see stream_chunk).
+template <int NRB, bool GENERAL>
+__device__ __forceinline__ bool stream16_chunk(const AttnParams &p, uint8_t *lds, int thread_id, int block_id) {
   using S = Stream16Shape<NRB>;
   using G = Geo<false>;
   constexpr int KSL = S::KSL, NST = S::NST, IPW = S::IPW;
   constexpr int NT = 64 * kWaves;
   constexpr int kTileM = 32 * NRB;
   constexpr int kStepBytes = KSL * G::kTile;
-  const int tid = threadIdx.x;
+  const int tid = thread_id;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ln = lane & 31, lh = lane >> 5;
   const int rb = wave % NRB, ks = wave / NRB;
 
-  int id = blockIdx.x;
+  int id = block_id;
   const int kvh = __builtin_amdgcn_readfirstlane(id % p.Hkv);
   id = __builtin_amdgcn_readfirstlane(id / p.Hkv);
   const int row_tile = __builtin_amdgcn_readfirstlane(id % p.n_row_tiles);
@@ -1007,6 +1077,8 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream16_kernel(const AttnPa
   }
 
   // ---- physical block ids of this chunk -> LDS (paged caches only) ------------------------------
+  int32_t *give_up = (int32_t *)(lds + S::kFlagOff);
+  if (tid == 0) *give_up = GENERAL ? 0 : p.force_again;  // (published by the barrier below)
   int32_t *blk_lds = (int32_t *)(lds + S::kBlkOff);
   const int first_lb = k_begin >> p.block_shift;
   const int32_t *table = p.block_tables ? p.block_tables + (size_t)b * p.max_blocks : nullptr;
@@ -1057,7 +1129,17 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream16_kernel(const AttnPa
   }
 
   const bool active = r0 + rb * 32 < p.R;
-  for (int step = 0; step < n_steps; ++step) {
+  int step = 0;
+  if constexpr (!GENERAL) {  // the steps all of whose tiles are full prefix tiles, in a loop of their own
+    for (; step < n_full_steps; ++step) {
+      wait_later<IPW, NST - 2>(min(n_steps - 1, step + NST - 2) - step);
+      __builtin_amdgcn_s_barrier();
+      if (step + NST - 1 < n_steps) issue(step + NST - 1);
+      if (active)
+        stream_tile16<MASK_NONE, true>(lds + (step % NST) * kStepBytes + ks * G::kTile, st, koff0, voff, lh, 0, 0, give_up);
+    }
+  }
+  for (; step < n_steps; ++step) {
     wait_later<IPW, NST - 2>(min(n_steps - 1, step + NST - 2) - step);
     __builtin_amdgcn_s_barrier();
     if (step + NST - 1 < n_steps) issue(step + NST - 1);
@@ -1065,16 +1147,29 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream16_kernel(const AttnPa
     const uint8_t *kt = lds + (step % NST) * kStepBytes + ks * G::kTile;
     if (step < n_pre_steps) {
       const int first = k_begin + (step * KSL + ks) * kTileN;
-      if (first + kTileN <= k_end)
-        stream_tile16<MASK_NONE>(kt, st, koff0, voff, lh, 0, 0);
-      else if (first < k_end)
-        stream_tile16<MASK_TAIL>(kt, st, koff0, voff, lh, first, k_end);
+      if constexpr (GENERAL) {
+        if (first < k_end) stream_tile16_lean<MASK_TAIL>(kt, st, koff0, voff, lh, first, k_end);
+      } else {
+        if (first + kTileN <= k_end)
+          stream_tile16<MASK_NONE, true>(kt, st, koff0, voff, lh, 0, 0, give_up);
+        else if (first < k_end)
+          stream_tile16<MASK_TAIL>(kt, st, koff0, voff, lh, first, k_end);
+      }
     } else {
       const int first = tk0 + ((step - n_pre_steps) * KSL + ks) * kTileN;
-      if (first <= t_hi) stream_tile16<MASK_BRANCH>(kt, st, koff0, voff, lh, first, 0);
+      if (first <= t_hi) {
+        if constexpr (GENERAL)
+          stream_tile16_lean<MASK_BRANCH>(kt, st, koff0, voff, lh, first, 0);
+        else
+          stream_tile16<MASK_BRANCH>(kt, st, koff0, voff, lh, first, 0);
+      }
     }
   }
   wait_vmcnt<0>();  // no direct load may still be on its way to LDS when the workgroup gives its LDS back
+  if constexpr (!GENERAL) {
+    __syncthreads();  // every wavefront's flag store has landed before anyone reads the flag
+    if (__builtin_expect(*(volatile int32_t *)give_up != 0, 0)) return false;
+  }
 
   // ---- the partial: one key slice per row block writes its registers, two are folded through LDS first ---------
   const size_t slot = (size_t)b * p.s_max + c;
@@ -1093,7 +1188,7 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream16_kernel(const AttnPa
       dst[65 * 64] = st.l_run[0];
     }
     __syncthreads();
-    if (ks > 0) return;
+    if (ks > 0) return true;
 #pragma unroll 1
     for (int s = 1; s < KSL; ++s) {
       const float *src = fold + (size_t)((s - 1) * NRB + rb) * 66 * 64 + lane;
@@ -1125,6 +1220,17 @@ __global__ __launch_bounds__(64 * kWaves) void attn_stream16_kernel(const AttnPa
       *(f32x2 *)(p.part_ml + out_row * 2) = ml;
     }
   }
+  return true;
+}
+
+template <int NRB>
+__global__ __launch_bounds__(64 * kWaves) void attn_stream16_kernel(const AttnParams p) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  if (__builtin_expect(!stream16_chunk<NRB, false>(p, lds, threadIdx.x, blockIdx.x), 0)) {
+    int thread_id = threadIdx.x, block_id = blockIdx.x;  // (opaque to the compiler: see attn_stream_kernel)
+    asm volatile("" : "+v"(thread_id), "+s"(block_id));
+    stream16_chunk<NRB, true>(p, lds, thread_id, block_id);
+  }
 }
 
 template <int NRB>
@@ -1135,14 +1241,16 @@ hipError_t launch_stream16_variant(const AttnParams &p, hipStream_t stream) {
   const int blk_entries =
       p.block_tables ? (attn_max_chunk_tokens(p.chunk_len, p.last_short) >> p.block_shift) + 2 : 0;
   if (blk_entries > kMaxBlkLds) return hipErrorInvalidValue;
-  const int lds_bytes = S::kBlkOff + blk_entries * 4 > S::kFoldBytes ? S::kBlkOff + blk_entries * 4 : S::kFoldBytes;
+  const int lds_bytes = S::kLdsMax;  // (the flag lies behind the largest block table)
   static std::once_flag once;
   static hipError_t configured = hipSuccess;
   std::call_once(once, [&] {
     configured = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::kLdsMax);
   });
   if (configured != hipSuccess) return configured;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * kWaves), lds_bytes, stream, p);
+  AttnParams q = p;
+  q.force_again = selftest_force_second_attempt ? selftest_force_second_attempt() : 0;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * kWaves), lds_bytes, stream, q);
   return hipGetLastError();
 }
 

@@ -168,10 +168,10 @@ def test_running_maximum_that_jumps_late(oracle, shape, kv, shift, monkeypatch):
             check_full(oracle, case, TOL_LOWP, kv_split_tokens=split, lse_tol=0.1)
 
 
-@pytest.mark.parametrize("shape", [2, 3, 4])
-@pytest.mark.parametrize("case", STREAM_CASES, ids=lambda c: c.name)
+@pytest.mark.parametrize("shape,case", [(s, c) for s in (2, 3, 4) for c in STREAM_CASES] +
+                         [(s, c) for s in (5, 6) for c in STREAM16_CASES], ids=lambda v: getattr(v, "name", str(v)))
 def test_second_attempt_of_the_streaming_shapes(oracle, case, shape, monkeypatch):
-    """The fp8 streaming shapes reduce a chunk a second time, in a general form, when a score lies far above the base
+    """The streaming shapes reduce a chunk a second time, in a general form, when a score lies far above the base
     its unmasked tiles started from.  The benchmark library can make every workgroup do so: same bar against the
     oracle, and within rounding of what the first attempt gives on the same inputs."""
     from gpu_util import row_errors, run_attention
