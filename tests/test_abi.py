@@ -69,6 +69,19 @@ def test_workspace_query_and_plan():
     assert B.la_spec_accept_workspace(acc) > 8 * 17 * 19 * 8
 
 
+def test_planner_deals_unequal_requests_as_the_hardware_does():
+    """Configuration 4's batch: four requests of 8K..32K keys on a bf16 cache, 3072 rows per KV head.  One chunk per
+    request and chunks of a quarter of the longest need the same number of rounds x longest-chunk steps; dealt out in
+    launch order the first leaves the chip half empty while the longest request runs (measured 1.17 against 1.04 ms).
+    The plan must be the balanced one; a single request keeps the plan that rounds x longest gives."""
+    kw = dict(num_requests=4, num_q_heads=64, num_kv_heads=8, gamma=8, branch_len=48, kv_dtype="bf16",
+              branch_kv_dtype="bf16", max_blocks_per_request=2060)
+    plan = B.la_verify_attention_plan(good_desc(**kw), [8192, 16384, 24576, 32768])
+    assert plan["chunk_tokens"] == 8192 and plan["chunks_total"] == 10
+    one = B.la_verify_attention_plan(good_desc(), [32768])
+    assert one["kernel_shape"] == 1 and one["chunk_tokens"] == 10944 and one["workgroups"] == 240
+
+
 @pytest.mark.parametrize("kw,lens,status", [
     (dict(num_q_heads=41), [100], 1),
     (dict(block_size=8), [100], 1),
