@@ -5,8 +5,6 @@
 #include <string.h>
 
 #include <mutex>
-#include <vector>
-
 #include "la_internal.hpp"
 #include <cstdio>
 
@@ -194,47 +192,57 @@ la_status make_plan(const la_attn_desc *d, const int32_t *prefix_lens_host, bool
       // (an fp8 streaming plan of several rounds has measured at its model cost, the row-tile shapes it competes with there
       // -- partly filled row tiles of 256 rows -- below theirs: the margin keeps those cases with the row tiles)
       double busy_us = (double)rounds * ((double)wg_steps * t_step + si.t_fixed);
-      if (d->num_requests > 1 && rounds > 1 && units <= 256) {
-        // Several requests of different lengths in several rounds: rounds x the longest chunk is what the dispatch of
-        // equal workgroups gives; with unequal ones the workgroups are dealt out here as the hardware deals them, in
-        // launch order (all workgroups of a chunk, chunk after chunk, request after request), each to the slot that
-        // is free first.  (Measured at configuration 4's ragged batch: one chunk per request, 1.17 ms; chunks of
-        // 8192 keys, 1.04 ms, where rounds x longest saw the two as equal.)
+      if (d->num_requests > 1 && rounds > 1 && n <= 8 && units <= 64) {
+        // Several requests of different lengths in several rounds, few chunks each: rounds x the longest chunk is
+        // what the dispatch of equal workgroups gives; with unequal ones the workgroups are dealt out here as the
+        // hardware deals them, in launch order (all workgroups of a chunk, chunk after chunk, request after request),
+        // each to the slot that is free first.  (Measured at configuration 4's ragged batch: one chunk per request,
+        // 1.17 ms; chunks of 8192 keys, 1.04 ms, where rounds x longest saw the two as equal.)  With many chunks per
+        // request they are nearly equal and the simple form holds; every call plans, so this stays small (fixed
+        // arrays, at most 64 chunks).
+        constexpr int kCap = 256;
         struct Free { double t; int64_t n; };
-        std::vector<Free> free_at{{0.0, slots}}, next;
-        for (int b = 0; b < d->num_requests; ++b) {
+        Free cur[kCap], nxt[kCap], mrg[kCap];
+        int n_cur = 1;
+        cur[0] = {0.0, slots};
+        bool fits = true;
+        for (int b = 0; b < d->num_requests && fits; ++b) {
           const int64_t nc = attn_num_chunks(prefix_lens_host[b], (int)len);
           const int64_t tiles_b = (prefix_lens_host[b] + 63) / 64 + last_short;
-          for (int64_t c = 0; c < nc; ++c) {
+          for (int64_t c = 0; c < nc && fits; ++c) {
             const int64_t tiles = tiles_b / nc + (c < tiles_b % nc ? 1 : 0);
             const double dur = (double)((tiles * 64 + si.step_keys - 1) / si.step_keys) * t_step + si.t_fixed;
-            for (int64_t left = base_wgs; left > 0;) {
-            int64_t need = left < slots ? left : slots;  // (the slots always add up to `slots`)
-            left -= need;
-            size_t i = 0;
-            next.clear();
-            for (; need > 0 && i < free_at.size(); ++i) {
-              const int64_t k = need < free_at[i].n ? need : free_at[i].n;
-              next.push_back({free_at[i].t + dur, k});
-              free_at[i].n -= k, need -= k;
-              if (free_at[i].n > 0) break;
-            }
-            // what was not taken keeps its place; the slots just filled come free later, in the order they were taken
-            std::vector<Free> merged;
-            size_t a = i, bq = 0;
-            while (a < free_at.size() || bq < next.size()) {
-              if (bq >= next.size() || (a < free_at.size() && free_at[a].t <= next[bq].t)) {
-                if (free_at[a].n > 0) merged.push_back(free_at[a]);
-                ++a;
-              } else {
-                merged.push_back(next[bq++]);
+            for (int64_t left = base_wgs; left > 0 && fits;) {
+              int64_t need = left < slots ? left : slots;  // (the entries always add up to `slots`)
+              left -= need;
+              int i = 0, n_nxt = 0;
+              for (; need > 0 && i < n_cur; ++i) {
+                const int64_t k = need < cur[i].n ? need : cur[i].n;
+                nxt[n_nxt++] = {cur[i].t + dur, k};
+                cur[i].n -= k, need -= k;
+                if (cur[i].n > 0) break;
               }
-            }
-            free_at.swap(merged);
+              // what was not taken keeps its place; the slots just filled come free later, in the order taken
+              int a2 = i, b2 = 0, n_mrg = 0;
+              while (a2 < n_cur || b2 < n_nxt) {
+                if (n_mrg >= kCap) {
+                  fits = false;
+                  break;
+                }
+                if (b2 >= n_nxt || (a2 < n_cur && cur[a2].t <= nxt[b2].t)) {
+                  if (cur[a2].n > 0) mrg[n_mrg++] = cur[a2];
+                  ++a2;
+                } else {
+                  mrg[n_mrg++] = nxt[b2++];
+                }
+              }
+              if (n_mrg + 2 >= kCap) fits = false;
+              for (int j = 0; j < n_mrg; ++j) cur[j] = mrg[j];
+              n_cur = n_mrg;
             }
           }
         }
-        busy_us = free_at.back().t;
+        if (fits && n_cur > 0) busy_us = cur[n_cur - 1].t;
       }
       // (an fp8 streaming plan of several rounds has measured at its model cost, the row-tile shapes it competes with there
       // -- partly filled row tiles of 256 rows -- below theirs: the margin keeps those cases with the row tiles)
