@@ -5,16 +5,20 @@
 // stream saturated:
 //   * K/V tiles go global -> LDS directly (global_load_lds_dwordx4, 16 bytes per lane, no staging registers), as
 //     stored (fp8 stays fp8), NST stages deep, issued NST-1 steps ahead of their use;
-//   * the MFMA operands are formed at the fragment read: K rows as they lie (the contraction runs over d),
-//     V through the transposing LDS read (ds_read_b64_tr_b8: each lane receives one head-dim column of eight
-//     keys), fp8 widened to bf16 in registers (exact);
+//   * the MFMA operands are formed at the fragment read: K rows as they lie (the contraction runs over d) -- with an
+//     fp8 cache they feed the fp8 MFMA unconverted, against a two-term fp8 expansion of Q (mfma_kq) --, V through the
+//     transposing LDS read (ds_read_b64_tr_b8: each lane receives one head-dim column of eight keys), fp8 widened
+//     to bf16 in registers (exact);
 //   * a workgroup is eight wavefronts = NRB row blocks of 32 rows x KSL = 8/NRB key slices: per pipeline step of
 //     KSL consecutive 64-key tiles, wavefront (rb, ks) reduces tile ks for its 32 rows, so that two wavefronts
 //     per SIMD work even when there are only 64 rows; the slices of a row block are folded through LDS at the
 //     end and leave one partial per row;
-//   * Q comes through LDS as well (one direct load per MFMA step, each lane fetching exactly the fragment it
-//     later reads back), so that every vector memory operation of the kernel is a direct load whose completion
-//     the kernel counts itself.
+//   * Q comes through LDS as well (fp8 cache: direct loads, each lane fetching exactly what it later reads back,
+//     rewritten in place as the fp8 operands while the first K/V tiles are on their way), so that every vector
+//     memory operation of the kernel is a direct load whose completion the kernel counts itself;
+//   * the unmasked tiles keep the base their probabilities are formed against and never rescale O; they run in a
+//     loop of their own, and a workgroup that meets a score far above its base reduces its chunk a second time in a
+//     general form (stream_tile_fast says why).
 // The last chunk's workgroup also reduces the branch-private keys (causal inside the branch), as further steps
 // of the same pipeline.
 //
